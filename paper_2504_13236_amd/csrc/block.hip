@@ -1,0 +1,263 @@
+// One GPT-2 block as a flow of tile tasks (section 3: the layers of the GPT2 model
+// in tile form; section 2: tasks are inserted in program order and run as soon as
+// their tiles are ready).  Pre-LN block with biases on the four linear layers,
+// causal attention and no dropout:
+//
+//   X1 = LN(X)            QKV = W_qkv X1 +. b      Q, K, V = heads(QKV)
+//   P  = softmax(K^T Q / sqrt(h))  (causal)        B = V P      Bm = merge(B)
+//   X2 = X + W_o Bm +. b_o
+//   X3 = LN(X2)           H1 = W_1 X3 +. b_1       G = gelu(H1)
+//   Out = X2 + W_2 G +. b_2
+//
+// The backward pass is the exact adjoint, in reverse order.
+#include "internal.hpp"
+
+#include <cmath>
+
+struct nnt_gpt2_block {
+    nnt_ctx* ctx;
+    nnt_gpt2_block_cfg cfg;
+    nnt_tensor* s[NNT_BLK_NSLOTS];
+    nnt_tensor* X;      // input of the last forward call
+};
+
+using namespace nnt;
+
+namespace {
+
+bool cfg_ok(const nnt_gpt2_block_cfg* c) {
+    if (!c) return false;
+    if (c->N_e < 1 || c->N_h < 1 || c->N_m < 1 || c->N_s < 1 || c->N_b < 1 || c->N_e % c->N_h != 0) return false;
+    if (c->tile_e < 1 || c->tile_m < 1 || c->tile_s < 1 || c->tile_b < 1 || c->tile_j < 1 || c->tile_i < 1) return false;
+    if (c->dtype != NNT_F32 && c->dtype != NNT_BF16) return false;
+    if (c->gelu_variant != NNT_GELU_TANH && c->gelu_variant != NNT_GELU_ERF) return false;
+    return true;
+}
+
+void set(nnt_slot_info* o, int dtype, int ndim, const int64_t* shape, const int64_t* base, int causal = 0) {
+    o->used = 1;
+    o->dtype = dtype;
+    o->ndim = ndim;
+    o->causal_tiles = causal;
+    for (int a = 0; a < NNT_MAX_DIM; a++) {
+        o->shape[a] = a < ndim ? shape[a] : 1;
+        o->basetile[a] = a < ndim ? (base[a] < shape[a] ? base[a] : shape[a]) : 1;
+    }
+}
+
+void param_geometry(const nnt_gpt2_block_cfg* c, int p, int* ndim, int64_t* shape, int64_t* base) {
+    const int64_t e = c->N_e, m = c->N_m, te = c->tile_e, tm = c->tile_m;
+    switch (p) {
+        case NNT_BLK_W_QKV: *ndim = 2; shape[0] = 3 * e; shape[1] = e; base[0] = te; base[1] = te; break;
+        case NNT_BLK_W_O: *ndim = 2; shape[0] = e; shape[1] = e; base[0] = te; base[1] = te; break;
+        case NNT_BLK_W_1: *ndim = 2; shape[0] = m; shape[1] = e; base[0] = tm; base[1] = te; break;
+        case NNT_BLK_W_2: *ndim = 2; shape[0] = e; shape[1] = m; base[0] = te; base[1] = tm; break;
+        case NNT_BLK_B_QKV: *ndim = 1; shape[0] = 3 * e; base[0] = te; break;
+        case NNT_BLK_B_1: *ndim = 1; shape[0] = m; base[0] = tm; break;
+        default: *ndim = 1; shape[0] = e; base[0] = te; break;   // b_o, b_2, gains and biases of the layer norms
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t nnt_gpt2_block_slot(const nnt_gpt2_block_cfg* c, int32_t slot, nnt_slot_info* o) {
+    if (!cfg_ok(c) || !o || slot < 0 || slot >= NNT_BLK_NSLOTS) return NNT_EINVAL;
+    *o = nnt_slot_info{};
+    const int64_t e = c->N_e, m = c->N_m, s = c->N_s, b = c->N_b, j = c->N_h, h = c->N_e / c->N_h;
+    const int64_t te = c->tile_e, tm = c->tile_m, ts = c->tile_s, tb = c->tile_b, tj = c->tile_j, ti = c->tile_i;
+    const int act = c->dtype;
+    int64_t shape[4], base[4];
+    int ndim;
+    if (slot < NNT_BLK_LOWP) {
+        param_geometry(c, slot % 12, &ndim, shape, base);
+        set(o, NNT_F32, ndim, shape, base);
+        return NNT_OK;
+    }
+    if (slot < NNT_BLK_LOWP + 4) {
+        if (act != NNT_BF16) return NNT_OK;      // unused in fp32 blocks
+        param_geometry(c, slot - NNT_BLK_LOWP, &ndim, shape, base);
+        set(o, NNT_BF16, ndim, shape, base);
+        return NNT_OK;
+    }
+    const int64_t act3[3] = {e, s, b}, act3b[3] = {te, ts, tb};
+    const int64_t qkv3[3] = {3 * e, s, b};
+    const int64_t mlp3[3] = {m, s, b}, mlp3b[3] = {tm, ts, tb};
+    const int64_t head4[4] = {h, s, b, j}, head4b[4] = {ti, ts, tb, tj};
+    const int64_t sc4[4] = {s, s, b, j}, sc4b[4] = {ts, ts, tb, tj};
+    const int64_t st3[3] = {2, s, b}, st3b[3] = {2, ts, tb};
+    const int64_t st4[4] = {2, s, b, j}, st4b[4] = {2, ts, tb, tj};
+    switch (slot) {
+        case NNT_BLK_STATS1: case NNT_BLK_STATS2: set(o, NNT_F32, 3, st3, st3b); break;
+        case NNT_BLK_SM_STATS: set(o, NNT_F32, 4, st4, st4b); break;
+        case NNT_BLK_X1: case NNT_BLK_BM: case NNT_BLK_X2: case NNT_BLK_X3:
+        case NNT_BLK_DX3: case NNT_BLK_DX2: case NNT_BLK_DBM: case NNT_BLK_DX1:
+            set(o, act, 3, act3, act3b); break;
+        case NNT_BLK_QKV: case NNT_BLK_DQKV: set(o, act, 3, qkv3, act3b); break;
+        case NNT_BLK_Q: case NNT_BLK_K: case NNT_BLK_V: case NNT_BLK_BH:
+        case NNT_BLK_DBH: case NNT_BLK_DQ: case NNT_BLK_DK: case NNT_BLK_DV:
+            set(o, act, 4, head4, head4b); break;
+        case NNT_BLK_P: case NNT_BLK_DP: set(o, act, 4, sc4, sc4b, c->causal ? 1 : 0); break;
+        case NNT_BLK_H1: case NNT_BLK_G: case NNT_BLK_DG: set(o, act, 3, mlp3, mlp3b); break;
+        default: return NNT_EINVAL;
+    }
+    return NNT_OK;
+}
+
+int32_t nnt_gpt2_block_create(nnt_ctx* ctx, const nnt_gpt2_block_cfg* cfg, nnt_tensor* const* slots, nnt_gpt2_block** out) {
+    NNT_CHECK_CTX(ctx);
+    if (!out) return NNT_EINVAL;
+    *out = nullptr;
+    if (!cfg_ok(cfg) || !slots) return fail(ctx, NNT_EINVAL, "nnt_gpt2_block_create: bad configuration");
+    nnt_gpt2_block* blk = new (std::nothrow) nnt_gpt2_block();
+    if (!blk) return fail(ctx, NNT_ENOMEM, "host allocation failed");
+    blk->ctx = ctx;
+    blk->cfg = *cfg;
+    blk->X = nullptr;
+    for (int i = 0; i < NNT_BLK_NSLOTS; i++) {
+        nnt_slot_info info;
+        nnt_gpt2_block_slot(cfg, i, &info);
+        nnt_tensor* t = slots[i];
+        blk->s[i] = t;
+        const bool optional = i >= NNT_BLK_ADAM_M && i < NNT_BLK_LOWP;
+        if (!info.used) continue;
+        if (!t) {
+            if (optional) continue;
+            delete blk;
+            return fail(ctx, NNT_EINVAL, "nnt_gpt2_block_create: missing tensor for slot " + std::to_string(i));
+        }
+        bool ok = t->ctx == ctx && t->dtype == info.dtype && t->ndim == info.ndim;
+        for (int a = 0; ok && a < info.ndim; a++) ok = t->shape[a] == info.shape[a] && t->base[a] == info.basetile[a];
+        if (!ok) {
+            delete blk;
+            return fail(ctx, NNT_EINVAL, "nnt_gpt2_block_create: tensor of slot " + std::to_string(i) + " has the wrong type, shape or tiling");
+        }
+    }
+    *out = blk;
+    return NNT_OK;
+}
+
+int32_t nnt_gpt2_block_destroy(nnt_gpt2_block* blk) {
+    if (!blk) return NNT_EINVAL;
+    delete blk;
+    return NNT_OK;
+}
+
+#define TRY(x)                      \
+    do {                            \
+        int32_t rc__ = (x);         \
+        if (rc__ != NNT_OK) return rc__; \
+    } while (0)
+
+static nnt_tensor* weight(nnt_gpt2_block* b, int p) { return b->cfg.dtype == NNT_BF16 ? b->s[NNT_BLK_LOWP + p] : b->s[p]; }
+
+// Y = W X +. bias: the bias rides in the product's epilogue when one launch covers
+// the whole operation, and is its own tile task otherwise.
+static int32_t linear(nnt_gpt2_block* b, nnt_tensor* W, nnt_tensor* X, nnt_tensor* bias, nnt_tensor* Y) {
+    nnt_ctx* ctx = b->ctx;
+    if (ctx->granularity == NNT_GRAN_OP) return nnt_gemm(ctx, 1.f, NNT_OP_N, W, NNT_OP_N, X, 0.f, Y, 1, 0, bias);
+    TRY(nnt_gemm(ctx, 1.f, NNT_OP_N, W, NNT_OP_N, X, 0.f, Y, 1, 0, nullptr));
+    return nnt_bias_add(ctx, bias, Y);
+}
+
+// dX = W^T dY,  dW = sum_{s,b} dY X^T,  db = sum_{s,b} dY
+static int32_t linear_bwd(nnt_gpt2_block* b, nnt_tensor* W, nnt_tensor* X, nnt_tensor* dY, nnt_tensor* dX,
+                          nnt_tensor* dW, nnt_tensor* db) {
+    nnt_ctx* ctx = b->ctx;
+    TRY(nnt_gemm(ctx, 1.f, NNT_OP_N, dY, NNT_OP_T, X, 0.f, dW, 2, 0, nullptr));
+    TRY(nnt_bias_grad(ctx, dY, db));
+    return nnt_gemm(ctx, 1.f, NNT_OP_T, W, NNT_OP_N, dY, 0.f, dX, 1, 0, nullptr);
+}
+
+int32_t nnt_gpt2_block_forward(nnt_gpt2_block* b, nnt_tensor* X, nnt_tensor* Out) {
+    if (!b) return NNT_EINVAL;
+    nnt_ctx* ctx = b->ctx;
+    NNT_CHECK_CTX(ctx);
+    if (!X || !Out) return fail(ctx, NNT_EINVAL, "nnt_gpt2_block_forward: null tensor");
+    nnt_tensor** s = b->s;
+    const nnt_gpt2_block_cfg& c = b->cfg;
+    const float sc = 1.f / std::sqrt((float)(c.N_e / c.N_h));
+    if (!same_tiling(X, s[NNT_BLK_X1]) || !same_tiling(Out, s[NNT_BLK_X1]) || X->dtype != c.dtype || Out->dtype != c.dtype)
+        return fail(ctx, NNT_EINVAL, "nnt_gpt2_block_forward: X / Out do not match the block's activations");
+    b->X = X;
+    TRY(nnt_layernorm_fwd(ctx, X, s[NNT_BLK_GAMMA1], s[NNT_BLK_BETA1], c.eps, s[NNT_BLK_X1], s[NNT_BLK_STATS1]));
+    TRY(linear(b, weight(b, NNT_BLK_W_QKV), s[NNT_BLK_X1], s[NNT_BLK_B_QKV], s[NNT_BLK_QKV]));
+    nnt_tensor* qkv[3] = {s[NNT_BLK_Q], s[NNT_BLK_K], s[NNT_BLK_V]};
+    TRY(nnt_head_split(ctx, s[NNT_BLK_QKV], 3, qkv));
+    TRY(nnt_gemm(ctx, sc, NNT_OP_T, s[NNT_BLK_K], NNT_OP_N, s[NNT_BLK_Q], 0.f, s[NNT_BLK_P], 1, 2, nullptr));
+    TRY(nnt_softmax_fwd(ctx, s[NNT_BLK_P], s[NNT_BLK_SM_STATS], 1.f, c.causal));
+    TRY(nnt_gemm(ctx, 1.f, NNT_OP_N, s[NNT_BLK_V], NNT_OP_N, s[NNT_BLK_P], 0.f, s[NNT_BLK_BH], 1, 2, nullptr));
+    nnt_tensor* bh[1] = {s[NNT_BLK_BH]};
+    TRY(nnt_head_merge(ctx, 1, bh, s[NNT_BLK_BM]));
+    TRY(linear(b, weight(b, NNT_BLK_W_O), s[NNT_BLK_BM], s[NNT_BLK_B_O], s[NNT_BLK_X2]));
+    TRY(nnt_add(ctx, 1.f, X, 1.f, s[NNT_BLK_X2]));
+    TRY(nnt_layernorm_fwd(ctx, s[NNT_BLK_X2], s[NNT_BLK_GAMMA2], s[NNT_BLK_BETA2], c.eps, s[NNT_BLK_X3], s[NNT_BLK_STATS2]));
+    TRY(linear(b, weight(b, NNT_BLK_W_1), s[NNT_BLK_X3], s[NNT_BLK_B_1], s[NNT_BLK_H1]));
+    TRY(nnt_gelu(ctx, c.gelu_variant, s[NNT_BLK_H1], s[NNT_BLK_G]));
+    TRY(linear(b, weight(b, NNT_BLK_W_2), s[NNT_BLK_G], s[NNT_BLK_B_2], Out));
+    return nnt_add(ctx, 1.f, s[NNT_BLK_X2], 1.f, Out);
+}
+
+int32_t nnt_gpt2_block_backward(nnt_gpt2_block* b, nnt_tensor* dOut, nnt_tensor* dX) {
+    if (!b) return NNT_EINVAL;
+    nnt_ctx* ctx = b->ctx;
+    NNT_CHECK_CTX(ctx);
+    if (!dOut || !dX) return fail(ctx, NNT_EINVAL, "nnt_gpt2_block_backward: null tensor");
+    if (!b->X) return fail(ctx, NNT_ESTATE, "nnt_gpt2_block_backward: no forward pass to differentiate");
+    nnt_tensor** s = b->s;
+    const nnt_gpt2_block_cfg& c = b->cfg;
+    const float sc = 1.f / std::sqrt((float)(c.N_e / c.N_h));
+    if (!same_tiling(dOut, s[NNT_BLK_X1]) || !same_tiling(dX, s[NNT_BLK_X1]) || dOut->dtype != c.dtype || dX->dtype != c.dtype)
+        return fail(ctx, NNT_EINVAL, "nnt_gpt2_block_backward: dOut / dX do not match the block's activations");
+    nnt_tensor** g = s + NNT_BLK_GRAD;
+    // MLP
+    TRY(linear_bwd(b, weight(b, NNT_BLK_W_2), s[NNT_BLK_G], dOut, s[NNT_BLK_DG], g[NNT_BLK_W_2], g[NNT_BLK_B_2]));
+    TRY(nnt_gelu_bwd(ctx, c.gelu_variant, s[NNT_BLK_H1], s[NNT_BLK_DG], s[NNT_BLK_DG]));
+    TRY(linear_bwd(b, weight(b, NNT_BLK_W_1), s[NNT_BLK_X3], s[NNT_BLK_DG], s[NNT_BLK_DX3], g[NNT_BLK_W_1], g[NNT_BLK_B_1]));
+    // second layer norm; the residual branch adds dOut
+    TRY(nnt_layernorm_bwd(ctx, s[NNT_BLK_X2], s[NNT_BLK_STATS2], s[NNT_BLK_GAMMA2], s[NNT_BLK_DX3], dOut, s[NNT_BLK_DX2],
+                          g[NNT_BLK_GAMMA2], g[NNT_BLK_BETA2]));
+    // attention output projection
+    TRY(linear_bwd(b, weight(b, NNT_BLK_W_O), s[NNT_BLK_BM], s[NNT_BLK_DX2], s[NNT_BLK_DBM], g[NNT_BLK_W_O], g[NNT_BLK_B_O]));
+    nnt_tensor* dbh[1] = {s[NNT_BLK_DBH]};
+    TRY(nnt_head_split(ctx, s[NNT_BLK_DBM], 1, dbh));
+    // dV = dB P^T, dP = V^T dB, softmax adjoint, dQ = K dA / sqrt(h), dK = Q dA^T / sqrt(h)
+    TRY(nnt_gemm(ctx, 1.f, NNT_OP_N, s[NNT_BLK_DBH], NNT_OP_T, s[NNT_BLK_P], 0.f, s[NNT_BLK_DV], 1, 2, nullptr));
+    TRY(nnt_gemm(ctx, 1.f, NNT_OP_T, s[NNT_BLK_V], NNT_OP_N, s[NNT_BLK_DBH], 0.f, s[NNT_BLK_DP], 1, 2, nullptr));
+    TRY(nnt_softmax_bwd(ctx, s[NNT_BLK_P], s[NNT_BLK_DP]));
+    TRY(nnt_gemm(ctx, sc, NNT_OP_N, s[NNT_BLK_K], NNT_OP_N, s[NNT_BLK_DP], 0.f, s[NNT_BLK_DQ], 1, 2, nullptr));
+    TRY(nnt_gemm(ctx, sc, NNT_OP_N, s[NNT_BLK_Q], NNT_OP_T, s[NNT_BLK_DP], 0.f, s[NNT_BLK_DK], 1, 2, nullptr));
+    nnt_tensor* dqkv[3] = {s[NNT_BLK_DQ], s[NNT_BLK_DK], s[NNT_BLK_DV]};
+    TRY(nnt_head_merge(ctx, 3, dqkv, s[NNT_BLK_DQKV]));
+    TRY(linear_bwd(b, weight(b, NNT_BLK_W_QKV), s[NNT_BLK_X1], s[NNT_BLK_DQKV], s[NNT_BLK_DX1], g[NNT_BLK_W_QKV], g[NNT_BLK_B_QKV]));
+    // first layer norm; the residual branch adds dX2
+    return nnt_layernorm_bwd(ctx, b->X, s[NNT_BLK_STATS1], s[NNT_BLK_GAMMA1], s[NNT_BLK_DX1], s[NNT_BLK_DX2], dX,
+                             g[NNT_BLK_GAMMA1], g[NNT_BLK_BETA1]);
+}
+
+int32_t nnt_gpt2_block_adam(nnt_gpt2_block* b, int32_t step, const nnt_adam_cfg* cfg) {
+    if (!b) return NNT_EINVAL;
+    nnt_ctx* ctx = b->ctx;
+    NNT_CHECK_CTX(ctx);
+    if (!cfg || step < 1) return fail(ctx, NNT_EINVAL, "nnt_gpt2_block_adam: bad argument");
+    for (int p = 0; p < 12; p++)
+        if (!b->s[NNT_BLK_ADAM_M + p] || !b->s[NNT_BLK_ADAM_V + p])
+            return fail(ctx, NNT_ESTATE, "nnt_gpt2_block_adam: the block was created without Adam moments");
+    for (int p = 0; p < 12; p++) {
+        nnt_tensor* lowp = (b->cfg.dtype == NNT_BF16 && p < 4) ? b->s[NNT_BLK_LOWP + p] : nullptr;
+        TRY(nnt_adam_step(ctx, cfg, step, b->s[NNT_BLK_GRAD + p], b->s[p], b->s[NNT_BLK_ADAM_M + p], b->s[NNT_BLK_ADAM_V + p], lowp));
+    }
+    return NNT_OK;
+}
+
+int32_t nnt_gpt2_block_sync_lowp(nnt_gpt2_block* b) {
+    if (!b) return NNT_EINVAL;
+    nnt_ctx* ctx = b->ctx;
+    NNT_CHECK_CTX(ctx);
+    if (b->cfg.dtype != NNT_BF16) return NNT_OK;
+    for (int p = 0; p < 4; p++) TRY(nnt_cast(ctx, b->s[p], b->s[NNT_BLK_LOWP + p]));
+    return NNT_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,730 @@
+// Memory-bound elementwise tile kernels (section 3: activations apply directly to
+// every tile; the optimizer update is a per-element weighted sum; the bias is
+// added over the unchanged dimensions) and their tensor-level forms.
+//
+// One kernel template serves both forms.  In the tile form the operands are plain
+// pointers; in the tensor form each operand is a table of tile pointers and
+// blockIdx.y selects the tile, so a whole tiled tensor is handled by one launch.
+// Every thread moves 16-byte vectors (4 fp32 or 8 bf16) when the tile extents and
+// pointers allow it, single elements otherwise.
+#include "device_util.hpp"
+#include "internal.hpp"
+
+#include <algorithm>
+#include <cmath>
+
+namespace nnt {
+namespace {
+
+constexpr int kUnroll = 4;
+
+struct EwGeom {
+    TiledView v;        // tiling of the operands (tensor form)
+    int64_t n_single;   // element count (tile form)
+    int32_t tiled;
+};
+
+template <typename T>
+__device__ __forceinline__ T* pick(void* const* table, void* single, int tile) {
+    return static_cast<T*>(table ? table[tile] : single);
+}
+
+template <typename F>
+__global__ void __launch_bounds__(256) ew_kernel(F f, EwGeom g, int vec) {
+    const int tile = blockIdx.y;
+    int64_t n;
+    if (g.tiled) {
+        n = tile_numel(g.v, tile);
+    } else {
+        n = g.n_single;
+    }
+    typename F::Ctx c;
+    if (!f.setup(c, g, tile)) return;
+    constexpr int V = F::V;
+    if (vec) {
+#pragma unroll
+        for (int u = 0; u < kUnroll; u++) {
+            const int64_t i = (((int64_t)blockIdx.x * kUnroll + u) * 256 + threadIdx.x) * V;
+            if (i + V <= n) {
+                f.template run<V>(c, i);
+            } else {
+                for (int64_t j = i; j < n; j++) f.template run<1>(c, j);
+            }
+        }
+    } else {
+#pragma unroll
+        for (int u = 0; u < kUnroll * V; u++) {
+            const int64_t i = ((int64_t)blockIdx.x * kUnroll * V + u) * 256 + threadIdx.x;
+            if (i < n) f.template run<1>(c, i);
+        }
+    }
+}
+
+template <typename F>
+int32_t launch_ew(hipStream_t st, const F& f, const EwGeom& g, int64_t max_numel, int64_t ntiles, bool vec) {
+    if (max_numel <= 0 || ntiles <= 0) return NNT_OK;
+    const int64_t per_block = (int64_t)256 * kUnroll * F::V;
+    const int64_t gx = (max_numel + per_block - 1) / per_block;
+    if (gx > INT32_MAX || ntiles > 65535) return NNT_EINVAL;
+    hipLaunchKernelGGL((ew_kernel<F>), dim3((unsigned)gx, (unsigned)ntiles), dim3(256), 0, st, f, g, vec ? 1 : 0);
+    return hipGetLastError() == hipSuccess ? NNT_OK : NNT_EHIP;
+}
+
+// ------------------------------------------------------------------ functors
+struct Operand {
+    void* const* table;
+    void* single;
+};
+
+template <typename T>
+struct FillF {
+    static constexpr int V = VecOf<T>::V;
+    Operand x;
+    float value;
+    struct Ctx { T* x; };
+    __device__ bool setup(Ctx& c, const EwGeom&, int tile) const { c.x = pick<T>(x.table, x.single, tile); return c.x != nullptr; }
+    template <int W> __device__ void run(const Ctx& c, int64_t i) const {
+        float f[W];
+#pragma unroll
+        for (int j = 0; j < W; j++) f[j] = value;
+        stv<W>(c.x + i, f);
+    }
+};
+
+template <typename T>
+struct AddF {
+    static constexpr int V = VecOf<T>::V;
+    Operand x, y;
+    float alpha, beta;
+    struct Ctx { const T* x; T* y; };
+    __device__ bool setup(Ctx& c, const EwGeom&, int tile) const {
+        c.x = pick<const T>(x.table, x.single, tile);
+        c.y = pick<T>(y.table, y.single, tile);
+        return c.y != nullptr;
+    }
+    template <int W> __device__ void run(const Ctx& c, int64_t i) const {
+        float a[W], b[W];
+        ldv<W>(c.x + i, a);
+        if (beta != 0.f) {
+            ldv<W>(c.y + i, b);
+#pragma unroll
+            for (int j = 0; j < W; j++) a[j] = alpha * a[j] + beta * b[j];
+        } else {
+#pragma unroll
+            for (int j = 0; j < W; j++) a[j] = alpha * a[j];
+        }
+        stv<W>(c.y + i, a);
+    }
+};
+
+template <typename TI, typename TO>
+struct CastF {
+    static constexpr int V = 8;     // 8 elements per thread whatever the types
+    Operand x, y;
+    struct Ctx { const TI* x; TO* y; };
+    __device__ bool setup(Ctx& c, const EwGeom&, int tile) const {
+        c.x = pick<const TI>(x.table, x.single, tile);
+        c.y = pick<TO>(y.table, y.single, tile);
+        return c.y != nullptr;
+    }
+    template <int W> __device__ void run(const Ctx& c, int64_t i) const {
+        if constexpr (W == 8) {
+            float a[4], b[4], f[8];
+            if constexpr (sizeof(TI) == 4) { ldv<4>(c.x + i, a); ldv<4>(c.x + i + 4, b);
+#pragma unroll
+                for (int j = 0; j < 4; j++) { f[j] = a[j]; f[4 + j] = b[j]; }
+            } else { ldv<8>(c.x + i, f); }
+            if constexpr (sizeof(TO) == 4) {
+#pragma unroll
+                for (int j = 0; j < 4; j++) { a[j] = f[j]; b[j] = f[4 + j]; }
+                stv<4>(c.y + i, a); stv<4>(c.y + i + 4, b);
+            } else { stv<8>(c.y + i, f); }
+        } else {
+            float f[1];
+            ldv<1>(c.x + i, f);
+            stv<1>(c.y + i, f);
+        }
+    }
+};
+
+__device__ __forceinline__ float gelu_f(float x, int variant) {
+    if (variant == NNT_GELU_TANH) {
+        const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
+        return 0.5f * x * (1.f + tanhf(u));
+    }
+    return 0.5f * x * (1.f + erff(x * 0.7071067811865476f));
+}
+__device__ __forceinline__ float gelu_grad_f(float x, int variant) {
+    if (variant == NNT_GELU_TANH) {
+        const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
+        const float t = tanhf(u);
+        return 0.5f * (1.f + t) + 0.5f * x * (1.f - t * t) * 0.7978845608028654f * (1.f + 3.f * 0.044715f * x * x);
+    }
+    return 0.5f * (1.f + erff(x * 0.7071067811865476f)) + x * 0.3989422804014327f * expf(-0.5f * x * x);
+}
+
+template <typename T>
+struct GeluF {
+    static constexpr int V = VecOf<T>::V;
+    Operand x, y;
+    int variant;
+    struct Ctx { const T* x; T* y; };
+    __device__ bool setup(Ctx& c, const EwGeom&, int tile) const {
+        c.x = pick<const T>(x.table, x.single, tile);
+        c.y = pick<T>(y.table, y.single, tile);
+        return c.y != nullptr;
+    }
+    template <int W> __device__ void run(const Ctx& c, int64_t i) const {
+        float a[W];
+        ldv<W>(c.x + i, a);
+#pragma unroll
+        for (int j = 0; j < W; j++) a[j] = gelu_f(a[j], variant);
+        stv<W>(c.y + i, a);
+    }
+};
+
+template <typename T>
+struct GeluBwdF {
+    static constexpr int V = VecOf<T>::V;
+    Operand x, dy, dx;
+    int variant;
+    struct Ctx { const T* x; const T* dy; T* dx; };
+    __device__ bool setup(Ctx& c, const EwGeom&, int tile) const {
+        c.x = pick<const T>(x.table, x.single, tile);
+        c.dy = pick<const T>(dy.table, dy.single, tile);
+        c.dx = pick<T>(dx.table, dx.single, tile);
+        return c.dx != nullptr;
+    }
+    template <int W> __device__ void run(const Ctx& c, int64_t i) const {
+        float a[W], d[W];
+        ldv<W>(c.x + i, a);
+        ldv<W>(c.dy + i, d);
+#pragma unroll
+        for (int j = 0; j < W; j++) a[j] = d[j] * gelu_grad_f(a[j], variant);
+        stv<W>(c.dx + i, a);
+    }
+};
+
+// Y (m x n, m fastest) += bias[m].  In the tensor form the bias tile is the one
+// with the tile's first grid coordinate.
+template <typename T>
+struct BiasAddF {
+    static constexpr int V = VecOf<T>::V;
+    Operand y, b;
+    int64_t m_single;
+    struct Ctx { T* y; const float* b; int m; };
+    __device__ bool setup(Ctx& c, const EwGeom& g, int tile) const {
+        c.y = pick<T>(y.table, y.single, tile);
+        if (g.tiled) {
+            int tc[kMaxDim], ext[kMaxDim];
+            tile_geometry(g.v, tile, tc, ext);
+            c.m = ext[0];
+            c.b = static_cast<const float*>(b.table[tc[0]]);
+        } else {
+            c.m = (int)m_single;
+            c.b = static_cast<const float*>(b.single);
+        }
+        return c.y != nullptr;
+    }
+    template <int W> __device__ void run(const Ctx& c, int64_t i) const {
+        float a[W];
+        ldv<W>(c.y + i, a);
+        const int r = (int)(i % c.m);       // a vector never crosses a column: m % W == 0 on this path
+#pragma unroll
+        for (int j = 0; j < W; j++) a[j] += c.b[r + j];
+        stv<W>(c.y + i, a);
+    }
+};
+
+struct AdamF {
+    static constexpr int V = 4;
+    Operand g, p, m, v, lp;
+    float lr, beta1, beta2, eps, wd, inv_bc1, inv_bc2;
+    struct Ctx { const float* g; float* p; float* m; float* v; bf16_t* lp; };
+    __device__ bool setup(Ctx& c, const EwGeom&, int tile) const {
+        c.g = pick<const float>(g.table, g.single, tile);
+        c.p = pick<float>(p.table, p.single, tile);
+        c.m = pick<float>(m.table, m.single, tile);
+        c.v = pick<float>(v.table, v.single, tile);
+        c.lp = (lp.table || lp.single) ? pick<bf16_t>(lp.table, lp.single, tile) : nullptr;
+        return c.p != nullptr;
+    }
+    template <int W> __device__ void run(const Ctx& c, int64_t i) const {
+        float gg[W], pp[W], mm[W], vv[W];
+        ldv<W>(c.g + i, gg);
+        ldv<W>(c.p + i, pp);
+        ldv<W>(c.m + i, mm);
+        ldv<W>(c.v + i, vv);
+#pragma unroll
+        for (int j = 0; j < W; j++) {
+            mm[j] = beta1 * mm[j] + (1.f - beta1) * gg[j];
+            vv[j] = beta2 * vv[j] + (1.f - beta2) * gg[j] * gg[j];
+            const float mhat = mm[j] * inv_bc1;
+            const float vhat = vv[j] * inv_bc2;
+            pp[j] = pp[j] - lr * wd * pp[j] - lr * mhat / (sqrtf(vhat) + eps);
+        }
+        stv<W>(c.p + i, pp);
+        stv<W>(c.m + i, mm);
+        stv<W>(c.v + i, vv);
+        if (c.lp) {
+            if constexpr (W == 4) {
+                uint2 x;
+                x.x = (uint32_t)f2bf(pp[0]) | ((uint32_t)f2bf(pp[1]) << 16);
+                x.y = (uint32_t)f2bf(pp[2]) | ((uint32_t)f2bf(pp[3]) << 16);
+                *reinterpret_cast<uint2*>(c.lp + i) = x;
+            } else {
+                c.lp[i] = f2bf(pp[0]);
+            }
+        }
+    }
+};
+
+// ------------------------------------------------------------------ strided block copy
+template <typename T>
+__global__ void __launch_bounds__(256) copy_block_kernel(const T* src, T* dst, int e0, int e1, int e2, int e3,
+                                                         int64_t s0, int64_t s1, int64_t s2, int64_t s3,
+                                                         int64_t d0, int64_t d1, int64_t d2, int64_t d3) {
+    const int64_t total = (int64_t)e0 * e1 * e2 * e3;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+        int64_t r = i;
+        const int i0 = (int)(r % e0); r /= e0;
+        const int i1 = (int)(r % e1); r /= e1;
+        const int i2 = (int)(r % e2); r /= e2;
+        const int i3 = (int)r;
+        dst[i0 * d0 + i1 * d1 + i2 * d2 + i3 * d3] = src[i0 * s0 + i1 * s1 + i2 * s2 + i3 * s3];
+    }
+}
+
+// ------------------------------------------------------------------ head split / merge over tiled views
+struct HeadArgs {
+    TiledView z;
+    TiledView part[3];
+    int32_t n_parts, N_h, h, to_parts;
+};
+
+template <typename T, int V>
+__global__ void __launch_bounds__(256) head_kernel(HeadArgs a) {
+    const int rows = a.z.shape[0], N_s = a.z.shape[1], N_b = a.z.shape[2];
+    const int64_t nvec = (int64_t)(rows / V) * N_s * N_b;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= nvec) return;
+    const int r = (int)(idx % (rows / V)) * V;
+    const int s = (int)((idx / (rows / V)) % N_s);
+    const int b = (int)(idx / ((int64_t)(rows / V) * N_s));
+    const int head = r / a.h, i = r - head * a.h;
+    const int p = head / a.N_h, j = head - p * a.N_h;
+    const int cz[kMaxDim] = {r, s, b, 0};
+    const int cp[kMaxDim] = {i, s, b, j};
+    int tz, tp;
+    int64_t oz, op;
+    locate(a.z, cz, tz, oz);
+    const TiledView& pv = a.part[p];
+    locate(pv, cp, tp, op);
+    T* zp = static_cast<T*>(a.z.tiles[tz]) + oz;
+    T* pp = static_cast<T*>(pv.tiles[tp]) + op;
+    if constexpr (V * sizeof(T) == 16) {
+        if (a.to_parts) *reinterpret_cast<uint4*>(pp) = *reinterpret_cast<const uint4*>(zp);
+        else *reinterpret_cast<uint4*>(zp) = *reinterpret_cast<const uint4*>(pp);
+    } else {
+        if (a.to_parts) *pp = *zp;
+        else *zp = *pp;
+    }
+}
+
+bool all_aligned(const nnt_tensor* t) {
+    for (void* p : t->tiles)
+        if (p && !aligned16(p)) return false;
+    return true;
+}
+// every tile extent along axis 0 is a multiple of v
+bool axis0_multiple(const nnt_tensor* t, int v) { return t->base[0] % v == 0 && t->shape[0] % v == 0; }
+int64_t max_tile_numel(const nnt_tensor* t) {
+    int64_t n = 1;
+    for (int a = 0; a < t->ndim; a++) n *= t->base[a];
+    return n;
+}
+EwGeom tiled_geom(const nnt_tensor* t) {
+    EwGeom g;
+    g.v = t->view();
+    g.n_single = 0;
+    g.tiled = 1;
+    return g;
+}
+EwGeom single_geom(int64_t n) {
+    EwGeom g = {};
+    g.n_single = n;
+    g.tiled = 0;
+    return g;
+}
+Operand tab(const nnt_tensor* t) { return Operand{t ? t->d_tiles : nullptr, nullptr}; }
+Operand tab1(const nnt_tensor* t, int64_t tile) { return Operand{nullptr, t ? t->tiles[tile] : nullptr}; }
+Operand ptr(const void* p) { return Operand{nullptr, const_cast<void*>(p)}; }
+
+// Runs functor maker `mk(single_tile_index or -1)` either once over all tiles or tile by tile.
+template <typename MakeF>
+int32_t run_tensor_ew(nnt_ctx* ctx, nnt_tensor* ref, const std::vector<std::pair<nnt_tensor*, int>>& operands,
+                      bool vec, MakeF mk) {
+    if (ref->ntiles > 65535) return fail(ctx, NNT_EINVAL, "too many tiles for one launch");
+    if (ctx->granularity == NNT_GRAN_OP) {
+        std::vector<Access> acc;
+        for (auto& o : operands) acc.push_back(o.first->all(o.second));
+        auto f = mk((int64_t)-1);
+        const EwGeom g = tiled_geom(ref);
+        const int64_t mx = max_tile_numel(ref), nt = ref->ntiles;
+        return submit(ctx, acc, [=](hipStream_t st) { return launch_ew(st, f, g, mx, nt, vec); });
+    }
+    for (int64_t t = 0; t < ref->ntiles; t++) {
+        if (!ref->tiles[t]) continue;
+        std::vector<Access> acc;
+        for (auto& o : operands) acc.push_back(o.first->one(o.first->ntiles == ref->ntiles ? t : 0, o.second));
+        auto f = mk(t);
+        const int64_t n = ref->tile_numel(t);
+        const EwGeom g = single_geom(n);
+        int32_t rc = submit(ctx, acc, [=](hipStream_t st) { return launch_ew(st, f, g, n, 1, vec); });
+        if (rc != NNT_OK) return rc;
+    }
+    return NNT_OK;
+}
+
+Operand opnd(const nnt_tensor* t, int64_t tile) { return tile < 0 ? tab(t) : tab1(t, tile); }
+
+}  // namespace
+}  // namespace nnt
+
+using namespace nnt;
+
+#define DT_OK(d) ((d) == NNT_F32 || (d) == NNT_BF16)
+
+extern "C" {
+
+// ------------------------------------------------------------------ tile form
+int32_t nnt_tile_fill(void* stream, int32_t dtype, int64_t n, float value, void* x) {
+    if (!DT_OK(dtype)) return NNT_EDTYPE;
+    if (n < 0 || (n > 0 && !x)) return NNT_EINVAL;
+    const bool vec = aligned16(x);
+    if (dtype == NNT_F32) return launch_ew((hipStream_t)stream, FillF<float>{ptr(x), value}, single_geom(n), n, 1, vec);
+    return launch_ew((hipStream_t)stream, FillF<bf16_t>{ptr(x), value}, single_geom(n), n, 1, vec);
+}
+
+int32_t nnt_tile_add(void* stream, int32_t dtype, int64_t n, float alpha, const void* x, float beta, void* y) {
+    if (!DT_OK(dtype)) return NNT_EDTYPE;
+    if (n < 0 || (n > 0 && (!x || !y))) return NNT_EINVAL;
+    const bool vec = aligned16(x) && aligned16(y);
+    if (dtype == NNT_F32) return launch_ew((hipStream_t)stream, AddF<float>{ptr(x), ptr(y), alpha, beta}, single_geom(n), n, 1, vec);
+    return launch_ew((hipStream_t)stream, AddF<bf16_t>{ptr(x), ptr(y), alpha, beta}, single_geom(n), n, 1, vec);
+}
+
+int32_t nnt_tile_cast(void* stream, int32_t dtype_in, int32_t dtype_out, int64_t n, const void* x, void* y) {
+    if (!DT_OK(dtype_in) || !DT_OK(dtype_out)) return NNT_EDTYPE;
+    if (n < 0 || (n > 0 && (!x || !y))) return NNT_EINVAL;
+    const bool vec = aligned16(x) && aligned16(y);
+    hipStream_t st = (hipStream_t)stream;
+    const EwGeom g = single_geom(n);
+    if (dtype_in == NNT_F32 && dtype_out == NNT_BF16) return launch_ew(st, CastF<float, bf16_t>{ptr(x), ptr(y)}, g, n, 1, vec);
+    if (dtype_in == NNT_BF16 && dtype_out == NNT_F32) return launch_ew(st, CastF<bf16_t, float>{ptr(x), ptr(y)}, g, n, 1, vec);
+    if (dtype_in == NNT_F32) return launch_ew(st, CastF<float, float>{ptr(x), ptr(y)}, g, n, 1, vec);
+    return launch_ew(st, CastF<bf16_t, bf16_t>{ptr(x), ptr(y)}, g, n, 1, vec);
+}
+
+int32_t nnt_tile_copy_block(void* stream, int32_t dtype, int32_t ndim, const int64_t* extent,
+                            const void* src, const int64_t* ss, void* dst, const int64_t* ds) {
+    if (!DT_OK(dtype)) return NNT_EDTYPE;
+    if (ndim < 1 || ndim > kMaxDim || !extent || !ss || !ds || !src || !dst) return NNT_EINVAL;
+    int64_t e[4] = {1, 1, 1, 1}, s[4] = {0, 0, 0, 0}, d[4] = {0, 0, 0, 0}, total = 1;
+    for (int a = 0; a < ndim; a++) {
+        if (extent[a] < 0 || extent[a] > INT32_MAX) return NNT_EINVAL;
+        e[a] = extent[a]; s[a] = ss[a]; d[a] = ds[a];
+        total *= e[a];
+    }
+    if (total == 0) return NNT_OK;
+    const unsigned blocks = (unsigned)std::min<int64_t>((total + 255) / 256, 1 << 16);
+    hipStream_t st = (hipStream_t)stream;
+    if (dtype == NNT_F32)
+        hipLaunchKernelGGL((copy_block_kernel<float>), dim3(blocks), dim3(256), 0, st, (const float*)src, (float*)dst,
+                           (int)e[0], (int)e[1], (int)e[2], (int)e[3], s[0], s[1], s[2], s[3], d[0], d[1], d[2], d[3]);
+    else
+        hipLaunchKernelGGL((copy_block_kernel<bf16_t>), dim3(blocks), dim3(256), 0, st, (const bf16_t*)src, (bf16_t*)dst,
+                           (int)e[0], (int)e[1], (int)e[2], (int)e[3], s[0], s[1], s[2], s[3], d[0], d[1], d[2], d[3]);
+    return hipGetLastError() == hipSuccess ? NNT_OK : NNT_EHIP;
+}
+
+int32_t nnt_tile_bias_add(void* stream, int32_t dtype, int64_t m, int64_t n, const float* bias, void* Y) {
+    if (!DT_OK(dtype)) return NNT_EDTYPE;
+    if (m < 0 || n < 0 || m > INT32_MAX || (m * n > 0 && (!bias || !Y))) return NNT_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    const EwGeom g = single_geom(m * n);
+    if (dtype == NNT_F32)
+        return launch_ew(st, BiasAddF<float>{ptr(Y), ptr(bias), m}, g, m * n, 1, aligned16(Y) && m % 4 == 0);
+    return launch_ew(st, BiasAddF<bf16_t>{ptr(Y), ptr(bias), m}, g, m * n, 1, aligned16(Y) && m % 8 == 0);
+}
+
+int32_t nnt_tile_gelu(void* stream, int32_t dtype, int32_t variant, int64_t n, const void* x, void* y) {
+    if (!DT_OK(dtype)) return NNT_EDTYPE;
+    if ((variant != NNT_GELU_TANH && variant != NNT_GELU_ERF) || n < 0 || (n > 0 && (!x || !y))) return NNT_EINVAL;
+    const bool vec = aligned16(x) && aligned16(y);
+    if (dtype == NNT_F32) return launch_ew((hipStream_t)stream, GeluF<float>{ptr(x), ptr(y), variant}, single_geom(n), n, 1, vec);
+    return launch_ew((hipStream_t)stream, GeluF<bf16_t>{ptr(x), ptr(y), variant}, single_geom(n), n, 1, vec);
+}
+
+int32_t nnt_tile_gelu_bwd(void* stream, int32_t dtype, int32_t variant, int64_t n, const void* x, const void* dy, void* dx) {
+    if (!DT_OK(dtype)) return NNT_EDTYPE;
+    if ((variant != NNT_GELU_TANH && variant != NNT_GELU_ERF) || n < 0 || (n > 0 && (!x || !dy || !dx))) return NNT_EINVAL;
+    const bool vec = aligned16(x) && aligned16(dy) && aligned16(dx);
+    if (dtype == NNT_F32)
+        return launch_ew((hipStream_t)stream, GeluBwdF<float>{ptr(x), ptr(dy), ptr(dx), variant}, single_geom(n), n, 1, vec);
+    return launch_ew((hipStream_t)stream, GeluBwdF<bf16_t>{ptr(x), ptr(dy), ptr(dx), variant}, single_geom(n), n, 1, vec);
+}
+
+static AdamF make_adam(int32_t step, float lr, float b1, float b2, float eps, float wd) {
+    AdamF f = {};
+    f.lr = lr; f.beta1 = b1; f.beta2 = b2; f.eps = eps; f.wd = wd;
+    f.inv_bc1 = (float)(1.0 / (1.0 - std::pow((double)b1, (double)step)));
+    f.inv_bc2 = (float)(1.0 / (1.0 - std::pow((double)b2, (double)step)));
+    return f;
+}
+
+int32_t nnt_tile_adam(void* stream, int64_t n, int32_t step, float lr, float beta1, float beta2, float eps,
+                      float weight_decay, const float* g, float* p, float* m, float* v, void* p_lowp) {
+    if (n < 0 || step < 1 || (n > 0 && (!g || !p || !m || !v))) return NNT_EINVAL;
+    AdamF f = make_adam(step, lr, beta1, beta2, eps, weight_decay);
+    f.g = ptr(g); f.p = ptr(p); f.m = ptr(m); f.v = ptr(v); f.lp = ptr(p_lowp);
+    const bool vec = aligned16(g) && aligned16(p) && aligned16(m) && aligned16(v) && (!p_lowp || ((uintptr_t)p_lowp & 7) == 0);
+    return launch_ew((hipStream_t)stream, f, single_geom(n), n, 1, vec);
+}
+
+// ------------------------------------------------------------------ tensor form
+int32_t nnt_fill(nnt_ctx* ctx, float value, nnt_tensor* X) {
+    NNT_CHECK_CTX(ctx);
+    if (!X) return fail(ctx, NNT_EINVAL, "nnt_fill: null tensor");
+    const bool vec = all_aligned(X);
+    if (X->dtype == NNT_F32)
+        return run_tensor_ew(ctx, X, {{X, kWrite}}, vec, [=](int64_t t) { return FillF<float>{opnd(X, t), value}; });
+    return run_tensor_ew(ctx, X, {{X, kWrite}}, vec, [=](int64_t t) { return FillF<bf16_t>{opnd(X, t), value}; });
+}
+
+int32_t nnt_add(nnt_ctx* ctx, float alpha, nnt_tensor* X, float beta, nnt_tensor* Y) {
+    NNT_CHECK_CTX(ctx);
+    if (!X || !Y) return fail(ctx, NNT_EINVAL, "nnt_add: null tensor");
+    if (!same_tiling(X, Y) || !null_alike(X, Y)) return fail(ctx, NNT_EINVAL, "nnt_add: operands tiled differently");
+    if (X->dtype != Y->dtype) return fail(ctx, NNT_EDTYPE, "nnt_add: operand types differ");
+    const bool vec = all_aligned(X) && all_aligned(Y);
+    const int ymode = beta != 0.f ? kReadWrite : kWrite;
+    if (X->dtype == NNT_F32)
+        return run_tensor_ew(ctx, Y, {{X, kRead}, {Y, ymode}}, vec,
+                             [=](int64_t t) { return AddF<float>{opnd(X, t), opnd(Y, t), alpha, beta}; });
+    return run_tensor_ew(ctx, Y, {{X, kRead}, {Y, ymode}}, vec,
+                         [=](int64_t t) { return AddF<bf16_t>{opnd(X, t), opnd(Y, t), alpha, beta}; });
+}
+
+int32_t nnt_cast(nnt_ctx* ctx, nnt_tensor* X, nnt_tensor* Y) {
+    NNT_CHECK_CTX(ctx);
+    if (!X || !Y) return fail(ctx, NNT_EINVAL, "nnt_cast: null tensor");
+    if (!same_tiling(X, Y) || !null_alike(X, Y)) return fail(ctx, NNT_EINVAL, "nnt_cast: operands tiled differently");
+    const bool vec = all_aligned(X) && all_aligned(Y);
+    std::vector<std::pair<nnt_tensor*, int>> ops = {{X, kRead}, {Y, kWrite}};
+    if (X->dtype == NNT_F32 && Y->dtype == NNT_BF16)
+        return run_tensor_ew(ctx, Y, ops, vec, [=](int64_t t) { return CastF<float, bf16_t>{opnd(X, t), opnd(Y, t)}; });
+    if (X->dtype == NNT_BF16 && Y->dtype == NNT_F32)
+        return run_tensor_ew(ctx, Y, ops, vec, [=](int64_t t) { return CastF<bf16_t, float>{opnd(X, t), opnd(Y, t)}; });
+    if (X->dtype == NNT_F32)
+        return run_tensor_ew(ctx, Y, ops, vec, [=](int64_t t) { return CastF<float, float>{opnd(X, t), opnd(Y, t)}; });
+    return run_tensor_ew(ctx, Y, ops, vec, [=](int64_t t) { return CastF<bf16_t, bf16_t>{opnd(X, t), opnd(Y, t)}; });
+}
+
+int32_t nnt_gelu(nnt_ctx* ctx, int32_t variant, nnt_tensor* X, nnt_tensor* Y) {
+    NNT_CHECK_CTX(ctx);
+    if (!X || !Y) return fail(ctx, NNT_EINVAL, "nnt_gelu: null tensor");
+    if (variant != NNT_GELU_TANH && variant != NNT_GELU_ERF) return fail(ctx, NNT_EINVAL, "nnt_gelu: unknown variant");
+    if (!same_tiling(X, Y) || !null_alike(X, Y)) return fail(ctx, NNT_EINVAL, "nnt_gelu: operands tiled differently");
+    if (X->dtype != Y->dtype) return fail(ctx, NNT_EDTYPE, "nnt_gelu: operand types differ");
+    const bool vec = all_aligned(X) && all_aligned(Y);
+    std::vector<std::pair<nnt_tensor*, int>> ops = {{X, kRead}, {Y, kWrite}};
+    if (X->dtype == NNT_F32)
+        return run_tensor_ew(ctx, Y, ops, vec, [=](int64_t t) { return GeluF<float>{opnd(X, t), opnd(Y, t), variant}; });
+    return run_tensor_ew(ctx, Y, ops, vec, [=](int64_t t) { return GeluF<bf16_t>{opnd(X, t), opnd(Y, t), variant}; });
+}
+
+int32_t nnt_gelu_bwd(nnt_ctx* ctx, int32_t variant, nnt_tensor* X, nnt_tensor* dY, nnt_tensor* dX) {
+    NNT_CHECK_CTX(ctx);
+    if (!X || !dY || !dX) return fail(ctx, NNT_EINVAL, "nnt_gelu_bwd: null tensor");
+    if (variant != NNT_GELU_TANH && variant != NNT_GELU_ERF) return fail(ctx, NNT_EINVAL, "nnt_gelu_bwd: unknown variant");
+    if (!same_tiling(X, dY) || !same_tiling(X, dX) || !null_alike(X, dY) || !null_alike(X, dX))
+        return fail(ctx, NNT_EINVAL, "nnt_gelu_bwd: operands tiled differently");
+    if (X->dtype != dY->dtype || X->dtype != dX->dtype) return fail(ctx, NNT_EDTYPE, "nnt_gelu_bwd: operand types differ");
+    const bool vec = all_aligned(X) && all_aligned(dY) && all_aligned(dX);
+    std::vector<std::pair<nnt_tensor*, int>> ops = {{X, kRead}, {dY, kRead}, {dX, dX == dY ? kReadWrite : kWrite}};
+    if (dX == dY) ops.erase(ops.begin() + 1);
+    if (X->dtype == NNT_F32)
+        return run_tensor_ew(ctx, dX, ops, vec,
+                             [=](int64_t t) { return GeluBwdF<float>{opnd(X, t), opnd(dY, t), opnd(dX, t), variant}; });
+    return run_tensor_ew(ctx, dX, ops, vec,
+                         [=](int64_t t) { return GeluBwdF<bf16_t>{opnd(X, t), opnd(dY, t), opnd(dX, t), variant}; });
+}
+
+int32_t nnt_bias_add(nnt_ctx* ctx, nnt_tensor* b, nnt_tensor* Y) {
+    NNT_CHECK_CTX(ctx);
+    if (!b || !Y) return fail(ctx, NNT_EINVAL, "nnt_bias_add: null tensor");
+    if (b->dtype != NNT_F32 || b->ndim != 1 || b->shape[0] != Y->shape[0] || b->base[0] != Y->base[0])
+        return fail(ctx, NNT_EINVAL, "nnt_bias_add: bias must be an fp32 vector tiled like Y's first axis");
+    for (void* p : b->tiles)
+        if (!p) return fail(ctx, NNT_EINVAL, "nnt_bias_add: bias tile missing");
+    const int V = Y->dtype == NNT_F32 ? 4 : 8;
+    const bool vec = all_aligned(Y) && axis0_multiple(Y, V);
+    if (Y->ntiles > 65535) return fail(ctx, NNT_EINVAL, "too many tiles for one launch");
+    if (ctx->granularity == NNT_GRAN_OP) {
+        const EwGeom g = tiled_geom(Y);
+        const int64_t mx = max_tile_numel(Y), nt = Y->ntiles;
+        std::vector<Access> acc = {b->all(kRead), Y->all(kReadWrite)};
+        if (Y->dtype == NNT_F32) {
+            BiasAddF<float> f{tab(Y), tab(b), 0};
+            return submit(ctx, acc, [=](hipStream_t st) { return launch_ew(st, f, g, mx, nt, vec); });
+        }
+        BiasAddF<bf16_t> f{tab(Y), tab(b), 0};
+        return submit(ctx, acc, [=](hipStream_t st) { return launch_ew(st, f, g, mx, nt, vec); });
+    }
+    for (int64_t t = 0; t < Y->ntiles; t++) {
+        if (!Y->tiles[t]) continue;
+        const int64_t c0 = t % Y->grid[0];
+        const int64_t m = Y->tile_extent(0, c0), n = Y->tile_numel(t) / m;
+        void* yp = Y->tiles[t];
+        const float* bp = static_cast<const float*>(b->tiles[c0]);
+        const int32_t dt = Y->dtype;
+        int32_t rc = submit(ctx, {b->one(c0, kRead), Y->one(t, kReadWrite)},
+                            [=](hipStream_t st) { return nnt_tile_bias_add(st, dt, m, n, bp, yp); });
+        if (rc != NNT_OK) return rc;
+    }
+    return NNT_OK;
+}
+
+int32_t nnt_adam_step(nnt_ctx* ctx, const nnt_adam_cfg* cfg, int32_t step, nnt_tensor* G, nnt_tensor* P,
+                      nnt_tensor* M, nnt_tensor* V, nnt_tensor* LP) {
+    NNT_CHECK_CTX(ctx);
+    if (!cfg || !G || !P || !M || !V || step < 1) return fail(ctx, NNT_EINVAL, "nnt_adam_step: bad argument");
+    if (!same_tiling(G, P) || !same_tiling(G, M) || !same_tiling(G, V) || (LP && !same_tiling(G, LP)))
+        return fail(ctx, NNT_EINVAL, "nnt_adam_step: operands tiled differently");
+    if (G->dtype != NNT_F32 || P->dtype != NNT_F32 || M->dtype != NNT_F32 || V->dtype != NNT_F32 || (LP && LP->dtype != NNT_BF16))
+        return fail(ctx, NNT_EDTYPE, "nnt_adam_step: g, p, m, v must be fp32 and the low-precision copy bf16");
+    const bool vec = all_aligned(G) && all_aligned(P) && all_aligned(M) && all_aligned(V) && (!LP || all_aligned(LP));
+    AdamF base = make_adam(step, cfg->lr, cfg->beta1, cfg->beta2, cfg->eps, cfg->weight_decay);
+    std::vector<std::pair<nnt_tensor*, int>> ops = {{G, kRead}, {P, kReadWrite}, {M, kReadWrite}, {V, kReadWrite}};
+    if (LP) ops.push_back({LP, kWrite});
+    return run_tensor_ew(ctx, P, ops, vec, [=](int64_t t) {
+        AdamF f = base;
+        f.g = opnd(G, t); f.p = opnd(P, t); f.m = opnd(M, t); f.v = opnd(V, t);
+        f.lp = LP ? opnd(LP, t) : Operand{nullptr, nullptr};
+        return f;
+    });
+}
+
+// ------------------------------------------------------------------ head split / merge
+static int32_t head_common(nnt_ctx* ctx, nnt_tensor* Z, int32_t n_parts, nnt_tensor* const* parts, int to_parts) {
+    NNT_CHECK_CTX(ctx);
+    if (!Z || !parts || n_parts < 1 || n_parts > 3) return fail(ctx, NNT_EINVAL, "head split/merge: bad argument");
+    if (Z->ndim != 3) return fail(ctx, NNT_EINVAL, "head split/merge: Z must have 3 axes");
+    for (int p = 0; p < n_parts; p++) {
+        const nnt_tensor* q = parts[p];
+        if (!q || q->ndim != 4 || q->dtype != Z->dtype || !same_tiling(q, parts[0]))
+            return fail(ctx, NNT_EINVAL, "head split/merge: parts must be 4-axis tensors of Z's type, tiled alike");
+        for (void* t : q->tiles)
+            if (!t) return fail(ctx, NNT_EINVAL, "head split/merge: structural-zero tiles not allowed");
+    }
+    for (void* t : Z->tiles)
+        if (!t) return fail(ctx, NNT_EINVAL, "head split/merge: structural-zero tiles not allowed");
+    const nnt_tensor* q0 = parts[0];
+    const int64_t h = q0->shape[0], N_h = q0->shape[3];
+    if (Z->shape[0] != n_parts * N_h * h || Z->shape[1] != q0->shape[1] || Z->shape[2] != q0->shape[2])
+        return fail(ctx, NNT_EINVAL, "head split/merge: shapes do not match");
+
+    if (ctx->granularity == NNT_GRAN_OP) {
+        HeadArgs a;
+        a.z = Z->view();
+        for (int p = 0; p < 3; p++) a.part[p] = parts[p < n_parts ? p : 0]->view();
+        a.n_parts = n_parts; a.N_h = (int32_t)N_h; a.h = (int32_t)h; a.to_parts = to_parts;
+        const int V = Z->dtype == NNT_F32 ? 4 : 8;
+        bool vec = all_aligned(Z) && axis0_multiple(Z, V) && h % V == 0;
+        for (int p = 0; p < n_parts; p++) vec = vec && all_aligned(parts[p]) && axis0_multiple(parts[p], V);
+        const int v = vec ? V : 1;
+        const int64_t nvec = Z->shape[0] / v * Z->shape[1] * Z->shape[2];
+        const int64_t blocks = (nvec + 255) / 256;
+        if (blocks > INT32_MAX) return fail(ctx, NNT_EINVAL, "head split/merge: tensor too large");
+        std::vector<Access> acc = {Z->all(to_parts ? kRead : kWrite)};
+        for (int p = 0; p < n_parts; p++) acc.push_back(parts[p]->all(to_parts ? kWrite : kRead));
+        const int32_t dt = Z->dtype;
+        return submit(ctx, acc, [=](hipStream_t st) {
+            dim3 grid((unsigned)blocks), block(256);
+            if (dt == NNT_F32) {
+                if (v == 4) hipLaunchKernelGGL((head_kernel<float, 4>), grid, block, 0, st, a);
+                else hipLaunchKernelGGL((head_kernel<float, 1>), grid, block, 0, st, a);
+            } else {
+                if (v == 8) hipLaunchKernelGGL((head_kernel<bf16_t, 8>), grid, block, 0, st, a);
+                else hipLaunchKernelGGL((head_kernel<bf16_t, 1>), grid, block, 0, st, a);
+            }
+            return hipGetLastError() == hipSuccess ? NNT_OK : NNT_EHIP;
+        });
+    }
+
+    // tile granularity: one task per (Z tile, part tile) pair that overlaps, made of block copies
+    const int32_t dt = Z->dtype;
+    for (int64_t zt = 0; zt < Z->ntiles; zt++) {
+        int64_t zc[kMaxDim];
+        Z->tile_coords(zt, zc);
+        const int64_t zr0 = zc[0] * Z->base[0], zr1 = zr0 + Z->tile_extent(0, zc[0]);
+        const int64_t zs0 = zc[1] * Z->base[1], zs1 = zs0 + Z->tile_extent(1, zc[1]);
+        const int64_t zb0 = zc[2] * Z->base[2], zb1 = zb0 + Z->tile_extent(2, zc[2]);
+        const int64_t zm = zr1 - zr0, zsn = zs1 - zs0;
+        for (int p = 0; p < n_parts; p++) {
+            nnt_tensor* q = parts[p];
+            for (int64_t qt = 0; qt < q->ntiles; qt++) {
+                int64_t qc[kMaxDim];
+                q->tile_coords(qt, qc);
+                const int64_t qi0 = qc[0] * q->base[0], qi1 = qi0 + q->tile_extent(0, qc[0]);
+                const int64_t qs0 = qc[1] * q->base[1], qs1 = qs0 + q->tile_extent(1, qc[1]);
+                const int64_t qb0 = qc[2] * q->base[2], qb1 = qb0 + q->tile_extent(2, qc[2]);
+                const int64_t qj0 = qc[3] * q->base[3], qj1 = qj0 + q->tile_extent(3, qc[3]);
+                const int64_t s0 = std::max(zs0, qs0), s1 = std::min(zs1, qs1);
+                const int64_t b0 = std::max(zb0, qb0), b1 = std::min(zb1, qb1);
+                if (s0 >= s1 || b0 >= b1) continue;
+                const int64_t qe0 = qi1 - qi0, qe1 = qs1 - qs0, qe2 = qb1 - qb0;
+                struct Copy { int64_t ext[3]; int64_t zoff, qoff; };
+                std::vector<Copy> copies;
+                for (int64_t j = qj0; j < qj1; j++) {
+                    const int64_t rbase = (p * N_h + j) * h;
+                    const int64_t r0 = std::max(zr0, rbase + qi0), r1 = std::min(zr1, rbase + qi1);
+                    if (r0 >= r1) continue;
+                    Copy c;
+                    c.ext[0] = r1 - r0; c.ext[1] = s1 - s0; c.ext[2] = b1 - b0;
+                    c.zoff = (r0 - zr0) + zm * ((s0 - zs0) + zsn * (b0 - zb0));
+                    c.qoff = (r0 - rbase - qi0) + qe0 * ((s0 - qs0) + qe1 * ((b0 - qb0) + qe2 * (j - qj0)));
+                    copies.push_back(c);
+                }
+                if (copies.empty()) continue;
+                const int64_t zstr[3] = {1, zm, zm * zsn};
+                const int64_t qstr[3] = {1, qe0, qe0 * qe1};
+                char* zbase = static_cast<char*>(Z->tiles[zt]);
+                char* qbase = static_cast<char*>(q->tiles[qt]);
+                const int64_t es = Z->elem_size();
+                std::vector<Access> acc = {Z->one(zt, to_parts ? kRead : kReadWrite), q->one(qt, to_parts ? kReadWrite : kRead)};
+                int32_t rc = submit(ctx, acc, [=](hipStream_t st) {
+                    for (const Copy& c : copies) {
+                        int32_t r;
+                        if (to_parts) r = nnt_tile_copy_block(st, dt, 3, c.ext, zbase + c.zoff * es, zstr, qbase + c.qoff * es, qstr);
+                        else r = nnt_tile_copy_block(st, dt, 3, c.ext, qbase + c.qoff * es, qstr, zbase + c.zoff * es, zstr);
+                        if (r != NNT_OK) return r;
+                    }
+                    return (int32_t)NNT_OK;
+                }, (int)copies.size());
+                if (rc != NNT_OK) return rc;
+            }
+        }
+    }
+    return NNT_OK;
+}
+
+int32_t nnt_head_split(nnt_ctx* ctx, nnt_tensor* Z, int32_t n_parts, nnt_tensor* const* parts) {
+    return head_common(ctx, Z, n_parts, parts, 1);
+}
+int32_t nnt_head_merge(nnt_ctx* ctx, int32_t n_parts, nnt_tensor* const* parts, nnt_tensor* Z) {
+    return head_common(ctx, Z, n_parts, parts, 0);
+}
+
+}  // extern "C"

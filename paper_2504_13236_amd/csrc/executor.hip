@@ -1,0 +1,321 @@
+// Sequential-task-flow executor on the HIP streams of one GPU (section 2, task
+// submission): tasks arrive in program order with the tiles they read and write;
+// read-after-write, write-after-read and write-after-write order per tile is kept
+// with events between streams, everything else may overlap.
+#include "internal.hpp"
+
+#include <algorithm>
+#include <cstring>
+
+namespace nnt {
+
+int32_t fail(nnt_ctx* ctx, int32_t code, const std::string& msg) {
+    if (ctx) {
+        ctx->error = msg;
+        // argument errors are the caller's to fix and leave the context usable;
+        // runtime failures stick
+        if (code == NNT_EHIP) ctx->status = code;
+    }
+    return code;
+}
+
+int32_t launch_status(const char* what) {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        fprintf(stderr, "nntile_mi: launch of %s failed: %s\n", what, hipGetErrorString(e));
+        return NNT_EHIP;
+    }
+    return NNT_OK;
+}
+
+static int32_t get_event(nnt_ctx* ctx, hipEvent_t* ev) {
+    if (!ctx->event_pool.empty()) {
+        *ev = ctx->event_pool.back();
+        ctx->event_pool.pop_back();
+        return NNT_OK;
+    }
+    NNT_HIP(ctx, hipEventCreateWithFlags(ev, hipEventDisableTiming));
+    return NNT_OK;
+}
+
+// Everything recorded so far is complete: forget the events.
+static void mark_all_synced(nnt_ctx* ctx) {
+    for (int s = 0; s < ctx->n_streams; s++) {
+        for (hipEvent_t e : ctx->events[s]) ctx->event_pool.push_back(e);
+        ctx->events[s].clear();
+        ctx->synced_seq[s] = ctx->tail_seq[s];
+    }
+}
+
+static int32_t sync_all(nnt_ctx* ctx) {
+    for (int s = 0; s < ctx->n_streams; s++) NNT_HIP(ctx, hipStreamSynchronize(ctx->streams[s]));
+    mark_all_synced(ctx);
+    return NNT_OK;
+}
+
+int32_t submit(nnt_ctx* ctx, const std::vector<Access>& acc,
+               const std::function<int32_t(hipStream_t)>& launch, int n_launches) {
+    NNT_CHECK_CTX(ctx);
+    const int ns = ctx->n_streams;
+    uint64_t need[kMaxStreams] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (const Access& a : acc) {
+        for (int64_t i = 0; i < a.count; i++) {
+            const TileDep& d = a.first[i];
+            if (d.w_stream >= 0) need[d.w_stream] = std::max(need[d.w_stream], d.w_seq);
+            if (a.mode & kWrite)
+                for (int s = 0; s < ns; s++) need[s] = std::max(need[s], d.r_seq[s]);
+        }
+    }
+    for (int s = 0; s < ns; s++)
+        if (need[s] <= ctx->synced_seq[s]) need[s] = 0;
+
+    // Stream choice: stay behind a producer whose task is the tail of its stream
+    // (no wait needed at all); otherwise take the next stream in turn, so that
+    // independent consumers of one result spread over the streams.
+    int chosen = -1;
+    if (ctx->serial || ns == 1) {
+        chosen = 0;
+    } else {
+        uint64_t best = 0;
+        for (int s = 0; s < ns; s++)
+            if (need[s] && need[s] == ctx->tail_seq[s] && need[s] >= best) { best = need[s]; chosen = s; }
+        if (chosen < 0) {
+            // prefer an idle-looking stream: one none of whose work is needed and that is not the last used
+            ctx->rr = (ctx->rr + 1) % ns;
+            chosen = ctx->rr;
+        }
+    }
+    hipStream_t st = ctx->streams[chosen];
+    for (int s = 0; s < ns; s++) {
+        if (s == chosen || !need[s]) continue;
+        if (ctx->waited[chosen][s] >= need[s]) continue;
+        hipEvent_t ev = ctx->events[s][need[s] - ctx->synced_seq[s] - 1];
+        NNT_HIP(ctx, hipStreamWaitEvent(st, ev, 0));
+        ctx->waited[chosen][s] = need[s];
+        ctx->stats.event_waits++;
+    }
+    int32_t rc = launch(st);
+    if (rc != NNT_OK) {
+        if (rc == NNT_EHIP) return fail(ctx, rc, "kernel launch failed");
+        return rc;
+    }
+    ctx->stats.tasks++;
+    ctx->stats.launches += n_launches;
+    uint64_t seq = ++ctx->tail_seq[chosen];
+    hipEvent_t ev;
+    int32_t erc = get_event(ctx, &ev);
+    if (erc != NNT_OK) return erc;
+    NNT_HIP(ctx, hipEventRecord(ev, st));
+    ctx->events[chosen].push_back(ev);
+    for (const Access& a : acc) {
+        for (int64_t i = 0; i < a.count; i++) {
+            TileDep& d = a.first[i];
+            if (a.mode & kWrite) {
+                d.w_stream = chosen;
+                d.w_seq = seq;
+                std::memset(d.r_seq, 0, sizeof(d.r_seq));
+            } else {
+                d.r_seq[chosen] = seq;
+            }
+        }
+    }
+    // bound the number of live events in long runs without nnt_wait
+    if (!ctx->capturing && ctx->events[chosen].size() > (1u << 16)) return sync_all(ctx);
+    return NNT_OK;
+}
+
+int32_t ensure_scratch(nnt_ctx* ctx, int64_t elems) {
+    if (elems <= ctx->red_scratch_elems) return NNT_OK;
+    if (ctx->capturing) return fail(ctx, NNT_ESTATE, "reduction scratch must exist before capture: run the operation once first");
+    int32_t rc = sync_all(ctx);
+    if (rc != NNT_OK) return rc;
+    if (ctx->red_scratch) NNT_HIP(ctx, hipFree(ctx->red_scratch));
+    ctx->red_scratch = nullptr;
+    ctx->red_scratch_elems = 0;
+    int64_t want = std::max<int64_t>(elems, 1 << 20);
+    NNT_HIP(ctx, hipMalloc((void**)&ctx->red_scratch, want * sizeof(float)));
+    ctx->red_scratch_elems = want;
+    return NNT_OK;
+}
+
+}  // namespace nnt
+
+using namespace nnt;
+
+struct nnt_graph {
+    nnt_ctx* ctx;
+    hipGraph_t graph;
+    hipGraphExec_t exec;
+};
+
+extern "C" {
+
+const char* nnt_version(void) { return "nntile_mi 0.1 (gfx950)"; }
+
+int32_t nnt_ctx_create(int32_t device, int32_t n_streams, void* const* caller_streams, nnt_ctx** out) {
+    if (!out || n_streams < 1 || n_streams > kMaxStreams) return NNT_EINVAL;
+    *out = nullptr;
+    if (hipSetDevice(device) != hipSuccess) return NNT_EHIP;
+    nnt_ctx* ctx = new (std::nothrow) nnt_ctx();
+    if (!ctx) return NNT_ENOMEM;
+    ctx->device = device;
+    ctx->n_streams = n_streams;
+    ctx->own_streams = caller_streams == nullptr;
+    for (int s = 0; s < kMaxStreams; s++) {
+        ctx->streams[s] = nullptr;
+        ctx->tail_seq[s] = ctx->synced_seq[s] = 0;
+        for (int d = 0; d < kMaxStreams; d++) ctx->waited[s][d] = 0;
+    }
+    for (int s = 0; s < n_streams; s++) {
+        if (caller_streams) {
+            ctx->streams[s] = (hipStream_t)caller_streams[s];
+        } else if (hipStreamCreateWithFlags(&ctx->streams[s], hipStreamNonBlocking) != hipSuccess) {
+            delete ctx;
+            return NNT_EHIP;
+        }
+    }
+    *out = ctx;
+    return NNT_OK;
+}
+
+int32_t nnt_ctx_destroy(nnt_ctx* ctx) {
+    if (!ctx) return NNT_EINVAL;
+    if (ctx->live_tensors != 0) return fail(ctx, NNT_ESTATE, "tensors still alive on this context");
+    for (int s = 0; s < ctx->n_streams; s++) (void)hipStreamSynchronize(ctx->streams[s]);
+    mark_all_synced(ctx);
+    for (hipEvent_t e : ctx->event_pool) (void)hipEventDestroy(e);
+    ctx->gemm_plans.clear();
+    if (ctx->red_scratch) (void)hipFree(ctx->red_scratch);
+    if (ctx->own_streams)
+        for (int s = 0; s < ctx->n_streams; s++) (void)hipStreamDestroy(ctx->streams[s]);
+    delete ctx;
+    return NNT_OK;
+}
+
+int32_t nnt_wait(nnt_ctx* ctx) {
+    if (!ctx) return NNT_EINVAL;
+    if (ctx->capturing) return fail(ctx, NNT_ESTATE, "nnt_wait during capture");
+    for (int s = 0; s < ctx->n_streams; s++) {
+        hipError_t e = hipStreamSynchronize(ctx->streams[s]);
+        if (e != hipSuccess) return fail(ctx, NNT_EHIP, std::string("hipStreamSynchronize: ") + hipGetErrorString(e));
+    }
+    mark_all_synced(ctx);
+    return ctx->status;
+}
+
+int32_t nnt_ctx_join(nnt_ctx* ctx) {
+    NNT_CHECK_CTX(ctx);
+    hipStream_t s0 = ctx->streams[0];
+    for (int s = 1; s < ctx->n_streams; s++) {
+        uint64_t tail = ctx->tail_seq[s];
+        if (tail <= ctx->synced_seq[s] || ctx->waited[0][s] >= tail) continue;
+        NNT_HIP(ctx, hipStreamWaitEvent(s0, ctx->events[s][tail - ctx->synced_seq[s] - 1], 0));
+        ctx->waited[0][s] = tail;
+    }
+    return NNT_OK;
+}
+
+int32_t nnt_ctx_stream(nnt_ctx* ctx, int32_t i, void** out) {
+    if (!ctx || !out || i < 0 || i >= ctx->n_streams) return NNT_EINVAL;
+    *out = (void*)ctx->streams[i];
+    return NNT_OK;
+}
+
+const char* nnt_last_error(nnt_ctx* ctx) { return ctx ? ctx->error.c_str() : "null context"; }
+
+int32_t nnt_ctx_set_serial(nnt_ctx* ctx, int32_t serial) {
+    NNT_CHECK_CTX(ctx);
+    ctx->serial = serial != 0;
+    return NNT_OK;
+}
+
+int32_t nnt_ctx_set_granularity(nnt_ctx* ctx, int32_t g) {
+    NNT_CHECK_CTX(ctx);
+    if (g != NNT_GRAN_OP && g != NNT_GRAN_TILE) return fail(ctx, NNT_EINVAL, "unknown granularity");
+    ctx->granularity = g;
+    return NNT_OK;
+}
+
+int32_t nnt_ctx_stats(nnt_ctx* ctx, nnt_exec_stats* out) {
+    if (!ctx || !out) return NNT_EINVAL;
+    *out = ctx->stats;
+    out->plans = (int64_t)ctx->gemm_plans.size();
+    return NNT_OK;
+}
+
+// ---------------------------------------------------------------- graph capture
+int32_t nnt_capture_begin(nnt_ctx* ctx) {
+    NNT_CHECK_CTX(ctx);
+    if (ctx->capturing) return fail(ctx, NNT_ESTATE, "capture already open");
+    int32_t rc = sync_all(ctx);
+    if (rc != NNT_OK) return rc;
+    NNT_HIP(ctx, hipStreamBeginCapture(ctx->streams[0], hipStreamCaptureModeRelaxed));
+    ctx->capturing = true;
+    // fork: every other stream joins the capture by waiting for a node of stream 0
+    if (ctx->n_streams > 1) {
+        hipEvent_t ev;
+        rc = get_event(ctx, &ev);
+        if (rc != NNT_OK) return rc;
+        NNT_HIP(ctx, hipEventRecord(ev, ctx->streams[0]));
+        for (int s = 1; s < ctx->n_streams; s++) NNT_HIP(ctx, hipStreamWaitEvent(ctx->streams[s], ev, 0));
+        ctx->event_pool.push_back(ev);
+    }
+    return NNT_OK;
+}
+
+int32_t nnt_capture_end(nnt_ctx* ctx, nnt_graph** out) {
+    if (!ctx || !out) return NNT_EINVAL;
+    if (!ctx->capturing) return fail(ctx, NNT_ESTATE, "no capture open");
+    *out = nullptr;
+    // join: stream 0 waits for the tails of all other streams
+    for (int s = 1; s < ctx->n_streams; s++) {
+        hipEvent_t ev;
+        int32_t rc = get_event(ctx, &ev);
+        if (rc != NNT_OK) return rc;
+        NNT_HIP(ctx, hipEventRecord(ev, ctx->streams[s]));
+        NNT_HIP(ctx, hipStreamWaitEvent(ctx->streams[0], ev, 0));
+        ctx->event_pool.push_back(ev);
+    }
+    hipGraph_t graph;
+    ctx->capturing = false;
+    NNT_HIP(ctx, hipStreamEndCapture(ctx->streams[0], &graph));
+    // the recorded tasks have not run: their events mean nothing outside the graph
+    mark_all_synced(ctx);
+    hipGraphExec_t exec;
+    NNT_HIP(ctx, hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0));
+    nnt_graph* g = new (std::nothrow) nnt_graph{ctx, graph, exec};
+    if (!g) return NNT_ENOMEM;
+    *out = g;
+    return NNT_OK;
+}
+
+int32_t nnt_graph_launch(nnt_graph* g) {
+    if (!g) return NNT_EINVAL;
+    nnt_ctx* ctx = g->ctx;
+    NNT_CHECK_CTX(ctx);
+    // everything submitted earlier on other streams must be done before the replay starts
+    int32_t rc = nnt_ctx_join(ctx);
+    if (rc != NNT_OK) return rc;
+    NNT_HIP(ctx, hipGraphLaunch(g->exec, ctx->streams[0]));
+    // later tasks on any stream must see the replay's results: they order after stream 0
+    if (ctx->n_streams > 1) {
+        hipEvent_t ev;
+        rc = get_event(ctx, &ev);
+        if (rc != NNT_OK) return rc;
+        NNT_HIP(ctx, hipEventRecord(ev, ctx->streams[0]));
+        for (int s = 1; s < ctx->n_streams; s++) NNT_HIP(ctx, hipStreamWaitEvent(ctx->streams[s], ev, 0));
+        ctx->event_pool.push_back(ev);   // safe to reuse: a re-record does not disturb waits already enqueued
+    }
+    ctx->stats.launches++;
+    return NNT_OK;
+}
+
+int32_t nnt_graph_destroy(nnt_graph* g) {
+    if (!g) return NNT_EINVAL;
+    (void)hipGraphExecDestroy(g->exec);
+    (void)hipGraphDestroy(g->graph);
+    delete g;
+    return NNT_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,309 @@
+// Tile-grid products: the single-tile entry point and the tensor-level nnt_gemm,
+// which turns a contraction of tiled tensors into a cached plan (tables of tasks,
+// chunks and workgroups in device memory) and submits it to the executor.
+#include "gemm_common.hpp"
+#include "internal.hpp"
+
+#include <algorithm>
+#include <sstream>
+
+namespace nnt {
+
+struct GemmPlan {
+    nnt_ctx* ctx = nullptr;
+    uint64_t ids[4] = {0, 0, 0, 0};            // tensors the tables point into (A, B, C, bias)
+    int dtype_in = NNT_F32, dtype_out = NNT_F32;
+    int akf = 0, bkf = 0, cfg = kCfgSquare;
+    std::vector<GemmTask> tasks;
+    std::vector<GemmChunk> chunks;
+    std::vector<GemmWg> wgs;
+    std::vector<int64_t> task_wg0;             // first workgroup of each task (+ total at the end)
+    std::vector<int64_t> task_ctile;           // C tile index per task
+    std::vector<std::vector<int64_t>> task_atiles, task_btiles;   // operand tiles per task (dependencies)
+    std::vector<int64_t> task_bias_tile;
+    GemmTask* d_tasks = nullptr;
+    GemmChunk* d_chunks = nullptr;
+    GemmWg* d_wgs = nullptr;
+    ~GemmPlan() {
+        if (d_tasks) (void)hipFree(d_tasks);
+        if (d_chunks) (void)hipFree(d_chunks);
+        if (d_wgs) (void)hipFree(d_wgs);
+    }
+};
+
+void drop_plans_of(nnt_ctx* ctx, uint64_t id) {
+    for (auto it = ctx->gemm_plans.begin(); it != ctx->gemm_plans.end();) {
+        const uint64_t* ids = it->second->ids;
+        if (ids[0] == id || ids[1] == id || ids[2] == id || ids[3] == id) it = ctx->gemm_plans.erase(it);
+        else ++it;
+    }
+}
+
+static int32_t launch_any(hipStream_t st, int dtype_in, int dtype_out, int akf, int bkf, int cfg,
+                          const GemmArgs& g, int64_t nwg) {
+    if (dtype_in == NNT_F32) return launch_gemm_f32(st, akf, bkf, cfg, g, nwg);
+    return launch_gemm_bf16(st, dtype_out == NNT_F32, akf, bkf, cfg, g, nwg);
+}
+
+static int vec_flag(const void* p, int64_t ld, int64_t stride, int elem) {
+    const int per = 16 / elem;
+    return ((uintptr_t)p % 16 == 0) && (ld % per == 0) && (stride % per == 0);
+}
+
+static int pick_cfg(int bf16, int64_t m_max, int64_t n_max, int64_t n_tiles_big) {
+    if (m_max <= 64) return kCfgSkinny64;
+    if (m_max <= 128 && n_max > 128) return kCfgSkinny128;
+    if (bf16 && (m_max <= 128 || n_max <= 128 || n_tiles_big < 256)) return kCfgMid;
+    return kCfgSquare;
+}
+
+}  // namespace nnt
+
+using namespace nnt;
+
+extern "C" int32_t nnt_tile_gemm(void* stream, int32_t dtype_in, int32_t dtype_out, int32_t opA, int32_t opB,
+                                 int64_t m, int64_t n, int64_t k, int64_t batch, float alpha,
+                                 const void* A, int64_t lda, int64_t strideA,
+                                 const void* B, int64_t ldb, int64_t strideB,
+                                 float beta, void* C, int64_t ldc, int64_t strideC) {
+    if (dtype_in != NNT_F32 && dtype_in != NNT_BF16) return NNT_EDTYPE;
+    if (dtype_out != NNT_F32 && dtype_out != NNT_BF16) return NNT_EDTYPE;
+    if (dtype_in == NNT_F32 && dtype_out != NNT_F32) return NNT_EDTYPE;
+    if ((opA != NNT_OP_N && opA != NNT_OP_T) || (opB != NNT_OP_N && opB != NNT_OP_T)) return NNT_EINVAL;
+    if (m < 0 || n < 0 || k < 0 || batch < 0 || m > INT32_MAX || n > INT32_MAX || k > INT32_MAX) return NNT_EINVAL;
+    if (m == 0 || n == 0 || batch == 0) return NNT_OK;
+    if (!C || (k > 0 && (!A || !B))) return NNT_EINVAL;
+    const int64_t a_rows = opA == NNT_OP_N ? m : k, b_rows = opB == NNT_OP_N ? k : n;
+    if (ldc < m || (k > 0 && (lda < a_rows || ldb < b_rows))) return NNT_EINVAL;
+    const int bf = dtype_in == NNT_BF16;
+    const int elem = bf ? 2 : 4;
+    GemmArgs g = {};
+    g.wgs = nullptr;
+    g.one_task.C = C;
+    g.one_task.bias = nullptr;
+    g.one_task.ldc = ldc;
+    g.one_task.strideC = strideC;
+    g.one_task.m = (int32_t)m;
+    g.one_task.n = (int32_t)n;
+    g.one_task.chunk0 = 0;
+    g.one_task.nchunk = k > 0 ? 1 : 0;
+    g.one_chunk.A = A;
+    g.one_chunk.B = B;
+    g.one_chunk.lda = lda;
+    g.one_chunk.ldb = ldb;
+    g.one_chunk.strideA = strideA;
+    g.one_chunk.strideB = strideB;
+    g.one_chunk.k = (int32_t)k;
+    g.one_chunk.vec_ok = vec_flag(A, lda, strideA, elem) | (vec_flag(B, ldb, strideB, elem) << 1);
+    g.alpha = alpha;
+    g.beta = beta;
+    int bm, bn;
+    const int cfg = pick_cfg(bf, m, n, ((m + 255) / 256) * ((n + 255) / 256) * batch);
+    gemm_cfg_tile(bf, cfg, &bm, &bn);
+    g.grid_m = (int32_t)((m + bm - 1) / bm);
+    g.grid_n = (int32_t)((n + bn - 1) / bn);
+    const int64_t nwg = (int64_t)g.grid_m * g.grid_n * batch;
+    if (nwg > INT32_MAX) return NNT_EINVAL;
+    return launch_any((hipStream_t)stream, dtype_in, dtype_out, opA == NNT_OP_T, opB == NNT_OP_N, cfg, g, nwg);
+}
+
+// ---------------------------------------------------------------- tensor-level product
+namespace {
+
+struct AxisMap {
+    std::vector<int> a_free, a_con, b_con, b_free, a_bat, b_bat;
+};
+
+int64_t prod_extent(const nnt_tensor* t, const int64_t* tc, const std::vector<int>& axes) {
+    int64_t p = 1;
+    for (int a : axes) p *= t->tile_extent(a, tc[a]);
+    return p;
+}
+
+int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B, nnt_tensor* C, int ncon, int nbat,
+                   nnt_tensor* bias, GemmPlan* P) {
+    const int na = A->ndim - nbat, nb = B->ndim - nbat;
+    if (ncon < 1 || nbat < 0 || na < ncon || nb < ncon)
+        return fail(ctx, NNT_EINVAL, "nnt_gemm: axis counts do not fit the operands");
+    AxisMap ax;
+    if (opA == NNT_OP_N) { for (int i = 0; i < na - ncon; i++) ax.a_free.push_back(i); for (int i = na - ncon; i < na; i++) ax.a_con.push_back(i); }
+    else { for (int i = 0; i < ncon; i++) ax.a_con.push_back(i); for (int i = ncon; i < na; i++) ax.a_free.push_back(i); }
+    if (opB == NNT_OP_N) { for (int i = 0; i < ncon; i++) ax.b_con.push_back(i); for (int i = ncon; i < nb; i++) ax.b_free.push_back(i); }
+    else { for (int i = 0; i < nb - ncon; i++) ax.b_free.push_back(i); for (int i = nb - ncon; i < nb; i++) ax.b_con.push_back(i); }
+    for (int i = 0; i < nbat; i++) { ax.a_bat.push_back(na + i); ax.b_bat.push_back(nb + i); }
+    const int nfa = (int)ax.a_free.size(), nfb = (int)ax.b_free.size();
+    if (C->ndim != nfa + nfb + nbat) return fail(ctx, NNT_EINVAL, "nnt_gemm: C has the wrong number of axes");
+    for (int i = 0; i < ncon; i++)
+        if (A->shape[ax.a_con[i]] != B->shape[ax.b_con[i]] || A->base[ax.a_con[i]] != B->base[ax.b_con[i]])
+            return fail(ctx, NNT_EINVAL, "nnt_gemm: contracted axes differ in extent or tiling");
+    for (int i = 0; i < nfa; i++)
+        if (A->shape[ax.a_free[i]] != C->shape[i] || A->base[ax.a_free[i]] != C->base[i])
+            return fail(ctx, NNT_EINVAL, "nnt_gemm: free axes of A and C differ in extent or tiling");
+    for (int i = 0; i < nfb; i++)
+        if (B->shape[ax.b_free[i]] != C->shape[nfa + i] || B->base[ax.b_free[i]] != C->base[nfa + i])
+            return fail(ctx, NNT_EINVAL, "nnt_gemm: free axes of B and C differ in extent or tiling");
+    for (int i = 0; i < nbat; i++) {
+        const int ca = nfa + nfb + i;
+        if (A->shape[ax.a_bat[i]] != C->shape[ca] || A->base[ax.a_bat[i]] != C->base[ca] ||
+            B->shape[ax.b_bat[i]] != C->shape[ca] || B->base[ax.b_bat[i]] != C->base[ca])
+            return fail(ctx, NNT_EINVAL, "nnt_gemm: batch axes differ in extent or tiling");
+    }
+    if (A->dtype != B->dtype) return fail(ctx, NNT_EDTYPE, "nnt_gemm: A and B must have one element type");
+    if (A->dtype == NNT_F32 && C->dtype != NNT_F32) return fail(ctx, NNT_EDTYPE, "nnt_gemm: fp32 operands need an fp32 result");
+    if (bias) {
+        if (bias->dtype != NNT_F32 || bias->ndim != 1 || nfa != 1 || bias->shape[0] != C->shape[0] || bias->base[0] != C->base[0])
+            return fail(ctx, NNT_EINVAL, "nnt_gemm: bias must be an fp32 vector tiled like C's first axis");
+    }
+
+    P->ctx = ctx;
+    P->ids[0] = A->id; P->ids[1] = B->id; P->ids[2] = C->id; P->ids[3] = bias ? bias->id : 0;
+    P->dtype_in = A->dtype;
+    P->dtype_out = C->dtype;
+    P->akf = opA == NNT_OP_T;
+    P->bkf = opB == NNT_OP_N;
+    const int elem = A->dtype == NNT_BF16 ? 2 : 4;
+
+    // contracted tile grid
+    int64_t ncon_tiles = 1;
+    for (int i = 0; i < ncon; i++) ncon_tiles *= A->grid[ax.a_con[i]];
+    int64_t m_max = 0, n_max = 0, big = 0;
+
+    struct TaskGeom { int64_t m, n, batch; };
+    std::vector<TaskGeom> geom;
+    for (int64_t ci = 0; ci < C->ntiles; ci++) {
+        if (!C->tiles[ci]) continue;
+        int64_t cc[kMaxDim], ac[kMaxDim] = {0, 0, 0, 0}, bc[kMaxDim] = {0, 0, 0, 0};
+        C->tile_coords(ci, cc);
+        for (int i = 0; i < nfa; i++) ac[ax.a_free[i]] = cc[i];
+        for (int i = 0; i < nfb; i++) bc[ax.b_free[i]] = cc[nfa + i];
+        for (int i = 0; i < nbat; i++) { ac[ax.a_bat[i]] = cc[nfa + nfb + i]; bc[ax.b_bat[i]] = cc[nfa + nfb + i]; }
+        const int64_t m = prod_extent(A, ac, ax.a_free), n = prod_extent(B, bc, ax.b_free);
+        const int64_t batch = prod_extent(A, ac, ax.a_bat);
+        if (m > INT32_MAX || n > INT32_MAX) return fail(ctx, NNT_EINVAL, "nnt_gemm: tile too large");
+        GemmTask t;
+        t.C = C->tiles[ci];
+        t.bias = bias ? static_cast<const float*>(bias->tiles[cc[0]]) : nullptr;
+        if (bias && !t.bias) return fail(ctx, NNT_EINVAL, "nnt_gemm: bias tile missing");
+        t.ldc = m;
+        t.strideC = m * n;
+        t.m = (int32_t)m;
+        t.n = (int32_t)n;
+        t.chunk0 = (int32_t)P->chunks.size();
+        std::vector<int64_t> atl, btl;
+        for (int64_t l = 0; l < ncon_tiles; l++) {
+            int64_t rem = l;
+            for (int i = 0; i < ncon; i++) {
+                const int64_t gi = A->grid[ax.a_con[i]];
+                ac[ax.a_con[i]] = rem % gi;
+                bc[ax.b_con[i]] = rem % gi;
+                rem /= gi;
+            }
+            const int64_t ai = A->tile_index(ac), bi = B->tile_index(bc);
+            if (!A->tiles[ai] || !B->tiles[bi]) continue;      // structural zeros: no contribution
+            const int64_t k = prod_extent(A, ac, ax.a_con);
+            GemmChunk ch;
+            ch.A = A->tiles[ai];
+            ch.B = B->tiles[bi];
+            ch.lda = P->akf ? k : m;
+            ch.ldb = P->bkf ? k : n;
+            ch.strideA = m * k;
+            ch.strideB = k * n;
+            ch.k = (int32_t)k;
+            ch.vec_ok = vec_flag(ch.A, ch.lda, ch.strideA, elem) | (vec_flag(ch.B, ch.ldb, ch.strideB, elem) << 1);
+            P->chunks.push_back(ch);
+            atl.push_back(ai);
+            btl.push_back(bi);
+        }
+        t.nchunk = (int32_t)P->chunks.size() - t.chunk0;
+        P->tasks.push_back(t);
+        P->task_ctile.push_back(ci);
+        P->task_atiles.push_back(atl);
+        P->task_btiles.push_back(btl);
+        P->task_bias_tile.push_back(bias ? cc[0] : -1);
+        geom.push_back({m, n, batch});
+        m_max = std::max(m_max, m);
+        n_max = std::max(n_max, n);
+        big += ((m + 255) / 256) * ((n + 255) / 256) * batch;
+    }
+    P->cfg = pick_cfg(A->dtype == NNT_BF16, m_max, n_max, big);
+    int bm, bn;
+    gemm_cfg_tile(A->dtype == NNT_BF16, P->cfg, &bm, &bn);
+    // Workgroup order inside a task: m index fastest, so that workgroups in flight
+    // together share a column panel of B.
+    for (size_t ti = 0; ti < P->tasks.size(); ti++) {
+        P->task_wg0.push_back((int64_t)P->wgs.size());
+        const int64_t gm = (geom[ti].m + bm - 1) / bm, gn = (geom[ti].n + bn - 1) / bn;
+        for (int64_t b = 0; b < geom[ti].batch; b++)
+            for (int64_t j = 0; j < gn; j++)
+                for (int64_t i = 0; i < gm; i++)
+                    P->wgs.push_back(GemmWg{(int32_t)ti, (int32_t)(i * bm), (int32_t)(j * bn), (int32_t)b});
+    }
+    P->task_wg0.push_back((int64_t)P->wgs.size());
+    if (P->wgs.size() > (size_t)INT32_MAX) return fail(ctx, NNT_EINVAL, "nnt_gemm: too many workgroups");
+
+    auto up = [&](void** d, const void* h, size_t bytes) -> hipError_t {
+        if (bytes == 0) return hipSuccess;
+        hipError_t e = hipMalloc(d, bytes);
+        if (e != hipSuccess) return e;
+        return hipMemcpy(*d, h, bytes, hipMemcpyHostToDevice);
+    };
+    NNT_HIP(ctx, up((void**)&P->d_tasks, P->tasks.data(), P->tasks.size() * sizeof(GemmTask)));
+    NNT_HIP(ctx, up((void**)&P->d_chunks, P->chunks.data(), P->chunks.size() * sizeof(GemmChunk)));
+    NNT_HIP(ctx, up((void**)&P->d_wgs, P->wgs.data(), P->wgs.size() * sizeof(GemmWg)));
+    return NNT_OK;
+}
+
+}  // namespace
+
+extern "C" int32_t nnt_gemm(nnt_ctx* ctx, float alpha, int32_t opA, nnt_tensor* A, int32_t opB, nnt_tensor* B,
+                            float beta, nnt_tensor* C, int32_t ncon, int32_t nbat, nnt_tensor* bias) {
+    NNT_CHECK_CTX(ctx);
+    if (!A || !B || !C) return fail(ctx, NNT_EINVAL, "nnt_gemm: null tensor");
+    if ((opA != NNT_OP_N && opA != NNT_OP_T) || (opB != NNT_OP_N && opB != NNT_OP_T))
+        return fail(ctx, NNT_EINVAL, "nnt_gemm: bad op");
+    std::ostringstream key;
+    key << opA << opB << ':' << A->id << ':' << B->id << ':' << C->id << ':' << (bias ? bias->id : 0) << ':' << ncon << ':' << nbat;
+    GemmPlan* P;
+    auto it = ctx->gemm_plans.find(key.str());
+    if (it == ctx->gemm_plans.end()) {
+        if (ctx->capturing) return fail(ctx, NNT_ESTATE, "nnt_gemm: plan must exist before capture (run the call once first)");
+        std::shared_ptr<GemmPlan> np(new GemmPlan());
+        int32_t rc = build_plan(ctx, opA, A, opB, B, C, ncon, nbat, bias, np.get());
+        if (rc != NNT_OK) return rc;
+        P = np.get();
+        ctx->gemm_plans[key.str()] = np;
+    } else {
+        P = it->second.get();
+    }
+    GemmArgs g = {};
+    g.tasks = P->d_tasks;
+    g.chunks = P->d_chunks;
+    g.alpha = alpha;
+    g.beta = beta;
+    const int cmode = beta != 0.f ? kReadWrite : kWrite;
+    if (ctx->granularity == NNT_GRAN_OP) {
+        std::vector<Access> acc = {A->all(kRead), B->all(kRead), C->all(cmode)};
+        if (bias) acc.push_back(bias->all(kRead));
+        g.wgs = P->d_wgs;
+        const int64_t nwg = (int64_t)P->wgs.size();
+        if (nwg == 0) return NNT_OK;
+        return submit(ctx, acc, [=](hipStream_t st) {
+            return launch_any(st, P->dtype_in, P->dtype_out, P->akf, P->bkf, P->cfg, g, nwg);
+        });
+    }
+    for (size_t ti = 0; ti < P->tasks.size(); ti++) {
+        std::vector<Access> acc;
+        acc.push_back(C->one(P->task_ctile[ti], cmode));
+        for (int64_t a : P->task_atiles[ti]) acc.push_back(A->one(a, kRead));
+        for (int64_t b : P->task_btiles[ti]) acc.push_back(B->one(b, kRead));
+        if (bias) acc.push_back(bias->one(P->task_bias_tile[ti], kRead));
+        GemmArgs gt = g;
+        gt.wgs = P->d_wgs + P->task_wg0[ti];
+        const int64_t nwg = P->task_wg0[ti + 1] - P->task_wg0[ti];
+        int32_t rc = submit(ctx, acc, [=](hipStream_t st) {
+            return launch_any(st, P->dtype_in, P->dtype_out, P->akf, P->bkf, P->cfg, gt, nwg);
+        });
+        if (rc != NNT_OK) return rc;
+    }
+    return NNT_OK;
+}

@@ -1,0 +1,294 @@
+// bf16-input tile-grid product on the gfx950 matrix cores
+// (v_mfma_f32_32x32x16_bf16): bf16 operands, fp32 accumulation over all chunks
+// of a task, one rounding when C is written (fp32 or bf16).
+//
+// Same structure as the fp32 kernel: four wavefronts per workgroup, a BM x BN
+// macro-tile, k-steps of BKT elements, two LDS buffers, one barrier per step.
+// The matrix cores want 8 consecutive k per lane, so both operands live in LDS as
+// [row][BKT + 8 pad] (k fastest).  An operand that is k-fast in memory is copied
+// with 128-bit loads and stores; one whose row index is contiguous is read as
+// 8-row vectors at 4 consecutive k and transposed in registers (16-bit packs)
+// before the LDS store.
+#include "gemm_common.hpp"
+#include "nntile_mi.h"
+
+namespace nnt {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+namespace {
+
+__device__ __forceinline__ uint16_t ld_bf16(const uint16_t* p) { return *p; }
+
+// ---- k-fast operand: vectors of 8 along k
+template <int ROWS, int BKT>
+struct LoaderK {
+    static constexpr int NV = ROWS * BKT / 8 / 256 > 0 ? ROWS * BKT / 8 / 256 : 1;
+    static constexpr int TOTAL = ROWS * BKT / 8;
+    static constexpr int KP = BKT + 8;
+    uint4 v[NV];
+    __device__ __forceinline__ void load(const uint16_t* base, int64_t ld, int row0, int nrows, int k0, int kc,
+                                         bool vec_ok, int tid) {
+#pragma unroll
+        for (int i = 0; i < NV; i++) {
+            const int idx = tid + 256 * i;
+            uint4 x = {0u, 0u, 0u, 0u};
+            if (TOTAL >= 256 || idx < TOTAL) {
+                const int r = idx / (BKT / 8), k = (idx % (BKT / 8)) * 8;
+                const int gr = row0 + r, gk = k0 + k;
+                const uint16_t* p = base + gk + (int64_t)gr * ld;
+                const int cnt = gr < nrows ? kc - gk : 0;
+                if (cnt >= 8 && vec_ok) {
+                    x = *reinterpret_cast<const uint4*>(p);
+                } else if (cnt > 0) {
+                    uint16_t e[8];
+#pragma unroll
+                    for (int j = 0; j < 8; j++) e[j] = j < cnt ? p[j] : (uint16_t)0;
+                    x.x = e[0] | ((uint32_t)e[1] << 16);
+                    x.y = e[2] | ((uint32_t)e[3] << 16);
+                    x.z = e[4] | ((uint32_t)e[5] << 16);
+                    x.w = e[6] | ((uint32_t)e[7] << 16);
+                }
+            }
+            v[i] = x;
+        }
+    }
+    __device__ __forceinline__ void store(uint16_t* l, int tid) const {
+#pragma unroll
+        for (int i = 0; i < NV; i++) {
+            const int idx = tid + 256 * i;
+            if (TOTAL >= 256 || idx < TOTAL) {
+                const int r = idx / (BKT / 8), k = (idx % (BKT / 8)) * 8;
+                *reinterpret_cast<uint4*>(&l[r * KP + k]) = v[i];
+            }
+        }
+    }
+};
+
+// ---- row-fast operand: micro-blocks of 8 rows x 4 k, transposed in registers
+template <int ROWS, int BKT>
+struct LoaderR {
+    static constexpr int TOTAL = (ROWS / 8) * (BKT / 4);
+    static constexpr int NB = TOTAL / 256 > 0 ? TOTAL / 256 : 1;
+    static constexpr int KP = BKT + 8;
+    uint4 v[NB][4];
+    __device__ __forceinline__ void load(const uint16_t* base, int64_t ld, int row0, int nrows, int k0, int kc,
+                                         bool vec_ok, int tid) {
+#pragma unroll
+        for (int i = 0; i < NB; i++) {
+            const int idx = tid + 256 * i;
+            const int kq = idx % (BKT / 4), rg = idx / (BKT / 4);
+            const int gr = row0 + rg * 8;
+            const int cnt = (TOTAL >= 256 || idx < TOTAL) ? nrows - gr : 0;
+#pragma unroll
+            for (int kk = 0; kk < 4; kk++) {
+                const int gk = k0 + kq * 4 + kk;
+                uint4 x = {0u, 0u, 0u, 0u};
+                if (gk < kc && cnt > 0) {
+                    const uint16_t* p = base + gr + (int64_t)gk * ld;
+                    if (cnt >= 8 && vec_ok) {
+                        x = *reinterpret_cast<const uint4*>(p);
+                    } else {
+                        uint16_t e[8];
+#pragma unroll
+                        for (int j = 0; j < 8; j++) e[j] = j < cnt ? p[j] : (uint16_t)0;
+                        x.x = e[0] | ((uint32_t)e[1] << 16);
+                        x.y = e[2] | ((uint32_t)e[3] << 16);
+                        x.z = e[4] | ((uint32_t)e[5] << 16);
+                        x.w = e[6] | ((uint32_t)e[7] << 16);
+                    }
+                }
+                v[i][kk] = x;
+            }
+        }
+    }
+    __device__ __forceinline__ void store(uint16_t* l, int tid) const {
+#pragma unroll
+        for (int i = 0; i < NB; i++) {
+            const int idx = tid + 256 * i;
+            if (TOTAL >= 256 || idx < TOTAL) {
+                const int kq = idx % (BKT / 4), rg = idx / (BKT / 4);
+                const uint32_t* w0 = reinterpret_cast<const uint32_t*>(&v[i][0]);
+                const uint32_t* w1 = reinterpret_cast<const uint32_t*>(&v[i][1]);
+                const uint32_t* w2 = reinterpret_cast<const uint32_t*>(&v[i][2]);
+                const uint32_t* w3 = reinterpret_cast<const uint32_t*>(&v[i][3]);
+#pragma unroll
+                for (int d = 0; d < 4; d++) {
+                    // dword d of each vector holds rows 2d (low half) and 2d + 1 (high half)
+                    uint2 lo, hi;
+                    lo.x = (w0[d] & 0xffffu) | (w1[d] << 16);
+                    lo.y = (w2[d] & 0xffffu) | (w3[d] << 16);
+                    hi.x = (w0[d] >> 16) | (w1[d] & 0xffff0000u);
+                    hi.y = (w2[d] >> 16) | (w3[d] & 0xffff0000u);
+                    *reinterpret_cast<uint2*>(&l[(rg * 8 + 2 * d) * KP + kq * 4]) = lo;
+                    *reinterpret_cast<uint2*>(&l[(rg * 8 + 2 * d + 1) * KP + kq * 4]) = hi;
+                }
+            }
+        }
+    }
+};
+
+template <bool KF, int ROWS, int BKT>
+struct LoaderSel { typedef LoaderR<ROWS, BKT> type; };
+template <int ROWS, int BKT>
+struct LoaderSel<true, ROWS, BKT> { typedef LoaderK<ROWS, BKT> type; };
+
+__device__ __forceinline__ void store_out(float* p, float v) { *p = v; }
+__device__ __forceinline__ void store_out(uint16_t* p, float v) {
+    const __bf16 h = (__bf16)v;
+    *p = __builtin_bit_cast(uint16_t, h);
+}
+__device__ __forceinline__ float load_out(const float* p) { return *p; }
+__device__ __forceinline__ float load_out(const uint16_t* p) { return __uint_as_float((uint32_t)*p << 16); }
+
+template <typename TO, bool AKF, bool BKF, int WAVES_M, int WAVES_N, int WMB, int WNB, int BKT>
+__global__ void __launch_bounds__(256) gemm_bf16_kernel(const GemmArgs g) {
+    constexpr int BM = 32 * WMB * WAVES_M, BN = 32 * WNB * WAVES_N;
+    constexpr int KP = BKT + 8;
+    constexpr int A_SZ = BM * KP, B_SZ = BN * KP;
+    __shared__ __attribute__((aligned(16))) uint16_t lds[2 * (A_SZ + B_SZ)];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave % WAVES_M, wn = wave / WAVES_M;
+    const int r32 = lane & 31, half = lane >> 5;
+
+    GemmTask task;
+    int m0, n0, bat;
+    const GemmChunk* chunks;
+    if (g.wgs) {
+        const GemmWg w = g.wgs[blockIdx.x];
+        task = g.tasks[w.task];
+        m0 = w.m0; n0 = w.n0; bat = w.batch;
+        chunks = g.chunks + task.chunk0;
+    } else {
+        task = g.one_task;
+        const int b = blockIdx.x;
+        m0 = (b % g.grid_m) * BM;
+        n0 = ((b / g.grid_m) % g.grid_n) * BN;
+        bat = b / (g.grid_m * g.grid_n);
+        chunks = &g.one_chunk;
+    }
+
+    f32x16 acc[WNB][WMB];
+#pragma unroll
+    for (int bn = 0; bn < WNB; bn++)
+#pragma unroll
+        for (int bm = 0; bm < WMB; bm++)
+#pragma unroll
+            for (int i = 0; i < 16; i++) acc[bn][bm][i] = 0.f;
+
+    if (task.nchunk > 0) {
+        int c = 0, k0 = 0;
+        GemmChunk ch = chunks[0];
+        const uint16_t* Ab = static_cast<const uint16_t*>(ch.A) + (int64_t)bat * ch.strideA;
+        const uint16_t* Bb = static_cast<const uint16_t*>(ch.B) + (int64_t)bat * ch.strideB;
+        typename LoaderSel<AKF, BM, BKT>::type la;
+        typename LoaderSel<BKF, BN, BKT>::type lb;
+        la.load(Ab, ch.lda, m0, task.m, k0, ch.k, ch.vec_ok & 1, tid);
+        lb.load(Bb, ch.ldb, n0, task.n, k0, ch.k, ch.vec_ok & 2, tid);
+        int cur = 0;
+        la.store(lds, tid);
+        lb.store(lds + A_SZ, tid);
+        __syncthreads();
+        bool more = true;
+        while (more) {
+            k0 += BKT;
+            if (k0 >= ch.k) {
+                c++;
+                k0 = 0;
+                if (c < task.nchunk) {
+                    ch = chunks[c];
+                    Ab = static_cast<const uint16_t*>(ch.A) + (int64_t)bat * ch.strideA;
+                    Bb = static_cast<const uint16_t*>(ch.B) + (int64_t)bat * ch.strideB;
+                }
+            }
+            more = c < task.nchunk;
+            if (more) {
+                la.load(Ab, ch.lda, m0, task.m, k0, ch.k, ch.vec_ok & 1, tid);
+                lb.load(Bb, ch.ldb, n0, task.n, k0, ch.k, ch.vec_ok & 2, tid);
+            }
+            const uint16_t* lA = lds + cur * (A_SZ + B_SZ);
+            const uint16_t* lB = lA + A_SZ;
+#pragma unroll
+            for (int ks = 0; ks < BKT / 16; ks++) {
+                bf16x8 pf[WNB], qf[WMB];
+#pragma unroll
+                for (int bn = 0; bn < WNB; bn++)
+                    pf[bn] = *reinterpret_cast<const bf16x8*>(&lB[((wn * WNB + bn) * 32 + r32) * KP + ks * 16 + half * 8]);
+#pragma unroll
+                for (int bm = 0; bm < WMB; bm++)
+                    qf[bm] = *reinterpret_cast<const bf16x8*>(&lA[((wm * WMB + bm) * 32 + r32) * KP + ks * 16 + half * 8]);
+#pragma unroll
+                for (int bn = 0; bn < WNB; bn++)
+#pragma unroll
+                    for (int bm = 0; bm < WMB; bm++)
+                        acc[bn][bm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf[bn], qf[bm], acc[bn][bm], 0, 0, 0);
+            }
+            if (more) {
+                uint16_t* nA = lds + (cur ^ 1) * (A_SZ + B_SZ);
+                la.store(nA, tid);
+                lb.store(nA + A_SZ, tid);
+            }
+            __syncthreads();
+            cur ^= 1;
+        }
+    }
+
+    TO* C = static_cast<TO*>(task.C) + (int64_t)bat * task.strideC;
+    const float alpha = g.alpha, beta = g.beta;
+#pragma unroll
+    for (int bm = 0; bm < WMB; bm++) {
+        const int gm = m0 + (wm * WMB + bm) * 32 + r32;
+        if (gm >= task.m) continue;
+        const float bias = task.bias ? task.bias[gm] : 0.f;
+#pragma unroll
+        for (int bn = 0; bn < WNB; bn++) {
+#pragma unroll
+            for (int i = 0; i < 16; i++) {
+                const int gn = n0 + (wn * WNB + bn) * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
+                if (gn < task.n) {
+                    TO* p = C + gm + (int64_t)gn * task.ldc;
+                    float v = alpha * acc[bn][bm][i] + bias;
+                    if (beta != 0.f) v += beta * load_out(p);
+                    store_out(p, v);
+                }
+            }
+        }
+    }
+}
+
+template <typename TO, bool AKF, bool BKF>
+int32_t launch_cfg(hipStream_t st, int cfg, const GemmArgs& g, int64_t nwg) {
+    dim3 grid((unsigned)nwg), block(256);
+    switch (cfg) {
+        case kCfgSquare:
+            hipLaunchKernelGGL((gemm_bf16_kernel<TO, AKF, BKF, 2, 2, 4, 4, 32>), grid, block, 0, st, g);
+            break;
+        case kCfgMid:
+            hipLaunchKernelGGL((gemm_bf16_kernel<TO, AKF, BKF, 2, 2, 2, 2, 32>), grid, block, 0, st, g);
+            break;
+        case kCfgSkinny64:
+            hipLaunchKernelGGL((gemm_bf16_kernel<TO, AKF, BKF, 1, 4, 2, 2, 32>), grid, block, 0, st, g);
+            break;
+        default:
+            hipLaunchKernelGGL((gemm_bf16_kernel<TO, AKF, BKF, 1, 4, 4, 2, 32>), grid, block, 0, st, g);
+            break;
+    }
+    return hipGetLastError() == hipSuccess ? NNT_OK : NNT_EHIP;
+}
+
+template <typename TO>
+int32_t launch_ops(hipStream_t st, int akf, int bkf, int cfg, const GemmArgs& g, int64_t nwg) {
+    if (akf) return bkf ? launch_cfg<TO, true, true>(st, cfg, g, nwg) : launch_cfg<TO, true, false>(st, cfg, g, nwg);
+    return bkf ? launch_cfg<TO, false, true>(st, cfg, g, nwg) : launch_cfg<TO, false, false>(st, cfg, g, nwg);
+}
+
+}  // namespace
+
+int32_t launch_gemm_bf16(hipStream_t st, int out_is_f32, int akf, int bkf, int cfg, const GemmArgs& g, int64_t nwg) {
+    if (nwg <= 0) return NNT_OK;
+    return out_is_f32 ? launch_ops<float>(st, akf, bkf, cfg, g, nwg) : launch_ops<uint16_t>(st, akf, bkf, cfg, g, nwg);
+}
+
+}  // namespace nnt

@@ -1,0 +1,65 @@
+// Descriptor tables of the tile-grid product kernels.
+//
+// A "task" is one tile of C (section 2: a task touches a few tiles); its "chunks"
+// are the (A tile, B tile) pairs along the contracted axes whose products are
+// summed into it (section 3, linear layer: products and sums of elementary
+// tiles).  One workgroup owns one macro-tile of one C tile for one batch member
+// and walks the task's chunks, so the whole sum over the contracted tiles stays
+// in the fp32 accumulators and is rounded once.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace nnt {
+
+struct GemmTask {
+    void* C;
+    const float* bias;      // length m, or nullptr
+    int64_t ldc, strideC;   // elements
+    int32_t m, n;
+    int32_t chunk0, nchunk;
+};
+
+struct GemmChunk {
+    const void* A;
+    const void* B;
+    int64_t lda, ldb, strideA, strideB;   // elements
+    int32_t k;
+    int32_t vec_ok;         // bit 0: A may be read with 16-byte vectors, bit 1: B
+};
+
+struct GemmWg {
+    int32_t task, m0, n0, batch;
+};
+
+struct GemmArgs {
+    const GemmTask* tasks;
+    const GemmChunk* chunks;
+    const GemmWg* wgs;      // nullptr: single product described by one_task / one_chunk
+    GemmTask one_task;
+    GemmChunk one_chunk;
+    int32_t grid_m, grid_n; // macro-tile grid of the single product
+    float alpha, beta;
+};
+
+// Macro-tile configurations.  M counts rows of C (first, fastest axis), N columns.
+enum GemmCfg {
+    kCfgSquare = 0,   // f32 128 x 128, bf16 256 x 256
+    kCfgMid = 1,      // f32 128 x 128, bf16 128 x 128
+    kCfgSkinny64 = 2, // 64 x 256   (attention products with m = head size 64)
+    kCfgSkinny128 = 3 // 128 x 256  (head size 128)
+};
+
+inline void gemm_cfg_tile(int dtype_is_bf16, int cfg, int* bm, int* bn) {
+    switch (cfg) {
+        case kCfgSquare: *bm = *bn = dtype_is_bf16 ? 256 : 128; break;
+        case kCfgMid: *bm = *bn = 128; break;
+        case kCfgSkinny64: *bm = 64; *bn = 256; break;
+        default: *bm = 128; *bn = 256; break;
+    }
+}
+
+int32_t launch_gemm_f32(hipStream_t st, int akf, int bkf, int cfg, const GemmArgs& g, int64_t nwg);
+int32_t launch_gemm_bf16(hipStream_t st, int out_is_f32, int akf, int bkf, int cfg, const GemmArgs& g, int64_t nwg);
+
+}  // namespace nnt

@@ -1,0 +1,224 @@
+// fp32 tile-grid product on the gfx950 matrix cores (v_mfma_f32_32x32x2_f32):
+// true fp32 inputs, fp32 accumulation.
+//
+// One workgroup of four wavefronts owns a BM x BN macro-tile of one C tile and
+// walks the task's chunks in k-steps of 16.  Both operands are staged through
+// LDS in the orientation they have in memory (no transposes): an operand whose
+// contracted index is contiguous ("k-fast") is kept as [row][16 + 4 pad], one
+// whose row index is contiguous as [k][rows]; the matrix-core fragments are read
+// with 128-bit or 32-bit LDS loads accordingly.  Global loads for step i+1 are
+// issued before the MFMAs of step i and written to the other LDS buffer after
+// them, so each step costs one barrier.
+//
+// The matrix-core "A" operand carries the columns of C (index n) and the "B"
+// operand the rows (index m): a lane then holds 16 values of one row index m =
+// lane % 32, and the 32 lanes of a half-wave store 32 consecutive rows, which are
+// contiguous in the column-major C tile.
+#include "gemm_common.hpp"
+#include "nntile_mi.h"
+
+namespace nnt {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+namespace {
+
+constexpr int BK = 16;
+constexpr int KP = BK + 4;   // padded k extent of a k-fast LDS row (conflict-free 128-bit reads)
+
+template <bool KF, int ROWS>
+__device__ __forceinline__ void gload(f32x4 (&v)[ROWS / 64], const float* base, int64_t ld, int row0,
+                                      int nrows, int k0, int kc, bool vec_ok, int tid) {
+#pragma unroll
+    for (int i = 0; i < ROWS / 64; i++) {
+        const int idx = tid + 256 * i;
+        int r, k;
+        if (KF) { r = idx >> 2; k = (idx & 3) << 2; }
+        else { k = idx / (ROWS / 4); r = (idx % (ROWS / 4)) << 2; }
+        const int gr = row0 + r, gk = k0 + k;
+        const float* p = KF ? base + gk + (int64_t)gr * ld : base + gr + (int64_t)gk * ld;
+        const int cnt = KF ? (gr < nrows ? kc - gk : 0) : (gk < kc ? nrows - gr : 0);
+        f32x4 x = {0.f, 0.f, 0.f, 0.f};
+        if (cnt >= 4 && vec_ok) {
+            x = *reinterpret_cast<const f32x4*>(p);
+        } else {
+            if (cnt > 0) x[0] = p[0];
+            if (cnt > 1) x[1] = p[1];
+            if (cnt > 2) x[2] = p[2];
+            if (cnt > 3) x[3] = p[3];
+        }
+        v[i] = x;
+    }
+}
+
+template <bool KF, int ROWS>
+__device__ __forceinline__ void lstore(float* l, const f32x4 (&v)[ROWS / 64], int tid) {
+#pragma unroll
+    for (int i = 0; i < ROWS / 64; i++) {
+        const int idx = tid + 256 * i;
+        if (KF) {
+            const int r = idx >> 2, k = (idx & 3) << 2;
+            *reinterpret_cast<f32x4*>(&l[r * KP + k]) = v[i];
+        } else {
+            const int k = idx / (ROWS / 4), r = (idx % (ROWS / 4)) << 2;
+            *reinterpret_cast<f32x4*>(&l[k * ROWS + r]) = v[i];
+        }
+    }
+}
+
+// The 8 k-values of this lane's half (k = 8 * half + j) for one 32-row block.
+template <bool KF, int ROWS>
+__device__ __forceinline__ void lfrag(float (&f)[8], const float* l, int row, int half) {
+    if (KF) {
+        const f32x4 a = *reinterpret_cast<const f32x4*>(&l[row * KP + half * 8]);
+        const f32x4 b = *reinterpret_cast<const f32x4*>(&l[row * KP + half * 8 + 4]);
+        f[0] = a[0]; f[1] = a[1]; f[2] = a[2]; f[3] = a[3];
+        f[4] = b[0]; f[5] = b[1]; f[6] = b[2]; f[7] = b[3];
+    } else {
+#pragma unroll
+        for (int j = 0; j < 8; j++) f[j] = l[(half * 8 + j) * ROWS + row];
+    }
+}
+
+template <bool AKF, bool BKF, int WAVES_M, int WAVES_N, int WMB, int WNB>
+__global__ void __launch_bounds__(256) gemm_f32_kernel(const GemmArgs g) {
+    constexpr int BM = 32 * WMB * WAVES_M, BN = 32 * WNB * WAVES_N;
+    constexpr int A_SZ = AKF ? BM * KP : BK * BM;
+    constexpr int B_SZ = BKF ? BN * KP : BK * BN;
+    __shared__ __attribute__((aligned(16))) float lds[2 * (A_SZ + B_SZ)];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave % WAVES_M, wn = wave / WAVES_M;
+    const int r32 = lane & 31, half = lane >> 5;
+
+    GemmTask task;
+    int m0, n0, bat;
+    const GemmChunk* chunks;
+    if (g.wgs) {
+        const GemmWg w = g.wgs[blockIdx.x];
+        task = g.tasks[w.task];
+        m0 = w.m0; n0 = w.n0; bat = w.batch;
+        chunks = g.chunks + task.chunk0;
+    } else {
+        task = g.one_task;
+        const int b = blockIdx.x;
+        m0 = (b % g.grid_m) * BM;
+        n0 = ((b / g.grid_m) % g.grid_n) * BN;
+        bat = b / (g.grid_m * g.grid_n);
+        chunks = &g.one_chunk;
+    }
+
+    f32x16 acc[WNB][WMB];
+#pragma unroll
+    for (int bn = 0; bn < WNB; bn++)
+#pragma unroll
+        for (int bm = 0; bm < WMB; bm++)
+#pragma unroll
+            for (int i = 0; i < 16; i++) acc[bn][bm][i] = 0.f;
+
+    if (task.nchunk > 0) {
+        int c = 0, k0 = 0;
+        GemmChunk ch = chunks[0];
+        const float* Ab = static_cast<const float*>(ch.A) + (int64_t)bat * ch.strideA;
+        const float* Bb = static_cast<const float*>(ch.B) + (int64_t)bat * ch.strideB;
+        f32x4 va[BM / 64], vb[BN / 64];
+        gload<AKF, BM>(va, Ab, ch.lda, m0, task.m, k0, ch.k, ch.vec_ok & 1, tid);
+        gload<BKF, BN>(vb, Bb, ch.ldb, n0, task.n, k0, ch.k, ch.vec_ok & 2, tid);
+        int cur = 0;
+        lstore<AKF, BM>(lds, va, tid);
+        lstore<BKF, BN>(lds + A_SZ, vb, tid);
+        __syncthreads();
+        bool more = true;
+        while (more) {
+            // advance to the next k-step (possibly the next chunk) and start its loads
+            k0 += BK;
+            if (k0 >= ch.k) {
+                c++;
+                k0 = 0;
+                if (c < task.nchunk) {
+                    ch = chunks[c];
+                    Ab = static_cast<const float*>(ch.A) + (int64_t)bat * ch.strideA;
+                    Bb = static_cast<const float*>(ch.B) + (int64_t)bat * ch.strideB;
+                }
+            }
+            more = c < task.nchunk;
+            if (more) {
+                gload<AKF, BM>(va, Ab, ch.lda, m0, task.m, k0, ch.k, ch.vec_ok & 1, tid);
+                gload<BKF, BN>(vb, Bb, ch.ldb, n0, task.n, k0, ch.k, ch.vec_ok & 2, tid);
+            }
+            const float* lA = lds + cur * (A_SZ + B_SZ);
+            const float* lB = lA + A_SZ;
+            float pf[WNB][8], qf[WMB][8];
+#pragma unroll
+            for (int bn = 0; bn < WNB; bn++) lfrag<BKF, BN>(pf[bn], lB, (wn * WNB + bn) * 32 + r32, half);
+#pragma unroll
+            for (int bm = 0; bm < WMB; bm++) lfrag<AKF, BM>(qf[bm], lA, (wm * WMB + bm) * 32 + r32, half);
+#pragma unroll
+            for (int j = 0; j < 8; j++)
+#pragma unroll
+                for (int bn = 0; bn < WNB; bn++)
+#pragma unroll
+                    for (int bm = 0; bm < WMB; bm++)
+                        acc[bn][bm] = __builtin_amdgcn_mfma_f32_32x32x2f32(pf[bn][j], qf[bm][j], acc[bn][bm], 0, 0, 0);
+            if (more) {
+                float* nA = lds + (cur ^ 1) * (A_SZ + B_SZ);
+                lstore<AKF, BM>(nA, va, tid);
+                lstore<BKF, BN>(nA + A_SZ, vb, tid);
+            }
+            __syncthreads();
+            cur ^= 1;
+        }
+    }
+
+    // epilogue: lane holds row m = r32, columns n = 8 * (i / 4) + 4 * half + i % 4 of each 32 x 32 block
+    float* C = static_cast<float*>(task.C) + (int64_t)bat * task.strideC;
+    const float alpha = g.alpha, beta = g.beta;
+#pragma unroll
+    for (int bm = 0; bm < WMB; bm++) {
+        const int gm = m0 + (wm * WMB + bm) * 32 + r32;
+        if (gm >= task.m) continue;
+        const float bias = task.bias ? task.bias[gm] : 0.f;
+#pragma unroll
+        for (int bn = 0; bn < WNB; bn++) {
+#pragma unroll
+            for (int i = 0; i < 16; i++) {
+                const int gn = n0 + (wn * WNB + bn) * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
+                if (gn < task.n) {
+                    float* p = C + gm + (int64_t)gn * task.ldc;
+                    float v = alpha * acc[bn][bm][i] + bias;
+                    if (beta != 0.f) v += beta * *p;
+                    *p = v;
+                }
+            }
+        }
+    }
+}
+
+template <bool AKF, bool BKF>
+int32_t launch_cfg(hipStream_t st, int cfg, const GemmArgs& g, int64_t nwg) {
+    dim3 grid((unsigned)nwg), block(256);
+    switch (cfg) {
+        case kCfgSquare:
+        case kCfgMid:
+            hipLaunchKernelGGL((gemm_f32_kernel<AKF, BKF, 2, 2, 2, 2>), grid, block, 0, st, g);
+            break;
+        case kCfgSkinny64:
+            hipLaunchKernelGGL((gemm_f32_kernel<AKF, BKF, 1, 4, 2, 2>), grid, block, 0, st, g);
+            break;
+        default:
+            hipLaunchKernelGGL((gemm_f32_kernel<AKF, BKF, 1, 4, 4, 2>), grid, block, 0, st, g);
+            break;
+    }
+    return hipGetLastError() == hipSuccess ? NNT_OK : NNT_EHIP;
+}
+
+}  // namespace
+
+int32_t launch_gemm_f32(hipStream_t st, int akf, int bkf, int cfg, const GemmArgs& g, int64_t nwg) {
+    if (nwg <= 0) return NNT_OK;
+    if (akf) return bkf ? launch_cfg<true, true>(st, cfg, g, nwg) : launch_cfg<true, false>(st, cfg, g, nwg);
+    return bkf ? launch_cfg<false, true>(st, cfg, g, nwg) : launch_cfg<false, false>(st, cfg, g, nwg);
+}
+
+}  // namespace nnt

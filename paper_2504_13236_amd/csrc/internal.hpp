@@ -1,0 +1,163 @@
+// Internal declarations shared by the translation units of libnntile_mi.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <functional>
+#include <map>
+#include <memory>
+#include <string>
+#include <vector>
+
+#include "nntile_mi.h"
+
+namespace nnt {
+
+constexpr int kMaxStreams = 8;
+constexpr int kMaxDim = NNT_MAX_DIM;
+
+// ---------------------------------------------------------------- device-side views
+// A tiled tensor as kernels see it: extents, base tile, grid and the table of
+// tile pointers (device memory, grid order, first axis fastest).
+struct TiledView {
+    void* const* tiles;
+    int32_t ndim;
+    int32_t shape[kMaxDim];
+    int32_t base[kMaxDim];
+    int32_t grid[kMaxDim];
+};
+
+// ---------------------------------------------------------------- dependency tracking
+// What the executor remembers per tile: who wrote it last and who has read it
+// since (one sequence number per stream is enough: streams run in order).
+struct TileDep {
+    int32_t w_stream = -1;
+    uint64_t w_seq = 0;
+    uint64_t r_seq[kMaxStreams] = {0, 0, 0, 0, 0, 0, 0, 0};
+};
+
+enum AccessMode { kRead = 1, kWrite = 2, kReadWrite = 3 };
+
+struct Access {
+    TileDep* first;
+    int64_t count;
+    int mode;
+};
+
+struct GemmPlan;
+
+}  // namespace nnt
+
+struct nnt_tensor {
+    nnt_ctx* ctx;
+    int32_t dtype;
+    int32_t ndim;
+    int64_t shape[nnt::kMaxDim];
+    int64_t base[nnt::kMaxDim];
+    int64_t grid[nnt::kMaxDim];
+    int64_t ntiles;
+    std::vector<void*> tiles;        // host copy of the tile pointers
+    void** d_tiles;                  // device copy
+    std::vector<nnt::TileDep> deps;  // one per tile
+    uint64_t id;
+
+    int64_t elem_size() const { return dtype == NNT_F32 ? 4 : 2; }
+    void tile_coords(int64_t idx, int64_t* c) const {
+        for (int a = 0; a < ndim; a++) { c[a] = idx % grid[a]; idx /= grid[a]; }
+    }
+    int64_t tile_index(const int64_t* c) const {
+        int64_t idx = 0;
+        for (int a = ndim - 1; a >= 0; a--) idx = idx * grid[a] + c[a];
+        return idx;
+    }
+    int64_t tile_extent(int a, int64_t c) const {
+        int64_t lo = c * base[a];
+        int64_t hi = lo + base[a];
+        return (hi > shape[a] ? shape[a] : hi) - lo;
+    }
+    int64_t tile_numel(int64_t idx) const {
+        int64_t c[nnt::kMaxDim];
+        tile_coords(idx, c);
+        int64_t n = 1;
+        for (int a = 0; a < ndim; a++) n *= tile_extent(a, c[a]);
+        return n;
+    }
+    nnt::TiledView view() const {
+        nnt::TiledView v;
+        v.tiles = d_tiles;
+        v.ndim = ndim;
+        for (int a = 0; a < nnt::kMaxDim; a++) {
+            v.shape[a] = a < ndim ? (int32_t)shape[a] : 1;
+            v.base[a] = a < ndim ? (int32_t)base[a] : 1;
+            v.grid[a] = a < ndim ? (int32_t)grid[a] : 1;
+        }
+        return v;
+    }
+    nnt::Access all(int mode) { return nnt::Access{deps.data(), ntiles, mode}; }
+    nnt::Access one(int64_t idx, int mode) { return nnt::Access{&deps[idx], 1, mode}; }
+};
+
+struct nnt_ctx {
+    int device = 0;
+    int n_streams = 1;
+    bool own_streams = true;
+    bool serial = false;
+    int granularity = NNT_GRAN_OP;
+    int status = NNT_OK;             // sticky
+    std::string error;
+    hipStream_t streams[nnt::kMaxStreams];
+    uint64_t tail_seq[nnt::kMaxStreams];     // last sequence number issued per stream
+    uint64_t synced_seq[nnt::kMaxStreams];   // everything up to here is known complete
+    uint64_t waited[nnt::kMaxStreams][nnt::kMaxStreams];  // waited[s][d]: s already waits for d up to this seq
+    std::vector<hipEvent_t> events[nnt::kMaxStreams];     // events[s][seq - synced_seq[s] - 1]
+    std::vector<hipEvent_t> event_pool;
+    int rr = 0;                      // round-robin cursor
+    bool capturing = false;
+    nnt_exec_stats stats = {0, 0, 0, 0};
+    uint64_t next_tensor_id = 1;
+    std::map<std::string, std::shared_ptr<nnt::GemmPlan>> gemm_plans;
+    int64_t live_tensors = 0;
+    // fp32 scratch for two-stage reductions (bias gradient, layer-norm parameter
+    // gradients); grows on demand, guarded by its own dependency record.
+    float* red_scratch = nullptr;
+    int64_t red_scratch_elems = 0;
+    nnt::TileDep red_dep;
+};
+
+namespace nnt {
+
+int32_t fail(nnt_ctx* ctx, int32_t code, const std::string& msg);
+#define NNT_CHECK_CTX(ctx)                                         \
+    do {                                                           \
+        if (!(ctx)) return NNT_EINVAL;                             \
+        if ((ctx)->status != NNT_OK) return NNT_ESTATE;            \
+    } while (0)
+#define NNT_HIP(ctx, expr)                                                                   \
+    do {                                                                                     \
+        hipError_t e__ = (expr);                                                             \
+        if (e__ != hipSuccess)                                                               \
+            return nnt::fail((ctx), NNT_EHIP, std::string(#expr) + ": " + hipGetErrorString(e__)); \
+    } while (0)
+
+// Submits one task: waits for the tiles' pending users, runs `launch` on the
+// chosen stream, records the task's completion.  `launch` returns a status.
+int32_t submit(nnt_ctx* ctx, const std::vector<Access>& acc,
+               const std::function<int32_t(hipStream_t)>& launch, int n_launches = 1);
+int32_t ensure_scratch(nnt_ctx* ctx, int64_t elems);
+void drop_plans_of(nnt_ctx* ctx, uint64_t tensor_id);
+
+inline bool same_tiling(const nnt_tensor* a, const nnt_tensor* b) {
+    if (a->ndim != b->ndim) return false;
+    for (int i = 0; i < a->ndim; i++)
+        if (a->shape[i] != b->shape[i] || a->base[i] != b->base[i]) return false;
+    return true;
+}
+inline bool null_alike(const nnt_tensor* a, const nnt_tensor* b) {
+    for (int64_t i = 0; i < a->ntiles; i++)
+        if ((a->tiles[i] == nullptr) != (b->tiles[i] == nullptr)) return false;
+    return true;
+}
+
+// ---- stream-level launchers used both by the tile API and by the tensor ops
+int32_t launch_status(const char* what);
+
+}  // namespace nnt

@@ -1,0 +1,115 @@
+"""Host-only checks of the boundary: the library loads, exports every entry point
+the header declares, the binding covers them all, and the host-side helpers
+(tiling arithmetic, argument validation that needs no device) behave."""
+import ctypes as C
+import os
+import re
+import subprocess
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "nntile_mi.h")
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    return sorted(set(re.findall(r"NNT_API\s+[\w\s\*]+?\b(nnt_\w+)\s*\(", text)))
+
+
+@pytest.fixture(scope="module")
+def capi():
+    from paper_2504_13236_amd import capi as m
+    return m
+
+
+def test_header_declares_entry_points():
+    syms = declared_symbols()
+    assert len(syms) >= 60
+    for must in ("nnt_tile_gemm", "nnt_gemm", "nnt_layernorm_fwd", "nnt_softmax_fwd", "nnt_adam_step",
+                 "nnt_gpt2_block_forward", "nnt_gpt2_block_backward", "nnt_ctx_create", "nnt_tensor_create"):
+        assert must in syms
+
+
+def test_library_exports_every_declared_symbol(capi):
+    out = subprocess.run(["nm", "-D", "--defined-only", capi.LIB_PATH], capture_output=True, text=True, check=True).stdout
+    exported = set(re.findall(r" T (nnt_\w+)", out))
+    missing = [s for s in declared_symbols() if s not in exported]
+    assert not missing, missing
+    # nothing but the C ABI is exported
+    others = [l for l in out.splitlines() if " T " in l and " T nnt_" not in l and "_init" not in l and "_fini" not in l]
+    assert not others, others[:5]
+
+
+def test_binding_covers_every_declared_symbol(capi):
+    syms = declared_symbols()
+    assert sorted(capi.PROTOTYPES) == syms
+    for s in syms:
+        assert callable(getattr(capi, s))
+    assert capi.nnt_version().startswith(b"nntile_mi")
+
+
+def test_binding_argument_counts_match_header(capi):
+    text = open(HEADER).read()
+    for name, (_, argtypes) in capi.PROTOTYPES.items():
+        m = re.search(r"NNT_API\s+[\w\s\*]+?\b%s\s*\(([^;]*?)\)\s*;" % name, text, re.S)
+        assert m, name
+        args = m.group(1).strip()
+        n = 0 if args in ("", "void") else len([a for a in args.split(",") if a.strip()])
+        assert n == len(argtypes), (name, n, len(argtypes))
+
+
+def test_tiling_helpers_host_only(capi):
+    n = C.c_int64()
+    capi.nnt_tiling_ntiles(3, capi.i64_array([1600, 1024, 8]), capi.i64_array([400, 400, 8]), C.byref(n))
+    assert n.value == 4 * 3 * 1
+    shp = (C.c_int64 * 3)()
+    # tile 11 = (3, 2, 0): ragged sequence tile 224
+    capi.nnt_tiling_tile_shape(3, capi.i64_array([1600, 1024, 8]), capi.i64_array([400, 400, 8]), 11, shp)
+    assert list(shp) == [400, 224, 8]
+    capi.nnt_tiling_tile_shape(2, capi.i64_array([10, 7]), capi.i64_array([4, 3]), 8, shp)
+    assert list(shp)[:2] == [2, 1]
+    assert capi.nnt_tiling_ntiles.raw(0, capi.i64_array([1]), capi.i64_array([1]), C.byref(n)) == capi.NNT_EINVAL
+    assert capi.nnt_tiling_ntiles.raw(2, capi.i64_array([4, 0]), capi.i64_array([1, 1]), C.byref(n)) == capi.NNT_EINVAL
+    assert capi.nnt_tiling_tile_shape.raw(1, capi.i64_array([4]), capi.i64_array([2]), 2, shp) == capi.NNT_EINVAL
+
+
+def test_argument_validation_without_device(capi):
+    # these return before touching the GPU
+    assert capi.nnt_tile_gemm.raw(None, 7, 0, 0, 0, 4, 4, 4, 1, 1.0, None, 4, 16, None, 4, 16, 0.0, None, 4, 16) == capi.NNT_EDTYPE
+    assert capi.nnt_tile_gemm.raw(None, 0, 1, 0, 0, 4, 4, 4, 1, 1.0, None, 4, 16, None, 4, 16, 0.0, None, 4, 16) == capi.NNT_EDTYPE
+    assert capi.nnt_tile_gemm.raw(None, 0, 0, 0, 0, 4, 4, 4, 1, 1.0, None, 4, 16, None, 4, 16, 0.0, None, 4, 16) == capi.NNT_EINVAL
+    assert capi.nnt_tile_gemm.raw(None, 0, 0, 0, 0, 0, 4, 4, 1, 1.0, None, 4, 16, None, 4, 16, 0.0, None, 4, 16) == capi.NNT_OK
+    assert capi.nnt_tile_gelu.raw(None, 0, 5, 8, None, None) == capi.NNT_EINVAL
+    assert capi.nnt_tile_adam.raw(None, 8, 0, 1e-3, 0.9, 0.999, 1e-8, 0.0, None, None, None, None, None) == capi.NNT_EINVAL
+    assert capi.nnt_tile_bias_grad_scratch(768, 2048) >= 768 * (2048 // 64)
+    assert capi.nnt_wait.raw(None) == capi.NNT_EINVAL
+    cfg = capi.nnt_gpt2_block_cfg()
+    info = capi.nnt_slot_info()
+    assert capi.nnt_gpt2_block_slot.raw(C.byref(cfg), 0, C.byref(info)) == capi.NNT_EINVAL      # all-zero config
+
+
+def test_block_slot_table_host_only(capi):
+    import workload
+    cfg = workload.CONFIGS[4]
+    bt = workload.base_tiles(cfg)
+    c = capi.nnt_gpt2_block_cfg(cfg.N_e, cfg.N_h, cfg.N_m, cfg.N_s, cfg.N_b, bt["e"], bt["m"], bt["s"], bt["b"], bt["j"], bt["i"],
+                                capi.NNT_BF16, capi.NNT_GELU_TANH, 1e-5, 1)
+    info = capi.nnt_slot_info()
+    capi.nnt_gpt2_block_slot(C.byref(c), capi.NNT_BLK_P, C.byref(info))
+    assert info.used and info.dtype == capi.NNT_BF16 and info.causal_tiles == 1
+    assert list(info.shape) == [1024, 1024, 8, 25] and list(info.basetile) == [400, 400, 8, 25]
+    capi.nnt_gpt2_block_slot(C.byref(c), capi.NNT_BLK_W_1, C.byref(info))
+    assert info.dtype == capi.NNT_F32 and list(info.shape)[:2] == [6400, 1600] and list(info.basetile)[:2] == [400, 400]
+    capi.nnt_gpt2_block_slot(C.byref(c), capi.NNT_BLK_LOWP + 2, C.byref(info))
+    assert info.used and info.dtype == capi.NNT_BF16
+    capi.nnt_gpt2_block_slot(C.byref(c), capi.NNT_BLK_Q, C.byref(info))
+    assert list(info.shape) == [64, 1024, 8, 25] and list(info.basetile) == [64, 400, 8, 25]
+    c.dtype = capi.NNT_F32
+    capi.nnt_gpt2_block_slot(C.byref(c), capi.NNT_BLK_LOWP, C.byref(info))
+    assert not info.used
+    used = 0
+    for s in range(capi.NNT_BLK_NSLOTS):
+        capi.nnt_gpt2_block_slot(C.byref(c), s, C.byref(info))
+        used += info.used
+    assert used == capi.NNT_BLK_NSLOTS - 4
