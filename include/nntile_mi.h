@@ -110,6 +110,25 @@ typedef struct nnt_exec_stats {
 } nnt_exec_stats;
 NNT_API int32_t nnt_ctx_stats(nnt_ctx* ctx, nnt_exec_stats* out);
 
+/* Per-task timing for measurements.  While enabled, every task is bracketed by a
+ * pair of timing events on the stream it runs on; nnt_profile_read waits for all
+ * work and returns one entry per operation label (at most `capacity` entries are
+ * written, *n_out is the number that exist): tasks, kernel launches, summed
+ * device time, and the algorithmic work the operations stand for (flops for
+ * products, bytes for memory-bound operations: the bytes that one pass over the
+ * operands moves).  Enabling clears earlier records.  Not available during capture. */
+typedef struct nnt_profile_entry {
+    char    label[112];
+    int64_t tasks;
+    int64_t launches;
+    double  ms;
+    double  work;
+    int32_t work_is_bytes;
+    int32_t reserved;
+} nnt_profile_entry;
+NNT_API int32_t nnt_profile_enable(nnt_ctx* ctx, int32_t on);
+NNT_API int32_t nnt_profile_read(nnt_ctx* ctx, nnt_profile_entry* out, int32_t capacity, int32_t* n_out);
+
 /* Stream capture of the task flow into a HIP graph (section 2: the graph of a
  * training iteration repeats, so it can be built once and replayed).  Between
  * begin and end, tensor-level calls are recorded instead of run; every plan they

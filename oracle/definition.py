@@ -208,8 +208,8 @@ def merge_heads(parts):
     return Z5.reshape(len(parts) * N_h * h, N_s, N_b)
 
 
-def _jb(T):   # [i, s, b, j] -> [j, b, i, s]
-    return T.transpose(3, 2, 0, 1)
+def _jb(T):   # [i, s, b, j] -> [j, b, i, s], stored contiguously so that matmul can hand each matrix to BLAS
+    return np.ascontiguousarray(T.transpose(3, 2, 0, 1))
 
 
 def _back(T):  # [j, b, x, y] -> [x, y, b, j]
@@ -224,7 +224,7 @@ def attention_scores(K, Q):
 
 def attention_values(V, P):
     """B[i, q, b, j] = sum_k V[i, k, b, j] P[k, q, b, j]."""
-    return _back(np.matmul(_jb(V), P.transpose(3, 2, 0, 1)))
+    return _back(np.matmul(_jb(V), _jb(P)))
 
 
 def attention_fwd(Q, K, V, causal=True):
@@ -236,12 +236,12 @@ def attention_fwd(Q, K, V, causal=True):
 def attention_bwd(Q, K, V, P, dB):
     h = Q.shape[0]
     sc = 1.0 / math.sqrt(h)
-    Pj = P.transpose(3, 2, 0, 1)             # [j, b, k, q]
+    Pj = _jb(P)                              # [j, b, k, q]
     dBj = _jb(dB)                            # [j, b, i, q]
     dV = _back(np.matmul(dBj, Pj.transpose(0, 1, 3, 2)))          # dV[i,k] = sum_q dB[i,q] P[k,q]
     dP = _back(np.matmul(_jb(V).transpose(0, 1, 3, 2), dBj))      # dP[k,q] = sum_i V[i,k] dB[i,q]
     dA = softmax_bwd(P, dP)
-    dAj = dA.transpose(3, 2, 0, 1)
+    dAj = _jb(dA)
     dQ = sc * _back(np.matmul(_jb(K), dAj))                        # dQ[i,q] = sc sum_k K[i,k] dA[k,q]
     dK = sc * _back(np.matmul(_jb(Q), dAj.transpose(0, 1, 3, 2)))  # dK[i,k] = sc sum_q Q[i,q] dA[k,q]
     return dQ, dK, dV

@@ -44,6 +44,11 @@ class nnt_exec_stats(C.Structure):
     _fields_ = [("tasks", C.c_int64), ("launches", C.c_int64), ("event_waits", C.c_int64), ("plans", C.c_int64)]
 
 
+class nnt_profile_entry(C.Structure):
+    _fields_ = [("label", C.c_char * 112), ("tasks", C.c_int64), ("launches", C.c_int64), ("ms", C.c_double),
+                ("work", C.c_double), ("work_is_bytes", C.c_int32), ("reserved", C.c_int32)]
+
+
 class nnt_adam_cfg(C.Structure):
     _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
                 ("weight_decay", C.c_float)]
@@ -80,6 +85,8 @@ PROTOTYPES = {
     "nnt_ctx_set_serial": (_i32, [_p, _i32]),
     "nnt_ctx_set_granularity": (_i32, [_p, _i32]),
     "nnt_ctx_stats": (_i32, [_p, C.POINTER(nnt_exec_stats)]),
+    "nnt_profile_enable": (_i32, [_p, _i32]),
+    "nnt_profile_read": (_i32, [_p, C.POINTER(nnt_profile_entry), _i32, C.POINTER(C.c_int32)]),
     "nnt_capture_begin": (_i32, [_p]),
     "nnt_capture_end": (_i32, [_p, _pp]),
     "nnt_graph_launch": (_i32, [_p]),

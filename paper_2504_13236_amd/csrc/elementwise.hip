@@ -388,6 +388,14 @@ int32_t run_tensor_ew(nnt_ctx* ctx, nnt_tensor* ref, const std::vector<std::pair
 
 Operand opnd(const nnt_tensor* t, int64_t tile) { return tile < 0 ? tab(t) : tab1(t, tile); }
 
+// elements held in the tiles that exist
+double present_numel(const nnt_tensor* t) {
+    double n = 0;
+    for (int64_t i = 0; i < t->ntiles; i++)
+        if (t->tiles[i]) n += (double)t->tile_numel(i);
+    return n;
+}
+
 }  // namespace
 }  // namespace nnt
 
@@ -496,6 +504,7 @@ int32_t nnt_tile_adam(void* stream, int64_t n, int32_t step, float lr, float bet
 int32_t nnt_fill(nnt_ctx* ctx, float value, nnt_tensor* X) {
     NNT_CHECK_CTX(ctx);
     if (!X) return fail(ctx, NNT_EINVAL, "nnt_fill: null tensor");
+    OpTag tag(ctx, "fill", present_numel(X) * X->elem_size(), true);
     const bool vec = all_aligned(X);
     if (X->dtype == NNT_F32)
         return run_tensor_ew(ctx, X, {{X, kWrite}}, vec, [=](int64_t t) { return FillF<float>{opnd(X, t), value}; });
@@ -508,6 +517,7 @@ int32_t nnt_add(nnt_ctx* ctx, float alpha, nnt_tensor* X, float beta, nnt_tensor
     if (!same_tiling(X, Y) || !null_alike(X, Y)) return fail(ctx, NNT_EINVAL, "nnt_add: operands tiled differently");
     if (X->dtype != Y->dtype) return fail(ctx, NNT_EDTYPE, "nnt_add: operand types differ");
     const bool vec = all_aligned(X) && all_aligned(Y);
+    OpTag tag(ctx, "add", present_numel(Y) * Y->elem_size() * (beta != 0.f ? 3 : 2), true);
     const int ymode = beta != 0.f ? kReadWrite : kWrite;
     if (X->dtype == NNT_F32)
         return run_tensor_ew(ctx, Y, {{X, kRead}, {Y, ymode}}, vec,
@@ -520,6 +530,7 @@ int32_t nnt_cast(nnt_ctx* ctx, nnt_tensor* X, nnt_tensor* Y) {
     NNT_CHECK_CTX(ctx);
     if (!X || !Y) return fail(ctx, NNT_EINVAL, "nnt_cast: null tensor");
     if (!same_tiling(X, Y) || !null_alike(X, Y)) return fail(ctx, NNT_EINVAL, "nnt_cast: operands tiled differently");
+    OpTag tag(ctx, "cast", present_numel(Y) * (X->elem_size() + Y->elem_size()), true);
     const bool vec = all_aligned(X) && all_aligned(Y);
     std::vector<std::pair<nnt_tensor*, int>> ops = {{X, kRead}, {Y, kWrite}};
     if (X->dtype == NNT_F32 && Y->dtype == NNT_BF16)
@@ -537,6 +548,7 @@ int32_t nnt_gelu(nnt_ctx* ctx, int32_t variant, nnt_tensor* X, nnt_tensor* Y) {
     if (variant != NNT_GELU_TANH && variant != NNT_GELU_ERF) return fail(ctx, NNT_EINVAL, "nnt_gelu: unknown variant");
     if (!same_tiling(X, Y) || !null_alike(X, Y)) return fail(ctx, NNT_EINVAL, "nnt_gelu: operands tiled differently");
     if (X->dtype != Y->dtype) return fail(ctx, NNT_EDTYPE, "nnt_gelu: operand types differ");
+    OpTag tag(ctx, "gelu", present_numel(Y) * Y->elem_size() * 2, true);
     const bool vec = all_aligned(X) && all_aligned(Y);
     std::vector<std::pair<nnt_tensor*, int>> ops = {{X, kRead}, {Y, kWrite}};
     if (X->dtype == NNT_F32)
@@ -552,6 +564,7 @@ int32_t nnt_gelu_bwd(nnt_ctx* ctx, int32_t variant, nnt_tensor* X, nnt_tensor* d
         return fail(ctx, NNT_EINVAL, "nnt_gelu_bwd: operands tiled differently");
     if (X->dtype != dY->dtype || X->dtype != dX->dtype) return fail(ctx, NNT_EDTYPE, "nnt_gelu_bwd: operand types differ");
     const bool vec = all_aligned(X) && all_aligned(dY) && all_aligned(dX);
+    OpTag tag(ctx, "gelu_bwd", present_numel(dX) * dX->elem_size() * 3, true);
     std::vector<std::pair<nnt_tensor*, int>> ops = {{X, kRead}, {dY, kRead}, {dX, dX == dY ? kReadWrite : kWrite}};
     if (dX == dY) ops.erase(ops.begin() + 1);
     if (X->dtype == NNT_F32)
@@ -570,6 +583,7 @@ int32_t nnt_bias_add(nnt_ctx* ctx, nnt_tensor* b, nnt_tensor* Y) {
         if (!p) return fail(ctx, NNT_EINVAL, "nnt_bias_add: bias tile missing");
     const int V = Y->dtype == NNT_F32 ? 4 : 8;
     const bool vec = all_aligned(Y) && axis0_multiple(Y, V);
+    OpTag tag(ctx, "bias_add", present_numel(Y) * Y->elem_size() * 2, true);
     if (Y->ntiles > 65535) return fail(ctx, NNT_EINVAL, "too many tiles for one launch");
     if (ctx->granularity == NNT_GRAN_OP) {
         const EwGeom g = tiled_geom(Y);
@@ -605,6 +619,7 @@ int32_t nnt_adam_step(nnt_ctx* ctx, const nnt_adam_cfg* cfg, int32_t step, nnt_t
     if (G->dtype != NNT_F32 || P->dtype != NNT_F32 || M->dtype != NNT_F32 || V->dtype != NNT_F32 || (LP && LP->dtype != NNT_BF16))
         return fail(ctx, NNT_EDTYPE, "nnt_adam_step: g, p, m, v must be fp32 and the low-precision copy bf16");
     const bool vec = all_aligned(G) && all_aligned(P) && all_aligned(M) && all_aligned(V) && (!LP || all_aligned(LP));
+    OpTag tag(ctx, "adam", present_numel(P) * (28 + (LP ? 2 : 0)), true);
     AdamF base = make_adam(step, cfg->lr, cfg->beta1, cfg->beta2, cfg->eps, cfg->weight_decay);
     std::vector<std::pair<nnt_tensor*, int>> ops = {{G, kRead}, {P, kReadWrite}, {M, kReadWrite}, {V, kReadWrite}};
     if (LP) ops.push_back({LP, kWrite});
@@ -634,6 +649,7 @@ static int32_t head_common(nnt_ctx* ctx, nnt_tensor* Z, int32_t n_parts, nnt_ten
     const int64_t h = q0->shape[0], N_h = q0->shape[3];
     if (Z->shape[0] != n_parts * N_h * h || Z->shape[1] != q0->shape[1] || Z->shape[2] != q0->shape[2])
         return fail(ctx, NNT_EINVAL, "head split/merge: shapes do not match");
+    OpTag tag(ctx, to_parts ? "head_split" : "head_merge", present_numel(Z) * Z->elem_size() * 2, true);
 
     if (ctx->granularity == NNT_GRAN_OP) {
         HeadArgs a;

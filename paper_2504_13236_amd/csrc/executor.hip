@@ -94,7 +94,25 @@ int32_t submit(nnt_ctx* ctx, const std::vector<Access>& acc,
         ctx->waited[chosen][s] = need[s];
         ctx->stats.event_waits++;
     }
+    nnt_ctx::ProfileRec prof;
+    const bool timed = ctx->profiling && !ctx->capturing;
+    if (timed) {
+        for (hipEvent_t* e : {&prof.start, &prof.stop}) {
+            if (!ctx->timing_pool.empty()) { *e = ctx->timing_pool.back(); ctx->timing_pool.pop_back(); }
+            else NNT_HIP(ctx, hipEventCreate(e));
+        }
+        prof.label = ctx->cur_label ? ctx->cur_label : "task";
+        prof.work = ctx->cur_work;
+        prof.bytes = ctx->cur_work_is_bytes;
+        prof.launches = n_launches;
+        ctx->cur_work = 0.0;     // the operation's work is counted once, on its first task
+        NNT_HIP(ctx, hipEventRecord(prof.start, st));
+    }
     int32_t rc = launch(st);
+    if (timed) {
+        NNT_HIP(ctx, hipEventRecord(prof.stop, st));
+        ctx->profile.push_back(prof);
+    }
     if (rc != NNT_OK) {
         if (rc == NNT_EHIP) return fail(ctx, rc, "kernel launch failed");
         return rc;
@@ -184,6 +202,8 @@ int32_t nnt_ctx_destroy(nnt_ctx* ctx) {
     for (int s = 0; s < ctx->n_streams; s++) (void)hipStreamSynchronize(ctx->streams[s]);
     mark_all_synced(ctx);
     for (hipEvent_t e : ctx->event_pool) (void)hipEventDestroy(e);
+    for (auto& r : ctx->profile) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
+    for (hipEvent_t e : ctx->timing_pool) (void)hipEventDestroy(e);
     ctx->gemm_plans.clear();
     if (ctx->red_scratch) (void)hipFree(ctx->red_scratch);
     if (ctx->own_streams)
@@ -240,6 +260,48 @@ int32_t nnt_ctx_stats(nnt_ctx* ctx, nnt_exec_stats* out) {
     if (!ctx || !out) return NNT_EINVAL;
     *out = ctx->stats;
     out->plans = (int64_t)ctx->gemm_plans.size();
+    return NNT_OK;
+}
+
+// ---------------------------------------------------------------- per-task timing
+int32_t nnt_profile_enable(nnt_ctx* ctx, int32_t on) {
+    NNT_CHECK_CTX(ctx);
+    if (ctx->capturing) return fail(ctx, NNT_ESTATE, "nnt_profile_enable during capture");
+    int32_t rc = sync_all(ctx);
+    if (rc != NNT_OK) return rc;
+    for (auto& r : ctx->profile) { ctx->timing_pool.push_back(r.start); ctx->timing_pool.push_back(r.stop); }
+    ctx->profile.clear();
+    ctx->profiling = on != 0;
+    return NNT_OK;
+}
+
+int32_t nnt_profile_read(nnt_ctx* ctx, nnt_profile_entry* out, int32_t capacity, int32_t* n_out) {
+    NNT_CHECK_CTX(ctx);
+    if (!n_out || capacity < 0 || (capacity > 0 && !out)) return fail(ctx, NNT_EINVAL, "nnt_profile_read: bad argument");
+    int32_t rc = sync_all(ctx);
+    if (rc != NNT_OK) return rc;
+    std::map<std::string, nnt_profile_entry> agg;
+    for (auto& r : ctx->profile) {
+        float ms = 0.f;
+        NNT_HIP(ctx, hipEventElapsedTime(&ms, r.start, r.stop));
+        auto it = agg.find(r.label);
+        if (it == agg.end()) {
+            nnt_profile_entry e = {};
+            snprintf(e.label, sizeof(e.label), "%s", r.label.c_str());
+            e.work_is_bytes = r.bytes ? 1 : 0;
+            it = agg.insert({r.label, e}).first;
+        }
+        it->second.tasks += 1;
+        it->second.launches += r.launches;
+        it->second.ms += ms;
+        it->second.work += r.work;
+    }
+    int32_t n = 0;
+    for (auto& kv : agg) {
+        if (n < capacity) out[n] = kv.second;
+        n++;
+    }
+    *n_out = n;
     return NNT_OK;
 }
 

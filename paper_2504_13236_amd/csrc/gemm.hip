@@ -14,6 +14,8 @@ struct GemmPlan {
     uint64_t ids[4] = {0, 0, 0, 0};            // tensors the tables point into (A, B, C, bias)
     int dtype_in = NNT_F32, dtype_out = NNT_F32;
     int akf = 0, bkf = 0, cfg = kCfgSquare;
+    double flops = 0.0;                        // 2 m n k summed over tasks, chunks and batch members
+    std::string label;                         // the kernel instance that runs the plan
     std::vector<GemmTask> tasks;
     std::vector<GemmChunk> chunks;
     std::vector<GemmWg> wgs;
@@ -215,6 +217,7 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
             btl.push_back(bi);
         }
         t.nchunk = (int32_t)P->chunks.size() - t.chunk0;
+        for (int32_t q = t.chunk0; q < t.chunk0 + t.nchunk; q++) P->flops += 2.0 * m * n * P->chunks[q].k * batch;
         P->tasks.push_back(t);
         P->task_ctile.push_back(ci);
         P->task_atiles.push_back(atl);
@@ -228,6 +231,16 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
     P->cfg = pick_cfg(A->dtype == NNT_BF16, m_max, n_max, big);
     int bm, bn;
     gemm_cfg_tile(A->dtype == NNT_BF16, P->cfg, &bm, &bn);
+    {
+        // spelled like the demangled kernel name, so that profiler output can be matched against it
+        static const char* const shape[4] = {"2, 2, 4, 4", "2, 2, 2, 2", "1, 4, 2, 2", "1, 4, 4, 2"};
+        std::ostringstream l;
+        const char* tf[2] = {"false", "true"};
+        if (A->dtype == NNT_F32) l << "gemm_f32_kernel<" << tf[P->akf] << ", " << tf[P->bkf] << ", " << shape[P->cfg == kCfgSquare ? 1 : P->cfg] << ">";
+        else l << "gemm_bf16_kernel<" << (C->dtype == NNT_F32 ? "float" : "unsigned short") << ", " << tf[P->akf] << ", " << tf[P->bkf]
+               << ", " << shape[P->cfg] << ", 32>";
+        P->label = l.str();
+    }
     // Workgroup order inside a task: m index fastest, so that workgroups in flight
     // together share a column panel of B.
     for (size_t ti = 0; ti < P->tasks.size(); ti++) {
@@ -275,6 +288,7 @@ extern "C" int32_t nnt_gemm(nnt_ctx* ctx, float alpha, int32_t opA, nnt_tensor* 
     } else {
         P = it->second.get();
     }
+    OpTag tag(ctx, P->label.c_str(), P->flops, false);
     GemmArgs g = {};
     g.tasks = P->d_tasks;
     g.chunks = P->d_chunks;

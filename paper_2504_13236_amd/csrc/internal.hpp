@@ -121,7 +121,29 @@ struct nnt_ctx {
     float* red_scratch = nullptr;
     int64_t red_scratch_elems = 0;
     nnt::TileDep red_dep;
+    // per-task timing (nnt_profile_*): what the operation being submitted is called and
+    // how much algorithmic work it stands for; the first task of the operation carries it
+    bool profiling = false;
+    const char* cur_label = nullptr;
+    double cur_work = 0.0;
+    bool cur_work_is_bytes = false;
+    struct ProfileRec { std::string label; hipEvent_t start, stop; double work; bool bytes; int launches; };
+    std::vector<ProfileRec> profile;
+    std::vector<hipEvent_t> timing_pool;
 };
+
+namespace nnt {
+// Names the tensor-level operation whose tasks are submitted while it is alive.
+struct OpTag {
+    nnt_ctx* c;
+    OpTag(nnt_ctx* ctx, const char* label, double work, bool bytes) : c(ctx) {
+        c->cur_label = label;
+        c->cur_work = work;
+        c->cur_work_is_bytes = bytes;
+    }
+    ~OpTag() { c->cur_label = nullptr; c->cur_work = 0.0; }
+};
+}  // namespace nnt
 
 namespace nnt {
 

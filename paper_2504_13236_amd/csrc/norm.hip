@@ -603,6 +603,9 @@ int32_t nnt_bias_grad(nnt_ctx* ctx, nnt_tensor* dY, nnt_tensor* db) {
         return fail(ctx, NNT_EINVAL, "nnt_bias_grad: db must be an fp32 vector tiled like dY's first axis");
     for (void* p : dY->tiles) if (!p) return fail(ctx, NNT_EINVAL, "nnt_bias_grad: structural-zero tiles not allowed");
     for (void* p : db->tiles) if (!p) return fail(ctx, NNT_EINVAL, "nnt_bias_grad: structural-zero tiles not allowed");
+    double numel = 1;
+    for (int a = 0; a < dY->ndim; a++) numel *= (double)dY->shape[a];
+    OpTag tag(ctx, "bias_grad", numel * dY->elem_size(), true);
     if (ctx->granularity == NNT_GRAN_OP) return rowsum_tensor(ctx, 0, dY, nullptr, nullptr, db, nullptr);
     // tile by tile: each dY tile adds its column sums to the db tile of its row range
     std::vector<char> seen(db->ntiles, 0);
@@ -635,6 +638,10 @@ int32_t nnt_layernorm_fwd(nnt_ctx* ctx, nnt_tensor* X, nnt_tensor* gamma, nnt_te
     for (void* p : Y->tiles) if (!p) return fail(ctx, NNT_EINVAL, "nnt_layernorm_fwd: structural-zero tiles not allowed");
     for (void* p : beta->tiles) if (!p) return fail(ctx, NNT_EINVAL, "nnt_layernorm_fwd: structural-zero tiles not allowed");
     const int dtype = X->dtype;
+    double numel = 1;
+    for (int a = 0; a < X->ndim; a++) numel *= (double)X->shape[a];
+    // one wave per token reads x once and writes y once; tile by tile x is read twice
+    OpTag tag(ctx, "layernorm_fwd", numel * X->elem_size() * (ctx->granularity == NNT_GRAN_OP ? 2 : 3), true);
     if (ctx->granularity == NNT_GRAN_OP) {
         const int V = dtype == NNT_F32 ? 4 : 8;
         const bool vec = tensors_vec_ok({X, Y, gamma, beta}, V);
@@ -692,6 +699,10 @@ int32_t nnt_layernorm_bwd(nnt_ctx* ctx, nnt_tensor* X, nnt_tensor* stats, nnt_te
     if (dRes) for (void* p : dRes->tiles) if (!p) return fail(ctx, NNT_EINVAL, "nnt_layernorm_bwd: structural-zero tiles not allowed");
     const int dtype = X->dtype;
     const int64_t g0 = X->grid[0], rest = X->ntiles / g0, N_e = X->shape[0];
+    double numel = 1;
+    for (int a = 0; a < X->ndim; a++) numel *= (double)X->shape[a];
+    // parameter gradients read x and dy; the input gradient reads x, dy (and the residual) and writes dx
+    OpTag tag(ctx, "layernorm_bwd", numel * X->elem_size() * (5 + (dRes ? 1 : 0)), true);
     if (ctx->granularity == NNT_GRAN_OP) {
         const int V = dtype == NNT_F32 ? 4 : 8;
         const bool vec = tensors_vec_ok({X, dY, dX, dRes, gamma}, V);

@@ -385,6 +385,11 @@ int32_t nnt_softmax_fwd(nnt_ctx* ctx, nnt_tensor* A, nnt_tensor* stats, float sc
         if (!causal || kfirst <= qlast) return fail(ctx, NNT_EINVAL, "nnt_softmax_fwd: a missing tile holds visible scores");
     }
     const int dtype = A->dtype;
+    double present = 0;
+    for (int64_t t = 0; t < A->ntiles; t++)
+        if (A->tiles[t]) present += (double)A->tile_numel(t);
+    // in place: the scores of every present tile are read once and written once (read twice tile by tile)
+    OpTag tag(ctx, "softmax_fwd", present * A->elem_size() * (ctx->granularity == NNT_GRAN_OP ? 2 : 3), true);
     if (ctx->granularity == NNT_GRAN_OP) {
         const int V = dtype == NNT_F32 ? 4 : 8;
         const bool vec = vec_ok_tensor(A, V);
@@ -439,6 +444,10 @@ int32_t nnt_softmax_bwd(nnt_ctx* ctx, nnt_tensor* P, nnt_tensor* dP) {
         return fail(ctx, NNT_EINVAL, "nnt_softmax_bwd: operands tiled or typed differently");
     const int dtype = P->dtype;
     const int64_t g0 = P->grid[0], rest = P->ntiles / g0;
+    double present = 0;
+    for (int64_t t = 0; t < P->ntiles; t++)
+        if (P->tiles[t]) present += (double)P->tile_numel(t);
+    OpTag tag(ctx, "softmax_bwd", present * P->elem_size() * (ctx->granularity == NNT_GRAN_OP ? 3 : 5), true);
     if (ctx->granularity == NNT_GRAN_OP) {
         const int V = dtype == NNT_F32 ? 4 : 8;
         const bool vec = vec_ok_tensor(P, V) && vec_ok_tensor(dP, V);

@@ -52,6 +52,21 @@ class Context:
         capi.nnt_ctx_stats(self.h, C.byref(s))
         return dict(tasks=s.tasks, launches=s.launches, event_waits=s.event_waits, plans=s.plans)
 
+    def profile(self, on=True):
+        capi.nnt_profile_enable(self.h, 1 if on else 0)
+
+    def profile_read(self):
+        """{label: dict(tasks, launches, ms, work, unit)} for the tasks run since profile(True)."""
+        cap = 256
+        arr = (capi.nnt_profile_entry * cap)()
+        n = C.c_int32()
+        capi.nnt_profile_read(self.h, arr, cap, C.byref(n))
+        out = {}
+        for e in arr[:min(n.value, cap)]:
+            out[e.label.decode()] = dict(tasks=e.tasks, launches=e.launches, ms=e.ms, work=e.work,
+                                         unit="bytes" if e.work_is_bytes else "flops")
+        return out
+
     def set_granularity(self, g):
         capi.nnt_ctx_set_granularity(self.h, g)
 

@@ -1,0 +1,152 @@
+"""GPU parity of the whole GPT-2 block (forward, backward, Adam) against the fp64
+oracle on the seeded workloads, in the launch configurations the benchmark times."""
+import numpy as np
+import pytest
+
+import workload
+from gpu_util import TOL, relerr
+from oracle import definition as D
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def mods():
+    from paper_2504_13236_amd import capi, tiled
+    return capi, tiled
+
+
+def oracle_run(cfg, inp, adam):
+    p64 = {k: np.asarray(inp[k], np.float64) for k in workload.PARAM_NAMES}
+    if cfg.dtype == "bf16":
+        # the block multiplies with bf16 copies of the fp32 master weights
+        for k in ("W_qkv", "W_o", "W_1", "W_2"):
+            p64[k] = D.round_to_bf16(inp[k]).astype(np.float64)
+    Out, cache = D.block_forward(p64, inp["X"], cfg.N_h, cfg.eps, cfg.gelu)
+    dX, grads = D.block_backward(p64, cache, inp["dOut"], cfg.N_h, cfg.gelu)
+    res = {"Out": Out, "dX": dX, "grads": grads}
+    if adam:
+        res["adam"] = {k: D.adam_step(np.asarray(inp[k], np.float64), grads[k], 0.0, 0.0, 1, **workload.ADAM)
+                       for k in workload.PARAM_NAMES}
+    return res
+
+
+def gpu_run(tiled, cfg, inp, tiles, adam, gran=0, n_streams=4, serial=False):
+    out = {}
+    with tiled.Context(n_streams=n_streams, granularity=gran, serial=serial) as ctx:
+        blk = tiled.Gpt2Block(ctx, cfg.N_e, cfg.N_h, cfg.N_m, cfg.N_s, cfg.N_b, tiles, dtype=cfg.dtype, eps=cfg.eps,
+                              gelu=cfg.gelu, adam=adam)
+        blk.set_params({k: inp[k] for k in workload.PARAM_NAMES})
+        X, dOut = blk.activation(inp["X"]), blk.activation(inp["dOut"])
+        Out, dX = blk.activation(), blk.activation()
+        blk.forward(X, Out)
+        blk.backward(dOut, dX)
+        out["Out"], out["dX"] = Out.download(), dX.download()
+        out["grads"] = {k: blk.grad(k).download() for k in workload.PARAM_NAMES}
+        if adam:
+            blk.adam(1, **workload.ADAM)
+            out["adam"] = {k: (blk.param(k).download(), blk.moment(k, "m").download(), blk.moment(k, "v").download())
+                           for k in workload.PARAM_NAMES}
+        out["stats"] = ctx.stats()
+        blk.close()
+    return out
+
+
+def compare(got, ref, dtype, adam):
+    tol = TOL[dtype]
+    errs = {"Out": relerr(got["Out"], ref["Out"]), "dX": relerr(got["dX"], ref["dX"])}
+    for k in workload.PARAM_NAMES:
+        errs["d" + k] = relerr(got["grads"][k], ref["grads"][k])
+    if adam:
+        for k in workload.PARAM_NAMES:
+            for i, nm in enumerate(("p", "m", "v")):
+                errs["adam_%s_%s" % (nm, k)] = relerr(got["adam"][k][i], ref["adam"][k][i])
+    bad = {k: v for k, v in errs.items() if not v <= tol}
+    assert not bad, "max-norm relative errors above %.0e: %s" % (tol, bad)
+    return errs
+
+
+@pytest.mark.parametrize("gran", [0, 1])
+def test_block_C1_forward_backward_adam(mods, gran):
+    capi, tiled = mods
+    cfg = workload.CONFIGS[1]
+    inp = workload.generate(cfg)
+    ref = oracle_run(cfg, inp, True)
+    got = gpu_run(tiled, cfg, inp, workload.base_tiles(cfg), True, gran=gran)
+    compare(got, ref, "f32", True)
+    assert got["stats"]["tasks"] > (500 if gran else 40)
+
+
+@pytest.mark.parametrize("tiles", [dict(e=24, m=56, s=24, b=1, j=1, i=40), dict(e=128, m=512, s=64, b=2, j=2, i=64)])
+def test_block_C1_other_tilings_give_the_same_result(mods, tiles):
+    """Tiling invariance on the device: ragged / whole tilings against the oracle."""
+    capi, tiled = mods
+    cfg = workload.CONFIGS[1]
+    inp = workload.generate(cfg)
+    ref = oracle_run(cfg, inp, False)
+    for gran in (0, 1):
+        compare(gpu_run(tiled, cfg, inp, tiles, False, gran=gran), ref, "f32", False)
+
+
+def test_block_serial_and_multistream_are_bit_identical(mods):
+    capi, tiled = mods
+    cfg = workload.CONFIGS[1]
+    inp = workload.generate(cfg)
+    a = gpu_run(tiled, cfg, inp, workload.base_tiles(cfg), True, gran=1, n_streams=1, serial=True)
+    b = gpu_run(tiled, cfg, inp, workload.base_tiles(cfg), True, gran=1, n_streams=8)
+    c = gpu_run(tiled, cfg, inp, workload.base_tiles(cfg), True, gran=0, n_streams=8)
+    assert b["stats"]["event_waits"] > 0
+    for other in (b,):
+        np.testing.assert_array_equal(a["Out"], other["Out"])
+        np.testing.assert_array_equal(a["dX"], other["dX"])
+        for k in workload.PARAM_NAMES:
+            np.testing.assert_array_equal(a["grads"][k], other["grads"][k])
+            np.testing.assert_array_equal(a["adam"][k][0], other["adam"][k][0])
+    # one launch per operation sums in a different order: equal within fp32 tolerance only
+    assert relerr(c["Out"], a["Out"]) < 1e-5 and relerr(c["dX"], a["dX"]) < 1e-5
+
+
+def small_bf16_cfg():
+    # C3's recipe at a size the oracle finishes at once: bf16 storage, fp32 accumulate and masters, Adam
+    return workload.CONFIGS[3].replace(N_e=256, N_h=4, N_m=1024, N_s=192, N_b=2, tile=128)
+
+
+@pytest.mark.parametrize("gran", [0, 1])
+def test_block_bf16_small(mods, gran):
+    capi, tiled = mods
+    cfg = small_bf16_cfg()
+    inp = workload.generate(cfg)
+    ref = oracle_run(cfg, inp, True)
+    got = gpu_run(tiled, cfg, inp, workload.base_tiles(cfg), True, gran=gran)
+    compare(got, ref, "bf16", True)
+
+
+def test_block_bf16_ragged_tiles(mods):
+    # C4's recipe scaled down: tile 100 against N_e = 200 (head size 40 crosses tile edges), sequence 100 + 100 + 56
+    capi, tiled = mods
+    cfg = workload.CONFIGS[4].replace(N_e=200, N_h=5, N_m=800, N_s=256, N_b=2, tile=100)
+    inp = workload.generate(cfg)
+    ref = oracle_run(cfg, inp, False)
+    got = gpu_run(tiled, cfg, inp, workload.base_tiles(cfg), False)
+    compare(got, ref, "bf16", False)
+
+
+def test_block_C2_full_size(mods):
+    """The benchmark's workload and launch configuration, every output compared in full."""
+    capi, tiled = mods
+    cfg = workload.CONFIGS[2]
+    inp = workload.generate(cfg)
+    ref = oracle_run(cfg, inp, False)
+    got = gpu_run(tiled, cfg, inp, workload.base_tiles(cfg), False)
+    errs = compare(got, ref, "f32", False)
+    print("C2 max-norm relative errors:", {k: "%.2e" % v for k, v in errs.items()})
+
+
+def test_block_C3_full_size_bf16(mods):
+    capi, tiled = mods
+    cfg = workload.CONFIGS[3]
+    inp = workload.generate(cfg)
+    ref = oracle_run(cfg, inp, True)
+    got = gpu_run(tiled, cfg, inp, workload.base_tiles(cfg), True)
+    errs = compare(got, ref, "bf16", True)
+    print("C3 max-norm relative errors:", {k: "%.2e" % v for k, v in errs.items()})

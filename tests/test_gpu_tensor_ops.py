@@ -1,0 +1,295 @@
+"""GPU parity of the tensor-level operations (tile grids, both executor
+granularities, ragged tilings, structural-zero tiles) against the fp64 oracle."""
+import ctypes as C
+import math
+
+import numpy as np
+import pytest
+
+from gpu_util import TOL, check, quant, relerr
+from oracle import definition as D
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def mods():
+    from paper_2504_13236_amd import capi, tiled
+    return capi, tiled
+
+
+def rng(seed):
+    return np.random.default_rng(seed)
+
+
+GRANS = [0, 1]     # NNT_GRAN_OP, NNT_GRAN_TILE
+
+
+def T(tiled, ctx, a, base, dtype, absent=None):
+    return tiled.TiledTensor.from_numpy(ctx, np.asarray(a, np.float32), base, dtype, absent)
+
+
+# ------------------------------------------------------------------ products
+@pytest.mark.parametrize("gran", GRANS)
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_gemm_linear_layer_forms(mods, gran, dtype):
+    """Y = W X +. b, dX = W^T dY, dW = sum_{s,b} dY X^T on ragged tilings."""
+    capi, tiled = mods
+    r = rng(1)
+    N_d, N_e, N_s, N_b = 200, 136, 72, 3
+    W = quant(r.standard_normal((N_d, N_e)) * 0.1, dtype)
+    X = quant(r.standard_normal((N_e, N_s, N_b)), dtype)
+    b = r.standard_normal(N_d).astype(np.float32)
+    dY = quant(r.standard_normal((N_d, N_s, N_b)), dtype)
+    with tiled.Context(n_streams=4, granularity=gran) as ctx:
+        tW, tX = T(tiled, ctx, W, (64, 48), dtype), T(tiled, ctx, X, (48, 32, 2), dtype)
+        tb = T(tiled, ctx, b, (64,), "f32")
+        tY = tiled.TiledTensor(ctx, dtype, (N_d, N_s, N_b), (64, 32, 2))
+        capi.nnt_gemm(ctx.h, 1.0, 0, tW.h, 0, tX.h, 0.0, tY.h, 1, 0, tb.h)
+        check(tY.download(), D.linear_fwd(W, X, b), dtype, "linear fwd")
+        tdY = T(tiled, ctx, dY, (64, 32, 2), dtype)
+        tdX = tiled.TiledTensor(ctx, dtype, X.shape, (48, 32, 2))
+        capi.nnt_gemm(ctx.h, 1.0, 1, tW.h, 0, tdY.h, 0.0, tdX.h, 1, 0, None)
+        tdW = tiled.TiledTensor(ctx, "f32", W.shape, (64, 48))
+        capi.nnt_gemm(ctx.h, 1.0, 0, tdY.h, 1, tX.h, 0.0, tdW.h, 2, 0, None)
+        dXr, dWr, dbr = D.linear_bwd(W, X, dY)
+        check(tdX.download(), dXr, dtype, "linear dX")
+        check(tdW.download(), dWr, "f32", "linear dW")
+        # beta = 1 accumulates on top of the previous result
+        capi.nnt_gemm(ctx.h, 0.5, 0, tdY.h, 1, tX.h, 1.0, tdW.h, 2, 0, None)
+        check(tdW.download(), 1.5 * dWr, "f32", "linear dW accumulate")
+        tdb = tiled.TiledTensor(ctx, "f32", (N_d,), (64,))
+        capi.nnt_bias_grad(ctx.h, tdY.h, tdb.h)
+        check(tdb.download(), dbr, "f32", "bias grad")
+        capi.nnt_bias_add(ctx.h, tb.h, tdY.h)
+        check(tdY.download(), D.bias_add(dY, b), dtype, "bias add")
+        st = ctx.stats()
+        assert st["tasks"] > 0 and (st["tasks"] > 8 if gran else st["tasks"] <= 8)
+
+
+@pytest.mark.parametrize("gran", GRANS)
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("tiles", [(64, 40, 2, 3), (32, 24, 1, 1)])
+def test_attention_products_with_causal_structure(mods, gran, dtype, tiles):
+    """scores, softmax, P V and the four backward products; tiles above the
+    diagonal are structural zeros."""
+    capi, tiled = mods
+    ti, ts, tb, tj = tiles
+    r = rng(2)
+    h, N_s, N_b, N_h = 64, 100, 2, 3
+    Q, K, V, dB = [quant(r.standard_normal((h, N_s, N_b, N_h)), dtype) for _ in range(4)]
+    sc = 1.0 / math.sqrt(h)
+    with tiled.Context(n_streams=4, granularity=gran) as ctx:
+        hb, sb = (ti, ts, tb, tj), (ts, ts, tb, tj)
+        absent = tiled.causal_absent(ts, ts, N_s)
+        tQ, tK, tV, tdB = [T(tiled, ctx, a, hb, dtype) for a in (Q, K, V, dB)]
+        tP = tiled.TiledTensor(ctx, dtype, (N_s, N_s, N_b, N_h), sb, absent)
+        tS = tiled.TiledTensor(ctx, "f32", (2, N_s, N_b, N_h), (2, ts, tb, tj))
+        capi.nnt_gemm(ctx.h, sc, 1, tK.h, 0, tQ.h, 0.0, tP.h, 1, 2, None)
+        capi.nnt_softmax_fwd(ctx.h, tP.h, tS.h, 1.0, 1)
+        A = D.attention_scores(K, Q)
+        if dtype == "bf16":
+            A = quant(A, dtype)           # the device stores the scores in bf16 before the softmax
+        Pref, tmax, den = D.softmax_fwd(A, causal=True)
+        P = tP.download().astype(np.float64)
+        check(P, Pref, dtype, "softmax(K^T Q)")
+        np.testing.assert_allclose(P.sum(axis=0), 1.0, atol=2e-2 if dtype == "bf16" else 1e-5)
+        stats = tS.download()
+        check(stats[0], tmax, dtype, "softmax max")
+        tB = tiled.TiledTensor(ctx, dtype, Q.shape, hb)
+        capi.nnt_gemm(ctx.h, 1.0, 0, tV.h, 0, tP.h, 0.0, tB.h, 1, 2, None)
+        check(tB.download(), D.attention_values(V, P), dtype, "V P")
+        # backward from the probabilities the device holds
+        tdV = tiled.TiledTensor(ctx, dtype, Q.shape, hb)
+        tdP = tiled.TiledTensor(ctx, dtype, (N_s, N_s, N_b, N_h), sb, absent)
+        capi.nnt_gemm(ctx.h, 1.0, 0, tdB.h, 1, tP.h, 0.0, tdV.h, 1, 2, None)
+        capi.nnt_gemm(ctx.h, 1.0, 1, tV.h, 0, tdB.h, 0.0, tdP.h, 1, 2, None)
+        dPdev = tdP.download().astype(np.float64)
+        capi.nnt_softmax_bwd(ctx.h, tP.h, tdP.h)
+        dA = tdP.download().astype(np.float64)
+        check(dA, D.softmax_bwd(P, dPdev), dtype, "softmax bwd")
+        tdQ, tdK = tiled.TiledTensor(ctx, dtype, Q.shape, hb), tiled.TiledTensor(ctx, dtype, Q.shape, hb)
+        capi.nnt_gemm(ctx.h, sc, 0, tK.h, 0, tdP.h, 0.0, tdQ.h, 1, 2, None)
+        capi.nnt_gemm(ctx.h, sc, 0, tQ.h, 1, tdP.h, 0.0, tdK.h, 1, 2, None)
+        Pj = P.transpose(3, 2, 0, 1)
+        dBj = dB.transpose(3, 2, 0, 1)
+        dVref = np.matmul(dBj, Pj.transpose(0, 1, 3, 2)).transpose(2, 3, 1, 0)
+        check(tdV.download(), dVref, dtype, "dV")
+        dAj = dA.transpose(3, 2, 0, 1)
+        dQref = sc * np.matmul(K.transpose(3, 2, 0, 1), dAj).transpose(2, 3, 1, 0)
+        dKref = sc * np.matmul(Q.transpose(3, 2, 0, 1), dAj.transpose(0, 1, 3, 2)).transpose(2, 3, 1, 0)
+        check(tdQ.download(), dQref, dtype, "dQ")
+        check(tdK.download(), dKref, dtype, "dK")
+
+
+def test_gemm_rejects_mismatched_tilings(mods):
+    capi, tiled = mods
+    with tiled.Context(n_streams=1) as ctx:
+        A = tiled.TiledTensor(ctx, "f32", (8, 6), (4, 3))
+        B = tiled.TiledTensor(ctx, "f32", (6, 5), (2, 5))       # contracted axis tiled 3 vs 2
+        Cc = tiled.TiledTensor(ctx, "f32", (8, 5), (4, 5))
+        assert capi.nnt_gemm.raw(ctx.h, 1.0, 0, A.h, 0, B.h, 0.0, Cc.h, 1, 0, None) == capi.NNT_EINVAL
+        assert b"contracted" in capi.nnt_last_error(ctx.h)
+        B2 = tiled.TiledTensor(ctx, "bf16", (6, 5), (3, 5))
+        assert capi.nnt_gemm.raw(ctx.h, 1.0, 0, A.h, 0, B2.h, 0.0, Cc.h, 1, 0, None) == capi.NNT_EDTYPE
+        # the context stays usable after an argument error
+        B3 = tiled.TiledTensor.from_numpy(ctx, np.ones((6, 5), np.float32), (3, 5))
+        A.upload(np.ones((8, 6), np.float32))
+        capi.nnt_gemm(ctx.h, 1.0, 0, A.h, 0, B3.h, 0.0, Cc.h, 1, 0, None)
+        assert np.all(Cc.download() == 6.0)
+
+
+# ------------------------------------------------------------------ memory-bound operations
+@pytest.mark.parametrize("gran", GRANS)
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape,base", [((768, 40, 3), (256, 16, 3)), ((100, 37, 2), (48, 10, 1)), ((1600, 12, 2), (400, 12, 2))])
+def test_layernorm_tensor(mods, gran, dtype, shape, base):
+    capi, tiled = mods
+    r = rng(3)
+    X = quant(r.standard_normal(shape) * 1.5 + 0.3, dtype)
+    dY = quant(r.standard_normal(shape), dtype)
+    dR = quant(r.standard_normal(shape), dtype)
+    gamma = (1 + 0.1 * r.standard_normal(shape[0])).astype(np.float32)
+    beta = (0.1 * r.standard_normal(shape[0])).astype(np.float32)
+    Yref, mean, rstd = D.layernorm_fwd(X, gamma, beta, 1e-5)
+    dXref, dgref, dbref = D.layernorm_bwd(X, gamma, mean, rstd, dY)
+    with tiled.Context(n_streams=4, granularity=gran) as ctx:
+        tX, tdY, tdR = [T(tiled, ctx, a, base, dtype) for a in (X, dY, dR)]
+        tg, tb = T(tiled, ctx, gamma, base[:1], "f32"), T(tiled, ctx, beta, base[:1], "f32")
+        tY = tiled.TiledTensor(ctx, dtype, shape, base)
+        tS = tiled.TiledTensor(ctx, "f32", (2,) + shape[1:], (2,) + base[1:])
+        capi.nnt_layernorm_fwd(ctx.h, tX.h, tg.h, tb.h, 1e-5, tY.h, tS.h)
+        check(tY.download(), Yref, dtype, "ln fwd")
+        s = tS.download()
+        check(s[0], mean, "f32", "ln mean")
+        check(s[1], rstd, "f32", "ln rstd")
+        tdX = tiled.TiledTensor(ctx, dtype, shape, base)
+        tdg, tdb = tiled.TiledTensor(ctx, "f32", shape[:1], base[:1]), tiled.TiledTensor(ctx, "f32", shape[:1], base[:1])
+        capi.nnt_layernorm_bwd(ctx.h, tX.h, tS.h, tg.h, tdY.h, tdR.h, tdX.h, tdg.h, tdb.h)
+        e = relerr(tdX.download(), dXref + dR)
+        assert e <= (2e-2 if dtype == "bf16" else 2e-5), e
+        check(tdg.download(), dgref, "f32", "ln dgamma")
+        check(tdb.download(), dbref, "f32", "ln dbeta")
+        capi.nnt_layernorm_bwd(ctx.h, tX.h, tS.h, tg.h, tdY.h, None, tdX.h, tdg.h, tdb.h)
+        e = relerr(tdX.download(), dXref)
+        assert e <= (2e-2 if dtype == "bf16" else 2e-5), e
+
+
+@pytest.mark.parametrize("gran", GRANS)
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_elementwise_tensor_ops(mods, gran, dtype):
+    capi, tiled = mods
+    r = rng(4)
+    shape, base = (200, 50, 3), (64, 24, 2)
+    X, Y = quant(r.standard_normal(shape) * 2, dtype), quant(r.standard_normal(shape), dtype)
+    with tiled.Context(n_streams=4, granularity=gran) as ctx:
+        tX, tY = T(tiled, ctx, X, base, dtype), T(tiled, ctx, Y, base, dtype)
+        capi.nnt_add(ctx.h, 1.0, tX.h, 1.0, tY.h)
+        check(tY.download(), X + Y, dtype, "add")
+        tG = tiled.TiledTensor(ctx, dtype, shape, base)
+        capi.nnt_gelu(ctx.h, 0, tX.h, tG.h)
+        check(tG.download(), D.gelu(X), dtype, "gelu")
+        tD = T(tiled, ctx, Y, base, dtype)
+        capi.nnt_gelu_bwd(ctx.h, 0, tX.h, tD.h, tD.h)            # in place
+        check(tD.download(), Y * D.gelu_grad(X), dtype, "gelu bwd in place")
+        capi.nnt_fill(ctx.h, -3.0, tG.h)
+        assert np.all(tG.download() == -3.0)
+        if dtype == "f32":
+            tL = tiled.TiledTensor(ctx, "bf16", shape, base)
+            capi.nnt_cast(ctx.h, tX.h, tL.h)
+            np.testing.assert_array_equal(tL.download(), D.round_to_bf16(X.astype(np.float32)))
+
+
+@pytest.mark.parametrize("gran", GRANS)
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("zb,pb", [((64, 16, 2), (32, 16, 2, 2)), ((100, 7, 1), (24, 5, 1, 1)), ((400, 30, 2), (64, 30, 2, 5))])
+def test_head_split_merge(mods, gran, dtype, zb, pb):
+    capi, tiled = mods
+    N_h, h, N_s, N_b = 5, 64, 30, 2
+    Z = quant(rng(5).standard_normal((3 * N_h * h, N_s, N_b)), dtype)
+    with tiled.Context(n_streams=4, granularity=gran) as ctx:
+        tZ = T(tiled, ctx, Z, zb, dtype)
+        parts = [tiled.TiledTensor(ctx, dtype, (h, N_s, N_b, N_h), pb) for _ in range(3)]
+        arr = capi.ptr_array([p.h.value for p in parts])
+        capi.nnt_head_split(ctx.h, tZ.h, 3, arr)
+        for got, ref in zip(parts, D.split_heads(Z, N_h, 3)):
+            np.testing.assert_array_equal(got.download(), ref.astype(np.float32))
+        tZ2 = tiled.TiledTensor(ctx, dtype, Z.shape, zb)
+        capi.nnt_head_merge(ctx.h, 3, arr, tZ2.h)
+        np.testing.assert_array_equal(tZ2.download(), Z.astype(np.float32))
+
+
+@pytest.mark.parametrize("gran", GRANS)
+@pytest.mark.parametrize("lowp", [False, True])
+def test_adam_tensor(mods, gran, lowp):
+    capi, tiled = mods
+    r = rng(6)
+    shape, base = (300, 130), (128, 64)
+    p, g = r.standard_normal(shape).astype(np.float32), r.standard_normal(shape).astype(np.float32)
+    with tiled.Context(n_streams=4, granularity=gran) as ctx:
+        tp, tg = T(tiled, ctx, p, base, "f32"), T(tiled, ctx, g, base, "f32")
+        tm, tv = tiled.TiledTensor.zeros(ctx, shape, base), tiled.TiledTensor.zeros(ctx, shape, base)
+        tl = tiled.TiledTensor(ctx, "bf16", shape, base) if lowp else None
+        cfg = capi.nnt_adam_cfg(1e-3, 0.9, 0.999, 1e-8, 0.0)
+        pr, mr, vr = p.astype(np.float64), 0.0, 0.0
+        for step in (1, 2):
+            capi.nnt_adam_step(ctx.h, C.byref(cfg), step, tg.h, tp.h, tm.h, tv.h, tl.h if lowp else None)
+            pr, mr, vr = D.adam_step(pr, g, mr, vr, step)
+        check(tp.download(), pr, "f32", "adam p")
+        check(tm.download(), mr, "f32", "adam m")
+        check(tv.download(), vr, "f32", "adam v")
+        if lowp:
+            np.testing.assert_array_equal(tl.download(), D.round_to_bf16(tp.download()))
+
+
+# ------------------------------------------------------------------ executor
+def test_executor_orders_dependent_tasks_across_streams(mods):
+    """A chain y <- y + x repeated many times on 8 streams must give the serial
+    result; independent chains may overlap."""
+    capi, tiled = mods
+    shape, base = (256, 64), (64, 16)
+    x = rng(7).standard_normal(shape).astype(np.float32)
+    results = {}
+    for name, kw in (("serial", dict(n_streams=1, serial=True)), ("streams8_tiles", dict(n_streams=8, granularity=1)),
+                     ("streams8_ops", dict(n_streams=8, granularity=0))):
+        with tiled.Context(**kw) as ctx:
+            tx = T(tiled, ctx, x, base, "f32")
+            ys = [tiled.TiledTensor.zeros(ctx, shape, base) for _ in range(3)]
+            for it in range(20):
+                for k, ty in enumerate(ys):
+                    capi.nnt_add(ctx.h, 1.0 + k, tx.h, 1.0, ty.h)         # RAW + WAW chain per y
+                capi.nnt_add(ctx.h, 1.0, ys[0].h, 0.5, ys[1].h)            # cross-chain dependency
+            results[name] = [t.download() for t in ys]
+            st = ctx.stats()
+            if name == "streams8_tiles":
+                assert st["event_waits"] > 0 and st["tasks"] == 20 * 4 * 16
+    for name in ("streams8_tiles", "streams8_ops"):
+        for a, b in zip(results[name], results["serial"]):
+            np.testing.assert_array_equal(a, b)
+
+
+def test_graph_capture_replays_task_flow(mods):
+    capi, tiled = mods
+    r = rng(8)
+    A, B = r.standard_normal((96, 80)).astype(np.float32), r.standard_normal((80, 70)).astype(np.float32)
+    with tiled.Context(n_streams=4) as ctx:
+        tA, tB = T(tiled, ctx, A, (32, 40), "f32"), T(tiled, ctx, B, (40, 35), "f32")
+        tC, tG = tiled.TiledTensor(ctx, "f32", (96, 70), (32, 35)), tiled.TiledTensor(ctx, "f32", (96, 70), (32, 35))
+
+        def flow():
+            capi.nnt_gemm(ctx.h, 1.0, 0, tA.h, 0, tB.h, 0.0, tC.h, 1, 0, None)
+            capi.nnt_gelu(ctx.h, 0, tC.h, tG.h)
+            capi.nnt_add(ctx.h, 1.0, tC.h, 1.0, tG.h)
+        flow()                                     # builds the plans
+        want = tG.download().copy()
+        g = C.c_void_p()
+        capi.nnt_capture_begin(ctx.h)
+        flow()
+        capi.nnt_capture_end(ctx.h, C.byref(g))
+        for rep in range(3):
+            capi.nnt_fill(ctx.h, 0.0, tG.h)        # eager work between replays
+            capi.nnt_graph_launch(g)
+            np.testing.assert_array_equal(tG.download(), want)
+        capi.nnt_graph_destroy(g)
+        ref = A.astype(np.float64) @ B.astype(np.float64)
+        check(want, ref + D.gelu(ref), "f32", "captured flow")
