@@ -265,8 +265,8 @@ NNT_API int32_t nnt_tile_softmax_bwd_apply(void* stream, int32_t dtype, int64_t 
  * Kingma & Ba with bias correction, eps outside the square root; weight_decay
  * > 0 gives the decoupled AdamW form).  g, p, m, v are fp32; p_lowp, when not
  * NULL, receives the bf16 copy of the updated parameters. */
-NNT_API int32_t nnt_tile_adam(void* stream, int64_t n, int32_t step, float lr, float beta1, float beta2,
-                      float eps, float weight_decay, const float* g, float* p, float* m, float* v,
+NNT_API int32_t nnt_tile_adam(void* stream, int64_t n, int32_t step, double lr, double beta1, double beta2,
+                      double eps, double weight_decay, const float* g, float* p, float* m, float* v,
                       void* p_lowp);
 
 /* ------------------------------------------------------------------------- */
@@ -314,7 +314,7 @@ NNT_API int32_t nnt_head_split(nnt_ctx* ctx, nnt_tensor* Z, int32_t n_parts, nnt
 NNT_API int32_t nnt_head_merge(nnt_ctx* ctx, int32_t n_parts, nnt_tensor* const* parts, nnt_tensor* Z);
 
 typedef struct nnt_adam_cfg {
-    float lr, beta1, beta2, eps, weight_decay;
+    double lr, beta1, beta2, eps, weight_decay;   /* doubles: 1 - beta is formed before rounding to fp32 */
 } nnt_adam_cfg;
 /* G, P, M, V: fp32 tensors tiled alike; P_lowp: bf16 tensor tiled alike or NULL. */
 NNT_API int32_t nnt_adam_step(nnt_ctx* ctx, const nnt_adam_cfg* cfg, int32_t step, nnt_tensor* G, nnt_tensor* P,

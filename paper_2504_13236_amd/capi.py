@@ -50,8 +50,8 @@ class nnt_profile_entry(C.Structure):
 
 
 class nnt_adam_cfg(C.Structure):
-    _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
-                ("weight_decay", C.c_float)]
+    _fields_ = [("lr", C.c_double), ("beta1", C.c_double), ("beta2", C.c_double), ("eps", C.c_double),
+                ("weight_decay", C.c_double)]
 
 
 class nnt_gpt2_block_cfg(C.Structure):
@@ -73,6 +73,7 @@ lib = C.CDLL(LIB_PATH)
 
 _p, _i32, _i64, _f, _pp = C.c_void_p, C.c_int32, C.c_int64, C.c_float, C.POINTER(C.c_void_p)
 _pi64 = C.POINTER(C.c_int64)
+_d = C.c_double
 
 # name -> (restype, argtypes).  Order and types follow include/nntile_mi.h.
 PROTOTYPES = {
@@ -119,7 +120,7 @@ PROTOTYPES = {
     "nnt_tile_softmax_apply": (_i32, [_p, _i32, _i64, _i64, _i64, _i64, _i64, _i32, _f, _p, _p]),
     "nnt_tile_softmax_bwd_dot": (_i32, [_p, _i32, _i64, _i64, _i64, _p, _p, _p, _i32]),
     "nnt_tile_softmax_bwd_apply": (_i32, [_p, _i32, _i64, _i64, _i64, _p, _p, _p]),
-    "nnt_tile_adam": (_i32, [_p, _i64, _i32, _f, _f, _f, _f, _f, _p, _p, _p, _p, _p]),
+    "nnt_tile_adam": (_i32, [_p, _i64, _i32, _d, _d, _d, _d, _d, _p, _p, _p, _p, _p]),
     "nnt_gemm": (_i32, [_p, _f, _i32, _p, _i32, _p, _f, _p, _i32, _i32, _p]),
     "nnt_fill": (_i32, [_p, _f, _p]),
     "nnt_add": (_i32, [_p, _f, _p, _f, _p]),

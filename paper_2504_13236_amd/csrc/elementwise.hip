@@ -239,7 +239,7 @@ struct BiasAddF {
 struct AdamF {
     static constexpr int V = 4;
     Operand g, p, m, v, lp;
-    float lr, beta1, beta2, eps, wd, inv_bc1, inv_bc2;
+    float lr, beta1, beta2, omb1, omb2, eps, wd, inv_bc1, inv_bc2;   // omb = 1 - beta, formed in double on the host
     struct Ctx { const float* g; float* p; float* m; float* v; bf16_t* lp; };
     __device__ bool setup(Ctx& c, const EwGeom&, int tile) const {
         c.g = pick<const float>(g.table, g.single, tile);
@@ -257,8 +257,8 @@ struct AdamF {
         ldv<W>(c.v + i, vv);
 #pragma unroll
         for (int j = 0; j < W; j++) {
-            mm[j] = beta1 * mm[j] + (1.f - beta1) * gg[j];
-            vv[j] = beta2 * vv[j] + (1.f - beta2) * gg[j] * gg[j];
+            mm[j] = beta1 * mm[j] + omb1 * gg[j];
+            vv[j] = beta2 * vv[j] + omb2 * gg[j] * gg[j];
             const float mhat = mm[j] * inv_bc1;
             const float vhat = vv[j] * inv_bc2;
             pp[j] = pp[j] - lr * wd * pp[j] - lr * mhat / (sqrtf(vhat) + eps);
@@ -483,16 +483,17 @@ int32_t nnt_tile_gelu_bwd(void* stream, int32_t dtype, int32_t variant, int64_t 
     return launch_ew((hipStream_t)stream, GeluBwdF<bf16_t>{ptr(x), ptr(dy), ptr(dx), variant}, single_geom(n), n, 1, vec);
 }
 
-static AdamF make_adam(int32_t step, float lr, float b1, float b2, float eps, float wd) {
+static AdamF make_adam(int32_t step, double lr, double b1, double b2, double eps, double wd) {
     AdamF f = {};
-    f.lr = lr; f.beta1 = b1; f.beta2 = b2; f.eps = eps; f.wd = wd;
+    f.lr = (float)lr; f.beta1 = (float)b1; f.beta2 = (float)b2; f.eps = (float)eps; f.wd = (float)wd;
+    f.omb1 = (float)(1.0 - b1); f.omb2 = (float)(1.0 - b2);
     f.inv_bc1 = (float)(1.0 / (1.0 - std::pow((double)b1, (double)step)));
     f.inv_bc2 = (float)(1.0 / (1.0 - std::pow((double)b2, (double)step)));
     return f;
 }
 
-int32_t nnt_tile_adam(void* stream, int64_t n, int32_t step, float lr, float beta1, float beta2, float eps,
-                      float weight_decay, const float* g, float* p, float* m, float* v, void* p_lowp) {
+int32_t nnt_tile_adam(void* stream, int64_t n, int32_t step, double lr, double beta1, double beta2, double eps,
+                      double weight_decay, const float* g, float* p, float* m, float* v, void* p_lowp) {
     if (n < 0 || step < 1 || (n > 0 && (!g || !p || !m || !v))) return NNT_EINVAL;
     AdamF f = make_adam(step, lr, beta1, beta2, eps, weight_decay);
     f.g = ptr(g); f.p = ptr(p); f.m = ptr(m); f.v = ptr(v); f.lp = ptr(p_lowp);
