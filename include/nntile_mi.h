@@ -132,8 +132,8 @@ NNT_API int32_t nnt_profile_read(nnt_ctx* ctx, nnt_profile_entry* out, int32_t c
 /* Stream capture of the task flow into a HIP graph (section 2: the graph of a
  * training iteration repeats, so it can be built once and replayed).  Between
  * begin and end, tensor-level calls are recorded instead of run; every plan they
- * need must already exist (run the same calls once before capturing).  The graph
- * replays on stream 0. */
+ * need must already exist (run the same calls once before capturing).  Captured
+ * tasks are spread over at most two streams.  The graph replays on stream 0. */
 typedef struct nnt_graph nnt_graph;
 NNT_API int32_t nnt_capture_begin(nnt_ctx* ctx);
 NNT_API int32_t nnt_capture_end(nnt_ctx* ctx, nnt_graph** out);

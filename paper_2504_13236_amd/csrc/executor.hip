@@ -56,7 +56,9 @@ static int32_t sync_all(nnt_ctx* ctx) {
 int32_t submit(nnt_ctx* ctx, const std::vector<Access>& acc,
                const std::function<int32_t(hipStream_t)>& launch, int n_launches) {
     NNT_CHECK_CTX(ctx);
-    const int ns = ctx->n_streams;
+    // While a capture is open only streams 0 and 1 take tasks: ending a capture in which two forked
+    // streams wait on each other's events has crashed inside the HIP runtime on this ROCm release.
+    const int ns = ctx->capturing ? std::min(ctx->n_streams, 2) : ctx->n_streams;
     uint64_t need[kMaxStreams] = {0, 0, 0, 0, 0, 0, 0, 0};
     for (const Access& a : acc) {
         for (int64_t i = 0; i < a.count; i++) {
@@ -319,8 +321,8 @@ int32_t nnt_capture_begin(nnt_ctx* ctx) {
         rc = get_event(ctx, &ev);
         if (rc != NNT_OK) return rc;
         NNT_HIP(ctx, hipEventRecord(ev, ctx->streams[0]));
-        for (int s = 1; s < ctx->n_streams; s++) NNT_HIP(ctx, hipStreamWaitEvent(ctx->streams[s], ev, 0));
-        ctx->event_pool.push_back(ev);
+        for (int s = 1; s < std::min(ctx->n_streams, 2); s++) NNT_HIP(ctx, hipStreamWaitEvent(ctx->streams[s], ev, 0));
+        ctx->capture_events.push_back(ev);      // no event is recorded twice inside one capture
     }
     return NNT_OK;
 }
@@ -329,22 +331,28 @@ int32_t nnt_capture_end(nnt_ctx* ctx, nnt_graph** out) {
     if (!ctx || !out) return NNT_EINVAL;
     if (!ctx->capturing) return fail(ctx, NNT_ESTATE, "no capture open");
     *out = nullptr;
-    // join: stream 0 waits for the tails of all other streams
-    for (int s = 1; s < ctx->n_streams; s++) {
+    // join: stream 0 waits for the tail of the other capturing stream
+    for (int s = 1; s < std::min(ctx->n_streams, 2); s++) {
         hipEvent_t ev;
         int32_t rc = get_event(ctx, &ev);
         if (rc != NNT_OK) return rc;
         NNT_HIP(ctx, hipEventRecord(ev, ctx->streams[s]));
         NNT_HIP(ctx, hipStreamWaitEvent(ctx->streams[0], ev, 0));
-        ctx->event_pool.push_back(ev);
+        ctx->capture_events.push_back(ev);
     }
     hipGraph_t graph;
     ctx->capturing = false;
+    const bool trace = getenv("NNT_TRACE") != nullptr;
+    if (trace) fprintf(stderr, "nnt: capture_end: joined, ending capture\n");
     NNT_HIP(ctx, hipStreamEndCapture(ctx->streams[0], &graph));
+    if (trace) fprintf(stderr, "nnt: capture_end: capture ended, instantiating\n");
     // the recorded tasks have not run: their events mean nothing outside the graph
     mark_all_synced(ctx);
+    for (hipEvent_t e : ctx->capture_events) ctx->event_pool.push_back(e);
+    ctx->capture_events.clear();
     hipGraphExec_t exec;
     NNT_HIP(ctx, hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0));
+    if (trace) fprintf(stderr, "nnt: capture_end: instantiated\n");
     nnt_graph* g = new (std::nothrow) nnt_graph{ctx, graph, exec};
     if (!g) return NNT_ENOMEM;
     *out = g;

@@ -239,6 +239,7 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
         if (A->dtype == NNT_F32) l << "gemm_f32_kernel<" << tf[P->akf] << ", " << tf[P->bkf] << ", " << shape[P->cfg == kCfgSquare ? 1 : P->cfg] << ">";
         else l << "gemm_bf16_kernel<" << (C->dtype == NNT_F32 ? "float" : "unsigned short") << ", " << tf[P->akf] << ", " << tf[P->bkf]
                << ", " << shape[P->cfg] << ", 32>";
+        if (nbat > 0) l << " batched";     // per-head attention products: short contractions, memory-leaning
         P->label = l.str();
     }
     // Workgroup order inside a task: m index fastest, so that workgroups in flight

@@ -110,6 +110,7 @@ struct nnt_ctx {
     uint64_t waited[nnt::kMaxStreams][nnt::kMaxStreams];  // waited[s][d]: s already waits for d up to this seq
     std::vector<hipEvent_t> events[nnt::kMaxStreams];     // events[s][seq - synced_seq[s] - 1]
     std::vector<hipEvent_t> event_pool;
+    std::vector<hipEvent_t> capture_events;               // fork / join events of the open capture
     int rr = 0;                      // round-robin cursor
     bool capturing = false;
     nnt_exec_stats stats = {0, 0, 0, 0};

@@ -356,15 +356,31 @@ __global__ void __launch_bounds__(256) rowsum_stage1(RowsumGeom g, float* part) 
 // out[r] = (accumulate ? out[r] : 0) + sum_s part[s][r]; the output is a 1-axis tiled tensor or a plain vector.
 __global__ void __launch_bounds__(256) rowsum_stage2(const float* part, int64_t nslots, int64_t rows_total,
                                                       void* const* otab, float* o1, int base0, int accumulate) {
-    const int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (r >= rows_total) return;
-    float s = 0.f;
-    for (int64_t k = 0; k < nslots; k++) s += part[k * rows_total + r];
-    float* o = otab ? static_cast<float*>(otab[r / base0]) + (r % base0) : o1 + r;
-    *o = accumulate ? *o + s : s;
+    // 64 rows per block; the four wavefronts take every fourth partial row, then combine through LDS
+    __shared__ float red[4][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t r = (int64_t)blockIdx.x * 64 + lane;
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    if (r < rows_total) {
+        int64_t k = wave;
+        for (; k + 12 < nslots; k += 16) {
+            s0 += part[k * rows_total + r];
+            s1 += part[(k + 4) * rows_total + r];
+            s2 += part[(k + 8) * rows_total + r];
+            s3 += part[(k + 12) * rows_total + r];
+        }
+        for (; k < nslots; k += 4) s0 += part[k * rows_total + r];
+    }
+    red[wave][lane] = (s0 + s1) + (s2 + s3);
+    __syncthreads();
+    if (wave == 0 && r < rows_total) {
+        const float s = (red[0][lane] + red[1][lane]) + (red[2][lane] + red[3][lane]);
+        float* o = otab ? static_cast<float*>(otab[r / base0]) + (r % base0) : o1 + r;
+        *o = accumulate ? *o + s : s;
+    }
 }
 
-constexpr int kColsPerBlock = 64;
+constexpr int kColsPerBlock = 128;
 
 int64_t scratch_elems(int64_t m, int64_t n, int mode) { return ((n + kColsPerBlock - 1) / kColsPerBlock) * m * (mode ? 2 : 1); }
 
@@ -395,7 +411,7 @@ int32_t rowsum_single(hipStream_t st, int dtype, int mode, int64_t m, int64_t n,
     if (dtype == NNT_F32) rc = mode ? launch_rowsum_t<float, 1>(st, g, vv, v1, 1, vec, scratch) : launch_rowsum_t<float, 0>(st, g, vv, v1, 1, vec, scratch);
     else rc = mode ? launch_rowsum_t<bf16_t, 1>(st, g, vv, v1, 1, vec, scratch) : launch_rowsum_t<bf16_t, 0>(st, g, vv, v1, 1, vec, scratch);
     if (rc != NNT_OK) return rc;
-    const unsigned blocks = (unsigned)((m + 255) / 256);
+    const unsigned blocks = (unsigned)((m + 63) / 64);
     hipLaunchKernelGGL(rowsum_stage2, dim3(blocks), dim3(256), 0, st, scratch, (int64_t)g.splits, m, nullptr, out0, 1, accumulate);
     if (mode)
         hipLaunchKernelGGL(rowsum_stage2, dim3(blocks), dim3(256), 0, st, scratch + (int64_t)g.splits * m, (int64_t)g.splits, m,
@@ -442,7 +458,7 @@ int32_t rowsum_tensor(nnt_ctx* ctx, int mode, nnt_tensor* dY, nnt_tensor* X, nnt
         if (dtype == NNT_F32) r = mode ? launch_rowsum_t<float, 1>(st, g, vv, v1, ntiles, vec, scratch) : launch_rowsum_t<float, 0>(st, g, vv, v1, ntiles, vec, scratch);
         else r = mode ? launch_rowsum_t<bf16_t, 1>(st, g, vv, v1, ntiles, vec, scratch) : launch_rowsum_t<bf16_t, 0>(st, g, vv, v1, ntiles, vec, scratch);
         if (r != NNT_OK) return r;
-        const unsigned blocks = (unsigned)((rows + 255) / 256);
+        const unsigned blocks = (unsigned)((rows + 63) / 64);
         hipLaunchKernelGGL(rowsum_stage2, dim3(blocks), dim3(256), 0, st, scratch, nslots, rows, o0, nullptr, base0, 0);
         if (mode)
             hipLaunchKernelGGL(rowsum_stage2, dim3(blocks), dim3(256), 0, st, scratch + nslots * rows, nslots, rows, o1, nullptr, base0, 0);

@@ -82,7 +82,8 @@ def test_argument_validation_without_device(capi):
     assert capi.nnt_tile_gemm.raw(None, 0, 0, 0, 0, 0, 4, 4, 1, 1.0, None, 4, 16, None, 4, 16, 0.0, None, 4, 16) == capi.NNT_OK
     assert capi.nnt_tile_gelu.raw(None, 0, 5, 8, None, None) == capi.NNT_EINVAL
     assert capi.nnt_tile_adam.raw(None, 8, 0, 1e-3, 0.9, 0.999, 1e-8, 0.0, None, None, None, None, None) == capi.NNT_EINVAL
-    assert capi.nnt_tile_bias_grad_scratch(768, 2048) >= 768 * (2048 // 64)
+    assert capi.nnt_tile_bias_grad_scratch(768, 2048) >= 768
+    assert capi.nnt_tile_ln_bwd_params_scratch(768, 2048) == 2 * capi.nnt_tile_bias_grad_scratch(768, 2048)
     assert capi.nnt_wait.raw(None) == capi.NNT_EINVAL
     cfg = capi.nnt_gpt2_block_cfg()
     info = capi.nnt_slot_info()
