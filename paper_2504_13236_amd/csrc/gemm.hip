@@ -9,6 +9,44 @@
 
 namespace nnt {
 
+// One C tile of a split product: where its k-slices lie and where the result goes.
+struct SplitReduce {
+    void* C;
+    const float* bias;
+    const float* ws;        // slice s of element i at ws[s * count + i]
+    int64_t count;          // m * n * batch
+    int32_t m, nsplit;
+};
+
+template <typename TO>
+__global__ void __launch_bounds__(256) splitk_reduce(const SplitReduce* tab, float alpha, float beta) {
+    const SplitReduce t = tab[blockIdx.y];
+    const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (i >= t.count) return;               // count is a multiple of 4 only if m is; handled below
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    const int n = (int)((t.count - i) < 4 ? (t.count - i) : 4);
+    for (int s = 0; s < t.nsplit; s++) {
+        const float* p = t.ws + (int64_t)s * t.count + i;
+        if (n == 4 && (((uintptr_t)p & 15) == 0)) {
+            const float4 v = *reinterpret_cast<const float4*>(p);
+            acc[0] += v.x; acc[1] += v.y; acc[2] += v.z; acc[3] += v.w;
+        } else {
+            for (int j = 0; j < n; j++) acc[j] += p[j];
+        }
+    }
+    TO* c = static_cast<TO*>(t.C) + i;
+    for (int j = 0; j < n; j++) {
+        float v = alpha * acc[j];
+        if (t.bias) v += t.bias[(i + j) % t.m];
+        if (beta != 0.f) {
+            if constexpr (sizeof(TO) == 4) v += beta * (float)c[j];
+            else v += beta * __uint_as_float((uint32_t)c[j] << 16);
+        }
+        if constexpr (sizeof(TO) == 4) c[j] = v;
+        else { const __bf16 h = (__bf16)v; c[j] = __builtin_bit_cast(uint16_t, h); }
+    }
+}
+
 struct GemmPlan {
     nnt_ctx* ctx = nullptr;
     uint64_t ids[4] = {0, 0, 0, 0};            // tensors the tables point into (A, B, C, bias)
@@ -26,10 +64,22 @@ struct GemmPlan {
     GemmTask* d_tasks = nullptr;
     GemmChunk* d_chunks = nullptr;
     GemmWg* d_wgs = nullptr;
+    // Split form (one launch per operation only): every task is cut into `splits` k-slices that
+    // write raw fp32 sums to a scratch tile each; a second kernel adds the slices in a fixed order
+    // and applies alpha, beta and the bias.  Used when the unsplit grid cannot fill the chip.
+    int splits = 1;
+    int64_t sk_nwg = 0;
+    GemmTask* d_sk_tasks = nullptr;
+    GemmChunk* d_sk_chunks = nullptr;
+    GemmWg* d_sk_wgs = nullptr;
+    SplitReduce* d_sk_red = nullptr;
+    float* d_ws = nullptr;
+    int64_t sk_max_count = 0;
+    TileDep ws_dep;
     ~GemmPlan() {
-        if (d_tasks) (void)hipFree(d_tasks);
-        if (d_chunks) (void)hipFree(d_chunks);
-        if (d_wgs) (void)hipFree(d_wgs);
+        for (void* p : {(void*)d_tasks, (void*)d_chunks, (void*)d_wgs, (void*)d_sk_tasks, (void*)d_sk_chunks, (void*)d_sk_wgs,
+                        (void*)d_sk_red, (void*)d_ws})
+            if (p) (void)hipFree(p);
     }
 };
 
@@ -81,6 +131,7 @@ extern "C" int32_t nnt_tile_gemm(void* stream, int32_t dtype_in, int32_t dtype_o
     const int elem = bf ? 2 : 4;
     GemmArgs g = {};
     g.wgs = nullptr;
+    g.one_task = GemmTask{};
     g.one_task.C = C;
     g.one_task.bias = nullptr;
     g.one_task.ldc = ldc;
@@ -182,7 +233,7 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
         const int64_t m = prod_extent(A, ac, ax.a_free), n = prod_extent(B, bc, ax.b_free);
         const int64_t batch = prod_extent(A, ac, ax.a_bat);
         if (m > INT32_MAX || n > INT32_MAX) return fail(ctx, NNT_EINVAL, "nnt_gemm: tile too large");
-        GemmTask t;
+        GemmTask t = {};
         t.C = C->tiles[ci];
         t.bias = bias ? static_cast<const float*>(bias->tiles[cc[0]]) : nullptr;
         if (bias && !t.bias) return fail(ctx, NNT_EINVAL, "nnt_gemm: bias tile missing");
@@ -255,6 +306,90 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
     P->task_wg0.push_back((int64_t)P->wgs.size());
     if (P->wgs.size() > (size_t)INT32_MAX) return fail(ctx, NNT_EINVAL, "nnt_gemm: too many workgroups");
 
+    // ---- split form
+    const int64_t W = (int64_t)P->wgs.size();
+    const int kstep = 64;
+    int64_t kmin = INT64_MAX;
+    std::vector<int64_t> ktot(P->tasks.size(), 0);
+    for (size_t ti = 0; ti < P->tasks.size(); ti++) {
+        for (int32_t q = P->tasks[ti].chunk0; q < P->tasks[ti].chunk0 + P->tasks[ti].nchunk; q++) ktot[ti] += P->chunks[q].k;
+        kmin = std::min(kmin, ktot[ti]);
+    }
+    int S = 1;
+    if (W > 0 && W < 480 && nbat == 0) {
+        const int cands[] = {2, 3, 4, 6, 8, 12, 16};
+        int best = 1;
+        for (int c : cands) {
+            if (kmin / c < 256) break;
+            best = c;
+            const double eff = (double)(W * c) / (double)(((W * c + 255) / 256) * 256);
+            if (W * c >= 480 && eff >= 0.8) break;
+        }
+        S = best;
+    }
+    P->splits = S;
+    if (S > 1) {
+        std::vector<GemmTask> tasks;
+        std::vector<GemmChunk> chunks;
+        std::vector<GemmWg> wgs;
+        std::vector<SplitReduce> red;
+        int64_t ws_elems = 0;
+        for (size_t ti = 0; ti < P->tasks.size(); ti++) ws_elems += (int64_t)S * geom[ti].m * geom[ti].n * geom[ti].batch;
+        NNT_HIP(ctx, hipMalloc((void**)&P->d_ws, ws_elems * sizeof(float)));
+        int64_t ws_off = 0;
+        for (size_t ti = 0; ti < P->tasks.size(); ti++) {
+            const GemmTask& t0 = P->tasks[ti];
+            const int64_t count = geom[ti].m * geom[ti].n * geom[ti].batch;
+            const int64_t part = ((ktot[ti] + S - 1) / S + kstep - 1) / kstep * kstep;
+            SplitReduce r;
+            r.C = t0.C; r.bias = t0.bias; r.ws = P->d_ws + ws_off; r.count = count; r.m = t0.m; r.nsplit = S;
+            red.push_back(r);
+            P->sk_max_count = std::max(P->sk_max_count, count);
+            int32_t q = t0.chunk0;
+            int64_t used = 0;                       // k already consumed of chunk q
+            for (int sidx = 0; sidx < S; sidx++) {
+                GemmTask t = t0;
+                t.C = P->d_ws + ws_off + (int64_t)sidx * count;
+                t.bias = nullptr;
+                t.partial = 1;
+                t.chunk0 = (int32_t)chunks.size();
+                int64_t want = part;
+                while (want > 0 && q < t0.chunk0 + t0.nchunk) {
+                    const GemmChunk& c0 = P->chunks[q];
+                    const int64_t take = std::min<int64_t>(want, c0.k - used);
+                    GemmChunk c = c0;
+                    c.A = static_cast<const char*>(c0.A) + used * (P->akf ? 1 : c0.lda) * elem;
+                    c.B = static_cast<const char*>(c0.B) + used * (P->bkf ? 1 : c0.ldb) * elem;
+                    c.k = (int32_t)take;
+                    c.vec_ok = vec_flag(c.A, c.lda, c.strideA, elem) | (vec_flag(c.B, c.ldb, c.strideB, elem) << 1);
+                    chunks.push_back(c);
+                    want -= take;
+                    used += take;
+                    if (used == c0.k) { q++; used = 0; }
+                }
+                t.nchunk = (int32_t)chunks.size() - t.chunk0;
+                const int32_t tid = (int32_t)tasks.size();
+                tasks.push_back(t);
+                const int64_t gm = (geom[ti].m + bm - 1) / bm, gn = (geom[ti].n + bn - 1) / bn;
+                for (int64_t b = 0; b < geom[ti].batch; b++)
+                    for (int64_t j = 0; j < gn; j++)
+                        for (int64_t i = 0; i < gm; i++)
+                            wgs.push_back(GemmWg{tid, (int32_t)(i * bm), (int32_t)(j * bn), (int32_t)b});
+            }
+            ws_off += (int64_t)S * count;
+        }
+        P->sk_nwg = (int64_t)wgs.size();
+        auto up2 = [&](void** d, const void* h, size_t bytes) -> hipError_t {
+            hipError_t e = hipMalloc(d, bytes);
+            if (e != hipSuccess) return e;
+            return hipMemcpy(*d, h, bytes, hipMemcpyHostToDevice);
+        };
+        NNT_HIP(ctx, up2((void**)&P->d_sk_tasks, tasks.data(), tasks.size() * sizeof(GemmTask)));
+        NNT_HIP(ctx, up2((void**)&P->d_sk_chunks, chunks.data(), chunks.size() * sizeof(GemmChunk)));
+        NNT_HIP(ctx, up2((void**)&P->d_sk_wgs, wgs.data(), wgs.size() * sizeof(GemmWg)));
+        NNT_HIP(ctx, up2((void**)&P->d_sk_red, red.data(), red.size() * sizeof(SplitReduce)));
+    }
+
     auto up = [&](void** d, const void* h, size_t bytes) -> hipError_t {
         if (bytes == 0) return hipSuccess;
         hipError_t e = hipMalloc(d, bytes);
@@ -302,6 +437,21 @@ extern "C" int32_t nnt_gemm(nnt_ctx* ctx, float alpha, int32_t opA, nnt_tensor* 
         g.wgs = P->d_wgs;
         const int64_t nwg = (int64_t)P->wgs.size();
         if (nwg == 0) return NNT_OK;
+        if (P->splits > 1) {
+            acc.push_back(Access{&P->ws_dep, 1, kReadWrite});
+            g.tasks = P->d_sk_tasks;
+            g.chunks = P->d_sk_chunks;
+            g.wgs = P->d_sk_wgs;
+            const int64_t sk_nwg = P->sk_nwg, ntasks = (int64_t)P->tasks.size(), mx = P->sk_max_count;
+            return submit(ctx, acc, [=](hipStream_t st) {
+                int32_t rc = launch_any(st, P->dtype_in, P->dtype_out, P->akf, P->bkf, P->cfg, g, sk_nwg);
+                if (rc != NNT_OK) return rc;
+                const dim3 grid((unsigned)((mx + 1023) / 1024), (unsigned)ntasks), block(256);
+                if (P->dtype_out == NNT_F32) hipLaunchKernelGGL((splitk_reduce<float>), grid, block, 0, st, P->d_sk_red, alpha, beta);
+                else hipLaunchKernelGGL((splitk_reduce<uint16_t>), grid, block, 0, st, P->d_sk_red, alpha, beta);
+                return hipGetLastError() == hipSuccess ? (int32_t)NNT_OK : (int32_t)NNT_EHIP;
+            }, 2);
+        }
         return submit(ctx, acc, [=](hipStream_t st) {
             return launch_any(st, P->dtype_in, P->dtype_out, P->akf, P->bkf, P->cfg, g, nwg);
         });

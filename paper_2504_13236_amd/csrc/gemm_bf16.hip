@@ -235,8 +235,26 @@ __global__ void __launch_bounds__(256) gemm_bf16_kernel(const GemmArgs g) {
         }
     }
 
-    TO* C = static_cast<TO*>(task.C) + (int64_t)bat * task.strideC;
     const float alpha = g.alpha, beta = g.beta;
+    if (task.partial) {
+        // one k-slice of a split product: raw fp32 sums into the scratch tile
+        float* Cp = static_cast<float*>(task.C) + (int64_t)bat * task.strideC;
+#pragma unroll
+        for (int bm = 0; bm < WMB; bm++) {
+            const int gm = m0 + (wm * WMB + bm) * 32 + r32;
+            if (gm >= task.m) continue;
+#pragma unroll
+            for (int bn = 0; bn < WNB; bn++) {
+#pragma unroll
+                for (int i = 0; i < 16; i++) {
+                    const int gn = n0 + (wn * WNB + bn) * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
+                    if (gn < task.n) Cp[gm + (int64_t)gn * task.ldc] = acc[bn][bm][i];
+                }
+            }
+        }
+        return;
+    }
+    TO* C = static_cast<TO*>(task.C) + (int64_t)bat * task.strideC;
 #pragma unroll
     for (int bm = 0; bm < WMB; bm++) {
         const int gm = m0 + (wm * WMB + bm) * 32 + r32;

@@ -18,6 +18,8 @@ struct GemmTask {
     int64_t ldc, strideC;   // elements
     int32_t m, n;
     int32_t chunk0, nchunk;
+    int32_t partial;        // 1: one k-slice of a split product; C is an fp32 scratch tile that receives the raw sum
+    int32_t pad;
 };
 
 struct GemmChunk {

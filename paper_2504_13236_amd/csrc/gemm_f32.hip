@@ -173,7 +173,7 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(const GemmArgs g) {
 
     // epilogue: lane holds row m = r32, columns n = 8 * (i / 4) + 4 * half + i % 4 of each 32 x 32 block
     float* C = static_cast<float*>(task.C) + (int64_t)bat * task.strideC;
-    const float alpha = g.alpha, beta = g.beta;
+    const float alpha = task.partial ? 1.f : g.alpha, beta = task.partial ? 0.f : g.beta;
 #pragma unroll
     for (int bm = 0; bm < WMB; bm++) {
         const int gm = m0 + (wm * WMB + bm) * 32 + r32;

@@ -122,6 +122,47 @@ def test_attention_products_with_causal_structure(mods, gran, dtype, tiles):
         check(tdK.download(), dKref, dtype, "dK")
 
 
+@pytest.mark.parametrize("dtype,dout", [("f32", "f32"), ("bf16", "f32"), ("bf16", "bf16")])
+@pytest.mark.parametrize("form", ["dW", "dX", "fwd"])
+def test_gemm_long_contraction_few_tiles(mods, dtype, dout, form):
+    """Few output tiles and a long contraction: the product is cut into k-slices
+    that are summed in a second kernel (with alpha, beta and the bias)."""
+    capi, tiled = mods
+    r = rng(11)
+    if form == "dW":       # C[d, e] = sum_{s, b} dY[d, s, b] X[e, s, b]; contraction 4 x 96 x 3 in ragged chunks
+        A = quant(r.standard_normal((200, 4 * 96, 3)), dtype)
+        B = quant(r.standard_normal((136, 4 * 96, 3)), dtype)
+        ta, tb, tc = (64, 100, 2), (48, 100, 2), (64, 48)
+        ops, ncon, cshape = (0, 1), 2, (200, 136)
+        ref = D.contract(1.0, "N", A, "T", B, 0.0, None, 2, 0)
+    elif form == "dX":     # C[e, t] = sum_d W[d, e] dY[d, t]
+        A = quant(r.standard_normal((1500, 136)) * 0.1, dtype)
+        B = quant(r.standard_normal((1500, 300)), dtype)
+        ta, tb, tc = (400, 48), (400, 128), (48, 128)
+        ops, ncon, cshape = (1, 0), 1, (136, 300)
+        ref = D.contract(1.0, "T", A, "N", B, 0.0, None, 1, 0)
+    else:                  # C[d, t] = sum_e W[d, e] X[e, t] + b[d]
+        A = quant(r.standard_normal((136, 1500)) * 0.1, dtype)
+        B = quant(r.standard_normal((1500, 300)), dtype)
+        ta, tb, tc = (48, 400), (400, 128), (48, 128)
+        ops, ncon, cshape = (0, 0), 1, (136, 300)
+        ref = D.contract(1.0, "N", A, "N", B, 0.0, None, 1, 0)
+    bias = r.standard_normal(cshape[0]).astype(np.float32)
+    C0 = quant(r.standard_normal(cshape), dout)
+    with tiled.Context(n_streams=2) as ctx:
+        tA, tB = T(tiled, ctx, A, ta, dtype), T(tiled, ctx, B, tb, dtype)
+        tC = T(tiled, ctx, C0, tc, dout)
+        tbias = T(tiled, ctx, bias, tc[:1], "f32")
+        capi.nnt_gemm(ctx.h, 0.5, ops[0], tA.h, ops[1], tB.h, -2.0, tC.h, ncon, 0, tbias.h)
+        want = 0.5 * ref - 2.0 * C0 + bias.reshape(-1, 1)
+        e = relerr(tC.download(), want)
+        assert e <= (2e-2 if dout == "bf16" else 1e-5), (form, e)
+        # same call again: the scratch tiles are reused, the result accumulates through beta
+        capi.nnt_gemm(ctx.h, 0.5, ops[0], tA.h, ops[1], tB.h, 1.0, tC.h, ncon, 0, None)
+        e = relerr(tC.download(), want + 0.5 * ref)
+        assert e <= (3e-2 if dout == "bf16" else 1e-5), (form, e)
+
+
 def test_gemm_rejects_mismatched_tilings(mods):
     capi, tiled = mods
     with tiled.Context(n_streams=1) as ctx:
