@@ -19,7 +19,14 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 namespace {
 
-__device__ __forceinline__ uint16_t ld_bf16(const uint16_t* p) { return *p; }
+// A pointer that is the same in every lane, moved to scalar registers.
+template <typename T>
+__device__ __forceinline__ const T* uniform_ptr(const T* p) {
+    const uint64_t v = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return reinterpret_cast<const T*>(((uint64_t)hi << 32) | lo);
+}
 
 // ---- k-fast operand: vectors of 8 along k
 template <int ROWS, int BKT>
@@ -28,7 +35,7 @@ struct LoaderK {
     static constexpr int TOTAL = ROWS * BKT / 8;
     static constexpr int KP = BKT + 8;
     uint4 v[NV];
-    __device__ __forceinline__ void load(const uint16_t* base, int64_t ld, int row0, int nrows, int k0, int kc,
+    __device__ __forceinline__ void load(const uint16_t* base, int ld, int row0, int nrows, int k0, int kc,
                                          bool vec_ok, int tid) {
 #pragma unroll
         for (int i = 0; i < NV; i++) {
@@ -54,6 +61,17 @@ struct LoaderK {
             v[i] = x;
         }
     }
+    // interior k-step of an aligned operand; `base` points at (row0, k0)
+    __device__ __forceinline__ void load_fast(const uint16_t* base, int ld, int tid) {
+#pragma unroll
+        for (int i = 0; i < NV; i++) {
+            const int idx = tid + 256 * i;
+            if (TOTAL >= 256 || idx < TOTAL) {
+                const int r = idx / (BKT / 8), k = (idx % (BKT / 8)) * 8;
+                v[i] = *reinterpret_cast<const uint4*>(base + k + (int64_t)r * ld);
+            }
+        }
+    }
     __device__ __forceinline__ void store(uint16_t* l, int tid) const {
 #pragma unroll
         for (int i = 0; i < NV; i++) {
@@ -73,7 +91,7 @@ struct LoaderR {
     static constexpr int NB = TOTAL / 256 > 0 ? TOTAL / 256 : 1;
     static constexpr int KP = BKT + 8;
     uint4 v[NB][4];
-    __device__ __forceinline__ void load(const uint16_t* base, int64_t ld, int row0, int nrows, int k0, int kc,
+    __device__ __forceinline__ void load(const uint16_t* base, int ld, int row0, int nrows, int k0, int kc,
                                          bool vec_ok, int tid) {
 #pragma unroll
         for (int i = 0; i < NB; i++) {
@@ -100,6 +118,18 @@ struct LoaderR {
                     }
                 }
                 v[i][kk] = x;
+            }
+        }
+    }
+    __device__ __forceinline__ void load_fast(const uint16_t* base, int ld, int tid) {
+#pragma unroll
+        for (int i = 0; i < NB; i++) {
+            const int idx = tid + 256 * i;
+            if (TOTAL >= 256 || idx < TOTAL) {
+                const int kq = idx % (BKT / 4), rg = idx / (BKT / 4);
+#pragma unroll
+                for (int kk = 0; kk < 4; kk++)
+                    v[i][kk] = *reinterpret_cast<const uint4*>(base + rg * 8 + (int64_t)(kq * 4 + kk) * ld);
             }
         }
     }
@@ -155,19 +185,19 @@ __global__ void __launch_bounds__(256) gemm_bf16_kernel(const GemmArgs g) {
 
     GemmTask task;
     int m0, n0, bat;
-    const GemmChunk* chunks;
-    if (g.wgs) {
+    // (the chunk table is only ever addressed through g.chunks, a global pointer with a uniform
+    // index, so that the descriptors arrive through scalar loads and the loop control stays scalar)
+    const bool table = g.wgs != nullptr;
+    if (table) {
         const GemmWg w = g.wgs[blockIdx.x];
         task = g.tasks[w.task];
         m0 = w.m0; n0 = w.n0; bat = w.batch;
-        chunks = g.chunks + task.chunk0;
     } else {
         task = g.one_task;
         const int b = blockIdx.x;
         m0 = (b % g.grid_m) * BM;
         n0 = ((b / g.grid_m) % g.grid_n) * BN;
         bat = b / (g.grid_m * g.grid_n);
-        chunks = &g.one_chunk;
     }
 
     f32x16 acc[WNB][WMB];
@@ -179,14 +209,32 @@ __global__ void __launch_bounds__(256) gemm_bf16_kernel(const GemmArgs g) {
             for (int i = 0; i < 16; i++) acc[bn][bm][i] = 0.f;
 
     if (task.nchunk > 0) {
-        int c = 0, k0 = 0;
-        GemmChunk ch = chunks[0];
-        const uint16_t* Ab = static_cast<const uint16_t*>(ch.A) + (int64_t)bat * ch.strideA;
-        const uint16_t* Bb = static_cast<const uint16_t*>(ch.B) + (int64_t)bat * ch.strideB;
+        // uniform loop state lives in scalar registers (see the fp32 kernel)
+        int c = 0, k0 = 0, chk = 0, chvec = 0, lda = 0, ldb = 0;
+        const uint16_t* Ab = nullptr;
+        const uint16_t* Bb = nullptr;
+        auto set_chunk = [&](const GemmChunk& ch) {
+            chk = __builtin_amdgcn_readfirstlane(ch.k);
+            chvec = __builtin_amdgcn_readfirstlane(ch.vec_ok);
+            lda = __builtin_amdgcn_readfirstlane((int)ch.lda);
+            ldb = __builtin_amdgcn_readfirstlane((int)ch.ldb);
+            Ab = uniform_ptr(static_cast<const uint16_t*>(ch.A) + (int64_t)bat * ch.strideA);
+            Bb = uniform_ptr(static_cast<const uint16_t*>(ch.B) + (int64_t)bat * ch.strideB);
+        };
+        set_chunk(table ? g.chunks[task.chunk0] : g.one_chunk);
         typename LoaderSel<AKF, BM, BKT>::type la;
         typename LoaderSel<BKF, BN, BKT>::type lb;
-        la.load(Ab, ch.lda, m0, task.m, k0, ch.k, ch.vec_ok & 1, tid);
-        lb.load(Bb, ch.ldb, n0, task.n, k0, ch.k, ch.vec_ok & 2, tid);
+        const bool inside = m0 + BM <= task.m && n0 + BN <= task.n;
+        auto load_step = [&]() {
+            if (inside && k0 + BKT <= chk && chvec == 3) {
+                la.load_fast(AKF ? Ab + k0 + (int64_t)m0 * lda : Ab + m0 + (int64_t)k0 * lda, lda, tid);
+                lb.load_fast(BKF ? Bb + k0 + (int64_t)n0 * ldb : Bb + n0 + (int64_t)k0 * ldb, ldb, tid);
+            } else {
+                la.load(Ab, lda, m0, task.m, k0, chk, chvec & 1, tid);
+                lb.load(Bb, ldb, n0, task.n, k0, chk, chvec & 2, tid);
+            }
+        };
+        load_step();
         int cur = 0;
         la.store(lds, tid);
         lb.store(lds + A_SZ, tid);
@@ -194,36 +242,35 @@ __global__ void __launch_bounds__(256) gemm_bf16_kernel(const GemmArgs g) {
         bool more = true;
         while (more) {
             k0 += BKT;
-            if (k0 >= ch.k) {
+            if (k0 >= chk) {
                 c++;
                 k0 = 0;
-                if (c < task.nchunk) {
-                    ch = chunks[c];
-                    Ab = static_cast<const uint16_t*>(ch.A) + (int64_t)bat * ch.strideA;
-                    Bb = static_cast<const uint16_t*>(ch.B) + (int64_t)bat * ch.strideB;
-                }
+                if (c < task.nchunk) set_chunk(g.chunks[task.chunk0 + c]);
             }
             more = c < task.nchunk;
-            if (more) {
-                la.load(Ab, ch.lda, m0, task.m, k0, ch.k, ch.vec_ok & 1, tid);
-                lb.load(Bb, ch.ldb, n0, task.n, k0, ch.k, ch.vec_ok & 2, tid);
-            }
+            if (more) load_step();
             const uint16_t* lA = lds + cur * (A_SZ + B_SZ);
             const uint16_t* lB = lA + A_SZ;
-#pragma unroll
-            for (int ks = 0; ks < BKT / 16; ks++) {
-                bf16x8 pf[WNB], qf[WMB];
+            // fragments of k-substep ks + 1 are requested from LDS before the matrix-core work of
+            // substep ks is issued, so that the LDS latency hides behind it
+            bf16x8 pf[2][WNB], qf[2][WMB];
+            auto frags = [&](int buf, int ks) {
 #pragma unroll
                 for (int bn = 0; bn < WNB; bn++)
-                    pf[bn] = *reinterpret_cast<const bf16x8*>(&lB[((wn * WNB + bn) * 32 + r32) * KP + ks * 16 + half * 8]);
+                    pf[buf][bn] = *reinterpret_cast<const bf16x8*>(&lB[((wn * WNB + bn) * 32 + r32) * KP + ks * 16 + half * 8]);
 #pragma unroll
                 for (int bm = 0; bm < WMB; bm++)
-                    qf[bm] = *reinterpret_cast<const bf16x8*>(&lA[((wm * WMB + bm) * 32 + r32) * KP + ks * 16 + half * 8]);
+                    qf[buf][bm] = *reinterpret_cast<const bf16x8*>(&lA[((wm * WMB + bm) * 32 + r32) * KP + ks * 16 + half * 8]);
+            };
+            frags(0, 0);
+#pragma unroll
+            for (int ks = 0; ks < BKT / 16; ks++) {
+                if (ks + 1 < BKT / 16) frags((ks + 1) & 1, ks + 1);
 #pragma unroll
                 for (int bn = 0; bn < WNB; bn++)
 #pragma unroll
                     for (int bm = 0; bm < WMB; bm++)
-                        acc[bn][bm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf[bn], qf[bm], acc[bn][bm], 0, 0, 0);
+                        acc[bn][bm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf[ks & 1][bn], qf[ks & 1][bm], acc[bn][bm], 0, 0, 0);
             }
             if (more) {
                 uint16_t* nA = lds + (cur ^ 1) * (A_SZ + B_SZ);

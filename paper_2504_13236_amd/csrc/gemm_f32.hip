@@ -24,11 +24,20 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 namespace {
 
+// A pointer that is the same in every lane, moved to scalar registers.
+template <typename T>
+__device__ __forceinline__ const T* uniform_ptr(const T* p) {
+    const uint64_t v = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return reinterpret_cast<const T*>(((uint64_t)hi << 32) | lo);
+}
+
 constexpr int BK = 16;
 constexpr int KP = BK + 4;   // padded k extent of a k-fast LDS row (conflict-free 128-bit reads)
 
 template <bool KF, int ROWS>
-__device__ __forceinline__ void gload(f32x4 (&v)[ROWS / 64], const float* base, int64_t ld, int row0,
+__device__ __forceinline__ void gload(f32x4 (&v)[ROWS / 64], const float* base, int ld, int row0,
                                       int nrows, int k0, int kc, bool vec_ok, int tid) {
 #pragma unroll
     for (int i = 0; i < ROWS / 64; i++) {
@@ -49,6 +58,21 @@ __device__ __forceinline__ void gload(f32x4 (&v)[ROWS / 64], const float* base, 
             if (cnt > 3) x[3] = p[3];
         }
         v[i] = x;
+    }
+}
+
+// Interior k-step of an aligned operand: no predicates, no branches, so the loads stay in
+// flight across the matrix-core work that follows.  `base` points at (row0, k0).
+template <bool KF, int ROWS>
+__device__ __forceinline__ void gload_fast(f32x4 (&v)[ROWS / 64], const float* base, int ld, int tid) {
+#pragma unroll
+    for (int i = 0; i < ROWS / 64; i++) {
+        const int idx = tid + 256 * i;
+        int r, k;
+        if (KF) { r = idx >> 2; k = (idx & 3) << 2; }
+        else { k = idx / (ROWS / 4); r = (idx % (ROWS / 4)) << 2; }
+        const float* p = KF ? base + k + (int64_t)r * ld : base + r + (int64_t)k * ld;
+        v[i] = *reinterpret_cast<const f32x4*>(p);
     }
 }
 
@@ -94,19 +118,19 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(const GemmArgs g) {
 
     GemmTask task;
     int m0, n0, bat;
-    const GemmChunk* chunks;
-    if (g.wgs) {
+    // (the chunk table is only ever addressed through g.chunks, a global pointer with a uniform
+    // index, so that the descriptors arrive through scalar loads and the loop control stays scalar)
+    const bool table = g.wgs != nullptr;
+    if (table) {
         const GemmWg w = g.wgs[blockIdx.x];
         task = g.tasks[w.task];
         m0 = w.m0; n0 = w.n0; bat = w.batch;
-        chunks = g.chunks + task.chunk0;
     } else {
         task = g.one_task;
         const int b = blockIdx.x;
         m0 = (b % g.grid_m) * BM;
         n0 = ((b / g.grid_m) % g.grid_n) * BN;
         bat = b / (g.grid_m * g.grid_n);
-        chunks = &g.one_chunk;
     }
 
     f32x16 acc[WNB][WMB];
@@ -118,13 +142,34 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(const GemmArgs g) {
             for (int i = 0; i < 16; i++) acc[bn][bm][i] = 0.f;
 
     if (task.nchunk > 0) {
-        int c = 0, k0 = 0;
-        GemmChunk ch = chunks[0];
-        const float* Ab = static_cast<const float*>(ch.A) + (int64_t)bat * ch.strideA;
-        const float* Bb = static_cast<const float*>(ch.B) + (int64_t)bat * ch.strideB;
+        // Loop state that is the same for every lane is kept in scalar registers on purpose
+        // (readfirstlane): the k-loop then branches on the scalar unit and the loads address
+        // memory as scalar base + per-lane offset.
+        int c = 0, k0 = 0, chk = 0, chvec = 0, lda = 0, ldb = 0;
+        const float* Ab = nullptr;
+        const float* Bb = nullptr;
+        auto set_chunk = [&](const GemmChunk& ch) {
+            chk = __builtin_amdgcn_readfirstlane(ch.k);
+            chvec = __builtin_amdgcn_readfirstlane(ch.vec_ok);
+            lda = __builtin_amdgcn_readfirstlane((int)ch.lda);
+            ldb = __builtin_amdgcn_readfirstlane((int)ch.ldb);
+            Ab = uniform_ptr(static_cast<const float*>(ch.A) + (int64_t)bat * ch.strideA);
+            Bb = uniform_ptr(static_cast<const float*>(ch.B) + (int64_t)bat * ch.strideB);
+        };
+        set_chunk(table ? g.chunks[task.chunk0] : g.one_chunk);
         f32x4 va[BM / 64], vb[BN / 64];
-        gload<AKF, BM>(va, Ab, ch.lda, m0, task.m, k0, ch.k, ch.vec_ok & 1, tid);
-        gload<BKF, BN>(vb, Bb, ch.ldb, n0, task.n, k0, ch.k, ch.vec_ok & 2, tid);
+        // whole macro-tile inside the C tile: k-steps that are also whole take the branch-free loads
+        const bool inside = m0 + BM <= task.m && n0 + BN <= task.n;
+        auto load_step = [&]() {
+            if (inside && k0 + BK <= chk && chvec == 3) {
+                gload_fast<AKF, BM>(va, AKF ? Ab + k0 + (int64_t)m0 * lda : Ab + m0 + (int64_t)k0 * lda, lda, tid);
+                gload_fast<BKF, BN>(vb, BKF ? Bb + k0 + (int64_t)n0 * ldb : Bb + n0 + (int64_t)k0 * ldb, ldb, tid);
+            } else {
+                gload<AKF, BM>(va, Ab, lda, m0, task.m, k0, chk, chvec & 1, tid);
+                gload<BKF, BN>(vb, Bb, ldb, n0, task.n, k0, chk, chvec & 2, tid);
+            }
+        };
+        load_step();
         int cur = 0;
         lstore<AKF, BM>(lds, va, tid);
         lstore<BKF, BN>(lds + A_SZ, vb, tid);
@@ -133,20 +178,13 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(const GemmArgs g) {
         while (more) {
             // advance to the next k-step (possibly the next chunk) and start its loads
             k0 += BK;
-            if (k0 >= ch.k) {
+            if (k0 >= chk) {
                 c++;
                 k0 = 0;
-                if (c < task.nchunk) {
-                    ch = chunks[c];
-                    Ab = static_cast<const float*>(ch.A) + (int64_t)bat * ch.strideA;
-                    Bb = static_cast<const float*>(ch.B) + (int64_t)bat * ch.strideB;
-                }
+                if (c < task.nchunk) set_chunk(g.chunks[task.chunk0 + c]);
             }
             more = c < task.nchunk;
-            if (more) {
-                gload<AKF, BM>(va, Ab, ch.lda, m0, task.m, k0, ch.k, ch.vec_ok & 1, tid);
-                gload<BKF, BN>(vb, Bb, ch.ldb, n0, task.n, k0, ch.k, ch.vec_ok & 2, tid);
-            }
+            if (more) load_step();
             const float* lA = lds + cur * (A_SZ + B_SZ);
             const float* lB = lA + A_SZ;
             float pf[WNB][8], qf[WMB][8];

@@ -157,3 +157,27 @@ def test_block_C3_full_size_bf16(mods):
     got = gpu_run(tiled, cfg, inp, workload.base_tiles(cfg), True)
     errs = compare(got, ref, "bf16", True)
     print("C3 max-norm relative errors:", {k: "%.2e" % v for k, v in errs.items()})
+
+
+def test_block_C4_full_size_bf16_ragged(mods):
+    """GPT-2-XL shape: tile 400 against 1600 / 6400 / 1024 (sequence tiles 400 + 400 + 224, head size 64 crossing tile edges)."""
+    capi, tiled = mods
+    cfg = workload.CONFIGS[4]
+    inp = workload.generate(cfg)
+    ref = oracle_run(cfg, inp, False)
+    got = gpu_run(tiled, cfg, inp, workload.base_tiles(cfg), False)
+    errs = compare(got, ref, "bf16", False)
+    print("C4 max-norm relative errors:", {k: "%.2e" % v for k, v in errs.items()})
+
+
+def test_block_C5_one_batch_member_bf16(mods):
+    """The 50B-class block (N_e = 8192, head size 128, tile 1024) on one of its four batch members: batch
+    members are independent except for the parameter-gradient sums, and the full batch would take the
+    fp64 oracle several minutes."""
+    capi, tiled = mods
+    cfg = workload.CONFIGS[5].replace(N_b=1)
+    inp = workload.generate(cfg)
+    ref = oracle_run(cfg, inp, True)
+    got = gpu_run(tiled, cfg, inp, workload.base_tiles(cfg), True)
+    errs = compare(got, ref, "bf16", True)
+    print("C5 (N_b=1) max-norm relative errors:", {k: "%.2e" % v for k, v in errs.items()})
