@@ -55,6 +55,9 @@ def main():
     ap.add_argument("--granularity", choices=["op", "tile"], default="op")
     ap.add_argument("--graph", action="store_true", help="replay the step from a captured HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
+                    help="instead of the benchmark, copy MIB MiB of fp32 a few times with the library's cast kernel "
+                         "(a plain copy kernel of known size, for scaling HBM counters)")
     ap.add_argument("--cpu-sample-batch", type=int, default=0)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -68,6 +71,25 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py needs a GPU: the HIP library is the only execution path", file=sys.stderr)
         sys.exit(3)
+    if args.copy_calibration:
+        n = args.copy_calibration * (1 << 20) // 4
+        src = torch.ones(n, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        st = torch.cuda.current_stream().cuda_stream
+        for _ in range(3):
+            capi.nnt_tile_cast(st, capi.NNT_F32, capi.NNT_F32, n, src.data_ptr(), dst.data_ptr())
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            capi.nnt_tile_cast(st, capi.NNT_F32, capi.NNT_F32, n, src.data_ptr(), dst.data_ptr())
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 5
+        print(json.dumps({"copy_calibration": {"bytes_read": 4 * n, "bytes_written": 4 * n, "launches": 8, "ms": ms,
+                                               "GB/s": 8.0 * n / ms / 1e6,
+                                               "kernel": "ew_kernel<CastF<float, float>>"}}))
+        return
     cfg = workload.CONFIGS[args.config]
     inp = workload.generate(cfg)
     gran = capi.NNT_GRAN_OP if args.granularity == "op" else capi.NNT_GRAN_TILE
@@ -146,6 +168,15 @@ def main():
                     "unit": "TFLOP/s", "frac": gemms[dom]["TFLOP/s"] / PEAK_TFLOPS[cfg.dtype], "traffic": None,
                     "avg_launch_us": gemms[dom]["avg_launch_us"], "launches": e["launches"],
                     "flops_per_launch": e["work"] / max(e["launches"], 1)}
+        # HBM bytes per launch of that kernel, as measured by the committed rocprofv3 --pmc runs
+        # (FETCH_SIZE and WRITE_SIZE scaled by a plain copy kernel); null when no such run is on file
+        tpath = os.path.join(ROOT, "profiles", "hbm_traffic_C%d.txt" % args.config)
+        if os.path.exists(tpath):
+            for line in open(tpath):
+                parts = line.rstrip("\n").split("\t")
+                if len(parts) == 3 and parts[0] == dom.replace(" batched", ""):
+                    roofline["traffic"] = {"read_bytes_per_launch": float(parts[1]), "written_bytes_per_launch": float(parts[2]),
+                                           "source": "profiles/" + os.path.basename(tpath)}
         wg = [v for k, v in gemms.items()]
         tot_ms = sum(v["ms_per_step"] for v in wg)
         tot_fl = sum(v["TFLOP/s"] * v["ms_per_step"] for v in wg)

@@ -8,6 +8,7 @@
 // Every thread moves 16-byte vectors (4 fp32 or 8 bf16) when the tile extents and
 // pointers allow it, single elements otherwise.
 #include "device_util.hpp"
+#include "ew_functors.hpp"
 #include "internal.hpp"
 
 #include <algorithm>
@@ -15,269 +16,6 @@
 
 namespace nnt {
 namespace {
-
-constexpr int kUnroll = 4;
-
-struct EwGeom {
-    TiledView v;        // tiling of the operands (tensor form)
-    int64_t n_single;   // element count (tile form)
-    int32_t tiled;
-};
-
-template <typename T>
-__device__ __forceinline__ T* pick(void* const* table, void* single, int tile) {
-    return static_cast<T*>(table ? table[tile] : single);
-}
-
-template <typename F>
-__global__ void __launch_bounds__(256) ew_kernel(F f, EwGeom g, int vec) {
-    const int tile = blockIdx.y;
-    int64_t n;
-    if (g.tiled) {
-        n = tile_numel(g.v, tile);
-    } else {
-        n = g.n_single;
-    }
-    typename F::Ctx c;
-    if (!f.setup(c, g, tile)) return;
-    constexpr int V = F::V;
-    if (vec) {
-#pragma unroll
-        for (int u = 0; u < kUnroll; u++) {
-            const int64_t i = (((int64_t)blockIdx.x * kUnroll + u) * 256 + threadIdx.x) * V;
-            if (i + V <= n) {
-                f.template run<V>(c, i);
-            } else {
-                for (int64_t j = i; j < n; j++) f.template run<1>(c, j);
-            }
-        }
-    } else {
-#pragma unroll
-        for (int u = 0; u < kUnroll * V; u++) {
-            const int64_t i = ((int64_t)blockIdx.x * kUnroll * V + u) * 256 + threadIdx.x;
-            if (i < n) f.template run<1>(c, i);
-        }
-    }
-}
-
-template <typename F>
-int32_t launch_ew(hipStream_t st, const F& f, const EwGeom& g, int64_t max_numel, int64_t ntiles, bool vec) {
-    if (max_numel <= 0 || ntiles <= 0) return NNT_OK;
-    const int64_t per_block = (int64_t)256 * kUnroll * F::V;
-    const int64_t gx = (max_numel + per_block - 1) / per_block;
-    if (gx > INT32_MAX || ntiles > 65535) return NNT_EINVAL;
-    hipLaunchKernelGGL((ew_kernel<F>), dim3((unsigned)gx, (unsigned)ntiles), dim3(256), 0, st, f, g, vec ? 1 : 0);
-    return hipGetLastError() == hipSuccess ? NNT_OK : NNT_EHIP;
-}
-
-// ------------------------------------------------------------------ functors
-struct Operand {
-    void* const* table;
-    void* single;
-};
-
-template <typename T>
-struct FillF {
-    static constexpr int V = VecOf<T>::V;
-    Operand x;
-    float value;
-    struct Ctx { T* x; };
-    __device__ bool setup(Ctx& c, const EwGeom&, int tile) const { c.x = pick<T>(x.table, x.single, tile); return c.x != nullptr; }
-    template <int W> __device__ void run(const Ctx& c, int64_t i) const {
-        float f[W];
-#pragma unroll
-        for (int j = 0; j < W; j++) f[j] = value;
-        stv<W>(c.x + i, f);
-    }
-};
-
-template <typename T>
-struct AddF {
-    static constexpr int V = VecOf<T>::V;
-    Operand x, y;
-    float alpha, beta;
-    struct Ctx { const T* x; T* y; };
-    __device__ bool setup(Ctx& c, const EwGeom&, int tile) const {
-        c.x = pick<const T>(x.table, x.single, tile);
-        c.y = pick<T>(y.table, y.single, tile);
-        return c.y != nullptr;
-    }
-    template <int W> __device__ void run(const Ctx& c, int64_t i) const {
-        float a[W], b[W];
-        ldv<W>(c.x + i, a);
-        if (beta != 0.f) {
-            ldv<W>(c.y + i, b);
-#pragma unroll
-            for (int j = 0; j < W; j++) a[j] = alpha * a[j] + beta * b[j];
-        } else {
-#pragma unroll
-            for (int j = 0; j < W; j++) a[j] = alpha * a[j];
-        }
-        stv<W>(c.y + i, a);
-    }
-};
-
-template <typename TI, typename TO>
-struct CastF {
-    static constexpr int V = 8;     // 8 elements per thread whatever the types
-    Operand x, y;
-    struct Ctx { const TI* x; TO* y; };
-    __device__ bool setup(Ctx& c, const EwGeom&, int tile) const {
-        c.x = pick<const TI>(x.table, x.single, tile);
-        c.y = pick<TO>(y.table, y.single, tile);
-        return c.y != nullptr;
-    }
-    template <int W> __device__ void run(const Ctx& c, int64_t i) const {
-        if constexpr (W == 8) {
-            float a[4], b[4], f[8];
-            if constexpr (sizeof(TI) == 4) { ldv<4>(c.x + i, a); ldv<4>(c.x + i + 4, b);
-#pragma unroll
-                for (int j = 0; j < 4; j++) { f[j] = a[j]; f[4 + j] = b[j]; }
-            } else { ldv<8>(c.x + i, f); }
-            if constexpr (sizeof(TO) == 4) {
-#pragma unroll
-                for (int j = 0; j < 4; j++) { a[j] = f[j]; b[j] = f[4 + j]; }
-                stv<4>(c.y + i, a); stv<4>(c.y + i + 4, b);
-            } else { stv<8>(c.y + i, f); }
-        } else {
-            float f[1];
-            ldv<1>(c.x + i, f);
-            stv<1>(c.y + i, f);
-        }
-    }
-};
-
-__device__ __forceinline__ float gelu_f(float x, int variant) {
-    if (variant == NNT_GELU_TANH) {
-        const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
-        return 0.5f * x * (1.f + tanhf(u));
-    }
-    return 0.5f * x * (1.f + erff(x * 0.7071067811865476f));
-}
-__device__ __forceinline__ float gelu_grad_f(float x, int variant) {
-    if (variant == NNT_GELU_TANH) {
-        const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
-        const float t = tanhf(u);
-        return 0.5f * (1.f + t) + 0.5f * x * (1.f - t * t) * 0.7978845608028654f * (1.f + 3.f * 0.044715f * x * x);
-    }
-    return 0.5f * (1.f + erff(x * 0.7071067811865476f)) + x * 0.3989422804014327f * expf(-0.5f * x * x);
-}
-
-template <typename T>
-struct GeluF {
-    static constexpr int V = VecOf<T>::V;
-    Operand x, y;
-    int variant;
-    struct Ctx { const T* x; T* y; };
-    __device__ bool setup(Ctx& c, const EwGeom&, int tile) const {
-        c.x = pick<const T>(x.table, x.single, tile);
-        c.y = pick<T>(y.table, y.single, tile);
-        return c.y != nullptr;
-    }
-    template <int W> __device__ void run(const Ctx& c, int64_t i) const {
-        float a[W];
-        ldv<W>(c.x + i, a);
-#pragma unroll
-        for (int j = 0; j < W; j++) a[j] = gelu_f(a[j], variant);
-        stv<W>(c.y + i, a);
-    }
-};
-
-template <typename T>
-struct GeluBwdF {
-    static constexpr int V = VecOf<T>::V;
-    Operand x, dy, dx;
-    int variant;
-    struct Ctx { const T* x; const T* dy; T* dx; };
-    __device__ bool setup(Ctx& c, const EwGeom&, int tile) const {
-        c.x = pick<const T>(x.table, x.single, tile);
-        c.dy = pick<const T>(dy.table, dy.single, tile);
-        c.dx = pick<T>(dx.table, dx.single, tile);
-        return c.dx != nullptr;
-    }
-    template <int W> __device__ void run(const Ctx& c, int64_t i) const {
-        float a[W], d[W];
-        ldv<W>(c.x + i, a);
-        ldv<W>(c.dy + i, d);
-#pragma unroll
-        for (int j = 0; j < W; j++) a[j] = d[j] * gelu_grad_f(a[j], variant);
-        stv<W>(c.dx + i, a);
-    }
-};
-
-// Y (m x n, m fastest) += bias[m].  In the tensor form the bias tile is the one
-// with the tile's first grid coordinate.
-template <typename T>
-struct BiasAddF {
-    static constexpr int V = VecOf<T>::V;
-    Operand y, b;
-    int64_t m_single;
-    struct Ctx { T* y; const float* b; int m; };
-    __device__ bool setup(Ctx& c, const EwGeom& g, int tile) const {
-        c.y = pick<T>(y.table, y.single, tile);
-        if (g.tiled) {
-            int tc[kMaxDim], ext[kMaxDim];
-            tile_geometry(g.v, tile, tc, ext);
-            c.m = ext[0];
-            c.b = static_cast<const float*>(b.table[tc[0]]);
-        } else {
-            c.m = (int)m_single;
-            c.b = static_cast<const float*>(b.single);
-        }
-        return c.y != nullptr;
-    }
-    template <int W> __device__ void run(const Ctx& c, int64_t i) const {
-        float a[W];
-        ldv<W>(c.y + i, a);
-        const int r = (int)(i % c.m);       // a vector never crosses a column: m % W == 0 on this path
-#pragma unroll
-        for (int j = 0; j < W; j++) a[j] += c.b[r + j];
-        stv<W>(c.y + i, a);
-    }
-};
-
-struct AdamF {
-    static constexpr int V = 4;
-    Operand g, p, m, v, lp;
-    float lr, beta1, beta2, omb1, omb2, eps, wd, inv_bc1, inv_bc2;   // omb = 1 - beta, formed in double on the host
-    struct Ctx { const float* g; float* p; float* m; float* v; bf16_t* lp; };
-    __device__ bool setup(Ctx& c, const EwGeom&, int tile) const {
-        c.g = pick<const float>(g.table, g.single, tile);
-        c.p = pick<float>(p.table, p.single, tile);
-        c.m = pick<float>(m.table, m.single, tile);
-        c.v = pick<float>(v.table, v.single, tile);
-        c.lp = (lp.table || lp.single) ? pick<bf16_t>(lp.table, lp.single, tile) : nullptr;
-        return c.p != nullptr;
-    }
-    template <int W> __device__ void run(const Ctx& c, int64_t i) const {
-        float gg[W], pp[W], mm[W], vv[W];
-        ldv<W>(c.g + i, gg);
-        ldv<W>(c.p + i, pp);
-        ldv<W>(c.m + i, mm);
-        ldv<W>(c.v + i, vv);
-#pragma unroll
-        for (int j = 0; j < W; j++) {
-            mm[j] = beta1 * mm[j] + omb1 * gg[j];
-            vv[j] = beta2 * vv[j] + omb2 * gg[j] * gg[j];
-            const float mhat = mm[j] * inv_bc1;
-            const float vhat = vv[j] * inv_bc2;
-            pp[j] = pp[j] - lr * wd * pp[j] - lr * mhat / (sqrtf(vhat) + eps);
-        }
-        stv<W>(c.p + i, pp);
-        stv<W>(c.m + i, mm);
-        stv<W>(c.v + i, vv);
-        if (c.lp) {
-            if constexpr (W == 4) {
-                uint2 x;
-                x.x = (uint32_t)f2bf(pp[0]) | ((uint32_t)f2bf(pp[1]) << 16);
-                x.y = (uint32_t)f2bf(pp[2]) | ((uint32_t)f2bf(pp[3]) << 16);
-                *reinterpret_cast<uint2*>(c.lp + i) = x;
-            } else {
-                c.lp[i] = f2bf(pp[0]);
-            }
-        }
-    }
-};
 
 // ------------------------------------------------------------------ strided block copy
 template <typename T>
@@ -462,8 +200,8 @@ int32_t nnt_tile_bias_add(void* stream, int32_t dtype, int64_t m, int64_t n, con
     hipStream_t st = (hipStream_t)stream;
     const EwGeom g = single_geom(m * n);
     if (dtype == NNT_F32)
-        return launch_ew(st, BiasAddF<float>{ptr(Y), ptr(bias), m}, g, m * n, 1, aligned16(Y) && m % 4 == 0);
-    return launch_ew(st, BiasAddF<bf16_t>{ptr(Y), ptr(bias), m}, g, m * n, 1, aligned16(Y) && m % 8 == 0);
+        return launch_ew(st, BiasAddF<float>{ptr(Y), ptr(bias), m}, g, m * n, 1, aligned16(Y) && aligned16(bias) && m % 4 == 0);
+    return launch_ew(st, BiasAddF<bf16_t>{ptr(Y), ptr(bias), m}, g, m * n, 1, aligned16(Y) && aligned16(bias) && m % 8 == 0);
 }
 
 int32_t nnt_tile_gelu(void* stream, int32_t dtype, int32_t variant, int64_t n, const void* x, void* y) {

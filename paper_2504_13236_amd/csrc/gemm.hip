@@ -56,7 +56,7 @@ struct GemmPlan {
     std::string label;                         // the kernel instance that runs the plan
     std::vector<GemmTask> tasks;
     std::vector<GemmChunk> chunks;
-    std::vector<GemmWg> wgs;
+    std::vector<GemmWg> wgs, wgs_op;
     std::vector<int64_t> task_wg0;             // first workgroup of each task (+ total at the end)
     std::vector<int64_t> task_ctile;           // C tile index per task
     std::vector<std::vector<int64_t>> task_atiles, task_btiles;   // operand tiles per task (dependencies)
@@ -64,6 +64,7 @@ struct GemmPlan {
     GemmTask* d_tasks = nullptr;
     GemmChunk* d_chunks = nullptr;
     GemmWg* d_wgs = nullptr;
+    GemmWg* d_wgs_op = nullptr;
     // Split form (one launch per operation only): every task is cut into `splits` k-slices that
     // write raw fp32 sums to a scratch tile each; a second kernel adds the slices in a fixed order
     // and applies alpha, beta and the bias.  Used when the unsplit grid cannot fill the chip.
@@ -77,7 +78,7 @@ struct GemmPlan {
     int64_t sk_max_count = 0;
     TileDep ws_dep;
     ~GemmPlan() {
-        for (void* p : {(void*)d_tasks, (void*)d_chunks, (void*)d_wgs, (void*)d_sk_tasks, (void*)d_sk_chunks, (void*)d_sk_wgs,
+        for (void* p : {(void*)d_tasks, (void*)d_chunks, (void*)d_wgs, (void*)d_wgs_op, (void*)d_sk_tasks, (void*)d_sk_chunks, (void*)d_sk_wgs,
                         (void*)d_sk_red, (void*)d_ws})
             if (p) (void)hipFree(p);
     }
@@ -100,6 +101,63 @@ static int32_t launch_any(hipStream_t st, int dtype_in, int dtype_out, int akf, 
 static int vec_flag(const void* p, int64_t ld, int64_t stride, int elem) {
     const int per = 16 / elem;
     return ((uintptr_t)p % 16 == 0) && (ld % per == 0) && (stride % per == 0);
+}
+
+// Workgroups are handed to the 8 XCDs (each with its own L2) in turn by their linear id, so the
+// workgroups with id = x (mod 8) run on XCD x, about one per CU at a time.  The list arrives in
+// tile order (rows fastest, then columns, batch members, tasks).  Each macro-tile grid is cut into
+// blocks of 16 x 16 tiles; inside a block XCD x owns a sub-block of 8 x 4 tiles, so the workgroups
+// that an XCD runs together need 8 + 4 operand panels instead of up to 33, and the eight XCDs
+// together work on one compact 16 x 16 region whose panels meet in the last-level cache.  Small
+// grids (batched attention products) go to one XCD each.  The per-XCD queues are then dealt out
+// in turn; a queue that runs dry takes work from the longest one.
+static void xcd_interleave(std::vector<GemmWg>& wgs, int bm, int bn) {
+    const size_t n = wgs.size();
+    if (n < 64) return;
+    std::vector<GemmWg> q[8];
+    int small_turn = 0;
+    size_t a = 0;
+    while (a < n) {
+        size_t b = a;
+        int gm = 0, gn = 0;
+        while (b < n && wgs[b].task == wgs[a].task && wgs[b].batch == wgs[a].batch) {
+            gm = std::max(gm, wgs[b].m0 / bm + 1);
+            gn = std::max(gn, wgs[b].n0 / bn + 1);
+            b++;
+        }
+        if ((size_t)gm * gn != b - a || gm * gn < 64) {
+            // small or irregular grid: keep it together on one XCD
+            std::vector<GemmWg>& dst = q[small_turn++ & 7];
+            dst.insert(dst.end(), wgs.begin() + a, wgs.begin() + b);
+        } else {
+            for (int J = 0; J < gn; J += 16)
+                for (int I = 0; I < gm; I += 16)
+                    for (int x = 0; x < 8; x++)
+                        for (int j = 0; j < 4; j++)
+                            for (int i = 0; i < 8; i++) {
+                                const int ii = I + (x & 1) * 8 + i, jj = J + (x >> 1) * 4 + j;
+                                if (ii < gm && jj < gn) q[x].push_back(wgs[a + (size_t)jj * gm + ii]);
+                            }
+        }
+        a = b;
+    }
+    std::vector<GemmWg> out;
+    out.reserve(n);
+    size_t head[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    while (out.size() < n) {
+        for (int x = 0; x < 8 && out.size() < n; x++) {
+            if (head[x] < q[x].size()) {
+                out.push_back(q[x][head[x]++]);
+            } else {
+                int longest = 0;
+                for (int y = 1; y < 8; y++)
+                    if (q[y].size() - head[y] > q[longest].size() - head[longest]) longest = y;
+                out.push_back(q[longest].back());
+                q[longest].pop_back();
+            }
+        }
+    }
+    wgs.swap(out);
 }
 
 static int pick_cfg(int bf16, int64_t m_max, int64_t n_max, int64_t n_tiles_big) {
@@ -305,6 +363,9 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
     }
     P->task_wg0.push_back((int64_t)P->wgs.size());
     if (P->wgs.size() > (size_t)INT32_MAX) return fail(ctx, NNT_EINVAL, "nnt_gemm: too many workgroups");
+    // whole-operation launches use the XCD-aware order; per-task launches keep the order by task
+    P->wgs_op = P->wgs;
+    xcd_interleave(P->wgs_op, bm, bn);
 
     // ---- split form
     const int64_t W = (int64_t)P->wgs.size();
@@ -379,6 +440,7 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
             ws_off += (int64_t)S * count;
         }
         P->sk_nwg = (int64_t)wgs.size();
+        xcd_interleave(wgs, bm, bn);
         auto up2 = [&](void** d, const void* h, size_t bytes) -> hipError_t {
             hipError_t e = hipMalloc(d, bytes);
             if (e != hipSuccess) return e;
@@ -399,6 +461,7 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
     NNT_HIP(ctx, up((void**)&P->d_tasks, P->tasks.data(), P->tasks.size() * sizeof(GemmTask)));
     NNT_HIP(ctx, up((void**)&P->d_chunks, P->chunks.data(), P->chunks.size() * sizeof(GemmChunk)));
     NNT_HIP(ctx, up((void**)&P->d_wgs, P->wgs.data(), P->wgs.size() * sizeof(GemmWg)));
+    NNT_HIP(ctx, up((void**)&P->d_wgs_op, P->wgs_op.data(), P->wgs_op.size() * sizeof(GemmWg)));
     return NNT_OK;
 }
 
@@ -434,7 +497,7 @@ extern "C" int32_t nnt_gemm(nnt_ctx* ctx, float alpha, int32_t opA, nnt_tensor* 
     if (ctx->granularity == NNT_GRAN_OP) {
         std::vector<Access> acc = {A->all(kRead), B->all(kRead), C->all(cmode)};
         if (bias) acc.push_back(bias->all(kRead));
-        g.wgs = P->d_wgs;
+        g.wgs = P->d_wgs_op;
         const int64_t nwg = (int64_t)P->wgs.size();
         if (nwg == 0) return NNT_OK;
         if (P->splits > 1) {

@@ -2,13 +2,23 @@
 // (v_mfma_f32_32x32x16_bf16): bf16 operands, fp32 accumulation over all chunks
 // of a task, one rounding when C is written (fp32 or bf16).
 //
-// Same structure as the fp32 kernel: four wavefronts per workgroup, a BM x BN
-// macro-tile, k-steps of BKT elements, two LDS buffers, one barrier per step.
-// The matrix cores want 8 consecutive k per lane, so both operands live in LDS as
-// [row][BKT + 8 pad] (k fastest).  An operand that is k-fast in memory is copied
-// with 128-bit loads and stores; one whose row index is contiguous is read as
-// 8-row vectors at 4 consecutive k and transposed in registers (16-bit packs)
+// Four wavefronts per workgroup own a BM x BN macro-tile and walk the task's
+// chunks in k-steps of BKT.  The matrix cores want 8 consecutive k per lane, so
+// both operands live in LDS as [row][BKT + 8 pad] (k fastest; the pad makes the
+// 128-bit fragment reads conflict-free).  An operand that is k-fast in memory is
+// copied with 128-bit loads and stores; one whose row index is contiguous is read
+// as 8-row vectors at 4 consecutive k and transposed in registers (16-bit packs)
 // before the LDS store.
+//
+// Pipeline (a workgroup has the matrix cores of its CU to itself, so latency has
+// to be hidden inside each wavefront):
+//   * three LDS stages: while step t is multiplied, step t+1 is already complete
+//     in LDS and step t+2 is being written, so one barrier per step suffices and
+//     the first fragments of step t+1 can be fetched before that barrier;
+//   * fragments of the next k-substep are requested from LDS before the matrix
+//     instructions of the current one are issued (two fragment register sets);
+//   * global loads of step t+3 are issued right after the registers of step t+2
+//     have been stored to LDS and stay in flight for a whole step.
 #include "gemm_common.hpp"
 #include "nntile_mi.h"
 
@@ -26,6 +36,18 @@ __device__ __forceinline__ const T* uniform_ptr(const T* p) {
     const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
     const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
     return reinterpret_cast<const T*>(((uint64_t)hi << 32) | lo);
+}
+
+__device__ __forceinline__ uint4 load8_guarded(const uint16_t* p, int cnt) {
+    uint16_t e[8];
+#pragma unroll
+    for (int j = 0; j < 8; j++) e[j] = j < cnt ? p[j] : (uint16_t)0;
+    uint4 x;
+    x.x = e[0] | ((uint32_t)e[1] << 16);
+    x.y = e[2] | ((uint32_t)e[3] << 16);
+    x.z = e[4] | ((uint32_t)e[5] << 16);
+    x.w = e[6] | ((uint32_t)e[7] << 16);
+    return x;
 }
 
 // ---- k-fast operand: vectors of 8 along k
@@ -46,17 +68,8 @@ struct LoaderK {
                 const int gr = row0 + r, gk = k0 + k;
                 const uint16_t* p = base + gk + (int64_t)gr * ld;
                 const int cnt = gr < nrows ? kc - gk : 0;
-                if (cnt >= 8 && vec_ok) {
-                    x = *reinterpret_cast<const uint4*>(p);
-                } else if (cnt > 0) {
-                    uint16_t e[8];
-#pragma unroll
-                    for (int j = 0; j < 8; j++) e[j] = j < cnt ? p[j] : (uint16_t)0;
-                    x.x = e[0] | ((uint32_t)e[1] << 16);
-                    x.y = e[2] | ((uint32_t)e[3] << 16);
-                    x.z = e[4] | ((uint32_t)e[5] << 16);
-                    x.w = e[6] | ((uint32_t)e[7] << 16);
-                }
+                if (cnt >= 8 && vec_ok) x = *reinterpret_cast<const uint4*>(p);
+                else if (cnt > 0) x = load8_guarded(p, cnt);
             }
             v[i] = x;
         }
@@ -105,17 +118,8 @@ struct LoaderR {
                 uint4 x = {0u, 0u, 0u, 0u};
                 if (gk < kc && cnt > 0) {
                     const uint16_t* p = base + gr + (int64_t)gk * ld;
-                    if (cnt >= 8 && vec_ok) {
-                        x = *reinterpret_cast<const uint4*>(p);
-                    } else {
-                        uint16_t e[8];
-#pragma unroll
-                        for (int j = 0; j < 8; j++) e[j] = j < cnt ? p[j] : (uint16_t)0;
-                        x.x = e[0] | ((uint32_t)e[1] << 16);
-                        x.y = e[2] | ((uint32_t)e[3] << 16);
-                        x.z = e[4] | ((uint32_t)e[5] << 16);
-                        x.w = e[6] | ((uint32_t)e[7] << 16);
-                    }
+                    if (cnt >= 8 && vec_ok) x = *reinterpret_cast<const uint4*>(p);
+                    else x = load8_guarded(p, cnt);
                 }
                 v[i][kk] = x;
             }
@@ -175,9 +179,10 @@ __device__ __forceinline__ float load_out(const uint16_t* p) { return __uint_as_
 template <typename TO, bool AKF, bool BKF, int WAVES_M, int WAVES_N, int WMB, int WNB, int BKT>
 __global__ void __launch_bounds__(256) gemm_bf16_kernel(const GemmArgs g) {
     constexpr int BM = 32 * WMB * WAVES_M, BN = 32 * WNB * WAVES_N;
-    constexpr int KP = BKT + 8;
-    constexpr int A_SZ = BM * KP, B_SZ = BN * KP;
-    __shared__ __attribute__((aligned(16))) uint16_t lds[2 * (A_SZ + B_SZ)];
+    constexpr int KP = BKT + 8, KS = BKT / 16;
+    constexpr int A_SZ = BM * KP, B_SZ = BN * KP, ST_SZ = A_SZ + B_SZ;
+    static_assert(KS % 2 == 0, "fragment buffers alternate per substep and must line up across steps");
+    __shared__ __attribute__((aligned(16))) uint16_t lds[3 * ST_SZ];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave % WAVES_M, wn = wave / WAVES_M;
@@ -208,8 +213,17 @@ __global__ void __launch_bounds__(256) gemm_bf16_kernel(const GemmArgs g) {
 #pragma unroll
             for (int i = 0; i < 16; i++) acc[bn][bm][i] = 0.f;
 
-    if (task.nchunk > 0) {
-        // uniform loop state lives in scalar registers (see the fp32 kernel)
+    // number of k-steps of the whole task
+    int T = 0;
+    if (table) {
+        for (int c = 0; c < task.nchunk; c++) T += (g.chunks[task.chunk0 + c].k + BKT - 1) / BKT;
+    } else if (task.nchunk > 0) {
+        T = (g.one_chunk.k + BKT - 1) / BKT;
+    }
+    T = __builtin_amdgcn_readfirstlane(T);
+
+    if (T > 0) {
+        // position of the next k-step to load; uniform state lives in scalar registers
         int c = 0, k0 = 0, chk = 0, chvec = 0, lda = 0, ldb = 0;
         const uint16_t* Ab = nullptr;
         const uint16_t* Bb = nullptr;
@@ -225,6 +239,7 @@ __global__ void __launch_bounds__(256) gemm_bf16_kernel(const GemmArgs g) {
         typename LoaderSel<AKF, BM, BKT>::type la;
         typename LoaderSel<BKF, BN, BKT>::type lb;
         const bool inside = m0 + BM <= task.m && n0 + BN <= task.n;
+        // loads the k-step at the current position into registers and moves the position on
         auto load_step = [&]() {
             if (inside && k0 + BKT <= chk && chvec == 3) {
                 la.load_fast(AKF ? Ab + k0 + (int64_t)m0 * lda : Ab + m0 + (int64_t)k0 * lda, lda, tid);
@@ -233,52 +248,73 @@ __global__ void __launch_bounds__(256) gemm_bf16_kernel(const GemmArgs g) {
                 la.load(Ab, lda, m0, task.m, k0, chk, chvec & 1, tid);
                 lb.load(Bb, ldb, n0, task.n, k0, chk, chvec & 2, tid);
             }
-        };
-        load_step();
-        int cur = 0;
-        la.store(lds, tid);
-        lb.store(lds + A_SZ, tid);
-        __syncthreads();
-        bool more = true;
-        while (more) {
             k0 += BKT;
             if (k0 >= chk) {
                 c++;
                 k0 = 0;
                 if (c < task.nchunk) set_chunk(g.chunks[task.chunk0 + c]);
             }
-            more = c < task.nchunk;
-            if (more) load_step();
-            const uint16_t* lA = lds + cur * (A_SZ + B_SZ);
+        };
+        auto store_step = [&](int stage) {
+            uint16_t* s = lds + stage * ST_SZ;
+            la.store(s, tid);
+            lb.store(s + A_SZ, tid);
+        };
+
+        // prologue: steps 0 and 1 into LDS, step 2 into registers
+        load_step();
+        store_step(0);
+        if (T > 1) { load_step(); store_step(1); }
+        bool in_regs = false;
+        if (T > 2) { load_step(); in_regs = true; }
+        __syncthreads();
+
+        bf16x8 pf[2][WNB], qf[2][WMB];
+        auto frags = [&](int buf, int stage, int ks) {
+            const uint16_t* lA = lds + stage * ST_SZ;
             const uint16_t* lB = lA + A_SZ;
-            // fragments of k-substep ks + 1 are requested from LDS before the matrix-core work of
-            // substep ks is issued, so that the LDS latency hides behind it
-            bf16x8 pf[2][WNB], qf[2][WMB];
-            auto frags = [&](int buf, int ks) {
 #pragma unroll
-                for (int bn = 0; bn < WNB; bn++)
-                    pf[buf][bn] = *reinterpret_cast<const bf16x8*>(&lB[((wn * WNB + bn) * 32 + r32) * KP + ks * 16 + half * 8]);
+            for (int bn = 0; bn < WNB; bn++)
+                pf[buf][bn] = *reinterpret_cast<const bf16x8*>(&lB[((wn * WNB + bn) * 32 + r32) * KP + ks * 16 + half * 8]);
 #pragma unroll
-                for (int bm = 0; bm < WMB; bm++)
-                    qf[buf][bm] = *reinterpret_cast<const bf16x8*>(&lA[((wm * WMB + bm) * 32 + r32) * KP + ks * 16 + half * 8]);
-            };
-            frags(0, 0);
+            for (int bm = 0; bm < WMB; bm++)
+                qf[buf][bm] = *reinterpret_cast<const bf16x8*>(&lA[((wm * WMB + bm) * 32 + r32) * KP + ks * 16 + half * 8]);
+        };
+        frags(0, 0, 0);
+        int stage = 0;                      // t % 3
+        for (int t = 0; t < T; t++) {
+            const int next_stage = stage == 2 ? 0 : stage + 1;
 #pragma unroll
-            for (int ks = 0; ks < BKT / 16; ks++) {
-                if (ks + 1 < BKT / 16) frags((ks + 1) & 1, ks + 1);
+            for (int ks = 0; ks < KS; ks++) {
+                // fragments of the next substep (of this step, or the first of the next step, which has
+                // been complete in LDS since the previous barrier) before the matrix work of this one
+                const int cur = ks & 1, nxt = cur ^ 1;
+                // (after the last step this reads a stale stage, in bounds and unused: keeping the reads
+                // unconditional keeps them in the same scheduling block as the matrix instructions)
+                if (ks + 1 < KS) frags(nxt, stage, ks + 1);
+                else frags(nxt, next_stage, 0);
 #pragma unroll
                 for (int bn = 0; bn < WNB; bn++)
 #pragma unroll
                     for (int bm = 0; bm < WMB; bm++)
-                        acc[bn][bm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf[ks & 1][bn], qf[ks & 1][bm], acc[bn][bm], 0, 0, 0);
+                        acc[bn][bm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf[cur][bn], qf[cur][bm], acc[bn][bm], 0, 0, 0);
+                // issue order: the LDS reads go out one per matrix instruction at the start of the substep,
+                // so that all of them have landed when the substep ends
+                constexpr int kReads = WNB + WMB, kMfma = WNB * WMB;
+#pragma unroll
+                for (int i = 0; i < kReads; i++) {
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    if (i < kMfma) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                }
+                if (kMfma > kReads) __builtin_amdgcn_sched_group_barrier(0x008, kMfma - kReads, 0);
             }
-            if (more) {
-                uint16_t* nA = lds + (cur ^ 1) * (A_SZ + B_SZ);
-                la.store(nA, tid);
-                lb.store(nA + A_SZ, tid);
+            if (in_regs) {                  // step t + 2, loaded during the previous step
+                store_step(next_stage == 2 ? 0 : next_stage + 1);
+                in_regs = false;
             }
+            if (t + 3 < T) { load_step(); in_regs = true; }
             __syncthreads();
-            cur ^= 1;
+            stage = next_stage;
         }
     }
 
