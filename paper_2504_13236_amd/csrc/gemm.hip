@@ -5,45 +5,45 @@
 #include "internal.hpp"
 
 #include <algorithm>
+#include <cstdlib>
 #include <sstream>
 
 namespace nnt {
 
-// One C tile of a split product: where its k-slices lie and where the result goes.
+// One macro-tile of C whose contraction was cut into k-slices: where the slices lie and where
+// the sum goes.
 struct SplitReduce {
-    void* C;
-    const float* bias;
-    const float* ws;        // slice s of element i at ws[s * count + i]
-    int64_t count;          // m * n * batch
-    int32_t m, nsplit;
+    void* C;                // base of the C tile
+    const float* bias;      // bias of the C tile (length m of the tile), or nullptr
+    const float* ws;        // slice s of element (i, j) of the macro-tile at ws[s * slice + j * ldw + i]
+    int64_t ldc, slice;
+    int32_t m0, n0, rows, cols, ldw, nsplit;
 };
 
 template <typename TO>
 __global__ void __launch_bounds__(256) splitk_reduce(const SplitReduce* tab, float alpha, float beta) {
     const SplitReduce t = tab[blockIdx.y];
-    const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
-    if (i >= t.count) return;               // count is a multiple of 4 only if m is; handled below
+    const int q = t.ldw >> 2;
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    const int i = (idx % q) << 2, j = idx / q;
+    if (j >= t.cols || i >= t.rows) return;
+    const int n = t.rows - i < 4 ? t.rows - i : 4;
     float acc[4] = {0.f, 0.f, 0.f, 0.f};
-    const int n = (int)((t.count - i) < 4 ? (t.count - i) : 4);
-    for (int s = 0; s < t.nsplit; s++) {
-        const float* p = t.ws + (int64_t)s * t.count + i;
-        if (n == 4 && (((uintptr_t)p & 15) == 0)) {
-            const float4 v = *reinterpret_cast<const float4*>(p);
-            acc[0] += v.x; acc[1] += v.y; acc[2] += v.z; acc[3] += v.w;
-        } else {
-            for (int j = 0; j < n; j++) acc[j] += p[j];
-        }
+    const float* p = t.ws + (int64_t)j * t.ldw + i;       // 16-byte aligned: ldw is a multiple of 4
+    for (int sl = 0; sl < t.nsplit; sl++) {
+        const float4 v = *reinterpret_cast<const float4*>(p + (int64_t)sl * t.slice);
+        acc[0] += v.x; acc[1] += v.y; acc[2] += v.z; acc[3] += v.w;
     }
-    TO* c = static_cast<TO*>(t.C) + i;
-    for (int j = 0; j < n; j++) {
-        float v = alpha * acc[j];
-        if (t.bias) v += t.bias[(i + j) % t.m];
+    TO* c = static_cast<TO*>(t.C) + (t.m0 + i) + (int64_t)(t.n0 + j) * t.ldc;
+    for (int jj = 0; jj < n; jj++) {
+        float v = alpha * acc[jj];
+        if (t.bias) v += t.bias[t.m0 + i + jj];
         if (beta != 0.f) {
-            if constexpr (sizeof(TO) == 4) v += beta * (float)c[j];
-            else v += beta * __uint_as_float((uint32_t)c[j] << 16);
+            if constexpr (sizeof(TO) == 4) v += beta * (float)c[jj];
+            else v += beta * __uint_as_float((uint32_t)c[jj] << 16);
         }
-        if constexpr (sizeof(TO) == 4) c[j] = v;
-        else { const __bf16 h = (__bf16)v; c[j] = __builtin_bit_cast(uint16_t, h); }
+        if constexpr (sizeof(TO) == 4) c[jj] = v;
+        else { const __bf16 h = (__bf16)v; c[jj] = __builtin_bit_cast(uint16_t, h); }
     }
 }
 
@@ -65,21 +65,19 @@ struct GemmPlan {
     GemmChunk* d_chunks = nullptr;
     GemmWg* d_wgs = nullptr;
     GemmWg* d_wgs_op = nullptr;
-    // Split form (one launch per operation only): every task is cut into `splits` k-slices that
-    // write raw fp32 sums to a scratch tile each; a second kernel adds the slices in a fixed order
-    // and applies alpha, beta and the bias.  Used when the unsplit grid cannot fill the chip.
+    // Whole-operation launches may cut the contraction of some macro-tiles (the last `n_split`
+    // of the launch order) into `splits` k-slices: each slice is a workgroup of its own that
+    // writes raw fp32 sums to scratch memory, and a second kernel adds the slices in a fixed
+    // order and applies alpha, beta and the bias.  The extra tasks and chunks of the slices
+    // follow the regular ones in the same device tables.
     int splits = 1;
-    int64_t sk_nwg = 0;
-    GemmTask* d_sk_tasks = nullptr;
-    GemmChunk* d_sk_chunks = nullptr;
-    GemmWg* d_sk_wgs = nullptr;
-    SplitReduce* d_sk_red = nullptr;
+    int64_t n_split = 0, op_nwg = 0;
+    int red_blocks = 0;
+    SplitReduce* d_red = nullptr;
     float* d_ws = nullptr;
-    int64_t sk_max_count = 0;
     TileDep ws_dep;
     ~GemmPlan() {
-        for (void* p : {(void*)d_tasks, (void*)d_chunks, (void*)d_wgs, (void*)d_wgs_op, (void*)d_sk_tasks, (void*)d_sk_chunks, (void*)d_sk_wgs,
-                        (void*)d_sk_red, (void*)d_ws})
+        for (void* p : {(void*)d_tasks, (void*)d_chunks, (void*)d_wgs, (void*)d_wgs_op, (void*)d_red, (void*)d_ws})
             if (p) (void)hipFree(p);
     }
 };
@@ -160,6 +158,61 @@ static void xcd_interleave(std::vector<GemmWg>& wgs, int bm, int bn) {
     wgs.swap(out);
 }
 
+// Cost model for a product of whole matrices (no batch axes): picks the macro-tile shape, how
+// many macro-tiles get their contraction cut into k-slices, and into how many.  The matrix cores
+// bound these kernels, so a compute unit that holds two workgroups needs twice as long as one
+// that holds one: a launch of W equal workgroups takes ceil(W / 256) workgroup times, plus the
+// start-up of a workgroup (first loads, result stores), which overlaps only with other
+// workgroups on the same unit.  A launch whose W is not a multiple of 256 leaves units idle in
+// its last round; cutting the W mod 256 macro-tiles of that round into s slices turns it into
+// 1/s of a round.  A launch with few macro-tiles cuts all of them.  Slices cost a second pass
+// over the fp32 partial results.  The rates are measured ones (large products of each shape);
+// the model only has to rank the candidates.
+constexpr int kSplitStep = 64;
+struct ShapeChoice { int cfg; int64_t n_split; int s; };
+static ShapeChoice choose_shape(bool bf16, bool out_f32, int akf, int bkf, const std::vector<int64_t>& tm,
+                                const std::vector<int64_t>& tn, const std::vector<int64_t>& ktot, bool may_split) {
+    struct Cand { int cfg; double flops_per_s_cu; double t0; };
+    static const Cand f32c[] = {{kCfgSquare, 0.515e12, 2.5e-6}, {kCfgMid, 0.45e12, 2.0e-6}};
+    static const Cand bf16c[] = {{kCfgSquare, 3.7e12, 5.0e-6}, {kCfgMid, 2.6e12, 3.0e-6}};
+    const Cand* cands = bf16 ? bf16c : f32c;
+    ShapeChoice best = {kCfgSquare, 0, 1};
+    double best_t = 1e30;
+    int64_t kmax = 0, kmin = INT64_MAX;
+    for (int64_t kq : ktot) { kmax = std::max(kmax, kq); kmin = std::min(kmin, kq); }
+    for (int ci = 0; ci < 2; ci++) {
+        const Cand& cd = cands[ci];
+        int bm, bn;
+        gemm_cfg_tile(bf16, cd.cfg, &bm, &bn);
+        const int occ = bf16 ? gemm_bf16_occupancy(out_f32, akf, bkf, cd.cfg) : gemm_f32_occupancy(akf, bkf, cd.cfg);
+        const int64_t G = 256 * (int64_t)occ;      // workgroups resident at a time
+        int64_t W = 0;
+        for (size_t i = 0; i < tm.size(); i++) W += ((tm[i] + bm - 1) / bm) * ((tn[i] + bn - 1) / bn);
+        auto tile_time = [&](int64_t k) { return 2.0 * bm * bn * (double)k / cd.flops_per_s_cu; };
+        // X equal workgroups: whole resident sets, each as slow as `occ` workgroups in a row on
+        // every unit, then a last set spread over the units
+        auto group_time = [&](int64_t X, int64_t k) {
+            return ((double)(X / G) * occ + (double)((X % G + 255) / 256)) * tile_time(k) + (double)((X + G - 1) / G) * cd.t0;
+        };
+        const double t_plain = group_time(W, kmax);
+        if (t_plain < best_t) { best_t = t_plain; best = {cd.cfg, 0, 1}; }
+        if (!may_split) continue;
+        const int64_t R = W % G;
+        const int64_t ns_cands[2] = {W, (W > G && R > 0) ? R : 0};
+        for (int64_t ns : ns_cands) {
+            if (ns <= 0) continue;
+            for (int sp = 2; sp <= 32; sp++) {
+                const int64_t part = ((kmax + sp - 1) / sp + kSplitStep - 1) / kSplitStep * kSplitStep;
+                if (part < 256 || part * (sp - 1) >= kmin) break;
+                const double t = (ns < W ? group_time(W - ns, kmax) : 0.0) + group_time(ns * sp, part) + 6e-6 +
+                                 (double)ns * bm * bn * 4.0 * (sp + 1) / 3.5e12;
+                if (t < best_t) { best_t = t; best = {cd.cfg, ns, sp}; }
+            }
+        }
+    }
+    return best;
+}
+
 static int pick_cfg(int bf16, int64_t m_max, int64_t n_max, int64_t n_tiles_big) {
     if (m_max <= 64) return kCfgSkinny64;
     if (m_max <= 128 && n_max > 128) return kCfgSkinny128;
@@ -209,7 +262,8 @@ extern "C" int32_t nnt_tile_gemm(void* stream, int32_t dtype_in, int32_t dtype_o
     g.alpha = alpha;
     g.beta = beta;
     int bm, bn;
-    const int cfg = pick_cfg(bf, m, n, ((m + 255) / 256) * ((n + 255) / 256) * batch);
+    int cfg = pick_cfg(bf, m, n, ((m + 255) / 256) * ((n + 255) / 256) * batch);
+    if (batch == 1 && (cfg == kCfgSquare || cfg == kCfgMid)) cfg = choose_shape(bf, dtype_out == NNT_F32, opA == NNT_OP_T, opB == NNT_OP_N, {m}, {n}, {k}, false).cfg;
     gemm_cfg_tile(bf, cfg, &bm, &bn);
     g.grid_m = (int32_t)((m + bm - 1) / bm);
     g.grid_n = (int32_t)((n + bn - 1) / bn);
@@ -337,18 +391,41 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
         n_max = std::max(n_max, n);
         big += ((m + 255) / 256) * ((n + 255) / 256) * batch;
     }
-    P->cfg = pick_cfg(A->dtype == NNT_BF16, m_max, n_max, big);
+    const bool bf = A->dtype == NNT_BF16;
+    std::vector<int64_t> ktot(P->tasks.size(), 0);
+    for (size_t ti = 0; ti < P->tasks.size(); ti++)
+        for (int32_t q = P->tasks[ti].chunk0; q < P->tasks[ti].chunk0 + P->tasks[ti].nchunk; q++) ktot[ti] += P->chunks[q].k;
+    P->cfg = pick_cfg(bf, m_max, n_max, big);
+    int S = 1;
+    int64_t n_split = 0;
+    if (nbat == 0 && !P->tasks.empty() && (P->cfg == kCfgSquare || P->cfg == kCfgMid)) {
+        // products of whole matrices: macro-tile shape and k-slices by the cost model
+        std::vector<int64_t> tm, tn;
+        for (const TaskGeom& gq : geom) { tm.push_back(gq.m); tn.push_back(gq.n); }
+        const ShapeChoice sc = choose_shape(bf, C->dtype == NNT_F32, P->akf, P->bkf, tm, tn, ktot, true);
+        P->cfg = sc.cfg;
+        S = sc.s;
+        n_split = sc.n_split;
+    }
     int bm, bn;
-    gemm_cfg_tile(A->dtype == NNT_BF16, P->cfg, &bm, &bn);
+    gemm_cfg_tile(bf, P->cfg, &bm, &bn);
     {
         // spelled like the demangled kernel name, so that profiler output can be matched against it
         static const char* const shape[4] = {"2, 2, 4, 4", "2, 2, 2, 2", "1, 4, 2, 2", "1, 4, 4, 2"};
         std::ostringstream l;
         const char* tf[2] = {"false", "true"};
-        if (A->dtype == NNT_F32) l << "gemm_f32_kernel<" << tf[P->akf] << ", " << tf[P->bkf] << ", " << shape[P->cfg == kCfgSquare ? 1 : P->cfg] << ">";
+        if (A->dtype == NNT_F32) l << "gemm_f32_kernel<" << tf[P->akf] << ", " << tf[P->bkf] << ", " << (P->cfg == kCfgSquare ? "2, 2, 2, 2" : P->cfg == kCfgMid ? "2, 2, 1, 2" : shape[P->cfg]) << ">";
         else l << "gemm_bf16_kernel<" << (C->dtype == NNT_F32 ? "float" : "unsigned short") << ", " << tf[P->akf] << ", " << tf[P->bkf]
                << ", " << shape[P->cfg] << ", 32>";
         if (nbat > 0) l << " batched";     // per-head attention products: short contractions, memory-leaning
+        if (getenv("NNT_LABEL_SHAPES")) {  // one profile line per product shape instead of per kernel instance
+            int64_t kmax = 0;
+            for (int64_t kq : ktot) kmax = std::max(kmax, kq);
+            int64_t rows = 1, cols = 1;
+            for (int i = 0; i < nfa; i++) rows *= C->shape[i];
+            for (int i = nfa; i < nfa + nfb; i++) cols *= C->shape[i];
+            l << " [" << rows << " x " << cols << ", k/tile " << kmax << ", " << n_split << " macro-tiles in " << S << " slices]";
+        }
         P->label = l.str();
     }
     // Workgroup order inside a task: m index fastest, so that workgroups in flight
@@ -367,90 +444,79 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
     P->wgs_op = P->wgs;
     xcd_interleave(P->wgs_op, bm, bn);
 
-    // ---- split form
-    const int64_t W = (int64_t)P->wgs.size();
-    const int kstep = 64;
-    int64_t kmin = INT64_MAX;
-    std::vector<int64_t> ktot(P->tasks.size(), 0);
-    for (size_t ti = 0; ti < P->tasks.size(); ti++) {
-        for (int32_t q = P->tasks[ti].chunk0; q < P->tasks[ti].chunk0 + P->tasks[ti].nchunk; q++) ktot[ti] += P->chunks[q].k;
-        kmin = std::min(kmin, ktot[ti]);
-    }
-    int S = 1;
-    if (W > 0 && W < 480 && nbat == 0) {
-        const int cands[] = {2, 3, 4, 6, 8, 12, 16};
-        int best = 1;
-        for (int c : cands) {
-            if (kmin / c < 256) break;
-            best = c;
-            const double eff = (double)(W * c) / (double)(((W * c + 255) / 256) * 256);
-            if (W * c >= 480 && eff >= 0.8) break;
-        }
-        S = best;
-    }
+    // ---- k-slices for the last n_split macro-tiles of the whole-operation order
     P->splits = S;
-    if (S > 1) {
-        std::vector<GemmTask> tasks;
-        std::vector<GemmChunk> chunks;
-        std::vector<GemmWg> wgs;
-        std::vector<SplitReduce> red;
-        int64_t ws_elems = 0;
-        for (size_t ti = 0; ti < P->tasks.size(); ti++) ws_elems += (int64_t)S * geom[ti].m * geom[ti].n * geom[ti].batch;
-        NNT_HIP(ctx, hipMalloc((void**)&P->d_ws, ws_elems * sizeof(float)));
-        int64_t ws_off = 0;
-        for (size_t ti = 0; ti < P->tasks.size(); ti++) {
-            const GemmTask& t0 = P->tasks[ti];
-            const int64_t count = geom[ti].m * geom[ti].n * geom[ti].batch;
-            const int64_t part = ((ktot[ti] + S - 1) / S + kstep - 1) / kstep * kstep;
-            SplitReduce r;
-            r.C = t0.C; r.bias = t0.bias; r.ws = P->d_ws + ws_off; r.count = count; r.m = t0.m; r.nsplit = S;
-            red.push_back(r);
-            P->sk_max_count = std::max(P->sk_max_count, count);
+    P->n_split = n_split = std::min<int64_t>(n_split, (int64_t)P->wgs_op.size());
+    if (S > 1 && n_split > 0) {
+        const size_t keep = P->wgs_op.size() - (size_t)n_split;
+        const std::vector<GemmWg> cut(P->wgs_op.begin() + keep, P->wgs_op.end());
+        P->wgs_op.resize(keep);
+        const int64_t slice = (int64_t)bm * bn;
+        NNT_HIP(ctx, hipMalloc((void**)&P->d_ws, (size_t)n_split * S * slice * sizeof(float)));
+        // chunk ranges of the slices, built once per C tile
+        std::vector<std::vector<std::pair<int32_t, int32_t>>> ranges(P->tasks.size());
+        auto slice_chunks = [&](int32_t ti) {
+            if (!ranges[ti].empty()) return;
+            const GemmTask t0 = P->tasks[ti];
+            const int64_t part = ((ktot[ti] + S - 1) / S + kSplitStep - 1) / kSplitStep * kSplitStep;
             int32_t q = t0.chunk0;
             int64_t used = 0;                       // k already consumed of chunk q
             for (int sidx = 0; sidx < S; sidx++) {
-                GemmTask t = t0;
-                t.C = P->d_ws + ws_off + (int64_t)sidx * count;
-                t.bias = nullptr;
-                t.partial = 1;
-                t.chunk0 = (int32_t)chunks.size();
+                const int32_t c0i = (int32_t)P->chunks.size();
                 int64_t want = part;
                 while (want > 0 && q < t0.chunk0 + t0.nchunk) {
-                    const GemmChunk& c0 = P->chunks[q];
+                    const GemmChunk c0 = P->chunks[q];
                     const int64_t take = std::min<int64_t>(want, c0.k - used);
                     GemmChunk c = c0;
                     c.A = static_cast<const char*>(c0.A) + used * (P->akf ? 1 : c0.lda) * elem;
                     c.B = static_cast<const char*>(c0.B) + used * (P->bkf ? 1 : c0.ldb) * elem;
                     c.k = (int32_t)take;
                     c.vec_ok = vec_flag(c.A, c.lda, c.strideA, elem) | (vec_flag(c.B, c.ldb, c.strideB, elem) << 1);
-                    chunks.push_back(c);
+                    P->chunks.push_back(c);
                     want -= take;
                     used += take;
                     if (used == c0.k) { q++; used = 0; }
                 }
-                t.nchunk = (int32_t)chunks.size() - t.chunk0;
-                const int32_t tid = (int32_t)tasks.size();
-                tasks.push_back(t);
-                const int64_t gm = (geom[ti].m + bm - 1) / bm, gn = (geom[ti].n + bn - 1) / bn;
-                for (int64_t b = 0; b < geom[ti].batch; b++)
-                    for (int64_t j = 0; j < gn; j++)
-                        for (int64_t i = 0; i < gm; i++)
-                            wgs.push_back(GemmWg{tid, (int32_t)(i * bm), (int32_t)(j * bn), (int32_t)b});
+                ranges[ti].push_back({c0i, (int32_t)P->chunks.size() - c0i});
             }
-            ws_off += (int64_t)S * count;
-        }
-        P->sk_nwg = (int64_t)wgs.size();
-        xcd_interleave(wgs, bm, bn);
-        auto up2 = [&](void** d, const void* h, size_t bytes) -> hipError_t {
-            hipError_t e = hipMalloc(d, bytes);
-            if (e != hipSuccess) return e;
-            return hipMemcpy(*d, h, bytes, hipMemcpyHostToDevice);
         };
-        NNT_HIP(ctx, up2((void**)&P->d_sk_tasks, tasks.data(), tasks.size() * sizeof(GemmTask)));
-        NNT_HIP(ctx, up2((void**)&P->d_sk_chunks, chunks.data(), chunks.size() * sizeof(GemmChunk)));
-        NNT_HIP(ctx, up2((void**)&P->d_sk_wgs, wgs.data(), wgs.size() * sizeof(GemmWg)));
-        NNT_HIP(ctx, up2((void**)&P->d_sk_red, red.data(), red.size() * sizeof(SplitReduce)));
+        std::vector<SplitReduce> red;
+        std::vector<std::vector<GemmWg>> by_slice(S);
+        for (size_t w = 0; w < cut.size(); w++) {
+            const GemmWg& mw = cut[w];
+            slice_chunks(mw.task);
+            const GemmTask t0 = P->tasks[mw.task];
+            float* block = P->d_ws + (int64_t)w * S * slice;
+            SplitReduce r;
+            r.C = t0.C; r.bias = t0.bias; r.ws = block; r.ldc = t0.ldc; r.slice = slice;
+            r.m0 = mw.m0; r.n0 = mw.n0;
+            r.rows = std::min<int32_t>(bm, t0.m - mw.m0);
+            r.cols = std::min<int32_t>(bn, t0.n - mw.n0);
+            r.ldw = bm; r.nsplit = S;
+            red.push_back(r);
+            for (int sidx = 0; sidx < S; sidx++) {
+                GemmTask t = t0;
+                // element (m0 + i, n0 + j) of the "tile" lands on block[i + j * bm] of this slice
+                t.C = block + (int64_t)sidx * slice - (mw.m0 + (int64_t)mw.n0 * bm);
+                t.ldc = bm;
+                t.strideC = 0;
+                t.bias = nullptr;
+                t.partial = 1;
+                t.chunk0 = ranges[mw.task][sidx].first;
+                t.nchunk = ranges[mw.task][sidx].second;
+                by_slice[sidx].push_back(GemmWg{(int32_t)P->tasks.size(), mw.m0, mw.n0, 0});
+                P->tasks.push_back(t);
+            }
+        }
+        for (int sidx = 0; sidx < S; sidx++) P->wgs_op.insert(P->wgs_op.end(), by_slice[sidx].begin(), by_slice[sidx].end());
+        P->red_blocks = (int)((slice / 4 + 255) / 256);
+        NNT_HIP(ctx, hipMalloc((void**)&P->d_red, red.size() * sizeof(SplitReduce)));
+        NNT_HIP(ctx, hipMemcpy(P->d_red, red.data(), red.size() * sizeof(SplitReduce), hipMemcpyHostToDevice));
+    } else {
+        P->splits = 1;
+        P->n_split = 0;
     }
+    P->op_nwg = (int64_t)P->wgs_op.size();
 
     auto up = [&](void** d, const void* h, size_t bytes) -> hipError_t {
         if (bytes == 0) return hipSuccess;
@@ -498,20 +564,16 @@ extern "C" int32_t nnt_gemm(nnt_ctx* ctx, float alpha, int32_t opA, nnt_tensor* 
         std::vector<Access> acc = {A->all(kRead), B->all(kRead), C->all(cmode)};
         if (bias) acc.push_back(bias->all(kRead));
         g.wgs = P->d_wgs_op;
-        const int64_t nwg = (int64_t)P->wgs.size();
+        const int64_t nwg = P->op_nwg;
         if (nwg == 0) return NNT_OK;
-        if (P->splits > 1) {
+        if (P->n_split > 0) {
             acc.push_back(Access{&P->ws_dep, 1, kReadWrite});
-            g.tasks = P->d_sk_tasks;
-            g.chunks = P->d_sk_chunks;
-            g.wgs = P->d_sk_wgs;
-            const int64_t sk_nwg = P->sk_nwg, ntasks = (int64_t)P->tasks.size(), mx = P->sk_max_count;
             return submit(ctx, acc, [=](hipStream_t st) {
-                int32_t rc = launch_any(st, P->dtype_in, P->dtype_out, P->akf, P->bkf, P->cfg, g, sk_nwg);
+                int32_t rc = launch_any(st, P->dtype_in, P->dtype_out, P->akf, P->bkf, P->cfg, g, nwg);
                 if (rc != NNT_OK) return rc;
-                const dim3 grid((unsigned)((mx + 1023) / 1024), (unsigned)ntasks), block(256);
-                if (P->dtype_out == NNT_F32) hipLaunchKernelGGL((splitk_reduce<float>), grid, block, 0, st, P->d_sk_red, alpha, beta);
-                else hipLaunchKernelGGL((splitk_reduce<uint16_t>), grid, block, 0, st, P->d_sk_red, alpha, beta);
+                const dim3 grid((unsigned)P->red_blocks, (unsigned)P->n_split), block(256);
+                if (P->dtype_out == NNT_F32) hipLaunchKernelGGL((splitk_reduce<float>), grid, block, 0, st, P->d_red, alpha, beta);
+                else hipLaunchKernelGGL((splitk_reduce<uint16_t>), grid, block, 0, st, P->d_red, alpha, beta);
                 return hipGetLastError() == hipSuccess ? (int32_t)NNT_OK : (int32_t)NNT_EHIP;
             }, 2);
         }
@@ -519,7 +581,8 @@ extern "C" int32_t nnt_gemm(nnt_ctx* ctx, float alpha, int32_t opA, nnt_tensor* 
             return launch_any(st, P->dtype_in, P->dtype_out, P->akf, P->bkf, P->cfg, g, nwg);
         });
     }
-    for (size_t ti = 0; ti < P->tasks.size(); ti++) {
+    const size_t n_tile_tasks = P->task_ctile.size();
+    for (size_t ti = 0; ti < n_tile_tasks; ti++) {
         std::vector<Access> acc;
         acc.push_back(C->one(P->task_ctile[ti], cmode));
         for (int64_t a : P->task_atiles[ti]) acc.push_back(A->one(a, kRead));

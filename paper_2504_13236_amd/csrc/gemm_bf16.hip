@@ -176,6 +176,97 @@ __device__ __forceinline__ void store_out(uint16_t* p, float v) {
 __device__ __forceinline__ float load_out(const float* p) { return *p; }
 __device__ __forceinline__ float load_out(const uint16_t* p) { return __uint_as_float((uint32_t)*p << 16); }
 
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// Writes one wave's (32 WMB) x (32 WNB) block of C = alpha * acc + bias + beta * C.  `stage` is
+// 32 rows of 32 WMB + 4 floats of LDS owned by the wave; every wave of the workgroup must call
+// this (it synchronises the workgroup between the passes).  Vector stores need a 16-byte
+// aligned tile and leading dimension; anything else, and the ragged edge, goes element by element.
+template <typename TO, int WMB, int WNB>
+__device__ __forceinline__ void write_tile(float* stage, const f32x16 (&acc)[WNB][WMB], TO* C, int64_t ldc,
+                                           const float* bias, float alpha, float beta, int m_base, int n_base,
+                                           int m_lim, int n_lim, int lane) {
+    constexpr int MW = 32 * WMB, ROW = MW + 4;
+    constexpr int V = 16 / (int)sizeof(TO);          // elements per 16-byte store
+    constexpr int CH = MW / V, RPI = 64 / CH;        // vectors per row, rows per pass of the wave
+    static_assert(CH <= 64 && 32 % RPI == 0, "row shape");
+    const int r32 = lane & 31, half = lane >> 5;
+    const bool vec_ok = (reinterpret_cast<uintptr_t>(C) % 16 == 0) && (ldc % V == 0);
+#pragma unroll
+    for (int bn = 0; bn < WNB; bn++) {
+#pragma unroll
+        for (int bm = 0; bm < WMB; bm++)
+#pragma unroll
+            for (int q = 0; q < 4; q++) {
+                f32x4 v;
+                v[0] = alpha * acc[bn][bm][4 * q];
+                v[1] = alpha * acc[bn][bm][4 * q + 1];
+                v[2] = alpha * acc[bn][bm][4 * q + 2];
+                v[3] = alpha * acc[bn][bm][4 * q + 3];
+                *reinterpret_cast<f32x4*>(&stage[r32 * ROW + bm * 32 + 8 * q + 4 * half]) = v;
+            }
+        __syncthreads();
+#pragma unroll
+        for (int it = 0; it < 32 / RPI; it++) {
+            const int row = it * RPI + lane / CH, mc = (lane % CH) * V;
+            float v[V];
+#pragma unroll
+            for (int j = 0; j < V; j += 4) {
+                const f32x4 x = *reinterpret_cast<const f32x4*>(&stage[row * ROW + mc + j]);
+                v[j] = x[0]; v[j + 1] = x[1]; v[j + 2] = x[2]; v[j + 3] = x[3];
+            }
+            const int gn = n_base + bn * 32 + row, gm = m_base + mc;
+            if (gn < n_lim && gm < m_lim) {
+                TO* p = C + gm + (int64_t)gn * ldc;
+                if (vec_ok && gm + V <= m_lim) {
+                    if (bias) {
+#pragma unroll
+                        for (int j = 0; j < V; j += 4) {
+                            const f32x4 bv = *reinterpret_cast<const f32x4*>(bias + gm + j);
+                            v[j] += bv[0]; v[j + 1] += bv[1]; v[j + 2] += bv[2]; v[j + 3] += bv[3];
+                        }
+                    }
+                    if constexpr (sizeof(TO) == 4) {
+                        if (beta != 0.f) {
+                            const f32x4 c = *reinterpret_cast<const f32x4*>(p);
+                            v[0] += beta * c[0]; v[1] += beta * c[1]; v[2] += beta * c[2]; v[3] += beta * c[3];
+                        }
+                        f32x4 o = {v[0], v[1], v[2], v[3]};
+                        *reinterpret_cast<f32x4*>(p) = o;
+                    } else {
+                        if (beta != 0.f) {
+                            const uint4 c = *reinterpret_cast<const uint4*>(p);
+                            const uint32_t w[4] = {c.x, c.y, c.z, c.w};
+#pragma unroll
+                            for (int j = 0; j < 4; j++) {
+                                v[2 * j] += beta * __uint_as_float(w[j] << 16);
+                                v[2 * j + 1] += beta * __uint_as_float(w[j] & 0xffff0000u);
+                            }
+                        }
+                        uint32_t w[4];
+#pragma unroll
+                        for (int j = 0; j < 4; j++) {
+                            const __bf16 lo = (__bf16)v[2 * j], hi = (__bf16)v[2 * j + 1];
+                            w[j] = (uint32_t)__builtin_bit_cast(uint16_t, lo) | ((uint32_t)__builtin_bit_cast(uint16_t, hi) << 16);
+                        }
+                        *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[2], w[3]);
+                    }
+                } else {
+#pragma unroll
+                    for (int j = 0; j < V; j++) {
+                        if (gm + j < m_lim) {
+                            float x = v[j] + (bias ? bias[gm + j] : 0.f);
+                            if (beta != 0.f) x += beta * load_out(p + j);
+                            store_out(p + j, x);
+                        }
+                    }
+                }
+            }
+        }
+        __syncthreads();
+    }
+}
+
 template <typename TO, bool AKF, bool BKF, int WAVES_M, int WAVES_N, int WMB, int WNB, int BKT>
 __global__ void __launch_bounds__(256) gemm_bf16_kernel(const GemmArgs g) {
     constexpr int BM = 32 * WMB * WAVES_M, BN = 32 * WNB * WAVES_N;
@@ -297,7 +388,7 @@ __global__ void __launch_bounds__(256) gemm_bf16_kernel(const GemmArgs g) {
                 for (int bn = 0; bn < WNB; bn++)
 #pragma unroll
                     for (int bm = 0; bm < WMB; bm++)
-                        acc[bn][bm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf[cur][bn], qf[cur][bm], acc[bn][bm], 0, 0, 0);
+                        acc[bn][bm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[cur][bm], pf[cur][bn], acc[bn][bm], 0, 0, 0);
                 // issue order: the LDS reads go out one per matrix instruction at the start of the substep,
                 // so that all of them have landed when the substep ends
                 constexpr int kReads = WNB + WMB, kMfma = WNB * WMB;
@@ -318,78 +409,55 @@ __global__ void __launch_bounds__(256) gemm_bf16_kernel(const GemmArgs g) {
         }
     }
 
-    const float alpha = g.alpha, beta = g.beta;
+    // The matrix-core "A" operand carries the rows of C (index m): a lane holds, for column
+    // n = lane % 32 of each 32 x 32 block, the rows 8 * (i / 4) + 4 * half + i % 4.  Results go
+    // through a per-wave LDS buffer (the pipeline stages are free by now) so that they leave as
+    // 16-byte vectors along m, the contiguous index of the C tile.
+    float* stage = reinterpret_cast<float*>(lds) + wave * (32 * (32 * WMB + 4));
+    static_assert(4 * 32 * (32 * WMB + 4) * 4 <= 3 * ST_SZ * 2, "result staging must fit the pipeline's LDS");
+    const int m_base = m0 + wm * WMB * 32, n_base = n0 + wn * WNB * 32;
     if (task.partial) {
         // one k-slice of a split product: raw fp32 sums into the scratch tile
-        float* Cp = static_cast<float*>(task.C) + (int64_t)bat * task.strideC;
-#pragma unroll
-        for (int bm = 0; bm < WMB; bm++) {
-            const int gm = m0 + (wm * WMB + bm) * 32 + r32;
-            if (gm >= task.m) continue;
-#pragma unroll
-            for (int bn = 0; bn < WNB; bn++) {
-#pragma unroll
-                for (int i = 0; i < 16; i++) {
-                    const int gn = n0 + (wn * WNB + bn) * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
-                    if (gn < task.n) Cp[gm + (int64_t)gn * task.ldc] = acc[bn][bm][i];
-                }
-            }
-        }
-        return;
-    }
-    TO* C = static_cast<TO*>(task.C) + (int64_t)bat * task.strideC;
-#pragma unroll
-    for (int bm = 0; bm < WMB; bm++) {
-        const int gm = m0 + (wm * WMB + bm) * 32 + r32;
-        if (gm >= task.m) continue;
-        const float bias = task.bias ? task.bias[gm] : 0.f;
-#pragma unroll
-        for (int bn = 0; bn < WNB; bn++) {
-#pragma unroll
-            for (int i = 0; i < 16; i++) {
-                const int gn = n0 + (wn * WNB + bn) * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
-                if (gn < task.n) {
-                    TO* p = C + gm + (int64_t)gn * task.ldc;
-                    float v = alpha * acc[bn][bm][i] + bias;
-                    if (beta != 0.f) v += beta * load_out(p);
-                    store_out(p, v);
-                }
-            }
-        }
+        write_tile<float, WMB, WNB>(stage, acc, static_cast<float*>(task.C) + (int64_t)bat * task.strideC, task.ldc, nullptr,
+                                    1.f, 0.f, m_base, n_base, task.m, task.n, lane);
+    } else {
+        write_tile<TO, WMB, WNB>(stage, acc, static_cast<TO*>(task.C) + (int64_t)bat * task.strideC, task.ldc, task.bias,
+                                 g.alpha, g.beta, m_base, n_base, task.m, task.n, lane);
     }
 }
 
+using KernelFn = void (*)(const GemmArgs);
+
 template <typename TO, bool AKF, bool BKF>
-int32_t launch_cfg(hipStream_t st, int cfg, const GemmArgs& g, int64_t nwg) {
-    dim3 grid((unsigned)nwg), block(256);
+KernelFn kernel_of(int cfg) {
     switch (cfg) {
-        case kCfgSquare:
-            hipLaunchKernelGGL((gemm_bf16_kernel<TO, AKF, BKF, 2, 2, 4, 4, 32>), grid, block, 0, st, g);
-            break;
-        case kCfgMid:
-            hipLaunchKernelGGL((gemm_bf16_kernel<TO, AKF, BKF, 2, 2, 2, 2, 32>), grid, block, 0, st, g);
-            break;
-        case kCfgSkinny64:
-            hipLaunchKernelGGL((gemm_bf16_kernel<TO, AKF, BKF, 1, 4, 2, 2, 32>), grid, block, 0, st, g);
-            break;
-        default:
-            hipLaunchKernelGGL((gemm_bf16_kernel<TO, AKF, BKF, 1, 4, 4, 2, 32>), grid, block, 0, st, g);
-            break;
+        case kCfgSquare: return gemm_bf16_kernel<TO, AKF, BKF, 2, 2, 4, 4, 32>;
+        case kCfgMid: return gemm_bf16_kernel<TO, AKF, BKF, 2, 2, 2, 2, 32>;
+        case kCfgSkinny64: return gemm_bf16_kernel<TO, AKF, BKF, 1, 4, 2, 2, 32>;
+        default: return gemm_bf16_kernel<TO, AKF, BKF, 1, 4, 4, 2, 32>;
     }
-    return hipGetLastError() == hipSuccess ? NNT_OK : NNT_EHIP;
 }
 
 template <typename TO>
-int32_t launch_ops(hipStream_t st, int akf, int bkf, int cfg, const GemmArgs& g, int64_t nwg) {
-    if (akf) return bkf ? launch_cfg<TO, true, true>(st, cfg, g, nwg) : launch_cfg<TO, true, false>(st, cfg, g, nwg);
-    return bkf ? launch_cfg<TO, false, true>(st, cfg, g, nwg) : launch_cfg<TO, false, false>(st, cfg, g, nwg);
+KernelFn kernel_of(int akf, int bkf, int cfg) {
+    if (akf) return bkf ? kernel_of<TO, true, true>(cfg) : kernel_of<TO, true, false>(cfg);
+    return bkf ? kernel_of<TO, false, true>(cfg) : kernel_of<TO, false, false>(cfg);
 }
 
 }  // namespace
 
 int32_t launch_gemm_bf16(hipStream_t st, int out_is_f32, int akf, int bkf, int cfg, const GemmArgs& g, int64_t nwg) {
     if (nwg <= 0) return NNT_OK;
-    return out_is_f32 ? launch_ops<float>(st, akf, bkf, cfg, g, nwg) : launch_ops<uint16_t>(st, akf, bkf, cfg, g, nwg);
+    const KernelFn fn = out_is_f32 ? kernel_of<float>(akf, bkf, cfg) : kernel_of<uint16_t>(akf, bkf, cfg);
+    hipLaunchKernelGGL(fn, dim3((unsigned)nwg), dim3(256), 0, st, g);
+    return hipGetLastError() == hipSuccess ? NNT_OK : NNT_EHIP;
+}
+
+int gemm_bf16_occupancy(int out_is_f32, int akf, int bkf, int cfg) {
+    const KernelFn fn = out_is_f32 ? kernel_of<float>(akf, bkf, cfg) : kernel_of<uint16_t>(akf, bkf, cfg);
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, fn, 256, 0) != hipSuccess || n < 1) n = 1;
+    return n;
 }
 
 }  // namespace nnt

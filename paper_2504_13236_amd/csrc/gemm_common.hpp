@@ -47,7 +47,7 @@ struct GemmArgs {
 // Macro-tile configurations.  M counts rows of C (first, fastest axis), N columns.
 enum GemmCfg {
     kCfgSquare = 0,   // f32 128 x 128, bf16 256 x 256
-    kCfgMid = 1,      // f32 128 x 128, bf16 128 x 128
+    kCfgMid = 1,      // f32 64 x 128, bf16 128 x 128
     kCfgSkinny64 = 2, // 64 x 256   (attention products with m = head size 64)
     kCfgSkinny128 = 3 // 128 x 256  (head size 128)
 };
@@ -55,7 +55,7 @@ enum GemmCfg {
 inline void gemm_cfg_tile(int dtype_is_bf16, int cfg, int* bm, int* bn) {
     switch (cfg) {
         case kCfgSquare: *bm = *bn = dtype_is_bf16 ? 256 : 128; break;
-        case kCfgMid: *bm = *bn = 128; break;
+        case kCfgMid: *bm = dtype_is_bf16 ? 128 : 64; *bn = 128; break;
         case kCfgSkinny64: *bm = 64; *bn = 256; break;
         default: *bm = 128; *bn = 256; break;
     }
@@ -63,5 +63,8 @@ inline void gemm_cfg_tile(int dtype_is_bf16, int cfg, int* bm, int* bn) {
 
 int32_t launch_gemm_f32(hipStream_t st, int akf, int bkf, int cfg, const GemmArgs& g, int64_t nwg);
 int32_t launch_gemm_bf16(hipStream_t st, int out_is_f32, int akf, int bkf, int cfg, const GemmArgs& g, int64_t nwg);
+// workgroups of the kernel instance that a compute unit holds at a time (registers, LDS)
+int gemm_f32_occupancy(int akf, int bkf, int cfg);
+int gemm_bf16_occupancy(int out_is_f32, int akf, int bkf, int cfg);
 
 }  // namespace nnt

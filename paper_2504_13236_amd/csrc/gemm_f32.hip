@@ -233,30 +233,35 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(const GemmArgs g) {
     }
 }
 
+using KernelFn = void (*)(const GemmArgs);
+
 template <bool AKF, bool BKF>
-int32_t launch_cfg(hipStream_t st, int cfg, const GemmArgs& g, int64_t nwg) {
-    dim3 grid((unsigned)nwg), block(256);
+KernelFn kernel_of(int cfg) {
     switch (cfg) {
-        case kCfgSquare:
-        case kCfgMid:
-            hipLaunchKernelGGL((gemm_f32_kernel<AKF, BKF, 2, 2, 2, 2>), grid, block, 0, st, g);
-            break;
-        case kCfgSkinny64:
-            hipLaunchKernelGGL((gemm_f32_kernel<AKF, BKF, 1, 4, 2, 2>), grid, block, 0, st, g);
-            break;
-        default:
-            hipLaunchKernelGGL((gemm_f32_kernel<AKF, BKF, 1, 4, 4, 2>), grid, block, 0, st, g);
-            break;
+        case kCfgSquare: return gemm_f32_kernel<AKF, BKF, 2, 2, 2, 2>;
+        case kCfgMid: return gemm_f32_kernel<AKF, BKF, 2, 2, 1, 2>;
+        case kCfgSkinny64: return gemm_f32_kernel<AKF, BKF, 1, 4, 2, 2>;
+        default: return gemm_f32_kernel<AKF, BKF, 1, 4, 4, 2>;
     }
-    return hipGetLastError() == hipSuccess ? NNT_OK : NNT_EHIP;
+}
+
+KernelFn kernel_of(int akf, int bkf, int cfg) {
+    if (akf) return bkf ? kernel_of<true, true>(cfg) : kernel_of<true, false>(cfg);
+    return bkf ? kernel_of<false, true>(cfg) : kernel_of<false, false>(cfg);
 }
 
 }  // namespace
 
 int32_t launch_gemm_f32(hipStream_t st, int akf, int bkf, int cfg, const GemmArgs& g, int64_t nwg) {
     if (nwg <= 0) return NNT_OK;
-    if (akf) return bkf ? launch_cfg<true, true>(st, cfg, g, nwg) : launch_cfg<true, false>(st, cfg, g, nwg);
-    return bkf ? launch_cfg<false, true>(st, cfg, g, nwg) : launch_cfg<false, false>(st, cfg, g, nwg);
+    hipLaunchKernelGGL(kernel_of(akf, bkf, cfg), dim3((unsigned)nwg), dim3(256), 0, st, g);
+    return hipGetLastError() == hipSuccess ? NNT_OK : NNT_EHIP;
+}
+
+int gemm_f32_occupancy(int akf, int bkf, int cfg) {
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel_of(akf, bkf, cfg), 256, 0) != hipSuccess || n < 1) n = 1;
+    return n;
 }
 
 }  // namespace nnt
