@@ -58,6 +58,8 @@ struct GemmPlan {
     std::vector<GemmChunk> chunks;
     std::vector<GemmWg> wgs, wgs_op;
     std::vector<int64_t> task_wg0;             // first workgroup of each task (+ total at the end)
+    std::vector<int64_t> task_nfast;           // leading workgroups of each task that qualify for the direct-load kernel
+    int64_t op_nfast = 0;                      // the same for the whole-operation order
     std::vector<int64_t> task_ctile;           // C tile index per task
     std::vector<std::vector<int64_t>> task_atiles, task_btiles;   // operand tiles per task (dependencies)
     std::vector<int64_t> task_bias_tile;
@@ -90,10 +92,16 @@ void drop_plans_of(nnt_ctx* ctx, uint64_t id) {
     }
 }
 
+// The first `nfast` workgroups of the table qualify for the direct-load kernel (bf16, 256 x 256).
 static int32_t launch_any(hipStream_t st, int dtype_in, int dtype_out, int akf, int bkf, int cfg,
-                          const GemmArgs& g, int64_t nwg) {
+                          const GemmArgs& g, int64_t nwg, int64_t nfast = 0) {
     if (dtype_in == NNT_F32) return launch_gemm_f32(st, akf, bkf, cfg, g, nwg);
-    return launch_gemm_bf16(st, dtype_out == NNT_F32, akf, bkf, cfg, g, nwg);
+    if (nfast <= 0) return launch_gemm_bf16(st, dtype_out == NNT_F32, akf, bkf, cfg, g, nwg);
+    int32_t rc = launch_gemm_bf16_dl(st, dtype_out == NNT_F32, akf, bkf, g, nfast);
+    if (rc != NNT_OK || nfast == nwg) return rc;
+    GemmArgs rest = g;
+    if (rest.wgs) rest.wgs += nfast;
+    return launch_gemm_bf16(st, dtype_out == NNT_F32, akf, bkf, cfg, rest, nwg - nfast);
 }
 
 static int vec_flag(const void* p, int64_t ld, int64_t stride, int elem) {
@@ -174,7 +182,7 @@ static ShapeChoice choose_shape(bool bf16, bool out_f32, int akf, int bkf, const
                                 const std::vector<int64_t>& tn, const std::vector<int64_t>& ktot, bool may_split) {
     struct Cand { int cfg; double flops_per_s_cu; double t0; };
     static const Cand f32c[] = {{kCfgSquare, 0.515e12, 2.5e-6}, {kCfgMid, 0.45e12, 2.0e-6}};
-    static const Cand bf16c[] = {{kCfgSquare, 3.7e12, 5.0e-6}, {kCfgMid, 2.6e12, 3.0e-6}};
+    static const Cand bf16c[] = {{kCfgSquare, 4.4e12, 8.0e-6}, {kCfgMid, 1.6e12, 3.0e-6}};
     const Cand* cands = bf16 ? bf16c : f32c;
     ShapeChoice best = {kCfgSquare, 0, 1};
     double best_t = 1e30;
@@ -213,10 +221,13 @@ static ShapeChoice choose_shape(bool bf16, bool out_f32, int akf, int bkf, const
     return best;
 }
 
-static int pick_cfg(int bf16, int64_t m_max, int64_t n_max, int64_t n_tiles_big) {
+static int pick_cfg(int bf16, int64_t m_max, int64_t n_max, int64_t n_tiles_big, int64_t k_max) {
     if (m_max <= 64) return kCfgSkinny64;
     if (m_max <= 128 && n_max > 128) return kCfgSkinny128;
     if (bf16 && (m_max <= 128 || n_max <= 128 || n_tiles_big < 256)) return kCfgMid;
+    // short contractions are bound by the result stores: several small workgroups per compute
+    // unit overlap one's stores with another's loads, one large workgroup cannot
+    if (bf16 && k_max <= 128) return kCfgMid;
     return kCfgSquare;
 }
 
@@ -262,14 +273,15 @@ extern "C" int32_t nnt_tile_gemm(void* stream, int32_t dtype_in, int32_t dtype_o
     g.alpha = alpha;
     g.beta = beta;
     int bm, bn;
-    int cfg = pick_cfg(bf, m, n, ((m + 255) / 256) * ((n + 255) / 256) * batch);
+    int cfg = pick_cfg(bf, m, n, ((m + 255) / 256) * ((n + 255) / 256) * batch, k);
     if (batch == 1 && (cfg == kCfgSquare || cfg == kCfgMid)) cfg = choose_shape(bf, dtype_out == NNT_F32, opA == NNT_OP_T, opB == NNT_OP_N, {m}, {n}, {k}, false).cfg;
     gemm_cfg_tile(bf, cfg, &bm, &bn);
     g.grid_m = (int32_t)((m + bm - 1) / bm);
     g.grid_n = (int32_t)((n + bn - 1) / bn);
     const int64_t nwg = (int64_t)g.grid_m * g.grid_n * batch;
     if (nwg > INT32_MAX) return NNT_EINVAL;
-    return launch_any((hipStream_t)stream, dtype_in, dtype_out, opA == NNT_OP_T, opB == NNT_OP_N, cfg, g, nwg);
+    const bool fast = bf && cfg == kCfgSquare && m % 256 == 0 && n % 256 == 0 && k > 0 && k % 32 == 0 && g.one_chunk.vec_ok == 3;
+    return launch_any((hipStream_t)stream, dtype_in, dtype_out, opA == NNT_OP_T, opB == NNT_OP_N, cfg, g, nwg, fast ? nwg : 0);
 }
 
 // ---------------------------------------------------------------- tensor-level product
@@ -395,7 +407,9 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
     std::vector<int64_t> ktot(P->tasks.size(), 0);
     for (size_t ti = 0; ti < P->tasks.size(); ti++)
         for (int32_t q = P->tasks[ti].chunk0; q < P->tasks[ti].chunk0 + P->tasks[ti].nchunk; q++) ktot[ti] += P->chunks[q].k;
-    P->cfg = pick_cfg(bf, m_max, n_max, big);
+    int64_t k_max = 0;
+    for (int64_t kq : ktot) k_max = std::max(k_max, kq);
+    P->cfg = pick_cfg(bf, m_max, n_max, big, k_max);
     int S = 1;
     int64_t n_split = 0;
     if (nbat == 0 && !P->tasks.empty() && (P->cfg == kCfgSquare || P->cfg == kCfgMid)) {
@@ -518,6 +532,31 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
     }
     P->op_nwg = (int64_t)P->wgs_op.size();
 
+    // workgroups that qualify for the direct-load kernel go first in every launch range
+    P->task_nfast.assign(P->task_ctile.size(), 0);
+    if (bf && P->cfg == kCfgSquare) {
+        std::vector<char> task_ok(P->tasks.size(), 1);
+        for (size_t ti = 0; ti < P->tasks.size(); ti++)
+            for (int32_t q = P->tasks[ti].chunk0; q < P->tasks[ti].chunk0 + P->tasks[ti].nchunk; q++)
+                if (P->chunks[q].vec_ok != 3 || P->chunks[q].k <= 0 || P->chunks[q].k % 32 != 0) task_ok[ti] = 0;
+        auto qualifies = [&](const GemmWg& w) {
+            const GemmTask& t = P->tasks[w.task];
+            return task_ok[w.task] && w.m0 + 256 <= t.m && w.n0 + 256 <= t.n;
+        };
+        P->op_nfast = std::stable_partition(P->wgs_op.begin(), P->wgs_op.end(), qualifies) - P->wgs_op.begin();
+        for (size_t ti = 0; ti + 1 < P->task_wg0.size(); ti++)
+            P->task_nfast[ti] = std::stable_partition(P->wgs.begin() + P->task_wg0[ti], P->wgs.begin() + P->task_wg0[ti + 1], qualifies) -
+                                (P->wgs.begin() + P->task_wg0[ti]);
+        if (2 * P->op_nfast >= P->op_nwg && P->op_nwg > 0) {
+            // most of the work runs in the direct-load kernel: profile lines carry its name
+            const std::string old_name = P->label.substr(0, P->label.find('>') + 1);
+            const char* tf[2] = {"false", "true"};
+            std::ostringstream l;
+            l << "gemm_bf16_dl_kernel<" << (C->dtype == NNT_F32 ? "float" : "unsigned short") << ", " << tf[P->akf] << ", " << tf[P->bkf] << ">";
+            P->label = l.str() + P->label.substr(old_name.size());
+        }
+    }
+
     auto up = [&](void** d, const void* h, size_t bytes) -> hipError_t {
         if (bytes == 0) return hipSuccess;
         hipError_t e = hipMalloc(d, bytes);
@@ -569,7 +608,7 @@ extern "C" int32_t nnt_gemm(nnt_ctx* ctx, float alpha, int32_t opA, nnt_tensor* 
         if (P->n_split > 0) {
             acc.push_back(Access{&P->ws_dep, 1, kReadWrite});
             return submit(ctx, acc, [=](hipStream_t st) {
-                int32_t rc = launch_any(st, P->dtype_in, P->dtype_out, P->akf, P->bkf, P->cfg, g, nwg);
+                int32_t rc = launch_any(st, P->dtype_in, P->dtype_out, P->akf, P->bkf, P->cfg, g, nwg, P->op_nfast);
                 if (rc != NNT_OK) return rc;
                 const dim3 grid((unsigned)P->red_blocks, (unsigned)P->n_split), block(256);
                 if (P->dtype_out == NNT_F32) hipLaunchKernelGGL((splitk_reduce<float>), grid, block, 0, st, P->d_red, alpha, beta);
@@ -578,7 +617,7 @@ extern "C" int32_t nnt_gemm(nnt_ctx* ctx, float alpha, int32_t opA, nnt_tensor* 
             }, 2);
         }
         return submit(ctx, acc, [=](hipStream_t st) {
-            return launch_any(st, P->dtype_in, P->dtype_out, P->akf, P->bkf, P->cfg, g, nwg);
+            return launch_any(st, P->dtype_in, P->dtype_out, P->akf, P->bkf, P->cfg, g, nwg, P->op_nfast);
         });
     }
     const size_t n_tile_tasks = P->task_ctile.size();
@@ -591,8 +630,9 @@ extern "C" int32_t nnt_gemm(nnt_ctx* ctx, float alpha, int32_t opA, nnt_tensor* 
         GemmArgs gt = g;
         gt.wgs = P->d_wgs + P->task_wg0[ti];
         const int64_t nwg = P->task_wg0[ti + 1] - P->task_wg0[ti];
+        const int64_t nfast = P->task_nfast[ti];
         int32_t rc = submit(ctx, acc, [=](hipStream_t st) {
-            return launch_any(st, P->dtype_in, P->dtype_out, P->akf, P->bkf, P->cfg, gt, nwg);
+            return launch_any(st, P->dtype_in, P->dtype_out, P->akf, P->bkf, P->cfg, gt, nwg, nfast);
         });
         if (rc != NNT_OK) return rc;
     }

@@ -103,6 +103,18 @@ def test_gemm_multi_macro_tile(capi, din, dout, m, n, k):
         assert e <= (2e-2 if dout == "bf16" else 1e-5), (opA, opB, e)
 
 
+@pytest.mark.parametrize("dout", ["f32", "bf16"])
+@pytest.mark.parametrize("opA,opB", list(itertools.product("NT", "NT")))
+@pytest.mark.parametrize("m,n,k", [(256, 256, 32), (512, 768, 96), (768, 256, 416)])
+def test_gemm_bf16_whole_macro_tiles_aligned(capi, opA, opB, m, n, k, dout):
+    """Shapes made of whole 256 x 256 macro-tiles with k a multiple of 32 and 16-byte aligned operands:
+    the kernel that loads straight into LDS (short and long k, padded leading dimensions, batch, beta)."""
+    for batch, alpha, beta, pad in ((1, 1.0, 0.0, 0), (2, 0.7, -1.3, 8)):
+        got, ref = run_gemm(capi, "bf16", dout, opA, opB, m, n, k, batch, alpha, beta, pad, seed=m + n + k)
+        e = relerr(got, ref)
+        assert e <= (2e-2 if dout == "bf16" else 1e-5), ("gemm bf16->%s %s%s %dx%dx%d b%d" % (dout, opA, opB, m, n, k, batch), e)
+
+
 def test_gemm_degenerate(capi):
     # k = 0: C <- beta * C; beta = 0 must not propagate NaNs already in C
     C0 = rng(1).standard_normal((9, 5)).astype(np.float32)
