@@ -425,7 +425,7 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
     gemm_cfg_tile(bf, P->cfg, &bm, &bn);
     {
         // spelled like the demangled kernel name, so that profiler output can be matched against it
-        static const char* const shape[4] = {"2, 2, 4, 4", "2, 2, 2, 2", "1, 4, 2, 2", "1, 4, 4, 2"};
+        static const char* const shape[6] = {"2, 2, 4, 4", "2, 2, 2, 2", "1, 4, 2, 2", "1, 4, 4, 2", "1, 4, 2, 1", "2, 2, 1, 1"};
         std::ostringstream l;
         const char* tf[2] = {"false", "true"};
         if (A->dtype == NNT_F32) l << "gemm_f32_kernel<" << tf[P->akf] << ", " << tf[P->bkf] << ", " << (P->cfg == kCfgSquare ? "2, 2, 2, 2" : P->cfg == kCfgMid ? "2, 2, 1, 2" : shape[P->cfg]) << ">";

@@ -49,7 +49,9 @@ enum GemmCfg {
     kCfgSquare = 0,   // f32 128 x 128, bf16 256 x 256
     kCfgMid = 1,      // f32 64 x 128, bf16 128 x 128
     kCfgSkinny64 = 2, // 64 x 256   (attention products with m = head size 64)
-    kCfgSkinny128 = 3 // 128 x 256  (head size 128)
+    kCfgSkinny128 = 3, // 128 x 256  (head size 128)
+    kCfgSkinny64n128 = 4, // 64 x 128
+    kCfgSkinny64n64 = 5   // 64 x 64   (the two narrower shapes give memory-bound products more workgroups)
 };
 
 inline void gemm_cfg_tile(int dtype_is_bf16, int cfg, int* bm, int* bn) {
@@ -57,6 +59,8 @@ inline void gemm_cfg_tile(int dtype_is_bf16, int cfg, int* bm, int* bn) {
         case kCfgSquare: *bm = *bn = dtype_is_bf16 ? 256 : 128; break;
         case kCfgMid: *bm = dtype_is_bf16 ? 128 : 64; *bn = 128; break;
         case kCfgSkinny64: *bm = 64; *bn = 256; break;
+        case kCfgSkinny64n128: *bm = 64; *bn = 128; break;
+        case kCfgSkinny64n64: *bm = 64; *bn = 64; break;
         default: *bm = 128; *bn = 256; break;
     }
 }
