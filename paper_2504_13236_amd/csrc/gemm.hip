@@ -92,12 +92,12 @@ void drop_plans_of(nnt_ctx* ctx, uint64_t id) {
     }
 }
 
-// The first `nfast` workgroups of the table qualify for the direct-load kernel (bf16, 256 x 256).
+// The first `nfast` workgroups of the table qualify for the direct-load kernel (bf16, 256 rows).
 static int32_t launch_any(hipStream_t st, int dtype_in, int dtype_out, int akf, int bkf, int cfg,
                           const GemmArgs& g, int64_t nwg, int64_t nfast = 0) {
     if (dtype_in == NNT_F32) return launch_gemm_f32(st, akf, bkf, cfg, g, nwg);
     if (nfast <= 0) return launch_gemm_bf16(st, dtype_out == NNT_F32, akf, bkf, cfg, g, nwg);
-    int32_t rc = launch_gemm_bf16_dl(st, dtype_out == NNT_F32, akf, bkf, g, nfast);
+    int32_t rc = launch_gemm_bf16_dl(st, dtype_out == NNT_F32, akf, bkf, cfg, g, nfast);
     if (rc != NNT_OK || nfast == nwg) return rc;
     GemmArgs rest = g;
     if (rest.wgs) rest.wgs += nfast;
@@ -180,19 +180,23 @@ constexpr int kSplitStep = 64;
 struct ShapeChoice { int cfg; int64_t n_split; int s; };
 static ShapeChoice choose_shape(bool bf16, bool out_f32, int akf, int bkf, const std::vector<int64_t>& tm,
                                 const std::vector<int64_t>& tn, const std::vector<int64_t>& ktot, bool may_split) {
-    struct Cand { int cfg; double flops_per_s_cu; double t0; };
-    static const Cand f32c[] = {{kCfgSquare, 0.515e12, 2.5e-6}, {kCfgMid, 0.45e12, 2.0e-6}};
-    static const Cand bf16c[] = {{kCfgSquare, 4.4e12, 8.0e-6}, {kCfgMid, 1.6e12, 3.0e-6}};
+    // rate of a compute unit with its full set of workgroups; start-up time of a workgroup; factor by
+    // which a workgroup that is alone on its unit is slower than its share of that rate
+    struct Cand { int cfg; double flops_per_s_cu; double t0; double solo; };
+    static const Cand f32c[] = {{kCfgSquare, 0.515e12, 2.5e-6, 1.2}, {kCfgMid, 0.45e12, 2.0e-6, 1.3}};
+    static const Cand bf16c[] = {{kCfgSquare, 4.4e12, 8.0e-6, 1.0}, {kCfgTall, 4.2e12, 3.0e-6, 1.6}, {kCfgMid, 1.6e12, 3.0e-6, 1.5}};
     const Cand* cands = bf16 ? bf16c : f32c;
+    const int ncand = bf16 ? 3 : 2;
     ShapeChoice best = {kCfgSquare, 0, 1};
     double best_t = 1e30;
     int64_t kmax = 0, kmin = INT64_MAX;
     for (int64_t kq : ktot) { kmax = std::max(kmax, kq); kmin = std::min(kmin, kq); }
-    for (int ci = 0; ci < 2; ci++) {
+    for (int ci = 0; ci < ncand; ci++) {
         const Cand& cd = cands[ci];
         int bm, bn;
         gemm_cfg_tile(bf16, cd.cfg, &bm, &bn);
-        const int occ = bf16 ? gemm_bf16_occupancy(out_f32, akf, bkf, cd.cfg) : gemm_f32_occupancy(akf, bkf, cd.cfg);
+        const int occ = !bf16 ? gemm_f32_occupancy(akf, bkf, cd.cfg)
+                        : (cd.cfg == kCfgMid ? gemm_bf16_occupancy(out_f32, akf, bkf, cd.cfg) : gemm_bf16_dl_occupancy(out_f32, akf, bkf, cd.cfg));
         const int64_t G = 256 * (int64_t)occ;      // workgroups resident at a time
         int64_t W = 0;
         for (size_t i = 0; i < tm.size(); i++) W += ((tm[i] + bm - 1) / bm) * ((tn[i] + bn - 1) / bn);
@@ -200,7 +204,9 @@ static ShapeChoice choose_shape(bool bf16, bool out_f32, int akf, int bkf, const
         // X equal workgroups: whole resident sets, each as slow as `occ` workgroups in a row on
         // every unit, then a last set spread over the units
         auto group_time = [&](int64_t X, int64_t k) {
-            return ((double)(X / G) * occ + (double)((X % G + 255) / 256)) * tile_time(k) + (double)((X + G - 1) / G) * cd.t0;
+            const int64_t last = (X % G + 255) / 256;          // workgroups per unit in the last, partial set
+            const double last_t = (last == 1 && occ > 1) ? cd.solo : (double)last;
+            return ((double)(X / G) * occ + last_t) * tile_time(k) + (double)((X + G - 1) / G) * cd.t0;
         };
         const double t_plain = group_time(W, kmax);
         if (t_plain < best_t) { best_t = t_plain; best = {cd.cfg, 0, 1}; }
@@ -274,13 +280,13 @@ extern "C" int32_t nnt_tile_gemm(void* stream, int32_t dtype_in, int32_t dtype_o
     g.beta = beta;
     int bm, bn;
     int cfg = pick_cfg(bf, m, n, ((m + 255) / 256) * ((n + 255) / 256) * batch, k);
-    if (batch == 1 && (cfg == kCfgSquare || cfg == kCfgMid)) cfg = choose_shape(bf, dtype_out == NNT_F32, opA == NNT_OP_T, opB == NNT_OP_N, {m}, {n}, {k}, false).cfg;
+    if (batch == 1 && (cfg == kCfgSquare || cfg == kCfgMid || cfg == kCfgTall)) cfg = choose_shape(bf, dtype_out == NNT_F32, opA == NNT_OP_T, opB == NNT_OP_N, {m}, {n}, {k}, false).cfg;
     gemm_cfg_tile(bf, cfg, &bm, &bn);
     g.grid_m = (int32_t)((m + bm - 1) / bm);
     g.grid_n = (int32_t)((n + bn - 1) / bn);
     const int64_t nwg = (int64_t)g.grid_m * g.grid_n * batch;
     if (nwg > INT32_MAX) return NNT_EINVAL;
-    const bool fast = bf && cfg == kCfgSquare && m % 256 == 0 && n % 256 == 0 && k > 0 && k % 32 == 0 && g.one_chunk.vec_ok == 3;
+    const bool fast = bf && (cfg == kCfgSquare || cfg == kCfgTall) && m % bm == 0 && n % bn == 0 && k > 0 && k % 32 == 0 && g.one_chunk.vec_ok == 3;
     return launch_any((hipStream_t)stream, dtype_in, dtype_out, opA == NNT_OP_T, opB == NNT_OP_N, cfg, g, nwg, fast ? nwg : 0);
 }
 
@@ -412,7 +418,7 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
     P->cfg = pick_cfg(bf, m_max, n_max, big, k_max);
     int S = 1;
     int64_t n_split = 0;
-    if (nbat == 0 && !P->tasks.empty() && (P->cfg == kCfgSquare || P->cfg == kCfgMid)) {
+    if (nbat == 0 && !P->tasks.empty() && (P->cfg == kCfgSquare || P->cfg == kCfgMid || P->cfg == kCfgTall)) {
         // products of whole matrices: macro-tile shape and k-slices by the cost model
         std::vector<int64_t> tm, tn;
         for (const TaskGeom& gq : geom) { tm.push_back(gq.m); tn.push_back(gq.n); }
@@ -425,7 +431,7 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
     gemm_cfg_tile(bf, P->cfg, &bm, &bn);
     {
         // spelled like the demangled kernel name, so that profiler output can be matched against it
-        static const char* const shape[6] = {"2, 2, 4, 4", "2, 2, 2, 2", "1, 4, 2, 2", "1, 4, 4, 2", "1, 4, 2, 1", "2, 2, 1, 1"};
+        static const char* const shape[7] = {"2, 2, 4, 4", "2, 2, 2, 2", "1, 4, 2, 2", "1, 4, 4, 2", "1, 4, 2, 1", "2, 2, 1, 1", "2, 2, 4, 2"};
         std::ostringstream l;
         const char* tf[2] = {"false", "true"};
         if (A->dtype == NNT_F32) l << "gemm_f32_kernel<" << tf[P->akf] << ", " << tf[P->bkf] << ", " << (P->cfg == kCfgSquare ? "2, 2, 2, 2" : P->cfg == kCfgMid ? "2, 2, 1, 2" : shape[P->cfg]) << ">";
@@ -534,14 +540,14 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
 
     // workgroups that qualify for the direct-load kernel go first in every launch range
     P->task_nfast.assign(P->task_ctile.size(), 0);
-    if (bf && P->cfg == kCfgSquare) {
+    if (bf && (P->cfg == kCfgSquare || P->cfg == kCfgTall)) {
         std::vector<char> task_ok(P->tasks.size(), 1);
         for (size_t ti = 0; ti < P->tasks.size(); ti++)
             for (int32_t q = P->tasks[ti].chunk0; q < P->tasks[ti].chunk0 + P->tasks[ti].nchunk; q++)
                 if (P->chunks[q].vec_ok != 3 || P->chunks[q].k <= 0 || P->chunks[q].k % 32 != 0) task_ok[ti] = 0;
         auto qualifies = [&](const GemmWg& w) {
             const GemmTask& t = P->tasks[w.task];
-            return task_ok[w.task] && w.m0 + 256 <= t.m && w.n0 + 256 <= t.n;
+            return task_ok[w.task] && w.m0 + bm <= t.m && w.n0 + bn <= t.n;
         };
         P->op_nfast = std::stable_partition(P->wgs_op.begin(), P->wgs_op.end(), qualifies) - P->wgs_op.begin();
         for (size_t ti = 0; ti + 1 < P->task_wg0.size(); ti++)
@@ -552,7 +558,8 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
             const std::string old_name = P->label.substr(0, P->label.find('>') + 1);
             const char* tf[2] = {"false", "true"};
             std::ostringstream l;
-            l << "gemm_bf16_dl_kernel<" << (C->dtype == NNT_F32 ? "float" : "unsigned short") << ", " << tf[P->akf] << ", " << tf[P->bkf] << ">";
+            l << (P->cfg == kCfgTall ? "gemm_bf16_dl_tall_kernel<" : "gemm_bf16_dl_kernel<") << (C->dtype == NNT_F32 ? "float" : "unsigned short")
+              << ", " << tf[P->akf] << ", " << tf[P->bkf] << ">";
             P->label = l.str() + P->label.substr(old_name.size());
         }
     }

@@ -1,17 +1,17 @@
-// bf16 product kernel for whole 256 x 256 macro-tiles of 16-byte aligned operands
-// whose chunks are multiples of 32 long: the operands go from global memory
-// straight into LDS (global_load_lds_dwordx4), four k-steps of 32 deep, so that
-// three steps of loads are in flight while one is multiplied and no registers are
+// bf16 product kernel for whole 256 x 256 or 256 x 128 macro-tiles of 16-byte
+// aligned operands whose chunks are multiples of 32 long: the operands go from
+// global memory straight into LDS (global_load_lds_dwordx4), three or four k-steps
+// of 32 deep, so that loads stay in flight across whole steps and no registers are
 // spent on staging.
 //
-// LDS layout of one step (32 KB; A then B, 16 KB each), chosen so that both the
+// LDS layout of one step (A then B, 64 bytes per row), chosen so that both the
 // 1 KB runs a wave's load instruction fills (lane i -> bytes 16 i .. 16 i + 15)
 // and the fragment reads of the matrix cores are free of bank conflicts (64 banks
 // of 4 bytes):
 //   * operand with the contracted index contiguous in memory ("k-fast"): rows of
 //     32 k = 64 bytes; the 16-byte chunk c of row r sits at slot c ^ ((r >> 2) & 3).
 //     A lane's fragment (8 consecutive k of one row) is one 128-bit read.
-//   * operand with the row index contiguous: lines of 256 rows = 512 bytes per k;
+//   * operand with the row index contiguous: one line of all its rows per k;
 //     the 16-byte chunk c (8 rows) of line k sits at slot c ^ ((k & 3) << 2).
 //     Fragments are fetched with ds_read_b64_tr_b16, which hands each lane four
 //     consecutive k of its row from four lines (two reads per fragment).
@@ -39,12 +39,9 @@ typedef __attribute__((address_space(3))) void* lds_void_ptr;
 typedef const __attribute__((address_space(1))) void* glb_void_ptr;
 
 constexpr int kBK = 32;                 // k-step
-constexpr int kStages = 4;
-constexpr int kOpBytes = 256 * kBK * 2; // one operand of one step
-constexpr int kStageBytes = 2 * kOpBytes;
 
-// s_waitcnt immediates (gfx9 encoding): only vmcnt constrained
-constexpr int kWaitVm0 = 0x0F70, kWaitVm8 = 0x0F78, kWaitVm16 = 0x4F70, kWaitVm24 = 0x4F78;
+// s_waitcnt immediate (gfx9 encoding) that constrains only vmcnt
+constexpr int wait_vm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }
 
 // A chunk descriptor in scalar registers.  The descriptor tables are constant for the lifetime of
 // a launch, but the compiler cannot know that next to the loads that write LDS, so the scalar
@@ -79,28 +76,30 @@ __device__ __forceinline__ ChunkS sload_chunk(const GemmChunk* p) {
     return r;
 }
 
-// Starts load instruction j (0..3) of this wave for one operand of one k-step.  `tile` points at
-// (first row, first k) of the 256 x 32 block, `dst` at its LDS region; both are the same for all
-// lanes.
-template <bool KF>
+// Starts load instruction j (0 .. ROWS / 64 - 1) of this wave for one operand of one k-step.  `tile`
+// points at (first row, first k) of the ROWS x 32 block, `dst` at its LDS region; both are the same
+// for all lanes.
+template <bool KF, int ROWS>
 __device__ __forceinline__ void issue_one(const uint16_t* tile, int ld, char* dst, int wave, int lane, int j) {
+    constexpr int NI = ROWS / 64;                            // instructions per wave and step
     const uint16_t* gp;
     if (KF) {
         // an instruction covers 16 rows; lane -> row lane / 4, slot lane % 4
         const int r = lane >> 2;
         const int c = (lane & 3) ^ ((r >> 2) & 3);
-        gp = tile + (int64_t)(64 * wave + 16 * j) * ld + (uint32_t)(r * ld + c * 8);
+        gp = tile + (int64_t)(16 * (NI * wave + j)) * ld + (uint32_t)(r * ld + c * 8);
     } else {
-        // an instruction covers two k-lines; lane -> line lane / 32, slot lane % 32
-        const int kk = 2 * j + (lane >> 5);                 // line within the wave's 8; 8 * wave is 0 mod 4
-        const int c = (lane & 31) ^ ((kk & 3) << 2);
-        gp = tile + (int64_t)(8 * wave + 2 * j) * ld + (uint32_t)((lane >> 5) * ld + c * 8);
+        // an instruction covers 1024 / (2 ROWS) k-lines; lane -> line lane / LPL, slot lane % LPL
+        constexpr int LPL = ROWS / 8, LPI = 64 / LPL;        // lanes per line, lines per instruction
+        const int kk = LPI * j + lane / LPL;                 // line within the wave's 8; 8 * wave is 0 mod 4
+        const int c = (lane % LPL) ^ ((kk & 3) << 2);
+        gp = tile + (int64_t)(8 * wave + LPI * j) * ld + (uint32_t)((lane / LPL) * ld + c * 8);
     }
-    __builtin_amdgcn_global_load_lds((glb_void_ptr)gp, (lds_void_ptr)(dst + (wave * 4 + j) * 1024), 16, 0, 0);
+    __builtin_amdgcn_global_load_lds((glb_void_ptr)gp, (lds_void_ptr)(dst + (wave * NI + j) * 1024), 16, 0, 0);
 }
 
-// Per-lane part of the fragment address of an operand region.
-template <bool KF>
+// Per-lane part of the fragment address of an operand region of ROWS rows.
+template <bool KF, int ROWS>
 __device__ __forceinline__ uint32_t frag_lane_offset(int lane) {
     if (KF) {
         const int r32 = lane & 31, half = lane >> 5;
@@ -109,7 +108,7 @@ __device__ __forceinline__ uint32_t frag_lane_offset(int lane) {
     const int j = lane & 15, gq = lane >> 4, half = gq >> 1;
     const int x = (j >> 2) & 3;                                 // k & 3 of the line this lane addresses
     const int low2 = 2 * (gq & 1) + ((j & 3) >> 1);             // 16-byte chunk within the 32-row block
-    return (uint32_t)((8 * half + (j >> 2)) * 512 + x * 64 + low2 * 16 + (j & 1) * 8);
+    return (uint32_t)((8 * half + (j >> 2)) * (2 * ROWS) + x * 64 + low2 * 16 + (j & 1) * 8);
 }
 
 // LDS reads of the pipeline are spelled as inline assembly: the compiler treats every LDS read
@@ -138,24 +137,38 @@ struct Frag<false> {
     }
 };
 
-// Starts the read of the fragment of 32-row block `blk` (0..7) of an operand region (LDS byte
-// offset `region`) for substep ks (16 k each).
-template <bool KF>
+// Starts the read of the fragment of 32-row block `blk` of an operand region of ROWS rows (LDS
+// byte offset `region`) for substep ks (16 k each).
+template <bool KF, int ROWS>
 __device__ __forceinline__ void read_frag(Frag<KF>& f, uint32_t region, uint32_t lane_off, int blk, int ks) {
     if constexpr (KF) {
         const uint32_t addr = region + blk * 2048 + (lane_off ^ (uint32_t)(ks * 32));
         asm volatile("ds_read_b128 %0, %1" : "=v"(f.v) : "v"(addr));
     } else {
-        const uint32_t addr = region + ks * 16 * 512 + (blk >> 2) * 256 + (lane_off ^ (uint32_t)((blk & 3) * 64));
+        constexpr int LB = 2 * ROWS;                            // bytes of a k-line
+        const uint32_t addr = region + ks * 16 * LB + (blk >> 2) * 256 + (lane_off ^ (uint32_t)((blk & 3) * 64));
         asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(f.lo) : "v"(addr));
-        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:2048" : "=v"(f.hi) : "v"(addr));
+        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(f.hi) : "v"(addr), "n"(4 * LB));
     }
 }
 
-template <typename TO, bool AKF, bool BKF>
-__global__ void __launch_bounds__(256) gemm_bf16_dl_kernel(const GemmArgs g) {
-    constexpr int WMB = 4, WNB = 4;
-    __shared__ __attribute__((aligned(16))) char lds[kStages * kStageBytes];
+// Macro-tile 256 x 64 WNB: WNB = 4 has a CU to itself (four stages), WNB = 2 leaves room for two
+// workgroups per CU (three stages each), which cover each other's first loads and result stores.
+template <int WNB>
+struct DlShape {
+    static constexpr int kStages = WNB == 4 ? 4 : 3;
+    static constexpr int kStageBytes = (256 + 64 * WNB) * kBK * 2;
+    static constexpr int kLdsBytes = kStages * kStageBytes;
+};
+
+template <typename TO, bool AKF, bool BKF, int WNB>
+__device__ __forceinline__ void dl_body(const GemmArgs& g, char* lds) {
+    constexpr int WMB = 4, BM = 256, BN = 64 * WNB;
+    constexpr int kStages = DlShape<WNB>::kStages;
+    constexpr int kOpABytes = BM * kBK * 2, kStageBytes = DlShape<WNB>::kStageBytes;
+    constexpr int NIA = BM / 64, NIB = BN / 64, kLoads = NIA + NIB;     // load instructions per wave and step
+    constexpr int kFrags = WNB + WMB, kMfma = WNB * WMB;
+    static_assert(4 * 32 * (32 * WMB + 4) * 4 <= kStages * kStageBytes, "result staging must fit the pipeline's LDS");
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -171,8 +184,8 @@ __global__ void __launch_bounds__(256) gemm_bf16_dl_kernel(const GemmArgs g) {
     } else {
         task = g.one_task;
         const int b = blockIdx.x;
-        m0 = (b % g.grid_m) * 256;
-        n0 = ((b / g.grid_m) % g.grid_n) * 256;
+        m0 = (b % g.grid_m) * BM;
+        n0 = ((b / g.grid_m) % g.grid_n) * BN;
         bat = b / (g.grid_m * g.grid_n);
     }
     m0 = __builtin_amdgcn_readfirstlane(m0);
@@ -231,11 +244,11 @@ __global__ void __launch_bounds__(256) gemm_bf16_dl_kernel(const GemmArgs g) {
             set_chunk(one);
         }
         set_step();
-        // load instruction i (0..7: four for A, four for B) of the k-step at the current position
+        // load instruction i (first those of A, then those of B) of the k-step at the current position
         auto load_one = [&](int stage, int i) {
             char* sa = lds + stage * kStageBytes;
-            if (i < 4) issue_one<AKF>(At, lda, sa, wave, lane, i);
-            else issue_one<BKF>(Bt, ldb, sa + kOpBytes, wave, lane, i - 4);
+            if (i < NIA) issue_one<AKF, BM>(At, lda, sa, wave, lane, i);
+            else issue_one<BKF, BN>(Bt, ldb, sa + kOpABytes, wave, lane, i - NIA);
         };
         auto advance = [&]() {
             if (--to_issue > 0) {
@@ -252,19 +265,19 @@ __global__ void __launch_bounds__(256) gemm_bf16_dl_kernel(const GemmArgs g) {
         };
         for (int s = 0; s < kStages - 1; s++) {
 #pragma unroll
-            for (int i = 0; i < 8; i++) load_one(s, i);
+            for (int i = 0; i < kLoads; i++) load_one(s, i);
             advance();
         }
 
-        const uint32_t offA = frag_lane_offset<AKF>(lane), offB = frag_lane_offset<BKF>(lane);
+        const uint32_t offA = frag_lane_offset<AKF, BM>(lane), offB = frag_lane_offset<BKF, BN>(lane);
         Frag<BKF> pf[2][WNB];
         Frag<AKF> qf[2][WMB];
         const uint32_t lds0 = lds_offset(lds);
-        // fragment i (0..7: four column blocks of B, four row blocks of A) of a substep
+        // fragment i (first the column blocks of B, then the row blocks of A) of a substep
         auto frag_one = [&](int buf, int stage, int ks, int i) {
             const uint32_t sa = lds0 + stage * kStageBytes;
-            if (i < WNB) read_frag<BKF>(pf[buf][i], sa + kOpBytes, offB, wn * WNB + i, ks);
-            else read_frag<AKF>(qf[buf][i - WNB], sa, offA, wm * WMB + i - WNB, ks);
+            if (i < WNB) read_frag<BKF, BN>(pf[buf][i], sa + kOpABytes, offB, wn * WNB + i, ks);
+            else read_frag<AKF, BM>(qf[buf][i - WNB], sa, offA, wm * WMB + i - WNB, ks);
         };
         // all fragment reads issued so far have landed; the matrix instructions on set `buf` stay behind this
         auto wait_frags = [&](int buf) {
@@ -278,35 +291,38 @@ __global__ void __launch_bounds__(256) gemm_bf16_dl_kernel(const GemmArgs g) {
             const int bn = i / WMB, bm = i % WMB;
             acc[bn][bm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[buf][bm].value(), pf[buf][bn].value(), acc[bn][bm], 0, 0, 0);
         };
-        // One substep: 16 matrix instructions on fragment set `buf`; under them the 8 fragments of
-        // the next substep are fetched into the other set and, with `with_loads`, the 8 load
-        // instructions of a k-step are started.  The pieces are fenced so that they stay spread
-        // over the matrix instructions.
+        // One substep: the matrix instructions on fragment set `buf`; under them the fragments of
+        // the next substep are fetched into the other set and, with `with_loads`, the load
+        // instructions of a k-step are started.  The pieces are dealt out evenly over the matrix
+        // instructions and fenced so that they stay there.
         auto substep = [&](auto with_loads, int buf, int f_stage, int f_ks, int load_stage) {
+            constexpr int kItems = kFrags + (decltype(with_loads)::value ? kLoads : 0);
             wait_frags(buf);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int q = 0; q < 8; q++) {
-                // fragments under the first half of the matrix instructions, loads under the second
-                mfma_one(buf, 2 * q);
-                if (q < 4) { frag_one(buf ^ 1, f_stage, f_ks, 2 * q); frag_one(buf ^ 1, f_stage, f_ks, 2 * q + 1); }
-                else if constexpr (decltype(with_loads)::value) { load_one(load_stage, 2 * (q - 4)); load_one(load_stage, 2 * (q - 4) + 1); }
-                mfma_one(buf, 2 * q + 1);
+            for (int q = 0; q < kMfma; q++) {
+                mfma_one(buf, q);
+#pragma unroll
+                for (int i = 0; i < kItems; i++) {
+                    if (i * kMfma / kItems != q) continue;
+                    if (i < kFrags) frag_one(buf ^ 1, f_stage, f_ks, i);
+                    else load_one(load_stage, i - kFrags);
+                }
                 __builtin_amdgcn_sched_barrier(0);
             }
         };
         // step 0 has landed in this wave's part once only the loads of steps 1 .. kStages - 2 remain
-        __builtin_amdgcn_s_waitcnt(kStages == 4 ? kWaitVm16 : kWaitVm24);
+        __builtin_amdgcn_s_waitcnt(wait_vm((kStages - 2) * kLoads));
         asm volatile("s_barrier" ::: "memory");
 #pragma unroll
-        for (int i = 0; i < 8; i++) frag_one(0, 0, 0, i);
+        for (int i = 0; i < kFrags; i++) frag_one(0, 0, 0, i);
         int stage = 0, next_stage = kStages - 1;
         for (int t = 0; t < T; t++) {
             const int stage1 = stage + 1 == kStages ? 0 : stage + 1;
             substep(std::false_type{}, 0, stage, 1, 0);
             // step t + 1 complete for everybody (loads of steps t + 2 .. t + kStages - 2 may remain),
             // and everybody done with the stage of step t - 1, which the next loads overwrite
-            __builtin_amdgcn_s_waitcnt(kStages == 4 ? kWaitVm8 : kWaitVm16);
+            __builtin_amdgcn_s_waitcnt(wait_vm((kStages - 3) * kLoads));
             asm volatile("s_barrier" ::: "memory");
             // (after the last step the fragment reads hit a stage that holds no new data: in bounds
             // and unused)
@@ -331,21 +347,47 @@ __global__ void __launch_bounds__(256) gemm_bf16_dl_kernel(const GemmArgs g) {
     }
 }
 
+template <typename TO, bool AKF, bool BKF>
+__global__ void __launch_bounds__(256) gemm_bf16_dl_kernel(const GemmArgs g) {
+    __shared__ __attribute__((aligned(16))) char lds[DlShape<4>::kLdsBytes];
+    dl_body<TO, AKF, BKF, 4>(g, lds);
+}
+
+// two workgroups per compute unit: at most 256 registers per lane
+template <typename TO, bool AKF, bool BKF>
+__global__ void __launch_bounds__(256, 2) gemm_bf16_dl_tall_kernel(const GemmArgs g) {
+    __shared__ __attribute__((aligned(16))) char lds[DlShape<2>::kLdsBytes];
+    dl_body<TO, AKF, BKF, 2>(g, lds);
+}
+
 using KernelFn = void (*)(const GemmArgs);
 
 template <typename TO>
-KernelFn kernel_of(int akf, int bkf) {
+KernelFn kernel_of(int akf, int bkf, bool tall) {
+    if (tall) {
+        if (akf) return bkf ? gemm_bf16_dl_tall_kernel<TO, true, true> : gemm_bf16_dl_tall_kernel<TO, true, false>;
+        return bkf ? gemm_bf16_dl_tall_kernel<TO, false, true> : gemm_bf16_dl_tall_kernel<TO, false, false>;
+    }
     if (akf) return bkf ? gemm_bf16_dl_kernel<TO, true, true> : gemm_bf16_dl_kernel<TO, true, false>;
     return bkf ? gemm_bf16_dl_kernel<TO, false, true> : gemm_bf16_dl_kernel<TO, false, false>;
 }
 
+KernelFn kernel_of(int out_is_f32, int akf, int bkf, int cfg) {
+    return out_is_f32 ? kernel_of<float>(akf, bkf, cfg == kCfgTall) : kernel_of<uint16_t>(akf, bkf, cfg == kCfgTall);
+}
+
 }  // namespace
 
-int32_t launch_gemm_bf16_dl(hipStream_t st, int out_is_f32, int akf, int bkf, const GemmArgs& g, int64_t nwg) {
+int32_t launch_gemm_bf16_dl(hipStream_t st, int out_is_f32, int akf, int bkf, int cfg, const GemmArgs& g, int64_t nwg) {
     if (nwg <= 0) return NNT_OK;
-    const KernelFn fn = out_is_f32 ? kernel_of<float>(akf, bkf) : kernel_of<uint16_t>(akf, bkf);
-    hipLaunchKernelGGL(fn, dim3((unsigned)nwg), dim3(256), 0, st, g);
+    hipLaunchKernelGGL(kernel_of(out_is_f32, akf, bkf, cfg), dim3((unsigned)nwg), dim3(256), 0, st, g);
     return hipGetLastError() == hipSuccess ? NNT_OK : NNT_EHIP;
+}
+
+int gemm_bf16_dl_occupancy(int out_is_f32, int akf, int bkf, int cfg) {
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel_of(out_is_f32, akf, bkf, cfg), 256, 0) != hipSuccess || n < 1) n = 1;
+    return n;
 }
 
 }  // namespace nnt

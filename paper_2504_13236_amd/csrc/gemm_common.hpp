@@ -51,7 +51,8 @@ enum GemmCfg {
     kCfgSkinny64 = 2, // 64 x 256   (attention products with m = head size 64)
     kCfgSkinny128 = 3, // 128 x 256  (head size 128)
     kCfgSkinny64n128 = 4, // 64 x 128
-    kCfgSkinny64n64 = 5   // 64 x 64   (the two narrower shapes give memory-bound products more workgroups)
+    kCfgSkinny64n64 = 5,  // 64 x 64   (the two narrower shapes give memory-bound products more workgroups)
+    kCfgTall = 6          // bf16 256 x 128 (two workgroups per compute unit); f32 128 x 128
 };
 
 inline void gemm_cfg_tile(int dtype_is_bf16, int cfg, int* bm, int* bn) {
@@ -61,15 +62,17 @@ inline void gemm_cfg_tile(int dtype_is_bf16, int cfg, int* bm, int* bn) {
         case kCfgSkinny64: *bm = 64; *bn = 256; break;
         case kCfgSkinny64n128: *bm = 64; *bn = 128; break;
         case kCfgSkinny64n64: *bm = 64; *bn = 64; break;
+        case kCfgTall: *bm = dtype_is_bf16 ? 256 : 128; *bn = 128; break;
         default: *bm = 128; *bn = 256; break;
     }
 }
 
 int32_t launch_gemm_f32(hipStream_t st, int akf, int bkf, int cfg, const GemmArgs& g, int64_t nwg);
 int32_t launch_gemm_bf16(hipStream_t st, int out_is_f32, int akf, int bkf, int cfg, const GemmArgs& g, int64_t nwg);
-// 256 x 256 macro-tiles that lie wholly inside their C tile, with 16-byte aligned operands and
+// 256 x 256 (kCfgSquare) or 256 x 128 (kCfgTall) macro-tiles that lie wholly inside their C tile, with 16-byte aligned operands and
 // chunk lengths that are multiples of 32 (loads go straight to LDS)
-int32_t launch_gemm_bf16_dl(hipStream_t st, int out_is_f32, int akf, int bkf, const GemmArgs& g, int64_t nwg);
+int32_t launch_gemm_bf16_dl(hipStream_t st, int out_is_f32, int akf, int bkf, int cfg, const GemmArgs& g, int64_t nwg);
+int gemm_bf16_dl_occupancy(int out_is_f32, int akf, int bkf, int cfg);
 // workgroups of the kernel instance that a compute unit holds at a time (registers, LDS)
 int gemm_f32_occupancy(int akf, int bkf, int cfg);
 int gemm_bf16_occupancy(int out_is_f32, int akf, int bkf, int cfg);
