@@ -320,18 +320,30 @@ __global__ void __launch_bounds__(256) rowsum_stage1(RowsumGeom g, float* part) 
 #pragma unroll
     for (int k = 0; k < V; k++) a0[k] = a1[k] = 0.f;
     if (y && e < ext0) {
-        for (int64_t c = c0 + wave; c < c1; c += 4) {
-            float d[V];
-            ldv<V>(y + c * ext0 + e, d);
-            if (MODE == 1) {
-                float f[V];
-                ldv<V>(x + c * ext0 + e, f);
-                const float mean = st[2 * c], rstd = st[2 * c + 1];
+        // four columns per trip so that four loads per operand are in flight
+        for (int64_t cb = c0 + wave; cb < c1; cb += 16) {
+            float d[4][V], f[4][V];
 #pragma unroll
-                for (int k = 0; k < V; k++) { a0[k] += d[k] * ((f[k] - mean) * rstd); a1[k] += d[k]; }
-            } else {
+            for (int u = 0; u < 4; u++) {
+                const int64_t c = cb + 4 * u;
+                if (c < c1) {
+                    ldv<V>(y + c * ext0 + e, d[u]);
+                    if (MODE == 1) ldv<V>(x + c * ext0 + e, f[u]);
+                }
+            }
 #pragma unroll
-                for (int k = 0; k < V; k++) a0[k] += d[k];
+            for (int u = 0; u < 4; u++) {
+                const int64_t c = cb + 4 * u;
+                if (c < c1) {
+                    if (MODE == 1) {
+                        const float mean = st[2 * c], rstd = st[2 * c + 1];
+#pragma unroll
+                        for (int k = 0; k < V; k++) { a0[k] += d[u][k] * ((f[u][k] - mean) * rstd); a1[k] += d[u][k]; }
+                    } else {
+#pragma unroll
+                        for (int k = 0; k < V; k++) a0[k] += d[u][k];
+                    }
+                }
             }
         }
     }
@@ -429,8 +441,15 @@ int32_t rowsum_tensor(nnt_ctx* ctx, int mode, nnt_tensor* dY, nnt_tensor* X, nnt
     g.ytab = dY->d_tiles;
     g.xtab = X ? X->d_tiles : nullptr;
     g.stab = S ? S->d_tiles : nullptr;
-    g.cpb = kColsPerBlock;
-    g.splits = (int32_t)((max_cols + kColsPerBlock - 1) / kColsPerBlock);
+    // columns per block: fewer when the tensor would otherwise give the chip too few blocks
+    int cpb = kColsPerBlock;
+    {
+        const int V0 = dY->dtype == NNT_F32 ? 4 : 8;
+        const int64_t row_blocks = (dY->base[0] + 64 * V0 - 1) / (64 * V0);
+        while (cpb > 32 && row_blocks * ((max_cols + cpb - 1) / cpb) * dY->ntiles < 1024) cpb /= 2;
+    }
+    g.cpb = cpb;
+    g.splits = (int32_t)((max_cols + cpb - 1) / cpb);
     g.rows_total = dY->shape[0];
     const int64_t nslots = rest_tiles * g.splits;
     g.nslots = nslots;
