@@ -286,7 +286,8 @@ extern "C" int32_t nnt_tile_gemm(void* stream, int32_t dtype_in, int32_t dtype_o
     g.grid_n = (int32_t)((n + bn - 1) / bn);
     const int64_t nwg = (int64_t)g.grid_m * g.grid_n * batch;
     if (nwg > INT32_MAX) return NNT_EINVAL;
-    const bool fast = bf && (cfg == kCfgSquare || cfg == kCfgTall) && m % bm == 0 && n % bn == 0 && k > 0 && k % 32 == 0 && g.one_chunk.vec_ok == 3;
+    const bool fast = bf && (cfg == kCfgSquare || cfg == kCfgTall) && m % bm == 0 && n % bn == 0 && k > 0 && k % (cfg == kCfgSquare ? 64 : 32) == 0 &&
+                      g.one_chunk.vec_ok == 3;
     return launch_any((hipStream_t)stream, dtype_in, dtype_out, opA == NNT_OP_T, opB == NNT_OP_N, cfg, g, nwg, fast ? nwg : 0);
 }
 
@@ -541,10 +542,11 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
     // workgroups that qualify for the direct-load kernel go first in every launch range
     P->task_nfast.assign(P->task_ctile.size(), 0);
     if (bf && (P->cfg == kCfgSquare || P->cfg == kCfgTall)) {
+        const int kmul = P->cfg == kCfgSquare ? 64 : 32;   // the 256 x 256 kernel loads two k-steps at a time
         std::vector<char> task_ok(P->tasks.size(), 1);
         for (size_t ti = 0; ti < P->tasks.size(); ti++)
             for (int32_t q = P->tasks[ti].chunk0; q < P->tasks[ti].chunk0 + P->tasks[ti].nchunk; q++)
-                if (P->chunks[q].vec_ok != 3 || P->chunks[q].k <= 0 || P->chunks[q].k % 32 != 0) task_ok[ti] = 0;
+                if (P->chunks[q].vec_ok != 3 || P->chunks[q].k <= 0 || P->chunks[q].k % kmul != 0) task_ok[ti] = 0;
         auto qualifies = [&](const GemmWg& w) {
             const GemmTask& t = P->tasks[w.task];
             return task_ok[w.task] && w.m0 + bm <= t.m && w.n0 + bn <= t.n;

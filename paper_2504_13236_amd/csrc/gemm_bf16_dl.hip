@@ -29,6 +29,7 @@
 #include "nntile_mi.h"
 
 #include <type_traits>
+#include <utility>
 
 namespace nnt {
 
@@ -76,26 +77,23 @@ __device__ __forceinline__ ChunkS sload_chunk(const GemmChunk* p) {
     return r;
 }
 
-// Starts load instruction j (0 .. ROWS / 64 - 1) of this wave for one operand of one k-step.  `tile`
-// points at (first row, first k) of the ROWS x 32 block, `dst` at its LDS region; both are the same
-// for all lanes.
+// Byte offset, from (first row, first k) of an operand's ROWS x 32 block, of what this lane
+// fetches in load instruction j (0 .. ROWS / 64 - 1) of its wave; the data lands in LDS at
+// (wave * ROWS / 64 + j) * 1024 + 16 * lane of the operand's region.
 template <bool KF, int ROWS>
-__device__ __forceinline__ void issue_one(const uint16_t* tile, int ld, char* dst, int wave, int lane, int j) {
+__device__ __forceinline__ uint32_t load_offset(int ld, int wave, int lane, int j) {
     constexpr int NI = ROWS / 64;                            // instructions per wave and step
-    const uint16_t* gp;
     if (KF) {
         // an instruction covers 16 rows; lane -> row lane / 4, slot lane % 4
         const int r = lane >> 2;
         const int c = (lane & 3) ^ ((r >> 2) & 3);
-        gp = tile + (int64_t)(16 * (NI * wave + j)) * ld + (uint32_t)(r * ld + c * 8);
-    } else {
-        // an instruction covers 1024 / (2 ROWS) k-lines; lane -> line lane / LPL, slot lane % LPL
-        constexpr int LPL = ROWS / 8, LPI = 64 / LPL;        // lanes per line, lines per instruction
-        const int kk = LPI * j + lane / LPL;                 // line within the wave's 8; 8 * wave is 0 mod 4
-        const int c = (lane % LPL) ^ ((kk & 3) << 2);
-        gp = tile + (int64_t)(8 * wave + LPI * j) * ld + (uint32_t)((lane / LPL) * ld + c * 8);
+        return (uint32_t)(((16 * (NI * wave + j) + r) * ld + c * 8) * 2);
     }
-    __builtin_amdgcn_global_load_lds((glb_void_ptr)gp, (lds_void_ptr)(dst + (wave * NI + j) * 1024), 16, 0, 0);
+    // an instruction covers 1024 / (2 ROWS) k-lines; lane -> line lane / LPL, slot lane % LPL
+    constexpr int LPL = ROWS / 8, LPI = 64 / LPL;            // lanes per line, lines per instruction
+    const int kk = LPI * j + lane / LPL;                     // line within the wave's 8; 8 * wave is 0 mod 4
+    const int c = (lane % LPL) ^ ((kk & 3) << 2);
+    return (uint32_t)(((8 * wave + kk) * ld + c * 8) * 2);
 }
 
 // Per-lane part of the fragment address of an operand region of ROWS rows.
@@ -137,26 +135,55 @@ struct Frag<false> {
     }
 };
 
-// Starts the read of the fragment of 32-row block `blk` of an operand region of ROWS rows (LDS
-// byte offset `region`) for substep ks (16 k each).
-template <bool KF, int ROWS>
-__device__ __forceinline__ void read_frag(Frag<KF>& f, uint32_t region, uint32_t lane_off, int blk, int ks) {
+// Starts the read of fragment B (the wave's B-th 32-row block) of an operand for substep KS (16 k
+// each).  `addr` is the LDS byte address of the stage plus everything that depends on the lane
+// and the wave (see FragAddr); the rest is an immediate, REGION being the operand's offset inside
+// the stage.
+template <bool KF, int ROWS, int REGION, int B, int KS>
+__device__ __forceinline__ void read_frag(Frag<KF>& f, uint32_t addr) {
     if constexpr (KF) {
-        const uint32_t addr = region + blk * 2048 + (lane_off ^ (uint32_t)(ks * 32));
-        asm volatile("ds_read_b128 %0, %1" : "=v"(f.v) : "v"(addr));
+        asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(f.v) : "v"(addr), "n"(REGION + B * 2048));
     } else {
         constexpr int LB = 2 * ROWS;                            // bytes of a k-line
-        const uint32_t addr = region + ks * 16 * LB + (blk >> 2) * 256 + (lane_off ^ (uint32_t)((blk & 3) * 64));
-        asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(f.lo) : "v"(addr));
-        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(f.hi) : "v"(addr), "n"(4 * LB));
+        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(f.lo) : "v"(addr), "n"(REGION + KS * 16 * LB));
+        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(f.hi) : "v"(addr), "n"(REGION + KS * 16 * LB + 4 * LB));
     }
 }
 
-// Macro-tile 256 x 64 WNB: WNB = 4 has a CU to itself (four stages), WNB = 2 leaves room for two
-// workgroups per CU (three stages each), which cover each other's first loads and result stores.
+// Lane- and wave-dependent parts of the fragment addresses of one operand, relative to the stage.
+// k-contiguous operand: one value per substep (the substep flips bit 5 of the lane's offset), the
+// block index is an immediate.  Row-contiguous operand: one value per block (the block index
+// enters through an xor), the substep is an immediate.
+template <bool KF, int ROWS, int NB>
+struct FragAddr {
+    static constexpr int N = KF ? 2 : NB;
+    uint32_t v[N];
+    __device__ __forceinline__ void init(int lane, int first_blk) {
+        const uint32_t lo = frag_lane_offset<KF, ROWS>(lane);
+        if constexpr (KF) {
+            v[0] = lo + first_blk * 2048;
+            v[1] = (lo ^ 32u) + first_blk * 2048;
+        } else {
+#pragma unroll
+            for (int b = 0; b < NB; b++) v[b] = (lo ^ (uint32_t)(((first_blk + b) & 3) * 64)) + ((first_blk + b) >> 2) * 256;
+        }
+    }
+    template <int B, int KS>
+    __device__ __forceinline__ uint32_t at(uint32_t stage_addr) const { return stage_addr + v[KF ? KS : B]; }
+};
+
+template <typename F, int... I>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
 template <int WNB>
 struct DlShape {
-    static constexpr int kStages = WNB == 4 ? 4 : 3;
+    static constexpr int kStages = WNB == 4 ? 5 : 3;
     static constexpr int kStageBytes = (256 + 64 * WNB) * kBK * 2;
     static constexpr int kLdsBytes = kStages * kStageBytes;
 };
@@ -168,6 +195,10 @@ __device__ __forceinline__ void dl_body(const GemmArgs& g, char* lds) {
     constexpr int kOpABytes = BM * kBK * 2, kStageBytes = DlShape<WNB>::kStageBytes;
     constexpr int NIA = BM / 64, NIB = BN / 64, kLoads = NIA + NIB;     // load instructions per wave and step
     constexpr int kFrags = WNB + WMB, kMfma = WNB * WMB;
+    // The 256 x 256 shape starts its loads two k-steps at a time (see the loop below); its chunks
+    // must be multiples of 64 long.
+    constexpr bool kPaired = WNB == 4;
+    static_assert(!kPaired || kStages == 5, "the paired schedule needs five stages");
     static_assert(4 * 32 * (32 * WMB + 4) * 4 <= kStages * kStageBytes, "result staging must fit the pipeline's LDS");
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -213,25 +244,30 @@ __device__ __forceinline__ void dl_body(const GemmArgs& g, char* lds) {
 
     if (T > 0) {
         const int chunk_end = chunk_i + __builtin_amdgcn_readfirstlane(task.nchunk);
-        // Position of the next k-step to load (all uniform).  Loads are started for every step of
-        // the loop, needed or not, so that the count of loads in flight is the same at every wait:
-        // once the last real step has been started the position stays where it is and the spare
+        // Position of the next k-step to load.  A lane's loads of a step are `base + offset` with a
+        // uniform base that moves on by a fixed amount per step and per-lane byte offsets that only
+        // change with the chunk (they depend on the leading dimension).  Loads are started for every
+        // step of the loop, needed or not, so that the count of loads in flight is the same at every
+        // wait: once the last real step has been started the position stays where it is and the spare
         // loads fetch that step again into a stage nobody reads.
-        int k0 = 0, chk = 0, lda = 0, ldb = 0, to_issue = T;
-        const uint16_t* Ab = nullptr;
-        const uint16_t* Bb = nullptr;
-        const uint16_t* At = nullptr;
-        const uint16_t* Bt = nullptr;
+        int k0 = 0, chk = 0, to_issue = T;
+        const char* baseA = nullptr;
+        const char* baseB = nullptr;
+        int64_t advA = 0, advB = 0;
+        uint32_t voffA[NIA], voffB[NIB];
         auto set_chunk = [&](const ChunkS& ch) {
             chk = ch.k;
-            lda = (int)ch.lda;
-            ldb = (int)ch.ldb;
-            Ab = reinterpret_cast<const uint16_t*>(ch.A) + (int64_t)bat * ch.strideA;
-            Bb = reinterpret_cast<const uint16_t*>(ch.B) + (int64_t)bat * ch.strideB;
-        };
-        auto set_step = [&]() {
-            At = AKF ? Ab + (int64_t)m0 * lda + k0 : Ab + m0 + (int64_t)k0 * lda;
-            Bt = BKF ? Bb + (int64_t)n0 * ldb + k0 : Bb + n0 + (int64_t)k0 * ldb;
+            const int lda = (int)ch.lda, ldb = (int)ch.ldb;
+            const uint16_t* Ab = reinterpret_cast<const uint16_t*>(ch.A) + (int64_t)bat * ch.strideA;
+            const uint16_t* Bb = reinterpret_cast<const uint16_t*>(ch.B) + (int64_t)bat * ch.strideB;
+            baseA = reinterpret_cast<const char*>(AKF ? Ab + (int64_t)m0 * lda : Ab + m0);
+            baseB = reinterpret_cast<const char*>(BKF ? Bb + (int64_t)n0 * ldb : Bb + n0);
+            advA = AKF ? kBK * 2 : (int64_t)kBK * lda * 2;
+            advB = BKF ? kBK * 2 : (int64_t)kBK * ldb * 2;
+#pragma unroll
+            for (int j = 0; j < NIA; j++) voffA[j] = load_offset<AKF, BM>(lda, wave, lane, j);
+#pragma unroll
+            for (int j = 0; j < NIB; j++) voffB[j] = load_offset<BKF, BN>(ldb, wave, lane, j);
         };
         if (table) {
             set_chunk(sload_chunk(g.chunks + chunk_i));
@@ -243,12 +279,15 @@ __device__ __forceinline__ void dl_body(const GemmArgs& g, char* lds) {
             one.k = g.one_chunk.k; one.vec_ok = g.one_chunk.vec_ok;
             set_chunk(one);
         }
-        set_step();
         // load instruction i (first those of A, then those of B) of the k-step at the current position
         auto load_one = [&](int stage, int i) {
             char* sa = lds + stage * kStageBytes;
-            if (i < NIA) issue_one<AKF, BM>(At, lda, sa, wave, lane, i);
-            else issue_one<BKF, BN>(Bt, ldb, sa + kOpABytes, wave, lane, i - NIA);
+            if (i < NIA) {
+                __builtin_amdgcn_global_load_lds((glb_void_ptr)(baseA + voffA[i]), (lds_void_ptr)(sa + (wave * NIA + i) * 1024), 16, 0, 0);
+            } else {
+                const int j = i - NIA;
+                __builtin_amdgcn_global_load_lds((glb_void_ptr)(baseB + voffB[j]), (lds_void_ptr)(sa + kOpABytes + (wave * NIB + j) * 1024), 16, 0, 0);
+            }
         };
         auto advance = [&]() {
             if (--to_issue > 0) {
@@ -257,27 +296,75 @@ __device__ __forceinline__ void dl_body(const GemmArgs& g, char* lds) {
                     chunk_i++;
                     k0 = 0;
                     if (chunk_i < chunk_end) set_chunk(sload_chunk(g.chunks + chunk_i));
+                } else {
+                    baseA += advA;
+                    baseB += advB;
                 }
-                set_step();
             } else {
                 to_issue = 1;
             }
         };
-        for (int s = 0; s < kStages - 1; s++) {
+        // Paired schedule: load instruction i (0 .. 2 kLoads - 1) of the two k-steps at the current
+        // position.  The two steps take the two 64-byte halves of the same 128-byte lines of a
+        // k-contiguous operand; asking for both halves back to back lets the second request ride on
+        // the first one's miss (measured: half-line requests issued a step apart stall the wave
+        // at issue and cost about a fifth of the matrix rate, paired ones cost nothing).
+        auto load_pair_item = [&](int stage_x, int stage_y, int i) {
+            const int j = i >> 1, second = i & 1;
+            char* sa = lds + (second ? stage_y : stage_x) * kStageBytes;
+            if (j < NIA) {
+                __builtin_amdgcn_global_load_lds((glb_void_ptr)(baseA + (second ? advA : 0) + voffA[j]),
+                                                 (lds_void_ptr)(sa + (wave * NIA + j) * 1024), 16, 0, 0);
+            } else {
+                const int jb = j - NIA;
+                __builtin_amdgcn_global_load_lds((glb_void_ptr)(baseB + (second ? advB : 0) + voffB[jb]),
+                                                 (lds_void_ptr)(sa + kOpABytes + (wave * NIB + jb) * 1024), 16, 0, 0);
+            }
+        };
+        // moves the position on by two k-steps (chunks are multiples of 64 long)
+        auto advance2 = [&]() {
+            to_issue -= 2;
+            if (to_issue > 0) {
+                k0 += 2 * kBK;
+                if (k0 >= chk) {
+                    chunk_i++;
+                    k0 = 0;
+                    if (chunk_i < chunk_end) set_chunk(sload_chunk(g.chunks + chunk_i));
+                } else {
+                    baseA += 2 * advA;
+                    baseB += 2 * advB;
+                }
+            } else {
+                to_issue = 2;
+            }
+        };
+        if constexpr (kPaired) {
 #pragma unroll
-            for (int i = 0; i < kLoads; i++) load_one(s, i);
-            advance();
+            for (int i = 0; i < 2 * kLoads; i++) load_pair_item(0, 1, i);
+            advance2();
+#pragma unroll
+            for (int i = 0; i < 2 * kLoads; i++) load_pair_item(2, 3, i);
+            advance2();
+        } else {
+            for (int s = 0; s < kStages - 1; s++) {
+#pragma unroll
+                for (int i = 0; i < kLoads; i++) load_one(s, i);
+                advance();
+            }
         }
 
-        const uint32_t offA = frag_lane_offset<AKF, BM>(lane), offB = frag_lane_offset<BKF, BN>(lane);
+        FragAddr<AKF, BM, WMB> fa;
+        FragAddr<BKF, BN, WNB> fb;
+        fa.init(lane, wm * WMB);
+        fb.init(lane, wn * WNB);
         Frag<BKF> pf[2][WNB];
         Frag<AKF> qf[2][WMB];
         const uint32_t lds0 = lds_offset(lds);
-        // fragment i (first the column blocks of B, then the row blocks of A) of a substep
-        auto frag_one = [&](int buf, int stage, int ks, int i) {
-            const uint32_t sa = lds0 + stage * kStageBytes;
-            if (i < WNB) read_frag<BKF, BN>(pf[buf][i], sa + kOpABytes, offB, wn * WNB + i, ks);
-            else read_frag<AKF, BM>(qf[buf][i - WNB], sa, offA, wm * WMB + i - WNB, ks);
+        // fragment I (first the column blocks of B, then the row blocks of A) of substep KS of a stage
+        auto frag_one = [&](auto I, auto KS, int buf, uint32_t stage_addr) {
+            constexpr int i = decltype(I)::value, ks = decltype(KS)::value;
+            if constexpr (i < WNB) read_frag<BKF, BN, kOpABytes, i, ks>(pf[buf][i], fb.template at<i, ks>(stage_addr));
+            else read_frag<AKF, BM, 0, i - WNB, ks>(qf[buf][i - WNB], fa.template at<i - WNB, ks>(stage_addr));
         };
         // all fragment reads issued so far have landed; the matrix instructions on set `buf` stay behind this
         auto wait_frags = [&](int buf) {
@@ -292,44 +379,82 @@ __device__ __forceinline__ void dl_body(const GemmArgs& g, char* lds) {
             acc[bn][bm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[buf][bm].value(), pf[buf][bn].value(), acc[bn][bm], 0, 0, 0);
         };
         // One substep: the matrix instructions on fragment set `buf`; under them the fragments of
-        // the next substep are fetched into the other set and, with `with_loads`, the load
-        // instructions of a k-step are started.  The pieces are dealt out evenly over the matrix
-        // instructions and fenced so that they stay there.
-        auto substep = [&](auto with_loads, int buf, int f_stage, int f_ks, int load_stage) {
-            constexpr int kItems = kFrags + (decltype(with_loads)::value ? kLoads : 0);
+        // substep F_KS of the stage at `f_addr` are fetched into the other set and NL load
+        // instructions are started through `load(i)`.  The pieces are dealt out evenly over the
+        // matrix instructions and fenced so that they stay there.
+        auto substep = [&](auto NL, auto F_KS, int buf, uint32_t f_addr, auto&& load) {
+            constexpr int kItems = kFrags + decltype(NL)::value;
             wait_frags(buf);
             __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int q = 0; q < kMfma; q++) {
+            static_for<kMfma>([&](auto Q) {
+                constexpr int q = decltype(Q)::value;
                 mfma_one(buf, q);
-#pragma unroll
-                for (int i = 0; i < kItems; i++) {
-                    if (i * kMfma / kItems != q) continue;
-                    if (i < kFrags) frag_one(buf ^ 1, f_stage, f_ks, i);
-                    else load_one(load_stage, i - kFrags);
-                }
+                static_for<kItems>([&](auto I) {
+                    constexpr int i = decltype(I)::value;
+                    if constexpr (i * kMfma / kItems == q) {
+#ifndef NNT_EXP
+                        if constexpr (i < kFrags) frag_one(I, F_KS, buf ^ 1, f_addr);
+                        else load(i - kFrags);
+#else
+                        if constexpr (i < kFrags) { if (NNT_EXP != 2 && NNT_EXP != 3) frag_one(I, F_KS, buf ^ 1, f_addr); }
+                        else { if (NNT_EXP != 1 && NNT_EXP != 3) load(i - kFrags); }
+#endif
+                    }
+                });
                 __builtin_amdgcn_sched_barrier(0);
-            }
+            });
         };
-        // step 0 has landed in this wave's part once only the loads of steps 1 .. kStages - 2 remain
-        __builtin_amdgcn_s_waitcnt(wait_vm((kStages - 2) * kLoads));
-        asm volatile("s_barrier" ::: "memory");
-#pragma unroll
-        for (int i = 0; i < kFrags; i++) frag_one(0, 0, 0, i);
-        int stage = 0, next_stage = kStages - 1;
-        for (int t = 0; t < T; t++) {
-            const int stage1 = stage + 1 == kStages ? 0 : stage + 1;
-            substep(std::false_type{}, 0, stage, 1, 0);
-            // step t + 1 complete for everybody (loads of steps t + 2 .. t + kStages - 2 may remain),
-            // and everybody done with the stage of step t - 1, which the next loads overwrite
-            __builtin_amdgcn_s_waitcnt(wait_vm((kStages - 3) * kLoads));
+        auto no_load = [](int) {};
+        using KS0 = std::integral_constant<int, 0>;
+        using KS1 = std::integral_constant<int, 1>;
+        using None = std::integral_constant<int, 0>;
+        auto stage_addr = [&](int st) { return lds0 + (uint32_t)(st * kStageBytes); };
+        auto next_of = [](int st) { return st + 1 == kStages ? 0 : st + 1; };
+        if constexpr (kPaired) {
+            // Steps come in pairs (2u, 2u + 1); the loads of a pair are started together, under the
+            // second half of the odd step, four steps ahead.
+            __builtin_amdgcn_s_waitcnt(wait_vm(2 * kLoads));          // pair 0 landed; pair 1 may remain
             asm volatile("s_barrier" ::: "memory");
-            // (after the last step the fragment reads hit a stage that holds no new data: in bounds
-            // and unused)
-            substep(std::true_type{}, 1, stage1, 0, next_stage);
-            advance();
-            next_stage = next_stage + 1 == kStages ? 0 : next_stage + 1;
-            stage = stage1;
+            static_for<kFrags>([&](auto I) { frag_one(I, KS0{}, 0, lds0); });
+            int st = 0;                                               // stage of step 2u
+            for (int u = 0; u < T / 2; u++) {
+                const int s1 = next_of(st), s2 = next_of(s1), s3 = next_of(s2), s4 = next_of(s3);
+                substep(None{}, KS1{}, 0, stage_addr(st), no_load);
+                // pair u complete for everybody (pair u + 1 may remain in flight)
+                __builtin_amdgcn_s_waitcnt(wait_vm(2 * kLoads));
+                asm volatile("s_barrier" ::: "memory");
+                substep(None{}, KS0{}, 1, stage_addr(s1), no_load);
+                substep(None{}, KS1{}, 0, stage_addr(s1), no_load);
+                // pair u + 1 complete for everybody, and everybody done with the stages of steps
+                // 2u - 1 and 2u, which the next pair of loads overwrites
+                __builtin_amdgcn_s_waitcnt(wait_vm(0));
+                asm volatile("s_barrier" ::: "memory");
+                // (after the last pair the fragment reads hit a stage that holds no new data: in
+                // bounds and unused)
+                substep(std::integral_constant<int, 2 * kLoads>{}, KS0{}, 1, stage_addr(s2), [&](int i) { load_pair_item(s4, st, i); });
+                advance2();
+                st = s2;
+            }
+        } else {
+            // step 0 has landed in this wave's part once only the loads of steps 1 .. kStages - 2 remain
+            __builtin_amdgcn_s_waitcnt(wait_vm((kStages - 2) * kLoads));
+            asm volatile("s_barrier" ::: "memory");
+            static_for<kFrags>([&](auto I) { frag_one(I, KS0{}, 0, lds0); });
+            int stage = 0, next_stage = kStages - 1;
+            for (int t = 0; t < T; t++) {
+                const int stage1 = next_of(stage);
+                substep(None{}, KS1{}, 0, stage_addr(stage), no_load);
+                // step t + 1 complete for everybody (loads of steps t + 2 .. t + kStages - 2 may
+                // remain), and everybody done with the stage of step t - 1, which the next loads overwrite
+                __builtin_amdgcn_s_waitcnt(wait_vm((kStages - 3) * kLoads));
+                asm volatile("s_barrier" ::: "memory");
+                // (after the last step the fragment reads hit a stage that holds no new data: in
+                // bounds and unused)
+                substep(std::integral_constant<int, kLoads>{}, KS0{}, 1, stage_addr(stage1), [&](int i) { load_one(next_stage, i); });
+                advance();
+                next_stage = next_of(next_stage);
+                stage = stage1;
+            }
         }
         // nothing may still be on its way into LDS or into fragment registers when the results are staged
         asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");

@@ -70,7 +70,7 @@ inline void gemm_cfg_tile(int dtype_is_bf16, int cfg, int* bm, int* bn) {
 int32_t launch_gemm_f32(hipStream_t st, int akf, int bkf, int cfg, const GemmArgs& g, int64_t nwg);
 int32_t launch_gemm_bf16(hipStream_t st, int out_is_f32, int akf, int bkf, int cfg, const GemmArgs& g, int64_t nwg);
 // 256 x 256 (kCfgSquare) or 256 x 128 (kCfgTall) macro-tiles that lie wholly inside their C tile, with 16-byte aligned operands and
-// chunk lengths that are multiples of 32 (loads go straight to LDS)
+// chunk lengths that are multiples of 64 (kCfgSquare) or 32 (kCfgTall); loads go straight to LDS
 int32_t launch_gemm_bf16_dl(hipStream_t st, int out_is_f32, int akf, int bkf, int cfg, const GemmArgs& g, int64_t nwg);
 int gemm_bf16_dl_occupancy(int out_is_f32, int akf, int bkf, int cfg);
 // workgroups of the kernel instance that a compute unit holds at a time (registers, LDS)
