@@ -92,16 +92,19 @@ void drop_plans_of(nnt_ctx* ctx, uint64_t id) {
     }
 }
 
-// The first `nfast` workgroups of the table qualify for the direct-load kernel (bf16, 256 rows).
+// The first `nfast` workgroups of the table qualify for the direct-load kernel of the type.
 static int32_t launch_any(hipStream_t st, int dtype_in, int dtype_out, int akf, int bkf, int cfg,
                           const GemmArgs& g, int64_t nwg, int64_t nfast = 0) {
-    if (dtype_in == NNT_F32) return launch_gemm_f32(st, akf, bkf, cfg, g, nwg);
-    if (nfast <= 0) return launch_gemm_bf16(st, dtype_out == NNT_F32, akf, bkf, cfg, g, nwg);
-    int32_t rc = launch_gemm_bf16_dl(st, dtype_out == NNT_F32, akf, bkf, cfg, g, nfast);
+    const bool f32 = dtype_in == NNT_F32;
+    auto general = [&](const GemmArgs& ga, int64_t n) {
+        return f32 ? launch_gemm_f32(st, akf, bkf, cfg, ga, n) : launch_gemm_bf16(st, dtype_out == NNT_F32, akf, bkf, cfg, ga, n);
+    };
+    if (nfast <= 0) return general(g, nwg);
+    int32_t rc = f32 ? launch_gemm_f32_dl(st, akf, bkf, g, nfast) : launch_gemm_bf16_dl(st, dtype_out == NNT_F32, akf, bkf, cfg, g, nfast);
     if (rc != NNT_OK || nfast == nwg) return rc;
     GemmArgs rest = g;
     if (rest.wgs) rest.wgs += nfast;
-    return launch_gemm_bf16(st, dtype_out == NNT_F32, akf, bkf, cfg, rest, nwg - nfast);
+    return general(rest, nwg - nfast);
 }
 
 static int vec_flag(const void* p, int64_t ld, int64_t stride, int elem) {
@@ -183,7 +186,7 @@ static ShapeChoice choose_shape(bool bf16, bool out_f32, int akf, int bkf, const
     // rate of a compute unit with its full set of workgroups; start-up time of a workgroup; factor by
     // which a workgroup that is alone on its unit is slower than its share of that rate
     struct Cand { int cfg; double flops_per_s_cu; double t0; double solo; };
-    static const Cand f32c[] = {{kCfgSquare, 0.515e12, 2.5e-6, 1.2}, {kCfgMid, 0.45e12, 2.0e-6, 1.3}};
+    static const Cand f32c[] = {{kCfgSquare, 0.56e12, 2.5e-6, 1.15}, {kCfgMid, 0.45e12, 2.0e-6, 1.3}};
     static const Cand bf16c[] = {{kCfgSquare, 4.4e12, 8.0e-6, 1.0}, {kCfgTall, 4.2e12, 3.0e-6, 1.6}, {kCfgMid, 1.6e12, 3.0e-6, 1.5}};
     const Cand* cands = bf16 ? bf16c : f32c;
     const int ncand = bf16 ? 3 : 2;
@@ -195,7 +198,7 @@ static ShapeChoice choose_shape(bool bf16, bool out_f32, int akf, int bkf, const
         const Cand& cd = cands[ci];
         int bm, bn;
         gemm_cfg_tile(bf16, cd.cfg, &bm, &bn);
-        const int occ = !bf16 ? gemm_f32_occupancy(akf, bkf, cd.cfg)
+        const int occ = !bf16 ? (cd.cfg == kCfgSquare ? gemm_f32_dl_occupancy(akf, bkf) : gemm_f32_occupancy(akf, bkf, cd.cfg))
                         : (cd.cfg == kCfgMid ? gemm_bf16_occupancy(out_f32, akf, bkf, cd.cfg) : gemm_bf16_dl_occupancy(out_f32, akf, bkf, cd.cfg));
         const int64_t G = 256 * (int64_t)occ;      // workgroups resident at a time
         int64_t W = 0;
@@ -286,8 +289,8 @@ extern "C" int32_t nnt_tile_gemm(void* stream, int32_t dtype_in, int32_t dtype_o
     g.grid_n = (int32_t)((n + bn - 1) / bn);
     const int64_t nwg = (int64_t)g.grid_m * g.grid_n * batch;
     if (nwg > INT32_MAX) return NNT_EINVAL;
-    const bool fast = bf && (cfg == kCfgSquare || cfg == kCfgTall) && m % bm == 0 && n % bn == 0 && k > 0 && k % (cfg == kCfgSquare ? 64 : 32) == 0 &&
-                      g.one_chunk.vec_ok == 3;
+    const bool fast = (bf ? (cfg == kCfgSquare || cfg == kCfgTall) : cfg == kCfgSquare) && m % bm == 0 && n % bn == 0 && k > 0 &&
+                      k % ((bf && cfg == kCfgSquare) ? 64 : 32) == 0 && g.one_chunk.vec_ok == 3;
     return launch_any((hipStream_t)stream, dtype_in, dtype_out, opA == NNT_OP_T, opB == NNT_OP_N, cfg, g, nwg, fast ? nwg : 0);
 }
 
@@ -541,8 +544,8 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
 
     // workgroups that qualify for the direct-load kernel go first in every launch range
     P->task_nfast.assign(P->task_ctile.size(), 0);
-    if (bf && (P->cfg == kCfgSquare || P->cfg == kCfgTall)) {
-        const int kmul = P->cfg == kCfgSquare ? 64 : 32;   // the 256 x 256 kernel loads two k-steps at a time
+    if (bf ? (P->cfg == kCfgSquare || P->cfg == kCfgTall) : P->cfg == kCfgSquare) {
+        const int kmul = (bf && P->cfg == kCfgSquare) ? 64 : 32;   // loads are started two k-steps at a time
         std::vector<char> task_ok(P->tasks.size(), 1);
         for (size_t ti = 0; ti < P->tasks.size(); ti++)
             for (int32_t q = P->tasks[ti].chunk0; q < P->tasks[ti].chunk0 + P->tasks[ti].nchunk; q++)
@@ -560,8 +563,11 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
             const std::string old_name = P->label.substr(0, P->label.find('>') + 1);
             const char* tf[2] = {"false", "true"};
             std::ostringstream l;
-            l << (P->cfg == kCfgTall ? "gemm_bf16_dl_tall_kernel<" : "gemm_bf16_dl_kernel<") << (C->dtype == NNT_F32 ? "float" : "unsigned short")
-              << ", " << tf[P->akf] << ", " << tf[P->bkf] << ">";
+            if (bf)
+                l << (P->cfg == kCfgTall ? "gemm_bf16_dl_tall_kernel<" : "gemm_bf16_dl_kernel<") << (C->dtype == NNT_F32 ? "float" : "unsigned short")
+                  << ", " << tf[P->akf] << ", " << tf[P->bkf] << ">";
+            else
+                l << "gemm_f32_dl_kernel<" << tf[P->akf] << ", " << tf[P->bkf] << ">";
             P->label = l.str() + P->label.substr(old_name.size());
         }
     }

@@ -115,6 +115,16 @@ def test_gemm_bf16_whole_macro_tiles_aligned(capi, opA, opB, m, n, k, dout):
         assert e <= (2e-2 if dout == "bf16" else 1e-5), ("gemm bf16->%s %s%s %dx%dx%d b%d" % (dout, opA, opB, m, n, k, batch), e)
 
 
+@pytest.mark.parametrize("opA,opB", list(itertools.product("NT", "NT")))
+@pytest.mark.parametrize("m,n,k", [(128, 128, 32), (256, 384, 96), (512, 256, 416)])
+def test_gemm_f32_whole_macro_tiles_aligned(capi, opA, opB, m, n, k):
+    """fp32 shapes made of whole 128 x 128 macro-tiles with k a multiple of 32 and 16-byte aligned operands:
+    the fp32 kernel that loads straight into LDS (short and long k, padded leading dimensions, batch, beta)."""
+    for batch, alpha, beta, pad in ((1, 1.0, 0.0, 0), (2, 0.7, -1.3, 4)):
+        got, ref = run_gemm(capi, "f32", "f32", opA, opB, m, n, k, batch, alpha, beta, pad, seed=m + n + k)
+        check(got, ref, "f32", "gemm f32 %s%s %dx%dx%d b%d" % (opA, opB, m, n, k, batch))
+
+
 def test_gemm_degenerate(capi):
     # k = 0: C <- beta * C; beta = 0 must not propagate NaNs already in C
     C0 = rng(1).standard_normal((9, 5)).astype(np.float32)
