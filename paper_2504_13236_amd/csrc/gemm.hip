@@ -100,7 +100,7 @@ static int32_t launch_any(hipStream_t st, int dtype_in, int dtype_out, int akf, 
         return f32 ? launch_gemm_f32(st, akf, bkf, cfg, ga, n) : launch_gemm_bf16(st, dtype_out == NNT_F32, akf, bkf, cfg, ga, n);
     };
     if (nfast <= 0) return general(g, nwg);
-    int32_t rc = f32 ? launch_gemm_f32_dl(st, akf, bkf, g, nfast) : launch_gemm_bf16_dl(st, dtype_out == NNT_F32, akf, bkf, cfg, g, nfast);
+    int32_t rc = f32 ? launch_gemm_f32_dl(st, akf, bkf, cfg, g, nfast) : launch_gemm_bf16_dl(st, dtype_out == NNT_F32, akf, bkf, cfg, g, nfast);
     if (rc != NNT_OK || nfast == nwg) return rc;
     GemmArgs rest = g;
     if (rest.wgs) rest.wgs += nfast;
@@ -186,7 +186,7 @@ static ShapeChoice choose_shape(bool bf16, bool out_f32, int akf, int bkf, const
     // rate of a compute unit with its full set of workgroups; start-up time of a workgroup; factor by
     // which a workgroup that is alone on its unit is slower than its share of that rate
     struct Cand { int cfg; double flops_per_s_cu; double t0; double solo; };
-    static const Cand f32c[] = {{kCfgSquare, 0.56e12, 2.5e-6, 1.15}, {kCfgMid, 0.45e12, 2.0e-6, 1.3}};
+    static const Cand f32c[] = {{kCfgSquare, 0.56e12, 2.5e-6, 1.7}, {kCfgMid, 0.45e12, 2.0e-6, 1.3}};
     static const Cand bf16c[] = {{kCfgSquare, 4.4e12, 8.0e-6, 1.0}, {kCfgTall, 4.2e12, 3.0e-6, 1.6}, {kCfgMid, 1.6e12, 3.0e-6, 1.5}};
     const Cand* cands = bf16 ? bf16c : f32c;
     const int ncand = bf16 ? 3 : 2;
@@ -198,7 +198,7 @@ static ShapeChoice choose_shape(bool bf16, bool out_f32, int akf, int bkf, const
         const Cand& cd = cands[ci];
         int bm, bn;
         gemm_cfg_tile(bf16, cd.cfg, &bm, &bn);
-        const int occ = !bf16 ? (cd.cfg == kCfgSquare ? gemm_f32_dl_occupancy(akf, bkf) : gemm_f32_occupancy(akf, bkf, cd.cfg))
+        const int occ = !bf16 ? (cd.cfg == kCfgSquare ? gemm_f32_dl_occupancy(akf, bkf, cd.cfg) : gemm_f32_occupancy(akf, bkf, cd.cfg))
                         : (cd.cfg == kCfgMid ? gemm_bf16_occupancy(out_f32, akf, bkf, cd.cfg) : gemm_bf16_dl_occupancy(out_f32, akf, bkf, cd.cfg));
         const int64_t G = 256 * (int64_t)occ;      // workgroups resident at a time
         int64_t W = 0;
@@ -231,7 +231,7 @@ static ShapeChoice choose_shape(bool bf16, bool out_f32, int akf, int bkf, const
 }
 
 static int pick_cfg(int bf16, int64_t m_max, int64_t n_max, int64_t n_tiles_big, int64_t k_max) {
-    if (m_max <= 64) return kCfgSkinny64;
+    if (m_max <= 64) return bf16 ? kCfgSkinny64 : kCfgSkinny64n128;   // fp32: the shape its direct-load kernel has
     if (m_max <= 128 && n_max > 128) return kCfgSkinny128;
     if (bf16 && (m_max <= 128 || n_max <= 128 || n_tiles_big < 256)) return kCfgMid;
     // short contractions are bound by the result stores: several small workgroups per compute
@@ -289,7 +289,7 @@ extern "C" int32_t nnt_tile_gemm(void* stream, int32_t dtype_in, int32_t dtype_o
     g.grid_n = (int32_t)((n + bn - 1) / bn);
     const int64_t nwg = (int64_t)g.grid_m * g.grid_n * batch;
     if (nwg > INT32_MAX) return NNT_EINVAL;
-    const bool fast = (bf ? (cfg == kCfgSquare || cfg == kCfgTall) : cfg == kCfgSquare) && m % bm == 0 && n % bn == 0 && k > 0 &&
+    const bool fast = (bf ? (cfg == kCfgSquare || cfg == kCfgTall) : (cfg == kCfgSquare || cfg == kCfgSkinny64n128)) && m % bm == 0 && n % bn == 0 && k > 0 &&
                       k % ((bf && cfg == kCfgSquare) ? 64 : 32) == 0 && g.one_chunk.vec_ok == 3;
     return launch_any((hipStream_t)stream, dtype_in, dtype_out, opA == NNT_OP_T, opB == NNT_OP_N, cfg, g, nwg, fast ? nwg : 0);
 }
@@ -544,7 +544,7 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
 
     // workgroups that qualify for the direct-load kernel go first in every launch range
     P->task_nfast.assign(P->task_ctile.size(), 0);
-    if (bf ? (P->cfg == kCfgSquare || P->cfg == kCfgTall) : P->cfg == kCfgSquare) {
+    if (bf ? (P->cfg == kCfgSquare || P->cfg == kCfgTall) : (P->cfg == kCfgSquare || P->cfg == kCfgSkinny64n128)) {
         const int kmul = (bf && P->cfg == kCfgSquare) ? 64 : 32;   // loads are started two k-steps at a time
         std::vector<char> task_ok(P->tasks.size(), 1);
         for (size_t ti = 0; ti < P->tasks.size(); ti++)
@@ -567,7 +567,7 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
                 l << (P->cfg == kCfgTall ? "gemm_bf16_dl_tall_kernel<" : "gemm_bf16_dl_kernel<") << (C->dtype == NNT_F32 ? "float" : "unsigned short")
                   << ", " << tf[P->akf] << ", " << tf[P->bkf] << ">";
             else
-                l << "gemm_f32_dl_kernel<" << tf[P->akf] << ", " << tf[P->bkf] << ">";
+                l << "gemm_f32_dl_kernel<" << tf[P->akf] << ", " << tf[P->bkf] << (P->cfg == kCfgSquare ? ", 2, 2>" : ", 1, 2>");
             P->label = l.str() + P->label.substr(old_name.size());
         }
     }

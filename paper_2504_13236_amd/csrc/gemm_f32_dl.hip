@@ -1,7 +1,8 @@
-// fp32 product kernel (v_mfma_f32_32x32x2_f32) for whole 128 x 128 macro-tiles of
-// 16-byte aligned operands whose chunks are multiples of 32 long: the operands go
-// from global memory straight into LDS (global_load_lds_dwordx4), five stages of
-// one k-step of 16 each, and the loads of two k-steps are started together.
+// fp32 product kernel (v_mfma_f32_32x32x2_f32) for whole 128 x 128 macro-tiles (64 x
+// 128 for products whose row count is a head size) of 16-byte aligned operands whose
+// chunks are multiples of 32 long: the operands go from global memory straight into
+// LDS (global_load_lds_dwordx4), five stages of one k-step of 16 each, and the loads
+// of two k-steps are started together.
 //
 // Why: with register-staged loads a k-step's data is asked for one step ahead, in
 // 64-byte pieces for an operand whose contracted index is contiguous (16 floats of a
@@ -17,8 +18,8 @@
 //   * k-contiguous operand: rows of 16 k = 64 bytes; the 16-byte chunk c of row r
 //     sits at slot c ^ ((r >> 2) & 3).  A lane's fragment of a substep (4
 //     consecutive k of one row) is one 128-bit read.
-//   * row-contiguous operand: one line of 128 rows = 512 bytes per k; the 16-byte
-//     chunk c (4 rows) of line k sits at slot c ^ (((k >> 2) & 1) << 3), which keeps
+//   * row-contiguous operand: one line of all its rows (512 or 256 bytes) per k; the
+//     16-byte chunk c (4 rows) of line k sits at slot c ^ (((k >> 2) & 1) << 3), which keeps
 //     the two half-waves of a 32-bit fragment read (lines 4 apart) on different
 //     banks.  A fragment of a substep is four 32-bit reads.
 // A k-step is two substeps of 8 k: in substep s lane (row, h) holds k = 8 s + 4 h + i,
@@ -36,25 +37,23 @@ namespace {
 
 constexpr int kBK = 16;                                  // k-step
 constexpr int kStages = 5;
-constexpr int kOpBytes = 128 * kBK * 4;                  // one operand of one step: 8 KB
-constexpr int kStageBytes = 2 * kOpBytes;
-constexpr int kNI = 2;                                   // load instructions per wave, operand and step
-constexpr int kLoads = 2 * kNI;
 
-// Byte offset, from (first row, first k) of an operand's 128 x 16 block, of what this lane fetches
-// in load instruction j (0, 1) of its wave; the data lands in LDS at (2 wave + j) * 1024 + 16 lane
-// of the operand's region.
-template <bool KF>
+// Byte offset, from (first row, first k) of an operand's ROWS x 16 block, of what this lane fetches
+// in load instruction j (0 .. ROWS / 64 - 1) of its wave; the data lands in LDS at
+// (wave * ROWS / 64 + j) * 1024 + 16 lane of the operand's region.
+template <bool KF, int ROWS>
 __device__ __forceinline__ uint32_t load_offset(int ld, int wave, int lane, int j) {
+    constexpr int NI = ROWS / 64;
     if (KF) {
         // an instruction covers 16 rows; lane -> row lane / 4, slot lane % 4
         const int r = lane >> 2;
         const int c = (lane & 3) ^ ((r >> 2) & 3);
-        return (uint32_t)(((16 * (kNI * wave + j) + r) * ld + c * 4) * 4);
+        return (uint32_t)(((16 * (NI * wave + j) + r) * ld + c * 4) * 4);
     }
-    // an instruction covers two k-lines; lane -> line lane / 32, slot lane % 32
-    const int kk = 4 * wave + 2 * j + (lane >> 5);
-    const int c = (lane & 31) ^ (((kk >> 2) & 1) << 3);
+    // an instruction covers 256 / ROWS k-lines; lane -> line lane / LPL, slot lane % LPL
+    constexpr int LPL = ROWS / 4, LPI = 64 / LPL;            // lanes per line, lines per instruction
+    const int kk = LPI * (NI * wave + j) + lane / LPL;
+    const int c = (lane % LPL) ^ (((kk >> 2) & 1) << 3);
     return (uint32_t)((kk * ld + c * 4) * 4);
 }
 
@@ -73,48 +72,53 @@ template <> struct FragSel<true> { typedef Frag type; };
 __device__ __forceinline__ float frag_at(const Frag& f, int i) { return f.v[i]; }
 __device__ __forceinline__ float frag_at(const FragR& f, int i) { return f.v[i]; }
 
-// Lane- and wave-dependent parts of the fragment addresses of one operand, relative to the stage.
-// k-contiguous: one value per substep (the substep flips bit 5), the block is an immediate.
-// Row-contiguous: one value per block (the block enters next to an xor), the substep is an immediate.
-template <bool KF>
+// Lane- and wave-dependent parts of the fragment addresses of one operand of ROWS rows, relative to
+// the stage.  k-contiguous: one value per substep (the substep flips bit 5), the block is an
+// immediate.  Row-contiguous: one value per block (the block enters next to an xor), the substep is
+// an immediate.
+template <bool KF, int ROWS, int NB>
 struct FragAddr {
-    uint32_t v[2];
+    uint32_t v[KF ? 2 : NB];
     __device__ __forceinline__ void init(int lane, int first_blk) {
         const int r32 = lane & 31, h = lane >> 5;
-        if (KF) {
+        if constexpr (KF) {
             const uint32_t lo = (uint32_t)(r32 * 64 + ((h ^ ((r32 >> 2) & 3)) << 4));
             v[0] = lo + first_blk * 2048;
             v[1] = (lo ^ 32u) + first_blk * 2048;
         } else {
 #pragma unroll
-            for (int b = 0; b < 2; b++) {
+            for (int b = 0; b < NB; b++) {
                 // 32-row block first_blk + b starts at byte 128 (first_blk + b) of a line; lines with
-                // bit 2 of k set (h = 1) have 128-byte halves of each 256 bytes swapped
+                // bit 2 of k set (h = 1) have the 128-byte halves of each 256 bytes swapped
                 const uint32_t blk = (uint32_t)(first_blk + b);
-                v[b] = (uint32_t)(4 * h * 512) + ((blk * 128u + (uint32_t)r32 * 4u) ^ ((uint32_t)h * 128u));
+                v[b] = (uint32_t)(4 * h * ROWS * 4) + ((blk * 128u + (uint32_t)r32 * 4u) ^ ((uint32_t)h * 128u));
             }
         }
     }
 };
 
 // Starts the read of fragment B (the wave's B-th 32-row block) of an operand for substep KS.
-template <bool KF, int REGION, int B, int KS>
-__device__ __forceinline__ void read_frag(typename FragSel<KF>::type& f, const FragAddr<KF>& fa, uint32_t stage_addr) {
+template <bool KF, int ROWS, int NB, int REGION, int B, int KS>
+__device__ __forceinline__ void read_frag(typename FragSel<KF>::type& f, const FragAddr<KF, ROWS, NB>& fa, uint32_t stage_addr) {
     if constexpr (KF) {
         asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(f.v) : "v"(stage_addr + fa.v[KS]), "n"(REGION + B * 2048));
     } else {
+        constexpr int LB = ROWS * 4;                            // bytes of a k-line
         const uint32_t addr = stage_addr + fa.v[B];
-        asm volatile("ds_read_b32 %0, %1 offset:%2" : "=v"(f.v[0]) : "v"(addr), "n"(REGION + (8 * KS + 0) * 512));
-        asm volatile("ds_read_b32 %0, %1 offset:%2" : "=v"(f.v[1]) : "v"(addr), "n"(REGION + (8 * KS + 1) * 512));
-        asm volatile("ds_read_b32 %0, %1 offset:%2" : "=v"(f.v[2]) : "v"(addr), "n"(REGION + (8 * KS + 2) * 512));
-        asm volatile("ds_read_b32 %0, %1 offset:%2" : "=v"(f.v[3]) : "v"(addr), "n"(REGION + (8 * KS + 3) * 512));
+        asm volatile("ds_read_b32 %0, %1 offset:%2" : "=v"(f.v[0]) : "v"(addr), "n"(REGION + (8 * KS + 0) * LB));
+        asm volatile("ds_read_b32 %0, %1 offset:%2" : "=v"(f.v[1]) : "v"(addr), "n"(REGION + (8 * KS + 1) * LB));
+        asm volatile("ds_read_b32 %0, %1 offset:%2" : "=v"(f.v[2]) : "v"(addr), "n"(REGION + (8 * KS + 2) * LB));
+        asm volatile("ds_read_b32 %0, %1 offset:%2" : "=v"(f.v[3]) : "v"(addr), "n"(REGION + (8 * KS + 3) * LB));
     }
 }
 
-template <bool AKF, bool BKF>
+// Macro-tile (64 WMB) x (64 WNB): four waves as 2 x 2, each (32 WMB) x (32 WNB).
+template <bool AKF, bool BKF, int WMB, int WNB>
 __global__ void __launch_bounds__(256, 2) gemm_f32_dl_kernel(const GemmArgs g) {
-    constexpr int WMB = 2, WNB = 2, BM = 128, BN = 128;
-    constexpr int kFrags = WNB + WMB, kMfma = 4 * WNB * WMB;     // per substep
+    constexpr int BM = 64 * WMB, BN = 64 * WNB;
+    constexpr int kOpABytes = BM * kBK * 4, kOpBBytes = BN * kBK * 4, kStageBytes = kOpABytes + kOpBBytes;
+    constexpr int NIA = BM / 64, NIB = BN / 64, kLoads = NIA + NIB;     // load instructions per wave and step
+    constexpr int kFrags = WNB + WMB, kMfma = 4 * WNB * WMB;            // per substep
     __shared__ __attribute__((aligned(16))) char lds[kStages * kStageBytes];
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -171,7 +175,7 @@ __global__ void __launch_bounds__(256, 2) gemm_f32_dl_kernel(const GemmArgs g) {
         const char* baseA = nullptr;
         const char* baseB = nullptr;
         int64_t advA = 0, advB = 0;
-        uint32_t voffA[kNI], voffB[kNI];
+        uint32_t voffA[NIA], voffB[NIB];
         auto set_chunk = [&](const ChunkS& ch) {
             chk = ch.k;
             const int lda = (int)ch.lda, ldb = (int)ch.ldb;
@@ -182,10 +186,9 @@ __global__ void __launch_bounds__(256, 2) gemm_f32_dl_kernel(const GemmArgs g) {
             advA = AKF ? kBK * 4 : (int64_t)kBK * lda * 4;
             advB = BKF ? kBK * 4 : (int64_t)kBK * ldb * 4;
 #pragma unroll
-            for (int j = 0; j < kNI; j++) {
-                voffA[j] = load_offset<AKF>(lda, wave, lane, j);
-                voffB[j] = load_offset<BKF>(ldb, wave, lane, j);
-            }
+            for (int j = 0; j < NIA; j++) voffA[j] = load_offset<AKF, BM>(lda, wave, lane, j);
+#pragma unroll
+            for (int j = 0; j < NIB; j++) voffB[j] = load_offset<BKF, BN>(ldb, wave, lane, j);
         };
         if (table) {
             set_chunk(sload_chunk(g.chunks + chunk_i));
@@ -202,13 +205,13 @@ __global__ void __launch_bounds__(256, 2) gemm_f32_dl_kernel(const GemmArgs g) {
         auto load_pair_item = [&](int stage_x, int stage_y, int i) {
             const int j = i >> 1, second = i & 1;
             char* sa = lds + (second ? stage_y : stage_x) * kStageBytes;
-            if (j < kNI) {
+            if (j < NIA) {
                 __builtin_amdgcn_global_load_lds((glb_void_ptr)(baseA + (second ? advA : 0) + voffA[j]),
-                                                 (lds_void_ptr)(sa + (wave * kNI + j) * 1024), 16, 0, 0);
+                                                 (lds_void_ptr)(sa + (wave * NIA + j) * 1024), 16, 0, 0);
             } else {
-                const int jb = j - kNI;
+                const int jb = j - NIA;
                 __builtin_amdgcn_global_load_lds((glb_void_ptr)(baseB + (second ? advB : 0) + voffB[jb]),
-                                                 (lds_void_ptr)(sa + kOpBytes + (wave * kNI + jb) * 1024), 16, 0, 0);
+                                                 (lds_void_ptr)(sa + kOpABytes + (wave * NIB + jb) * 1024), 16, 0, 0);
             }
         };
         // moves the position on by two k-steps (chunks are multiples of 32 long)
@@ -235,8 +238,8 @@ __global__ void __launch_bounds__(256, 2) gemm_f32_dl_kernel(const GemmArgs g) {
         for (int i = 0; i < 2 * kLoads; i++) load_pair_item(2, 3, i);
         advance2();
 
-        FragAddr<AKF> fa;
-        FragAddr<BKF> fb;
+        FragAddr<AKF, BM, WMB> fa;
+        FragAddr<BKF, BN, WNB> fb;
         fa.init(lane, wm * WMB);
         fb.init(lane, wn * WNB);
         typename FragSel<BKF>::type pf[2][WNB];
@@ -245,8 +248,8 @@ __global__ void __launch_bounds__(256, 2) gemm_f32_dl_kernel(const GemmArgs g) {
         // fragment I (first the column blocks of B, then the row blocks of A) of substep KS of a stage
         auto frag_one = [&](auto I, auto KS, int buf, uint32_t stage_addr) {
             constexpr int i = decltype(I)::value, ks = decltype(KS)::value;
-            if constexpr (i < WNB) read_frag<BKF, kOpBytes, i, ks>(pf[buf][i], fb, stage_addr);
-            else read_frag<AKF, 0, i - WNB, ks>(qf[buf][i - WNB], fa, stage_addr);
+            if constexpr (i < WNB) read_frag<BKF, BN, WNB, kOpABytes, i, ks>(pf[buf][i], fb, stage_addr);
+            else read_frag<AKF, BM, WMB, 0, i - WNB, ks>(qf[buf][i - WNB], fa, stage_addr);
         };
         // all fragment reads issued so far have landed; the matrix instructions on set `buf` stay behind this
         auto wait_frags = [&](int buf) {
@@ -259,10 +262,10 @@ __global__ void __launch_bounds__(256, 2) gemm_f32_dl_kernel(const GemmArgs g) {
         // matrix instruction q of a substep: k pair q / 4 of block pair q % 4.  The "A" operand of
         // the matrix core carries the columns of C and "B" the rows, so that a lane owns one row of C.
         auto mfma_one = [&](int buf, int q) {
-            const int i = q >> 2, bn = (q >> 1) & 1, bm = q & 1;
+            const int i = q / (WNB * WMB), bn = (q / WMB) % WNB, bm = q % WMB;
             acc[bn][bm] = __builtin_amdgcn_mfma_f32_32x32x2f32(frag_at(pf[buf][bn], i), frag_at(qf[buf][bm], i), acc[bn][bm], 0, 0, 0);
         };
-        // One substep: 16 matrix instructions on fragment set `buf`; under them the fragments of
+        // One substep: the matrix instructions on fragment set `buf`; under them the fragments of
         // substep F_KS of the stage at `f_addr` are fetched into the other set and NL load
         // instructions are started through `load(i)`, dealt out evenly and fenced in place.
         auto substep = [&](auto NL, auto F_KS, int buf, uint32_t f_addr, auto&& load) {
@@ -340,22 +343,27 @@ __global__ void __launch_bounds__(256, 2) gemm_f32_dl_kernel(const GemmArgs g) {
 
 using KernelFn = void (*)(const GemmArgs);
 
+template <int WMB, int WNB>
 KernelFn kernel_of(int akf, int bkf) {
-    if (akf) return bkf ? gemm_f32_dl_kernel<true, true> : gemm_f32_dl_kernel<true, false>;
-    return bkf ? gemm_f32_dl_kernel<false, true> : gemm_f32_dl_kernel<false, false>;
+    if (akf) return bkf ? gemm_f32_dl_kernel<true, true, WMB, WNB> : gemm_f32_dl_kernel<true, false, WMB, WNB>;
+    return bkf ? gemm_f32_dl_kernel<false, true, WMB, WNB> : gemm_f32_dl_kernel<false, false, WMB, WNB>;
+}
+
+KernelFn kernel_of(int akf, int bkf, int cfg) {
+    return cfg == kCfgSkinny64n128 ? kernel_of<1, 2>(akf, bkf) : kernel_of<2, 2>(akf, bkf);
 }
 
 }  // namespace
 
-int32_t launch_gemm_f32_dl(hipStream_t st, int akf, int bkf, const GemmArgs& g, int64_t nwg) {
+int32_t launch_gemm_f32_dl(hipStream_t st, int akf, int bkf, int cfg, const GemmArgs& g, int64_t nwg) {
     if (nwg <= 0) return NNT_OK;
-    hipLaunchKernelGGL(kernel_of(akf, bkf), dim3((unsigned)nwg), dim3(256), 0, st, g);
+    hipLaunchKernelGGL(kernel_of(akf, bkf, cfg), dim3((unsigned)nwg), dim3(256), 0, st, g);
     return hipGetLastError() == hipSuccess ? NNT_OK : NNT_EHIP;
 }
 
-int gemm_f32_dl_occupancy(int akf, int bkf) {
+int gemm_f32_dl_occupancy(int akf, int bkf, int cfg) {
     int n = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel_of(akf, bkf), 256, 0) != hipSuccess || n < 1) n = 1;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel_of(akf, bkf, cfg), 256, 0) != hipSuccess || n < 1) n = 1;
     return n;
 }
 

@@ -116,9 +116,9 @@ def test_gemm_bf16_whole_macro_tiles_aligned(capi, opA, opB, m, n, k, dout):
 
 
 @pytest.mark.parametrize("opA,opB", list(itertools.product("NT", "NT")))
-@pytest.mark.parametrize("m,n,k", [(128, 128, 32), (256, 384, 96), (512, 256, 416)])
+@pytest.mark.parametrize("m,n,k", [(128, 128, 32), (256, 384, 96), (512, 256, 416), (64, 128, 32), (64, 384, 224)])
 def test_gemm_f32_whole_macro_tiles_aligned(capi, opA, opB, m, n, k):
-    """fp32 shapes made of whole 128 x 128 macro-tiles with k a multiple of 32 and 16-byte aligned operands:
+    """fp32 shapes made of whole 128 x 128 (64 x 128 for 64 rows) macro-tiles with k a multiple of 32 and 16-byte aligned operands:
     the fp32 kernel that loads straight into LDS (short and long k, padded leading dimensions, batch, beta)."""
     for batch, alpha, beta, pad in ((1, 1.0, 0.0, 0), (2, 0.7, -1.3, 4)):
         got, ref = run_gemm(capi, "f32", "f32", opA, opB, m, n, k, batch, alpha, beta, pad, seed=m + n + k)
