@@ -198,7 +198,7 @@ static ShapeChoice choose_shape(bool bf16, bool out_f32, int akf, int bkf, const
         const Cand& cd = cands[ci];
         int bm, bn;
         gemm_cfg_tile(bf16, cd.cfg, &bm, &bn);
-        const int occ = !bf16 ? (cd.cfg == kCfgSquare ? gemm_f32_dl_occupancy(akf, bkf, cd.cfg) : gemm_f32_occupancy(akf, bkf, cd.cfg))
+        const int occ = !bf16 ? gemm_f32_dl_occupancy(akf, bkf, cd.cfg)
                         : (cd.cfg == kCfgMid ? gemm_bf16_occupancy(out_f32, akf, bkf, cd.cfg) : gemm_bf16_dl_occupancy(out_f32, akf, bkf, cd.cfg));
         const int64_t G = 256 * (int64_t)occ;      // workgroups resident at a time
         int64_t W = 0;
@@ -289,7 +289,7 @@ extern "C" int32_t nnt_tile_gemm(void* stream, int32_t dtype_in, int32_t dtype_o
     g.grid_n = (int32_t)((n + bn - 1) / bn);
     const int64_t nwg = (int64_t)g.grid_m * g.grid_n * batch;
     if (nwg > INT32_MAX) return NNT_EINVAL;
-    const bool fast = (bf ? (cfg == kCfgSquare || cfg == kCfgTall) : (cfg == kCfgSquare || cfg == kCfgSkinny64n128)) && m % bm == 0 && n % bn == 0 && k > 0 &&
+    const bool fast = (bf ? (cfg == kCfgSquare || cfg == kCfgTall) : (cfg == kCfgSquare || cfg == kCfgSkinny64n128 || cfg == kCfgMid)) && m % bm == 0 && n % bn == 0 && k > 0 &&
                       k % ((bf && cfg == kCfgSquare) ? 64 : 32) == 0 && g.one_chunk.vec_ok == 3;
     return launch_any((hipStream_t)stream, dtype_in, dtype_out, opA == NNT_OP_T, opB == NNT_OP_N, cfg, g, nwg, fast ? nwg : 0);
 }
@@ -544,7 +544,7 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
 
     // workgroups that qualify for the direct-load kernel go first in every launch range
     P->task_nfast.assign(P->task_ctile.size(), 0);
-    if (bf ? (P->cfg == kCfgSquare || P->cfg == kCfgTall) : (P->cfg == kCfgSquare || P->cfg == kCfgSkinny64n128)) {
+    if (bf ? (P->cfg == kCfgSquare || P->cfg == kCfgTall) : (P->cfg == kCfgSquare || P->cfg == kCfgSkinny64n128 || P->cfg == kCfgMid)) {
         const int kmul = (bf && P->cfg == kCfgSquare) ? 64 : 32;   // loads are started two k-steps at a time
         std::vector<char> task_ok(P->tasks.size(), 1);
         for (size_t ti = 0; ti < P->tasks.size(); ti++)

@@ -73,7 +73,7 @@ int32_t launch_gemm_bf16(hipStream_t st, int out_is_f32, int akf, int bkf, int c
 // chunk lengths that are multiples of 64 (kCfgSquare) or 32 (kCfgTall); loads go straight to LDS
 int32_t launch_gemm_bf16_dl(hipStream_t st, int out_is_f32, int akf, int bkf, int cfg, const GemmArgs& g, int64_t nwg);
 int gemm_bf16_dl_occupancy(int out_is_f32, int akf, int bkf, int cfg);
-// fp32: 128 x 128 (kCfgSquare) or 64 x 128 (kCfgSkinny64n128) macro-tiles that lie wholly inside their
+// fp32: 128 x 128 (kCfgSquare) or 64 x 128 (kCfgMid, kCfgSkinny64n128) macro-tiles that lie wholly inside their
 // C tile, 16-byte aligned operands, chunk lengths that are multiples of 32
 int32_t launch_gemm_f32_dl(hipStream_t st, int akf, int bkf, int cfg, const GemmArgs& g, int64_t nwg);
 int gemm_f32_dl_occupancy(int akf, int bkf, int cfg);

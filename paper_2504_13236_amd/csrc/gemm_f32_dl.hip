@@ -350,7 +350,7 @@ KernelFn kernel_of(int akf, int bkf) {
 }
 
 KernelFn kernel_of(int akf, int bkf, int cfg) {
-    return cfg == kCfgSkinny64n128 ? kernel_of<1, 2>(akf, bkf) : kernel_of<2, 2>(akf, bkf);
+    return (cfg == kCfgSkinny64n128 || cfg == kCfgMid) ? kernel_of<1, 2>(akf, bkf) : kernel_of<2, 2>(akf, bkf);
 }
 
 }  // namespace
