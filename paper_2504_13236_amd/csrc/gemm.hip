@@ -466,6 +466,15 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
     if (P->wgs.size() > (size_t)INT32_MAX) return fail(ctx, NNT_EINVAL, "nnt_gemm: too many workgroups");
     // whole-operation launches use the XCD-aware order; per-task launches keep the order by task
     P->wgs_op = P->wgs;
+    {
+        // tasks of unequal length (causal attention: one to N_s / tile chunks): longest first, so that
+        // the short ones fill the end of the launch instead of the long ones making its tail
+        int64_t kmx = 0, kmn = INT64_MAX;
+        for (int64_t kq : ktot) { kmx = std::max(kmx, kq); kmn = std::min(kmn, kq); }
+        if (kmx > kmn)
+            std::stable_sort(P->wgs_op.begin(), P->wgs_op.end(),
+                             [&](const GemmWg& a, const GemmWg& b) { return ktot[a.task] > ktot[b.task]; });
+    }
     xcd_interleave(P->wgs_op, bm, bn);
 
     // ---- k-slices for the last n_split macro-tiles of the whole-operation order

@@ -338,13 +338,8 @@ __device__ __forceinline__ void dl_body(const GemmArgs& g, char* lds) {
                 static_for<kItems>([&](auto I) {
                     constexpr int i = decltype(I)::value;
                     if constexpr (i * kMfma / kItems == q) {
-#ifndef NNT_EXP
                         if constexpr (i < kFrags) frag_one(I, F_KS, buf ^ 1, f_addr);
                         else load(i - kFrags);
-#else
-                        if constexpr (i < kFrags) { if (NNT_EXP != 2 && NNT_EXP != 3) frag_one(I, F_KS, buf ^ 1, f_addr); }
-                        else { if (NNT_EXP != 1 && NNT_EXP != 3) load(i - kFrags); }
-#endif
                     }
                 });
                 __builtin_amdgcn_sched_barrier(0);
