@@ -236,7 +236,7 @@ static int pick_cfg(int bf16, int64_t m_max, int64_t n_max, int64_t n_tiles_big,
     if (bf16 && (m_max <= 128 || n_max <= 128 || n_tiles_big < 256)) return kCfgMid;
     // short contractions are bound by the result stores: several small workgroups per compute
     // unit overlap one's stores with another's loads, one large workgroup cannot
-    if (bf16 && k_max <= 128) return kCfgMid;
+    if (bf16 && k_max <= 128) return (m_max % 256 == 0 && n_max % 128 == 0) ? kCfgTall : kCfgMid;
     return kCfgSquare;
 }
 
