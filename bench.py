@@ -45,6 +45,99 @@ def cpu_baseline(cfg, sample_batch):
             "seconds": dt}
 
 
+def tile_kernels(cfg, capi, torch):
+    """Single-kernel figures through the nnt_tile_* entry points at the shapes of `cfg`."""
+    dt = capi.NNT_F32 if cfg.dtype == "f32" else capi.NNT_BF16
+    tdt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
+    w = 4 if cfg.dtype == "f32" else 2
+    st = torch.cuda.current_stream().cuda_stream
+    T = cfg.N_s * cfg.N_b
+
+    def timed(call, nsets, iters=24, warm=3):
+        for i in range(warm):
+            call(i % nsets)
+        torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(iters + 1)]
+        ev[0].record()
+        for i in range(iters):
+            call(i % nsets)
+            ev[i + 1].record()
+        torch.cuda.synchronize()
+        ts = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(iters))
+        return ts[len(ts) // 2], ts[0]
+
+    out = {"products": [], "memory_bound": []}
+    # products: the whole operations of the block (what one launch covers) and the paper's tile task
+    t = cfg.tile
+    shapes = [("qkv / fc1-like  W X", "N", "N", 3 * cfg.N_e, T, cfg.N_e), ("fc1  W X", "N", "N", cfg.N_m, T, cfg.N_e),
+              ("fc2  W X", "N", "N", cfg.N_e, T, cfg.N_m), ("dX = W^T dY", "T", "N", cfg.N_e, T, cfg.N_m),
+              ("dW = dY X^T", "N", "T", cfg.N_m, cfg.N_e, T), ("one tile task (paper's granularity)", "N", "N", min(t, cfg.N_e), min(t, cfg.N_s) * cfg.N_b, min(t, cfg.N_e))]
+    for name, opA, opB, m, n, k in shapes:
+        A = torch.randn(m * k, device="cuda").to(tdt)
+        B = torch.randn(k * n, device="cuda").to(tdt)
+        Cm = torch.zeros(m * n, device="cuda").to(tdt)
+        lda = m if opA == "N" else k
+        ldb = k if opB == "N" else n
+        med, mn = timed(lambda i: capi.nnt_tile_gemm(st, dt, dt, 0 if opA == "N" else 1, 0 if opB == "N" else 1, m, n, k, 1, 1.0,
+                                                     A.data_ptr(), lda, m * k, B.data_ptr(), ldb, k * n, 0.0, Cm.data_ptr(), m, m * n), 1)
+        tf = 2.0 * m * n * k / med / 1e9
+        out["products"].append({"name": name, "op": opA + opB, "m": m, "n": n, "k": k, "median_us": med * 1e3, "min_us": mn * 1e3,
+                                "TFLOP/s": tf, "frac_mfma_peak": tf / PEAK_TFLOPS[cfg.dtype]})
+    # attention products, batched over (batch, head), one sequence-tile pair
+    ts_ = min(t, cfg.N_s)
+    h, nb = cfg.N_e // cfg.N_h, cfg.N_b * cfg.N_h
+    for name, opA, opB, m, n, k in (("scores K^T Q", "T", "N", ts_, ts_, h), ("V P", "N", "N", h, ts_, ts_), ("dV = dB P^T", "N", "T", h, ts_, ts_)):
+        A = torch.randn(m * k * nb, device="cuda").to(tdt)
+        B = torch.randn(k * n * nb, device="cuda").to(tdt)
+        Cm = torch.zeros(m * n * nb, device="cuda").to(tdt)
+        lda = m if opA == "N" else k
+        ldb = k if opB == "N" else n
+        med, mn = timed(lambda i: capi.nnt_tile_gemm(st, dt, dt, 0 if opA == "N" else 1, 0 if opB == "N" else 1, m, n, k, nb, 1.0,
+                                                     A.data_ptr(), lda, m * k, B.data_ptr(), ldb, k * n, 0.0, Cm.data_ptr(), m, m * n), 1)
+        tf = 2.0 * m * n * k * nb / med / 1e9
+        gb = w * nb * (m * k + k * n + m * n) / med / 1e6
+        out["products"].append({"name": name, "op": opA + opB, "m": m, "n": n, "k": k, "batch": nb, "median_us": med * 1e3,
+                                "min_us": mn * 1e3, "TFLOP/s": tf, "frac_mfma_peak": tf / PEAK_TFLOPS[cfg.dtype], "GB/s": gb,
+                                "frac_hbm_peak": gb / PEAK_HBM_GBS})
+
+    # memory-bound kernels on one activation-sized tile set (N_m x T elements), warm and cold
+    n_el = cfg.N_m * T
+    nsets = max(3, -(-(640 << 20) // (3 * n_el * w)))
+
+    def bufs(count, dtype=tdt):
+        return [[torch.randn(n_el, device="cuda").to(dtype) for _ in range(count)] for _ in range(nsets)]
+
+    def report(name, bytes_per_el, call, sets):
+        rec = {"name": name, "elements": n_el, "bytes_per_element": bytes_per_el}
+        for label, ns in (("warm", 1), ("cold", sets)):
+            med, mn = timed(call, ns)
+            rec[label] = {"median_us": med * 1e3, "GB/s": bytes_per_el * n_el / med / 1e6, "frac_hbm_peak": bytes_per_el * n_el / med / 1e6 / PEAK_HBM_GBS}
+        out["memory_bound"].append(rec)
+
+    b = bufs(3)
+    report("gelu", 2 * w, lambda i: capi.nnt_tile_gelu(st, dt, 0, n_el, b[i][0].data_ptr(), b[i][1].data_ptr()), nsets)
+    report("gelu_bwd", 3 * w, lambda i: capi.nnt_tile_gelu_bwd(st, dt, 0, n_el, b[i][0].data_ptr(), b[i][1].data_ptr(), b[i][2].data_ptr()), nsets)
+    report("add (y = a x + b y)", 3 * w, lambda i: capi.nnt_tile_add(st, dt, n_el, 1.0, b[i][0].data_ptr(), 1.0, b[i][1].data_ptr()), nsets)
+    bias = torch.randn(cfg.N_m, device="cuda")
+    report("bias_add", 2 * w, lambda i: capi.nnt_tile_bias_add(st, dt, cfg.N_m, T, bias.data_ptr(), b[i][0].data_ptr()), nsets)
+    scratch = torch.empty(int(capi.nnt_tile_bias_grad_scratch(cfg.N_m, T)), device="cuda")
+    db = torch.empty(cfg.N_m, device="cuda")
+    report("bias_grad (column sums)", w, lambda i: capi.nnt_tile_bias_grad(st, dt, cfg.N_m, T, b[i][0].data_ptr(), db.data_ptr(), 0, scratch.data_ptr()), nsets)
+    if cfg.dtype == "bf16":
+        f32b = [torch.randn(n_el, device="cuda") for _ in range(nsets)]
+        report("cast fp32 -> bf16", 6, lambda i: capi.nnt_tile_cast(st, capi.NNT_F32, capi.NNT_BF16, n_el, f32b[i].data_ptr(), b[i][0].data_ptr()), nsets)
+        del f32b
+    del b
+    # Adam on an fp32 parameter set of the same size
+    pa = [[torch.randn(n_el, device="cuda").abs() * 0.01 for _ in range(4)] for _ in range(nsets)]
+    import workload
+    a = workload.ADAM
+    report("adam (fp32 p, g, m, v)", 28, lambda i: capi.nnt_tile_adam(st, n_el, 1, a["lr"], a["beta1"], a["beta2"], a["eps"], a["weight_decay"],
+                                                                    pa[i][0].data_ptr(), pa[i][1].data_ptr(), pa[i][2].data_ptr(), pa[i][3].data_ptr(), None), nsets)
+    del pa
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -59,6 +152,10 @@ def main():
                     help="instead of the benchmark, copy MIB MiB of fp32 a few times with the library's cast kernel "
                          "(a plain copy kernel of known size, for scaling HBM counters)")
     ap.add_argument("--cpu-sample-batch", type=int, default=0)
+    ap.add_argument("--tile-kernels", action="store_true",
+                    help="instead of the block benchmark, time single calls of the tile kernels at the config's shapes: "
+                         "products against the MFMA peak, memory-bound kernels against HBM, warm (one buffer set) and "
+                         "cold (rotating over > 512 MB of buffer sets, more than the 256 MB Infinity Cache)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (--gpus %d refused)" % args.gpus, file=sys.stderr)
@@ -89,6 +186,9 @@ def main():
         print(json.dumps({"copy_calibration": {"bytes_read": 4 * n, "bytes_written": 4 * n, "launches": 8, "ms": ms,
                                                "GB/s": 8.0 * n / ms / 1e6,
                                                "kernel": "ew_kernel<CastF<float, float>>"}}))
+        return
+    if args.tile_kernels:
+        print(json.dumps({"tile_kernels": tile_kernels(workload.CONFIGS[args.config], capi, torch)}))
         return
     cfg = workload.CONFIGS[args.config]
     inp = workload.generate(cfg)
@@ -182,6 +282,20 @@ def main():
         tot_fl = sum(v["TFLOP/s"] * v["ms_per_step"] for v in wg)
         roofline["all_products_TFLOP/s"] = tot_fl / tot_ms if tot_ms else None
 
+    # the metric's other two figures, as time-weighted aggregates of the serial per-kernel pass
+    def aggregate(items, key, peak):
+        ms = sum(v["ms_per_step"] for v in items)
+        work = sum(v[key] * v["ms_per_step"] for v in items)
+        return {"ms_per_step": ms, key: work / ms if ms else None, "frac_of_peak": work / ms / peak if ms else None}
+    summary = {
+        "tile_gemm_weights": aggregate([v for k, v in gemms.items() if "batched" not in k], "TFLOP/s", PEAK_TFLOPS[cfg.dtype]),
+        "tile_gemm_attention": aggregate([v for k, v in gemms.items() if "batched" in k], "TFLOP/s", PEAK_TFLOPS[cfg.dtype]),
+        "memory_bound_kernels": aggregate([v for k, v in kernels.items() if "GB/s" in v], "GB/s", PEAK_HBM_GBS),
+    }
+    # time the step would take if every kernel ran at its roofline, over the measured step
+    bound_ms = sum(v["ms_per_step"] * v.get("frac_mfma_peak", v.get("frac_hbm_peak", 0.0)) for v in kernels.values())
+    summary["time_weighted_roofline"] = bound_ms / ms_per_step if ms_per_step else None
+
     out = {"metric": "GPT-2 block fwd+bwd TFLOP/s on 1 MI355X", "value": value, "unit": "TFLOP/s", "n_gpus": 1,
            "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
            "scaling": "weak", "vs_baseline": None, "dtype": "f32" if cfg.dtype == "f32" else "bf16", "data": "synthetic",
@@ -190,7 +304,7 @@ def main():
                                      "+Adam" if cfg.adam else ""),
                       "streams": args.streams, "granularity": args.granularity, "graph_replay": bool(args.graph),
                       "flops_per_step": flops, "attention_flops": "computed sequence-tile pairs only"},
-           "roofline": roofline, "kernels": kernels, "executor": ctx.stats()}
+           "roofline": roofline, "summary": summary, "kernels": kernels, "executor": ctx.stats()}
     if not args.no_cpu_baseline:
         # the whole workload takes the oracle a few seconds up to C4; C5 is sampled on one batch member
         sb = args.cpu_sample_batch or (cfg.N_b if args.config <= 4 else 1)
