@@ -53,6 +53,28 @@ static int32_t sync_all(nnt_ctx* ctx) {
     return NNT_OK;
 }
 
+void profile_mark(nnt_ctx* ctx, hipStream_t st, const char* label, double work, bool bytes) {
+    nnt_ctx::ProfileRec* p = ctx->cur_prof;
+    if (!p) return;
+    hipEvent_t ev[2];
+    for (hipEvent_t& e : ev) {
+        if (!ctx->timing_pool.empty()) { e = ctx->timing_pool.back(); ctx->timing_pool.pop_back(); }
+        else if (hipEventCreate(&e) != hipSuccess) return;
+    }
+    nnt_ctx::ProfileRec done = *p;
+    done.launches = p->launches > 1 ? p->launches - 1 : 1;
+    (void)hipEventRecord(ev[0], st);
+    (void)hipEventRecord(ev[1], st);
+    // the events of the running record: its start goes with the closed part, its stop stays for the rest
+    done.stop = ev[0];
+    ctx->profile.push_back(done);
+    p->start = ev[1];
+    p->label = label;
+    p->work = work;
+    p->bytes = bytes;
+    p->launches = 1;
+}
+
 int32_t submit(nnt_ctx* ctx, const std::vector<Access>& acc,
                const std::function<int32_t(hipStream_t)>& launch, int n_launches) {
     NNT_CHECK_CTX(ctx);
@@ -110,7 +132,9 @@ int32_t submit(nnt_ctx* ctx, const std::vector<Access>& acc,
         ctx->cur_work = 0.0;     // the operation's work is counted once, on its first task
         NNT_HIP(ctx, hipEventRecord(prof.start, st));
     }
+    ctx->cur_prof = timed ? &prof : nullptr;
     int32_t rc = launch(st);
+    ctx->cur_prof = nullptr;
     if (timed) {
         NNT_HIP(ctx, hipEventRecord(prof.stop, st));
         ctx->profile.push_back(prof);

@@ -75,6 +75,7 @@ struct GemmPlan {
     int splits = 1;
     int64_t n_split = 0, op_nwg = 0;
     int red_blocks = 0;
+    int64_t slice_elems = 0;                   // elements of one slice of one cut macro-tile
     SplitReduce* d_red = nullptr;
     float* d_ws = nullptr;
     TileDep ws_dep;
@@ -543,6 +544,7 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
         }
         for (int sidx = 0; sidx < S; sidx++) P->wgs_op.insert(P->wgs_op.end(), by_slice[sidx].begin(), by_slice[sidx].end());
         P->red_blocks = (int)((slice / 4 + 255) / 256);
+        P->slice_elems = slice;
         NNT_HIP(ctx, hipMalloc((void**)&P->d_red, red.size() * sizeof(SplitReduce)));
         NNT_HIP(ctx, hipMemcpy(P->d_red, red.data(), red.size() * sizeof(SplitReduce), hipMemcpyHostToDevice));
     } else {
@@ -631,9 +633,11 @@ extern "C" int32_t nnt_gemm(nnt_ctx* ctx, float alpha, int32_t opA, nnt_tensor* 
         if (nwg == 0) return NNT_OK;
         if (P->n_split > 0) {
             acc.push_back(Access{&P->ws_dep, 1, kReadWrite});
+            const double red_bytes = (double)P->n_split * P->slice_elems * 4.0 * (P->splits + 1);
             return submit(ctx, acc, [=](hipStream_t st) {
                 int32_t rc = launch_any(st, P->dtype_in, P->dtype_out, P->akf, P->bkf, P->cfg, g, nwg, P->op_nfast);
                 if (rc != NNT_OK) return rc;
+                profile_mark(ctx, st, "splitk_reduce", red_bytes, true);
                 const dim3 grid((unsigned)P->red_blocks, (unsigned)P->n_split), block(256);
                 if (P->dtype_out == NNT_F32) hipLaunchKernelGGL((splitk_reduce<float>), grid, block, 0, st, P->d_red, alpha, beta);
                 else hipLaunchKernelGGL((splitk_reduce<uint16_t>), grid, block, 0, st, P->d_red, alpha, beta);

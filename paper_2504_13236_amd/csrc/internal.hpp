@@ -131,6 +131,7 @@ struct nnt_ctx {
     struct ProfileRec { std::string label; hipEvent_t start, stop; double work; bool bytes; int launches; };
     std::vector<ProfileRec> profile;
     std::vector<hipEvent_t> timing_pool;
+    ProfileRec* cur_prof = nullptr;   // record of the task whose launches are being issued, if timed
 };
 
 namespace nnt {
@@ -149,6 +150,9 @@ struct OpTag {
 namespace nnt {
 
 int32_t fail(nnt_ctx* ctx, int32_t code, const std::string& msg);
+// Inside a task's launch function, between two of its kernels: when tasks are being timed, what was
+// launched so far is closed as one profile record and the rest of the task gets a record of its own.
+void profile_mark(nnt_ctx* ctx, hipStream_t st, const char* label, double work, bool bytes);
 #define NNT_CHECK_CTX(ctx)                                         \
     do {                                                           \
         if (!(ctx)) return NNT_EINVAL;                             \
