@@ -8,7 +8,9 @@ paper_2504_13236_amd/libnntile_mi.so.  Works without a GPU (cross-compilation).
 from __future__ import annotations
 
 import concurrent.futures
+import json
 import os
+import re
 import subprocess
 import sys
 
@@ -24,15 +26,72 @@ FLAGS = [
     # packed fp32 VALU forms are kept off on this hardware pool
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument",
+    # per-kernel register, scratch and LDS figures on stderr (parsed below)
+    "-Rpass-analysis=kernel-resource-usage",
 ]
+
+# Sources whose kernels keep LDS reads in flight across statements (the reads are issued by
+# inline assembly and waited for later by hand): a register the compiler spills or reloads
+# between a read and its wait would hold stale data, so inside their loops these kernels
+# must not touch scratch memory.  (Spills in the prologue or after the last wait are harmless.)
+IN_FLIGHT_SOURCES = ("gemm_bf16_dl.hip", "gemm_f32_dl.hip")
+
+
+def scratch_in_loops(asm_text: str) -> list:
+    """[(kernel, line number)] of scratch instructions inside loop blocks of a device assembly listing.
+
+    The listing marks each basic block that belongs to a loop in the comment on its label."""
+    hits = []
+    kernel, in_loop = None, False
+    for no, line in enumerate(asm_text.splitlines(), 1):
+        t = line.strip()
+        if t.startswith("_Z") and t.split(":")[0].isidentifier() and ":" in t:
+            kernel, in_loop = t.split(":")[0], False
+        elif t.startswith(".LBB") or t.startswith("; %bb."):
+            in_loop = "Loop" in t
+        elif in_loop and t.startswith("scratch_"):
+            hits.append((kernel, no))
+    return hits
+
+
+_NAME = re.compile(r"remark: Function Name: (\S+)")
+_FIELD = re.compile(r"remark:\s+(TotalSGPRs|VGPRs|AGPRs|ScratchSize \[bytes/lane\]|Occupancy \[waves/SIMD\]"
+                    r"|VGPRs Spill|LDS Size \[bytes/block\]): (\d+)")
+
+
+def resource_usage(stderr: str) -> dict:
+    """{mangled kernel name: {field: value}} from hipcc's kernel-resource-usage remarks."""
+    out: dict = {}
+    cur = None
+    for line in stderr.splitlines():
+        m = _NAME.search(line)
+        if m:
+            cur = out.setdefault(m.group(1), {})
+            continue
+        m = _FIELD.search(line)
+        if m and cur is not None:
+            cur[m.group(1).split(" [")[0]] = int(m.group(2))
+    return out
 
 
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ, os.path.basename(src) + ".o")
-    cmd = ["hipcc", *FLAGS, "-c", src, "-o", obj]
+    in_flight = os.path.basename(src) in IN_FLIGHT_SOURCES
+    cmd = ["hipcc", *FLAGS, *(["-save-temps=obj"] if in_flight else []), "-c", src, "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("hipcc failed for %s:\n%s" % (src, r.stderr[-4000:]))
+    usage = resource_usage(r.stderr)
+    if in_flight:
+        stem = os.path.splitext(os.path.basename(src))[0]
+        with open(os.path.join(OBJ, stem + "-hip-amdgcn-amd-amdhsa-gfx950.s")) as f:
+            hits = scratch_in_loops(f.read())
+        if hits:
+            raise RuntimeError("%s: scratch access inside a loop of %s (assembly line %d, %d in all): "
+                               "in-flight fragment registers do not survive a spill"
+                               % (os.path.basename(src), hits[0][0], hits[0][1], len(hits)))
+    with open(obj + ".usage.json", "w") as f:
+        json.dump(usage, f, indent=1, sort_keys=True)
     return obj
 
 

@@ -114,3 +114,32 @@ def test_block_slot_table_host_only(capi):
         capi.nnt_gpt2_block_slot(C.byref(c), s, C.byref(info))
         used += info.used
     assert used == capi.NNT_BLK_NSLOTS - 4
+
+
+def test_build_guard_finds_scratch_only_inside_loops():
+    """The build refuses direct-load kernels that touch scratch memory inside a loop: their
+    fragment registers are filled by LDS reads that are waited for later by hand."""
+    from paper_2504_13236_amd.build import resource_usage, scratch_in_loops
+    listing = "\n".join([
+        "_Z6kernelv:                             ; @_Z6kernelv",
+        "; %bb.0:",
+        "\tscratch_store_dword off, v1, off",                       # prologue: allowed
+        ".LBB0_1:                                ; =>This Inner Loop Header: Depth=1",
+        "\tv_mfma_f32_32x32x16_bf16 v[0:15], v[16:19], v[20:23], v[0:15]",
+        "\tscratch_store_dwordx4 off, v[4:7], off offset:16 ; 16-byte Folded Spill",
+        "; %bb.2:                                ;   in Loop: Header=BB0_1 Depth=1",
+        "\tscratch_load_dwordx4 v[4:7], off, off offset:16 ; 16-byte Folded Reload",
+        "\ts_cbranch_scc0 .LBB0_1",
+        ".LBB0_3:",
+        "\tscratch_store_dword off, v3, off offset:64 ; 4-byte Folded Spill",   # epilogue: allowed
+        "_Z5otherv:",
+        "\tscratch_store_dword off, v1, off",
+    ])
+    assert scratch_in_loops(listing) == [("_Z6kernelv", 6), ("_Z6kernelv", 8)]
+    remarks = "\n".join([
+        "a.hip:1:1: remark: Function Name: _Z6kernelv [-Rpass-analysis=kernel-resource-usage]",
+        "a.hip:1:1: remark:     VGPRs: 72 [-Rpass-analysis=kernel-resource-usage]",
+        "a.hip:1:1: remark:     ScratchSize [bytes/lane]: 8 [-Rpass-analysis=kernel-resource-usage]",
+        "a.hip:1:1: remark:     LDS Size [bytes/block]: 61440 [-Rpass-analysis=kernel-resource-usage]",
+    ])
+    assert resource_usage(remarks) == {"_Z6kernelv": {"VGPRs": 72, "ScratchSize": 8, "LDS Size": 61440}}
