@@ -313,6 +313,34 @@ NNT_API int32_t nnt_softmax_bwd(nnt_ctx* ctx, nnt_tensor* P, nnt_tensor* dP);
 NNT_API int32_t nnt_head_split(nnt_ctx* ctx, nnt_tensor* Z, int32_t n_parts, nnt_tensor* const* parts);
 NNT_API int32_t nnt_head_merge(nnt_ctx* ctx, int32_t n_parts, nnt_tensor* const* parts, nnt_tensor* Z);
 
+/* Fused tile attention (section 3, attention layer and SoftMax): what the three
+ * operations "scores, softmax over the keys, product with the values" compute,
+ * in one kernel that walks the key tiles of each query tile and carries the
+ * SoftMax subroutines' running column statistics (maximum, sum of shifted
+ * exponentials) along instead of storing the N_s x N_s scores:
+ *   B[i,q,b,j] = sum_k V[i,k,b,j] P[k,q,b,j],
+ *   P[.,q,b,j] = softmax over k of scale * sum_i K[i,k,b,j] Q[i,q,b,j],
+ * with causal != 0 over the keys k <= q only.  Q, K, V, B: [h, N_s, N_b, N_h]
+ * tensors of one dtype (fp32 or bf16), tiled alike, first axis untiled, h = 64 or
+ * 128, every tile present and 16-byte aligned; stats: fp32 [2, N_s, N_b, N_h]
+ * tiled like their other axes, overwritten with the final (maximum of the scaled
+ * scores, sum of exp(score - maximum)) of every column.  One task for the whole
+ * tensor, or one per query tile at tile granularity.  N_b * N_h <= 65535.
+ * Errors: NNT_EINVAL (shape, tiling, missing tile), NNT_EDTYPE. */
+NNT_API int32_t nnt_attention_fwd(nnt_ctx* ctx, nnt_tensor* Q, nnt_tensor* K, nnt_tensor* V, float scale,
+                          int32_t causal, nnt_tensor* B, nnt_tensor* stats);
+/* Its adjoint, recomputing the probabilities from Q, K and the statistics that
+ * the forward call left: with D[q] = sum_i dB[i,q] B[i,q] and
+ * dA[k,q] = P[k,q] (sum_i V[i,k] dB[i,q] - D[q]),
+ *   dV[i,k] = sum_q dB[i,q] P[k,q],  dQ[i,q] = scale sum_k K[i,k] dA[k,q],
+ *   dK[i,k] = scale sum_q Q[i,q] dA[k,q]        (per batch element and head).
+ * B, stats: the forward call's outputs; dQ, dK, dV (tiled like Q) are overwritten.
+ * One task of two kernels (dQ, then dK and dV); uses the context's reduction
+ * scratch (2 N_s N_b N_h floats), which must exist before a graph capture. */
+NNT_API int32_t nnt_attention_bwd(nnt_ctx* ctx, nnt_tensor* Q, nnt_tensor* K, nnt_tensor* V, nnt_tensor* B,
+                          nnt_tensor* stats, nnt_tensor* dB, float scale, int32_t causal,
+                          nnt_tensor* dQ, nnt_tensor* dK, nnt_tensor* dV);
+
 typedef struct nnt_adam_cfg {
     double lr, beta1, beta2, eps, weight_decay;   /* doubles: 1 - beta is formed before rounding to fp32 */
 } nnt_adam_cfg;

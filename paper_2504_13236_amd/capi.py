@@ -135,6 +135,8 @@ PROTOTYPES = {
     "nnt_softmax_bwd": (_i32, [_p, _p, _p]),
     "nnt_head_split": (_i32, [_p, _p, _i32, _pp]),
     "nnt_head_merge": (_i32, [_p, _i32, _pp, _p]),
+    "nnt_attention_fwd": (_i32, [_p, _p, _p, _p, _f, _i32, _p, _p]),
+    "nnt_attention_bwd": (_i32, [_p, _p, _p, _p, _p, _p, _p, _f, _i32, _p, _p, _p]),
     "nnt_adam_step": (_i32, [_p, C.POINTER(nnt_adam_cfg), _i32, _p, _p, _p, _p, _p]),
     "nnt_gpt2_block_slot": (_i32, [C.POINTER(nnt_gpt2_block_cfg), _i32, C.POINTER(nnt_slot_info)]),
     "nnt_gpt2_block_create": (_i32, [_p, C.POINTER(nnt_gpt2_block_cfg), _pp, _pp]),
