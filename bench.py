@@ -147,6 +147,9 @@ def main():
     ap.add_argument("--streams", type=int, default=4)
     ap.add_argument("--granularity", choices=["op", "tile"], default="op")
     ap.add_argument("--graph", action="store_true", help="replay the step from a captured HIP graph")
+    ap.add_argument("--attention", choices=["tiles", "fused"], default="tiles",
+                    help="tiles: scores, softmax and the product with V as three operations on the stored N_s x N_s "
+                         "tensor (the paper's flow, the default); fused: one kernel per direction that never stores it")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="instead of the benchmark, copy MIB MiB of fp32 a few times with the library's cast kernel "
@@ -195,7 +198,7 @@ def main():
     gran = capi.NNT_GRAN_OP if args.granularity == "op" else capi.NNT_GRAN_TILE
     ctx = tiled.Context(n_streams=args.streams, granularity=gran)
     blk = tiled.Gpt2Block(ctx, cfg.N_e, cfg.N_h, cfg.N_m, cfg.N_s, cfg.N_b, workload.base_tiles(cfg), dtype=cfg.dtype,
-                          eps=cfg.eps, gelu=cfg.gelu, adam=cfg.adam)
+                          eps=cfg.eps, gelu=cfg.gelu, adam=cfg.adam, fused_attention=args.attention == "fused")
     blk.set_params({k: inp[k] for k in workload.PARAM_NAMES})
     X, dOut = blk.activation(inp["X"]), blk.activation(inp["dOut"])
     Out, dX = blk.activation(), blk.activation()
@@ -242,7 +245,7 @@ def main():
     ctx.profile(False)
     ctx.set_serial(False)
     ms_per_step = dt / args.steps * 1e3
-    flops = workload.model_flops(cfg, tile_skip=True)
+    flops = workload.model_flops(cfg, tile_skip=True, visible_only=args.attention == "fused")
     value = flops / (dt / args.steps) / 1e12
 
     # per-operation figures from the executor's event pairs
@@ -288,8 +291,10 @@ def main():
         work = sum(v[key] * v["ms_per_step"] for v in items)
         return {"ms_per_step": ms, key: work / ms if ms else None, "frac_of_peak": work / ms / peak if ms else None}
     summary = {
-        "tile_gemm_weights": aggregate([v for k, v in gemms.items() if "batched" not in k], "TFLOP/s", PEAK_TFLOPS[cfg.dtype]),
-        "tile_gemm_attention": aggregate([v for k, v in gemms.items() if "batched" in k], "TFLOP/s", PEAK_TFLOPS[cfg.dtype]),
+        "tile_gemm_weights": aggregate([v for k, v in gemms.items() if "batched" not in k and not k.startswith("attention")],
+                                       "TFLOP/s", PEAK_TFLOPS[cfg.dtype]),
+        "tile_gemm_attention": aggregate([v for k, v in gemms.items() if "batched" in k or k.startswith("attention")],
+                                         "TFLOP/s", PEAK_TFLOPS[cfg.dtype]),
         "memory_bound_kernels": aggregate([v for k, v in kernels.items() if "GB/s" in v], "GB/s", PEAK_HBM_GBS),
     }
     # time the step would take if every kernel ran at its roofline, over the measured step
@@ -303,7 +308,10 @@ def main():
                                   % (cfg.name, cfg.dtype, cfg.N_e, cfg.N_h, cfg.N_m, cfg.N_s, cfg.N_b, cfg.tile,
                                      "+Adam" if cfg.adam else ""),
                       "streams": args.streams, "granularity": args.granularity, "graph_replay": bool(args.graph),
-                      "flops_per_step": flops, "attention_flops": "computed sequence-tile pairs only"},
+                      "attention": args.attention,
+                      "flops_per_step": flops,
+                      "attention_flops": "visible (key, query) pairs only, no recomputation" if args.attention == "fused"
+                                         else "computed sequence-tile pairs only"},
            "roofline": roofline, "summary": summary, "kernels": kernels, "executor": ctx.stats()}
     if not args.no_cpu_baseline:
         # the whole workload takes the oracle a few seconds up to C4; C5 is sampled on one batch member

@@ -325,7 +325,8 @@ NNT_API int32_t nnt_head_merge(nnt_ctx* ctx, int32_t n_parts, nnt_tensor* const*
  * 128, every tile present and 16-byte aligned; stats: fp32 [2, N_s, N_b, N_h]
  * tiled like their other axes, overwritten with the final (maximum of the scaled
  * scores, sum of exp(score - maximum)) of every column.  One task for the whole
- * tensor, or one per query tile at tile granularity.  N_b * N_h <= 65535.
+ * tensor, or one per query tile at tile granularity.  At most 65535 blocks of
+ * 128 queries (counted per sequence tile).
  * Errors: NNT_EINVAL (shape, tiling, missing tile), NNT_EDTYPE. */
 NNT_API int32_t nnt_attention_fwd(nnt_ctx* ctx, nnt_tensor* Q, nnt_tensor* K, nnt_tensor* V, float scale,
                           int32_t causal, nnt_tensor* B, nnt_tensor* stats);
@@ -361,6 +362,9 @@ typedef struct nnt_gpt2_block_cfg {
     int32_t gelu_variant;
     float   eps;                        /* layer-norm epsilon (inside the square root)          */
     int32_t causal;
+    int32_t fused_attention;            /* 0: scores, softmax and the product with V as three operations on a stored
+                                           N_s x N_s tensor (the paper's flow); 1: nnt_attention_fwd / _bwd, which
+                                           needs tile_i >= N_e / N_h; the slots P and DP are then unused */
 } nnt_gpt2_block_cfg;
 
 /* Tensors of a block.  The caller asks nnt_gpt2_block_slot() for the type, shape

@@ -58,7 +58,8 @@ class nnt_gpt2_block_cfg(C.Structure):
     _fields_ = [("N_e", C.c_int64), ("N_h", C.c_int64), ("N_m", C.c_int64), ("N_s", C.c_int64), ("N_b", C.c_int64),
                 ("tile_e", C.c_int64), ("tile_m", C.c_int64), ("tile_s", C.c_int64),
                 ("tile_b", C.c_int64), ("tile_j", C.c_int64), ("tile_i", C.c_int64),
-                ("dtype", C.c_int32), ("gelu_variant", C.c_int32), ("eps", C.c_float), ("causal", C.c_int32)]
+                ("dtype", C.c_int32), ("gelu_variant", C.c_int32), ("eps", C.c_float), ("causal", C.c_int32),
+                ("fused_attention", C.c_int32)]
 
 
 class nnt_slot_info(C.Structure):

@@ -155,8 +155,10 @@ __global__ void __launch_bounds__(256, 2) attn_fwd_f32(const FwdArgs a) {
     __shared__ float lds[2][Blk::kFloats + kBlk * LDV];
     const AttnGeom& g = a.g;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, hh = lane >> 5, ln = lane & 31;
-    const int l = g.tile0 + blockIdx.x / g.nblk, e0 = (blockIdx.x % g.nblk) * kWgRows;
-    const int b = blockIdx.y % g.Nb, j = blockIdx.y / g.Nb;
+    // under the causal mask the later a query block, the more key blocks it walks: the longest go first
+    const int rblk = g.causal ? gridDim.y - 1 - blockIdx.y : blockIdx.y;
+    const int l = g.tile0 + rblk / g.nblk, e0 = (rblk % g.nblk) * kWgRows;
+    const int b = blockIdx.x % g.Nb, j = blockIdx.x / g.Nb;
     const Slab sq = slab_of(g, l, b, j);
     if (e0 >= sq.ext) return;
     const int eq = e0 + 32 * w + ln;
@@ -274,8 +276,10 @@ __global__ void __launch_bounds__(256, 2) attn_dq_f32(const BwdArgs a) {
     __shared__ float lds[2][2 * Blk::kFloats];
     const AttnGeom& g = a.g;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, hh = lane >> 5, ln = lane & 31;
-    const int l = g.tile0 + blockIdx.x / g.nblk, e0 = (blockIdx.x % g.nblk) * kWgRows;
-    const int b = blockIdx.y % g.Nb, j = blockIdx.y / g.Nb;
+    // under the causal mask the later a query block, the more key blocks it walks: the longest go first
+    const int rblk = g.causal ? gridDim.y - 1 - blockIdx.y : blockIdx.y;
+    const int l = g.tile0 + rblk / g.nblk, e0 = (rblk % g.nblk) * kWgRows;
+    const int b = blockIdx.x % g.Nb, j = blockIdx.x / g.Nb;
     const Slab sq = slab_of(g, l, b, j);
     if (e0 >= sq.ext) return;
     const int eq = e0 + 32 * w + ln;
@@ -370,8 +374,9 @@ __global__ void __launch_bounds__(256, 2) attn_dkv_f32(const BwdArgs a) {
     __shared__ float lds[2][2 * Blk::kFloats + 2 * kBlk];
     const AttnGeom& g = a.g;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, hh = lane >> 5, ln = lane & 31;
-    const int l = g.tile0 + blockIdx.x / g.nblk, e0 = (blockIdx.x % g.nblk) * kWgRows;
-    const int b = blockIdx.y % g.Nb, j = blockIdx.y / g.Nb;
+    // (under the causal mask the earliest key blocks meet the most query blocks: already first)
+    const int l = g.tile0 + blockIdx.y / g.nblk, e0 = (blockIdx.y % g.nblk) * kWgRows;
+    const int b = blockIdx.x % g.Nb, j = blockIdx.x / g.Nb;
     const Slab sk = slab_of(g, l, b, j);
     if (e0 >= sk.ext) return;
     const int ek = e0 + 32 * w + ln;
@@ -489,7 +494,8 @@ int32_t check_attn(nnt_ctx* ctx, const char* who, std::initializer_list<const nn
             return fail(ctx, NNT_EINVAL, std::string(who) + ": stats must be tiled like the operands' other axes");
     for (void* p : stats->tiles)
         if (!p) return fail(ctx, NNT_EINVAL, std::string(who) + ": stats tile missing");
-    if (first->shape[2] * first->shape[3] > 65535) return fail(ctx, NNT_EINVAL, std::string(who) + ": more than 65535 (batch, head) pairs");
+    if (first->grid[1] * ((first->base[1] + kWgRows - 1) / kWgRows) > 65535 || first->shape[2] * first->shape[3] > INT32_MAX)
+        return fail(ctx, NNT_EINVAL, std::string(who) + ": sequence too long for one launch");
     return NNT_OK;
 }
 
@@ -530,7 +536,7 @@ int32_t nnt_attention_fwd(nnt_ctx* ctx, nnt_tensor* Q, nnt_tensor* K, nnt_tensor
     FwdArgs a{g, Q->d_tiles, K->d_tiles, V->d_tiles, B->d_tiles, stats->d_tiles};
     const double pair_flops = 4.0 * g.H * g.Nb * g.Nh;   // two products, 2 flops per multiply-add
     auto launch = [](hipStream_t st, const FwdArgs& fa, int ntile) {
-        const dim3 grid((unsigned)(ntile * fa.g.nblk), (unsigned)(fa.g.Nb * fa.g.Nh)), block(256);
+        const dim3 grid((unsigned)(fa.g.Nb * fa.g.Nh), (unsigned)(ntile * fa.g.nblk)), block(256);
         if (fa.g.H == 64) hipLaunchKernelGGL(attn_fwd_f32<64>, grid, block, 0, st, fa);
         else hipLaunchKernelGGL(attn_fwd_f32<128>, grid, block, 0, st, fa);
         return hipGetLastError() == hipSuccess ? (int32_t)NNT_OK : (int32_t)NNT_EHIP;
@@ -576,7 +582,7 @@ int32_t nnt_attention_bwd(nnt_ctx* ctx, nnt_tensor* Q, nnt_tensor* K, nnt_tensor
     return submit(ctx, {Q->all(kRead), K->all(kRead), V->all(kRead), B->all(kRead), stats->all(kRead), dB->all(kRead),
                         dQ->all(kWrite), dK->all(kWrite), dV->all(kWrite), scr},
                   [=](hipStream_t st) {
-                      const dim3 grid((unsigned)(a.g.gs * a.g.nblk), (unsigned)(a.g.Nb * a.g.Nh)), block(256);
+                      const dim3 grid((unsigned)(a.g.Nb * a.g.Nh), (unsigned)(a.g.gs * a.g.nblk)), block(256);
                       if (a.g.H == 64) hipLaunchKernelGGL(attn_dq_f32<64>, grid, block, 0, st, a);
                       else hipLaunchKernelGGL(attn_dq_f32<128>, grid, block, 0, st, a);
                       if (hipGetLastError() != hipSuccess) return (int32_t)NNT_EHIP;

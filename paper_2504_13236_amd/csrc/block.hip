@@ -31,6 +31,8 @@ bool cfg_ok(const nnt_gpt2_block_cfg* c) {
     if (c->tile_e < 1 || c->tile_m < 1 || c->tile_s < 1 || c->tile_b < 1 || c->tile_j < 1 || c->tile_i < 1) return false;
     if (c->dtype != NNT_F32 && c->dtype != NNT_BF16) return false;
     if (c->gelu_variant != NNT_GELU_TANH && c->gelu_variant != NNT_GELU_ERF) return false;
+    if (c->fused_attention != 0 && c->fused_attention != 1) return false;
+    if (c->fused_attention && c->tile_i < c->N_e / c->N_h) return false;    // the fused kernels keep whole heads
     return true;
 }
 
@@ -98,7 +100,9 @@ int32_t nnt_gpt2_block_slot(const nnt_gpt2_block_cfg* c, int32_t slot, nnt_slot_
         case NNT_BLK_Q: case NNT_BLK_K: case NNT_BLK_V: case NNT_BLK_BH:
         case NNT_BLK_DBH: case NNT_BLK_DQ: case NNT_BLK_DK: case NNT_BLK_DV:
             set(o, act, 4, head4, head4b); break;
-        case NNT_BLK_P: case NNT_BLK_DP: set(o, act, 4, sc4, sc4b, c->causal ? 1 : 0); break;
+        case NNT_BLK_P: case NNT_BLK_DP:
+            if (!c->fused_attention) set(o, act, 4, sc4, sc4b, c->causal ? 1 : 0);   // never formed by the fused kernels
+            break;
         case NNT_BLK_H1: case NNT_BLK_G: case NNT_BLK_DG: set(o, act, 3, mlp3, mlp3b); break;
         default: return NNT_EINVAL;
     }
@@ -185,9 +189,13 @@ int32_t nnt_gpt2_block_forward(nnt_gpt2_block* b, nnt_tensor* X, nnt_tensor* Out
     TRY(linear(b, weight(b, NNT_BLK_W_QKV), s[NNT_BLK_X1], s[NNT_BLK_B_QKV], s[NNT_BLK_QKV]));
     nnt_tensor* qkv[3] = {s[NNT_BLK_Q], s[NNT_BLK_K], s[NNT_BLK_V]};
     TRY(nnt_head_split(ctx, s[NNT_BLK_QKV], 3, qkv));
-    TRY(nnt_gemm(ctx, sc, NNT_OP_T, s[NNT_BLK_K], NNT_OP_N, s[NNT_BLK_Q], 0.f, s[NNT_BLK_P], 1, 2, nullptr));
-    TRY(nnt_softmax_fwd(ctx, s[NNT_BLK_P], s[NNT_BLK_SM_STATS], 1.f, c.causal));
-    TRY(nnt_gemm(ctx, 1.f, NNT_OP_N, s[NNT_BLK_V], NNT_OP_N, s[NNT_BLK_P], 0.f, s[NNT_BLK_BH], 1, 2, nullptr));
+    if (c.fused_attention) {
+        TRY(nnt_attention_fwd(ctx, s[NNT_BLK_Q], s[NNT_BLK_K], s[NNT_BLK_V], sc, c.causal, s[NNT_BLK_BH], s[NNT_BLK_SM_STATS]));
+    } else {
+        TRY(nnt_gemm(ctx, sc, NNT_OP_T, s[NNT_BLK_K], NNT_OP_N, s[NNT_BLK_Q], 0.f, s[NNT_BLK_P], 1, 2, nullptr));
+        TRY(nnt_softmax_fwd(ctx, s[NNT_BLK_P], s[NNT_BLK_SM_STATS], 1.f, c.causal));
+        TRY(nnt_gemm(ctx, 1.f, NNT_OP_N, s[NNT_BLK_V], NNT_OP_N, s[NNT_BLK_P], 0.f, s[NNT_BLK_BH], 1, 2, nullptr));
+    }
     nnt_tensor* bh[1] = {s[NNT_BLK_BH]};
     TRY(nnt_head_merge(ctx, 1, bh, s[NNT_BLK_BM]));
     TRY(linear(b, weight(b, NNT_BLK_W_O), s[NNT_BLK_BM], s[NNT_BLK_B_O], s[NNT_BLK_X2]));
@@ -222,12 +230,17 @@ int32_t nnt_gpt2_block_backward(nnt_gpt2_block* b, nnt_tensor* dOut, nnt_tensor*
     TRY(linear_bwd(b, weight(b, NNT_BLK_W_O), s[NNT_BLK_BM], s[NNT_BLK_DX2], s[NNT_BLK_DBM], g[NNT_BLK_W_O], g[NNT_BLK_B_O]));
     nnt_tensor* dbh[1] = {s[NNT_BLK_DBH]};
     TRY(nnt_head_split(ctx, s[NNT_BLK_DBM], 1, dbh));
-    // dV = dB P^T, dP = V^T dB, softmax adjoint, dQ = K dA / sqrt(h), dK = Q dA^T / sqrt(h)
-    TRY(nnt_gemm(ctx, 1.f, NNT_OP_N, s[NNT_BLK_DBH], NNT_OP_T, s[NNT_BLK_P], 0.f, s[NNT_BLK_DV], 1, 2, nullptr));
-    TRY(nnt_gemm(ctx, 1.f, NNT_OP_T, s[NNT_BLK_V], NNT_OP_N, s[NNT_BLK_DBH], 0.f, s[NNT_BLK_DP], 1, 2, nullptr));
-    TRY(nnt_softmax_bwd(ctx, s[NNT_BLK_P], s[NNT_BLK_DP]));
-    TRY(nnt_gemm(ctx, sc, NNT_OP_N, s[NNT_BLK_K], NNT_OP_N, s[NNT_BLK_DP], 0.f, s[NNT_BLK_DQ], 1, 2, nullptr));
-    TRY(nnt_gemm(ctx, sc, NNT_OP_N, s[NNT_BLK_Q], NNT_OP_T, s[NNT_BLK_DP], 0.f, s[NNT_BLK_DK], 1, 2, nullptr));
+    if (c.fused_attention) {
+        TRY(nnt_attention_bwd(ctx, s[NNT_BLK_Q], s[NNT_BLK_K], s[NNT_BLK_V], s[NNT_BLK_BH], s[NNT_BLK_SM_STATS], s[NNT_BLK_DBH],
+                              sc, c.causal, s[NNT_BLK_DQ], s[NNT_BLK_DK], s[NNT_BLK_DV]));
+    } else {
+        // dV = dB P^T, dP = V^T dB, softmax adjoint, dQ = K dA / sqrt(h), dK = Q dA^T / sqrt(h)
+        TRY(nnt_gemm(ctx, 1.f, NNT_OP_N, s[NNT_BLK_DBH], NNT_OP_T, s[NNT_BLK_P], 0.f, s[NNT_BLK_DV], 1, 2, nullptr));
+        TRY(nnt_gemm(ctx, 1.f, NNT_OP_T, s[NNT_BLK_V], NNT_OP_N, s[NNT_BLK_DBH], 0.f, s[NNT_BLK_DP], 1, 2, nullptr));
+        TRY(nnt_softmax_bwd(ctx, s[NNT_BLK_P], s[NNT_BLK_DP]));
+        TRY(nnt_gemm(ctx, sc, NNT_OP_N, s[NNT_BLK_K], NNT_OP_N, s[NNT_BLK_DP], 0.f, s[NNT_BLK_DQ], 1, 2, nullptr));
+        TRY(nnt_gemm(ctx, sc, NNT_OP_N, s[NNT_BLK_Q], NNT_OP_T, s[NNT_BLK_DP], 0.f, s[NNT_BLK_DK], 1, 2, nullptr));
+    }
     nnt_tensor* dqkv[3] = {s[NNT_BLK_DQ], s[NNT_BLK_DK], s[NNT_BLK_DV]};
     TRY(nnt_head_merge(ctx, 3, dqkv, s[NNT_BLK_DQKV]));
     TRY(linear_bwd(b, weight(b, NNT_BLK_W_QKV), s[NNT_BLK_X1], s[NNT_BLK_DQKV], s[NNT_BLK_DX1], g[NNT_BLK_W_QKV], g[NNT_BLK_B_QKV]));

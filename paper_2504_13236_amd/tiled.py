@@ -201,7 +201,7 @@ class Gpt2Block:
     slot) and exposes forward / backward / adam."""
 
     def __init__(self, ctx: Context, N_e, N_h, N_m, N_s, N_b, tiles, dtype="f32", eps=1e-5, gelu="tanh",
-                 causal=True, adam=True):
+                 causal=True, adam=True, fused_attention=False):
         self.ctx = ctx
         cfg = capi.nnt_gpt2_block_cfg()
         cfg.N_e, cfg.N_h, cfg.N_m, cfg.N_s, cfg.N_b = N_e, N_h, N_m, N_s, N_b
@@ -211,6 +211,7 @@ class Gpt2Block:
         cfg.gelu_variant = capi.NNT_GELU_TANH if gelu == "tanh" else capi.NNT_GELU_ERF
         cfg.eps = eps
         cfg.causal = 1 if causal else 0
+        cfg.fused_attention = 1 if fused_attention else 0
         self.cfg = cfg
         self.dtype = cfg.dtype
         self.slots = [None] * capi.NNT_BLK_NSLOTS

@@ -31,11 +31,11 @@ def oracle_run(cfg, inp, adam):
     return res
 
 
-def gpu_run(tiled, cfg, inp, tiles, adam, gran=0, n_streams=4, serial=False):
+def gpu_run(tiled, cfg, inp, tiles, adam, gran=0, n_streams=4, serial=False, fused=False):
     out = {}
     with tiled.Context(n_streams=n_streams, granularity=gran, serial=serial) as ctx:
         blk = tiled.Gpt2Block(ctx, cfg.N_e, cfg.N_h, cfg.N_m, cfg.N_s, cfg.N_b, tiles, dtype=cfg.dtype, eps=cfg.eps,
-                              gelu=cfg.gelu, adam=adam)
+                              gelu=cfg.gelu, adam=adam, fused_attention=fused)
         blk.set_params({k: inp[k] for k in workload.PARAM_NAMES})
         X, dOut = blk.activation(inp["X"]), blk.activation(inp["dOut"])
         Out, dX = blk.activation(), blk.activation()
@@ -113,6 +113,28 @@ def test_block_serial_and_multistream_are_bit_identical(mods):
     assert relerr(c["Out"], a["Out"]) < 1e-5 and relerr(c["dX"], a["dX"]) < 1e-5
 
 
+@pytest.mark.parametrize("gran", [0, 1])
+def test_block_C1_fused_attention(mods, gran):
+    """The same block with scores, softmax and the product with V replaced by the fused kernels
+    (whole heads per tile: tile_i = head size)."""
+    capi, tiled = mods
+    cfg = workload.CONFIGS[1]
+    inp = workload.generate(cfg)
+    ref = oracle_run(cfg, inp, True)
+    tiles = dict(workload.base_tiles(cfg), i=cfg.h)
+    got = gpu_run(tiled, cfg, inp, tiles, True, gran=gran, fused=True)
+    compare(got, ref, "f32", True)
+
+
+def test_block_fused_attention_needs_whole_heads(mods):
+    capi, tiled = mods
+    cfg = workload.CONFIGS[1]
+    with tiled.Context(n_streams=1) as ctx:
+        with pytest.raises(capi.NntError):
+            tiled.Gpt2Block(ctx, cfg.N_e, cfg.N_h, cfg.N_m, cfg.N_s, cfg.N_b, dict(workload.base_tiles(cfg), i=32),
+                            dtype="f32", fused_attention=True)
+
+
 def small_bf16_cfg():
     # C3's recipe at a size the oracle finishes at once: bf16 storage, fp32 accumulate and masters, Adam
     return workload.CONFIGS[3].replace(N_e=256, N_h=4, N_m=1024, N_s=192, N_b=2, tile=128)
@@ -147,6 +169,16 @@ def test_block_C2_full_size(mods):
     got = gpu_run(tiled, cfg, inp, workload.base_tiles(cfg), False)
     errs = compare(got, ref, "f32", False)
     print("C2 max-norm relative errors:", {k: "%.2e" % v for k, v in errs.items()})
+
+
+def test_block_C2_full_size_fused_attention(mods):
+    capi, tiled = mods
+    cfg = workload.CONFIGS[2]
+    inp = workload.generate(cfg)
+    ref = oracle_run(cfg, inp, False)
+    got = gpu_run(tiled, cfg, inp, workload.base_tiles(cfg), False, fused=True)
+    errs = compare(got, ref, "f32", False)
+    print("C2 (fused attention) max-norm relative errors:", {k: "%.2e" % v for k, v in errs.items()})
 
 
 def test_block_C3_full_size_bf16(mods):

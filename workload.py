@@ -139,14 +139,19 @@ def causal_tile_pairs(cfg: BlockConfig):
     return [(kt, qt) for qt in range(g) for kt in range(g) if kt * ts <= min(cfg.N_s, (qt + 1) * ts) - 1]
 
 
-def model_flops(cfg: BlockConfig, tile_skip: bool = True) -> float:
+def model_flops(cfg: BlockConfig, tile_skip: bool = True, visible_only: bool = False) -> float:
     """Forward+backward flops of one block: weight GEMMs 3 * 24 T N_e^2 and
     attention products 3 * 4 N_s^2 N_e N_b, the latter counted only on the
-    sequence-tile pairs that are actually computed when `tile_skip`."""
+    sequence-tile pairs that are actually computed when `tile_skip`, or only on
+    the (key, query) pairs the causal mask leaves visible when `visible_only`
+    (the fused kernels skip masked work below tile granularity, and the flops of
+    their recomputation are not credited either)."""
     ts = base_tiles(cfg)["s"]
     g = math.ceil(cfg.N_s / ts)
     ext = [min(ts, cfg.N_s - i * ts) for i in range(g)]
-    if tile_skip:
+    if visible_only:
+        pairs = cfg.N_s * (cfg.N_s + 1) // 2
+    elif tile_skip:
         pairs = sum(ext[kt] * ext[qt] for kt, qt in causal_tile_pairs(cfg))
     else:
         pairs = cfg.N_s * cfg.N_s
