@@ -71,43 +71,15 @@ __device__ __forceinline__ T* rows_of(void* const* tiles, const Slab& s, int wid
     return static_cast<T*>(tiles[s.tile]) + s.off * width;
 }
 
-// ---------------------------------------------------------------- fp32 building blocks
-template <int H> struct F32Block {
-    static constexpr int LD = H + 1;                 // odd row pitch: row-wise and column-wise fragment reads both spread over the banks
-    static constexpr int kFloats = kBlk * LD;
-    static constexpr int kVec = H / 16;              // float4 per thread per block (64 rows x H / 4 vectors over 256 threads)
-
-    // rows r0 .. r0+63 of a slab (rows of H contiguous floats), zeros beyond `ext`
-    static __device__ __forceinline__ void load(const float* slab, int r0, int ext, int tid, float4 (&reg)[kVec]) {
-#pragma unroll
-        for (int c = 0; c < kVec; c++) {
-            const int idx = tid + 256 * c;
-            const int row = idx / (H / 4), c4 = idx % (H / 4);
-            reg[c] = (r0 + row < ext) ? *reinterpret_cast<const float4*>(slab + (int64_t)(r0 + row) * H + c4 * 4)
-                                      : make_float4(0.f, 0.f, 0.f, 0.f);
-        }
-    }
-    static __device__ __forceinline__ void store(float* lds, int tid, const float4 (&reg)[kVec]) {
-#pragma unroll
-        for (int c = 0; c < kVec; c++) {
-            const int idx = tid + 256 * c;
-            const int row = idx / (H / 4), c4 = idx % (H / 4);
-            float* d = lds + row * LD + c4 * 4;
-            d[0] = reg[c].x; d[1] = reg[c].y; d[2] = reg[c].z; d[3] = reg[c].w;
-        }
-    }
-    // A operand of a product whose rows are the block's rows and whose contraction runs over the
-    // first axis: lane (row ln, half hh) of k-step s takes element s + (H/2) hh of row 32 sub + ln
-    static __device__ __forceinline__ float by_row(const float* lds, int sub, int ln, int hh, int s) {
-        return lds[(32 * sub + ln) * LD + s + (H / 2) * hh];
-    }
-    // A operand of a product whose rows are first-axis elements 32 rb + ln and whose contraction
-    // runs over the block's rows: k-step r of half hh is row 32 sub + 8 (r/4) + 4 hh + r%4, the row
-    // that accumulator register r of that half belongs to
-    static __device__ __forceinline__ float by_col(const float* lds, int sub, int rb, int ln, int hh, int r) {
-        return lds[(32 * sub + 8 * (r / 4) + 4 * hh + (r % 4)) * LD + 32 * rb + ln];
-    }
-};
+// ---------------------------------------------------------------- element-type traits
+// What differs between the two storage types: how a block of 64 streamed rows sits in LDS, how a
+// lane keeps its own row, and the two kinds of products.
+//
+//   rows_times_own   acc[r][c] += sum_i block[32 sub + r][i] * own[c][i]      (32 x 32, contraction over
+//                    the first axis; A operand read row-wise from LDS, B operand = the lane's own row)
+//   cols_times_acc   out[rb][i][c] += sum_r block[32 sub + r][32 rb + i] * p[r][c]   (contraction over the
+//                    block's rows; p comes from accumulator registers: register r of lane half hh holds
+//                    row acc_row(r, hh), and the A operand is read from LDS in that same order)
 
 __device__ __forceinline__ int acc_row(int r, int hh) { return 8 * (r / 4) + 4 * hh + (r % 4); }
 
@@ -118,28 +90,180 @@ __device__ __forceinline__ f32x16 zero16() {
     return z;
 }
 
-// this lane's half (elements (H/2) hh ..) of row `row` of a slab, times `mul`; zeros if !valid
-template <int H>
-__device__ __forceinline__ void load_own_row(const float* slab, int row, int hh, bool valid, float mul, float (&f)[H / 2]) {
-    const float4* p = reinterpret_cast<const float4*>(slab + (int64_t)row * H + (H / 2) * hh);
+template <int H_> struct F32Traits {
+    static constexpr int H = H_;
+    using T = float;
+    using Vec = float4;                               // 16 bytes of a row
+    static constexpr int kPer = 4;                    // elements per Vec
+    static constexpr int kVec = H / 16;               // Vec per thread per block (64 rows x H / 4 over 256 threads)
+    // v_mfma_f32_32x32x2_f32: a lane supplies one element per instruction, half hh the k index hh.
+    // Odd row pitch: row-wise and column-wise fragment reads both spread over the banks.
+    static constexpr int LD = H + 1;
+    // pitch for a block that is only read column-wise: puts the two lane halves 32 banks apart
+    static constexpr int LD_COLS = H + 8;
+    struct Own { float v[H / 2]; };                   // elements s + (H/2) hh of the lane's row
+    struct Packed { f32x16 v; };
+
+    static __device__ __forceinline__ Vec zero_vec() { return make_float4(0.f, 0.f, 0.f, 0.f); }
+    template <int LDX>
+    static __device__ __forceinline__ void put(T* lds, int row, int c, const Vec& x) {
+        T* d = lds + row * LDX + c * kPer;
+        if constexpr (LDX % 4 == 0) {
+            *reinterpret_cast<Vec*>(d) = x;
+        } else {
+            d[0] = x.x; d[1] = x.y; d[2] = x.z; d[3] = x.w;
+        }
+    }
+    static __device__ __forceinline__ void load_own(const T* slab, int row, int hh, bool valid, Own& o) {
+        const float4* p = reinterpret_cast<const float4*>(slab + (int64_t)row * H + (H / 2) * hh);
 #pragma unroll
-    for (int s4 = 0; s4 < H / 8; s4++) {
-        const float4 v = valid ? p[s4] : make_float4(0.f, 0.f, 0.f, 0.f);
-        f[4 * s4 + 0] = v.x * mul; f[4 * s4 + 1] = v.y * mul; f[4 * s4 + 2] = v.z * mul; f[4 * s4 + 3] = v.w * mul;
+        for (int s4 = 0; s4 < H / 8; s4++) {
+            const float4 x = valid ? p[s4] : make_float4(0.f, 0.f, 0.f, 0.f);
+            o.v[4 * s4 + 0] = x.x; o.v[4 * s4 + 1] = x.y; o.v[4 * s4 + 2] = x.z; o.v[4 * s4 + 3] = x.w;
+        }
+    }
+    // sum over the first axis of a[i] * b[i] restricted to this lane's half of the row
+    static __device__ __forceinline__ float dot_own(const Own& a, const Own& b) {
+        float d = 0.f;
+#pragma unroll
+        for (int k = 0; k < H / 2; k++) d += a.v[k] * b.v[k];
+        return d;
+    }
+    template <int LDX>
+    static __device__ __forceinline__ void rows_times_own(f32x16& acc, const T* lds, int sub, int ln, int hh, const Own& o) {
+        const T* p = lds + (32 * sub + ln) * LDX + (H / 2) * hh;
+#pragma unroll
+        for (int k = 0; k < H / 2; k++) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(p[k], o.v[k], acc, 0, 0, 0);
+    }
+    static __device__ __forceinline__ void pack(const f32x16& x, Packed& pk) { pk.v = x; }
+    template <int LDX>
+    static __device__ __forceinline__ void cols_times_acc(f32x16 (&out)[H / 32], const T* lds, int sub, int lane, const Packed& pk) {
+        const int ln = lane & 31, hh = lane >> 5;
+#pragma unroll
+        for (int r = 0; r < 16; r++)
+#pragma unroll
+            for (int rb = 0; rb < H / 32; rb++)
+                out[rb] = __builtin_amdgcn_mfma_f32_32x32x2f32(lds[(32 * sub + acc_row(r, hh)) * LDX + 32 * rb + ln], pk.v[r], out[rb], 0, 0, 0);
+    }
+    static __device__ __forceinline__ void store4(T* p, float a, float b, float c, float d) {
+        *reinterpret_cast<float4*>(p) = make_float4(a, b, c, d);
+    }
+};
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+
+template <int H_> struct Bf16Traits {
+    static constexpr int H = H_;
+    using T = bf16_t;
+    using Vec = uint4;
+    static constexpr int kPer = 8;
+    static constexpr int kVec = H / 32;               // 64 rows x H / 8 vectors over 256 threads
+    // v_mfma_f32_32x32x16_bf16: a lane supplies 8 consecutive k per instruction, half hh the k indices 8 hh ..
+    // Row-wise fragments are 16-byte reads of rows 144 (272) bytes apart: 16 lanes cover all 64 banks.
+    static constexpr int LD = H + 8;
+    // Column-wise fragments are transposing reads (ds_read_b64_tr_b16) of 4 rows x 64 bytes per half
+    // wave: rows 64 bytes apart modulo 256 keep the four rows on different banks.
+    static constexpr int LD_COLS = H + 32;
+    struct Own { bf16x8 v[H / 16]; };                 // elements 16 s + 8 hh .. + 7 of the lane's row
+    struct Packed { bf16x8 v[2]; };                   // registers 8 m .. 8 m + 7 of an accumulator, rounded
+
+    static __device__ __forceinline__ Vec zero_vec() { return make_uint4(0u, 0u, 0u, 0u); }
+    template <int LDX>
+    static __device__ __forceinline__ void put(T* lds, int row, int c, const Vec& x) {
+        *reinterpret_cast<Vec*>(lds + row * LDX + c * kPer) = x;
+    }
+    static __device__ __forceinline__ void load_own(const T* slab, int row, int hh, bool valid, Own& o) {
+        const uint4* p = reinterpret_cast<const uint4*>(slab + (int64_t)row * H + 8 * hh);
+#pragma unroll
+        for (int s = 0; s < H / 16; s++) {
+            const uint4 x = valid ? p[2 * s] : make_uint4(0u, 0u, 0u, 0u);
+            o.v[s] = __builtin_bit_cast(bf16x8, x);
+        }
+    }
+    static __device__ __forceinline__ float dot_own(const Own& a, const Own& b) {
+        float d = 0.f;
+#pragma unroll
+        for (int s = 0; s < H / 16; s++)
+#pragma unroll
+            for (int e = 0; e < 8; e++) d += (float)a.v[s][e] * (float)b.v[s][e];
+        return d;
+    }
+    template <int LDX>
+    static __device__ __forceinline__ void rows_times_own(f32x16& acc, const T* lds, int sub, int ln, int hh, const Own& o) {
+        const T* p = lds + (32 * sub + ln) * LDX + 8 * hh;
+#pragma unroll
+        for (int s = 0; s < H / 16; s++)
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(p + 16 * s), o.v[s], acc, 0, 0, 0);
+    }
+    static __device__ __forceinline__ void pack(const f32x16& x, Packed& pk) {
+#pragma unroll
+        for (int m = 0; m < 2; m++)
+#pragma unroll
+            for (int e = 0; e < 8; e++) pk.v[m][e] = (__bf16)x[8 * m + e];
+    }
+    template <int LDX>
+    static __device__ __forceinline__ void cols_times_acc(f32x16 (&out)[H / 32], const T* lds, int sub, int lane, const Packed& pk) {
+        // Accumulator registers 8 m + e of half hh are the rows 16 m + 8 (e / 4) + 4 hh + e % 4: two runs of
+        // four consecutive rows, one transposing read each.  In such a read the 16 lanes of a group fetch
+        // 8 bytes each -- lane j the columns 4 (j % 4) .. + 3 of row j / 4 of a 4 x 16 patch -- and lane j
+        // receives the four rows of column j.
+        typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+        const int j = lane & 15, grp = lane >> 4, hh = grp >> 1;
+        const T* base = lds + (32 * sub + 4 * hh + (j >> 2)) * LDX + 16 * (grp & 1) + 4 * (j & 3);
+#pragma unroll
+        for (int m = 0; m < 2; m++)
+#pragma unroll
+            for (int rb = 0; rb < H / 32; rb++) {
+                const T* p = base + (16 * m) * LDX + 32 * rb;
+                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
+                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 8 * LDX));
+                const s16x8 x = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                out[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, x), pk.v[m], out[rb], 0, 0, 0);
+            }
+    }
+    static __device__ __forceinline__ void store4(T* p, float a, float b, float c, float d) {
+        uint2 x;
+        x.x = (uint32_t)f2bf(a) | ((uint32_t)f2bf(b) << 16);
+        x.y = (uint32_t)f2bf(c) | ((uint32_t)f2bf(d) << 16);
+        *reinterpret_cast<uint2*>(p) = x;
+    }
+};
+
+// rows r0 .. r0+63 of a slab (rows of H contiguous elements) into registers, zeros beyond `ext`
+template <class X>
+__device__ __forceinline__ void load_block(const typename X::T* slab, int r0, int ext, int tid, typename X::Vec (&reg)[X::kVec]) {
+    constexpr int kRowVecs = X::H / X::kPer;
+#pragma unroll
+    for (int c = 0; c < X::kVec; c++) {
+        const int idx = tid + 256 * c;
+        const int row = idx / kRowVecs, cv = idx % kRowVecs;
+        reg[c] = (r0 + row < ext) ? *reinterpret_cast<const typename X::Vec*>(slab + (int64_t)(r0 + row) * X::H + cv * X::kPer)
+                                  : X::zero_vec();
+    }
+}
+template <class X, int LDX>
+__device__ __forceinline__ void store_block(typename X::T* lds, int tid, const typename X::Vec (&reg)[X::kVec]) {
+    constexpr int kRowVecs = X::H / X::kPer;
+#pragma unroll
+    for (int c = 0; c < X::kVec; c++) {
+        const int idx = tid + 256 * c;
+        X::template put<LDX>(lds, idx / kRowVecs, idx % kRowVecs, reg[c]);
     }
 }
 
 // accumulators (lane = this lane's row of the slab, register r = first-axis element 32 rb + acc_row(r)) to memory
-template <int H>
-__device__ __forceinline__ void store_own_row(float* slab, int row, int hh, bool valid, float mul, const f32x16 (&acc)[H / 32]) {
+template <class X>
+__device__ __forceinline__ void store_own_row(typename X::T* slab, int row, int hh, bool valid, float mul, const f32x16 (&acc)[X::H / 32]) {
     if (!valid) return;
-    float* p = slab + (int64_t)row * H;
+    typename X::T* p = slab + (int64_t)row * X::H;
 #pragma unroll
-    for (int rb = 0; rb < H / 32; rb++)
+    for (int rb = 0; rb < X::H / 32; rb++)
 #pragma unroll
         for (int g = 0; g < 4; g++)
-            *reinterpret_cast<float4*>(p + 32 * rb + 8 * g + 4 * hh) =
-                make_float4(acc[rb][4 * g] * mul, acc[rb][4 * g + 1] * mul, acc[rb][4 * g + 2] * mul, acc[rb][4 * g + 3] * mul);
+            X::store4(p + 32 * rb + 8 * g + 4 * hh, acc[rb][4 * g] * mul, acc[rb][4 * g + 1] * mul, acc[rb][4 * g + 2] * mul,
+                      acc[rb][4 * g + 3] * mul);
 }
 
 struct FwdArgs {
@@ -147,12 +271,17 @@ struct FwdArgs {
     void* const* Q; void* const* K; void* const* V; void* const* O; void* const* stats;
 };
 
-// ---------------------------------------------------------------- forward, fp32
-template <int H>
-__global__ void __launch_bounds__(256, 2) attn_fwd_f32(const FwdArgs a) {
-    using Blk = F32Block<H>;
-    constexpr int LDV = H + 8;   // values are only read column-wise: this pitch puts the two lane halves 32 banks apart
-    __shared__ float lds[2][Blk::kFloats + kBlk * LDV];
+// Which rows of the streamed block a wave has to look at: `nsub` sub-blocks of 32, and whether any
+// of their entries is masked or beyond the tile.
+struct Visible { int nsub; bool plain; };
+
+// ---------------------------------------------------------------- forward
+template <class X>
+__global__ void __launch_bounds__(256, 2) attn_fwd(const FwdArgs a) {
+    using T = typename X::T;
+    constexpr int H = X::H, LDK = X::LD, LDV = X::LD_COLS;
+    constexpr int kBufElems = kBlk * LDK + kBlk * LDV;
+    __shared__ __attribute__((aligned(16))) T lds[2][kBufElems];
     const AttnGeom& g = a.g;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, hh = lane >> 5, ln = lane & 31;
     // under the causal mask the later a query block, the more key blocks it walks: the longest go first
@@ -164,12 +293,13 @@ __global__ void __launch_bounds__(256, 2) attn_fwd_f32(const FwdArgs a) {
     const int eq = e0 + 32 * w + ln;
     const bool qvalid = eq < sq.ext;
     const int qglob = l * g.bs + eq;
+    const int wave_qfirst = l * g.bs + e0 + 32 * w;
     const int wave_qlast = l * g.bs + min(e0 + 32 * w + 31, sq.ext - 1);
     const int wg_qlast = l * g.bs + min(e0 + kWgRows - 1, sq.ext - 1);
+    const float sc2 = g.scale * kLog2e;        // scores are kept in units of log 2
 
-    // queries pre-multiplied so that the scores come out in units of log 2
-    float qf[H / 2];
-    load_own_row<H>(rows_of<const float>(a.Q, sq, H), eq, hh, qvalid, g.scale * kLog2e, qf);
+    typename X::Own qf;
+    X::load_own(rows_of<const T>(a.Q, sq, H), eq, hh, qvalid, qf);
 
     int nit;
     if (g.causal) nit = (wg_qlast / g.bs) * g.nstep + (wg_qlast % g.bs) / kBlk + 1;
@@ -180,22 +310,16 @@ __global__ void __launch_bounds__(256, 2) attn_fwd_f32(const FwdArgs a) {
     for (int rb = 0; rb < H / 32; rb++) O[rb] = zero16();
     float m = kNegInf, lsum = 0.f;
 
-    float4 kr[Blk::kVec], vr[Blk::kVec];
+    typename X::Vec kr[X::kVec], vr[X::kVec];
     auto fetch = [&](int it) {
         const int lk = it / g.nstep, k0 = (it % g.nstep) * kBlk;
         const Slab sk = slab_of(g, lk, b, j);
-        Blk::load(rows_of<const float>(a.K, sk, H), k0, sk.ext, tid, kr);
-        Blk::load(rows_of<const float>(a.V, sk, H), k0, sk.ext, tid, vr);
+        load_block<X>(rows_of<const T>(a.K, sk, H), k0, sk.ext, tid, kr);
+        load_block<X>(rows_of<const T>(a.V, sk, H), k0, sk.ext, tid, vr);
     };
     auto stash = [&](int buf) {
-        Blk::store(lds[buf], tid, kr);
-        float* vs = lds[buf] + Blk::kFloats;
-#pragma unroll
-        for (int c = 0; c < Blk::kVec; c++) {
-            const int idx = tid + 256 * c;
-            const int row = idx / (H / 4), c4 = idx % (H / 4);
-            *reinterpret_cast<float4*>(vs + row * LDV + c4 * 4) = vr[c];
-        }
+        store_block<X, LDK>(lds[buf], tid, kr);
+        store_block<X, LDV>(lds[buf] + kBlk * LDK, tid, vr);
     };
     fetch(0);
     stash(0);
@@ -206,24 +330,34 @@ __global__ void __launch_bounds__(256, 2) attn_fwd_f32(const FwdArgs a) {
         const int ext_k = min(g.bs, g.Ns - lk * g.bs);
         const int kglob0 = lk * g.bs + kloc0;
         if (!(g.causal && kglob0 > wave_qlast)) {
-            const float* Ks = lds[it & 1];
-            const float* Vs = Ks + Blk::kFloats;
+            const T* Ks = lds[it & 1];
+            const T* Vs = Ks + kBlk * LDK;
+            // the second half of the block may be hidden from all of this wave's queries
+            const bool two = !(g.causal && kglob0 + 32 > wave_qlast) && kloc0 + 32 < ext_k;
+            const bool plain = kloc0 + kBlk <= ext_k && (!g.causal || kglob0 + kBlk - 1 <= wave_qfirst);
             f32x16 s[2] = {zero16(), zero16()};
-#pragma unroll
-            for (int k = 0; k < H / 2; k++) {
-                s[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(Blk::by_row(Ks, 0, ln, hh, k), qf[k], s[0], 0, 0, 0);
-                s[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(Blk::by_row(Ks, 1, ln, hh, k), qf[k], s[1], 0, 0, 0);
-            }
+            X::template rows_times_own<LDK>(s[0], Ks, 0, ln, hh, qf);
+            if (two) X::template rows_times_own<LDK>(s[1], Ks, 1, ln, hh, qf);
             float mx = kNegInf;
+            if (plain) {
 #pragma unroll
-            for (int sub = 0; sub < 2; sub++)
+                for (int sub = 0; sub < 2; sub++)
 #pragma unroll
-                for (int r = 0; r < 16; r++) {
-                    const int kl = 32 * sub + acc_row(r, hh);
-                    const bool ok = kloc0 + kl < ext_k && (!g.causal || kglob0 + kl <= qglob);
-                    s[sub][r] = ok ? s[sub][r] : kNegInf;
-                    mx = fmaxf(mx, s[sub][r]);
-                }
+                    for (int r = 0; r < 16; r++) {
+                        s[sub][r] *= sc2;
+                        mx = fmaxf(mx, s[sub][r]);
+                    }
+            } else {
+#pragma unroll
+                for (int sub = 0; sub < 2; sub++)
+#pragma unroll
+                    for (int r = 0; r < 16; r++) {
+                        const int kl = 32 * sub + acc_row(r, hh);
+                        const bool ok = kloc0 + kl < ext_k && (!g.causal || kglob0 + kl <= qglob) && (sub == 0 || two);
+                        s[sub][r] = ok ? s[sub][r] * sc2 : kNegInf;
+                        mx = fmaxf(mx, s[sub][r]);
+                    }
+            }
             mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
             const float m_new = fmaxf(m, mx);
             const float shift = m_new == kNegInf ? 0.f : m_new;
@@ -242,19 +376,19 @@ __global__ void __launch_bounds__(256, 2) attn_fwd_f32(const FwdArgs a) {
             for (int rb = 0; rb < H / 32; rb++)
 #pragma unroll
                 for (int r = 0; r < 16; r++) O[rb][r] *= alpha;
-#pragma unroll
-            for (int sub = 0; sub < 2; sub++)
-#pragma unroll
-                for (int r = 0; r < 16; r++)
-#pragma unroll
-                    for (int rb = 0; rb < H / 32; rb++)
-                        O[rb] = __builtin_amdgcn_mfma_f32_32x32x2f32(Vs[(32 * sub + acc_row(r, hh)) * LDV + 32 * rb + ln], s[sub][r], O[rb], 0, 0, 0);
+            typename X::Packed pk;
+            X::pack(s[0], pk);
+            X::template cols_times_acc<LDV>(O, Vs, 0, lane, pk);
+            if (two) {
+                X::pack(s[1], pk);
+                X::template cols_times_acc<LDV>(O, Vs, 1, lane, pk);
+            }
         }
         if (it + 1 < nit) stash((it + 1) & 1);
         __syncthreads();
     }
     lsum += __shfl_xor(lsum, 32, 64);
-    store_own_row<H>(rows_of<float>(a.O, sq, H), eq, hh, qvalid, 1.f / lsum, O);
+    store_own_row<X>(rows_of<T>(a.O, sq, H), eq, hh, qvalid, 1.f / lsum, O);
     if (qvalid && hh == 0) {
         float* st = rows_of<float>(a.stats, sq, 2) + 2 * (int64_t)eq;
         st[0] = m * kLn2;
@@ -266,17 +400,17 @@ struct BwdArgs {
     AttnGeom g;
     void* const* Q; void* const* K; void* const* V; void* const* O; void* const* stats; void* const* dO;
     void* const* dQ; void* const* dK; void* const* dV;
-    float* aux;     // per (query, batch, head): log2 of the softmax denominator times 2^maximum, and D
+    float* aux;     // per (query, batch, head): log2 of (softmax denominator times 2^maximum), and D
 };
 
-// ---------------------------------------------------------------- dQ, fp32 (also writes aux)
-template <int H>
-__global__ void __launch_bounds__(256, 2) attn_dq_f32(const BwdArgs a) {
-    using Blk = F32Block<H>;
-    __shared__ float lds[2][2 * Blk::kFloats];
+// ---------------------------------------------------------------- dQ (also writes aux)
+template <class X>
+__global__ void __launch_bounds__(256, 2) attn_dq(const BwdArgs a) {
+    using T = typename X::T;
+    constexpr int H = X::H, LD = X::LD;
+    __shared__ __attribute__((aligned(16))) T lds[2][2 * kBlk * LD];
     const AttnGeom& g = a.g;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, hh = lane >> 5, ln = lane & 31;
-    // under the causal mask the later a query block, the more key blocks it walks: the longest go first
     const int rblk = g.causal ? gridDim.y - 1 - blockIdx.y : blockIdx.y;
     const int l = g.tile0 + rblk / g.nblk, e0 = (rblk % g.nblk) * kWgRows;
     const int b = blockIdx.x % g.Nb, j = blockIdx.x / g.Nb;
@@ -285,18 +419,19 @@ __global__ void __launch_bounds__(256, 2) attn_dq_f32(const BwdArgs a) {
     const int eq = e0 + 32 * w + ln;
     const bool qvalid = eq < sq.ext;
     const int qglob = l * g.bs + eq;
+    const int wave_qfirst = l * g.bs + e0 + 32 * w;
     const int wave_qlast = l * g.bs + min(e0 + 32 * w + 31, sq.ext - 1);
     const int wg_qlast = l * g.bs + min(e0 + kWgRows - 1, sq.ext - 1);
+    const float sc2 = g.scale * kLog2e;
 
-    float qf[H / 2], dof[H / 2];
-    load_own_row<H>(rows_of<const float>(a.Q, sq, H), eq, hh, qvalid, g.scale * kLog2e, qf);
-    load_own_row<H>(rows_of<const float>(a.dO, sq, H), eq, hh, qvalid, 1.f, dof);
+    typename X::Own qf, dof;
+    X::load_own(rows_of<const T>(a.Q, sq, H), eq, hh, qvalid, qf);
+    X::load_own(rows_of<const T>(a.dO, sq, H), eq, hh, qvalid, dof);
     float lse = 0.f, D = 0.f;
     {
-        float of[H / 2];
-        load_own_row<H>(rows_of<const float>(a.O, sq, H), eq, hh, qvalid, 1.f, of);
-#pragma unroll
-        for (int k = 0; k < H / 2; k++) D += of[k] * dof[k];
+        typename X::Own of;
+        X::load_own(rows_of<const T>(a.O, sq, H), eq, hh, qvalid, of);
+        D = X::dot_own(of, dof);
         D += __shfl_xor(D, 32, 64);
         if (qvalid) {
             const float* st = rows_of<const float>(a.stats, sq, 2) + 2 * (int64_t)eq;
@@ -317,16 +452,16 @@ __global__ void __launch_bounds__(256, 2) attn_dq_f32(const BwdArgs a) {
 #pragma unroll
     for (int rb = 0; rb < H / 32; rb++) dQ[rb] = zero16();
 
-    float4 kr[Blk::kVec], vr[Blk::kVec];
+    typename X::Vec kr[X::kVec], vr[X::kVec];
     auto fetch = [&](int it) {
         const int lk = it / g.nstep, k0 = (it % g.nstep) * kBlk;
         const Slab sk = slab_of(g, lk, b, j);
-        Blk::load(rows_of<const float>(a.K, sk, H), k0, sk.ext, tid, kr);
-        Blk::load(rows_of<const float>(a.V, sk, H), k0, sk.ext, tid, vr);
+        load_block<X>(rows_of<const T>(a.K, sk, H), k0, sk.ext, tid, kr);
+        load_block<X>(rows_of<const T>(a.V, sk, H), k0, sk.ext, tid, vr);
     };
     auto stash = [&](int buf) {
-        Blk::store(lds[buf], tid, kr);
-        Blk::store(lds[buf] + Blk::kFloats, tid, vr);
+        store_block<X, LD>(lds[buf], tid, kr);
+        store_block<X, LD>(lds[buf] + kBlk * LD, tid, vr);
     };
     fetch(0);
     stash(0);
@@ -337,41 +472,39 @@ __global__ void __launch_bounds__(256, 2) attn_dq_f32(const BwdArgs a) {
         const int ext_k = min(g.bs, g.Ns - lk * g.bs);
         const int kglob0 = lk * g.bs + kloc0;
         if (!(g.causal && kglob0 > wave_qlast)) {
-            const float* Ks = lds[it & 1];
-            const float* Vs = Ks + Blk::kFloats;
-#pragma unroll
-            for (int sub = 0; sub < 2; sub++) {
+            const T* Ks = lds[it & 1];
+            const T* Vs = Ks + kBlk * LD;
+            const int nsub = (!(g.causal && kglob0 + 32 > wave_qlast) && kloc0 + 32 < ext_k) ? 2 : 1;
+            const bool plain = kloc0 + kBlk <= ext_k && (!g.causal || kglob0 + kBlk - 1 <= wave_qfirst);
+            for (int sub = 0; sub < nsub; sub++) {
                 f32x16 s = zero16(), dp = zero16();
-#pragma unroll
-                for (int k = 0; k < H / 2; k++) {
-                    s = __builtin_amdgcn_mfma_f32_32x32x2f32(Blk::by_row(Ks, sub, ln, hh, k), qf[k], s, 0, 0, 0);
-                    dp = __builtin_amdgcn_mfma_f32_32x32x2f32(Blk::by_row(Vs, sub, ln, hh, k), dof[k], dp, 0, 0, 0);
-                }
+                X::template rows_times_own<LD>(s, Ks, sub, ln, hh, qf);
+                X::template rows_times_own<LD>(dp, Vs, sub, ln, hh, dof);
 #pragma unroll
                 for (int r = 0; r < 16; r++) {
                     const int kl = 32 * sub + acc_row(r, hh);
-                    const bool ok = kloc0 + kl < ext_k && (!g.causal || kglob0 + kl <= qglob);
-                    const float p = ok ? __builtin_amdgcn_exp2f(s[r] - lse) : 0.f;
+                    const bool ok = plain || (kloc0 + kl < ext_k && (!g.causal || kglob0 + kl <= qglob));
+                    const float p = ok ? __builtin_amdgcn_exp2f(s[r] * sc2 - lse) : 0.f;
                     s[r] = p * (dp[r] - D);
                 }
-#pragma unroll
-                for (int r = 0; r < 16; r++)
-#pragma unroll
-                    for (int rb = 0; rb < H / 32; rb++)
-                        dQ[rb] = __builtin_amdgcn_mfma_f32_32x32x2f32(Blk::by_col(Ks, sub, rb, ln, hh, r), s[r], dQ[rb], 0, 0, 0);
+                typename X::Packed pk;
+                X::pack(s, pk);
+                X::template cols_times_acc<LD>(dQ, Ks, sub, lane, pk);
             }
         }
         if (it + 1 < nit) stash((it + 1) & 1);
         __syncthreads();
     }
-    store_own_row<H>(rows_of<float>(a.dQ, sq, H), eq, hh, qvalid, g.scale, dQ);
+    store_own_row<X>(rows_of<T>(a.dQ, sq, H), eq, hh, qvalid, g.scale, dQ);
 }
 
-// ---------------------------------------------------------------- dK and dV, fp32 (reads aux)
-template <int H>
-__global__ void __launch_bounds__(256, 2) attn_dkv_f32(const BwdArgs a) {
-    using Blk = F32Block<H>;
-    __shared__ float lds[2][2 * Blk::kFloats + 2 * kBlk];
+// ---------------------------------------------------------------- dK and dV (reads aux)
+template <class X>
+__global__ void __launch_bounds__(256, 2) attn_dkv(const BwdArgs a) {
+    using T = typename X::T;
+    constexpr int H = X::H, LD = X::LD;
+    constexpr int kAuxElems = 2 * kBlk * (int)(sizeof(float) / sizeof(T));   // 2 x 64 floats, in units of T
+    __shared__ __attribute__((aligned(16))) T lds[2][2 * kBlk * LD + kAuxElems];
     const AttnGeom& g = a.g;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, hh = lane >> 5, ln = lane & 31;
     // (under the causal mask the earliest key blocks meet the most query blocks: already first)
@@ -383,10 +516,12 @@ __global__ void __launch_bounds__(256, 2) attn_dkv_f32(const BwdArgs a) {
     const bool kvalid = ek < sk.ext;
     const int kglob = l * g.bs + ek;
     const int wave_kfirst = l * g.bs + e0 + 32 * w;
+    const int wave_klast = wave_kfirst + 31;
+    const float sc2 = g.scale * kLog2e;
 
-    float kf[H / 2], vf[H / 2];
-    load_own_row<H>(rows_of<const float>(a.K, sk, H), ek, hh, kvalid, g.scale * kLog2e, kf);
-    load_own_row<H>(rows_of<const float>(a.V, sk, H), ek, hh, kvalid, 1.f, vf);
+    typename X::Own kf, vf;
+    X::load_own(rows_of<const T>(a.K, sk, H), ek, hh, kvalid, kf);
+    X::load_own(rows_of<const T>(a.V, sk, H), ek, hh, kvalid, vf);
 
     const int nit = (g.gs - 1) * g.nstep + (g.Ns - (g.gs - 1) * g.bs + kBlk - 1) / kBlk;
     // with the causal mask the first query block that sees any of these keys is the one that holds key e0
@@ -396,13 +531,13 @@ __global__ void __launch_bounds__(256, 2) attn_dkv_f32(const BwdArgs a) {
 #pragma unroll
     for (int rb = 0; rb < H / 32; rb++) { dK[rb] = zero16(); dV[rb] = zero16(); }
 
-    float4 qr[Blk::kVec], dr[Blk::kVec];
+    typename X::Vec qr[X::kVec], dr[X::kVec];
     float2 ar = make_float2(0.f, 0.f);
     auto fetch = [&](int it) {
         const int lq = it / g.nstep, q0 = (it % g.nstep) * kBlk;
         const Slab sq = slab_of(g, lq, b, j);
-        Blk::load(rows_of<const float>(a.Q, sq, H), q0, sq.ext, tid, qr);
-        Blk::load(rows_of<const float>(a.dO, sq, H), q0, sq.ext, tid, dr);
+        load_block<X>(rows_of<const T>(a.Q, sq, H), q0, sq.ext, tid, qr);
+        load_block<X>(rows_of<const T>(a.dO, sq, H), q0, sq.ext, tid, dr);
         if (tid < kBlk) {
             const bool ok = q0 + tid < sq.ext;
             const int64_t qg = (int64_t)lq * g.bs + q0 + tid;
@@ -410,11 +545,12 @@ __global__ void __launch_bounds__(256, 2) attn_dkv_f32(const BwdArgs a) {
         }
     };
     auto stash = [&](int buf) {
-        Blk::store(lds[buf], tid, qr);
-        Blk::store(lds[buf] + Blk::kFloats, tid, dr);
+        store_block<X, LD>(lds[buf], tid, qr);
+        store_block<X, LD>(lds[buf] + kBlk * LD, tid, dr);
         if (tid < kBlk) {
-            lds[buf][2 * Blk::kFloats + tid] = ar.x;
-            lds[buf][2 * Blk::kFloats + kBlk + tid] = ar.y;
+            float* ax = reinterpret_cast<float*>(lds[buf] + 2 * kBlk * LD);
+            ax[tid] = ar.x;
+            ax[kBlk + tid] = ar.y;
         }
     };
     if (it0 < nit) {
@@ -428,40 +564,54 @@ __global__ void __launch_bounds__(256, 2) attn_dkv_f32(const BwdArgs a) {
         const int ext_q = min(g.bs, g.Ns - lq * g.bs);
         const int qglob0 = lq * g.bs + qloc0;
         if (!(g.causal && qglob0 + kBlk - 1 < wave_kfirst)) {
-            const float* Qs = lds[it & 1];
-            const float* Ds = Qs + Blk::kFloats;
-            const float* lses = Ds + Blk::kFloats;
+            const T* Qs = lds[it & 1];
+            const T* Ds = Qs + kBlk * LD;
+            const float* lses = reinterpret_cast<const float*>(Ds + kBlk * LD);
             const float* dsum = lses + kBlk;
-#pragma unroll
-            for (int sub = 0; sub < 2; sub++) {
+            // the first half of the block may hold only queries that precede all of this wave's keys
+            const int sub0 = (g.causal && qglob0 + 31 < wave_kfirst) ? 1 : 0;
+            const int nsub = qloc0 + 32 < ext_q ? 2 : 1;
+            const bool plain = qloc0 + kBlk <= ext_q && (!g.causal || wave_klast <= qglob0);
+            for (int sub = sub0; sub < nsub; sub++) {
                 f32x16 s = zero16(), dp = zero16();
-#pragma unroll
-                for (int k = 0; k < H / 2; k++) {
-                    s = __builtin_amdgcn_mfma_f32_32x32x2f32(Blk::by_row(Qs, sub, ln, hh, k), kf[k], s, 0, 0, 0);
-                    dp = __builtin_amdgcn_mfma_f32_32x32x2f32(Blk::by_row(Ds, sub, ln, hh, k), vf[k], dp, 0, 0, 0);
-                }
+                X::template rows_times_own<LD>(s, Qs, sub, ln, hh, kf);
+                X::template rows_times_own<LD>(dp, Ds, sub, ln, hh, vf);
                 f32x16 p;
 #pragma unroll
                 for (int r = 0; r < 16; r++) {
                     const int ql = 32 * sub + acc_row(r, hh);
-                    const bool ok = qloc0 + ql < ext_q && (!g.causal || kglob <= qglob0 + ql);
-                    p[r] = ok ? __builtin_amdgcn_exp2f(s[r] - lses[ql]) : 0.f;
+                    const bool ok = plain || (qloc0 + ql < ext_q && (!g.causal || kglob <= qglob0 + ql));
+                    p[r] = ok ? __builtin_amdgcn_exp2f(s[r] * sc2 - lses[ql]) : 0.f;
                     s[r] = p[r] * (dp[r] - dsum[ql]);
                 }
-#pragma unroll
-                for (int r = 0; r < 16; r++)
-#pragma unroll
-                    for (int rb = 0; rb < H / 32; rb++) {
-                        dV[rb] = __builtin_amdgcn_mfma_f32_32x32x2f32(Blk::by_col(Ds, sub, rb, ln, hh, r), p[r], dV[rb], 0, 0, 0);
-                        dK[rb] = __builtin_amdgcn_mfma_f32_32x32x2f32(Blk::by_col(Qs, sub, rb, ln, hh, r), s[r], dK[rb], 0, 0, 0);
-                    }
+                typename X::Packed pk;
+                X::pack(p, pk);
+                X::template cols_times_acc<LD>(dV, Ds, sub, lane, pk);
+                X::pack(s, pk);
+                X::template cols_times_acc<LD>(dK, Qs, sub, lane, pk);
             }
         }
         if (it + 1 < nit) stash((it + 1) & 1);
         __syncthreads();
     }
-    store_own_row<H>(rows_of<float>(a.dK, sk, H), ek, hh, kvalid, g.scale, dK);
-    store_own_row<H>(rows_of<float>(a.dV, sk, H), ek, hh, kvalid, 1.f, dV);
+    store_own_row<X>(rows_of<T>(a.dK, sk, H), ek, hh, kvalid, g.scale, dK);
+    store_own_row<X>(rows_of<T>(a.dV, sk, H), ek, hh, kvalid, 1.f, dV);
+}
+
+using FwdKernel = void (*)(const FwdArgs);
+using BwdKernel = void (*)(const BwdArgs);
+
+FwdKernel fwd_kernel(int dtype, int H) {
+    if (dtype == NNT_F32) return H == 64 ? attn_fwd<F32Traits<64>> : attn_fwd<F32Traits<128>>;
+    return H == 64 ? attn_fwd<Bf16Traits<64>> : attn_fwd<Bf16Traits<128>>;
+}
+BwdKernel dq_kernel(int dtype, int H) {
+    if (dtype == NNT_F32) return H == 64 ? attn_dq<F32Traits<64>> : attn_dq<F32Traits<128>>;
+    return H == 64 ? attn_dq<Bf16Traits<64>> : attn_dq<Bf16Traits<128>>;
+}
+BwdKernel dkv_kernel(int dtype, int H) {
+    if (dtype == NNT_F32) return H == 64 ? attn_dkv<F32Traits<64>> : attn_dkv<F32Traits<128>>;
+    return H == 64 ? attn_dkv<Bf16Traits<64>> : attn_dkv<Bf16Traits<128>>;
 }
 
 }  // namespace
@@ -483,7 +633,7 @@ int32_t check_attn(nnt_ctx* ctx, const char* who, std::initializer_list<const nn
         for (void* p : t->tiles)
             if (!p || !aligned16(p)) return fail(ctx, NNT_EINVAL, std::string(who) + ": missing or unaligned tile");
     }
-    if (first->dtype != NNT_F32) return fail(ctx, NNT_EDTYPE, std::string(who) + ": fp32 only");
+    if (first->dtype != NNT_F32 && first->dtype != NNT_BF16) return fail(ctx, NNT_EDTYPE, std::string(who) + ": fp32 or bf16 operands");
     if (first->shape[0] != 64 && first->shape[0] != 128)
         return fail(ctx, NNT_EINVAL, std::string(who) + ": head size must be 64 or 128");
     if (!stats) return fail(ctx, NNT_EINVAL, std::string(who) + ": null tensor");
@@ -535,10 +685,10 @@ int32_t nnt_attention_fwd(nnt_ctx* ctx, nnt_tensor* Q, nnt_tensor* K, nnt_tensor
     AttnGeom g = geom_of(Q, scale, causal);
     FwdArgs a{g, Q->d_tiles, K->d_tiles, V->d_tiles, B->d_tiles, stats->d_tiles};
     const double pair_flops = 4.0 * g.H * g.Nb * g.Nh;   // two products, 2 flops per multiply-add
-    auto launch = [](hipStream_t st, const FwdArgs& fa, int ntile) {
+    const FwdKernel kernel = fwd_kernel(Q->dtype, g.H);
+    auto launch = [kernel](hipStream_t st, const FwdArgs& fa, int ntile) {
         const dim3 grid((unsigned)(fa.g.Nb * fa.g.Nh), (unsigned)(ntile * fa.g.nblk)), block(256);
-        if (fa.g.H == 64) hipLaunchKernelGGL(attn_fwd_f32<64>, grid, block, 0, st, fa);
-        else hipLaunchKernelGGL(attn_fwd_f32<128>, grid, block, 0, st, fa);
+        hipLaunchKernelGGL(kernel, grid, block, 0, st, fa);
         return hipGetLastError() == hipSuccess ? (int32_t)NNT_OK : (int32_t)NNT_EHIP;
     };
     OpTag tag(ctx, "attention_fwd", pair_flops * visible_pairs(g.Ns, 0, g.Ns, causal), false);
@@ -577,18 +727,17 @@ int32_t nnt_attention_bwd(nnt_ctx* ctx, nnt_tensor* Q, nnt_tensor* K, nnt_tensor
     const double pair_flops = 2.0 * g.H * g.Nb * g.Nh;   // per product
     const double pairs = visible_pairs(g.Ns, 0, g.Ns, causal);
     const Access scr{&ctx->red_dep, 1, kReadWrite};
+    const BwdKernel k_dq = dq_kernel(Q->dtype, g.H), k_dkv = dkv_kernel(Q->dtype, g.H);
     // one task, two launches: the dQ kernel leaves log-sum-exp and D per query for the dK/dV kernel
     OpTag tag(ctx, "attention_bwd_dq", 3.0 * pair_flops * pairs, false);
     return submit(ctx, {Q->all(kRead), K->all(kRead), V->all(kRead), B->all(kRead), stats->all(kRead), dB->all(kRead),
                         dQ->all(kWrite), dK->all(kWrite), dV->all(kWrite), scr},
                   [=](hipStream_t st) {
                       const dim3 grid((unsigned)(a.g.Nb * a.g.Nh), (unsigned)(a.g.gs * a.g.nblk)), block(256);
-                      if (a.g.H == 64) hipLaunchKernelGGL(attn_dq_f32<64>, grid, block, 0, st, a);
-                      else hipLaunchKernelGGL(attn_dq_f32<128>, grid, block, 0, st, a);
+                      hipLaunchKernelGGL(k_dq, grid, block, 0, st, a);
                       if (hipGetLastError() != hipSuccess) return (int32_t)NNT_EHIP;
                       profile_mark(ctx, st, "attention_bwd_dkv", 4.0 * pair_flops * pairs, false);
-                      if (a.g.H == 64) hipLaunchKernelGGL(attn_dkv_f32<64>, grid, block, 0, st, a);
-                      else hipLaunchKernelGGL(attn_dkv_f32<128>, grid, block, 0, st, a);
+                      hipLaunchKernelGGL(k_dkv, grid, block, 0, st, a);
                       return hipGetLastError() == hipSuccess ? (int32_t)NNT_OK : (int32_t)NNT_EHIP;
                   }, 2);
 }

@@ -43,10 +43,10 @@ CASES = [
 
 @pytest.mark.parametrize("gran", [0, 1])
 @pytest.mark.parametrize("causal", [1, 0])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("case", CASES, ids=lambda c: "x".join(map(str, c[0])) + "-t%d" % c[1])
-def test_fused_attention_f32(mods, case, causal, gran):
+def test_fused_attention(mods, case, dtype, causal, gran):
     capi, tiled = mods
-    dtype = "f32"
     shape, ts, tb, th = case
     h, N_s, N_b, N_h = shape
     r = np.random.default_rng(hash((shape, ts, causal)) % (2 ** 31))
