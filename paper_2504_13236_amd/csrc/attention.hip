@@ -572,6 +572,8 @@ __global__ void __launch_bounds__(256, 2) attn_dkv(const BwdArgs a) {
             const int sub0 = (g.causal && qglob0 + 31 < wave_kfirst) ? 1 : 0;
             const int nsub = qloc0 + 32 < ext_q ? 2 : 1;
             const bool plain = qloc0 + kBlk <= ext_q && (!g.causal || wave_klast <= qglob0);
+            // (not unrolled: the second pass would keep a second set of temporaries alive and spill)
+#pragma unroll 1
             for (int sub = sub0; sub < nsub; sub++) {
                 f32x16 s = zero16(), dp = zero16();
                 X::template rows_times_own<LD>(s, Qs, sub, ln, hh, kf);

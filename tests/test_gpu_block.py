@@ -150,6 +150,16 @@ def test_block_bf16_small(mods, gran):
     compare(got, ref, "bf16", True)
 
 
+@pytest.mark.parametrize("gran", [0, 1])
+def test_block_bf16_small_fused_attention(mods, gran):
+    capi, tiled = mods
+    cfg = small_bf16_cfg()
+    inp = workload.generate(cfg)
+    ref = oracle_run(cfg, inp, True)
+    got = gpu_run(tiled, cfg, inp, workload.base_tiles(cfg), True, gran=gran, fused=True)
+    compare(got, ref, "bf16", True)
+
+
 def test_block_bf16_ragged_tiles(mods):
     # C4's recipe scaled down: tile 100 against N_e = 200 (head size 40 crosses tile edges), sequence 100 + 100 + 56
     capi, tiled = mods
@@ -191,6 +201,27 @@ def test_block_C3_full_size_bf16(mods):
     print("C3 max-norm relative errors:", {k: "%.2e" % v for k, v in errs.items()})
 
 
+def test_block_C3_full_size_bf16_fused_attention(mods):
+    capi, tiled = mods
+    cfg = workload.CONFIGS[3]
+    inp = workload.generate(cfg)
+    ref = oracle_run(cfg, inp, True)
+    got = gpu_run(tiled, cfg, inp, workload.base_tiles(cfg), True, fused=True)
+    errs = compare(got, ref, "bf16", True)
+    print("C3 (fused attention) max-norm relative errors:", {k: "%.2e" % v for k, v in errs.items()})
+
+
+def test_block_C4_full_size_bf16_ragged_fused_attention(mods):
+    """Sequence tiles 400 + 400 + 224: workgroup blocks of 128 and streamed blocks of 64 rows end inside every tile."""
+    capi, tiled = mods
+    cfg = workload.CONFIGS[4]
+    inp = workload.generate(cfg)
+    ref = oracle_run(cfg, inp, False)
+    got = gpu_run(tiled, cfg, inp, workload.base_tiles(cfg), False, fused=True)
+    errs = compare(got, ref, "bf16", False)
+    print("C4 (fused attention) max-norm relative errors:", {k: "%.2e" % v for k, v in errs.items()})
+
+
 def test_block_C4_full_size_bf16_ragged(mods):
     """GPT-2-XL shape: tile 400 against 1600 / 6400 / 1024 (sequence tiles 400 + 400 + 224, head size 64 crossing tile edges)."""
     capi, tiled = mods
@@ -202,7 +233,8 @@ def test_block_C4_full_size_bf16_ragged(mods):
     print("C4 max-norm relative errors:", {k: "%.2e" % v for k, v in errs.items()})
 
 
-def test_block_C5_one_batch_member_bf16(mods):
+@pytest.mark.parametrize("fused", [False, True], ids=["tiles", "fused"])
+def test_block_C5_one_batch_member_bf16(mods, fused):
     """The 50B-class block (N_e = 8192, head size 128, tile 1024) on one of its four batch members: batch
     members are independent except for the parameter-gradient sums, and the full batch would take the
     fp64 oracle several minutes."""
@@ -210,6 +242,6 @@ def test_block_C5_one_batch_member_bf16(mods):
     cfg = workload.CONFIGS[5].replace(N_b=1)
     inp = workload.generate(cfg)
     ref = oracle_run(cfg, inp, True)
-    got = gpu_run(tiled, cfg, inp, workload.base_tiles(cfg), True)
+    got = gpu_run(tiled, cfg, inp, workload.base_tiles(cfg), True, fused=fused)
     errs = compare(got, ref, "bf16", True)
-    print("C5 (N_b=1) max-norm relative errors:", {k: "%.2e" % v for k, v in errs.items()})
+    print("C5 (N_b=1%s) max-norm relative errors:" % (", fused attention" if fused else ""), {k: "%.2e" % v for k, v in errs.items()})
