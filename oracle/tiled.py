@@ -278,6 +278,62 @@ def softmax_bwd(P, dP):
 
 
 # --------------------------------------------------------------------------
+# attention without the stored scores: the SoftMax subroutines' running column
+# statistics carried along the key tiles (section 3, SoftMax and attention layer)
+# --------------------------------------------------------------------------
+def attention_fwd_online(Q, K, V, key_tile, causal=True):
+    """Q, K, V: arrays [h, N_s, N_b, N_h].  Walks the keys `key_tile` at a time; after
+    each tile the running maximum m, the running sum of shifted exponentials d and
+    the unnormalised result are those of the keys seen so far.  Returns
+    (B, m, d) with B[i, q, b, j], m and d [q, b, j]."""
+    Q, K, V = (np.asarray(x, F64) for x in (Q, K, V))
+    h, N_s, N_b, N_h = Q.shape
+    sc = 1.0 / np.sqrt(h)
+    m = np.full((N_s, N_b, N_h), -np.inf)
+    d = np.zeros((N_s, N_b, N_h))
+    acc = np.zeros((h, N_s, N_b, N_h))
+    for k0 in range(0, N_s, key_tile):
+        k1 = min(N_s, k0 + key_tile)
+        A = sc * np.einsum("ikbj,iqbj->kqbj", K[:, k0:k1], Q)             # scores of this key tile
+        if causal:
+            vis = (k0 + np.arange(k1 - k0))[:, None] <= np.arange(N_s)[None, :]
+            A = np.where(vis[:, :, None, None], A, -np.inf)
+        m_t = A.max(axis=0)
+        m_new = np.maximum(m, m_t)
+        ref = np.where(np.isfinite(m_new), m_new, 0.0)                     # columns that have seen no key yet
+        E = np.exp(A - ref)                                                # masked entries: exp(-inf) = 0
+        alpha = np.exp(np.where(np.isfinite(m), m - ref, -np.inf))         # rescales what earlier tiles left
+        d = d * alpha + E.sum(axis=0)
+        acc = acc * alpha + np.einsum("ikbj,kqbj->iqbj", V[:, k0:k1], E)
+        m = m_new
+    return acc / d, m, d
+
+
+def attention_bwd_recompute(Q, K, V, B, m, d, dB, query_tile, causal=True):
+    """The adjoint from (Q, K, V, B, running statistics, dB), the probabilities
+    recomputed query tile by query tile: P = exp(A - m) / d,
+    D[q] = sum_i dB[i, q] B[i, q], dA = P o (V^T dB - D)."""
+    Q, K, V, B, dB = (np.asarray(x, F64) for x in (Q, K, V, B, dB))
+    h, N_s, N_b, N_h = Q.shape
+    sc = 1.0 / np.sqrt(h)
+    dQ, dK, dV = np.zeros_like(Q), np.zeros_like(K), np.zeros_like(V)
+    Dq = (dB * B).sum(axis=0)
+    for q0 in range(0, N_s, query_tile):
+        q1 = min(N_s, q0 + query_tile)
+        A = sc * np.einsum("ikbj,iqbj->kqbj", K, Q[:, q0:q1])
+        if causal:
+            vis = np.arange(N_s)[:, None] <= (q0 + np.arange(q1 - q0))[None, :]
+            A = np.where(vis[:, :, None, None], A, -np.inf)
+        P = np.exp(A - m[q0:q1]) / d[q0:q1]
+        dV += np.einsum("iqbj,kqbj->ikbj", dB[:, q0:q1], P)
+        dP = np.einsum("ikbj,iqbj->kqbj", V, dB[:, q0:q1])
+        dA = P * (dP - Dq[q0:q1])
+        dQ[:, q0:q1] = sc * np.einsum("ikbj,kqbj->iqbj", K, dA)
+        dK += sc * np.einsum("iqbj,kqbj->ikbj", Q[:, q0:q1], dA)
+    return dQ, dK, dV
+
+
+# --------------------------------------------------------------------------
 # head split / merge: pure data movement between two tilings
 # --------------------------------------------------------------------------
 def split_heads(Z, N_h, n_parts, base4):

@@ -281,6 +281,57 @@ def test_attention_vs_torch_sdpa():
     np.testing.assert_allclose(Bo, ref.numpy().transpose(3, 2, 0, 1), rtol=1e-11, atol=1e-13)
 
 
+def test_attention_bwd_finite_differences_and_torch():
+    """The attention adjoint on its own: central differences of sum(B o G), and autograd of the library routine."""
+    Q, K, V = _qkv(h=5, N_s=6, N_b=2, N_h=2)
+    G = rng.standard_normal(Q.shape)
+    Bo, P = D.attention_fwd(Q, K, V, causal=True)
+    dQ, dK, dV = D.attention_bwd(Q, K, V, P, G)
+    eps = 1e-6
+    for T, dT in ((Q, dQ), (K, dK), (V, dV)):
+        for _ in range(6):
+            idx = tuple(int(rng.integers(0, n)) for n in T.shape)
+            Tp, Tm = T.copy(), T.copy()
+            Tp[idx] += eps
+            Tm[idx] -= eps
+            args_p = [Tp if X is T else X for X in (Q, K, V)]
+            args_m = [Tm if X is T else X for X in (Q, K, V)]
+            fd = ((D.attention_fwd(*args_p, causal=True)[0] - D.attention_fwd(*args_m, causal=True)[0]) * G).sum() / (2 * eps)
+            assert abs(fd - dT[idx]) < 1e-7 * max(1.0, abs(fd))
+    tq, tk, tv = [torch.from_numpy(T.transpose(2, 3, 1, 0).copy()).requires_grad_(True) for T in (Q, K, V)]   # [b, j, s, i]
+    out = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, is_causal=True)
+    out.backward(torch.from_numpy(G.transpose(2, 3, 1, 0).copy()))
+    for t, dT in ((tq, dQ), (tk, dK), (tv, dV)):
+        np.testing.assert_allclose(dT, t.grad.numpy().transpose(3, 2, 0, 1), rtol=1e-10, atol=1e-12)
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_attention_online_form_equals_definition(causal):
+    """Walking the key tiles with running (maximum, sum of shifted exponentials) gives the definition's
+    result and statistics for any key tile, and the adjoint recomputed from those statistics is the
+    definition's adjoint for any query tile."""
+    from oracle import tiled as TL
+    Q, K, V = _qkv(h=6, N_s=11, N_b=2, N_h=2)
+    G = rng.standard_normal(Q.shape)
+    Bo, P = D.attention_fwd(Q, K, V, causal=causal)
+    _, tmax, den = D.softmax_fwd(D.attention_scores(K, Q), causal)
+    dQ, dK, dV = D.attention_bwd(Q, K, V, P, G)
+    for tile in (1, 3, 4, 11, 16):
+        B2, m, d = TL.attention_fwd_online(Q, K, V, tile, causal)
+        np.testing.assert_allclose(B2, Bo, rtol=1e-12, atol=1e-14)
+        np.testing.assert_allclose(m, tmax, rtol=1e-13, atol=1e-15)
+        np.testing.assert_allclose(d, den, rtol=1e-12)
+        g = TL.attention_bwd_recompute(Q, K, V, B2, m, d, G, tile, causal)
+        for got, want in zip(g, (dQ, dK, dV)):
+            np.testing.assert_allclose(got, want, rtol=1e-11, atol=1e-13)
+    # a large shift of all scores of one column moves the maximum, not the result (the rescaling is exact)
+    K2 = K.copy()
+    K2[:, 0] *= 40.0
+    B3, m3, d3 = TL.attention_fwd_online(Q, K2, V, 2, causal)
+    np.testing.assert_allclose(B3, D.attention_fwd(Q, K2, V, causal=causal)[0], rtol=1e-11, atol=1e-13)
+    assert np.all(np.isfinite(B3)) and np.all(d3 >= 1.0 - 1e-12)
+
+
 # ------------------------------------------------------------------ Adam
 def test_adam_golden_two_steps():
     rows = [l.split() for l in open(os.path.join(GOLD, "adam_two_steps.txt")) if not l.startswith("#")]
