@@ -320,7 +320,7 @@ NNT_API int32_t nnt_head_merge(nnt_ctx* ctx, int32_t n_parts, nnt_tensor* const*
  * exponentials) along instead of storing the N_s x N_s scores:
  *   B[i,q,b,j] = sum_k V[i,k,b,j] P[k,q,b,j],
  *   P[.,q,b,j] = softmax over k of scale * sum_i K[i,k,b,j] Q[i,q,b,j],
- * with causal != 0 over the keys k <= q only.  Q, K, V, B: [h, N_s, N_b, N_h]
+ * with causal != 0 over the keys k <= q only; scale > 0.  Q, K, V, B: [h, N_s, N_b, N_h]
  * tensors of one dtype (fp32 or bf16), tiled alike, first axis untiled, h = 64 or
  * 128, every tile present and 16-byte aligned; stats: fp32 [2, N_s, N_b, N_h]
  * tiled like their other axes, overwritten with the final (maximum of the scaled

@@ -34,7 +34,6 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 constexpr int kWgRows = 128;   // rows owned by a workgroup
 constexpr int kBlk = 64;       // rows streamed per iteration
 constexpr float kLog2e = 1.4426950408889634f;
-constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kNegInf = -__builtin_huge_valf();
 
 // The tensors of one call: all are (H, N_s, N_b, N_h), tiled alike along the last three axes.
@@ -55,14 +54,25 @@ struct Slab {
     int ext;       // extent of the tile along the sequence axis
 };
 
-// where the rows of (batch b, head j) of sequence tile l live; `off` counts rows of the slab's first axis
-__device__ __forceinline__ Slab slab_of(const AttnGeom& g, int l, int b, int j) {
+// The part of a slab lookup that depends on (batch b, head j) only.
+struct Pair {
+    int tile;      // tile number of sequence tile 0 for this pair
+    int rows;      // (b, j)'s position among the pairs of its tile: its slab starts rows * ext rows into the tile
+};
+__device__ __forceinline__ Pair pair_of(const AttnGeom& g, int b, int j) {
     const int tb = b / g.bb, tj = j / g.bh;
+    const int eb = min(g.bb, g.Nb - tb * g.bb);
+    Pair p;
+    p.tile = g.gs * (tb + g.gb * tj);
+    p.rows = (b - tb * g.bb) + eb * (j - tj * g.bh);
+    return p;
+}
+// where the rows of that pair in sequence tile l live; `off` counts rows of the slab's first axis
+__device__ __forceinline__ Slab slab_of(const AttnGeom& g, const Pair& p, int l) {
     Slab s;
     s.ext = min(g.bs, g.Ns - l * g.bs);
-    const int eb = min(g.bb, g.Nb - tb * g.bb);
-    s.tile = l + g.gs * (tb + g.gb * tj);
-    s.off = (int64_t)s.ext * ((b - tb * g.bb) + (int64_t)eb * (j - tj * g.bh));
+    s.tile = l + p.tile;
+    s.off = (int64_t)s.ext * p.rows;
     return s;
 }
 
@@ -130,10 +140,12 @@ template <int H_> struct F32Traits {
         return d;
     }
     template <int LDX>
-    static __device__ __forceinline__ void rows_times_own(f32x16& acc, const T* lds, int sub, int ln, int hh, const Own& o) {
+    static __device__ __forceinline__ f32x16 rows_times_own(const T* lds, int sub, int ln, int hh, const Own& o) {
         const T* p = lds + (32 * sub + ln) * LDX + (H / 2) * hh;
+        f32x16 acc = __builtin_amdgcn_mfma_f32_32x32x2f32(p[0], o.v[0], zero16(), 0, 0, 0);
 #pragma unroll
-        for (int k = 0; k < H / 2; k++) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(p[k], o.v[k], acc, 0, 0, 0);
+        for (int k = 1; k < H / 2; k++) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(p[k], o.v[k], acc, 0, 0, 0);
+        return acc;
     }
     static __device__ __forceinline__ void pack(const f32x16& x, Packed& pk) { pk.v = x; }
     template <int LDX>
@@ -191,11 +203,13 @@ template <int H_> struct Bf16Traits {
         return d;
     }
     template <int LDX>
-    static __device__ __forceinline__ void rows_times_own(f32x16& acc, const T* lds, int sub, int ln, int hh, const Own& o) {
+    static __device__ __forceinline__ f32x16 rows_times_own(const T* lds, int sub, int ln, int hh, const Own& o) {
         const T* p = lds + (32 * sub + ln) * LDX + 8 * hh;
+        f32x16 acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(p), o.v[0], zero16(), 0, 0, 0);
 #pragma unroll
-        for (int s = 0; s < H / 16; s++)
+        for (int s = 1; s < H / 16; s++)
             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(p + 16 * s), o.v[s], acc, 0, 0, 0);
+        return acc;
     }
     static __device__ __forceinline__ void pack(const f32x16& x, Packed& pk) {
 #pragma unroll
@@ -288,7 +302,8 @@ __global__ void __launch_bounds__(256, 2) attn_fwd(const FwdArgs a) {
     const int rblk = g.causal ? gridDim.y - 1 - blockIdx.y : blockIdx.y;
     const int l = g.tile0 + rblk / g.nblk, e0 = (rblk % g.nblk) * kWgRows;
     const int b = blockIdx.x % g.Nb, j = blockIdx.x / g.Nb;
-    const Slab sq = slab_of(g, l, b, j);
+    const Pair pr = pair_of(g, b, j);
+    const Slab sq = slab_of(g, pr, l);
     if (e0 >= sq.ext) return;
     const int eq = e0 + 32 * w + ln;
     const bool qvalid = eq < sq.ext;
@@ -313,7 +328,7 @@ __global__ void __launch_bounds__(256, 2) attn_fwd(const FwdArgs a) {
     typename X::Vec kr[X::kVec], vr[X::kVec];
     auto fetch = [&](int it) {
         const int lk = it / g.nstep, k0 = (it % g.nstep) * kBlk;
-        const Slab sk = slab_of(g, lk, b, j);
+        const Slab sk = slab_of(g, pr, lk);
         load_block<X>(rows_of<const T>(a.K, sk, H), k0, sk.ext, tid, kr);
         load_block<X>(rows_of<const T>(a.V, sk, H), k0, sk.ext, tid, vr);
     };
@@ -335,18 +350,17 @@ __global__ void __launch_bounds__(256, 2) attn_fwd(const FwdArgs a) {
             // the second half of the block may be hidden from all of this wave's queries
             const bool two = !(g.causal && kglob0 + 32 > wave_qlast) && kloc0 + 32 < ext_k;
             const bool plain = kloc0 + kBlk <= ext_k && (!g.causal || kglob0 + kBlk - 1 <= wave_qfirst);
-            f32x16 s[2] = {zero16(), zero16()};
-            X::template rows_times_own<LDK>(s[0], Ks, 0, ln, hh, qf);
-            if (two) X::template rows_times_own<LDK>(s[1], Ks, 1, ln, hh, qf);
+            f32x16 s[2];
+            s[0] = X::template rows_times_own<LDK>(Ks, 0, ln, hh, qf);
+            if (two) s[1] = X::template rows_times_own<LDK>(Ks, 1, ln, hh, qf);
+            else s[1] = s[0];                       // masked below
+            // the running maximum is kept in units of the raw scores (scale > 0 keeps the order)
             float mx = kNegInf;
             if (plain) {
 #pragma unroll
                 for (int sub = 0; sub < 2; sub++)
 #pragma unroll
-                    for (int r = 0; r < 16; r++) {
-                        s[sub][r] *= sc2;
-                        mx = fmaxf(mx, s[sub][r]);
-                    }
+                    for (int r = 0; r < 16; r++) mx = fmaxf(mx, s[sub][r]);
             } else {
 #pragma unroll
                 for (int sub = 0; sub < 2; sub++)
@@ -354,28 +368,30 @@ __global__ void __launch_bounds__(256, 2) attn_fwd(const FwdArgs a) {
                     for (int r = 0; r < 16; r++) {
                         const int kl = 32 * sub + acc_row(r, hh);
                         const bool ok = kloc0 + kl < ext_k && (!g.causal || kglob0 + kl <= qglob) && (sub == 0 || two);
-                        s[sub][r] = ok ? s[sub][r] * sc2 : kNegInf;
+                        s[sub][r] = ok ? s[sub][r] : kNegInf;
                         mx = fmaxf(mx, s[sub][r]);
                     }
             }
             mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
             const float m_new = fmaxf(m, mx);
-            const float shift = m_new == kNegInf ? 0.f : m_new;
-            const float alpha = m == m_new ? 1.f : __builtin_amdgcn_exp2f(m - shift);
+            const float shift = m_new == kNegInf ? 0.f : m_new * sc2;
+            const float alpha = m == m_new ? 1.f : __builtin_amdgcn_exp2f(m * sc2 - shift);
             m = m_new;
             float rowsum = 0.f;
 #pragma unroll
             for (int sub = 0; sub < 2; sub++)
 #pragma unroll
                 for (int r = 0; r < 16; r++) {
-                    s[sub][r] = __builtin_amdgcn_exp2f(s[sub][r] - shift);
+                    s[sub][r] = __builtin_amdgcn_exp2f(fmaf(s[sub][r], sc2, -shift));
                     rowsum += s[sub][r];
                 }
             lsum = lsum * alpha + rowsum;
+            if (__any(alpha != 1.f)) {              // after the first blocks the maxima seldom move
 #pragma unroll
-            for (int rb = 0; rb < H / 32; rb++)
+                for (int rb = 0; rb < H / 32; rb++)
 #pragma unroll
-                for (int r = 0; r < 16; r++) O[rb][r] *= alpha;
+                    for (int r = 0; r < 16; r++) O[rb][r] *= alpha;
+            }
             typename X::Packed pk;
             X::pack(s[0], pk);
             X::template cols_times_acc<LDV>(O, Vs, 0, lane, pk);
@@ -391,7 +407,7 @@ __global__ void __launch_bounds__(256, 2) attn_fwd(const FwdArgs a) {
     store_own_row<X>(rows_of<T>(a.O, sq, H), eq, hh, qvalid, 1.f / lsum, O);
     if (qvalid && hh == 0) {
         float* st = rows_of<float>(a.stats, sq, 2) + 2 * (int64_t)eq;
-        st[0] = m * kLn2;
+        st[0] = m * g.scale;
         st[1] = lsum;
     }
 }
@@ -414,7 +430,8 @@ __global__ void __launch_bounds__(256, 2) attn_dq(const BwdArgs a) {
     const int rblk = g.causal ? gridDim.y - 1 - blockIdx.y : blockIdx.y;
     const int l = g.tile0 + rblk / g.nblk, e0 = (rblk % g.nblk) * kWgRows;
     const int b = blockIdx.x % g.Nb, j = blockIdx.x / g.Nb;
-    const Slab sq = slab_of(g, l, b, j);
+    const Pair pr = pair_of(g, b, j);
+    const Slab sq = slab_of(g, pr, l);
     if (e0 >= sq.ext) return;
     const int eq = e0 + 32 * w + ln;
     const bool qvalid = eq < sq.ext;
@@ -455,7 +472,7 @@ __global__ void __launch_bounds__(256, 2) attn_dq(const BwdArgs a) {
     typename X::Vec kr[X::kVec], vr[X::kVec];
     auto fetch = [&](int it) {
         const int lk = it / g.nstep, k0 = (it % g.nstep) * kBlk;
-        const Slab sk = slab_of(g, lk, b, j);
+        const Slab sk = slab_of(g, pr, lk);
         load_block<X>(rows_of<const T>(a.K, sk, H), k0, sk.ext, tid, kr);
         load_block<X>(rows_of<const T>(a.V, sk, H), k0, sk.ext, tid, vr);
     };
@@ -477,9 +494,8 @@ __global__ void __launch_bounds__(256, 2) attn_dq(const BwdArgs a) {
             const int nsub = (!(g.causal && kglob0 + 32 > wave_qlast) && kloc0 + 32 < ext_k) ? 2 : 1;
             const bool plain = kloc0 + kBlk <= ext_k && (!g.causal || kglob0 + kBlk - 1 <= wave_qfirst);
             for (int sub = 0; sub < nsub; sub++) {
-                f32x16 s = zero16(), dp = zero16();
-                X::template rows_times_own<LD>(s, Ks, sub, ln, hh, qf);
-                X::template rows_times_own<LD>(dp, Vs, sub, ln, hh, dof);
+                f32x16 s = X::template rows_times_own<LD>(Ks, sub, ln, hh, qf);
+                const f32x16 dp = X::template rows_times_own<LD>(Vs, sub, ln, hh, dof);
 #pragma unroll
                 for (int r = 0; r < 16; r++) {
                     const int kl = 32 * sub + acc_row(r, hh);
@@ -510,7 +526,8 @@ __global__ void __launch_bounds__(256, 2) attn_dkv(const BwdArgs a) {
     // (under the causal mask the earliest key blocks meet the most query blocks: already first)
     const int l = g.tile0 + blockIdx.y / g.nblk, e0 = (blockIdx.y % g.nblk) * kWgRows;
     const int b = blockIdx.x % g.Nb, j = blockIdx.x / g.Nb;
-    const Slab sk = slab_of(g, l, b, j);
+    const Pair pr = pair_of(g, b, j);
+    const Slab sk = slab_of(g, pr, l);
     if (e0 >= sk.ext) return;
     const int ek = e0 + 32 * w + ln;
     const bool kvalid = ek < sk.ext;
@@ -533,15 +550,15 @@ __global__ void __launch_bounds__(256, 2) attn_dkv(const BwdArgs a) {
 
     typename X::Vec qr[X::kVec], dr[X::kVec];
     float2 ar = make_float2(0.f, 0.f);
+    const float* aux_pair = a.aux + 2 * (int64_t)g.Ns * (b + (int64_t)g.Nb * j);
     auto fetch = [&](int it) {
         const int lq = it / g.nstep, q0 = (it % g.nstep) * kBlk;
-        const Slab sq = slab_of(g, lq, b, j);
+        const Slab sq = slab_of(g, pr, lq);
         load_block<X>(rows_of<const T>(a.Q, sq, H), q0, sq.ext, tid, qr);
         load_block<X>(rows_of<const T>(a.dO, sq, H), q0, sq.ext, tid, dr);
         if (tid < kBlk) {
             const bool ok = q0 + tid < sq.ext;
-            const int64_t qg = (int64_t)lq * g.bs + q0 + tid;
-            ar = ok ? *reinterpret_cast<const float2*>(a.aux + 2 * (qg + (int64_t)g.Ns * (b + (int64_t)g.Nb * j))) : make_float2(0.f, 0.f);
+            ar = ok ? *reinterpret_cast<const float2*>(aux_pair + 2 * (lq * g.bs + q0 + tid)) : make_float2(0.f, 0.f);
         }
     };
     auto stash = [&](int buf) {
@@ -575,9 +592,8 @@ __global__ void __launch_bounds__(256, 2) attn_dkv(const BwdArgs a) {
             // (not unrolled: the second pass would keep a second set of temporaries alive and spill)
 #pragma unroll 1
             for (int sub = sub0; sub < nsub; sub++) {
-                f32x16 s = zero16(), dp = zero16();
-                X::template rows_times_own<LD>(s, Qs, sub, ln, hh, kf);
-                X::template rows_times_own<LD>(dp, Ds, sub, ln, hh, vf);
+                f32x16 s = X::template rows_times_own<LD>(Qs, sub, ln, hh, kf);
+                const f32x16 dp = X::template rows_times_own<LD>(Ds, sub, ln, hh, vf);
                 f32x16 p;
 #pragma unroll
                 for (int r = 0; r < 16; r++) {
@@ -624,7 +640,7 @@ using namespace nnt;
 // ------------------------------------------------------------------ host side
 namespace {
 
-int32_t check_attn(nnt_ctx* ctx, const char* who, std::initializer_list<const nnt_tensor*> ts, const nnt_tensor* stats) {
+int32_t check_attn(nnt_ctx* ctx, const char* who, std::initializer_list<const nnt_tensor*> ts, const nnt_tensor* stats, float scale) {
     const nnt_tensor* first = *ts.begin();
     for (const nnt_tensor* t : ts) {
         if (!t) return fail(ctx, NNT_EINVAL, std::string(who) + ": null tensor");
@@ -639,6 +655,7 @@ int32_t check_attn(nnt_ctx* ctx, const char* who, std::initializer_list<const nn
     if (first->shape[0] != 64 && first->shape[0] != 128)
         return fail(ctx, NNT_EINVAL, std::string(who) + ": head size must be 64 or 128");
     if (!stats) return fail(ctx, NNT_EINVAL, std::string(who) + ": null tensor");
+    if (!(scale > 0.f)) return fail(ctx, NNT_EINVAL, std::string(who) + ": scale must be positive");
     if (stats->dtype != NNT_F32 || stats->ndim != 4 || stats->shape[0] != 2 || stats->base[0] != 2)
         return fail(ctx, NNT_EINVAL, std::string(who) + ": stats must be fp32 (2, N_s, N_b, N_h) with an untiled first axis");
     for (int a = 1; a < 4; a++)
@@ -682,7 +699,7 @@ std::vector<Access> seq_tile(nnt_tensor* t, int64_t l, int mode) {
 int32_t nnt_attention_fwd(nnt_ctx* ctx, nnt_tensor* Q, nnt_tensor* K, nnt_tensor* V, float scale, int32_t causal,
                           nnt_tensor* B, nnt_tensor* stats) {
     NNT_CHECK_CTX(ctx);
-    int32_t rc = check_attn(ctx, "nnt_attention_fwd", {Q, K, V, B}, stats);
+    int32_t rc = check_attn(ctx, "nnt_attention_fwd", {Q, K, V, B}, stats, scale);
     if (rc != NNT_OK) return rc;
     AttnGeom g = geom_of(Q, scale, causal);
     FwdArgs a{g, Q->d_tiles, K->d_tiles, V->d_tiles, B->d_tiles, stats->d_tiles};
@@ -719,7 +736,7 @@ int32_t nnt_attention_fwd(nnt_ctx* ctx, nnt_tensor* Q, nnt_tensor* K, nnt_tensor
 int32_t nnt_attention_bwd(nnt_ctx* ctx, nnt_tensor* Q, nnt_tensor* K, nnt_tensor* V, nnt_tensor* B, nnt_tensor* stats,
                           nnt_tensor* dB, float scale, int32_t causal, nnt_tensor* dQ, nnt_tensor* dK, nnt_tensor* dV) {
     NNT_CHECK_CTX(ctx);
-    int32_t rc = check_attn(ctx, "nnt_attention_bwd", {Q, K, V, B, dB, dQ, dK, dV}, stats);
+    int32_t rc = check_attn(ctx, "nnt_attention_bwd", {Q, K, V, B, dB, dQ, dK, dV}, stats, scale);
     if (rc != NNT_OK) return rc;
     AttnGeom g = geom_of(Q, scale, causal);
     rc = ensure_scratch(ctx, 2 * (int64_t)g.Ns * g.Nb * g.Nh);
