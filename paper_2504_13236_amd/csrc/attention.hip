@@ -148,6 +148,7 @@ template <int H_> struct F32Traits {
         return acc;
     }
     static __device__ __forceinline__ void pack(const f32x16& x, Packed& pk) { pk.v = x; }
+    static __device__ __forceinline__ void set(Packed& pk, int r, float x) { pk.v[r] = x; }
     template <int LDX>
     static __device__ __forceinline__ void cols_times_acc(f32x16 (&out)[H / 32], const T* lds, int sub, int lane, const Packed& pk) {
         const int ln = lane & 31, hh = lane >> 5;
@@ -217,6 +218,7 @@ template <int H_> struct Bf16Traits {
 #pragma unroll
             for (int e = 0; e < 8; e++) pk.v[m][e] = (__bf16)x[8 * m + e];
     }
+    static __device__ __forceinline__ void set(Packed& pk, int r, float x) { pk.v[r / 8][r % 8] = (__bf16)x; }
     template <int LDX>
     static __device__ __forceinline__ void cols_times_acc(f32x16 (&out)[H / 32], const T* lds, int sub, int lane, const Packed& pk) {
         // Accumulator registers 8 m + e of half hh are the rows 16 m + 8 (e / 4) + 4 hh + e % 4: two runs of
@@ -594,16 +596,15 @@ __global__ void __launch_bounds__(256, 2) attn_dkv(const BwdArgs a) {
             for (int sub = sub0; sub < nsub; sub++) {
                 f32x16 s = X::template rows_times_own<LD>(Qs, sub, ln, hh, kf);
                 const f32x16 dp = X::template rows_times_own<LD>(Ds, sub, ln, hh, vf);
-                f32x16 p;
+                typename X::Packed pk;
 #pragma unroll
                 for (int r = 0; r < 16; r++) {
                     const int ql = 32 * sub + acc_row(r, hh);
                     const bool ok = plain || (qloc0 + ql < ext_q && (!g.causal || kglob <= qglob0 + ql));
-                    p[r] = ok ? __builtin_amdgcn_exp2f(s[r] * sc2 - lses[ql]) : 0.f;
-                    s[r] = p[r] * (dp[r] - dsum[ql]);
+                    const float p = ok ? __builtin_amdgcn_exp2f(s[r] * sc2 - lses[ql]) : 0.f;
+                    X::set(pk, r, p);
+                    s[r] = p * (dp[r] - dsum[ql]);
                 }
-                typename X::Packed pk;
-                X::pack(p, pk);
                 X::template cols_times_acc<LD>(dV, Ds, sub, lane, pk);
                 X::pack(s, pk);
                 X::template cols_times_acc<LD>(dK, Qs, sub, lane, pk);
