@@ -138,67 +138,13 @@ def tile_kernels(cfg, capi, torch):
     return out
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=2, help="workload number 1..5 (default: the fp32 GPT-2-small-shaped block)")
-    ap.add_argument("--streams", type=int, default=4)
-    ap.add_argument("--granularity", choices=["op", "tile"], default="op")
-    ap.add_argument("--graph", action="store_true", help="replay the step from a captured HIP graph")
-    ap.add_argument("--attention", choices=["tiles", "fused"], default="tiles",
-                    help="tiles: scores, softmax and the product with V as three operations on the stored N_s x N_s "
-                         "tensor (the paper's flow, the default); fused: one kernel per direction that never stores it")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
-                    help="instead of the benchmark, copy MIB MiB of fp32 a few times with the library's cast kernel "
-                         "(a plain copy kernel of known size, for scaling HBM counters)")
-    ap.add_argument("--cpu-sample-batch", type=int, default=0)
-    ap.add_argument("--tile-kernels", action="store_true",
-                    help="instead of the block benchmark, time single calls of the tile kernels at the config's shapes: "
-                         "products against the MFMA peak, memory-bound kernels against HBM, warm (one buffer set) and "
-                         "cold (rotating over > 512 MB of buffer sets, more than the 256 MB Infinity Cache)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py measures one GPU: this build has no multi-GPU path (--gpus %d refused)" % args.gpus, file=sys.stderr)
-        sys.exit(2)
-
-    import torch
-    import workload
-    from paper_2504_13236_amd import capi, tiled
-
-    if not torch.cuda.is_available():
-        print("bench.py needs a GPU: the HIP library is the only execution path", file=sys.stderr)
-        sys.exit(3)
-    if args.copy_calibration:
-        n = args.copy_calibration * (1 << 20) // 4
-        src = torch.ones(n, dtype=torch.float32, device="cuda")
-        dst = torch.empty_like(src)
-        st = torch.cuda.current_stream().cuda_stream
-        for _ in range(3):
-            capi.nnt_tile_cast(st, capi.NNT_F32, capi.NNT_F32, n, src.data_ptr(), dst.data_ptr())
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(5):
-            capi.nnt_tile_cast(st, capi.NNT_F32, capi.NNT_F32, n, src.data_ptr(), dst.data_ptr())
-        e1.record()
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / 5
-        print(json.dumps({"copy_calibration": {"bytes_read": 4 * n, "bytes_written": 4 * n, "launches": 8, "ms": ms,
-                                               "GB/s": 8.0 * n / ms / 1e6,
-                                               "kernel": "ew_kernel<CastF<float, float>>"}}))
-        return
-    if args.tile_kernels:
-        print(json.dumps({"tile_kernels": tile_kernels(workload.CONFIGS[args.config], capi, torch)}))
-        return
-    cfg = workload.CONFIGS[args.config]
-    inp = workload.generate(cfg)
+def measure(args, cfg, inp, attention, capi, tiled, torch, workload):
+    """Times K steps of the block (forward + backward [+ Adam]) with the given attention flow and
+    returns the bench record."""
     gran = capi.NNT_GRAN_OP if args.granularity == "op" else capi.NNT_GRAN_TILE
     ctx = tiled.Context(n_streams=args.streams, granularity=gran)
     blk = tiled.Gpt2Block(ctx, cfg.N_e, cfg.N_h, cfg.N_m, cfg.N_s, cfg.N_b, workload.base_tiles(cfg), dtype=cfg.dtype,
-                          eps=cfg.eps, gelu=cfg.gelu, adam=cfg.adam, fused_attention=args.attention == "fused")
+                          eps=cfg.eps, gelu=cfg.gelu, adam=cfg.adam, fused_attention=attention == "fused")
     blk.set_params({k: inp[k] for k in workload.PARAM_NAMES})
     X, dOut = blk.activation(inp["X"]), blk.activation(inp["dOut"])
     Out, dX = blk.activation(), blk.activation()
@@ -245,7 +191,7 @@ def main():
     ctx.profile(False)
     ctx.set_serial(False)
     ms_per_step = dt / args.steps * 1e3
-    flops = workload.model_flops(cfg, tile_skip=True, visible_only=args.attention == "fused")
+    flops = workload.model_flops(cfg, tile_skip=True, visible_only=attention == "fused")
     value = flops / (dt / args.steps) / 1e12
 
     # per-operation figures from the executor's event pairs
@@ -308,17 +254,84 @@ def main():
                                   % (cfg.name, cfg.dtype, cfg.N_e, cfg.N_h, cfg.N_m, cfg.N_s, cfg.N_b, cfg.tile,
                                      "+Adam" if cfg.adam else ""),
                       "streams": args.streams, "granularity": args.granularity, "graph_replay": bool(args.graph),
-                      "attention": args.attention,
+                      "attention": attention,
                       "flops_per_step": flops,
-                      "attention_flops": "visible (key, query) pairs only, no recomputation" if args.attention == "fused"
+                      "attention_flops": "visible (key, query) pairs only, no recomputation" if attention == "fused"
                                          else "computed sequence-tile pairs only"},
            "roofline": roofline, "summary": summary, "kernels": kernels, "executor": ctx.stats()}
+    blk.close()
+    ctx.close()
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=2, help="workload number 1..5 (default: the fp32 GPT-2-small-shaped block)")
+    ap.add_argument("--streams", type=int, default=4)
+    ap.add_argument("--granularity", choices=["op", "tile"], default="op")
+    ap.add_argument("--graph", action="store_true", help="replay the step from a captured HIP graph")
+    ap.add_argument("--attention", choices=["tiles", "fused"], default="tiles",
+                    help="tiles: scores, softmax and the product with V as three operations on the stored N_s x N_s "
+                         "tensor (the paper's flow, the default); fused: one kernel per direction that never stores it")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-next-rows", action="store_true", help="skip the extra pass with the fused attention kernels")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
+                    help="instead of the benchmark, copy MIB MiB of fp32 a few times with the library's cast kernel "
+                         "(a plain copy kernel of known size, for scaling HBM counters)")
+    ap.add_argument("--cpu-sample-batch", type=int, default=0)
+    ap.add_argument("--tile-kernels", action="store_true",
+                    help="instead of the block benchmark, time single calls of the tile kernels at the config's shapes: "
+                         "products against the MFMA peak, memory-bound kernels against HBM, warm (one buffer set) and "
+                         "cold (rotating over > 512 MB of buffer sets, more than the 256 MB Infinity Cache)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (--gpus %d refused)" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import workload
+    from paper_2504_13236_amd import capi, tiled
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU: the HIP library is the only execution path", file=sys.stderr)
+        sys.exit(3)
+    if args.copy_calibration:
+        n = args.copy_calibration * (1 << 20) // 4
+        src = torch.ones(n, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        st = torch.cuda.current_stream().cuda_stream
+        for _ in range(3):
+            capi.nnt_tile_cast(st, capi.NNT_F32, capi.NNT_F32, n, src.data_ptr(), dst.data_ptr())
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            capi.nnt_tile_cast(st, capi.NNT_F32, capi.NNT_F32, n, src.data_ptr(), dst.data_ptr())
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 5
+        print(json.dumps({"copy_calibration": {"bytes_read": 4 * n, "bytes_written": 4 * n, "launches": 8, "ms": ms,
+                                               "GB/s": 8.0 * n / ms / 1e6,
+                                               "kernel": "ew_kernel<CastF<float, float>>"}}))
+        return
+    if args.tile_kernels:
+        print(json.dumps({"tile_kernels": tile_kernels(workload.CONFIGS[args.config], capi, torch)}))
+        return
+    cfg = workload.CONFIGS[args.config]
+    inp = workload.generate(cfg)
+    out = measure(args, cfg, inp, args.attention, capi, tiled, torch, workload)
+    if args.attention == "tiles" and cfg.h in (64, 128) and not args.no_next_rows:
+        # the first of the "next" rows beside the headline: the same block with the fused attention kernels
+        f = measure(args, cfg, inp, "fused", capi, tiled, torch, workload)
+        out["next_rows"] = {"fused_attention": {k: f[k] for k in ("value", "unit", "ms_per_step", "config", "summary")}}
+        out["next_rows"]["fused_attention"]["kernels"] = {k: v for k, v in f["kernels"].items() if k.startswith("attention")}
     if not args.no_cpu_baseline:
         # the whole workload takes the oracle a few seconds up to C4; C5 is sampled on one batch member
         sb = args.cpu_sample_batch or (cfg.N_b if args.config <= 4 else 1)
         out["cpu_baseline"] = cpu_baseline(cfg, sb)
-    blk.close()
-    ctx.close()
     print(json.dumps(out))
 
 
