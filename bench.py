@@ -134,6 +134,8 @@ def tile_kernels(cfg, capi, torch):
     a = workload.ADAM
     report("adam (fp32 p, g, m, v)", 28, lambda i: capi.nnt_tile_adam(st, n_el, 1, a["lr"], a["beta1"], a["beta2"], a["eps"], a["weight_decay"],
                                                                     pa[i][0].data_ptr(), pa[i][1].data_ptr(), pa[i][2].data_ptr(), pa[i][3].data_ptr(), None), nsets)
+    report("sgd with momentum (fp32 p, g, v)", 20, lambda i: capi.nnt_tile_sgd(st, n_el, 0.05, 0.9, 0.0, 0, pa[i][1].data_ptr(), pa[i][0].data_ptr(),
+                                                                                pa[i][2].data_ptr(), None), nsets)
     del pa
     return out
 

@@ -268,6 +268,10 @@ NNT_API int32_t nnt_tile_softmax_bwd_apply(void* stream, int32_t dtype, int64_t 
 NNT_API int32_t nnt_tile_adam(void* stream, int64_t n, int32_t step, double lr, double beta1, double beta2,
                       double eps, double weight_decay, const float* g, float* p, float* m, float* v,
                       void* p_lowp);
+/* One tile of the SGD-with-momentum step (formulas at nnt_sgd_step); n fp32
+ * elements of g, p, v; p_lowp: bf16 copy of the new p, or NULL. */
+NNT_API int32_t nnt_tile_sgd(void* stream, int64_t n, double lr, double momentum, double weight_decay,
+                     int32_t nesterov, const float* g, float* p, float* v, void* p_lowp);
 
 /* ------------------------------------------------------------------------- */
 /* Tensor-level operations: walk the tile grid and submit tasks.               */
@@ -349,6 +353,19 @@ typedef struct nnt_adam_cfg {
 NNT_API int32_t nnt_adam_step(nnt_ctx* ctx, const nnt_adam_cfg* cfg, int32_t step, nnt_tensor* G, nnt_tensor* P,
                       nnt_tensor* M, nnt_tensor* V, nnt_tensor* P_lowp);
 
+/* SGD with momentum (section 3, Optimizers: the update is a weighted sum of the
+ * parameter, the gradient and the momentum term):
+ *   g' = g + weight_decay * p;  v <- momentum * v + g';
+ *   p <- p - lr * v            (nesterov != 0:  p <- p - lr * (g' + momentum * v)).
+ * With v = 0 before the first step this is the usual first step v = g'.
+ * G, P, V: fp32 tensors tiled alike; P_lowp: bf16 tensor tiled alike or NULL. */
+typedef struct nnt_sgd_cfg {
+    double lr, momentum, weight_decay;
+    int32_t nesterov;
+} nnt_sgd_cfg;
+NNT_API int32_t nnt_sgd_step(nnt_ctx* ctx, const nnt_sgd_cfg* cfg, nnt_tensor* G, nnt_tensor* P, nnt_tensor* V,
+                     nnt_tensor* P_lowp);
+
 /* ------------------------------------------------------------------------- */
 /* One GPT-2 block (pre-LN, biases on all four linear layers, causal attention, */
 /* no dropout): forward, backward and Adam as a flow of the tasks above.        */
@@ -412,6 +429,9 @@ NNT_API int32_t nnt_gpt2_block_forward(nnt_gpt2_block* blk, nnt_tensor* X, nnt_t
 NNT_API int32_t nnt_gpt2_block_backward(nnt_gpt2_block* blk, nnt_tensor* dOut, nnt_tensor* dX);
 /* Adam step on all 12 parameters; bf16 blocks also refresh the bf16 weight copies. */
 NNT_API int32_t nnt_gpt2_block_adam(nnt_gpt2_block* blk, int32_t step, const nnt_adam_cfg* cfg);
+/* SGD-with-momentum step on all 12 parameters; the velocities live in the slots
+ * NNT_BLK_ADAM_M + parameter (the second-moment slots are not touched). */
+NNT_API int32_t nnt_gpt2_block_sgd(nnt_gpt2_block* blk, const nnt_sgd_cfg* cfg);
 /* bf16 blocks: (re)make the bf16 weight copies from the fp32 masters. */
 NNT_API int32_t nnt_gpt2_block_sync_lowp(nnt_gpt2_block* blk);
 

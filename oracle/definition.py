@@ -309,6 +309,18 @@ def adam_step(p, g, m, v, t, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_d
 # --------------------------------------------------------------------------
 # bf16 storage rounding (round to nearest, ties to even, on the fp32 bit pattern)
 # --------------------------------------------------------------------------
+def sgd_step(p, g, v, lr=1e-2, momentum=0.9, weight_decay=0.0, nesterov=False):
+    """SGD with momentum (section 3, Optimizers: a weighted sum of parameter, gradient and momentum
+    term): g' = g + weight_decay p, v <- momentum v + g', p <- p - lr v; with `nesterov` the step
+    direction is g' + momentum v.  Zero v before the first step gives the usual v = g'.
+    Returns (p, v)."""
+    p, g, v = (np.asarray(x, F64) for x in (p, g, v))
+    g = g + weight_decay * p
+    v = momentum * v + g
+    step = g + momentum * v if nesterov else v
+    return p - lr * step, v
+
+
 def round_to_bf16(x):
     """Value of the nearest bf16 number to each fp32 input, returned as fp32.
     NaNs stay NaN (quiet); overflow past the largest finite bf16 gives inf."""

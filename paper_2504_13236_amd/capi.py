@@ -62,6 +62,10 @@ class nnt_gpt2_block_cfg(C.Structure):
                 ("fused_attention", C.c_int32)]
 
 
+class nnt_sgd_cfg(C.Structure):
+    _fields_ = [("lr", C.c_double), ("momentum", C.c_double), ("weight_decay", C.c_double), ("nesterov", C.c_int32)]
+
+
 class nnt_slot_info(C.Structure):
     _fields_ = [("used", C.c_int32), ("dtype", C.c_int32), ("ndim", C.c_int32), ("causal_tiles", C.c_int32),
                 ("shape", C.c_int64 * NNT_MAX_DIM), ("basetile", C.c_int64 * NNT_MAX_DIM)]
@@ -122,6 +126,7 @@ PROTOTYPES = {
     "nnt_tile_softmax_bwd_dot": (_i32, [_p, _i32, _i64, _i64, _i64, _p, _p, _p, _i32]),
     "nnt_tile_softmax_bwd_apply": (_i32, [_p, _i32, _i64, _i64, _i64, _p, _p, _p]),
     "nnt_tile_adam": (_i32, [_p, _i64, _i32, _d, _d, _d, _d, _d, _p, _p, _p, _p, _p]),
+    "nnt_tile_sgd": (_i32, [_p, _i64, _d, _d, _d, _i32, _p, _p, _p, _p]),
     "nnt_gemm": (_i32, [_p, _f, _i32, _p, _i32, _p, _f, _p, _i32, _i32, _p]),
     "nnt_fill": (_i32, [_p, _f, _p]),
     "nnt_add": (_i32, [_p, _f, _p, _f, _p]),
@@ -139,12 +144,14 @@ PROTOTYPES = {
     "nnt_attention_fwd": (_i32, [_p, _p, _p, _p, _f, _i32, _p, _p]),
     "nnt_attention_bwd": (_i32, [_p, _p, _p, _p, _p, _p, _p, _f, _i32, _p, _p, _p]),
     "nnt_adam_step": (_i32, [_p, C.POINTER(nnt_adam_cfg), _i32, _p, _p, _p, _p, _p]),
+    "nnt_sgd_step": (_i32, [_p, C.POINTER(nnt_sgd_cfg), _p, _p, _p, _p]),
     "nnt_gpt2_block_slot": (_i32, [C.POINTER(nnt_gpt2_block_cfg), _i32, C.POINTER(nnt_slot_info)]),
     "nnt_gpt2_block_create": (_i32, [_p, C.POINTER(nnt_gpt2_block_cfg), _pp, _pp]),
     "nnt_gpt2_block_destroy": (_i32, [_p]),
     "nnt_gpt2_block_forward": (_i32, [_p, _p, _p]),
     "nnt_gpt2_block_backward": (_i32, [_p, _p, _p]),
     "nnt_gpt2_block_adam": (_i32, [_p, _i32, C.POINTER(nnt_adam_cfg)]),
+    "nnt_gpt2_block_sgd": (_i32, [_p, C.POINTER(nnt_sgd_cfg)]),
     "nnt_gpt2_block_sync_lowp": (_i32, [_p]),
     "nnt_version": (C.c_char_p, []),
 }

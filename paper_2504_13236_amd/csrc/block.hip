@@ -264,6 +264,21 @@ int32_t nnt_gpt2_block_adam(nnt_gpt2_block* b, int32_t step, const nnt_adam_cfg*
     return NNT_OK;
 }
 
+int32_t nnt_gpt2_block_sgd(nnt_gpt2_block* b, const nnt_sgd_cfg* cfg) {
+    if (!b) return NNT_EINVAL;
+    nnt_ctx* ctx = b->ctx;
+    NNT_CHECK_CTX(ctx);
+    if (!cfg) return fail(ctx, NNT_EINVAL, "nnt_gpt2_block_sgd: bad argument");
+    for (int p = 0; p < 12; p++)
+        if (!b->s[NNT_BLK_ADAM_M + p])
+            return fail(ctx, NNT_ESTATE, "nnt_gpt2_block_sgd: the block was created without moment tensors");
+    for (int p = 0; p < 12; p++) {
+        nnt_tensor* lowp = (b->cfg.dtype == NNT_BF16 && p < 4) ? b->s[NNT_BLK_LOWP + p] : nullptr;
+        TRY(nnt_sgd_step(ctx, cfg, b->s[NNT_BLK_GRAD + p], b->s[p], b->s[NNT_BLK_ADAM_M + p], lowp));
+    }
+    return NNT_OK;
+}
+
 int32_t nnt_gpt2_block_sync_lowp(nnt_gpt2_block* b) {
     if (!b) return NNT_EINVAL;
     nnt_ctx* ctx = b->ctx;

@@ -239,6 +239,16 @@ int32_t nnt_tile_adam(void* stream, int64_t n, int32_t step, double lr, double b
     return launch_ew((hipStream_t)stream, f, single_geom(n), n, 1, vec);
 }
 
+int32_t nnt_tile_sgd(void* stream, int64_t n, double lr, double momentum, double weight_decay, int32_t nesterov,
+                     const float* g, float* p, float* v, void* p_lowp) {
+    if (n < 0 || momentum < 0.0 || (n > 0 && (!g || !p || !v))) return NNT_EINVAL;
+    SgdF f = {};
+    f.lr = (float)lr; f.mu = (float)momentum; f.wd = (float)weight_decay; f.nesterov = nesterov ? 1 : 0;
+    f.g = ptr(g); f.p = ptr(p); f.v = ptr(v); f.lp = ptr(p_lowp);
+    const bool vec = aligned16(g) && aligned16(p) && aligned16(v) && (!p_lowp || ((uintptr_t)p_lowp & 7) == 0);
+    return launch_ew((hipStream_t)stream, f, single_geom(n), n, 1, vec);
+}
+
 // ------------------------------------------------------------------ tensor form
 int32_t nnt_fill(nnt_ctx* ctx, float value, nnt_tensor* X) {
     NNT_CHECK_CTX(ctx);
@@ -365,6 +375,27 @@ int32_t nnt_adam_step(nnt_ctx* ctx, const nnt_adam_cfg* cfg, int32_t step, nnt_t
     return run_tensor_ew(ctx, P, ops, vec, [=](int64_t t) {
         AdamF f = base;
         f.g = opnd(G, t); f.p = opnd(P, t); f.m = opnd(M, t); f.v = opnd(V, t);
+        f.lp = LP ? opnd(LP, t) : Operand{nullptr, nullptr};
+        return f;
+    });
+}
+
+int32_t nnt_sgd_step(nnt_ctx* ctx, const nnt_sgd_cfg* cfg, nnt_tensor* G, nnt_tensor* P, nnt_tensor* V, nnt_tensor* LP) {
+    NNT_CHECK_CTX(ctx);
+    if (!cfg || !G || !P || !V || cfg->momentum < 0.0) return fail(ctx, NNT_EINVAL, "nnt_sgd_step: bad argument");
+    if (!same_tiling(G, P) || !same_tiling(G, V) || (LP && !same_tiling(G, LP)))
+        return fail(ctx, NNT_EINVAL, "nnt_sgd_step: operands tiled differently");
+    if (G->dtype != NNT_F32 || P->dtype != NNT_F32 || V->dtype != NNT_F32 || (LP && LP->dtype != NNT_BF16))
+        return fail(ctx, NNT_EDTYPE, "nnt_sgd_step: g, p, v must be fp32 and the low-precision copy bf16");
+    const bool vec = all_aligned(G) && all_aligned(P) && all_aligned(V) && (!LP || all_aligned(LP));
+    OpTag tag(ctx, "sgd", present_numel(P) * (20 + (LP ? 2 : 0)), true);
+    SgdF base = {};
+    base.lr = (float)cfg->lr; base.mu = (float)cfg->momentum; base.wd = (float)cfg->weight_decay; base.nesterov = cfg->nesterov ? 1 : 0;
+    std::vector<std::pair<nnt_tensor*, int>> ops = {{G, kRead}, {P, kReadWrite}, {V, kReadWrite}};
+    if (LP) ops.push_back({LP, kWrite});
+    return run_tensor_ew(ctx, P, ops, vec, [=](int64_t t) {
+        SgdF f = base;
+        f.g = opnd(G, t); f.p = opnd(P, t); f.v = opnd(V, t);
         f.lp = LP ? opnd(LP, t) : Operand{nullptr, nullptr};
         return f;
     });

@@ -303,5 +303,48 @@ struct AdamF {
     }
 };
 
+// SGD with momentum (section 3, Optimizers): the update is a weighted sum of parameter, gradient and
+// momentum term.  g' = g + wd p;  v <- mu v + g';  p <- p - lr v   (Nesterov: p - lr (g' + mu v)).
+struct SgdF {
+    static constexpr int V = 4, NIN = 3;
+    Operand g, p, v, lp;
+    float lr, mu, wd;
+    int nesterov;
+    struct Ctx { const float* g; float* p; float* v; bf16_t* lp; };
+    __device__ bool setup(Ctx& c, const EwGeom&, int tile) const {
+        c.g = pick<const float>(g, tile);
+        c.p = pick<float>(p, tile);
+        c.v = pick<float>(v, tile);
+        c.lp = (lp.table || lp.single) ? pick<bf16_t>(lp, tile) : nullptr;
+        return c.p != nullptr;
+    }
+    template <int W> __device__ void load(const Ctx& c, int64_t i, float (&in)[3][W]) const {
+        ldv<W>(c.g + i, in[0]);
+        ldv<W>(c.p + i, in[1]);
+        ldv<W>(c.v + i, in[2]);
+    }
+    template <int W> __device__ void store(const Ctx& c, int64_t i, float (&in)[3][W]) const {
+        float pp[W], vv[W];
+#pragma unroll
+        for (int j = 0; j < W; j++) {
+            const float gg = in[0][j] + wd * in[1][j];
+            vv[j] = mu * in[2][j] + gg;
+            pp[j] = in[1][j] - lr * (nesterov ? gg + mu * vv[j] : vv[j]);
+        }
+        stv<W>(c.p + i, pp);
+        stv<W>(c.v + i, vv);
+        if (c.lp) {
+            if constexpr (W == 4) {
+                uint2 x;
+                x.x = (uint32_t)f2bf(pp[0]) | ((uint32_t)f2bf(pp[1]) << 16);
+                x.y = (uint32_t)f2bf(pp[2]) | ((uint32_t)f2bf(pp[3]) << 16);
+                *reinterpret_cast<uint2*>(c.lp + i) = x;
+            } else {
+                c.lp[i] = f2bf(pp[0]);
+            }
+        }
+    }
+};
+
 }  // namespace
 }  // namespace nnt

@@ -255,6 +255,10 @@ class Gpt2Block:
         cfg = capi.nnt_adam_cfg(lr, beta1, beta2, eps, weight_decay)
         capi.nnt_gpt2_block_adam(self.h, step, C.byref(cfg))
 
+    def sgd(self, lr=1e-2, momentum=0.9, weight_decay=0.0, nesterov=False):
+        cfg = capi.nnt_sgd_cfg(lr, momentum, weight_decay, 1 if nesterov else 0)
+        capi.nnt_gpt2_block_sgd(self.h, C.byref(cfg))
+
     def param(self, name):
         return self.slots[PARAM_SLOTS[name]]
 

@@ -135,6 +135,33 @@ def test_block_fused_attention_needs_whole_heads(mods):
                             dtype="f32", fused_attention=True)
 
 
+def test_block_C1_sgd_momentum_steps(mods):
+    """Two forward / backward / SGD-with-momentum iterations of the block against the oracle's."""
+    capi, tiled = mods
+    cfg = workload.CONFIGS[1]
+    inp = workload.generate(cfg)
+    hyper = dict(lr=0.05, momentum=0.9, weight_decay=0.01)
+    p64 = {k: np.asarray(inp[k], np.float64) for k in workload.PARAM_NAMES}
+    vel = {k: 0.0 for k in workload.PARAM_NAMES}
+    with tiled.Context(n_streams=4) as ctx:
+        blk = tiled.Gpt2Block(ctx, cfg.N_e, cfg.N_h, cfg.N_m, cfg.N_s, cfg.N_b, workload.base_tiles(cfg), dtype="f32", adam=True)
+        blk.set_params({k: inp[k] for k in workload.PARAM_NAMES})
+        X, dOut = blk.activation(inp["X"]), blk.activation(inp["dOut"])
+        Out, dX = blk.activation(), blk.activation()
+        for it in range(2):
+            blk.forward(X, Out)
+            blk.backward(dOut, dX)
+            blk.sgd(**hyper)
+            _, cache = D.block_forward(p64, inp["X"], cfg.N_h, cfg.eps, cfg.gelu)
+            _, grads = D.block_backward(p64, cache, inp["dOut"], cfg.N_h, cfg.gelu)
+            for k in workload.PARAM_NAMES:
+                p64[k], vel[k] = D.sgd_step(p64[k], grads[k], vel[k], **hyper)
+        for k in workload.PARAM_NAMES:
+            assert relerr(blk.param(k).download(), p64[k]) <= 1e-5, k
+            assert relerr(blk.moment(k, "m").download(), vel[k]) <= 1e-5, k
+        blk.close()
+
+
 def small_bf16_cfg():
     # C3's recipe at a size the oracle finishes at once: bf16 storage, fp32 accumulate and masters, Adam
     return workload.CONFIGS[3].replace(N_e=256, N_h=4, N_m=1024, N_s=192, N_b=2, tile=128)

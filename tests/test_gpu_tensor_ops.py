@@ -283,6 +283,30 @@ def test_adam_tensor(mods, gran, lowp):
             np.testing.assert_array_equal(tl.download(), D.round_to_bf16(tp.download()))
 
 
+@pytest.mark.parametrize("gran", GRANS)
+@pytest.mark.parametrize("lowp", [False, True])
+def test_sgd_tensor(mods, gran, lowp):
+    capi, tiled = mods
+    r = rng(7)
+    shape, base = (300, 130), (128, 64)
+    p = r.standard_normal(shape).astype(np.float32)
+    with tiled.Context(n_streams=4, granularity=gran) as ctx:
+        tp = T(tiled, ctx, p, base, "f32")
+        tv = tiled.TiledTensor.zeros(ctx, shape, base)
+        tl = tiled.TiledTensor(ctx, "bf16", shape, base) if lowp else None
+        cfg = capi.nnt_sgd_cfg(0.05, 0.9, 0.01, 0)
+        pr, vr = p.astype(np.float64), 0.0
+        for step in (1, 2):
+            g = r.standard_normal(shape).astype(np.float32)
+            tg = T(tiled, ctx, g, base, "f32")
+            capi.nnt_sgd_step(ctx.h, C.byref(cfg), tg.h, tp.h, tv.h, tl.h if lowp else None)
+            pr, vr = D.sgd_step(pr, g, vr, 0.05, 0.9, 0.01)
+        check(tp.download(), pr, "f32", "sgd p")
+        check(tv.download(), vr, "f32", "sgd v")
+        if lowp:
+            np.testing.assert_array_equal(tl.download(), D.round_to_bf16(tp.download()))
+
+
 # ------------------------------------------------------------------ executor
 def test_executor_orders_dependent_tasks_across_streams(mods):
     """A chain y <- y + x repeated many times on 8 streams must give the serial

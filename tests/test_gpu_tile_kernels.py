@@ -384,6 +384,28 @@ def test_adam_first_step_closed_form(capi):
     check(from_dev(dp, (n,)), want, "f32", "adam closed form")
 
 
+# ------------------------------------------------------------------ SGD with momentum
+@pytest.mark.parametrize("n", [3, 1000, 100003])
+@pytest.mark.parametrize("nesterov", [0, 1])
+def test_sgd_tile(capi, n, nesterov):
+    r = rng(n + nesterov)
+    p = r.standard_normal(n).astype(np.float32)
+    dp, dv = to_dev(p), to_dev(np.zeros(n))
+    lp = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+    pr, vr = p.astype(np.float64), np.zeros(n)
+    for step in range(3):
+        g = r.standard_normal(n).astype(np.float32)
+        dg = to_dev(g)
+        capi.nnt_tile_sgd(stream_ptr(), n, 0.05, 0.9, 0.01, nesterov, dg.data_ptr(), dp.data_ptr(), dv.data_ptr(), lp.data_ptr())
+        torch.cuda.synchronize()
+        pr, vr = D.sgd_step(pr, g, vr, 0.05, 0.9, 0.01, bool(nesterov))
+    check(from_dev(dp, (n,)), pr, "f32", "sgd p")
+    check(from_dev(dv, (n,)), vr, "f32", "sgd v")
+    got_lp = lp.to(torch.float32).cpu().numpy()
+    np.testing.assert_array_equal(got_lp.view(np.uint32), D.round_to_bf16(dp.cpu().numpy()).view(np.uint32))
+    assert capi.nnt_tile_sgd.raw(stream_ptr(), n, 0.05, -0.1, 0.0, 0, dg.data_ptr(), dp.data_ptr(), dv.data_ptr(), None) == capi.NNT_EINVAL
+
+
 def test_tile_calls_reject_bad_arguments(capi):
     x = torch.zeros(16, device="cuda")
     st = stream_ptr()

@@ -362,6 +362,36 @@ def test_adam_first_step_closed_form_and_torch():
 
 
 # ------------------------------------------------------------------ bf16 rounding
+@pytest.mark.parametrize("nesterov", [False, True])
+def test_sgd_momentum_closed_form_and_torch(nesterov):
+    p0 = rng.standard_normal(37)
+    gs = [rng.standard_normal(37) for _ in range(3)]
+    lr, mu, wd = 0.05, 0.9, 0.01
+    # by hand, one element, two steps from zero velocity
+    g1 = gs[0][0] + wd * p0[0]
+    v1 = g1
+    p1 = p0[0] - lr * ((g1 + mu * v1) if nesterov else v1)
+    g2 = gs[1][0] + wd * p1
+    v2 = mu * v1 + g2
+    p2 = p1 - lr * ((g2 + mu * v2) if nesterov else v2)
+    p, v = p0.copy(), np.zeros(37)
+    for k in range(2):
+        p, v = D.sgd_step(p, gs[k], v, lr, mu, wd, nesterov)
+    assert abs(p[0] - p2) < 1e-14 and abs(v[0] - v2) < 1e-14
+    # the library optimiser, three steps
+    tp = torch.tensor(p0.copy(), requires_grad=True)
+    opt = torch.optim.SGD([tp], lr=lr, momentum=mu, weight_decay=wd, nesterov=nesterov)
+    p, v = p0.copy(), np.zeros(37)
+    for k in range(3):
+        tp.grad = torch.tensor(gs[k].copy())
+        opt.step()
+        p, v = D.sgd_step(p, gs[k], v, lr, mu, wd, nesterov)
+    np.testing.assert_allclose(p, tp.detach().numpy(), rtol=1e-13, atol=1e-15)
+    # no momentum, no decay: plain gradient descent
+    p, v = D.sgd_step(p0, gs[0], np.zeros(37), 0.1, 0.0, 0.0)
+    np.testing.assert_allclose(p, p0 - 0.1 * gs[0], rtol=1e-15)
+
+
 def test_round_to_bf16_matches_library_and_ties():
     x = np.concatenate([
         rng.standard_normal(5000).astype(np.float32) * 10,
