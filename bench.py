@@ -145,19 +145,35 @@ def measure(args, cfg, inp, attention, capi, tiled, torch, workload):
     returns the bench record."""
     gran = capi.NNT_GRAN_OP if args.granularity == "op" else capi.NNT_GRAN_TILE
     ctx = tiled.Context(n_streams=args.streams, granularity=gran)
-    blk = tiled.Gpt2Block(ctx, cfg.N_e, cfg.N_h, cfg.N_m, cfg.N_s, cfg.N_b, workload.base_tiles(cfg), dtype=cfg.dtype,
-                          eps=cfg.eps, gelu=cfg.gelu, adam=cfg.adam, fused_attention=attention == "fused")
-    blk.set_params({k: inp[k] for k in workload.PARAM_NAMES})
-    X, dOut = blk.activation(inp["X"]), blk.activation(inp["dOut"])
-    Out, dX = blk.activation(), blk.activation()
+    nblk = max(1, args.blocks)
+    blks = [tiled.Gpt2Block(ctx, cfg.N_e, cfg.N_h, cfg.N_m, cfg.N_s, cfg.N_b, workload.base_tiles(cfg), dtype=cfg.dtype,
+                            eps=cfg.eps, gelu=cfg.gelu, adam=cfg.adam, fused_attention=attention == "fused") for _ in range(nblk)]
+    for b in blks:
+        b.set_params({k: inp[k] for k in workload.PARAM_NAMES})
+    blk = blks[0]
     step_no = [0]
+    if nblk == 1:
+        X, dOut = blk.activation(inp["X"]), blk.activation(inp["dOut"])
+        Out, dX = blk.activation(), blk.activation()
 
-    def step():
-        blk.forward(X, Out)
-        blk.backward(dOut, dX)
-        if cfg.adam:
-            step_no[0] += 1
-            blk.adam(step_no[0], **workload.ADAM)
+        def step():
+            blk.forward(X, Out)
+            blk.backward(dOut, dX)
+            if cfg.adam:
+                step_no[0] += 1
+                blk.adam(step_no[0], **workload.ADAM)
+    else:
+        # a chain of identical blocks as one flow of tasks
+        stack = tiled.Gpt2Stack(ctx, blks)
+        stack.acts[0].upload(inp["X"])
+        stack.dacts[nblk].upload(inp["dOut"])
+
+        def step():
+            stack.forward()
+            stack.backward()
+            if cfg.adam:
+                step_no[0] += 1
+                stack.adam(step_no[0], **workload.ADAM)
 
     for _ in range(max(args.warmup, 1)):
         step()
@@ -193,7 +209,7 @@ def measure(args, cfg, inp, attention, capi, tiled, torch, workload):
     ctx.profile(False)
     ctx.set_serial(False)
     ms_per_step = dt / args.steps * 1e3
-    flops = workload.model_flops(cfg, tile_skip=True, visible_only=attention == "fused")
+    flops = nblk * workload.model_flops(cfg, tile_skip=True, visible_only=attention == "fused")
     value = flops / (dt / args.steps) / 1e12
 
     # per-operation figures from the executor's event pairs
@@ -256,12 +272,15 @@ def measure(args, cfg, inp, attention, capi, tiled, torch, workload):
                                   % (cfg.name, cfg.dtype, cfg.N_e, cfg.N_h, cfg.N_m, cfg.N_s, cfg.N_b, cfg.tile,
                                      "+Adam" if cfg.adam else ""),
                       "streams": args.streams, "granularity": args.granularity, "graph_replay": bool(args.graph),
-                      "attention": attention,
+                      "attention": attention, "blocks": nblk,
                       "flops_per_step": flops,
                       "attention_flops": "visible (key, query) pairs only, no recomputation" if attention == "fused"
                                          else "computed sequence-tile pairs only"},
            "roofline": roofline, "summary": summary, "kernels": kernels, "executor": ctx.stats()}
-    blk.close()
+    if nblk > 1:
+        stack.close()
+    for b in blks:
+        b.close()
     ctx.close()
     return out
 
@@ -275,6 +294,7 @@ def main():
     ap.add_argument("--streams", type=int, default=4)
     ap.add_argument("--granularity", choices=["op", "tile"], default="op")
     ap.add_argument("--graph", action="store_true", help="replay the step from a captured HIP graph")
+    ap.add_argument("--blocks", type=int, default=1, help="chain this many identical blocks into one flow of tasks")
     ap.add_argument("--attention", choices=["tiles", "fused"], default="tiles",
                     help="tiles: scores, softmax and the product with V as three operations on the stored N_s x N_s "
                          "tensor (the paper's flow, the default); fused: one kernel per direction that never stores it")
@@ -325,7 +345,7 @@ def main():
     cfg = workload.CONFIGS[args.config]
     inp = workload.generate(cfg)
     out = measure(args, cfg, inp, args.attention, capi, tiled, torch, workload)
-    if args.attention == "tiles" and cfg.h in (64, 128) and not args.no_next_rows:
+    if args.attention == "tiles" and cfg.h in (64, 128) and not args.no_next_rows and args.blocks == 1:
         # the first of the "next" rows beside the headline: the same block with the fused attention kernels
         f = measure(args, cfg, inp, "fused", capi, tiled, torch, workload)
         out["next_rows"] = {"fused_attention": {k: f[k] for k in ("value", "unit", "ms_per_step", "config", "summary")}}

@@ -435,6 +435,26 @@ NNT_API int32_t nnt_gpt2_block_sgd(nnt_gpt2_block* blk, const nnt_sgd_cfg* cfg);
 /* bf16 blocks: (re)make the bf16 weight copies from the fp32 masters. */
 NNT_API int32_t nnt_gpt2_block_sync_lowp(nnt_gpt2_block* blk);
 
+/* acc[p] <- alpha * (gradient of parameter p) + acc[p] for the 12 parameters, as
+ * 12 residual-add operations: gradient accumulation over micro-batches.  acc:
+ * fp32 tensors shaped and tiled like the parameters (slot order). */
+NNT_API int32_t nnt_gpt2_block_grads_axpy(nnt_gpt2_block* blk, float alpha, nnt_tensor* const* acc);
+
+/* A chain of blocks as one flow of tasks (section 2: the whole training
+ * iteration is submitted as one sequence of tasks and runs asynchronously):
+ * acts[i] is the input of block i, acts[n_blocks] the output; dacts[i] is the
+ * gradient with respect to acts[i] (dacts[n_blocks] is the input of backward).
+ * All are [N_e, N_s, N_b] tensors of the blocks' dtype and tiling, owned by the
+ * caller, as are the blocks.  Between nnt_capture_begin and nnt_capture_end the
+ * three calls record the iteration of all blocks into one graph. */
+typedef struct nnt_gpt2_stack nnt_gpt2_stack;
+NNT_API int32_t nnt_gpt2_stack_create(nnt_ctx* ctx, int32_t n_blocks, nnt_gpt2_block* const* blocks,
+                              nnt_tensor* const* acts, nnt_tensor* const* dacts, nnt_gpt2_stack** out);
+NNT_API int32_t nnt_gpt2_stack_destroy(nnt_gpt2_stack* st);
+NNT_API int32_t nnt_gpt2_stack_forward(nnt_gpt2_stack* st);
+NNT_API int32_t nnt_gpt2_stack_backward(nnt_gpt2_stack* st);
+NNT_API int32_t nnt_gpt2_stack_adam(nnt_gpt2_stack* st, int32_t step, const nnt_adam_cfg* cfg);
+
 NNT_API const char* nnt_version(void);
 
 #ifdef __cplusplus

@@ -153,6 +153,12 @@ PROTOTYPES = {
     "nnt_gpt2_block_adam": (_i32, [_p, _i32, C.POINTER(nnt_adam_cfg)]),
     "nnt_gpt2_block_sgd": (_i32, [_p, C.POINTER(nnt_sgd_cfg)]),
     "nnt_gpt2_block_sync_lowp": (_i32, [_p]),
+    "nnt_gpt2_block_grads_axpy": (_i32, [_p, _f, _pp]),
+    "nnt_gpt2_stack_create": (_i32, [_p, _i32, _pp, _pp, _pp, _pp]),
+    "nnt_gpt2_stack_destroy": (_i32, [_p]),
+    "nnt_gpt2_stack_forward": (_i32, [_p]),
+    "nnt_gpt2_stack_backward": (_i32, [_p]),
+    "nnt_gpt2_stack_adam": (_i32, [_p, _i32, C.POINTER(nnt_adam_cfg)]),
     "nnt_version": (C.c_char_p, []),
 }
 
@@ -161,7 +167,8 @@ _CTX_FIRST = {n for n, (r, a) in PROTOTYPES.items()
               if n.startswith("nnt_") and not n.startswith("nnt_tile_") and not n.startswith("nnt_tiling_")
               and n not in ("nnt_ctx_create", "nnt_version", "nnt_gpt2_block_slot", "nnt_last_error")
               and not n.startswith("nnt_tensor_") and not n.startswith("nnt_graph_")
-              and not n.startswith("nnt_gpt2_block_")}
+              and not n.startswith("nnt_gpt2_block_")
+              and (not n.startswith("nnt_gpt2_stack_") or n == "nnt_gpt2_stack_create")}
 
 
 def _wrap(name, restype, argtypes):

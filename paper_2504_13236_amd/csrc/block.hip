@@ -12,6 +12,8 @@
 // The backward pass is the exact adjoint, in reverse order.
 #include "internal.hpp"
 
+#include <vector>
+
 #include <cmath>
 
 struct nnt_gpt2_block {
@@ -19,6 +21,13 @@ struct nnt_gpt2_block {
     nnt_gpt2_block_cfg cfg;
     nnt_tensor* s[NNT_BLK_NSLOTS];
     nnt_tensor* X;      // input of the last forward call
+};
+
+// A chain of blocks: acts[i] feeds block i, acts[n] is the output; dacts[i] is the gradient of acts[i].
+struct nnt_gpt2_stack {
+    nnt_ctx* ctx;
+    std::vector<nnt_gpt2_block*> blocks;
+    std::vector<nnt_tensor*> acts, dacts;
 };
 
 using namespace nnt;
@@ -276,6 +285,65 @@ int32_t nnt_gpt2_block_sgd(nnt_gpt2_block* b, const nnt_sgd_cfg* cfg) {
         nnt_tensor* lowp = (b->cfg.dtype == NNT_BF16 && p < 4) ? b->s[NNT_BLK_LOWP + p] : nullptr;
         TRY(nnt_sgd_step(ctx, cfg, b->s[NNT_BLK_GRAD + p], b->s[p], b->s[NNT_BLK_ADAM_M + p], lowp));
     }
+    return NNT_OK;
+}
+
+int32_t nnt_gpt2_block_grads_axpy(nnt_gpt2_block* b, float alpha, nnt_tensor* const* acc) {
+    if (!b) return NNT_EINVAL;
+    nnt_ctx* ctx = b->ctx;
+    NNT_CHECK_CTX(ctx);
+    if (!acc) return fail(ctx, NNT_EINVAL, "nnt_gpt2_block_grads_axpy: bad argument");
+    for (int p = 0; p < 12; p++)
+        if (!acc[p]) return fail(ctx, NNT_EINVAL, "nnt_gpt2_block_grads_axpy: missing accumulator");
+    for (int p = 0; p < 12; p++) TRY(nnt_add(ctx, alpha, b->s[NNT_BLK_GRAD + p], 1.f, acc[p]));
+    return NNT_OK;
+}
+
+int32_t nnt_gpt2_stack_create(nnt_ctx* ctx, int32_t n_blocks, nnt_gpt2_block* const* blocks, nnt_tensor* const* acts,
+                              nnt_tensor* const* dacts, nnt_gpt2_stack** out) {
+    NNT_CHECK_CTX(ctx);
+    if (!out) return NNT_EINVAL;
+    *out = nullptr;
+    if (n_blocks < 1 || !blocks || !acts || !dacts) return fail(ctx, NNT_EINVAL, "nnt_gpt2_stack_create: bad argument");
+    for (int i = 0; i < n_blocks; i++)
+        if (!blocks[i] || blocks[i]->ctx != ctx) return fail(ctx, NNT_EINVAL, "nnt_gpt2_stack_create: block of another context");
+    for (int i = 0; i <= n_blocks; i++) {
+        const nnt_tensor* like = blocks[0]->s[NNT_BLK_X1];
+        if (!acts[i] || !dacts[i] || !same_tiling(acts[i], like) || !same_tiling(dacts[i], like) ||
+            acts[i]->dtype != like->dtype || dacts[i]->dtype != like->dtype)
+            return fail(ctx, NNT_EINVAL, "nnt_gpt2_stack_create: activation " + std::to_string(i) + " does not match the blocks");
+    }
+    nnt_gpt2_stack* st = new (std::nothrow) nnt_gpt2_stack();
+    if (!st) return fail(ctx, NNT_ENOMEM, "host allocation failed");
+    st->ctx = ctx;
+    st->blocks.assign(blocks, blocks + n_blocks);
+    st->acts.assign(acts, acts + n_blocks + 1);
+    st->dacts.assign(dacts, dacts + n_blocks + 1);
+    *out = st;
+    return NNT_OK;
+}
+
+int32_t nnt_gpt2_stack_destroy(nnt_gpt2_stack* st) {
+    if (!st) return NNT_EINVAL;
+    delete st;
+    return NNT_OK;
+}
+
+int32_t nnt_gpt2_stack_forward(nnt_gpt2_stack* st) {
+    if (!st) return NNT_EINVAL;
+    for (size_t i = 0; i < st->blocks.size(); i++) TRY(nnt_gpt2_block_forward(st->blocks[i], st->acts[i], st->acts[i + 1]));
+    return NNT_OK;
+}
+
+int32_t nnt_gpt2_stack_backward(nnt_gpt2_stack* st) {
+    if (!st) return NNT_EINVAL;
+    for (size_t i = st->blocks.size(); i-- > 0;) TRY(nnt_gpt2_block_backward(st->blocks[i], st->dacts[i + 1], st->dacts[i]));
+    return NNT_OK;
+}
+
+int32_t nnt_gpt2_stack_adam(nnt_gpt2_stack* st, int32_t step, const nnt_adam_cfg* cfg) {
+    if (!st) return NNT_EINVAL;
+    for (nnt_gpt2_block* b : st->blocks) TRY(nnt_gpt2_block_adam(b, step, cfg));
     return NNT_OK;
 }
 

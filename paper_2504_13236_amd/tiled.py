@@ -273,3 +273,34 @@ class Gpt2Block:
             self.ctx.wait()
             capi.nnt_gpt2_block_destroy(self.h)
             self.h = None
+
+
+class Gpt2Stack:
+    """A chain of blocks with the activations between them (allocated here) as one flow of tasks."""
+
+    def __init__(self, ctx: Context, blocks):
+        self.ctx, self.blocks = ctx, list(blocks)
+        n = len(self.blocks)
+        self.acts = [self.blocks[0].activation() for _ in range(n + 1)]
+        self.dacts = [self.blocks[0].activation() for _ in range(n + 1)]
+        h = C.c_void_p()
+        capi.nnt_gpt2_stack_create(ctx.h, n, capi.ptr_array([b.h.value for b in self.blocks]),
+                                   capi.ptr_array([t.h.value for t in self.acts]),
+                                   capi.ptr_array([t.h.value for t in self.dacts]), C.byref(h))
+        self.h = h
+
+    def forward(self):
+        capi.nnt_gpt2_stack_forward(self.h)
+
+    def backward(self):
+        capi.nnt_gpt2_stack_backward(self.h)
+
+    def adam(self, step, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0):
+        cfg = capi.nnt_adam_cfg(lr, beta1, beta2, eps, weight_decay)
+        capi.nnt_gpt2_stack_adam(self.h, step, C.byref(cfg))
+
+    def close(self):
+        if self.h:
+            self.ctx.wait()
+            capi.nnt_gpt2_stack_destroy(self.h)
+            self.h = None

@@ -162,6 +162,101 @@ def test_block_C1_sgd_momentum_steps(mods):
         blk.close()
 
 
+def _two_block_inputs(cfg):
+    a = workload.generate(cfg)
+    b = workload.generate(cfg.replace(index=cfg.index + 5))      # another seed for the second block's parameters
+    return a, b
+
+
+def _oracle_chain(cfg, pa, pb, X, dOut):
+    X1, ca = D.block_forward(pa, X, cfg.N_h, cfg.eps, cfg.gelu)
+    X2, cb = D.block_forward(pb, X1, cfg.N_h, cfg.eps, cfg.gelu)
+    dX1, gb = D.block_backward(pb, cb, dOut, cfg.N_h, cfg.gelu)
+    dX0, ga = D.block_backward(pa, ca, dX1, cfg.N_h, cfg.gelu)
+    return X2, dX0, ga, gb
+
+
+@pytest.mark.parametrize("graph", [False, True], ids=["eager", "graph"])
+def test_two_block_chain_forward_backward(mods, graph):
+    """Two blocks chained into one flow of tasks (and, with `graph`, replayed three times from one captured
+    HIP graph with eager work in between) against the oracle's composition of the two blocks."""
+    import ctypes as C
+    capi, tiled = mods
+    cfg = workload.CONFIGS[1]
+    ia, ib = _two_block_inputs(cfg)
+    pa = {k: np.asarray(ia[k], np.float64) for k in workload.PARAM_NAMES}
+    pb = {k: np.asarray(ib[k], np.float64) for k in workload.PARAM_NAMES}
+    Out, dX0, ga, gb = _oracle_chain(cfg, pa, pb, ia["X"], ia["dOut"])
+    with tiled.Context(n_streams=4) as ctx:
+        blocks = [tiled.Gpt2Block(ctx, cfg.N_e, cfg.N_h, cfg.N_m, cfg.N_s, cfg.N_b, workload.base_tiles(cfg), dtype="f32", adam=False)
+                  for _ in range(2)]
+        blocks[0].set_params({k: ia[k] for k in workload.PARAM_NAMES})
+        blocks[1].set_params({k: ib[k] for k in workload.PARAM_NAMES})
+        st = tiled.Gpt2Stack(ctx, blocks)
+        st.acts[0].upload(ia["X"])
+        st.dacts[2].upload(ia["dOut"])
+
+        def check_all(tag):
+            assert relerr(st.acts[2].download(), Out) <= 1e-5, tag
+            assert relerr(st.dacts[0].download(), dX0) <= 1e-5, tag
+            for blk, g in ((blocks[0], ga), (blocks[1], gb)):
+                for k in workload.PARAM_NAMES:
+                    assert relerr(blk.grad(k).download(), g[k]) <= 1e-5, (tag, k)
+
+        st.forward()
+        st.backward()
+        check_all("eager")
+        if graph:
+            gh = C.c_void_p()
+            capi.nnt_capture_begin(ctx.h)
+            st.forward()
+            st.backward()
+            capi.nnt_capture_end(ctx.h, C.byref(gh))
+            for rep in range(3):
+                # eager work between the replays: wipe the outputs so that a replay that did nothing would show
+                for t in (st.acts[2], st.dacts[0]):
+                    capi.nnt_fill(ctx.h, 0.0, t.h)
+                ctx.wait()
+                capi.nnt_graph_launch(gh)
+                ctx.wait()
+                check_all("replay %d" % rep)
+            capi.nnt_graph_destroy(gh)
+        st.close()
+        for b in blocks:
+            b.close()
+
+
+def test_gradient_accumulation_over_micro_batches(mods):
+    """Parameter gradients of two micro-batches added into accumulators equal the oracle's sum."""
+    capi, tiled = mods
+    cfg = workload.CONFIGS[1]
+    i1 = workload.generate(cfg)
+    i2 = workload.generate(cfg.replace(index=cfg.index + 7))
+    p64 = {k: np.asarray(i1[k], np.float64) for k in workload.PARAM_NAMES}
+    want = {k: 0.0 for k in workload.PARAM_NAMES}
+    for inp in (i1, i2):
+        _, cache = D.block_forward(p64, inp["X"], cfg.N_h, cfg.eps, cfg.gelu)
+        _, g = D.block_backward(p64, cache, inp["dOut"], cfg.N_h, cfg.gelu)
+        for k in workload.PARAM_NAMES:
+            want[k] = want[k] + 0.5 * g[k]
+    with tiled.Context(n_streams=4) as ctx:
+        blk = tiled.Gpt2Block(ctx, cfg.N_e, cfg.N_h, cfg.N_m, cfg.N_s, cfg.N_b, workload.base_tiles(cfg), dtype="f32", adam=False)
+        blk.set_params({k: i1[k] for k in workload.PARAM_NAMES})
+        acc = [tiled.TiledTensor.zeros(ctx, blk.slots[p].shape, blk.slots[p].base) for p in range(12)]
+        X, dOut, Out, dX = blk.activation(), blk.activation(), blk.activation(), blk.activation()
+        for inp in (i1, i2):
+            X.upload(inp["X"])
+            dOut.upload(inp["dOut"])
+            blk.forward(X, Out)
+            blk.backward(dOut, dX)
+            capi.nnt_gpt2_block_grads_axpy(blk.h, 0.5, capi.ptr_array([t.h.value for t in acc]))
+            ctx.wait()
+        from paper_2504_13236_amd.tiled import PARAM_SLOTS
+        for k in workload.PARAM_NAMES:
+            assert relerr(acc[PARAM_SLOTS[k]].download(), want[k]) <= 1e-5, k
+        blk.close()
+
+
 def small_bf16_cfg():
     # C3's recipe at a size the oracle finishes at once: bf16 storage, fp32 accumulate and masters, Adam
     return workload.CONFIGS[3].replace(N_e=256, N_h=4, N_m=1024, N_s=192, N_b=2, tile=128)
