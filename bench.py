@@ -45,6 +45,49 @@ def cpu_baseline(cfg, sample_batch):
             "seconds": dt}
 
 
+def model_ops(cfg, capi, tiled, torch):
+    """Embedding lookup, its adjoint and the cross-entropy loss over vocabulary tiles at the config's token
+    count and a GPT-2-sized vocabulary (50304 = 50257 padded to a multiple of 128), timed per operation."""
+    import numpy as np
+    N_v, tv = 50304, 8192
+    T = cfg.N_s * cfg.N_b
+    w = 4 if cfg.dtype == "f32" else 2
+    out = []
+    with tiled.Context(n_streams=1) as ctx:
+        base_e, base_s = min(cfg.tile, cfg.N_e), min(cfg.tile, cfg.N_s)
+        W = tiled.TiledTensor(ctx, "f32", (cfg.N_e, N_v), (base_e, tv))
+        dW = tiled.TiledTensor.zeros(ctx, (cfg.N_e, N_v), (base_e, tv))
+        Y = tiled.TiledTensor(ctx, cfg.dtype, (cfg.N_e, cfg.N_s, cfg.N_b), (base_e, base_s, cfg.N_b))
+        X = tiled.TiledTensor(ctx, cfg.dtype, (N_v, cfg.N_s, cfg.N_b), (tv, base_s, cfg.N_b))
+        S = tiled.TiledTensor(ctx, "f32", (2, cfg.N_s, cfg.N_b), (2, base_s, cfg.N_b))
+        for t in (W, Y, X):
+            for k in range(len(t.tile_index)):
+                t.tile_view(k).normal_()
+        g = torch.Generator(device="cuda").manual_seed(1)
+        tok = torch.randint(0, N_v, (T,), device="cuda", dtype=torch.int32, generator=g)
+        col, tot = torch.empty(T, device="cuda"), torch.empty(1, device="cuda")
+
+        def run(call, reps=6):
+            call()
+            ctx.wait()
+            ctx.profile(True)
+            for _ in range(reps):
+                call()
+            ctx.wait()
+            rec = ctx.profile_read()
+            ctx.profile(False)
+            return rec
+        for name, call in (("embedding_fwd", lambda: capi.nnt_embedding_fwd(ctx.h, tok.data_ptr(), W.h, Y.h)),
+                           ("embedding_bwd", lambda: capi.nnt_embedding_bwd(ctx.h, tok.data_ptr(), Y.h, dW.h)),
+                           ("cross_entropy", lambda: capi.nnt_cross_entropy(ctx.h, X.h, tok.data_ptr(), S.h, col.data_ptr(), tot.data_ptr()))):
+            for label, e in run(call).items():
+                ms = e["ms"] / max(e["tasks"], 1)
+                gbs = e["work"] / max(e["tasks"], 1) / ms / 1e6
+                out.append({"operation": name, "kernel": label, "N_v": N_v, "tokens": T, "median_free_ms": ms, "GB/s": gbs,
+                            "frac_hbm_peak": gbs / PEAK_HBM_GBS})
+    return out
+
+
 def tile_kernels(cfg, capi, torch):
     """Single-kernel figures through the nnt_tile_* entry points at the shapes of `cfg`."""
     dt = capi.NNT_F32 if cfg.dtype == "f32" else capi.NNT_BF16
@@ -340,7 +383,9 @@ def main():
                                                "kernel": "ew_kernel<CastF<float, float>>"}}))
         return
     if args.tile_kernels:
-        print(json.dumps({"tile_kernels": tile_kernels(workload.CONFIGS[args.config], capi, torch)}))
+        res = tile_kernels(workload.CONFIGS[args.config], capi, torch)
+        res["model_ops"] = model_ops(workload.CONFIGS[args.config], capi, tiled, torch)
+        print(json.dumps({"tile_kernels": res}))
         return
     cfg = workload.CONFIGS[args.config]
     inp = workload.generate(cfg)

@@ -353,6 +353,32 @@ typedef struct nnt_adam_cfg {
 NNT_API int32_t nnt_adam_step(nnt_ctx* ctx, const nnt_adam_cfg* cfg, int32_t step, nnt_tensor* G, nnt_tensor* P,
                       nnt_tensor* M, nnt_tensor* V, nnt_tensor* P_lowp);
 
+/* Embedding layer (section 3, Embedding layer): every token of the N_s x N_b
+ * input gets its embedding vector, Y[e, s, b] = W[e, tokens[s + N_s * b]].
+ * tokens: device pointer to N_s * N_b int32 (not tiled); W: [N_e, N_v] (one column
+ * per vocabulary item), Y: [N_e, N_s, N_b], fp32 or bf16 each, any tiling.  A
+ * token outside [0, N_v) yields a zero vector. */
+NNT_API int32_t nnt_embedding_fwd(nnt_ctx* ctx, const int32_t* tokens, nnt_tensor* W, nnt_tensor* Y);
+/* Its adjoint: dW[e, v] += sum of dY[e, s, b] over the positions whose token is v
+ * (dW: fp32, accumulated into: clear it first; out-of-range tokens add nothing).
+ * Positions that share a token are summed with floating-point atomics, so the
+ * summation order, and with it the last bits, can differ from run to run. */
+NNT_API int32_t nnt_embedding_bwd(nnt_ctx* ctx, const int32_t* tokens, nnt_tensor* dY, nnt_tensor* dW);
+/* Cross-entropy loss (section 3, Cross-Entropy loss) over logits split into tiles,
+ * L = - sum_{s,b} log(exp(x[c,s,b]) / sum_j exp(x[j,s,b])), c = labels[s + N_s * b]:
+ * the SoftMax subroutines give the running (maximum, sum of shifted exponentials)
+ * per column (stats, fp32 [2, N_s, N_b] tiled like X's other axes) and the
+ * probabilities in place; then the label's entry of every column gives that
+ * column's loss and is decreased by one, which leaves dL/dx in X.
+ * X: [N_v, N_s, N_b] logits, fp32 or bf16, overwritten with the gradient;
+ * labels: device pointer to N_s * N_b int32 in [0, N_v) (a label outside adds no
+ * loss and leaves its column's probabilities); losses: device buffer of
+ * N_s * N_b floats (per-column losses); loss: device float, their sum (summed
+ * in a fixed order).  The caller owns both and must not reuse them before
+ * nnt_wait or a later operation on X. */
+NNT_API int32_t nnt_cross_entropy(nnt_ctx* ctx, nnt_tensor* X, const int32_t* labels, nnt_tensor* stats,
+                          float* losses, float* loss);
+
 /* SGD with momentum (section 3, Optimizers: the update is a weighted sum of the
  * parameter, the gradient and the momentum term):
  *   g' = g + weight_decay * p;  v <- momentum * v + g';

@@ -309,6 +309,45 @@ def adam_step(p, g, m, v, t, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_d
 # --------------------------------------------------------------------------
 # bf16 storage rounding (round to nearest, ties to even, on the fp32 bit pattern)
 # --------------------------------------------------------------------------
+# --------------------------------------------------------------------------
+# embedding layer and cross-entropy loss (section 3)
+# --------------------------------------------------------------------------
+def embedding_fwd(W, tokens):
+    """W: [N_e, N_v] (one column per vocabulary item); tokens: int [N_s, N_b].
+    Y[e, s, b] = W[e, tokens[s, b]]."""
+    W = np.asarray(W, F64)
+    return W[:, np.asarray(tokens)]
+
+
+def embedding_bwd(dY, tokens, N_v):
+    """dW[e, v] = sum of dY[e, s, b] over the positions (s, b) whose token is v."""
+    dY = np.asarray(dY, F64)
+    tokens = np.asarray(tokens)
+    dW = np.zeros((dY.shape[0], N_v), F64)
+    for s in range(tokens.shape[0]):
+        for b in range(tokens.shape[1]):
+            dW[:, tokens[s, b]] += dY[:, s, b]
+    return dW
+
+
+def cross_entropy(X, labels):
+    """X: logits [N_v, N_s, N_b]; labels: int [N_s, N_b].
+    L = - sum_{s,b} log(exp(x[c]) / sum_j exp(x[j])), c the label of the column;
+    returns (L, per-column losses, dL/dX = softmax(X) - onehot(labels))."""
+    X = np.asarray(X, F64)
+    labels = np.asarray(labels)
+    m = X.max(axis=0)
+    E = np.exp(X - m)
+    den = E.sum(axis=0)
+    P = E / den
+    s_idx, b_idx = np.meshgrid(np.arange(X.shape[1]), np.arange(X.shape[2]), indexing="ij")
+    picked = X[labels, s_idx, b_idx]
+    losses = m + np.log(den) - picked
+    dX = P.copy()
+    dX[labels, s_idx, b_idx] -= 1.0
+    return losses.sum(), losses, dX
+
+
 def sgd_step(p, g, v, lr=1e-2, momentum=0.9, weight_decay=0.0, nesterov=False):
     """SGD with momentum (section 3, Optimizers: a weighted sum of parameter, gradient and momentum
     term): g' = g + weight_decay p, v <- momentum v + g', p <- p - lr v; with `nesterov` the step

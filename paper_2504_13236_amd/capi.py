@@ -144,6 +144,9 @@ PROTOTYPES = {
     "nnt_attention_fwd": (_i32, [_p, _p, _p, _p, _f, _i32, _p, _p]),
     "nnt_attention_bwd": (_i32, [_p, _p, _p, _p, _p, _p, _p, _f, _i32, _p, _p, _p]),
     "nnt_adam_step": (_i32, [_p, C.POINTER(nnt_adam_cfg), _i32, _p, _p, _p, _p, _p]),
+    "nnt_embedding_fwd": (_i32, [_p, _p, _p, _p]),
+    "nnt_embedding_bwd": (_i32, [_p, _p, _p, _p]),
+    "nnt_cross_entropy": (_i32, [_p, _p, _p, _p, _p, _p]),
     "nnt_sgd_step": (_i32, [_p, C.POINTER(nnt_sgd_cfg), _p, _p, _p, _p]),
     "nnt_gpt2_block_slot": (_i32, [C.POINTER(nnt_gpt2_block_cfg), _i32, C.POINTER(nnt_slot_info)]),
     "nnt_gpt2_block_create": (_i32, [_p, C.POINTER(nnt_gpt2_block_cfg), _pp, _pp]),

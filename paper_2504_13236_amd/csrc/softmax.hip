@@ -51,44 +51,63 @@ __global__ void __launch_bounds__(256) softmax_fwd_fused(TiledView A, TiledView 
     const int kmax = causal ? min(nk, c.c1 + 1) : nk;      // keys 0 .. kmax-1 are visible to query c1
     float cache[NV > 0 ? NV : 1][V];
     float mx = kNegInf;
-    walk_keys<V, NV>(A, lane, kmax, [&](int slot, int l, int e, int ext) {
-        const T* p = col_ptr<const T>(A, c, l, ext);
-        float x[V];
-        if (p) {
-            ldv<V>(p + e, x);
-        } else {
-#pragma unroll
-            for (int k = 0; k < V; k++) x[k] = kNegInf;
-        }
-        const int k0 = l * A.base[0] + e;
-#pragma unroll
-        for (int k = 0; k < V; k++) {
-            x[k] = (k0 + k < kmax && p) ? x[k] * scale : kNegInf;
-            mx = fmaxf(mx, x[k]);
-            if constexpr (NV > 0) cache[slot][k] = x[k];
-        }
-    });
-    mx = wave_max(mx);
     float sum = 0.f;
-    walk_keys<V, NV>(A, lane, kmax, [&](int slot, int l, int e, int ext) {
-        float x[V];
-        if constexpr (NV > 0) {
-#pragma unroll
-            for (int k = 0; k < V; k++) x[k] = cache[slot][k];
-        } else {
+    if constexpr (NV > 0) {
+        // the column fits in registers: maximum, then shifted exponentials, from one read
+        walk_keys<V, NV>(A, lane, kmax, [&](int slot, int l, int e, int ext) {
             const T* p = col_ptr<const T>(A, c, l, ext);
+            float x[V];
+            if (p) {
+                ldv<V>(p + e, x);
+            } else {
+#pragma unroll
+                for (int k = 0; k < V; k++) x[k] = kNegInf;
+            }
             const int k0 = l * A.base[0] + e;
-            if (p) ldv<V>(p + e, x);
 #pragma unroll
-            for (int k = 0; k < V; k++) x[k] = (k0 + k < kmax && p) ? x[k] * scale : kNegInf;
-        }
+            for (int k = 0; k < V; k++) {
+                x[k] = (k0 + k < kmax && p) ? x[k] * scale : kNegInf;
+                mx = fmaxf(mx, x[k]);
+                cache[slot][k] = x[k];
+            }
+        });
+        mx = wave_max(mx);
+        walk_keys<V, NV>(A, lane, kmax, [&](int slot, int l, int e, int ext) {
 #pragma unroll
-        for (int k = 0; k < V; k++) {
-            x[k] = expf(x[k] - mx);
-            sum += x[k];
-            if constexpr (NV > 0) cache[slot][k] = x[k];
-        }
-    });
+            for (int k = 0; k < V; k++) {
+                const float x = expf(cache[slot][k] - mx);
+                sum += x;
+                cache[slot][k] = x;
+            }
+        });
+    } else {
+        // long column: one read for both statistics -- every lane keeps a running maximum and a sum
+        // of exponentials shifted by it, rescaled when its maximum moves (the merge rule of the
+        // tile subroutines), and the lanes are merged the same way at the end
+        walk_keys<V, NV>(A, lane, kmax, [&](int slot, int l, int e, int ext) {
+            const T* p = col_ptr<const T>(A, c, l, ext);
+            if (!p) return;
+            float x[V];
+            ldv<V>(p + e, x);
+            const int k0 = l * A.base[0] + e;
+            float vm = kNegInf;
+#pragma unroll
+            for (int k = 0; k < V; k++) {
+                x[k] = (k0 + k < kmax) ? x[k] * scale : kNegInf;
+                vm = fmaxf(vm, x[k]);
+            }
+            if (vm == kNegInf) return;
+            const float m_new = fmaxf(mx, vm);
+            float part = 0.f;
+#pragma unroll
+            for (int k = 0; k < V; k++) part += expf(x[k] - m_new);
+            sum = sum * expf(mx - m_new) + part;        // exp(-inf) = 0 the first time
+            mx = m_new;
+        });
+        const float lane_mx = mx;
+        mx = wave_max(mx);
+        sum *= (lane_mx == kNegInf) ? 0.f : expf(lane_mx - mx);
+    }
     sum = wave_sum(sum);
     const float inv = 1.f / sum;
     // every vector of every present tile is written: masked entries become 0

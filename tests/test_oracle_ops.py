@@ -362,6 +362,66 @@ def test_adam_first_step_closed_form_and_torch():
 
 
 # ------------------------------------------------------------------ bf16 rounding
+def test_embedding_index_map_and_adjoint():
+    N_e, N_v, N_s, N_b = 5, 7, 6, 2
+    W = rng.standard_normal((N_e, N_v))
+    tok = rng.integers(0, N_v, (N_s, N_b))
+    tok[0, 0] = tok[1, 1] = 3                       # a repeated token
+    Y = D.embedding_fwd(W, tok)
+    for e, s, b in itertools.product(range(N_e), range(N_s), range(N_b)):
+        assert Y[e, s, b] == W[e, tok[s, b]]
+    G = rng.standard_normal(Y.shape)
+    dW = D.embedding_bwd(G, tok, N_v)
+    # adjoint identity <Y(W), G> = <W, dW>, column sums by hand, and the library's autograd
+    assert abs((Y * G).sum() - (W * dW).sum()) < 1e-12
+    want3 = sum(G[:, s, b] for s in range(N_s) for b in range(N_b) if tok[s, b] == 3)
+    np.testing.assert_allclose(dW[:, 3], want3, rtol=1e-14)
+    tw = torch.tensor(W.T.copy(), requires_grad=True)                                   # [N_v, N_e]
+    out = torch.nn.functional.embedding(torch.from_numpy(tok.astype(np.int64)), tw)     # [N_s, N_b, N_e]
+    out.backward(torch.from_numpy(G.transpose(1, 2, 0).copy()))
+    np.testing.assert_allclose(dW, tw.grad.numpy().T, rtol=1e-13, atol=1e-15)
+    unused = [v for v in range(N_v) if v not in tok]
+    assert unused and np.all(dW[:, unused] == 0)
+
+
+def test_cross_entropy_by_hand_library_and_differences():
+    N_v, N_s, N_b = 6, 4, 3
+    X = 3.0 * rng.standard_normal((N_v, N_s, N_b))
+    lab = rng.integers(0, N_v, (N_s, N_b))
+    L, losses, dX = D.cross_entropy(X, lab)
+    for s, b in itertools.product(range(N_s), range(N_b)):
+        den = sum(math.exp(X[j, s, b]) for j in range(N_v))
+        assert abs(losses[s, b] + math.log(math.exp(X[lab[s, b], s, b]) / den)) < 1e-12
+    assert abs(L - losses.sum()) < 1e-12
+    # uniform logits: log N_v per column; a shift of a column changes nothing; gradient columns sum to zero
+    L0, _, _ = D.cross_entropy(np.zeros((N_v, N_s, N_b)), lab)
+    assert abs(L0 - N_s * N_b * math.log(N_v)) < 1e-12
+    np.testing.assert_allclose(D.cross_entropy(X + 100.0, lab)[0], L, rtol=1e-12)
+    np.testing.assert_allclose(dX.sum(axis=0), 0.0, atol=1e-14)
+    # library value and autograd
+    tx = torch.tensor(X.transpose(1, 2, 0).reshape(-1, N_v).copy(), requires_grad=True)
+    tl = torch.nn.functional.cross_entropy(tx, torch.from_numpy(lab.reshape(-1).astype(np.int64)), reduction="sum")
+    tl.backward()
+    assert abs(tl.item() - L) < 1e-11
+    np.testing.assert_allclose(dX, tx.grad.numpy().reshape(N_s, N_b, N_v).transpose(2, 0, 1), rtol=1e-12, atol=1e-14)
+    # central differences
+    for _ in range(5):
+        idx = tuple(int(rng.integers(0, n)) for n in X.shape)
+        Xp, Xm = X.copy(), X.copy()
+        Xp[idx] += 1e-6
+        Xm[idx] -= 1e-6
+        fd = (D.cross_entropy(Xp, lab)[0] - D.cross_entropy(Xm, lab)[0]) / 2e-6
+        assert abs(fd - dX[idx]) < 1e-8
+    # over vocabulary tiles with the softmax subroutines' running statistics: the same loss
+    from oracle import tiled as TL
+    A = TL.Tiled.from_array(X, (4, 3, 2))
+    P, stats = TL.softmax_fwd(A, causal=False)
+    Pa, st = P.to_array(), stats.to_array()
+    s_idx, b_idx = np.meshgrid(np.arange(N_s), np.arange(N_b), indexing="ij")
+    np.testing.assert_allclose(-np.log(Pa[lab, s_idx, b_idx]), losses, rtol=1e-12)
+    np.testing.assert_allclose(st[0] + np.log(st[1]) - X[lab, s_idx, b_idx], losses, rtol=1e-12, atol=1e-13)
+
+
 @pytest.mark.parametrize("nesterov", [False, True])
 def test_sgd_momentum_closed_form_and_torch(nesterov):
     p0 = rng.standard_normal(37)
