@@ -11,6 +11,8 @@
 #include "ew_functors.hpp"
 #include "internal.hpp"
 
+#include <type_traits>
+
 #include <algorithm>
 #include <cmath>
 
@@ -40,33 +42,57 @@ struct HeadArgs {
     int32_t n_parts, N_h, h, to_parts;
 };
 
+// A thread owns one vector of V rows of Z and copies it for kHeadTok consecutive tokens (s, b): the
+// decomposition of its row into (part, head, component) and tiles costs integer divisions once, the
+// token's share of the addresses is the same for the whole workgroup (scalar arithmetic), and
+// the copies of a thread are independent loads in flight together.  Along the rows both sides are
+// contiguous (whole rows of Z, runs of h elements of a part).
+constexpr int kHeadTok = 8;
+
 template <typename T, int V>
 __global__ void __launch_bounds__(256) head_kernel(HeadArgs a) {
     const int rows = a.z.shape[0], N_s = a.z.shape[1], N_b = a.z.shape[2];
-    const int64_t nvec = (int64_t)(rows / V) * N_s * N_b;
-    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= nvec) return;
-    const int r = (int)(idx % (rows / V)) * V;
-    const int s = (int)((idx / (rows / V)) % N_s);
-    const int b = (int)(idx / ((int64_t)(rows / V) * N_s));
+    const int r = (blockIdx.x * blockDim.x + threadIdx.x) * V;
+    if (r >= rows) return;
     const int head = r / a.h, i = r - head * a.h;
     const int p = head / a.N_h, j = head - p * a.N_h;
-    const int cz[kMaxDim] = {r, s, b, 0};
-    const int cp[kMaxDim] = {i, s, b, j};
-    int tz, tp;
-    int64_t oz, op;
-    locate(a.z, cz, tz, oz);
     const TiledView& pv = a.part[p];
-    locate(pv, cp, tp, op);
-    T* zp = static_cast<T*>(a.z.tiles[tz]) + oz;
-    T* pp = static_cast<T*>(pv.tiles[tp]) + op;
-    if constexpr (V * sizeof(T) == 16) {
-        if (a.to_parts) *reinterpret_cast<uint4*>(pp) = *reinterpret_cast<const uint4*>(zp);
-        else *reinterpret_cast<uint4*>(zp) = *reinterpret_cast<const uint4*>(pp);
-    } else {
-        if (a.to_parts) *pp = *zp;
-        else *zp = *pp;
+    // row part of the Z address: tile coordinate, position and pitch along axis 0
+    const int zt0 = r / a.z.base[0], zr = r - zt0 * a.z.base[0];
+    const int zext0 = min(a.z.base[0], rows - zt0 * a.z.base[0]);
+    // row part of the part's address: axis 0 (component i) and axis 3 (head j)
+    const int pt0 = i / pv.base[0], pi = i - pt0 * pv.base[0];
+    const int pext0 = min(pv.base[0], a.h - pt0 * pv.base[0]);
+    const int ptj = j / pv.base[3], pj = j - ptj * pv.base[3];
+    const int ntok = N_s * N_b;
+    const int tok0 = blockIdx.y * kHeadTok;
+    using Vec = std::conditional_t<V * sizeof(T) == 16, uint4, T>;
+    Vec val[kHeadTok];
+    T* src[kHeadTok];
+    T* dst[kHeadTok];
+#pragma unroll
+    for (int t = 0; t < kHeadTok; t++) {
+        const int tok = min(tok0 + t, ntok - 1);           // the tail repeats the last token (same value twice)
+        const int b = tok / N_s, s = tok - b * N_s;
+        // all parts are tiled alike, so part 0 stands for their sequence and batch tiling
+        const TiledView& q = a.part[0];
+        const int zs = s / a.z.base[1], zls = zs * a.z.base[1], zes = min(a.z.base[1], N_s - zls);
+        const int zb = b / a.z.base[2], zlb = zb * a.z.base[2];
+        const int qs = s / q.base[1], qls = qs * q.base[1], qes = min(q.base[1], N_s - qls);
+        const int qb = b / q.base[2], qlb = qb * q.base[2], qeb = min(q.base[2], N_b - qlb);
+        const int ztile = zt0 + a.z.grid[0] * (zs + a.z.grid[1] * zb);
+        const int64_t zoff = zr + (int64_t)zext0 * ((s - zls) + zes * (b - zlb));
+        const int ptile = pt0 + q.grid[0] * (qs + q.grid[1] * (qb + q.grid[2] * ptj));
+        const int64_t poff = pi + (int64_t)pext0 * ((s - qls) + (int64_t)qes * ((b - qlb) + qeb * pj));
+        T* zp = static_cast<T*>(a.z.tiles[ztile]) + zoff;
+        T* pp = static_cast<T*>(pv.tiles[ptile]) + poff;
+        src[t] = a.to_parts ? zp : pp;
+        dst[t] = a.to_parts ? pp : zp;
     }
+#pragma unroll
+    for (int t = 0; t < kHeadTok; t++) val[t] = *reinterpret_cast<const Vec*>(src[t]);
+#pragma unroll
+    for (int t = 0; t < kHeadTok; t++) *reinterpret_cast<Vec*>(dst[t]) = val[t];
 }
 
 bool all_aligned(const nnt_tensor* t) {
@@ -430,14 +456,21 @@ static int32_t head_common(nnt_ctx* ctx, nnt_tensor* Z, int32_t n_parts, nnt_ten
         bool vec = all_aligned(Z) && axis0_multiple(Z, V) && h % V == 0;
         for (int p = 0; p < n_parts; p++) vec = vec && all_aligned(parts[p]) && axis0_multiple(parts[p], V);
         const int v = vec ? V : 1;
-        const int64_t nvec = Z->shape[0] / v * Z->shape[1] * Z->shape[2];
-        const int64_t blocks = (nvec + 255) / 256;
-        if (blocks > INT32_MAX) return fail(ctx, NNT_EINVAL, "head split/merge: tensor too large");
+        // workgroup width: the multiple of 64 lanes that wastes the fewest on the row vectors of Z
+        const int64_t rowvecs = Z->shape[0] / v, ntok = Z->shape[1] * Z->shape[2];
+        int bs = 256;
+        int64_t waste = -1;
+        for (int cand = 256; cand >= 64; cand -= 64) {
+            const int64_t w = (rowvecs + cand - 1) / cand * cand - rowvecs;
+            if (waste < 0 || w < waste) { waste = w; bs = cand; }
+        }
+        const int64_t gx = (rowvecs + bs - 1) / bs, gy = (ntok + kHeadTok - 1) / kHeadTok;
+        if (gx > INT32_MAX || gy > 65535) return fail(ctx, NNT_EINVAL, "head split/merge: tensor too large");
         std::vector<Access> acc = {Z->all(to_parts ? kRead : kWrite)};
         for (int p = 0; p < n_parts; p++) acc.push_back(parts[p]->all(to_parts ? kWrite : kRead));
         const int32_t dt = Z->dtype;
         return submit(ctx, acc, [=](hipStream_t st) {
-            dim3 grid((unsigned)blocks), block(256);
+            dim3 grid((unsigned)gx, (unsigned)gy), block((unsigned)bs);
             if (dt == NNT_F32) {
                 if (v == 4) hipLaunchKernelGGL((head_kernel<float, 4>), grid, block, 0, st, a);
                 else hipLaunchKernelGGL((head_kernel<float, 1>), grid, block, 0, st, a);
