@@ -100,7 +100,9 @@ static int32_t launch_any(hipStream_t st, int dtype_in, int dtype_out, int akf, 
     auto general = [&](const GemmArgs& ga, int64_t n) {
         return f32 ? launch_gemm_f32(st, akf, bkf, cfg, ga, n) : launch_gemm_bf16(st, dtype_out == NNT_F32, akf, bkf, cfg, ga, n);
     };
-    if (nfast <= 0) return general(g, nwg);
+    // debugging aid: NNT_GEMM_NO_DL=1 sends every workgroup to the general kernels
+    static const bool no_dl = getenv("NNT_GEMM_NO_DL") != nullptr;
+    if (nfast <= 0 || no_dl) return general(g, nwg);
     int32_t rc = f32 ? launch_gemm_f32_dl(st, akf, bkf, cfg, g, nfast) : launch_gemm_bf16_dl(st, dtype_out == NNT_F32, akf, bkf, cfg, g, nfast);
     if (rc != NNT_OK || nfast == nwg) return rc;
     GemmArgs rest = g;
