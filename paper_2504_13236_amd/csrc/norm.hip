@@ -366,27 +366,40 @@ __global__ void __launch_bounds__(256) rowsum_stage1(RowsumGeom g, float* part) 
 }
 
 // out[r] = (accumulate ? out[r] : 0) + sum_s part[s][r]; the output is a 1-axis tiled tensor or a plain vector.
+constexpr int kStage2Rows = 16;
+
+// gridDim.y = 2 reduces a second set of partial rows (right behind the first) into (otab_b, ob)
 __global__ void __launch_bounds__(256) rowsum_stage2(const float* part, int64_t nslots, int64_t rows_total,
-                                                      void* const* otab, float* o1, int base0, int accumulate) {
-    // 64 rows per block; the four wavefronts take every fourth partial row, then combine through LDS
-    __shared__ float red[4][64];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int64_t r = (int64_t)blockIdx.x * 64 + lane;
+                                                      void* const* otab, float* o1, int base0, int accumulate,
+                                                      void* const* otab_b, float* ob) {
+    if (blockIdx.y) {
+        part += nslots * rows_total;
+        otab = otab_b;
+        o1 = ob;
+    }
+    // 16 rows per block (64-byte runs of a partial row); 16 groups of lanes take every sixteenth partial
+    // row, four loads in flight each, then combine through LDS in a fixed order.  The grid is small
+    // (rows / 16 blocks), so the kernel is bound by the latency of its load chain: many short chains.
+    __shared__ float red[16][17];
+    const int rl = threadIdx.x & 15, kg = threadIdx.x >> 4;
+    const int64_t r = (int64_t)blockIdx.x * kStage2Rows + rl;
     float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
     if (r < rows_total) {
-        int64_t k = wave;
-        for (; k + 12 < nslots; k += 16) {
+        int64_t k = kg;
+        for (; k + 48 < nslots; k += 64) {
             s0 += part[k * rows_total + r];
-            s1 += part[(k + 4) * rows_total + r];
-            s2 += part[(k + 8) * rows_total + r];
-            s3 += part[(k + 12) * rows_total + r];
+            s1 += part[(k + 16) * rows_total + r];
+            s2 += part[(k + 32) * rows_total + r];
+            s3 += part[(k + 48) * rows_total + r];
         }
-        for (; k < nslots; k += 4) s0 += part[k * rows_total + r];
+        for (; k < nslots; k += 16) s0 += part[k * rows_total + r];
     }
-    red[wave][lane] = (s0 + s1) + (s2 + s3);
+    red[kg][rl] = (s0 + s1) + (s2 + s3);
     __syncthreads();
-    if (wave == 0 && r < rows_total) {
-        const float s = (red[0][lane] + red[1][lane]) + (red[2][lane] + red[3][lane]);
+    if (kg == 0 && r < rows_total) {
+        float s = 0.f;
+#pragma unroll
+        for (int q = 0; q < 16; q++) s += red[q][rl];
         float* o = otab ? static_cast<float*>(otab[r / base0]) + (r % base0) : o1 + r;
         *o = accumulate ? *o + s : s;
     }
@@ -423,11 +436,9 @@ int32_t rowsum_single(hipStream_t st, int dtype, int mode, int64_t m, int64_t n,
     if (dtype == NNT_F32) rc = mode ? launch_rowsum_t<float, 1>(st, g, vv, v1, 1, vec, scratch) : launch_rowsum_t<float, 0>(st, g, vv, v1, 1, vec, scratch);
     else rc = mode ? launch_rowsum_t<bf16_t, 1>(st, g, vv, v1, 1, vec, scratch) : launch_rowsum_t<bf16_t, 0>(st, g, vv, v1, 1, vec, scratch);
     if (rc != NNT_OK) return rc;
-    const unsigned blocks = (unsigned)((m + 63) / 64);
-    hipLaunchKernelGGL(rowsum_stage2, dim3(blocks), dim3(256), 0, st, scratch, (int64_t)g.splits, m, nullptr, out0, 1, accumulate);
-    if (mode)
-        hipLaunchKernelGGL(rowsum_stage2, dim3(blocks), dim3(256), 0, st, scratch + (int64_t)g.splits * m, (int64_t)g.splits, m,
-                           nullptr, out1, 1, accumulate);
+    const unsigned blocks = (unsigned)((m + kStage2Rows - 1) / kStage2Rows);
+    hipLaunchKernelGGL(rowsum_stage2, dim3(blocks, mode ? 2 : 1), dim3(256), 0, st, scratch, (int64_t)g.splits, m, nullptr, out0, 1,
+                       accumulate, nullptr, out1);
     return hipGetLastError() == hipSuccess ? NNT_OK : NNT_EHIP;
 }
 
@@ -477,12 +488,11 @@ int32_t rowsum_tensor(nnt_ctx* ctx, int mode, nnt_tensor* dY, nnt_tensor* X, nnt
         if (dtype == NNT_F32) r = mode ? launch_rowsum_t<float, 1>(st, g, vv, v1, ntiles, vec, scratch) : launch_rowsum_t<float, 0>(st, g, vv, v1, ntiles, vec, scratch);
         else r = mode ? launch_rowsum_t<bf16_t, 1>(st, g, vv, v1, ntiles, vec, scratch) : launch_rowsum_t<bf16_t, 0>(st, g, vv, v1, ntiles, vec, scratch);
         if (r != NNT_OK) return r;
-        const unsigned blocks = (unsigned)((rows + 63) / 64);
-        hipLaunchKernelGGL(rowsum_stage2, dim3(blocks), dim3(256), 0, st, scratch, nslots, rows, o0, nullptr, base0, 0);
-        if (mode)
-            hipLaunchKernelGGL(rowsum_stage2, dim3(blocks), dim3(256), 0, st, scratch + nslots * rows, nslots, rows, o1, nullptr, base0, 0);
+        const unsigned blocks = (unsigned)((rows + kStage2Rows - 1) / kStage2Rows);
+        hipLaunchKernelGGL(rowsum_stage2, dim3(blocks, mode ? 2 : 1), dim3(256), 0, st, scratch, nslots, rows, o0, nullptr, base0, 0,
+                           o1, nullptr);
         return hipGetLastError() == hipSuccess ? (int32_t)NNT_OK : (int32_t)NNT_EHIP;
-    }, mode ? 3 : 2);
+    }, 2);
 }
 
 bool tensors_vec_ok(std::initializer_list<const nnt_tensor*> ts, int V) {
@@ -794,7 +804,7 @@ int32_t nnt_layernorm_bwd(nnt_ctx* ctx, nnt_tensor* X, nnt_tensor* stats, nnt_te
                                       dgamma->one(l, acc ? kReadWrite : kWrite), dbeta->one(l, acc ? kReadWrite : kWrite)};
             rc = submit(ctx, a1, [=](hipStream_t st) {
                 return rowsum_single(st, dtype, 1, m, n, dyp, xp, sp, dgp, dbp, acc, pscratch);
-            }, 3);
+            }, 2);
             if (rc != NNT_OK) return rc;
             std::vector<Access> a2 = {X->one(t, kRead), dY->one(t, kRead), stats->one(r, kRead), gamma->one(l, kRead), scr,
                                       dX->one(t, kWrite)};
