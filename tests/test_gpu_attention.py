@@ -38,6 +38,9 @@ CASES = [
     ((64, 330, 1, 3), 400, 1, 2),
     ((64, 72, 3, 1), 40, 2, 1),
     ((128, 160, 1, 2), 160, 1, 1),
+    ((64, 1, 1, 1), 1, 1, 1),              # a single position: P = 1, B = V
+    ((64, 33, 2, 1), 7, 1, 1),             # tiles far smaller than a streamed block
+    ((128, 200, 2, 1), 72, 2, 1),          # head size 128 on ragged tiles
 ]
 
 
@@ -71,6 +74,33 @@ def test_fused_attention(mods, case, dtype, causal, gran):
         # a second call overwrites, it does not accumulate
         capi.nnt_attention_bwd(ctx.h, tQ.h, tK.h, tV.h, tB.h, tS.h, tdB.h, scale, causal, tdQ.h, tdK.h, tdV.h)
         check(tdK.download(), dK, dtype, "attention dK, second call")
+
+
+def test_fused_attention_survives_large_scores(mods):
+    """Scores of several hundred: the running maximum keeps every exponent at or below zero."""
+    capi, tiled = mods
+    r = np.random.default_rng(5)
+    shape, base = (64, 96, 1, 2), (64, 48, 1, 2)
+    Q, K, V = (r.standard_normal(shape) for _ in range(3))
+    Q *= 30.0
+    K *= 30.0
+    Q, K, V = (quant(x, "f32") for x in (Q, K, V))
+    B, _ = D.attention_fwd(Q, K, V, causal=True)
+    with tiled.Context(n_streams=1) as ctx:
+        tQ, tK, tV = (T(tiled, ctx, x, base, "f32") for x in (Q, K, V))
+        tB = tiled.TiledTensor(ctx, "f32", shape, base)
+        tS = tiled.TiledTensor(ctx, "f32", (2, 96, 1, 2), (2, 48, 1, 2))
+        capi.nnt_attention_fwd(ctx.h, tQ.h, tK.h, tV.h, 0.125, 1, tB.h, tS.h)
+        got = tB.download()
+        assert np.all(np.isfinite(got))
+        # exp(x) carries the rounding of its argument: a score of magnitude |x| held in fp32 is off by up to
+        # |x| 2^-24, and so is the probability, relatively.  The bound scales with the largest score.
+        big = float(np.abs(D.attention_scores(K, Q)).max())
+        assert big > 300
+        err = float(np.abs(got - B).max() / np.abs(B).max())
+        assert err <= 8 * big * 2.0 ** -24, (err, big)
+        with pytest.raises(capi.NntError):
+            capi.nnt_attention_fwd(ctx.h, tQ.h, tK.h, tV.h, -0.125, 1, tB.h, tS.h)      # scale must be positive
 
 
 def test_fused_attention_rejects_bad_operands(mods):
