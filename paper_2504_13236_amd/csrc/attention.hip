@@ -596,14 +596,23 @@ __global__ void __launch_bounds__(256, 2) attn_dkv(const BwdArgs a) {
             for (int sub = sub0; sub < nsub; sub++) {
                 f32x16 s = X::template rows_times_own<LD>(Qs, sub, ln, hh, kf);
                 const f32x16 dp = X::template rows_times_own<LD>(Ds, sub, ln, hh, vf);
+                // log-sum-exp and D of the 16 queries this lane's accumulator registers stand for: four runs of four
+                float lse_r[16], d_r[16];
+#pragma unroll
+                for (int q4 = 0; q4 < 4; q4++) {
+                    const float4 a4 = *reinterpret_cast<const float4*>(lses + 32 * sub + 8 * q4 + 4 * hh);
+                    const float4 b4 = *reinterpret_cast<const float4*>(dsum + 32 * sub + 8 * q4 + 4 * hh);
+                    lse_r[4 * q4] = a4.x; lse_r[4 * q4 + 1] = a4.y; lse_r[4 * q4 + 2] = a4.z; lse_r[4 * q4 + 3] = a4.w;
+                    d_r[4 * q4] = b4.x; d_r[4 * q4 + 1] = b4.y; d_r[4 * q4 + 2] = b4.z; d_r[4 * q4 + 3] = b4.w;
+                }
                 typename X::Packed pk;
 #pragma unroll
                 for (int r = 0; r < 16; r++) {
                     const int ql = 32 * sub + acc_row(r, hh);
                     const bool ok = plain || (qloc0 + ql < ext_q && (!g.causal || kglob <= qglob0 + ql));
-                    const float p = ok ? __builtin_amdgcn_exp2f(s[r] * sc2 - lses[ql]) : 0.f;
+                    const float p = ok ? __builtin_amdgcn_exp2f(s[r] * sc2 - lse_r[r]) : 0.f;
                     X::set(pk, r, p);
-                    s[r] = p * (dp[r] - dsum[ql]);
+                    s[r] = p * (dp[r] - d_r[r]);
                 }
                 X::template cols_times_acc<LD>(dV, Ds, sub, lane, pk);
                 X::pack(s, pk);
