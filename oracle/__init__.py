@@ -5,12 +5,16 @@ Plain numpy, fp64, written from the paper's statement of the operations
 design notes.  Two modules:
 
   definition.py  the untiled definition of every operation, the block forward,
-                 its analytic adjoint and the Adam step.  Tiling only regroups
-                 sums, so this is what any tiled execution must reproduce.
+                 its analytic adjoint, the Adam and SGD-with-momentum steps,
+                 the embedding layer and the cross-entropy loss.  Tiling only
+                 regroups sums, so this is what any tiled execution must
+                 reproduce.
   tiled.py       the same operations carried out tile by tile in the order the
                  paper describes (products and sums of elementary tiles for the
                  linear layer, three steps for layer norm, two subroutines for
-                 softmax).  It exists to pin tiling invariance.
+                 softmax), and attention walked key tile by key tile with the
+                 softmax subroutines' running statistics, with its recomputing
+                 adjoint.  It exists to pin tiling invariance.
 
 Only tests/, the smoke check and the benchmark's cpu_baseline leg may import
 this package.  It shares no code with the HIP library and never calls it.
