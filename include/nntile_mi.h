@@ -129,6 +129,21 @@ typedef struct nnt_profile_entry {
 NNT_API int32_t nnt_profile_enable(nnt_ctx* ctx, int32_t on);
 NNT_API int32_t nnt_profile_read(nnt_ctx* ctx, nnt_profile_entry* out, int32_t capacity, int32_t* n_out);
 
+/* Host-only replay of the executor's decisions (section 2, task submission: tasks are
+ * submitted in sequence and run asynchronously, ordered only by their data): for
+ * n_tasks tasks over n_tiles tiles -- task t accesses the tiles
+ * acc_tile[task_first[t] .. task_first[t+1]-1] with the modes acc_mode[...]
+ * (1 read, 2 write, 3 read-write) -- reports the stream each task would run on, its
+ * sequence number on that stream, and per task NNT_MAX_STREAMS entries: the sequence
+ * number on every other stream that it would wait for (0 = none).  Uses the same
+ * code as the executor, touches no device: it lets a test check on the CPU that
+ * every read-after-write, write-after-read and write-after-write pair is ordered.
+ * All pointers are host memory. */
+#define NNT_MAX_STREAMS 8
+NNT_API int32_t nnt_sched_simulate(int32_t n_streams, int32_t serial, int32_t n_tiles, int32_t n_tasks,
+                           const int32_t* task_first, const int32_t* acc_tile, const int32_t* acc_mode,
+                           int32_t* stream_out, int64_t* seq_out, int64_t* wait_seq_out);
+
 /* Stream capture of the task flow into a HIP graph (section 2: the graph of a
  * training iteration repeats, so it can be built once and replayed).  Between
  * begin and end, tensor-level calls are recorded instead of run; every plan they

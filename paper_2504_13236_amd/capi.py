@@ -97,6 +97,7 @@ PROTOTYPES = {
     "nnt_capture_end": (_i32, [_p, _pp]),
     "nnt_graph_launch": (_i32, [_p]),
     "nnt_graph_destroy": (_i32, [_p]),
+    "nnt_sched_simulate": (_i32, [_i32, _i32, _i32, _i32, _p, _p, _p, _p, _p, _p]),
     "nnt_tiling_ntiles": (_i32, [_i32, _pi64, _pi64, _pi64]),
     "nnt_tiling_tile_shape": (_i32, [_i32, _pi64, _pi64, _i64, _pi64]),
     "nnt_tensor_create": (_i32, [_p, _i32, _i32, _pi64, _pi64, _pp, _pp]),
@@ -168,7 +169,7 @@ PROTOTYPES = {
 # functions whose first argument is a context (their failures carry nnt_last_error text)
 _CTX_FIRST = {n for n, (r, a) in PROTOTYPES.items()
               if n.startswith("nnt_") and not n.startswith("nnt_tile_") and not n.startswith("nnt_tiling_")
-              and n not in ("nnt_ctx_create", "nnt_version", "nnt_gpt2_block_slot", "nnt_last_error")
+              and n not in ("nnt_ctx_create", "nnt_version", "nnt_gpt2_block_slot", "nnt_last_error", "nnt_sched_simulate")
               and not n.startswith("nnt_tensor_") and not n.startswith("nnt_graph_")
               and not n.startswith("nnt_gpt2_block_")
               and (not n.startswith("nnt_gpt2_stack_") or n == "nnt_gpt2_stack_create")}

@@ -75,12 +75,18 @@ void profile_mark(nnt_ctx* ctx, hipStream_t st, const char* label, double work, 
     p->launches = 1;
 }
 
-int32_t submit(nnt_ctx* ctx, const std::vector<Access>& acc,
-               const std::function<int32_t(hipStream_t)>& launch, int n_launches) {
-    NNT_CHECK_CTX(ctx);
-    // While a capture is open only streams 0 and 1 take tasks: ending a capture in which two forked
-    // streams wait on each other's events has crashed inside the HIP runtime on this ROCm release.
-    const int ns = ctx->capturing ? std::min(ctx->n_streams, 2) : ctx->n_streams;
+// Where a task goes and what it has to wait for: pure bookkeeping, no device calls (the host-side
+// simulation below runs the same two functions).
+struct TaskPlan {
+    int chosen;                          // stream of the task
+    uint64_t wait_seq[kMaxStreams];      // per other stream: sequence number to wait for, 0 = none
+};
+
+// A task must run after the last writer of every tile it touches (read-after-write, write-after-write)
+// and, if it writes, after every reader since that write (write-after-read).  One sequence number
+// per stream is enough because a stream runs its tasks in order.
+static TaskPlan plan_task(const std::vector<Access>& acc, int ns, bool serial, const uint64_t* tail_seq,
+                          const uint64_t* synced_seq, uint64_t (*waited)[kMaxStreams], int* rr) {
     uint64_t need[kMaxStreams] = {0, 0, 0, 0, 0, 0, 0, 0};
     for (const Access& a : acc) {
         for (int64_t i = 0; i < a.count; i++) {
@@ -91,31 +97,63 @@ int32_t submit(nnt_ctx* ctx, const std::vector<Access>& acc,
         }
     }
     for (int s = 0; s < ns; s++)
-        if (need[s] <= ctx->synced_seq[s]) need[s] = 0;
+        if (need[s] <= synced_seq[s]) need[s] = 0;
 
     // Stream choice: stay behind a producer whose task is the tail of its stream
     // (no wait needed at all); otherwise take the next stream in turn, so that
     // independent consumers of one result spread over the streams.
+    TaskPlan plan = {};
     int chosen = -1;
-    if (ctx->serial || ns == 1) {
+    if (serial || ns == 1) {
         chosen = 0;
     } else {
         uint64_t best = 0;
         for (int s = 0; s < ns; s++)
-            if (need[s] && need[s] == ctx->tail_seq[s] && need[s] >= best) { best = need[s]; chosen = s; }
+            if (need[s] && need[s] == tail_seq[s] && need[s] >= best) { best = need[s]; chosen = s; }
         if (chosen < 0) {
-            // prefer an idle-looking stream: one none of whose work is needed and that is not the last used
-            ctx->rr = (ctx->rr + 1) % ns;
-            chosen = ctx->rr;
+            *rr = (*rr + 1) % ns;
+            chosen = *rr;
         }
     }
-    hipStream_t st = ctx->streams[chosen];
+    plan.chosen = chosen;
     for (int s = 0; s < ns; s++) {
         if (s == chosen || !need[s]) continue;
-        if (ctx->waited[chosen][s] >= need[s]) continue;
-        hipEvent_t ev = ctx->events[s][need[s] - ctx->synced_seq[s] - 1];
+        if (waited[chosen][s] >= need[s]) continue;      // an earlier task of this stream already waited that far
+        plan.wait_seq[s] = need[s];
+        waited[chosen][s] = need[s];
+    }
+    return plan;
+}
+
+// The task with sequence number `seq` on stream `chosen` becomes the last user of its tiles.
+static void commit_task(const std::vector<Access>& acc, int chosen, uint64_t seq) {
+    for (const Access& a : acc) {
+        for (int64_t i = 0; i < a.count; i++) {
+            TileDep& d = a.first[i];
+            if (a.mode & kWrite) {
+                d.w_stream = chosen;
+                d.w_seq = seq;
+                std::memset(d.r_seq, 0, sizeof(d.r_seq));
+            } else {
+                d.r_seq[chosen] = seq;
+            }
+        }
+    }
+}
+
+int32_t submit(nnt_ctx* ctx, const std::vector<Access>& acc,
+               const std::function<int32_t(hipStream_t)>& launch, int n_launches) {
+    NNT_CHECK_CTX(ctx);
+    // While a capture is open only streams 0 and 1 take tasks: ending a capture in which two forked
+    // streams wait on each other's events has crashed inside the HIP runtime on this ROCm release.
+    const int ns = ctx->capturing ? std::min(ctx->n_streams, 2) : ctx->n_streams;
+    const TaskPlan plan = plan_task(acc, ns, ctx->serial, ctx->tail_seq, ctx->synced_seq, ctx->waited, &ctx->rr);
+    const int chosen = plan.chosen;
+    hipStream_t st = ctx->streams[chosen];
+    for (int s = 0; s < ns; s++) {
+        if (!plan.wait_seq[s]) continue;
+        hipEvent_t ev = ctx->events[s][plan.wait_seq[s] - ctx->synced_seq[s] - 1];
         NNT_HIP(ctx, hipStreamWaitEvent(st, ev, 0));
-        ctx->waited[chosen][s] = need[s];
         ctx->stats.event_waits++;
     }
     nnt_ctx::ProfileRec prof;
@@ -151,18 +189,7 @@ int32_t submit(nnt_ctx* ctx, const std::vector<Access>& acc,
     if (erc != NNT_OK) return erc;
     NNT_HIP(ctx, hipEventRecord(ev, st));
     ctx->events[chosen].push_back(ev);
-    for (const Access& a : acc) {
-        for (int64_t i = 0; i < a.count; i++) {
-            TileDep& d = a.first[i];
-            if (a.mode & kWrite) {
-                d.w_stream = chosen;
-                d.w_seq = seq;
-                std::memset(d.r_seq, 0, sizeof(d.r_seq));
-            } else {
-                d.r_seq[chosen] = seq;
-            }
-        }
-    }
+    commit_task(acc, chosen, seq);
     // bound the number of live events in long runs without nnt_wait
     if (!ctx->capturing && ctx->events[chosen].size() > (1u << 16)) return sync_all(ctx);
     return NNT_OK;
@@ -195,6 +222,30 @@ struct nnt_graph {
 extern "C" {
 
 const char* nnt_version(void) { return "nntile_mi 0.1 (gfx950)"; }
+
+int32_t nnt_sched_simulate(int32_t n_streams, int32_t serial, int32_t n_tiles, int32_t n_tasks, const int32_t* task_first,
+                           const int32_t* acc_tile, const int32_t* acc_mode, int32_t* stream_out, int64_t* seq_out,
+                           int64_t* wait_seq_out) {
+    if (n_streams < 1 || n_streams > kMaxStreams || n_tiles < 0 || n_tasks < 0) return NNT_EINVAL;
+    if (n_tasks > 0 && (!task_first || !acc_tile || !acc_mode || !stream_out || !seq_out || !wait_seq_out)) return NNT_EINVAL;
+    std::vector<TileDep> tiles((size_t)n_tiles);
+    uint64_t tail[kMaxStreams] = {0}, synced[kMaxStreams] = {0}, waited[kMaxStreams][kMaxStreams] = {{0}};
+    int rr = 0;
+    for (int t = 0; t < n_tasks; t++) {
+        std::vector<Access> acc;
+        for (int i = task_first[t]; i < task_first[t + 1]; i++) {
+            if (acc_tile[i] < 0 || acc_tile[i] >= n_tiles || acc_mode[i] < kRead || acc_mode[i] > kReadWrite) return NNT_EINVAL;
+            acc.push_back(Access{&tiles[(size_t)acc_tile[i]], 1, acc_mode[i]});
+        }
+        const TaskPlan plan = plan_task(acc, n_streams, serial != 0, tail, synced, waited, &rr);
+        const uint64_t seq = ++tail[plan.chosen];
+        commit_task(acc, plan.chosen, seq);
+        stream_out[t] = plan.chosen;
+        seq_out[t] = (int64_t)seq;
+        for (int s = 0; s < kMaxStreams; s++) wait_seq_out[(size_t)t * kMaxStreams + s] = (int64_t)plan.wait_seq[s];
+    }
+    return NNT_OK;
+}
 
 int32_t nnt_ctx_create(int32_t device, int32_t n_streams, void* const* caller_streams, nnt_ctx** out) {
     if (!out || n_streams < 1 || n_streams > kMaxStreams) return NNT_EINVAL;

@@ -143,3 +143,92 @@ def test_build_guard_finds_scratch_only_inside_loops():
         "a.hip:1:1: remark:     LDS Size [bytes/block]: 61440 [-Rpass-analysis=kernel-resource-usage]",
     ])
     assert resource_usage(remarks) == {"_Z6kernelv": {"VGPRs": 72, "ScratchSize": 8, "LDS Size": 61440}}
+
+
+def _simulate(capi, n_streams, serial, n_tiles, tasks):
+    import numpy as np
+    first = np.zeros(len(tasks) + 1, np.int32)
+    tiles, modes = [], []
+    for t, acc in enumerate(tasks):
+        for tile, mode in acc:
+            tiles.append(tile)
+            modes.append(mode)
+        first[t + 1] = len(tiles)
+    tiles, modes = np.asarray(tiles, np.int32), np.asarray(modes, np.int32)
+    stream = np.zeros(len(tasks), np.int32)
+    seq = np.zeros(len(tasks), np.int64)
+    waits = np.zeros((len(tasks), 8), np.int64)
+    capi.nnt_sched_simulate(n_streams, serial, n_tiles, len(tasks), first.ctypes.data, tiles.ctypes.data, modes.ctypes.data,
+                            stream.ctypes.data, seq.ctypes.data, waits.ctypes.data)
+    return stream, seq, waits
+
+
+@pytest.mark.parametrize("n_streams", [1, 2, 4, 8])
+def test_executor_orders_every_conflicting_pair(capi, n_streams):
+    """Host-side race check of the task executor's decisions: for random task sequences, every pair of
+    tasks that touch a common tile, at least one of them writing, must be ordered by the happens-before
+    relation that stream order and the event waits generate (read-after-write, write-after-read,
+    write-after-write); tasks that only share read tiles need not be."""
+    import numpy as np
+    r = np.random.default_rng(100 + n_streams)
+    for trial in range(20):
+        n_tiles = int(r.integers(1, 9))
+        n_tasks = int(r.integers(5, 120))
+        tasks = []
+        for _ in range(n_tasks):
+            k = int(r.integers(1, min(4, n_tiles) + 1))
+            chosen = r.choice(n_tiles, size=k, replace=False)
+            tasks.append([(int(t), int(r.choice([1, 1, 2, 3]))) for t in chosen])
+        stream, seq, waits = _simulate(capi, n_streams, 0, n_tiles, tasks)
+        assert stream.min() >= 0 and stream.max() < n_streams
+        at = {(int(stream[t]), int(seq[t])): t for t in range(n_tasks)}
+        assert len(at) == n_tasks                                  # sequence numbers are unique per stream
+        before = []                                                # before[t]: the tasks known to finish before t starts
+        last_on = {}
+        for t in range(n_tasks):
+            s = int(stream[t])
+            assert int(seq[t]) == sum(1 for u in range(t + 1) if stream[u] == s)     # streams number their tasks 1, 2, ...
+            anc = set()
+            preds = []
+            if s in last_on:
+                preds.append(last_on[s])
+            for o in range(8):
+                if waits[t, o]:
+                    assert o != s and o < n_streams
+                    preds.append(at[(o, int(waits[t, o]))])
+            for p in preds:
+                assert p < t
+                anc.add(p)
+                anc |= before[p]
+            before.append(anc)
+            last_on[s] = t
+        for j in range(n_tasks):
+            for i in range(j):
+                for ti, mi in tasks[i]:
+                    for tj, mj in tasks[j]:
+                        if ti == tj and ((mi | mj) & 2):
+                            assert i in before[j], (trial, i, j, tasks[i], tasks[j])
+    # serial mode keeps everything on one stream
+    stream, seq, waits = _simulate(capi, n_streams, 1, 3, [[(0, 2)], [(1, 2)], [(0, 1), (1, 1)], [(2, 3)]])
+    assert not stream.any() and not waits.any()
+
+
+def test_executor_spreads_independent_tasks_and_chains_dependent_ones(capi):
+    # four independent writers land on four streams; a reader of all of them waits for the other three
+    tasks = [[(t, 2)] for t in range(4)] + [[(0, 1), (1, 1), (2, 1), (3, 1)]]
+    stream, seq, waits = _simulate(capi, 4, 0, 4, tasks)
+    assert sorted(stream[:4].tolist()) == [0, 1, 2, 3]
+    assert (waits[4] > 0).sum() == 3
+    # a chain on one tile stays on the producer's stream and needs no event at all
+    stream, seq, waits = _simulate(capi, 4, 0, 1, [[(0, 3)] for _ in range(6)])
+    assert len(set(stream.tolist())) == 1 and not waits.any()
+    # bad arguments
+    import numpy as np
+    z = np.zeros(8, np.int64)
+    assert capi.nnt_sched_simulate.raw(0, 0, 1, 0, None, None, None, None, None, None) == capi.NNT_EINVAL
+    first = np.asarray([0, 1], np.int32)
+    bad_tile = np.asarray([5], np.int32)
+    mode = np.asarray([1], np.int32)
+    out_s = np.zeros(1, np.int32)
+    assert capi.nnt_sched_simulate.raw(2, 0, 1, 1, first.ctypes.data, bad_tile.ctypes.data, mode.ctypes.data,
+                                       out_s.ctypes.data, z.ctypes.data, z.ctypes.data) == capi.NNT_EINVAL
