@@ -111,6 +111,7 @@ template <int H_> struct F32Traits {
     static constexpr int LD = H + 1;
     // pitch for a block that is only read column-wise: puts the two lane halves 32 banks apart
     static constexpr int LD_COLS = H + 8;
+    static constexpr int kDkvBlocks = 2;
     struct Own { float v[H / 2]; };                   // elements s + (H/2) hh of the lane's row
     struct Packed { f32x16 v; };
 
@@ -179,6 +180,7 @@ template <int H_> struct Bf16Traits {
     // Column-wise fragments are transposing reads (ds_read_b64_tr_b16) of 4 rows x 64 bytes per half
     // wave: rows 64 bytes apart modulo 256 keep the four rows on different banks.
     static constexpr int LD_COLS = H + 32;
+    static constexpr int kDkvBlocks = H == 64 ? 2 : 1;
     struct Own { bf16x8 v[H / 16]; };                 // elements 16 s + 8 hh .. + 7 of the lane's row
     struct Packed { bf16x8 v[2]; };                   // registers 8 m .. 8 m + 7 of an accumulator, rounded
 
@@ -517,8 +519,10 @@ __global__ void __launch_bounds__(256, 2) attn_dq(const BwdArgs a) {
 }
 
 // ---------------------------------------------------------------- dK and dV (reads aux)
+// (bf16 with head size 128 needs more than 256 registers per lane for its four accumulator sets and two
+// fragment sets: compiled for one workgroup per CU it keeps them all, for two it spills and runs 3x slower)
 template <class X>
-__global__ void __launch_bounds__(256, 2) attn_dkv(const BwdArgs a) {
+__global__ void __launch_bounds__(256, X::kDkvBlocks) attn_dkv(const BwdArgs a) {
     using T = typename X::T;
     constexpr int H = X::H, LD = X::LD;
     constexpr int kAuxElems = 2 * kBlk * (int)(sizeof(float) / sizeof(T));   // 2 x 64 floats, in units of T
