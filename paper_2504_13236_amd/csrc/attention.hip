@@ -49,7 +49,7 @@ struct AttnGeom {
 };
 
 struct Slab {
-    int64_t off;   // element offset of (0, 0, b, j) in its tile, in units of one first-axis element
+    int64_t off;   // where (0, 0, b, j) sits in its tile, counted in rows (a row = the first-axis elements of one position)
     int tile;      // tile number
     int ext;       // extent of the tile along the sequence axis
 };
@@ -288,10 +288,6 @@ struct FwdArgs {
     AttnGeom g;
     void* const* Q; void* const* K; void* const* V; void* const* O; void* const* stats;
 };
-
-// Which rows of the streamed block a wave has to look at: `nsub` sub-blocks of 32, and whether any
-// of their entries is masked or beyond the tile.
-struct Visible { int nsub; bool plain; };
 
 // ---------------------------------------------------------------- forward
 template <class X>
