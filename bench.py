@@ -126,6 +126,29 @@ def tile_kernels(cfg, capi, torch):
         tf = 2.0 * m * n * k / med / 1e9
         out["products"].append({"name": name, "op": opA + opB, "m": m, "n": n, "k": k, "median_us": med * 1e3, "min_us": mn * 1e3,
                                 "TFLOP/s": tf, "frac_mfma_peak": tf / PEAK_TFLOPS[cfg.dtype]})
+    # the weight-gradient shape again through the tensor-level operation, whose plan may cut the long
+    # contraction into slices (the stateless tile call has no workspace and leaves most CUs idle here)
+    from paper_2504_13236_amd import tiled as _tiled
+    with _tiled.Context(n_streams=1) as ctx:
+        m, n, k = cfg.N_m, cfg.N_e, T
+        tA = _tiled.TiledTensor(ctx, cfg.dtype, (m, k), (m, k))
+        tB = _tiled.TiledTensor(ctx, cfg.dtype, (n, k), (n, k))
+        tC = _tiled.TiledTensor(ctx, "f32", (m, n), (m, n))
+        for t_ in (tA, tB):
+            t_.tile_view(0).normal_()
+        for _ in range(3):
+            capi.nnt_gemm(ctx.h, 1.0, 0, tA.h, 1, tB.h, 0.0, tC.h, 1, 0, None)
+        ctx.wait()
+        ctx.profile(True)
+        for _ in range(12):
+            capi.nnt_gemm(ctx.h, 1.0, 0, tA.h, 1, tB.h, 0.0, tC.h, 1, 0, None)
+        ctx.wait()
+        rec = ctx.profile_read()
+        ms = sum(e["ms"] for e in rec.values()) / 12
+        tf = 2.0 * m * n * k / ms / 1e9
+        out["products"].append({"name": "dW = dY X^T through nnt_gemm (k cut into slices, sum kernel included)", "op": "NT", "m": m, "n": n,
+                                "k": k, "median_us": ms * 1e3, "min_us": ms * 1e3, "TFLOP/s": tf,
+                                "frac_mfma_peak": tf / PEAK_TFLOPS[cfg.dtype]})
     # attention products, batched over (batch, head), one sequence-tile pair
     ts_ = min(t, cfg.N_s)
     h, nb = cfg.N_e // cfg.N_h, cfg.N_b * cfg.N_h
