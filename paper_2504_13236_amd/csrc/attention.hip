@@ -107,8 +107,9 @@ template <int H_> struct F32Traits {
     static constexpr int kPer = 4;                    // elements per Vec
     static constexpr int kVec = H / 16;               // Vec per thread per block (64 rows x H / 4 over 256 threads)
     // v_mfma_f32_32x32x2_f32: a lane supplies one element per instruction, half hh the k index hh.
-    // Odd row pitch: row-wise and column-wise fragment reads both spread over the banks.
-    static constexpr int LD = H + 1;
+    // Row pitch H + 4: rows stay 16-byte aligned, so a lane fetches four k-steps of its row with one
+    // 128-bit read, and 16 lanes (rows r .. r+15, 4 r + c modulo 64) cover all 64 banks.
+    static constexpr int LD = H + 4;
     // pitch for a block that is only read column-wise: puts the two lane halves 32 banks apart
     static constexpr int LD_COLS = H + 8;
     static constexpr int kDkvBlocks = 2;
@@ -142,10 +143,17 @@ template <int H_> struct F32Traits {
     }
     template <int LDX>
     static __device__ __forceinline__ f32x16 rows_times_own(const T* lds, int sub, int ln, int hh, const Own& o) {
-        const T* p = lds + (32 * sub + ln) * LDX + (H / 2) * hh;
-        f32x16 acc = __builtin_amdgcn_mfma_f32_32x32x2f32(p[0], o.v[0], zero16(), 0, 0, 0);
+        static_assert(LDX % 4 == 0, "128-bit fragment reads need 16-byte aligned rows");
+        const float4* p = reinterpret_cast<const float4*>(lds + (32 * sub + ln) * LDX + (H / 2) * hh);
+        f32x16 acc = zero16();
 #pragma unroll
-        for (int k = 1; k < H / 2; k++) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(p[k], o.v[k], acc, 0, 0, 0);
+        for (int k4 = 0; k4 < H / 8; k4++) {
+            const float4 a = p[k4];
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, o.v[4 * k4], acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, o.v[4 * k4 + 1], acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, o.v[4 * k4 + 2], acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, o.v[4 * k4 + 3], acc, 0, 0, 0);
+        }
         return acc;
     }
     static __device__ __forceinline__ void pack(const f32x16& x, Packed& pk) { pk.v = x; }
