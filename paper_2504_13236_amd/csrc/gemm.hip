@@ -79,8 +79,20 @@ struct GemmPlan {
     SplitReduce* d_red = nullptr;
     float* d_ws = nullptr;
     TileDep ws_dep;
+    // Per-tile launches: a task that has only a few macro-tiles but a long contraction (a tile of a
+    // weight gradient: 256 x 256 over all tokens) would leave the chip idle, so its contraction is cut
+    // the same way, into its own scratch block (tasks of one operation run concurrently on several
+    // streams), followed by the slice sum over just that task's macro-tiles.
+    struct TileSplit { int64_t wg0 = 0, nwg = 0, nfast = 0, red0 = 0, nred = 0; };
+    std::vector<TileSplit> tile_split;         // per task; nwg == 0: launched whole
+    std::vector<GemmWg> wgs_ts;
+    int64_t slice_elems_ts = 0;
+    GemmWg* d_wgs_ts = nullptr;
+    SplitReduce* d_red_ts = nullptr;
+    float* d_ws_ts = nullptr;
     ~GemmPlan() {
-        for (void* p : {(void*)d_tasks, (void*)d_chunks, (void*)d_wgs, (void*)d_wgs_op, (void*)d_red, (void*)d_ws})
+        for (void* p : {(void*)d_tasks, (void*)d_chunks, (void*)d_wgs, (void*)d_wgs_op, (void*)d_red, (void*)d_ws, (void*)d_wgs_ts,
+                        (void*)d_red_ts, (void*)d_ws_ts})
             if (p) (void)hipFree(p);
     }
 };
@@ -555,6 +567,92 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
     }
     P->op_nwg = (int64_t)P->wgs_op.size();
 
+    // ---- k-slices per task for tile-granular launches
+    const size_t n_tile_tasks = P->task_ctile.size();
+    P->tile_split.assign(n_tile_tasks, GemmPlan::TileSplit{});
+    std::vector<SplitReduce> red_ts;
+    if (nbat == 0) {
+        constexpr int64_t kTargetWgs = 64, kMaxSlices = 8, kMinSlice = 512;
+        const int64_t slice = (int64_t)bm * bn;
+        int64_t ws_blocks = 0;
+        std::vector<int> st(n_tile_tasks, 1);
+        for (size_t ti = 0; ti < n_tile_tasks; ti++) {
+            const int64_t nwg = P->task_wg0[ti + 1] - P->task_wg0[ti];
+            if (nwg == 0 || nwg >= kTargetWgs) continue;
+            const int64_t want = std::min<int64_t>({kMaxSlices, (kTargetWgs + nwg - 1) / nwg, ktot[ti] / kMinSlice});
+            if (want < 2) continue;
+            st[ti] = (int)want;
+            ws_blocks += nwg * want;
+        }
+        if (ws_blocks > 0) {
+            NNT_HIP(ctx, hipMalloc((void**)&P->d_ws_ts, (size_t)ws_blocks * slice * sizeof(float)));
+            float* next_block = P->d_ws_ts;
+            for (size_t ti = 0; ti < n_tile_tasks; ti++) {
+                const int St = st[ti];
+                if (St < 2) continue;
+                // chunk ranges of this task's slices (lengths in multiples of the step the kernels want)
+                const GemmTask t0 = P->tasks[ti];
+                const int64_t part = ((ktot[ti] + St - 1) / St + kSplitStep - 1) / kSplitStep * kSplitStep;
+                std::vector<std::pair<int32_t, int32_t>> ranges;
+                int32_t q = t0.chunk0;
+                int64_t used = 0;
+                for (int sidx = 0; sidx < St; sidx++) {
+                    const int32_t c0i = (int32_t)P->chunks.size();
+                    int64_t need_k = part;
+                    while (need_k > 0 && q < t0.chunk0 + t0.nchunk) {
+                        const GemmChunk c0 = P->chunks[q];
+                        const int64_t take = std::min<int64_t>(need_k, c0.k - used);
+                        GemmChunk c = c0;
+                        c.A = static_cast<const char*>(c0.A) + used * (P->akf ? 1 : c0.lda) * elem;
+                        c.B = static_cast<const char*>(c0.B) + used * (P->bkf ? 1 : c0.ldb) * elem;
+                        c.k = (int32_t)take;
+                        c.vec_ok = vec_flag(c.A, c.lda, c.strideA, elem) | (vec_flag(c.B, c.ldb, c.strideB, elem) << 1);
+                        P->chunks.push_back(c);
+                        need_k -= take;
+                        used += take;
+                        if (used == c0.k) { q++; used = 0; }
+                    }
+                    ranges.push_back({c0i, (int32_t)P->chunks.size() - c0i});
+                }
+                GemmPlan::TileSplit& ts = P->tile_split[ti];
+                ts.wg0 = (int64_t)P->wgs_ts.size();
+                ts.red0 = (int64_t)red_ts.size();
+                std::vector<std::vector<GemmWg>> by_slice(St);
+                for (int64_t w = P->task_wg0[ti]; w < P->task_wg0[ti + 1]; w++) {
+                    const GemmWg mw = P->wgs[w];
+                    float* block = next_block;
+                    next_block += (int64_t)St * slice;
+                    SplitReduce r;
+                    r.C = t0.C; r.bias = t0.bias; r.ws = block; r.ldc = t0.ldc; r.slice = slice;
+                    r.m0 = mw.m0; r.n0 = mw.n0;
+                    r.rows = std::min<int32_t>(bm, t0.m - mw.m0);
+                    r.cols = std::min<int32_t>(bn, t0.n - mw.n0);
+                    r.ldw = bm; r.nsplit = St;
+                    red_ts.push_back(r);
+                    for (int sidx = 0; sidx < St; sidx++) {
+                        GemmTask t = t0;
+                        t.C = block + (int64_t)sidx * slice - (mw.m0 + (int64_t)mw.n0 * bm);
+                        t.ldc = bm;
+                        t.strideC = 0;
+                        t.bias = nullptr;
+                        t.partial = 1;
+                        t.chunk0 = ranges[sidx].first;
+                        t.nchunk = ranges[sidx].second;
+                        by_slice[sidx].push_back(GemmWg{(int32_t)P->tasks.size(), mw.m0, mw.n0, 0});
+                        P->tasks.push_back(t);
+                    }
+                }
+                for (int sidx = 0; sidx < St; sidx++) P->wgs_ts.insert(P->wgs_ts.end(), by_slice[sidx].begin(), by_slice[sidx].end());
+                ts.nwg = (int64_t)P->wgs_ts.size() - ts.wg0;
+                ts.nred = (int64_t)red_ts.size() - ts.red0;
+            }
+            P->red_blocks = (int)((slice / 4 + 255) / 256);    // (the same value the whole-operation slices set)
+            P->slice_elems_ts = slice;
+            NNT_HIP(ctx, hipMalloc((void**)&P->d_red_ts, red_ts.size() * sizeof(SplitReduce)));
+            NNT_HIP(ctx, hipMemcpy(P->d_red_ts, red_ts.data(), red_ts.size() * sizeof(SplitReduce), hipMemcpyHostToDevice));
+        }
+    }
+
     // workgroups that qualify for the direct-load kernel go first in every launch range
     P->task_nfast.assign(P->task_ctile.size(), 0);
     if (bf ? (P->cfg == kCfgSquare || P->cfg == kCfgTall) : (P->cfg == kCfgSquare || P->cfg == kCfgSkinny64n128 || P->cfg == kCfgMid)) {
@@ -571,6 +669,10 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
         for (size_t ti = 0; ti + 1 < P->task_wg0.size(); ti++)
             P->task_nfast[ti] = std::stable_partition(P->wgs.begin() + P->task_wg0[ti], P->wgs.begin() + P->task_wg0[ti + 1], qualifies) -
                                 (P->wgs.begin() + P->task_wg0[ti]);
+        for (GemmPlan::TileSplit& ts : P->tile_split)
+            if (ts.nwg > 0)
+                ts.nfast = std::stable_partition(P->wgs_ts.begin() + ts.wg0, P->wgs_ts.begin() + ts.wg0 + ts.nwg, qualifies) -
+                           (P->wgs_ts.begin() + ts.wg0);
         if (2 * P->op_nfast >= P->op_nwg && P->op_nwg > 0) {
             // most of the work runs in the direct-load kernel: profile lines carry its name
             const std::string old_name = P->label.substr(0, P->label.find('>') + 1);
@@ -595,6 +697,7 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
     NNT_HIP(ctx, up((void**)&P->d_chunks, P->chunks.data(), P->chunks.size() * sizeof(GemmChunk)));
     NNT_HIP(ctx, up((void**)&P->d_wgs, P->wgs.data(), P->wgs.size() * sizeof(GemmWg)));
     NNT_HIP(ctx, up((void**)&P->d_wgs_op, P->wgs_op.data(), P->wgs_op.size() * sizeof(GemmWg)));
+    NNT_HIP(ctx, up((void**)&P->d_wgs_ts, P->wgs_ts.data(), P->wgs_ts.size() * sizeof(GemmWg)));
     return NNT_OK;
 }
 
@@ -658,12 +761,29 @@ extern "C" int32_t nnt_gemm(nnt_ctx* ctx, float alpha, int32_t opA, nnt_tensor* 
         for (int64_t b : P->task_btiles[ti]) acc.push_back(B->one(b, kRead));
         if (bias) acc.push_back(bias->one(P->task_bias_tile[ti], kRead));
         GemmArgs gt = g;
-        gt.wgs = P->d_wgs + P->task_wg0[ti];
-        const int64_t nwg = P->task_wg0[ti + 1] - P->task_wg0[ti];
-        const int64_t nfast = P->task_nfast[ti];
-        int32_t rc = submit(ctx, acc, [=](hipStream_t st) {
-            return launch_any(st, P->dtype_in, P->dtype_out, P->akf, P->bkf, P->cfg, gt, nwg, nfast);
-        });
+        const GemmPlan::TileSplit ts = P->tile_split[ti];
+        int32_t rc;
+        if (ts.nwg > 0) {
+            // few macro-tiles, long contraction: k-slices into this task's scratch block, then their sum
+            gt.wgs = P->d_wgs_ts + ts.wg0;
+            const double red_bytes = (double)ts.nred * P->slice_elems_ts * 4.0 * (ts.nwg / ts.nred + 1);
+            rc = submit(ctx, acc, [=](hipStream_t st) {
+                int32_t r = launch_any(st, P->dtype_in, P->dtype_out, P->akf, P->bkf, P->cfg, gt, ts.nwg, ts.nfast);
+                if (r != NNT_OK) return r;
+                profile_mark(ctx, st, "splitk_reduce", red_bytes, true);
+                const dim3 grid((unsigned)P->red_blocks, (unsigned)ts.nred), block(256);
+                if (P->dtype_out == NNT_F32) hipLaunchKernelGGL((splitk_reduce<float>), grid, block, 0, st, P->d_red_ts + ts.red0, alpha, beta);
+                else hipLaunchKernelGGL((splitk_reduce<uint16_t>), grid, block, 0, st, P->d_red_ts + ts.red0, alpha, beta);
+                return hipGetLastError() == hipSuccess ? (int32_t)NNT_OK : (int32_t)NNT_EHIP;
+            }, 2);
+        } else {
+            gt.wgs = P->d_wgs + P->task_wg0[ti];
+            const int64_t nwg = P->task_wg0[ti + 1] - P->task_wg0[ti];
+            const int64_t nfast = P->task_nfast[ti];
+            rc = submit(ctx, acc, [=](hipStream_t st) {
+                return launch_any(st, P->dtype_in, P->dtype_out, P->akf, P->bkf, P->cfg, gt, nwg, nfast);
+            });
+        }
         if (rc != NNT_OK) return rc;
     }
     return NNT_OK;
