@@ -571,18 +571,26 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
     const size_t n_tile_tasks = P->task_ctile.size();
     P->tile_split.assign(n_tile_tasks, GemmPlan::TileSplit{});
     std::vector<SplitReduce> red_ts;
-    if (nbat == 0) {
-        constexpr int64_t kTargetWgs = 64, kMaxSlices = 8, kMinSlice = 512;
+    if (nbat == 0 && ctx->granularity == NNT_GRAN_TILE) {      // (a plan first built for whole-operation launches has none)
+        constexpr int64_t kTargetWgs = 64, kMinSlice = 512;
+        constexpr int64_t kScratchCap = (int64_t)2 << 30;      // bytes of slice scratch per plan
         const int64_t slice = (int64_t)bm * bn;
         int64_t ws_blocks = 0;
         std::vector<int> st(n_tile_tasks, 1);
-        for (size_t ti = 0; ti < n_tile_tasks; ti++) {
-            const int64_t nwg = P->task_wg0[ti + 1] - P->task_wg0[ti];
-            if (nwg == 0 || nwg >= kTargetWgs) continue;
-            const int64_t want = std::min<int64_t>({kMaxSlices, (kTargetWgs + nwg - 1) / nwg, ktot[ti] / kMinSlice});
-            if (want < 2) continue;
-            st[ti] = (int)want;
-            ws_blocks += nwg * want;
+        for (int64_t max_slices = 8; max_slices >= 2; max_slices /= 2) {
+            ws_blocks = 0;
+            for (size_t ti = 0; ti < n_tile_tasks; ti++) {
+                st[ti] = 1;
+                const int64_t nwg = P->task_wg0[ti + 1] - P->task_wg0[ti];
+                if (nwg == 0 || nwg >= kTargetWgs) continue;
+                const int64_t want = std::min<int64_t>({max_slices, (kTargetWgs + nwg - 1) / nwg, ktot[ti] / kMinSlice});
+                if (want < 2) continue;
+                st[ti] = (int)want;
+                ws_blocks += nwg * want;
+            }
+            if (ws_blocks * slice * (int64_t)sizeof(float) <= kScratchCap) break;
+            ws_blocks = 0;
+            std::fill(st.begin(), st.end(), 1);
         }
         if (ws_blocks > 0) {
             NNT_HIP(ctx, hipMalloc((void**)&P->d_ws_ts, (size_t)ws_blocks * slice * sizeof(float)));
