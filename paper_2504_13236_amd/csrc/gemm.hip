@@ -322,6 +322,63 @@ int64_t prod_extent(const nnt_tensor* t, const int64_t* tc, const std::vector<in
     return p;
 }
 
+// Appends to P->chunks the chunks of `S` consecutive k-slices of task `t0` (slice lengths in multiples
+// of the step the kernels want) and returns (first chunk, chunk count) per slice.
+std::vector<std::pair<int32_t, int32_t>> cut_into_slices(GemmPlan* P, const GemmTask& t0, int64_t ktot, int S, int elem) {
+    std::vector<std::pair<int32_t, int32_t>> ranges;
+    const int64_t part = ((ktot + S - 1) / S + kSplitStep - 1) / kSplitStep * kSplitStep;
+    int32_t q = t0.chunk0;
+    int64_t used = 0;                       // k already consumed of chunk q
+    for (int sidx = 0; sidx < S; sidx++) {
+        const int32_t c0i = (int32_t)P->chunks.size();
+        int64_t want = part;
+        while (want > 0 && q < t0.chunk0 + t0.nchunk) {
+            const GemmChunk c0 = P->chunks[q];
+            const int64_t take = std::min<int64_t>(want, c0.k - used);
+            GemmChunk c = c0;
+            c.A = static_cast<const char*>(c0.A) + used * (P->akf ? 1 : c0.lda) * elem;
+            c.B = static_cast<const char*>(c0.B) + used * (P->bkf ? 1 : c0.ldb) * elem;
+            c.k = (int32_t)take;
+            c.vec_ok = vec_flag(c.A, c.lda, c.strideA, elem) | (vec_flag(c.B, c.ldb, c.strideB, elem) << 1);
+            P->chunks.push_back(c);
+            want -= take;
+            used += take;
+            if (used == c0.k) { q++; used = 0; }
+        }
+        ranges.push_back({c0i, (int32_t)P->chunks.size() - c0i});
+    }
+    return ranges;
+}
+
+// The slices of macro-tile `mw` of task `t0`: one partial task per slice, writing raw fp32 sums into
+// `block` (slice after slice, bm x bn each), appended to P->tasks; their workgroups go to `by_slice`.
+// Returns the record from which the slice-sum kernel finishes the macro-tile.
+SplitReduce add_slice_tasks(GemmPlan* P, const GemmTask& t0, const GemmWg& mw, const std::vector<std::pair<int32_t, int32_t>>& ranges,
+                            float* block, int bm, int bn, std::vector<std::vector<GemmWg>>& by_slice) {
+    const int S = (int)ranges.size();
+    const int64_t slice = (int64_t)bm * bn;
+    SplitReduce r;
+    r.C = t0.C; r.bias = t0.bias; r.ws = block; r.ldc = t0.ldc; r.slice = slice;
+    r.m0 = mw.m0; r.n0 = mw.n0;
+    r.rows = std::min<int32_t>(bm, t0.m - mw.m0);
+    r.cols = std::min<int32_t>(bn, t0.n - mw.n0);
+    r.ldw = bm; r.nsplit = S;
+    for (int sidx = 0; sidx < S; sidx++) {
+        GemmTask t = t0;
+        // element (m0 + i, n0 + j) of the "tile" lands on block[i + j * bm] of this slice
+        t.C = block + (int64_t)sidx * slice - (mw.m0 + (int64_t)mw.n0 * bm);
+        t.ldc = bm;
+        t.strideC = 0;
+        t.bias = nullptr;
+        t.partial = 1;
+        t.chunk0 = ranges[sidx].first;
+        t.nchunk = ranges[sidx].second;
+        by_slice[sidx].push_back(GemmWg{(int32_t)P->tasks.size(), mw.m0, mw.n0, 0});
+        P->tasks.push_back(t);
+    }
+    return r;
+}
+
 int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B, nnt_tensor* C, int ncon, int nbat,
                    nnt_tensor* bias, GemmPlan* P) {
     const int na = A->ndim - nbat, nb = B->ndim - nbat;
@@ -503,58 +560,13 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
         NNT_HIP(ctx, hipMalloc((void**)&P->d_ws, (size_t)n_split * S * slice * sizeof(float)));
         // chunk ranges of the slices, built once per C tile
         std::vector<std::vector<std::pair<int32_t, int32_t>>> ranges(P->tasks.size());
-        auto slice_chunks = [&](int32_t ti) {
-            if (!ranges[ti].empty()) return;
-            const GemmTask t0 = P->tasks[ti];
-            const int64_t part = ((ktot[ti] + S - 1) / S + kSplitStep - 1) / kSplitStep * kSplitStep;
-            int32_t q = t0.chunk0;
-            int64_t used = 0;                       // k already consumed of chunk q
-            for (int sidx = 0; sidx < S; sidx++) {
-                const int32_t c0i = (int32_t)P->chunks.size();
-                int64_t want = part;
-                while (want > 0 && q < t0.chunk0 + t0.nchunk) {
-                    const GemmChunk c0 = P->chunks[q];
-                    const int64_t take = std::min<int64_t>(want, c0.k - used);
-                    GemmChunk c = c0;
-                    c.A = static_cast<const char*>(c0.A) + used * (P->akf ? 1 : c0.lda) * elem;
-                    c.B = static_cast<const char*>(c0.B) + used * (P->bkf ? 1 : c0.ldb) * elem;
-                    c.k = (int32_t)take;
-                    c.vec_ok = vec_flag(c.A, c.lda, c.strideA, elem) | (vec_flag(c.B, c.ldb, c.strideB, elem) << 1);
-                    P->chunks.push_back(c);
-                    want -= take;
-                    used += take;
-                    if (used == c0.k) { q++; used = 0; }
-                }
-                ranges[ti].push_back({c0i, (int32_t)P->chunks.size() - c0i});
-            }
-        };
         std::vector<SplitReduce> red;
         std::vector<std::vector<GemmWg>> by_slice(S);
         for (size_t w = 0; w < cut.size(); w++) {
             const GemmWg& mw = cut[w];
-            slice_chunks(mw.task);
             const GemmTask t0 = P->tasks[mw.task];
-            float* block = P->d_ws + (int64_t)w * S * slice;
-            SplitReduce r;
-            r.C = t0.C; r.bias = t0.bias; r.ws = block; r.ldc = t0.ldc; r.slice = slice;
-            r.m0 = mw.m0; r.n0 = mw.n0;
-            r.rows = std::min<int32_t>(bm, t0.m - mw.m0);
-            r.cols = std::min<int32_t>(bn, t0.n - mw.n0);
-            r.ldw = bm; r.nsplit = S;
-            red.push_back(r);
-            for (int sidx = 0; sidx < S; sidx++) {
-                GemmTask t = t0;
-                // element (m0 + i, n0 + j) of the "tile" lands on block[i + j * bm] of this slice
-                t.C = block + (int64_t)sidx * slice - (mw.m0 + (int64_t)mw.n0 * bm);
-                t.ldc = bm;
-                t.strideC = 0;
-                t.bias = nullptr;
-                t.partial = 1;
-                t.chunk0 = ranges[mw.task][sidx].first;
-                t.nchunk = ranges[mw.task][sidx].second;
-                by_slice[sidx].push_back(GemmWg{(int32_t)P->tasks.size(), mw.m0, mw.n0, 0});
-                P->tasks.push_back(t);
-            }
+            if (ranges[mw.task].empty()) ranges[mw.task] = cut_into_slices(P, t0, ktot[mw.task], S, elem);
+            red.push_back(add_slice_tasks(P, t0, mw, ranges[mw.task], P->d_ws + (int64_t)w * S * slice, bm, bn, by_slice));
         }
         for (int sidx = 0; sidx < S; sidx++) P->wgs_op.insert(P->wgs_op.end(), by_slice[sidx].begin(), by_slice[sidx].end());
         P->red_blocks = (int)((slice / 4 + 255) / 256);
@@ -598,57 +610,15 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
             for (size_t ti = 0; ti < n_tile_tasks; ti++) {
                 const int St = st[ti];
                 if (St < 2) continue;
-                // chunk ranges of this task's slices (lengths in multiples of the step the kernels want)
                 const GemmTask t0 = P->tasks[ti];
-                const int64_t part = ((ktot[ti] + St - 1) / St + kSplitStep - 1) / kSplitStep * kSplitStep;
-                std::vector<std::pair<int32_t, int32_t>> ranges;
-                int32_t q = t0.chunk0;
-                int64_t used = 0;
-                for (int sidx = 0; sidx < St; sidx++) {
-                    const int32_t c0i = (int32_t)P->chunks.size();
-                    int64_t need_k = part;
-                    while (need_k > 0 && q < t0.chunk0 + t0.nchunk) {
-                        const GemmChunk c0 = P->chunks[q];
-                        const int64_t take = std::min<int64_t>(need_k, c0.k - used);
-                        GemmChunk c = c0;
-                        c.A = static_cast<const char*>(c0.A) + used * (P->akf ? 1 : c0.lda) * elem;
-                        c.B = static_cast<const char*>(c0.B) + used * (P->bkf ? 1 : c0.ldb) * elem;
-                        c.k = (int32_t)take;
-                        c.vec_ok = vec_flag(c.A, c.lda, c.strideA, elem) | (vec_flag(c.B, c.ldb, c.strideB, elem) << 1);
-                        P->chunks.push_back(c);
-                        need_k -= take;
-                        used += take;
-                        if (used == c0.k) { q++; used = 0; }
-                    }
-                    ranges.push_back({c0i, (int32_t)P->chunks.size() - c0i});
-                }
+                const std::vector<std::pair<int32_t, int32_t>> ranges = cut_into_slices(P, t0, ktot[ti], St, elem);
                 GemmPlan::TileSplit& ts = P->tile_split[ti];
                 ts.wg0 = (int64_t)P->wgs_ts.size();
                 ts.red0 = (int64_t)red_ts.size();
                 std::vector<std::vector<GemmWg>> by_slice(St);
                 for (int64_t w = P->task_wg0[ti]; w < P->task_wg0[ti + 1]; w++) {
-                    const GemmWg mw = P->wgs[w];
-                    float* block = next_block;
+                    red_ts.push_back(add_slice_tasks(P, t0, P->wgs[w], ranges, next_block, bm, bn, by_slice));
                     next_block += (int64_t)St * slice;
-                    SplitReduce r;
-                    r.C = t0.C; r.bias = t0.bias; r.ws = block; r.ldc = t0.ldc; r.slice = slice;
-                    r.m0 = mw.m0; r.n0 = mw.n0;
-                    r.rows = std::min<int32_t>(bm, t0.m - mw.m0);
-                    r.cols = std::min<int32_t>(bn, t0.n - mw.n0);
-                    r.ldw = bm; r.nsplit = St;
-                    red_ts.push_back(r);
-                    for (int sidx = 0; sidx < St; sidx++) {
-                        GemmTask t = t0;
-                        t.C = block + (int64_t)sidx * slice - (mw.m0 + (int64_t)mw.n0 * bm);
-                        t.ldc = bm;
-                        t.strideC = 0;
-                        t.bias = nullptr;
-                        t.partial = 1;
-                        t.chunk0 = ranges[sidx].first;
-                        t.nchunk = ranges[sidx].second;
-                        by_slice[sidx].push_back(GemmWg{(int32_t)P->tasks.size(), mw.m0, mw.n0, 0});
-                        P->tasks.push_back(t);
-                    }
                 }
                 for (int sidx = 0; sidx < St; sidx++) P->wgs_ts.insert(P->wgs_ts.end(), by_slice[sidx].begin(), by_slice[sidx].end());
                 ts.nwg = (int64_t)P->wgs_ts.size() - ts.wg0;
