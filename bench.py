@@ -342,6 +342,9 @@ def measure(args, cfg, inp, attention, capi, tiled, torch, workload):
                       "flops_per_step": flops,
                       "attention_flops": "visible (key, query) pairs only, no recomputation" if attention == "fused"
                                          else "computed sequence-tile pairs only"},
+           # the metric's second and third figure (time-weighted over the serial per-kernel pass)
+           "tile_gemm_pct_mfma_peak": 100.0 * (summary["tile_gemm_weights"]["frac_of_peak"] or 0.0),
+           "elementwise_GBps": summary["memory_bound_kernels"]["GB/s"],
            "roofline": roofline, "summary": summary, "kernels": kernels, "executor": ctx.stats()}
     if nblk > 1:
         stack.close()
