@@ -308,8 +308,9 @@ def measure(args, cfg, inp, attention, capi, tiled, torch, workload):
             for line in open(tpath):
                 parts = line.rstrip("\n").split("\t")
                 if len(parts) == 3 and parts[0] == dom.replace(" batched", ""):
-                    roofline["traffic"] = {"read_bytes_per_launch": float(parts[1]), "written_bytes_per_launch": float(parts[2]),
-                                           "source": "profiles/" + os.path.basename(tpath)}
+                    roofline["traffic"] = float(parts[1]) + float(parts[2])      # HBM bytes per launch, read + written
+                    roofline["traffic_detail"] = {"read_bytes_per_launch": float(parts[1]), "written_bytes_per_launch": float(parts[2]),
+                                                  "source": "profiles/" + os.path.basename(tpath)}
         wg = [v for k, v in gemms.items()]
         tot_ms = sum(v["ms_per_step"] for v in wg)
         tot_fl = sum(v["TFLOP/s"] * v["ms_per_step"] for v in wg)
