@@ -357,6 +357,69 @@ def measure(args, cfg, inp, attention, capi, tiled, torch, workload):
     return out
 
 
+def model_iteration(args, cfg, capi, tiled, torch, workload):
+    """A whole training iteration of a GPT-2-shaped language model built from the block of `cfg`: token and
+    position embeddings, `--blocks` blocks (12 when not given), final layer norm, tied head over a
+    50304-item vocabulary, cross-entropy loss, backward, Adam on every parameter; one flow of tasks."""
+    import numpy as np
+    nblk = args.blocks if args.blocks > 1 else 12
+    N_v, tile_v = 50304, 8192
+    ctx = tiled.Context(n_streams=args.streams)
+    inp = workload.generate(cfg)
+    blks = [tiled.Gpt2Block(ctx, cfg.N_e, cfg.N_h, cfg.N_m, cfg.N_s, cfg.N_b, workload.base_tiles(cfg), dtype=cfg.dtype,
+                            eps=cfg.eps, gelu=cfg.gelu, adam=True, fused_attention=args.attention == "fused") for _ in range(nblk)]
+    for b in blks:
+        b.set_params({k: inp[k] for k in workload.PARAM_NAMES})
+    model = tiled.Gpt2Model(ctx, blks, N_v, tile_v)
+    r = np.random.Generator(np.random.Philox(workload.SEED_BASE + 100 * cfg.index + 50))
+    model.set_params(0.02 * r.standard_normal((cfg.N_e, N_v)), 0.01 * r.standard_normal((cfg.N_e, cfg.N_s)),
+                     np.ones(cfg.N_e), np.zeros(cfg.N_e))
+    tok = r.integers(0, N_v, (cfg.N_s, cfg.N_b))
+    model.set_batch(tok, np.roll(tok, -1, axis=0))            # next-token labels of a random sequence
+    step_no = [0]
+    losses = []
+
+    def step():
+        step_no[0] += 1
+        model.forward()
+        model.backward()
+        model.adam(step_no[0], **workload.ADAM)
+    for _ in range(max(args.warmup, 1)):
+        step()
+        ctx.wait()
+        losses.append(model.loss.item())
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    dt_submit = time.perf_counter() - t0
+    ctx.wait()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    losses.append(model.loss.item())
+    T = cfg.N_s * cfg.N_b
+    head = 3.0 * 2.0 * N_v * T * cfg.N_e
+    flops = nblk * workload.model_flops(cfg, tile_skip=True, visible_only=args.attention == "fused") + head
+    sec = dt / args.steps
+    per_block = 4 * cfg.N_e ** 2 + 2 * cfg.N_e * cfg.N_m + 9 * cfg.N_e + cfg.N_m
+    nparams = nblk * per_block + cfg.N_e * (N_v + cfg.N_s) + 2 * cfg.N_e
+    out = {"metric": "GPT-2 language-model training iteration on 1 MI355X", "value": flops / sec / 1e12, "unit": "TFLOP/s",
+           "tokens_per_s": T / sec, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": sec * 1e3,
+           "host_submit_ms_per_step": dt_submit / args.steps * 1e3, "higher_is_better": True, "vs_baseline": None,
+           "dtype": "f32" if cfg.dtype == "f32" else "bf16", "data": "synthetic",
+           "config": {"workload": "%d blocks of %s (N_e=%d N_h=%d N_m=%d N_s=%d N_b=%d tile=%d), vocabulary %d in tiles of %d, "
+                                  "tied head, cross-entropy, forward+backward+Adam" % (nblk, cfg.name, cfg.N_e, cfg.N_h, cfg.N_m,
+                                                                                       cfg.N_s, cfg.N_b, cfg.tile, N_v, tile_v),
+                      "parameters": int(nparams), "streams": args.streams, "attention": args.attention, "flops_per_step": flops},
+           "loss_per_token_warmup_steps": [l / T for l in losses[:-1]], "loss_per_token_after_timed_steps": losses[-1] / T,
+           "executor": ctx.stats()}
+    model.close()
+    for b in blks:
+        b.close()
+    ctx.close()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -380,6 +443,10 @@ def main():
                     help="instead of the block benchmark, time single calls of the tile kernels at the config's shapes: "
                          "products against the MFMA peak, memory-bound kernels against HBM, warm (one buffer set) and "
                          "cold (rotating over > 512 MB of buffer sets, more than the 256 MB Infinity Cache)")
+    ap.add_argument("--model", action="store_true",
+                    help="instead of the block benchmark, time whole training iterations of a language model made of "
+                         "--blocks blocks (default 12) of the config: embeddings, blocks, final layer norm, tied head, loss, "
+                         "backward, Adam")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (--gpus %d refused)" % args.gpus, file=sys.stderr)
@@ -417,6 +484,9 @@ def main():
         print(json.dumps({"tile_kernels": res}))
         return
     cfg = workload.CONFIGS[args.config]
+    if args.model:
+        print(json.dumps(model_iteration(args, cfg, capi, tiled, torch, workload)))
+        return
     inp = workload.generate(cfg)
     out = measure(args, cfg, inp, args.attention, capi, tiled, torch, workload)
     if args.attention == "tiles" and cfg.h in (64, 128) and not args.no_next_rows and args.blocks == 1:

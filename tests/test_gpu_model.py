@@ -139,3 +139,76 @@ def test_small_language_model_forward_backward(mods):
         for k in workload.PARAM_NAMES:
             assert relerr(blk.grad(k).download(), grads[k]) <= 1e-5, k
         blk.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_two_block_language_model_training_step(mods, dtype):
+    """tokens -> token + position embeddings -> two blocks -> final layer norm -> tied head -> loss, the
+    whole backward pass and one Adam step, as one flow of tasks (tiled.Gpt2Model), against the oracle's
+    composition of the same definitions."""
+    capi, tiled = mods
+    cfg = workload.CONFIGS[1].replace(dtype=dtype)
+    tiles = workload.base_tiles(cfg)
+    r = np.random.default_rng(17)
+    N_v, tile_v, nblk = 200, 64, 2
+    inputs = [workload.generate(cfg.replace(index=1 + 5 * i)) for i in range(nblk)]
+    wte = (0.3 * r.standard_normal((cfg.N_e, N_v))).astype(np.float32)
+    wpe = (0.1 * r.standard_normal((cfg.N_e, cfg.N_s))).astype(np.float32)
+    gf = (1.0 + 0.05 * r.standard_normal(cfg.N_e)).astype(np.float32)
+    bf = (0.05 * r.standard_normal(cfg.N_e)).astype(np.float32)
+    tok = r.integers(0, N_v, (cfg.N_s, cfg.N_b))
+    lab = r.integers(0, N_v, (cfg.N_s, cfg.N_b))
+    # oracle
+    pos = np.repeat(np.arange(cfg.N_s)[:, None], cfg.N_b, axis=1)
+    p64 = [{k: np.asarray(inp[k], np.float64) for k in workload.PARAM_NAMES} for inp in inputs]
+    W64, P64 = wte.astype(np.float64), wpe.astype(np.float64)
+    X = D.embedding_fwd(W64, tok) + D.embedding_fwd(P64, pos)
+    caches = []
+    for p in p64:
+        X, cache = D.block_forward(p, X, cfg.N_h, cfg.eps, cfg.gelu)
+        caches.append(cache)
+    Xf, mean, rstd = D.layernorm_fwd(X, gf, bf, cfg.eps)
+    logits = np.einsum("ev,esb->vsb", W64, Xf)
+    L, _, dlogits = D.cross_entropy(logits, lab)
+    dXf = np.einsum("ev,vsb->esb", W64, dlogits)
+    dW_head = np.einsum("esb,vsb->ev", Xf, dlogits)
+    dX, dgf, dbf = D.layernorm_bwd(X, gf, mean, rstd, dXf)
+    grads = [None] * nblk
+    for i in reversed(range(nblk)):
+        dX, grads[i] = D.block_backward(p64[i], caches[i], dX, cfg.N_h, cfg.gelu)
+    dwte = dW_head + D.embedding_bwd(dX, tok, N_v)
+    dwpe = D.embedding_bwd(dX, pos, cfg.N_s)
+    # device
+    with tiled.Context(n_streams=4) as ctx:
+        blks = [tiled.Gpt2Block(ctx, cfg.N_e, cfg.N_h, cfg.N_m, cfg.N_s, cfg.N_b, tiles, dtype=dtype, adam=True) for _ in range(nblk)]
+        for b, inp in zip(blks, inputs):
+            b.set_params({k: inp[k] for k in workload.PARAM_NAMES})
+        model = tiled.Gpt2Model(ctx, blks, N_v, tile_v)
+        model.set_params(wte, wpe, gf, bf)
+        model.set_batch(tok, lab)
+        model.forward()
+        model.backward()
+        ctx.wait()
+        tol = TOL[dtype]
+        assert abs(model.loss.item() - L) <= tol * abs(L), (model.loss.item(), L)
+        check(model.wte["g"].download(), dwte, dtype, "token embedding gradient")
+        check(model.wpe["g"].download(), dwpe, dtype, "position embedding gradient")
+        check(model.gamma["g"].download(), dgf, dtype, "final layer norm gain gradient")
+        check(model.beta["g"].download(), dbf, dtype, "final layer norm bias gradient")
+        for i, b in enumerate(blks):
+            for k in workload.PARAM_NAMES:
+                assert relerr(b.grad(k).download(), grads[i][k]) <= tol, (i, k)
+        model.adam(1, **workload.ADAM)
+        ctx.wait()
+        new_wte, m_ref, v_ref = D.adam_step(W64, dwte, np.zeros_like(W64), np.zeros_like(W64), 1, **workload.ADAM)
+        check(model.wte["m"].download(), m_ref, dtype, "first moment of the token embedding")
+        check(model.wte["v"].download(), v_ref, dtype, "second moment of the token embedding")
+        # Adam's first step moves an entry by about lr whatever the gradient's size, so the step taken is
+        # compared where the gradient is well above its own error (elsewhere its sign is not determined)
+        step_gpu = model.wte["p"].download().astype(np.float64) - W64
+        moved = np.abs(dwte) > (1e-3 if dtype == "f32" else 0.1) * np.abs(dwte).max()
+        assert moved.sum() > 10
+        assert relerr(step_gpu[moved], (new_wte - W64)[moved]) <= (1e-4 if dtype == "f32" else 2e-2)
+        model.close()
+        for b in blks:
+            b.close()
