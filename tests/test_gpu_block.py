@@ -31,6 +31,27 @@ def oracle_run(cfg, inp, adam):
     return res
 
 
+_case_cache = {}
+
+
+def full_size_case(number, adam, **overrides):
+    """(config, inputs, oracle results) of a full-size workload; the last one is kept, so that the two
+    attention flows of one workload share one run of the fp64 oracle."""
+    key = (number, adam, tuple(sorted(overrides.items())))
+    if key not in _case_cache:
+        _case_cache.clear()
+        cfg = workload.CONFIGS[number].replace(**overrides) if overrides else workload.CONFIGS[number]
+        inp = workload.generate(cfg)
+        _case_cache[key] = (cfg, inp, oracle_run(cfg, inp, adam))
+    return _case_cache[key]
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _drop_case_cache():
+    yield
+    _case_cache.clear()
+
+
 def gpu_run(tiled, cfg, inp, tiles, adam, gran=0, n_streams=4, serial=False, fused=False):
     out = {}
     with tiled.Context(n_streams=n_streams, granularity=gran, serial=serial) as ctx:
@@ -295,9 +316,7 @@ def test_block_bf16_ragged_tiles(mods):
 def test_block_C2_full_size(mods):
     """The benchmark's workload and launch configuration, every output compared in full."""
     capi, tiled = mods
-    cfg = workload.CONFIGS[2]
-    inp = workload.generate(cfg)
-    ref = oracle_run(cfg, inp, False)
+    cfg, inp, ref = full_size_case(2, False)
     got = gpu_run(tiled, cfg, inp, workload.base_tiles(cfg), False)
     errs = compare(got, ref, "f32", False)
     print("C2 max-norm relative errors:", {k: "%.2e" % v for k, v in errs.items()})
@@ -305,9 +324,7 @@ def test_block_C2_full_size(mods):
 
 def test_block_C2_full_size_fused_attention(mods):
     capi, tiled = mods
-    cfg = workload.CONFIGS[2]
-    inp = workload.generate(cfg)
-    ref = oracle_run(cfg, inp, False)
+    cfg, inp, ref = full_size_case(2, False)
     got = gpu_run(tiled, cfg, inp, workload.base_tiles(cfg), False, fused=True)
     errs = compare(got, ref, "f32", False)
     print("C2 (fused attention) max-norm relative errors:", {k: "%.2e" % v for k, v in errs.items()})
@@ -315,9 +332,7 @@ def test_block_C2_full_size_fused_attention(mods):
 
 def test_block_C3_full_size_bf16(mods):
     capi, tiled = mods
-    cfg = workload.CONFIGS[3]
-    inp = workload.generate(cfg)
-    ref = oracle_run(cfg, inp, True)
+    cfg, inp, ref = full_size_case(3, True)
     got = gpu_run(tiled, cfg, inp, workload.base_tiles(cfg), True)
     errs = compare(got, ref, "bf16", True)
     print("C3 max-norm relative errors:", {k: "%.2e" % v for k, v in errs.items()})
@@ -325,9 +340,7 @@ def test_block_C3_full_size_bf16(mods):
 
 def test_block_C3_full_size_bf16_fused_attention(mods):
     capi, tiled = mods
-    cfg = workload.CONFIGS[3]
-    inp = workload.generate(cfg)
-    ref = oracle_run(cfg, inp, True)
+    cfg, inp, ref = full_size_case(3, True)
     got = gpu_run(tiled, cfg, inp, workload.base_tiles(cfg), True, fused=True)
     errs = compare(got, ref, "bf16", True)
     print("C3 (fused attention) max-norm relative errors:", {k: "%.2e" % v for k, v in errs.items()})
@@ -336,9 +349,7 @@ def test_block_C3_full_size_bf16_fused_attention(mods):
 def test_block_C4_full_size_bf16_ragged_fused_attention(mods):
     """Sequence tiles 400 + 400 + 224: workgroup blocks of 128 and streamed blocks of 64 rows end inside every tile."""
     capi, tiled = mods
-    cfg = workload.CONFIGS[4]
-    inp = workload.generate(cfg)
-    ref = oracle_run(cfg, inp, False)
+    cfg, inp, ref = full_size_case(4, False)
     got = gpu_run(tiled, cfg, inp, workload.base_tiles(cfg), False, fused=True)
     errs = compare(got, ref, "bf16", False)
     print("C4 (fused attention) max-norm relative errors:", {k: "%.2e" % v for k, v in errs.items()})
@@ -347,9 +358,7 @@ def test_block_C4_full_size_bf16_ragged_fused_attention(mods):
 def test_block_C4_full_size_bf16_ragged(mods):
     """GPT-2-XL shape: tile 400 against 1600 / 6400 / 1024 (sequence tiles 400 + 400 + 224, head size 64 crossing tile edges)."""
     capi, tiled = mods
-    cfg = workload.CONFIGS[4]
-    inp = workload.generate(cfg)
-    ref = oracle_run(cfg, inp, False)
+    cfg, inp, ref = full_size_case(4, False)
     got = gpu_run(tiled, cfg, inp, workload.base_tiles(cfg), False)
     errs = compare(got, ref, "bf16", False)
     print("C4 max-norm relative errors:", {k: "%.2e" % v for k, v in errs.items()})
@@ -361,9 +370,7 @@ def test_block_C5_one_batch_member_bf16(mods, fused):
     members are independent except for the parameter-gradient sums, and the full batch would take the
     fp64 oracle several minutes."""
     capi, tiled = mods
-    cfg = workload.CONFIGS[5].replace(N_b=1)
-    inp = workload.generate(cfg)
-    ref = oracle_run(cfg, inp, True)
+    cfg, inp, ref = full_size_case(5, True, N_b=1)
     got = gpu_run(tiled, cfg, inp, workload.base_tiles(cfg), True, fused=fused)
     errs = compare(got, ref, "bf16", True)
     print("C5 (N_b=1%s) max-norm relative errors:" % (", fused attention" if fused else ""), {k: "%.2e" % v for k, v in errs.items()})
