@@ -374,3 +374,36 @@ def test_block_C5_one_batch_member_bf16(mods, fused):
     got = gpu_run(tiled, cfg, inp, workload.base_tiles(cfg), True, fused=fused)
     errs = compare(got, ref, "bf16", True)
     print("C5 (N_b=1%s) max-norm relative errors:" % (", fused attention" if fused else ""), {k: "%.2e" % v for k, v in errs.items()})
+
+
+def test_block_C5_full_batch_sampled_member(mods):
+    """C5 at its full batch of four, as the benchmark launches it (`bench.py --config 5`): batch members
+    only meet in the parameter-gradient sums, so `Out` and `dX` of one sampled member are compared with the
+    oracle run on that member alone, and the gradient of the last bias with its closed form (the sum of
+    the upstream gradient over positions)."""
+    capi, tiled = mods
+    cfg = workload.CONFIGS[5]
+    inp = workload.generate(cfg)
+    member = 2
+    one = cfg.replace(N_b=1)
+    sub = dict(inp)
+    sub["X"] = np.ascontiguousarray(inp["X"][:, :, member:member + 1])
+    sub["dOut"] = np.ascontiguousarray(inp["dOut"][:, :, member:member + 1])
+    ref = oracle_run(one, sub, False)
+    with tiled.Context(n_streams=4) as ctx:
+        blk = tiled.Gpt2Block(ctx, cfg.N_e, cfg.N_h, cfg.N_m, cfg.N_s, cfg.N_b, workload.base_tiles(cfg), dtype=cfg.dtype,
+                              eps=cfg.eps, gelu=cfg.gelu, adam=False)
+        blk.set_params({k: inp[k] for k in workload.PARAM_NAMES})
+        X, dOut = blk.activation(inp["X"]), blk.activation(inp["dOut"])
+        Out, dX = blk.activation(), blk.activation()
+        blk.forward(X, Out)
+        blk.backward(dOut, dX)
+        got_out = Out.download()[:, :, member:member + 1]
+        got_dx = dX.download()[:, :, member:member + 1]
+        got_db2 = blk.grad("b_2").download()
+        blk.close()
+    errs = {"Out": relerr(got_out, ref["Out"]), "dX": relerr(got_dx, ref["dX"]),
+            "db_2": relerr(got_db2, np.asarray(inp["dOut"], np.float64).sum(axis=(1, 2)))}
+    print("C5 (full batch, member %d) max-norm relative errors:" % member, {k: "%.2e" % v for k, v in errs.items()})
+    bad = {k: v for k, v in errs.items() if not v <= TOL["bf16"]}
+    assert not bad, bad
