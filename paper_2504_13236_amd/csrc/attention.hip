@@ -25,6 +25,7 @@
 #include "internal.hpp"
 
 #include <cmath>
+#include <type_traits>
 
 namespace nnt {
 namespace {
@@ -92,6 +93,9 @@ __device__ __forceinline__ T* rows_of(void* const* tiles, const Slab& s, int wid
 //                    row acc_row(r, hh), and the A operand is read from LDS in that same order)
 
 __device__ __forceinline__ int acc_row(int r, int hh) { return 8 * (r / 4) + 4 * hh + (r % 4); }
+// the part of acc_row that is known at compile time: a bound `row < lim` on acc_row(r, hh) is the
+// per-lane bound `acc_row0(r) < lim - 4 hh`, one comparison with a constant per register
+__device__ __forceinline__ constexpr int acc_row0(int r) { return 8 * (r / 4) + (r % 4); }
 
 __device__ __forceinline__ f32x16 zero16() {
     f32x16 z;
@@ -370,13 +374,15 @@ __global__ void __launch_bounds__(256, 2) attn_fwd(const FwdArgs a) {
 #pragma unroll
                     for (int r = 0; r < 16; r++) mx = fmaxf(mx, s[sub][r]);
             } else {
+                // keys [0, lim) of the block are inside the tile, visible to this lane's query and computed
+                int lim = min(ext_k - kloc0, two ? kBlk : 32);
+                if (g.causal) lim = min(lim, qglob - kglob0 + 1);
+                const int lim_h = lim - 4 * hh;
 #pragma unroll
                 for (int sub = 0; sub < 2; sub++)
 #pragma unroll
                     for (int r = 0; r < 16; r++) {
-                        const int kl = 32 * sub + acc_row(r, hh);
-                        const bool ok = kloc0 + kl < ext_k && (!g.causal || kglob0 + kl <= qglob) && (sub == 0 || two);
-                        s[sub][r] = ok ? s[sub][r] : kNegInf;
+                        s[sub][r] = 32 * sub + acc_row0(r) < lim_h ? s[sub][r] : kNegInf;
                         mx = fmaxf(mx, s[sub][r]);
                     }
             }
@@ -501,20 +507,28 @@ __global__ void __launch_bounds__(256, 2) attn_dq(const BwdArgs a) {
             const T* Vs = Ks + kBlk * LD;
             const int nsub = (!(g.causal && kglob0 + 32 > wave_qlast) && kloc0 + 32 < ext_k) ? 2 : 1;
             const bool plain = kloc0 + kBlk <= ext_k && (!g.causal || kglob0 + kBlk - 1 <= wave_qfirst);
-            for (int sub = 0; sub < nsub; sub++) {
-                f32x16 s = X::template rows_times_own<LD>(Ks, sub, ln, hh, qf);
-                const f32x16 dp = X::template rows_times_own<LD>(Vs, sub, ln, hh, dof);
+            // keys [0, lim) of the block are inside the tile and visible to this lane's query
+            int lim = ext_k - kloc0;
+            if (g.causal) lim = min(lim, qglob - kglob0 + 1);
+            const int lim_h = lim - 4 * hh;
+            // (two copies of the body: blocks that are visible as a whole skip the mask arithmetic)
+            auto body = [&](auto masked) {
+                for (int sub = 0; sub < nsub; sub++) {
+                    f32x16 s = X::template rows_times_own<LD>(Ks, sub, ln, hh, qf);
+                    const f32x16 dp = X::template rows_times_own<LD>(Vs, sub, ln, hh, dof);
 #pragma unroll
-                for (int r = 0; r < 16; r++) {
-                    const int kl = 32 * sub + acc_row(r, hh);
-                    const bool ok = plain || (kloc0 + kl < ext_k && (!g.causal || kglob0 + kl <= qglob));
-                    const float p = ok ? __builtin_amdgcn_exp2f(s[r] * sc2 - lse) : 0.f;
-                    s[r] = p * (dp[r] - D);
+                    for (int r = 0; r < 16; r++) {
+                        float p = __builtin_amdgcn_exp2f(s[r] * sc2 - lse);
+                        if (decltype(masked)::value) p = 32 * sub + acc_row0(r) < lim_h ? p : 0.f;
+                        s[r] = p * (dp[r] - D);
+                    }
+                    typename X::Packed pk;
+                    X::pack(s, pk);
+                    X::template cols_times_acc<LD>(dQ, Ks, sub, lane, pk);
                 }
-                typename X::Packed pk;
-                X::pack(s, pk);
-                X::template cols_times_acc<LD>(dQ, Ks, sub, lane, pk);
-            }
+            };
+            if (plain) body(std::false_type{});
+            else body(std::true_type{});
         }
         if (it + 1 < nit) stash((it + 1) & 1);
         __syncthreads();
@@ -599,6 +613,9 @@ __global__ void __launch_bounds__(256, X::kDkvBlocks) attn_dkv(const BwdArgs a) 
             const int sub0 = (g.causal && qglob0 + 31 < wave_kfirst) ? 1 : 0;
             const int nsub = qloc0 + 32 < ext_q ? 2 : 1;
             const bool plain = qloc0 + kBlk <= ext_q && (!g.causal || wave_klast <= qglob0);
+            const int lo = g.causal ? max(kglob - qglob0, 0) : 0, hi = ext_q - qloc0;
+            const int lo_h = lo - 4 * hh;
+            const unsigned width = (unsigned)max(hi - lo, 0);
             // (not unrolled: the second pass would keep a second set of temporaries alive and spill)
 #pragma unroll 1
             for (int sub = sub0; sub < nsub; sub++) {
@@ -616,8 +633,9 @@ __global__ void __launch_bounds__(256, X::kDkvBlocks) attn_dkv(const BwdArgs a) 
                 typename X::Packed pk;
 #pragma unroll
                 for (int r = 0; r < 16; r++) {
-                    const int ql = 32 * sub + acc_row(r, hh);
-                    const bool ok = plain || (qloc0 + ql < ext_q && (!g.causal || kglob <= qglob0 + ql));
+                    // queries [lo, hi) of the block are inside the tile and see this lane's key: one unsigned
+                    // comparison of the register's row, shifted by the lane half, against the width of that range
+                    const bool ok = plain || (unsigned)(32 * sub + acc_row0(r) - lo_h) < width;
                     const float p = ok ? __builtin_amdgcn_exp2f(s[r] * sc2 - lse_r[r]) : 0.f;
                     X::set(pk, r, p);
                     s[r] = p * (dp[r] - d_r[r]);
