@@ -18,13 +18,20 @@ struct Column {
     int ncol_tile;    // number of columns in this tile (= ext1 * ext2 * ext3)
 };
 
-__device__ __forceinline__ Column column_of(const TiledView& v, int64_t col) {
+// (callers keep the number of columns below 2^31, so the index arithmetic is 32-bit: a 64-bit division
+// costs some hundred instructions on this hardware)
+__device__ __forceinline__ Column column_of(const TiledView& v, int64_t col64) {
     Column c;
-    c.c1 = (int)(col % v.shape[1]);
-    col /= v.shape[1];
-    c.c2 = (int)(col % v.shape[2]);
-    c.c3 = (int)(col / v.shape[2]);
-    const int t1 = c.c1 / v.base[1], t2 = c.c2 / v.base[2], t3 = c.c3 / v.base[3];
+    unsigned col = (unsigned)col64;
+    const unsigned s1 = (unsigned)v.shape[1], s2 = (unsigned)v.shape[2];
+    unsigned q = col / s1;
+    c.c1 = (int)(col - q * s1);
+    col = q;
+    q = col / s2;
+    c.c2 = (int)(col - q * s2);
+    c.c3 = (int)q;
+    const int t1 = (int)((unsigned)c.c1 / (unsigned)v.base[1]), t2 = (int)((unsigned)c.c2 / (unsigned)v.base[2]);
+    const int t3 = (int)((unsigned)c.c3 / (unsigned)v.base[3]);
     const int l1 = t1 * v.base[1], l2 = t2 * v.base[2], l3 = t3 * v.base[3];
     const int e1 = min(v.base[1], v.shape[1] - l1), e2 = min(v.base[2], v.shape[2] - l2);
     const int e3 = min(v.base[3], v.shape[3] - l3);

@@ -26,13 +26,17 @@ __device__ __forceinline__ void walk(const TiledView& v, int lane, Fn fn) {
     const int g0 = v.grid[0];
     if constexpr (NV > 0) {
         const int vpt = (v.base[0] + 64 * V - 1) / (64 * V);
+        int l = 0, j = 0;                 // slot it is vector j of tile l (counted up: no division per slot)
 #pragma unroll
         for (int it = 0; it < NV; it++) {
-            const int l = it / vpt, j = it - l * vpt;
             if (l < g0) {
                 const int ext = ext0_of(v, l);
                 const int e = (j * 64 + lane) * V;
                 if (e < ext) fn(it, l, e, ext);
+            }
+            if (++j == vpt) {
+                j = 0;
+                l++;
             }
         }
     } else {
@@ -47,7 +51,7 @@ template <typename T, int V, int NV>
 __global__ void __launch_bounds__(256) ln_fwd_fused(TiledView X, TiledView Y, TiledView S, TiledView G, TiledView Bt,
                                                      float eps, int64_t ncols) {
     const int lane = threadIdx.x & 63;
-    const int64_t col = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t col = (int64_t)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);      // wave-uniform: the index arithmetic below runs on the scalar unit
     if (col >= ncols) return;
     const Column c = column_of(X, col);
     const int N = X.shape[0];
@@ -101,7 +105,7 @@ template <typename T, int V, int NV>
 __global__ void __launch_bounds__(256) ln_bwd_fused(TiledView X, TiledView S, TiledView G, TiledView dY, TiledView dR,
                                                      TiledView dX, int has_res, int64_t ncols) {
     const int lane = threadIdx.x & 63;
-    const int64_t col = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t col = (int64_t)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);      // wave-uniform: the index arithmetic below runs on the scalar unit
     if (col >= ncols) return;
     const Column c = column_of(X, col);
     const int N = X.shape[0];
@@ -154,7 +158,7 @@ template <typename T, int V>
 __global__ void __launch_bounds__(256) ln_stats_tile(const T* x, float* stats, int m, int64_t n, int64_t count_before,
                                                       int64_t finalize_total, float eps) {
     const int lane = threadIdx.x & 63;
-    const int64_t col = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t col = (int64_t)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);      // wave-uniform: the index arithmetic below runs on the scalar unit
     if (col >= n) return;
     const T* p = x + col * m;
     float s = 0.f;
@@ -193,7 +197,7 @@ template <typename T, int V>
 __global__ void __launch_bounds__(256) ln_apply_tile(const T* x, const float* stats, const float* gamma, const float* beta,
                                                       T* y, int m, int64_t n) {
     const int lane = threadIdx.x & 63;
-    const int64_t col = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t col = (int64_t)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);      // wave-uniform: the index arithmetic below runs on the scalar unit
     if (col >= n) return;
     const float mean = stats[2 * col], rstd = stats[2 * col + 1];
     for (int e = lane * V; e < m; e += 64 * V) {
@@ -211,7 +215,7 @@ template <typename T, int V>
 __global__ void __launch_bounds__(256) ln_bwd_sums_tile(const T* x, const float* stats, const float* gamma, const T* dy,
                                                          float* sums, int init, int m, int64_t n) {
     const int lane = threadIdx.x & 63;
-    const int64_t col = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t col = (int64_t)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);      // wave-uniform: the index arithmetic below runs on the scalar unit
     if (col >= n) return;
     const float mean = stats[2 * col], rstd = stats[2 * col + 1];
     float a = 0.f, b = 0.f;
@@ -239,7 +243,7 @@ template <typename T, int V>
 __global__ void __launch_bounds__(256) ln_bwd_dx_tile(const T* x, const float* stats, const float* gamma, const T* dy,
                                                        const float* sums, const T* dres, T* dx, int m, int64_t n, float inv_N) {
     const int lane = threadIdx.x & 63;
-    const int64_t col = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t col = (int64_t)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);      // wave-uniform: the index arithmetic below runs on the scalar unit
     if (col >= n) return;
     const float mean = stats[2 * col], rstd = stats[2 * col + 1];
     const float a = sums[2 * col] * inv_N, b = sums[2 * col + 1] * inv_N;
@@ -693,7 +697,7 @@ int32_t nnt_layernorm_fwd(nnt_ctx* ctx, nnt_tensor* X, nnt_tensor* gamma, nnt_te
         const int nv = (int)(((X->base[0] + 64 * V - 1) / (64 * V)) * X->grid[0]);
         const TiledView vx = X->view(), vy = Y->view(), vs = stats->view(), vg = gamma->view(), vb = beta->view();
         const int64_t ncols = n_columns(X);
-        if ((ncols + 3) / 4 > INT32_MAX) return fail(ctx, NNT_EINVAL, "nnt_layernorm_fwd: tensor too large");
+        if (ncols > INT32_MAX) return fail(ctx, NNT_EINVAL, "nnt_layernorm_fwd: tensor too large");
         std::vector<Access> acc = {X->all(kRead), gamma->all(kRead), beta->all(kRead), Y->all(kWrite), stats->all(kWrite)};
         return submit(ctx, acc, [=](hipStream_t st) {
             return dtype == NNT_F32 ? launch_ln_fwd<float>(st, vec, nv, vx, vy, vs, vg, vb, eps, ncols)
@@ -756,7 +760,7 @@ int32_t nnt_layernorm_bwd(nnt_ctx* ctx, nnt_tensor* X, nnt_tensor* stats, nnt_te
         const TiledView vr = dRes ? dRes->view() : vdy;
         const int has_res = dRes != nullptr;
         const int64_t ncols = n_columns(X);
-        if ((ncols + 3) / 4 > INT32_MAX) return fail(ctx, NNT_EINVAL, "nnt_layernorm_bwd: tensor too large");
+        if (ncols > INT32_MAX) return fail(ctx, NNT_EINVAL, "nnt_layernorm_bwd: tensor too large");
         std::vector<Access> acc = {X->all(kRead), stats->all(kRead), gamma->all(kRead), dY->all(kRead), dX->all(kWrite)};
         if (dRes) acc.push_back(dRes->all(kRead));
         rc = rowsum_tensor(ctx, 1, dY, X, stats, dgamma, dbeta);

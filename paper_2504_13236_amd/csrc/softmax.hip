@@ -28,13 +28,17 @@ __device__ __forceinline__ void walk_keys(const TiledView& v, int lane, int kmax
     const int g0 = v.grid[0];
     if constexpr (NV > 0) {
         const int vpt = (v.base[0] + 64 * V - 1) / (64 * V);
+        int l = 0, j = 0;                 // slot it is vector j of tile l (counted up: no division per slot)
 #pragma unroll
         for (int it = 0; it < NV; it++) {
-            const int l = it / vpt, j = it - l * vpt;
             if (l < g0) {
                 const int ext = ext0_of(v, l);
                 const int e = (j * 64 + lane) * V;
                 if (e < ext && l * v.base[0] + e < kmax) fn(it, l, e, ext);
+            }
+            if (++j == vpt) {
+                j = 0;
+                l++;
             }
         }
     } else {
@@ -48,7 +52,7 @@ __device__ __forceinline__ void walk_keys(const TiledView& v, int lane, int kmax
 template <typename T, int V, int NV>
 __global__ void __launch_bounds__(256) softmax_fwd_fused(TiledView A, TiledView S, float scale, int causal, int64_t ncols) {
     const int lane = threadIdx.x & 63;
-    const int64_t col = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t col = (int64_t)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);      // wave-uniform: the index arithmetic below runs on the scalar unit
     if (col >= ncols) return;
     const Column c = column_of(A, col);
     const int nk = A.shape[0];
@@ -143,7 +147,7 @@ __global__ void __launch_bounds__(256) softmax_fwd_fused(TiledView A, TiledView 
 template <typename T, int V, int NV>
 __global__ void __launch_bounds__(256) softmax_bwd_fused(TiledView P, TiledView dP, int64_t ncols) {
     const int lane = threadIdx.x & 63;
-    const int64_t col = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t col = (int64_t)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);      // wave-uniform: the index arithmetic below runs on the scalar unit
     if (col >= ncols) return;
     const Column c = column_of(P, col);
     const int nk = P.shape[0];
@@ -188,7 +192,7 @@ template <typename T, int V>
 __global__ void __launch_bounds__(256) softmax_stats_tile(const T* a, float* stats, int tk, int tq, int64_t ncol, int k0, int q0,
                                                           int causal, float scale, int init) {
     const int lane = threadIdx.x & 63;
-    const int64_t col = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t col = (int64_t)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);      // wave-uniform: the index arithmetic below runs on the scalar unit
     if (col >= ncol) return;
     const int q = q0 + (int)(col % tq);
     const int kvis = causal ? min(tk, q + 1 - k0) : tk;     // rows of this tile visible to q (may be <= 0)
@@ -229,7 +233,7 @@ template <typename T, int V>
 __global__ void __launch_bounds__(256) softmax_apply_tile(T* a, const float* stats, int tk, int tq, int64_t ncol, int k0, int q0,
                                                           int causal, float scale) {
     const int lane = threadIdx.x & 63;
-    const int64_t col = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t col = (int64_t)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);      // wave-uniform: the index arithmetic below runs on the scalar unit
     if (col >= ncol) return;
     const int q = q0 + (int)(col % tq);
     const int kvis = causal ? min(tk, q + 1 - k0) : tk;
@@ -247,7 +251,7 @@ __global__ void __launch_bounds__(256) softmax_apply_tile(T* a, const float* sta
 template <typename T, int V>
 __global__ void __launch_bounds__(256) softmax_bwd_dot_tile(const T* p, const T* dp, float* dots, int tk, int64_t ncol, int init) {
     const int lane = threadIdx.x & 63;
-    const int64_t col = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t col = (int64_t)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);      // wave-uniform: the index arithmetic below runs on the scalar unit
     if (col >= ncol) return;
     float dot = 0.f;
     for (int e = lane * V; e < tk; e += 64 * V) {
@@ -264,7 +268,7 @@ __global__ void __launch_bounds__(256) softmax_bwd_dot_tile(const T* p, const T*
 template <typename T, int V>
 __global__ void __launch_bounds__(256) softmax_bwd_apply_tile(const T* p, T* dp, const float* dots, int tk, int64_t ncol) {
     const int lane = threadIdx.x & 63;
-    const int64_t col = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t col = (int64_t)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);      // wave-uniform: the index arithmetic below runs on the scalar unit
     if (col >= ncol) return;
     const float dot = dots[col];
     for (int e = lane * V; e < tk; e += 64 * V) {
@@ -419,7 +423,7 @@ int32_t nnt_softmax_fwd(nnt_ctx* ctx, nnt_tensor* A, nnt_tensor* stats, float sc
         const int nv = (int)(((A->base[0] + 64 * V - 1) / (64 * V)) * g0);
         const TiledView va = A->view(), vs = stats->view();
         const int64_t ncols = n_columns(A);
-        if ((ncols + 3) / 4 > INT32_MAX) return fail(ctx, NNT_EINVAL, "nnt_softmax_fwd: tensor too large");
+        if (ncols > INT32_MAX) return fail(ctx, NNT_EINVAL, "nnt_softmax_fwd: tensor too large");
         return submit(ctx, {A->all(kReadWrite), stats->all(kWrite)}, [=](hipStream_t st) {
             const dim3 grid((unsigned)((ncols + 3) / 4)), block(256);
             DISPATCH_TVN(dtype, vec, nv, softmax_fwd_fused, va, vs, scale, (int)causal, ncols);
@@ -477,7 +481,7 @@ int32_t nnt_softmax_bwd(nnt_ctx* ctx, nnt_tensor* P, nnt_tensor* dP) {
         const int nv = (int)(((P->base[0] + 64 * V - 1) / (64 * V)) * g0);
         const TiledView vp = P->view(), vd = dP->view();
         const int64_t ncols = n_columns(P);
-        if ((ncols + 3) / 4 > INT32_MAX) return fail(ctx, NNT_EINVAL, "nnt_softmax_bwd: tensor too large");
+        if (ncols > INT32_MAX) return fail(ctx, NNT_EINVAL, "nnt_softmax_bwd: tensor too large");
         return submit(ctx, {P->all(kRead), dP->all(kReadWrite)}, [=](hipStream_t st) {
             const dim3 grid((unsigned)((ncols + 3) / 4)), block(256);
             DISPATCH_TVN(dtype, vec, nv, softmax_bwd_fused, vp, vd, ncols);
