@@ -30,11 +30,61 @@ __global__ void __launch_bounds__(256) splitk_reduce(const SplitReduce* tab, flo
     const int n = t.rows - i < 4 ? t.rows - i : 4;
     float acc[4] = {0.f, 0.f, 0.f, 0.f};
     const float* p = t.ws + (int64_t)j * t.ldw + i;       // 16-byte aligned: ldw is a multiple of 4
-    for (int sl = 0; sl < t.nsplit; sl++) {
+    // slices are added in their fixed order; four loads are started before the first of them is used
+    int sl = 0;
+    for (; sl + 4 <= t.nsplit; sl += 4) {
+        float4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; u++) v[u] = *reinterpret_cast<const float4*>(p + (int64_t)(sl + u) * t.slice);
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+            acc[0] += v[u].x; acc[1] += v[u].y; acc[2] += v[u].z; acc[3] += v[u].w;
+        }
+    }
+    for (; sl < t.nsplit; sl++) {
         const float4 v = *reinterpret_cast<const float4*>(p + (int64_t)sl * t.slice);
         acc[0] += v.x; acc[1] += v.y; acc[2] += v.z; acc[3] += v.w;
     }
     TO* c = static_cast<TO*>(t.C) + (t.m0 + i) + (int64_t)(t.n0 + j) * t.ldc;
+    if constexpr (sizeof(TO) == 4) {
+        // four whole rows at a 16-byte aligned address: one vector access instead of four
+        if (n == 4 && (reinterpret_cast<uintptr_t>(c) & 15) == 0) {
+            float4 o = make_float4(alpha * acc[0], alpha * acc[1], alpha * acc[2], alpha * acc[3]);
+            if (t.bias) {
+                const float* bp = t.bias + t.m0 + i;
+                o.x += bp[0]; o.y += bp[1]; o.z += bp[2]; o.w += bp[3];
+            }
+            float4* c4 = reinterpret_cast<float4*>(c);
+            if (beta != 0.f) {
+                const float4 old = *c4;
+                o.x += beta * old.x; o.y += beta * old.y; o.z += beta * old.z; o.w += beta * old.w;
+            }
+            *c4 = o;
+            return;
+        }
+    } else {
+        if (n == 4 && (reinterpret_cast<uintptr_t>(c) & 7) == 0) {
+            float o[4];
+            uint2* c2 = reinterpret_cast<uint2*>(c);
+            uint2 old = make_uint2(0u, 0u);
+            if (beta != 0.f) old = *c2;
+            const uint32_t ow[2] = {old.x, old.y};
+#pragma unroll
+            for (int jj = 0; jj < 4; jj++) {
+                o[jj] = alpha * acc[jj];
+                if (t.bias) o[jj] += t.bias[t.m0 + i + jj];
+                if (beta != 0.f) o[jj] += beta * __uint_as_float((jj & 1) ? (ow[jj >> 1] & 0xffff0000u) : (ow[jj >> 1] << 16));
+            }
+            uint32_t h[4];
+#pragma unroll
+            for (int jj = 0; jj < 4; jj++) {
+                const __bf16 b = (__bf16)o[jj];
+                h[jj] = (uint32_t)__builtin_bit_cast(uint16_t, b);
+            }
+            *c2 = make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
+            return;
+        }
+    }
     for (int jj = 0; jj < n; jj++) {
         float v = alpha * acc[jj];
         if (t.bias) v += t.bias[t.m0 + i + jj];
