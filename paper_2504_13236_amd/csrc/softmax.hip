@@ -61,7 +61,14 @@ __global__ void __launch_bounds__(256) softmax_fwd_fused(TiledView A, TiledView 
     float mx = kNegInf;
     float sum = 0.f;
     if constexpr (NV > 0) {
-        // the column fits in registers: maximum, then shifted exponentials, from one read
+        // the column fits in registers: maximum, then shifted exponentials, from one read.  The cached
+        // values are the scores in units of log 2 (scale and log2(e) folded into one factor); masked
+        // entries and slots the walk does not reach end up as exact zeros, so the output pass needs no mask.
+#pragma unroll
+        for (int i = 0; i < NV; i++)
+#pragma unroll
+            for (int k = 0; k < V; k++) cache[i][k] = 0.f;
+        const float sc2 = scale * 1.4426950408889634f;
         walk_keys<V, NV>(A, lane, kmax, [&](int slot, int l, int e, int ext) {
             const T* p = col_ptr<const T>(A, c, l, ext);
             float x[V];
@@ -71,10 +78,10 @@ __global__ void __launch_bounds__(256) softmax_fwd_fused(TiledView A, TiledView 
 #pragma unroll
                 for (int k = 0; k < V; k++) x[k] = kNegInf;
             }
-            const int k0 = l * A.base[0] + e;
+            const int lim = p ? kmax - (l * A.base[0] + e) : 0;      // elements [0, lim) of the vector are visible
 #pragma unroll
             for (int k = 0; k < V; k++) {
-                x[k] = (k0 + k < kmax && p) ? x[k] * scale : kNegInf;
+                x[k] = k < lim ? x[k] * sc2 : kNegInf;
                 mx = fmaxf(mx, x[k]);
                 cache[slot][k] = x[k];
             }
@@ -83,11 +90,12 @@ __global__ void __launch_bounds__(256) softmax_fwd_fused(TiledView A, TiledView 
         walk_keys<V, NV>(A, lane, kmax, [&](int slot, int l, int e, int ext) {
 #pragma unroll
             for (int k = 0; k < V; k++) {
-                const float x = fexp(cache[slot][k] - mx);
+                const float x = __builtin_amdgcn_exp2f(cache[slot][k] - mx);
                 sum += x;
                 cache[slot][k] = x;
             }
         });
+        mx *= 0.6931471805599453f;        // back to natural units for the statistics
     } else {
         // long column: one read for both statistics -- every lane keeps a running maximum and a sum
         // of exponentials shifted by it, rescaled when its maximum moves (the merge rule of the
@@ -124,12 +132,12 @@ __global__ void __launch_bounds__(256) softmax_fwd_fused(TiledView A, TiledView 
         if (!p) return;
         const int k0 = l * A.base[0] + e;
         float x[V];
-        if (k0 >= kmax) {
-#pragma unroll
-            for (int k = 0; k < V; k++) x[k] = 0.f;
-        } else if constexpr (NV > 0) {
+        if constexpr (NV > 0) {
 #pragma unroll
             for (int k = 0; k < V; k++) x[k] = cache[slot][k] * inv;
+        } else if (k0 >= kmax) {
+#pragma unroll
+            for (int k = 0; k < V; k++) x[k] = 0.f;
         } else {
             ldv<V>(p + e, x);
 #pragma unroll
