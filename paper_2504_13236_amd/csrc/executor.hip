@@ -43,6 +43,8 @@ static void mark_all_synced(nnt_ctx* ctx) {
     for (int s = 0; s < ctx->n_streams; s++) {
         for (hipEvent_t e : ctx->events[s]) ctx->event_pool.push_back(e);
         ctx->events[s].clear();
+        ctx->event_seq[s].clear();
+        ctx->task_key[s].clear();
         ctx->synced_seq[s] = ctx->tail_seq[s];
     }
 }
@@ -50,6 +52,33 @@ static void mark_all_synced(nnt_ctx* ctx) {
 static int32_t sync_all(nnt_ctx* ctx) {
     for (int s = 0; s < ctx->n_streams; s++) NNT_HIP(ctx, hipStreamSynchronize(ctx->streams[s]));
     mark_all_synced(ctx);
+    return NNT_OK;
+}
+
+// Which recorded sequence number of a stream covers `need`: the first one at or after it, or, if
+// there is none, the stream's tail (which then gets an event).  Pure bookkeeping, shared with the
+// host-side simulation.
+static uint64_t covering_seq(const std::vector<uint64_t>& recorded, uint64_t need, uint64_t tail, bool* fresh) {
+    auto it = std::lower_bound(recorded.begin(), recorded.end(), need);
+    *fresh = it == recorded.end();
+    return *fresh ? tail : *it;
+}
+
+// An event of stream `s` that completes no earlier than its task number `need`: the task's own event
+// when it has one, else one recorded now at the tail of the stream.
+static int32_t event_covering(nnt_ctx* ctx, int s, uint64_t need, hipEvent_t* ev, uint64_t* got) {
+    bool fresh;
+    *got = covering_seq(ctx->event_seq[s], need, ctx->tail_seq[s], &fresh);
+    if (!fresh) {
+        const size_t i = std::lower_bound(ctx->event_seq[s].begin(), ctx->event_seq[s].end(), need) - ctx->event_seq[s].begin();
+        *ev = ctx->events[s][i];
+        return NNT_OK;
+    }
+    int32_t rc = get_event(ctx, ev);
+    if (rc != NNT_OK) return rc;
+    NNT_HIP(ctx, hipEventRecord(*ev, ctx->streams[s]));
+    ctx->events[s].push_back(*ev);
+    ctx->event_seq[s].push_back(*got);
     return NNT_OK;
 }
 
@@ -73,6 +102,13 @@ void profile_mark(nnt_ctx* ctx, hipStream_t st, const char* label, double work, 
     p->work = work;
     p->bytes = bytes;
     p->launches = 1;
+}
+
+// What identifies a task when the flow repeats: the first tile it writes (else the first it touches).
+static const void* task_key_of(const std::vector<Access>& acc) {
+    for (const Access& a : acc)
+        if ((a.mode & kWrite) && a.count > 0) return a.first;
+    return acc.empty() ? nullptr : static_cast<const void*>(acc[0].first);
 }
 
 // Where a task goes and what it has to wait for: pure bookkeeping, no device calls (the host-side
@@ -152,8 +188,15 @@ int32_t submit(nnt_ctx* ctx, const std::vector<Access>& acc,
     hipStream_t st = ctx->streams[chosen];
     for (int s = 0; s < ns; s++) {
         if (!plan.wait_seq[s]) continue;
-        hipEvent_t ev = ctx->events[s][plan.wait_seq[s] - ctx->synced_seq[s] - 1];
+        // the task waited for is consumed across streams: from now on its like gets an event of its own
+        const uint64_t rel = plan.wait_seq[s] - ctx->synced_seq[s] - 1;
+        if (rel < ctx->task_key[s].size() && ctx->task_key[s][rel]) ctx->hot_producers.insert(ctx->task_key[s][rel]);
+        hipEvent_t ev;
+        uint64_t got;
+        int32_t wrc = event_covering(ctx, s, plan.wait_seq[s], &ev, &got);
+        if (wrc != NNT_OK) return wrc;
         NNT_HIP(ctx, hipStreamWaitEvent(st, ev, 0));
+        ctx->waited[chosen][s] = std::max(ctx->waited[chosen][s], got);
         ctx->stats.event_waits++;
     }
     nnt_ctx::ProfileRec prof;
@@ -184,12 +227,23 @@ int32_t submit(nnt_ctx* ctx, const std::vector<Access>& acc,
     ctx->stats.tasks++;
     ctx->stats.launches += n_launches;
     uint64_t seq = ++ctx->tail_seq[chosen];
-    hipEvent_t ev;
-    int32_t erc = get_event(ctx, &ev);
-    if (erc != NNT_OK) return erc;
-    NNT_HIP(ctx, hipEventRecord(ev, st));
-    ctx->events[chosen].push_back(ev);
     commit_task(acc, chosen, seq);
+    // A marker between two kernels costs the device more than a microsecond, and most tasks are only
+    // ever waited for by their successor on the same stream, so only the tasks known to be consumed
+    // across streams get an event of their own; a wait for any other task records one at the tail of
+    // that stream at that moment (and so may wait for later tasks of that stream as well: a branch
+    // that should overlap is serialised once, then its producer is known).  With one stream nothing
+    // is ever waited for.
+    const void* key = task_key_of(acc);
+    ctx->task_key[chosen].push_back(key);
+    if (ns > 1 && !ctx->serial && key && ctx->hot_producers.count(key)) {
+        hipEvent_t ev;
+        int32_t erc = get_event(ctx, &ev);
+        if (erc != NNT_OK) return erc;
+        NNT_HIP(ctx, hipEventRecord(ev, st));
+        ctx->events[chosen].push_back(ev);
+        ctx->event_seq[chosen].push_back(seq);
+    }
     // bound the number of live events in long runs without nnt_wait
     if (!ctx->capturing && ctx->events[chosen].size() > (1u << 16)) return sync_all(ctx);
     return NNT_OK;
@@ -230,6 +284,9 @@ int32_t nnt_sched_simulate(int32_t n_streams, int32_t serial, int32_t n_tiles, i
     if (n_tasks > 0 && (!task_first || !acc_tile || !acc_mode || !stream_out || !seq_out || !wait_seq_out)) return NNT_EINVAL;
     std::vector<TileDep> tiles((size_t)n_tiles);
     uint64_t tail[kMaxStreams] = {0}, synced[kMaxStreams] = {0}, waited[kMaxStreams][kMaxStreams] = {{0}};
+    std::vector<uint64_t> recorded[kMaxStreams];
+    std::vector<const void*> keys[kMaxStreams];
+    std::unordered_set<const void*> hot;
     int rr = 0;
     for (int t = 0; t < n_tasks; t++) {
         std::vector<Access> acc;
@@ -238,11 +295,26 @@ int32_t nnt_sched_simulate(int32_t n_streams, int32_t serial, int32_t n_tiles, i
             acc.push_back(Access{&tiles[(size_t)acc_tile[i]], 1, acc_mode[i]});
         }
         const TaskPlan plan = plan_task(acc, n_streams, serial != 0, tail, synced, waited, &rr);
+        // the waits as the executor would issue them: on the first recorded event that covers the
+        // task asked for, else on a new one at the tail of that stream
+        for (int s = 0; s < kMaxStreams; s++) {
+            uint64_t got = 0;
+            if (plan.wait_seq[s]) {
+                if (keys[s][plan.wait_seq[s] - 1]) hot.insert(keys[s][plan.wait_seq[s] - 1]);
+                bool fresh;
+                got = covering_seq(recorded[s], plan.wait_seq[s], tail[s], &fresh);
+                if (fresh) recorded[s].push_back(got);
+                waited[plan.chosen][s] = std::max(waited[plan.chosen][s], got);
+            }
+            wait_seq_out[(size_t)t * kMaxStreams + s] = (int64_t)got;
+        }
         const uint64_t seq = ++tail[plan.chosen];
         commit_task(acc, plan.chosen, seq);
+        const void* key = task_key_of(acc);
+        keys[plan.chosen].push_back(key);
+        if (n_streams > 1 && !serial && key && hot.count(key)) recorded[plan.chosen].push_back(seq);
         stream_out[t] = plan.chosen;
         seq_out[t] = (int64_t)seq;
-        for (int s = 0; s < kMaxStreams; s++) wait_seq_out[(size_t)t * kMaxStreams + s] = (int64_t)plan.wait_seq[s];
     }
     return NNT_OK;
 }
@@ -306,7 +378,11 @@ int32_t nnt_ctx_join(nnt_ctx* ctx) {
     for (int s = 1; s < ctx->n_streams; s++) {
         uint64_t tail = ctx->tail_seq[s];
         if (tail <= ctx->synced_seq[s] || ctx->waited[0][s] >= tail) continue;
-        NNT_HIP(ctx, hipStreamWaitEvent(s0, ctx->events[s][tail - ctx->synced_seq[s] - 1], 0));
+        hipEvent_t ev;
+        uint64_t got;
+        int32_t rc = event_covering(ctx, s, tail, &ev, &got);
+        if (rc != NNT_OK) return rc;
+        NNT_HIP(ctx, hipStreamWaitEvent(s0, ev, 0));
         ctx->waited[0][s] = tail;
     }
     return NNT_OK;

@@ -6,6 +6,7 @@
 #include <map>
 #include <memory>
 #include <string>
+#include <unordered_set>
 #include <vector>
 
 #include "nntile_mi.h"
@@ -108,7 +109,13 @@ struct nnt_ctx {
     uint64_t tail_seq[nnt::kMaxStreams];     // last sequence number issued per stream
     uint64_t synced_seq[nnt::kMaxStreams];   // everything up to here is known complete
     uint64_t waited[nnt::kMaxStreams][nnt::kMaxStreams];  // waited[s][d]: s already waits for d up to this seq
-    std::vector<hipEvent_t> events[nnt::kMaxStreams];     // events[s][seq - synced_seq[s] - 1]
+    std::vector<hipEvent_t> events[nnt::kMaxStreams];     // events recorded on stream s since the last sync ...
+    std::vector<uint64_t> event_seq[nnt::kMaxStreams];    // ... and the sequence number each of them covers (ascending)
+    // Which tasks get an event of their own: those whose result (identified by the first tile the task
+    // writes) a task on another stream has waited for before.  A flow that repeats every step settles on
+    // the few producers that are consumed across streams; everything else is covered on demand.
+    std::unordered_set<const void*> hot_producers;
+    std::vector<const void*> task_key[nnt::kMaxStreams];  // key of the task with sequence number synced_seq + 1 + i
     std::vector<hipEvent_t> event_pool;
     std::vector<hipEvent_t> capture_events;               // fork / join events of the open capture
     int rr = 0;                      // round-robin cursor

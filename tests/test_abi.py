@@ -232,3 +232,26 @@ def test_executor_spreads_independent_tasks_and_chains_dependent_ones(capi):
     out_s = np.zeros(1, np.int32)
     assert capi.nnt_sched_simulate.raw(2, 0, 1, 1, first.ctypes.data, bad_tile.ctypes.data, mode.ctypes.data,
                                        out_s.ctypes.data, z.ctypes.data, z.ctypes.data) == capi.NNT_EINVAL
+
+
+def test_executor_learns_which_tasks_need_an_event_of_their_own(capi):
+    """Events are recorded on demand; a task that another stream had to wait for is remembered (by the first
+    tile it writes), and its next occurrence gets an event of its own, so that the wait is exact again.
+    Period: a writes t0; b writes t1; c reads t1 and writes t2 (stays behind b, so b is no longer the tail of
+    its stream); d reads t0 and t1 and writes t3 (runs behind a, must wait for b on the other stream)."""
+    period = [[(0, 2)], [(1, 2)], [(1, 1), (2, 2)], [(0, 1), (1, 1), (3, 2)]]
+    reps = 4
+    stream, seq, waits = _simulate(capi, 2, 0, 4, period * reps)
+    for rep in range(reps):
+        a, b, c, d = (4 * rep + i for i in range(4))
+        assert stream[c] == stream[b] and seq[c] == seq[b] + 1
+        sb = int(stream[b])
+        assert stream[d] != sb
+        w = int(waits[d, sb])
+        if rep == 0:
+            assert w == seq[c]          # no event of b's own yet: the wait covers the tail of that stream
+        else:
+            assert w == seq[b]          # b's like is known to be consumed across streams: exact wait
+    # one stream, or serial mode: no waits at all
+    stream, seq, waits = _simulate(capi, 1, 0, 4, period * 2)
+    assert not stream.any() and not waits.any()
