@@ -190,7 +190,10 @@ int32_t submit(nnt_ctx* ctx, const std::vector<Access>& acc,
         if (!plan.wait_seq[s]) continue;
         // the task waited for is consumed across streams: from now on its like gets an event of its own
         const uint64_t rel = plan.wait_seq[s] - ctx->synced_seq[s] - 1;
-        if (rel < ctx->task_key[s].size() && ctx->task_key[s][rel]) ctx->hot_producers.insert(ctx->task_key[s][rel]);
+        if (rel < ctx->task_key[s].size() && ctx->task_key[s][rel]) {
+            if (ctx->hot_producers.size() > (1u << 16)) ctx->hot_producers.clear();      // stale keys of destroyed tensors: learn afresh
+            ctx->hot_producers.insert(ctx->task_key[s][rel]);
+        }
         hipEvent_t ev;
         uint64_t got;
         int32_t wrc = event_covering(ctx, s, plan.wait_seq[s], &ev, &got);
