@@ -247,8 +247,8 @@ int32_t submit(nnt_ctx* ctx, const std::vector<Access>& acc,
         ctx->events[chosen].push_back(ev);
         ctx->event_seq[chosen].push_back(seq);
     }
-    // bound the number of live events in long runs without nnt_wait
-    if (!ctx->capturing && ctx->events[chosen].size() > (1u << 16)) return sync_all(ctx);
+    // bound the bookkeeping of long runs without nnt_wait
+    if (!ctx->capturing && (ctx->events[chosen].size() > (1u << 16) || ctx->task_key[chosen].size() > (1u << 20))) return sync_all(ctx);
     return NNT_OK;
 }
 
