@@ -21,6 +21,7 @@ struct nnt_gpt2_block {
     nnt_gpt2_block_cfg cfg;
     nnt_tensor* s[NNT_BLK_NSLOTS];
     nnt_tensor* X;      // input of the last forward call
+    nnt::AdamGroup* adam_group;   // all twelve parameters as one launch (made by the first whole-operation Adam step)
 };
 
 // A chain of blocks: acts[i] feeds block i, acts[n] is the output; dacts[i] is the gradient of acts[i].
@@ -153,6 +154,7 @@ int32_t nnt_gpt2_block_create(nnt_ctx* ctx, const nnt_gpt2_block_cfg* cfg, nnt_t
 
 int32_t nnt_gpt2_block_destroy(nnt_gpt2_block* blk) {
     if (!blk) return NNT_EINVAL;
+    nnt::adam_group_destroy(blk->adam_group);
     delete blk;
     return NNT_OK;
 }
@@ -266,6 +268,15 @@ int32_t nnt_gpt2_block_adam(nnt_gpt2_block* b, int32_t step, const nnt_adam_cfg*
     for (int p = 0; p < 12; p++)
         if (!b->s[NNT_BLK_ADAM_M + p] || !b->s[NNT_BLK_ADAM_V + p])
             return fail(ctx, NNT_ESTATE, "nnt_gpt2_block_adam: the block was created without Adam moments");
+    if (ctx->granularity == NNT_GRAN_OP) {
+        if (!b->adam_group) {
+            if (ctx->capturing) return fail(ctx, NNT_ESTATE, "nnt_gpt2_block_adam: run the step once before capture");
+            nnt_tensor* lowp[12];
+            for (int p = 0; p < 12; p++) lowp[p] = (b->cfg.dtype == NNT_BF16 && p < 4) ? b->s[NNT_BLK_LOWP + p] : nullptr;
+            TRY(adam_group_create(ctx, 12, b->s + NNT_BLK_GRAD, b->s, b->s + NNT_BLK_ADAM_M, b->s + NNT_BLK_ADAM_V, lowp, &b->adam_group));
+        }
+        return adam_group_step(ctx, b->adam_group, cfg, step);
+    }
     for (int p = 0; p < 12; p++) {
         nnt_tensor* lowp = (b->cfg.dtype == NNT_BF16 && p < 4) ? b->s[NNT_BLK_LOWP + p] : nullptr;
         TRY(nnt_adam_step(ctx, cfg, step, b->s[NNT_BLK_GRAD + p], b->s[p], b->s[NNT_BLK_ADAM_M + p], b->s[NNT_BLK_ADAM_V + p], lowp));

@@ -111,6 +111,7 @@ EwGeom tiled_geom(const nnt_tensor* t) {
     EwGeom g;
     g.v = t->view();
     g.n_single = 0;
+    g.numel = nullptr;
     g.tiled = 1;
     return g;
 }
@@ -405,6 +406,95 @@ int32_t nnt_adam_step(nnt_ctx* ctx, const nnt_adam_cfg* cfg, int32_t step, nnt_t
         return f;
     });
 }
+
+}  // extern "C"
+
+// ------------------------------------------------------------------ Adam on a group of parameters in one launch
+// The twelve parameters of a block are nine small vectors and four matrices: as twelve launches the
+// step costs more in launch latency than in memory traffic.  A group keeps, in device memory, the
+// tile-pointer tables of all its tensors back to back and the element count of every tile, and the
+// elementwise kernel runs over that union (blockIdx.y = entry).
+namespace nnt {
+
+struct AdamGroup {
+    std::vector<nnt_tensor*> G, P, M, V, LP;     // LP entries may be null
+    void** tabs = nullptr;                        // 5 tables of `entries` pointers each: g, p, m, v, low-precision copy
+    int64_t* numel = nullptr;
+    int64_t entries = 0, max_numel = 0;
+    bool vec = true;
+    double bytes = 0.0;
+};
+
+void adam_group_destroy(AdamGroup* a) {
+    if (!a) return;
+    if (a->tabs) (void)hipFree(a->tabs);
+    if (a->numel) (void)hipFree(a->numel);
+    delete a;
+}
+
+int32_t adam_group_create(nnt_ctx* ctx, int n, nnt_tensor* const* G, nnt_tensor* const* P, nnt_tensor* const* M,
+                          nnt_tensor* const* V, nnt_tensor* const* LP, AdamGroup** out) {
+    *out = nullptr;
+    std::unique_ptr<AdamGroup, void (*)(AdamGroup*)> a(new AdamGroup(), adam_group_destroy);
+    std::vector<void*> tg, tp, tm, tv, tl;
+    std::vector<int64_t> ne;
+    for (int i = 0; i < n; i++) {
+        nnt_tensor *g = G[i], *p = P[i], *m = M[i], *v = V[i], *lp = LP ? LP[i] : nullptr;
+        if (!g || !p || !m || !v) return fail(ctx, NNT_EINVAL, "adam group: null tensor");
+        if (!same_tiling(g, p) || !same_tiling(g, m) || !same_tiling(g, v) || (lp && !same_tiling(g, lp)))
+            return fail(ctx, NNT_EINVAL, "adam group: operands tiled differently");
+        if (g->dtype != NNT_F32 || p->dtype != NNT_F32 || m->dtype != NNT_F32 || v->dtype != NNT_F32 || (lp && lp->dtype != NNT_BF16))
+            return fail(ctx, NNT_EDTYPE, "adam group: g, p, m, v must be fp32 and the low-precision copy bf16");
+        a->vec = a->vec && all_aligned(g) && all_aligned(p) && all_aligned(m) && all_aligned(v) && (!lp || all_aligned(lp));
+        a->bytes += present_numel(p) * (28 + (lp ? 2 : 0));
+        for (int64_t t = 0; t < p->ntiles; t++) {
+            if (!p->tiles[t]) continue;
+            if (!g->tiles[t] || !m->tiles[t] || !v->tiles[t] || (lp && !lp->tiles[t])) return fail(ctx, NNT_EINVAL, "adam group: missing tile");
+            tg.push_back(g->tiles[t]); tp.push_back(p->tiles[t]); tm.push_back(m->tiles[t]); tv.push_back(v->tiles[t]);
+            tl.push_back(lp ? lp->tiles[t] : nullptr);
+            ne.push_back(p->tile_numel(t));
+            a->max_numel = std::max(a->max_numel, p->tile_numel(t));
+        }
+        a->G.push_back(g); a->P.push_back(p); a->M.push_back(m); a->V.push_back(v); a->LP.push_back(lp);
+    }
+    a->entries = (int64_t)ne.size();
+    if (a->entries == 0 || a->entries > 65535) return fail(ctx, NNT_EINVAL, "adam group: no tiles, or too many for one launch");
+    const size_t E = (size_t)a->entries;
+    std::vector<void*> all;
+    for (auto* t : {&tg, &tp, &tm, &tv, &tl}) all.insert(all.end(), t->begin(), t->end());
+    NNT_HIP(ctx, hipMalloc(&a->tabs, 5 * E * sizeof(void*)));
+    NNT_HIP(ctx, hipMalloc(&a->numel, E * sizeof(int64_t)));
+    NNT_HIP(ctx, hipMemcpy(a->tabs, all.data(), 5 * E * sizeof(void*), hipMemcpyHostToDevice));
+    NNT_HIP(ctx, hipMemcpy(a->numel, ne.data(), E * sizeof(int64_t), hipMemcpyHostToDevice));
+    *out = a.release();
+    return NNT_OK;
+}
+
+// One Adam step on every tensor of the group: one task, one launch (whole-operation granularity).
+int32_t adam_group_step(nnt_ctx* ctx, AdamGroup* a, const nnt_adam_cfg* cfg, int32_t step) {
+    OpTag tag(ctx, "adam", a->bytes, true);
+    AdamF f = make_adam(step, cfg->lr, cfg->beta1, cfg->beta2, cfg->eps, cfg->weight_decay);
+    const size_t E = (size_t)a->entries;
+    f.g = Operand{a->tabs, nullptr}; f.p = Operand{a->tabs + E, nullptr}; f.m = Operand{a->tabs + 2 * E, nullptr};
+    f.v = Operand{a->tabs + 3 * E, nullptr}; f.lp = Operand{a->tabs + 4 * E, nullptr};
+    EwGeom g = single_geom(0);
+    g.numel = a->numel;
+    std::vector<Access> acc;
+    for (size_t i = 0; i < a->P.size(); i++) {
+        acc.push_back(a->P[i]->all(kReadWrite));
+        acc.push_back(a->G[i]->all(kRead));
+        acc.push_back(a->M[i]->all(kReadWrite));
+        acc.push_back(a->V[i]->all(kReadWrite));
+        if (a->LP[i]) acc.push_back(a->LP[i]->all(kWrite));
+    }
+    const int64_t mx = a->max_numel, nt = a->entries;
+    const bool vec = a->vec;
+    return submit(ctx, acc, [=](hipStream_t st) { return launch_ew(st, f, g, mx, nt, vec); });
+}
+
+}  // namespace nnt
+
+extern "C" {
 
 int32_t nnt_sgd_step(nnt_ctx* ctx, const nnt_sgd_cfg* cfg, nnt_tensor* G, nnt_tensor* P, nnt_tensor* V, nnt_tensor* LP) {
     NNT_CHECK_CTX(ctx);

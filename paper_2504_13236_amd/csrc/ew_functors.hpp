@@ -19,6 +19,7 @@ constexpr int kUnroll = 4;
 struct EwGeom {
     TiledView v;        // tiling of the operands (tensor form)
     int64_t n_single;   // element count (tile form)
+    const int64_t* numel;   // element count per entry of the pointer tables (group form: tiles of several tensors), or nullptr
     int32_t tiled;
 };
 
@@ -37,7 +38,7 @@ __device__ __forceinline__ T* pick(const Operand& o, int tile) {
 template <typename F>
 __global__ void __launch_bounds__(256) ew_kernel(const F f, const EwGeom g, const int vec) {
     const int tile = blockIdx.y;
-    const int64_t n = g.tiled ? tile_numel(g.v, tile) : g.n_single;
+    const int64_t n = g.numel ? g.numel[tile] : (g.tiled ? tile_numel(g.v, tile) : g.n_single);
     typename F::Ctx c;
     if (!f.setup(c, g, tile)) return;
     constexpr int V = F::V, NIN = F::NIN > 0 ? F::NIN : 1;

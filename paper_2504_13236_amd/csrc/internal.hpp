@@ -177,6 +177,13 @@ void profile_mark(nnt_ctx* ctx, hipStream_t st, const char* label, double work, 
 int32_t submit(nnt_ctx* ctx, const std::vector<Access>& acc,
                const std::function<int32_t(hipStream_t)>& launch, int n_launches = 1);
 int32_t ensure_scratch(nnt_ctx* ctx, int64_t elems);
+
+// Adam on several parameter tensors in one launch (elementwise.hip); the group owns small device tables.
+struct AdamGroup;
+int32_t adam_group_create(nnt_ctx* ctx, int n, nnt_tensor* const* G, nnt_tensor* const* P, nnt_tensor* const* M,
+                          nnt_tensor* const* V, nnt_tensor* const* LP, AdamGroup** out);
+int32_t adam_group_step(nnt_ctx* ctx, AdamGroup* a, const nnt_adam_cfg* cfg, int32_t step);
+void adam_group_destroy(AdamGroup* a);
 void drop_plans_of(nnt_ctx* ctx, uint64_t tensor_id);
 
 inline bool same_tiling(const nnt_tensor* a, const nnt_tensor* b) {

@@ -102,7 +102,7 @@ def test_block_C1_forward_backward_adam(mods, gran):
     ref = oracle_run(cfg, inp, True)
     got = gpu_run(tiled, cfg, inp, workload.base_tiles(cfg), True, gran=gran)
     compare(got, ref, "f32", True)
-    assert got["stats"]["tasks"] > (500 if gran else 40)
+    assert got["stats"]["tasks"] > (500 if gran else 30)      # whole-operation flow: ~40 tasks, the Adam step of all parameters is one
 
 
 @pytest.mark.parametrize("tiles", [dict(e=24, m=56, s=24, b=1, j=1, i=40), dict(e=128, m=512, s=64, b=2, j=2, i=64)])
