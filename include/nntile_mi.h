@@ -468,7 +468,10 @@ NNT_API int32_t nnt_gpt2_block_destroy(nnt_gpt2_block* blk);
  * tile_s, tile_b).  forward keeps X (by reference) for backward. */
 NNT_API int32_t nnt_gpt2_block_forward(nnt_gpt2_block* blk, nnt_tensor* X, nnt_tensor* Out);
 NNT_API int32_t nnt_gpt2_block_backward(nnt_gpt2_block* blk, nnt_tensor* dOut, nnt_tensor* dX);
-/* Adam step on all 12 parameters; bf16 blocks also refresh the bf16 weight copies. */
+/* Adam step on all 12 parameters; bf16 blocks also refresh the bf16 weight copies.
+ * With one launch per operation the twelve tensors are updated by a single launch;
+ * the first such call allocates two small device tables (tile pointers, tile sizes),
+ * so it must come before nnt_capture_begin (NNT_ESTATE otherwise). */
 NNT_API int32_t nnt_gpt2_block_adam(nnt_gpt2_block* blk, int32_t step, const nnt_adam_cfg* cfg);
 /* SGD-with-momentum step on all 12 parameters; the velocities live in the slots
  * NNT_BLK_ADAM_M + parameter (the second-moment slots are not touched). */
