@@ -22,47 +22,92 @@ template <> __device__ __forceinline__ float ldf<bf16_t>(const bf16_t* p) { retu
 __device__ __forceinline__ void stf(float* p, float v) { *p = v; }
 __device__ __forceinline__ void stf(bf16_t* p, float v) { *p = f2bf(v); }
 
-// one thread per element of Y, first axis fastest: coalesced along the embedding axis on both sides
-template <typename TW, typename TY>
+// VE consecutive elements of the embedding axis as one access (VE = 4 needs every tile extent along that
+// axis to be a multiple of 4 and 16-byte aligned tiles; VE = 1 otherwise)
+template <int VE> __device__ __forceinline__ void ldw(const float* p, float (&f)[VE]) { ldv<VE>(p, f); }
+template <int VE> __device__ __forceinline__ void ldw(const bf16_t* p, float (&f)[VE]) {
+    if constexpr (VE == 4) {
+        const uint2 x = *reinterpret_cast<const uint2*>(p);
+        f[0] = __uint_as_float(x.x << 16); f[1] = __uint_as_float(x.x & 0xffff0000u);
+        f[2] = __uint_as_float(x.y << 16); f[3] = __uint_as_float(x.y & 0xffff0000u);
+    } else {
+        f[0] = bf2f(p[0]);
+    }
+}
+template <int VE> __device__ __forceinline__ void stw(float* p, const float (&f)[VE]) { stv<VE>(p, f); }
+template <int VE> __device__ __forceinline__ void stw(bf16_t* p, const float (&f)[VE]) {
+    if constexpr (VE == 4) {
+        uint2 x;
+        x.x = (uint32_t)f2bf(f[0]) | ((uint32_t)f2bf(f[1]) << 16);
+        x.y = (uint32_t)f2bf(f[2]) | ((uint32_t)f2bf(f[3]) << 16);
+        *reinterpret_cast<uint2*>(p) = x;
+    } else {
+        p[0] = f2bf(f[0]);
+    }
+}
+
+// (e, s, b) of the i-th group of VE elements, first axis fastest; 32-bit arithmetic when the count allows
+// (a 64-bit division costs about a hundred instructions)
+template <int VE>
+__device__ __forceinline__ void group_coords(int64_t i, int64_t total, int Ne, int Ns, int (&c)[kMaxDim]) {
+    const int NeV = Ne / VE;
+    if (total <= 0x7fffffff) {
+        const unsigned u = (unsigned)i, q = u / (unsigned)NeV, q2 = q / (unsigned)Ns;
+        c[0] = (int)(u - q * (unsigned)NeV) * VE; c[1] = (int)(q - q2 * (unsigned)Ns); c[2] = (int)q2;
+    } else {
+        c[0] = (int)(i % NeV) * VE; c[1] = (int)((i / NeV) % Ns); c[2] = (int)(i / ((int64_t)NeV * Ns));
+    }
+    c[3] = 0;
+}
+
+// one thread per group of VE elements of Y, first axis fastest: coalesced along the embedding axis on both sides
+template <typename TW, typename TY, int VE>
 __global__ void __launch_bounds__(256) embedding_fwd_kernel(const int32_t* tokens, TiledView W, TiledView Y, int64_t total) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= total) return;
-    const int Ne = Y.shape[0], Ns = Y.shape[1];
-    int c[kMaxDim] = {(int)(i % Ne), (int)((i / Ne) % Ns), (int)(i / ((int64_t)Ne * Ns)), 0};
+    const int Ns = Y.shape[1];
+    int c[kMaxDim];
+    group_coords<VE>(i, total, Y.shape[0], Ns, c);
     int tile;
     int64_t off;
     locate(Y, c, tile, off);
     const int tok = tokens[c[1] + (int64_t)Ns * c[2]];
-    float v = 0.f;
+    float v[VE];
+#pragma unroll
+    for (int k = 0; k < VE; k++) v[k] = 0.f;
     if (tok >= 0 && tok < W.shape[1]) {
         const int cw[kMaxDim] = {c[0], tok, 0, 0};
         int tw;
         int64_t ow;
         locate(W, cw, tw, ow);
-        v = ldf(static_cast<const TW*>(W.tiles[tw]) + ow);
+        ldw<VE>(static_cast<const TW*>(W.tiles[tw]) + ow, v);
     }
-    stf(static_cast<TY*>(Y.tiles[tile]) + off, v);
+    stw<VE>(static_cast<TY*>(Y.tiles[tile]) + off, v);
 }
 
-// one thread per element of dY; rows of dW that several positions share are summed with hardware
+// one thread per group of VE elements of dY; rows of dW that several positions share are summed with hardware
 // floating-point atomics (the order of those additions is not fixed)
-template <typename TY>
+template <typename TY, int VE>
 __global__ void __launch_bounds__(256) embedding_bwd_kernel(const int32_t* tokens, TiledView dY, TiledView dW, int64_t total) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= total) return;
-    const int Ne = dY.shape[0], Ns = dY.shape[1];
-    const int c[kMaxDim] = {(int)(i % Ne), (int)((i / Ne) % Ns), (int)(i / ((int64_t)Ne * Ns)), 0};
+    const int Ns = dY.shape[1];
+    int c[kMaxDim];
+    group_coords<VE>(i, total, dY.shape[0], Ns, c);
     const int tok = tokens[c[1] + (int64_t)Ns * c[2]];
     if (tok < 0 || tok >= dW.shape[1]) return;
     int tile;
     int64_t off;
     locate(dY, c, tile, off);
-    const float g = ldf(static_cast<const TY*>(dY.tiles[tile]) + off);
+    float g[VE];
+    ldw<VE>(static_cast<const TY*>(dY.tiles[tile]) + off, g);
     const int cw[kMaxDim] = {c[0], tok, 0, 0};
     int tw;
     int64_t ow;
     locate(dW, cw, tw, ow);
-    unsafeAtomicAdd(static_cast<float*>(dW.tiles[tw]) + ow, g);
+    float* dst = static_cast<float*>(dW.tiles[tw]) + ow;
+#pragma unroll
+    for (int k = 0; k < VE; k++) unsafeAtomicAdd(dst + k, g[k]);
 }
 
 // one thread per column (s, b) of the probabilities P[v, s, b]: loss of the column, and P[label] -= 1
@@ -122,17 +167,27 @@ int32_t nnt_embedding_fwd(nnt_ctx* ctx, const int32_t* tokens, nnt_tensor* W, nn
     if (W->ndim != 2 || W->shape[0] != Y->shape[0]) return fail(ctx, NNT_EINVAL, "nnt_embedding_fwd: W must be [N_e, N_v]");
     for (void* p : W->tiles)
         if (!p) return fail(ctx, NNT_EINVAL, "nnt_embedding_fwd: structural-zero tiles not allowed");
-    const int64_t total = Y->shape[0] * Y->shape[1] * Y->shape[2];
+    // four elements of the embedding axis per thread when every tile holds whole groups of four at aligned addresses
+    bool vec = W->base[0] % 4 == 0 && W->shape[0] % 4 == 0 && Y->base[0] % 4 == 0;
+    for (void* p : W->tiles) vec = vec && aligned16(p);
+    for (void* p : Y->tiles) vec = vec && aligned16(p);
+    const int64_t total = Y->shape[0] * Y->shape[1] * Y->shape[2] / (vec ? 4 : 1);
     if ((total + 255) / 256 > INT32_MAX) return fail(ctx, NNT_EINVAL, "nnt_embedding_fwd: tensor too large");
     const TiledView vw = W->view(), vy = Y->view();
     const int dw = W->dtype, dy = Y->dtype;
-    OpTag tag(ctx, "embedding_fwd", (double)total * (W->elem_size() + Y->elem_size()), true);
+    OpTag tag(ctx, "embedding_fwd", (double)Y->shape[0] * Y->shape[1] * Y->shape[2] * (W->elem_size() + Y->elem_size()), true);
     return submit(ctx, {W->all(kRead), Y->all(kWrite)}, [=](hipStream_t st) {
         const dim3 grid((unsigned)((total + 255) / 256)), block(256);
-        if (dw == NNT_F32 && dy == NNT_F32) hipLaunchKernelGGL((embedding_fwd_kernel<float, float>), grid, block, 0, st, tokens, vw, vy, total);
-        else if (dw == NNT_F32) hipLaunchKernelGGL((embedding_fwd_kernel<float, bf16_t>), grid, block, 0, st, tokens, vw, vy, total);
-        else if (dy == NNT_F32) hipLaunchKernelGGL((embedding_fwd_kernel<bf16_t, float>), grid, block, 0, st, tokens, vw, vy, total);
-        else hipLaunchKernelGGL((embedding_fwd_kernel<bf16_t, bf16_t>), grid, block, 0, st, tokens, vw, vy, total);
+#define NNT_EMB_FWD(TW, TY)                                                                                              \
+    do {                                                                                                                 \
+        if (vec) hipLaunchKernelGGL((embedding_fwd_kernel<TW, TY, 4>), grid, block, 0, st, tokens, vw, vy, total);       \
+        else hipLaunchKernelGGL((embedding_fwd_kernel<TW, TY, 1>), grid, block, 0, st, tokens, vw, vy, total);           \
+    } while (0)
+        if (dw == NNT_F32 && dy == NNT_F32) NNT_EMB_FWD(float, float);
+        else if (dw == NNT_F32) NNT_EMB_FWD(float, bf16_t);
+        else if (dy == NNT_F32) NNT_EMB_FWD(bf16_t, float);
+        else NNT_EMB_FWD(bf16_t, bf16_t);
+#undef NNT_EMB_FWD
         return hipGetLastError() == hipSuccess ? (int32_t)NNT_OK : (int32_t)NNT_EHIP;
     });
 }
@@ -146,6 +201,8 @@ int32_t nnt_embedding_bwd(nnt_ctx* ctx, const int32_t* tokens, nnt_tensor* dY, n
         return fail(ctx, NNT_EINVAL, "nnt_embedding_bwd: dW must be fp32 [N_e, N_v]");
     for (void* p : dW->tiles)
         if (!p) return fail(ctx, NNT_EINVAL, "nnt_embedding_bwd: structural-zero tiles not allowed");
+    // one element per thread: the atomics of a wavefront then fall on consecutive words (four elements per
+    // thread made the adjoint twice as slow: every atomic instruction touched every fourth word of 1 KB)
     const int64_t total = dY->shape[0] * dY->shape[1] * dY->shape[2];
     if ((total + 255) / 256 > INT32_MAX) return fail(ctx, NNT_EINVAL, "nnt_embedding_bwd: tensor too large");
     const TiledView vw = dW->view(), vy = dY->view();
@@ -153,8 +210,8 @@ int32_t nnt_embedding_bwd(nnt_ctx* ctx, const int32_t* tokens, nnt_tensor* dY, n
     OpTag tag(ctx, "embedding_bwd", (double)total * (dY->elem_size() + 8), true);
     return submit(ctx, {dY->all(kRead), dW->all(kReadWrite)}, [=](hipStream_t st) {
         const dim3 grid((unsigned)((total + 255) / 256)), block(256);
-        if (dy == NNT_F32) hipLaunchKernelGGL((embedding_bwd_kernel<float>), grid, block, 0, st, tokens, vy, vw, total);
-        else hipLaunchKernelGGL((embedding_bwd_kernel<bf16_t>), grid, block, 0, st, tokens, vy, vw, total);
+        if (dy == NNT_F32) hipLaunchKernelGGL((embedding_bwd_kernel<float, 1>), grid, block, 0, st, tokens, vy, vw, total);
+        else hipLaunchKernelGGL((embedding_bwd_kernel<bf16_t, 1>), grid, block, 0, st, tokens, vy, vw, total);
         return hipGetLastError() == hipSuccess ? (int32_t)NNT_OK : (int32_t)NNT_EHIP;
     });
 }
