@@ -618,7 +618,29 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
             if (ranges[mw.task].empty()) ranges[mw.task] = cut_into_slices(P, t0, ktot[mw.task], S, elem);
             red.push_back(add_slice_tasks(P, t0, mw, ranges[mw.task], P->d_ws + (int64_t)w * S * slice, bm, bn, by_slice));
         }
-        for (int sidx = 0; sidx < S; sidx++) P->wgs_op.insert(P->wgs_op.end(), by_slice[sidx].begin(), by_slice[sidx].end());
+        // Launch order of the slices: workgroup p runs on XCD p mod 8, and the workgroups of one k-slice read
+        // one k-range of both operands, so each slice is dealt to one XCD (slice s to XCD s mod 8): that XCD's
+        // L2 then fetches the range once for all macro-tiles.  An XCD whose queue runs dry takes from the
+        // longest one.
+        {
+            std::vector<GemmWg> q[8];
+            for (int sidx = 0; sidx < S; sidx++) q[sidx & 7].insert(q[sidx & 7].end(), by_slice[sidx].begin(), by_slice[sidx].end());
+            size_t head[8] = {0, 0, 0, 0, 0, 0, 0, 0}, left = 0;
+            for (int x = 0; x < 8; x++) left += q[x].size();
+            while (left > 0) {
+                const int x = (int)(P->wgs_op.size() & 7);
+                if (head[x] < q[x].size()) {
+                    P->wgs_op.push_back(q[x][head[x]++]);
+                } else {
+                    int longest = 0;
+                    for (int y = 1; y < 8; y++)
+                        if (q[y].size() - head[y] > q[longest].size() - head[longest]) longest = y;
+                    P->wgs_op.push_back(q[longest].back());
+                    q[longest].pop_back();
+                }
+                left--;
+            }
+        }
         P->red_blocks = (int)((slice / 4 + 255) / 256);
         P->slice_elems = slice;
         NNT_HIP(ctx, hipMalloc((void**)&P->d_red, red.size() * sizeof(SplitReduce)));
