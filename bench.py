@@ -275,6 +275,15 @@ def measure(args, cfg, inp, attention, capi, tiled, torch, workload):
     prof = ctx.profile_read()
     ctx.profile(False)
     ctx.set_serial(False)
+    # what a pair of timing events reads with nothing between them (median of 50): every per-kernel duration of
+    # the serial pass contains about this much marker time on top of launch gaps
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(50)]
+    with torch.cuda.stream(ctx.streams[0]):
+        for a, b in pairs:
+            a.record()
+            b.record()
+    torch.cuda.synchronize()
+    empty_pair_us = sorted(a.elapsed_time(b) for a, b in pairs)[25] * 1e3
     ms_per_step = dt / args.steps * 1e3
     flops = nblk * workload.model_flops(cfg, tile_skip=True, visible_only=attention == "fused")
     value = flops / (dt / args.steps) / 1e12
@@ -348,7 +357,8 @@ def measure(args, cfg, inp, attention, capi, tiled, torch, workload):
            # the metric's second and third figure (time-weighted over the serial per-kernel pass)
            "tile_gemm_pct_mfma_peak": 100.0 * (summary["tile_gemm_weights"]["frac_of_peak"] or 0.0),
            "elementwise_GBps": summary["memory_bound_kernels"]["GB/s"],
-           "roofline": roofline, "summary": summary, "kernels": kernels, "executor": ctx.stats()}
+           "roofline": roofline, "summary": summary, "kernels": kernels, "executor": ctx.stats(),
+           "empty_event_pair_us": empty_pair_us}
     if nblk > 1:
         stack.close()
     for b in blks:
