@@ -358,3 +358,35 @@ def test_graph_capture_replays_task_flow(mods):
         capi.nnt_graph_destroy(g)
         ref = A.astype(np.float64) @ B.astype(np.float64)
         check(want, ref + D.gelu(ref), "f32", "captured flow")
+
+
+@pytest.mark.parametrize("n_streams", [1, 4])
+def test_per_task_timing_records(mods, n_streams):
+    """nnt_profile_*: every task is bracketed by timing events; the records come back aggregated per
+    operation label."""
+    capi, tiled = mods
+    r = rng(21)
+    X = r.standard_normal((256, 64, 2)).astype(np.float32)
+    with tiled.Context(n_streams=n_streams) as ctx:
+        tX = T(tiled, ctx, X, (128, 32, 2), "f32")
+        tY = T(tiled, ctx, X, (128, 32, 2), "f32")
+        tG = tiled.TiledTensor(ctx, "f32", X.shape, (128, 32, 2))
+        ctx.profile(True)
+        for _ in range(3):
+            capi.nnt_add(ctx.h, 1.0, tX.h, 1.0, tY.h)
+        capi.nnt_gelu(ctx.h, capi.NNT_GELU_TANH, tY.h, tG.h)
+        ctx.wait()
+        capi.nnt_add(ctx.h, 1.0, tX.h, 1.0, tY.h)
+        rec = ctx.profile_read()
+        ctx.profile(False)
+        assert set(rec) == {"add", "gelu"}
+        assert rec["add"]["tasks"] == 4 and rec["add"]["launches"] == 4 and rec["gelu"]["tasks"] == 1
+        assert all(0.0 < e["ms"] < 50.0 for e in rec.values())
+        assert rec["add"]["unit"] == "bytes" and rec["add"]["work"] == 4 * 3 * X.size * 4
+        check(tY.download(), 5.0 * X, "f32", "sum")
+        # a second round reuses the events of the first
+        ctx.profile(True)
+        capi.nnt_gelu(ctx.h, capi.NNT_GELU_TANH, tY.h, tG.h)
+        rec = ctx.profile_read()
+        ctx.profile(False)
+        assert set(rec) == {"gelu"} and rec["gelu"]["tasks"] == 1 and rec["gelu"]["ms"] > 0.0
