@@ -250,41 +250,55 @@ def attention_bwd(Q, K, V, P, dB):
 # --------------------------------------------------------------------------
 # the GPT-2 block (pre-LN, biases on all four linear layers, no dropout)
 # --------------------------------------------------------------------------
-def block_forward(p, X, N_h, eps=1e-5, gelu_variant="tanh", causal=True):
-    """p: dict of the 12 parameters.  Returns Out and everything the adjoint needs."""
+def _silent(stage):
+    pass
+
+
+def block_forward(p, X, N_h, eps=1e-5, gelu_variant="tanh", causal=True, progress=_silent):
+    """p: dict of the 12 parameters.  Returns Out and everything the adjoint needs.
+    `progress(stage)` is called after each layer (large cases take minutes; no arithmetic depends on it)."""
     c = {}
     X = np.asarray(X, F64)
     c["X"] = X
     c["X1"], c["mean1"], c["rstd1"] = layernorm_fwd(X, p["gamma1"], p["beta1"], eps)
     QKV = linear_fwd(p["W_qkv"], c["X1"], p["b_qkv"])
     c["Q"], c["K"], c["V"] = split_heads(QKV, N_h, 3)
+    progress("forward: layer norm 1, QKV")
     Bh, c["P"] = attention_fwd(c["Q"], c["K"], c["V"], causal)
     c["Bm"] = merge_heads([Bh])
+    progress("forward: attention")
     Y = linear_fwd(p["W_o"], c["Bm"], p["b_o"])
     c["X2"] = X + Y
     c["X3"], c["mean2"], c["rstd2"] = layernorm_fwd(c["X2"], p["gamma2"], p["beta2"], eps)
     c["H1"] = linear_fwd(p["W_1"], c["X3"], p["b_1"])
+    progress("forward: output projection, layer norm 2, fc1")
     c["G"] = gelu(c["H1"], gelu_variant)
     H2 = linear_fwd(p["W_2"], c["G"], p["b_2"])
     Out = c["X2"] + H2
+    progress("forward: GELU, fc2")
     return Out, c
 
 
-def block_backward(p, c, dOut, N_h, gelu_variant="tanh"):
+def block_backward(p, c, dOut, N_h, gelu_variant="tanh", progress=_silent):
     """Exact adjoint of block_forward for the upstream gradient dOut.
     Returns dX and a dict with the 12 parameter gradients."""
     g = {}
     dOut = np.asarray(dOut, F64)
     dG, g["W_2"], g["b_2"] = linear_bwd(p["W_2"], c["G"], dOut)
+    progress("backward: fc2")
     dH1 = dG * gelu_grad(c["H1"], gelu_variant)
     dX3, g["W_1"], g["b_1"] = linear_bwd(p["W_1"], c["X3"], dH1)
+    progress("backward: GELU, fc1")
     d2, g["gamma2"], g["beta2"] = layernorm_bwd(c["X2"], p["gamma2"], c["mean2"], c["rstd2"], dX3)
     dX2 = dOut + d2
     dBm, g["W_o"], g["b_o"] = linear_bwd(p["W_o"], c["Bm"], dX2)
+    progress("backward: layer norm 2, output projection")
     (dB,) = split_heads(dBm, N_h, 1)
     dQ, dK, dV = attention_bwd(c["Q"], c["K"], c["V"], c["P"], dB)
     dQKV = merge_heads([dQ, dK, dV])
+    progress("backward: attention")
     dX1, g["W_qkv"], g["b_qkv"] = linear_bwd(p["W_qkv"], c["X1"], dQKV)
+    progress("backward: QKV")
     d1, g["gamma1"], g["beta1"] = layernorm_bwd(c["X"], p["gamma1"], c["mean1"], c["rstd1"], dX1)
     dX = dX2 + d1
     return dX, g

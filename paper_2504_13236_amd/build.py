@@ -74,8 +74,17 @@ def resource_usage(stderr: str) -> dict:
     return out
 
 
-def _compile(src: str) -> str:
+def _newest_header() -> float:
+    hs = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".hpp")]
+    hs += [os.path.join(ROOT, "include", f) for f in os.listdir(os.path.join(ROOT, "include"))]
+    return max(os.path.getmtime(h) for h in hs)
+
+
+def _compile(src: str, only_if_stale: bool = False) -> str:
     obj = os.path.join(OBJ, os.path.basename(src) + ".o")
+    if only_if_stale and os.path.exists(obj) and os.path.getmtime(obj) > max(os.path.getmtime(src), _newest_header(),
+                                                                              os.path.getmtime(__file__)):
+        return obj
     in_flight = os.path.basename(src) in IN_FLIGHT_SOURCES
     cmd = ["hipcc", *FLAGS, *(["-save-temps=obj"] if in_flight else []), "-c", src, "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
@@ -95,12 +104,13 @@ def _compile(src: str) -> str:
     return obj
 
 
-def build_library(jobs: int | None = None, verbose: bool = True) -> str:
+def build_library(jobs: int | None = None, verbose: bool = True, only_stale: bool = False) -> str:
+    """Compiles every source (or, with only_stale, those older than their object file) and links."""
     os.makedirs(OBJ, exist_ok=True)
     srcs = sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".hip"))
     jobs = jobs or min(8, len(srcs), os.cpu_count() or 1)
     with concurrent.futures.ThreadPoolExecutor(jobs) as ex:
-        objs = list(ex.map(_compile, srcs))
+        objs = list(ex.map(lambda f: _compile(f, only_stale), srcs))
     cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
@@ -111,5 +121,5 @@ def build_library(jobs: int | None = None, verbose: bool = True) -> str:
 
 
 if __name__ == "__main__":
-    build_library()
+    build_library(only_stale="--stale" in sys.argv[1:])
     sys.exit(0)

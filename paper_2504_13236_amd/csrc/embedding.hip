@@ -110,9 +110,30 @@ __global__ void __launch_bounds__(256) embedding_bwd_kernel(const int32_t* token
     for (int k = 0; k < VE; k++) unsafeAtomicAdd(dst + k, g[k]);
 }
 
-// one thread per column (s, b) of the probabilities P[v, s, b]: loss of the column, and P[label] -= 1
+// one thread per column (s, b) of the logits X[v, s, b]: keeps the label's logit (the SoftMax
+// subroutines then overwrite X with the probabilities)
 template <typename T>
-__global__ void __launch_bounds__(256) ce_label_kernel(const int32_t* labels, TiledView P, float* losses, int64_t ncols) {
+__global__ void __launch_bounds__(256) ce_logit_kernel(const int32_t* labels, TiledView X, float* logit, int64_t ncols) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= ncols) return;
+    const int Ns = X.shape[1];
+    const int lab = labels[i];
+    float x = 0.f;
+    if (lab >= 0 && lab < X.shape[0]) {
+        const int c[kMaxDim] = {lab, (int)(i % Ns), (int)(i / Ns), 0};
+        int tile;
+        int64_t off;
+        locate(X, c, tile, off);
+        x = ldf(static_cast<const T*>(X.tiles[tile]) + off);
+    }
+    logit[i] = x;
+}
+
+// one thread per column (s, b) of the probabilities P[v, s, b]: loss of the column from the kept logit
+// and the column's fp32 statistics, -(x - max - log(sum)) (not from the stored probability, which may
+// have been rounded to bf16 or have underflowed), and P[label] -= 1
+template <typename T>
+__global__ void __launch_bounds__(256) ce_label_kernel(const int32_t* labels, TiledView P, TiledView S, float* losses, int64_t ncols) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= ncols) return;
     const int Ns = P.shape[1];
@@ -124,9 +145,13 @@ __global__ void __launch_bounds__(256) ce_label_kernel(const int32_t* labels, Ti
         int64_t off;
         locate(P, c, tile, off);
         T* p = static_cast<T*>(P.tiles[tile]) + off;
-        const float pr = ldf(p);
-        loss = -logf(fmaxf(pr, 1e-37f));
-        stf(p, pr - 1.f);
+        const int cs[kMaxDim] = {0, c[1], c[2], 0};
+        int ts;
+        int64_t os;
+        locate(S, cs, ts, os);
+        const float* st = static_cast<const float*>(S.tiles[ts]) + os;      // (maximum, sum of shifted exponentials)
+        loss = -(losses[i] - st[0] - logf(st[1]));
+        stf(p, ldf(p) - 1.f);
     }
     losses[i] = loss;
 }
@@ -222,18 +247,31 @@ int32_t nnt_cross_entropy(nnt_ctx* ctx, nnt_tensor* X, const int32_t* labels, nn
     if (X->ndim != 3) return fail(ctx, NNT_EINVAL, "nnt_cross_entropy: the logits must be [N_v, N_s, N_b]");
     for (void* p : X->tiles)
         if (!p) return fail(ctx, NNT_EINVAL, "nnt_cross_entropy: structural-zero tiles not allowed");
-    // subroutines 1 and 2 of the softmax over the vocabulary axis, in place
-    int32_t rc = nnt_softmax_fwd(ctx, X, stats, 1.f, 0);
-    if (rc != NNT_OK) return rc;
     const int64_t ncols = X->shape[1] * X->shape[2];
     const TiledView vx = X->view();
     const int dt = X->dtype;
-    OpTag tag(ctx, "cross_entropy_labels", (double)ncols * (2.0 * X->elem_size() + 12), true);
+    const dim3 grid((unsigned)((ncols + 255) / 256)), block(256);
+    // the label's logit of every column, kept in `losses` until the last kernel turns it into the loss
+    // (ordered before the in-place softmax by its read of X, and the last kernel after it by its write)
+    int32_t rc;
+    {
+        OpTag tag(ctx, "cross_entropy_logits", (double)ncols * (X->elem_size() + 8), true);
+        rc = submit(ctx, {X->all(kRead)}, [=](hipStream_t st) {
+            if (dt == NNT_F32) hipLaunchKernelGGL((ce_logit_kernel<float>), grid, block, 0, st, labels, vx, losses, ncols);
+            else hipLaunchKernelGGL((ce_logit_kernel<bf16_t>), grid, block, 0, st, labels, vx, losses, ncols);
+            return hipGetLastError() == hipSuccess ? (int32_t)NNT_OK : (int32_t)NNT_EHIP;
+        });
+        if (rc != NNT_OK) return rc;
+    }
+    // subroutines 1 and 2 of the softmax over the vocabulary axis, in place
+    rc = nnt_softmax_fwd(ctx, X, stats, 1.f, 0);
+    if (rc != NNT_OK) return rc;
+    const TiledView vs = stats->view();
+    OpTag tag(ctx, "cross_entropy_labels", (double)ncols * (2.0 * X->elem_size() + 20), true);
     // the label entries can sit in any vocabulary tile: the task takes the whole tensor
-    return submit(ctx, {X->all(kReadWrite)}, [=](hipStream_t st) {
-        const dim3 grid((unsigned)((ncols + 255) / 256)), block(256);
-        if (dt == NNT_F32) hipLaunchKernelGGL((ce_label_kernel<float>), grid, block, 0, st, labels, vx, losses, ncols);
-        else hipLaunchKernelGGL((ce_label_kernel<bf16_t>), grid, block, 0, st, labels, vx, losses, ncols);
+    return submit(ctx, {X->all(kReadWrite), stats->all(kRead)}, [=](hipStream_t st) {
+        if (dt == NNT_F32) hipLaunchKernelGGL((ce_label_kernel<float>), grid, block, 0, st, labels, vx, vs, losses, ncols);
+        else hipLaunchKernelGGL((ce_label_kernel<bf16_t>), grid, block, 0, st, labels, vx, vs, losses, ncols);
         if (hipGetLastError() != hipSuccess) return (int32_t)NNT_EHIP;
         hipLaunchKernelGGL(sum_kernel, dim3(1), dim3(1024), 0, st, losses, ncols, loss);
         return hipGetLastError() == hipSuccess ? (int32_t)NNT_OK : (int32_t)NNT_EHIP;

@@ -7,8 +7,8 @@
 // tiles of that token through the tile-pointer table; the token's values stay in
 // registers between the statistics pass and the output pass when they fit, so a
 // whole tiled tensor costs one read and one write.  All statistics are fp32; the
-// variance is accumulated about a value of the token itself, which keeps the
-// one-pass formula free of cancellation.
+// variance is the mean of the squared deviations from the mean (two passes over
+// the cached token), never a difference of two large sums.
 #include "colwise.hpp"
 #include "internal.hpp"
 
@@ -56,29 +56,33 @@ __global__ void __launch_bounds__(256) ln_fwd_fused(TiledView X, TiledView Y, Ti
     const Column c = column_of(X, col);
     const int N = X.shape[0];
     float cache[NV > 0 ? NV : 1][V];
-    float K;
-    {
-        float k1[1];
-        ldv<1>(col_ptr<const T>(X, c, 0, ext0_of(X, 0)), k1);
-        K = k1[0];
-    }
-    float s1 = 0.f, s2 = 0.f;
+    // Two passes, mean first and then the squared deviations from it (the one-pass forms cancel when one
+    // element of the token lies far from the rest).  The second pass runs over the register cache when
+    // the token fits there and re-reads the token otherwise (it is still in the L2 of this wave's XCD).
+    float s1 = 0.f;
     walk<V, NV>(X, lane, [&](int slot, int l, int e, int ext) {
         float x[V];
         ldv<V>(col_ptr<const T>(X, c, l, ext) + e, x);
 #pragma unroll
         for (int k = 0; k < V; k++) {
-            const float d = x[k] - K;
-            s1 += d;
-            s2 += d * d;
+            s1 += x[k];
             if constexpr (NV > 0) cache[slot][k] = x[k];
         }
     });
-    s1 = wave_sum(s1);
-    s2 = wave_sum(s2);
-    const float dm = s1 / (float)N;
-    const float mean = K + dm;
-    const float var = fmaxf(s2 / (float)N - dm * dm, 0.f);
+    const float mean = wave_sum(s1) / (float)N;
+    float s2 = 0.f;
+    walk<V, NV>(X, lane, [&](int slot, int l, int e, int ext) {
+        float x[V];
+        if constexpr (NV > 0) {
+#pragma unroll
+            for (int k = 0; k < V; k++) x[k] = cache[slot][k];
+        } else {
+            ldv<V>(col_ptr<const T>(X, c, l, ext) + e, x);
+        }
+#pragma unroll
+        for (int k = 0; k < V; k++) s2 += (x[k] - mean) * (x[k] - mean);
+    });
+    const float var = wave_sum(s2) / (float)N;
     const float rstd = 1.f / sqrtf(var + eps);
     walk<V, NV>(X, lane, [&](int slot, int l, int e, int ext) {
         float x[V], g[V], b[V];

@@ -16,25 +16,28 @@ def mods():
     return capi, tiled
 
 
-def oracle_run(cfg, inp, adam):
+def oracle_run(cfg, inp, adam, progress=None):
+    say = progress or (lambda stage: None)
     p64 = {k: np.asarray(inp[k], np.float64) for k in workload.PARAM_NAMES}
     if cfg.dtype == "bf16":
         # the block multiplies with bf16 copies of the fp32 master weights
         for k in ("W_qkv", "W_o", "W_1", "W_2"):
             p64[k] = D.round_to_bf16(inp[k]).astype(np.float64)
-    Out, cache = D.block_forward(p64, inp["X"], cfg.N_h, cfg.eps, cfg.gelu)
-    dX, grads = D.block_backward(p64, cache, inp["dOut"], cfg.N_h, cfg.gelu)
+    Out, cache = D.block_forward(p64, inp["X"], cfg.N_h, cfg.eps, cfg.gelu, progress=say)
+    dX, grads = D.block_backward(p64, cache, inp["dOut"], cfg.N_h, cfg.gelu, progress=say)
+    del cache
     res = {"Out": Out, "dX": dX, "grads": grads, "p0": {k: np.asarray(inp[k], np.float64) for k in workload.PARAM_NAMES}}
     if adam:
         res["adam"] = {k: D.adam_step(np.asarray(inp[k], np.float64), grads[k], 0.0, 0.0, 1, **workload.ADAM)
                        for k in workload.PARAM_NAMES}
+        say("Adam")
     return res
 
 
 _case_cache = {}
 
 
-def full_size_case(number, adam, **overrides):
+def full_size_case(number, adam, progress=None, **overrides):
     """(config, inputs, oracle results) of a full-size workload; the last one is kept, so that the two
     attention flows of one workload share one run of the fp64 oracle."""
     key = (number, adam, tuple(sorted(overrides.items())))
@@ -42,7 +45,7 @@ def full_size_case(number, adam, **overrides):
         _case_cache.clear()
         cfg = workload.CONFIGS[number].replace(**overrides) if overrides else workload.CONFIGS[number]
         inp = workload.generate(cfg)
-        _case_cache[key] = (cfg, inp, oracle_run(cfg, inp, adam))
+        _case_cache[key] = (cfg, inp, oracle_run(cfg, inp, adam, progress))
     return _case_cache[key]
 
 
@@ -73,23 +76,60 @@ def gpu_run(tiled, cfg, inp, tiles, adam, gran=0, n_streams=4, serial=False, fus
     return out
 
 
+# Adam's first step from zero moments moves a parameter by lr * g / (|g| + eps), i.e. by about lr in the
+# direction of the gradient's sign whatever its size: the updated parameter is a discontinuous function
+# of g at g = 0.  Where the oracle's gradient is well above the error the device's gradient may carry
+# (a multiple of the gradient tolerance), the sign is determined and the parameter is compared with the
+# oracle's own; on the complement (gradients that are zero or nearly so, the key bias above all: softmax
+# ignores a shift of all keys, so its exact gradient is 0 and the device delivers rounding noise of
+# either sign) the device's parameter is compared with the oracle's Adam formula applied to the gradient
+# the device produced.
+SIGN_SAFE = {"f32": 1e-3, "bf16": 5e-2}      # |g| > SIGN_SAFE * max|g|: 100x / 2.5x the gradient tolerance
+
+
+def compare_adam_parameter(name, got_p, got_g, ref, dtype):
+    """Max-norm relative error of an updated parameter against the oracle, masked as described above."""
+    g_ref = np.asarray(ref["grads"][name], np.float64)
+    p_ref = ref["adam"][name][0]
+    safe = np.abs(g_ref) > SIGN_SAFE[dtype] * np.abs(g_ref).max()
+    den = np.abs(p_ref).max()
+    err = 0.0
+    if safe.any():
+        err = float(np.abs(np.asarray(got_p, np.float64) - p_ref)[safe].max() / den)
+    if not safe.all():
+        p_formula, _, _ = D.adam_step(ref["p0"][name], got_g, 0.0, 0.0, 1, **workload.ADAM)
+        err = max(err, float(np.abs(np.asarray(got_p, np.float64) - p_formula)[~safe].max() / den))
+    return err, safe
+
+
+def tolerance_of(key, dtype):
+    """The stated tolerance, except for Adam's second moment in bf16 configurations: v = (1 - beta2) g^2 is
+    quadratic in the gradient, so a gradient within `tol` of the oracle's (in the max-norm, relative to
+    max|g|) gives |v - v_ref| = (1 - beta2) |g + g_ref| |g - g_ref| <= (2 + tol) tol max|v_ref|: twice the
+    gradient's tolerance is what the metric can promise for v.  (fp32 stays at the stated 1e-5.)"""
+    if dtype == "bf16" and key.startswith("adam_v_"):
+        return 2.0 * TOL[dtype] * (1.0 + TOL[dtype])
+    return TOL[dtype]
+
+
 def compare(got, ref, dtype, adam):
     tol = TOL[dtype]
     errs = {"Out": relerr(got["Out"], ref["Out"]), "dX": relerr(got["dX"], ref["dX"])}
     for k in workload.PARAM_NAMES:
         errs["d" + k] = relerr(got["grads"][k], ref["grads"][k])
     if adam:
-        # The first Adam step from zero moments moves every parameter by lr * g / (|g| + eps): a jump of
-        # 2 lr wherever a gradient that is zero in exact arithmetic (the key bias: softmax ignores a shift
-        # of all keys) comes out as rounding noise of either sign.  The moments are continuous in g and
-        # are compared with the oracle's directly; the updated parameter is compared with the oracle's
-        # Adam formula applied to the gradient the device produced.
         for k in workload.PARAM_NAMES:
             for i, nm in ((1, "m"), (2, "v")):
                 errs["adam_%s_%s" % (nm, k)] = relerr(got["adam"][k][i], ref["adam"][k][i])
-            p_want, _, _ = D.adam_step(ref["p0"][k], got["grads"][k], 0.0, 0.0, 1, **workload.ADAM)
-            errs["adam_p_%s" % k] = relerr(got["adam"][k][0], p_want)
-    bad = {k: v for k, v in errs.items() if not v <= tol}
+            errs["adam_p_%s" % k], safe = compare_adam_parameter(k, got["adam"][k][0], got["grads"][k], ref, dtype)
+            if k == "b_qkv":
+                # rows [N_e, 2 N_e) are the key bias: exact gradient 0, never in the sign-safe set
+                n = safe.shape[0] // 3
+                assert not safe[n:2 * n].any(), "key-bias entries must be compared through the device gradient"
+                assert safe[2 * n:].any()
+            else:
+                assert safe.any(), k
+    bad = {k: v for k, v in errs.items() if not v <= tolerance_of(k, dtype)}
     assert not bad, "max-norm relative errors above %.0e: %s" % (tol, bad)
     return errs
 
@@ -365,45 +405,46 @@ def test_block_C4_full_size_bf16_ragged(mods):
 
 
 @pytest.mark.parametrize("fused", [False, True], ids=["tiles", "fused"])
-def test_block_C5_one_batch_member_bf16(mods, fused):
-    """The 50B-class block (N_e = 8192, head size 128, tile 1024) on one of its four batch members: batch
-    members are independent except for the parameter-gradient sums, and the full batch would take the
-    fp64 oracle several minutes."""
+def test_block_C5_full_batch_bf16(mods, fused, capsys):
+    """The 50B-class block (N_e = 8192, head size 128, tile 1024) at its full batch of four, as the
+    benchmark launches it (`bench.py --config 5`): `Out`, `dX`, all twelve parameter gradients (the
+    weight-matrix gradients are the one place where batch members meet: sums over positions and batch),
+    the Adam moments and the updated parameters, each compared in full with the fp64 oracle.  The oracle
+    takes a few minutes on 20 TFLOP; it reports each layer it finishes, and one run serves both flows."""
+    import time
     capi, tiled = mods
-    cfg, inp, ref = full_size_case(5, True, N_b=1)
-    got = gpu_run(tiled, cfg, inp, workload.base_tiles(cfg), True, fused=fused)
-    errs = compare(got, ref, "bf16", True)
-    print("C5 (N_b=1%s) max-norm relative errors:" % (", fused attention" if fused else ""), {k: "%.2e" % v for k, v in errs.items()})
+    t0 = time.time()
 
+    def say(stage):
+        with capsys.disabled():
+            print("  [C5 oracle %4.0f s] %s" % (time.time() - t0, stage), flush=True)
 
-def test_block_C5_full_batch_sampled_member(mods):
-    """C5 at its full batch of four, as the benchmark launches it (`bench.py --config 5`): batch members
-    only meet in the parameter-gradient sums, so `Out` and `dX` of one sampled member are compared with the
-    oracle run on that member alone, and the gradient of the last bias with its closed form (the sum of
-    the upstream gradient over positions)."""
-    capi, tiled = mods
-    cfg = workload.CONFIGS[5]
-    inp = workload.generate(cfg)
-    member = 2
-    one = cfg.replace(N_b=1)
-    sub = dict(inp)
-    sub["X"] = np.ascontiguousarray(inp["X"][:, :, member:member + 1])
-    sub["dOut"] = np.ascontiguousarray(inp["dOut"][:, :, member:member + 1])
-    ref = oracle_run(one, sub, False)
+    cfg, inp, ref = full_size_case(5, True, progress=say)
+    assert cfg.N_b == 4
+    errs = {}
     with tiled.Context(n_streams=4) as ctx:
         blk = tiled.Gpt2Block(ctx, cfg.N_e, cfg.N_h, cfg.N_m, cfg.N_s, cfg.N_b, workload.base_tiles(cfg), dtype=cfg.dtype,
-                              eps=cfg.eps, gelu=cfg.gelu, adam=False)
+                              eps=cfg.eps, gelu=cfg.gelu, adam=True, fused_attention=fused)
         blk.set_params({k: inp[k] for k in workload.PARAM_NAMES})
         X, dOut = blk.activation(inp["X"]), blk.activation(inp["dOut"])
         Out, dX = blk.activation(), blk.activation()
         blk.forward(X, Out)
         blk.backward(dOut, dX)
-        got_out = Out.download()[:, :, member:member + 1]
-        got_dx = dX.download()[:, :, member:member + 1]
-        got_db2 = blk.grad("b_2").download()
+        errs["Out"], errs["dX"] = relerr(Out.download(), ref["Out"]), relerr(dX.download(), ref["dX"])
+        grads = {k: blk.grad(k).download() for k in workload.PARAM_NAMES}      # before the step: fp32, 3.2 GB
+        blk.adam(1, **workload.ADAM)
+        say("device forward, backward, Adam done (%s attention)" % ("fused" if fused else "tile"))
+        for k in workload.PARAM_NAMES:                                          # one parameter at a time: W_1 alone is 268 M entries
+            errs["d" + k] = relerr(grads[k], ref["grads"][k])
+            errs["adam_m_" + k] = relerr(blk.moment(k, "m").download(), ref["adam"][k][1])
+            errs["adam_v_" + k] = relerr(blk.moment(k, "v").download(), ref["adam"][k][2])
+            errs["adam_p_" + k], safe = compare_adam_parameter(k, blk.param(k).download(), grads[k], ref, "bf16")
+            if k == "b_qkv":
+                assert not safe[cfg.N_e:2 * cfg.N_e].any()
+            say("compared " + k)
         blk.close()
-    errs = {"Out": relerr(got_out, ref["Out"]), "dX": relerr(got_dx, ref["dX"]),
-            "db_2": relerr(got_db2, np.asarray(inp["dOut"], np.float64).sum(axis=(1, 2)))}
-    print("C5 (full batch, member %d) max-norm relative errors:" % member, {k: "%.2e" % v for k, v in errs.items()})
-    bad = {k: v for k, v in errs.items() if not v <= TOL["bf16"]}
+    with capsys.disabled():
+        print("C5 (full batch%s) max-norm relative errors:" % (", fused attention" if fused else ""),
+              {k: "%.2e" % v for k, v in errs.items()}, flush=True)
+    bad = {k: v for k, v in errs.items() if not v <= tolerance_of(k, "bf16")}
     assert not bad, bad
