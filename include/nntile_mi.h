@@ -216,6 +216,22 @@ NNT_API int64_t nnt_tile_bias_grad_scratch(int64_t m, int64_t n);
 NNT_API int32_t nnt_tile_bias_grad(void* stream, int32_t dtype, int64_t m, int64_t n, const void* dY,
                            float* db, int32_t accumulate, float* scratch);
 
+/* nnt_tile_bias_grad for callers that cannot allocate (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): same kernels
+ * and result, but the partial column sums go to a static device array inside
+ * the library (4 MiB per GPU, held until the process ends) instead of caller
+ * scratch.  Neither allocates nor frees anything.  Limit: nnt_tile_bias_grad_scratch(m, n)
+ * <= nnt_tile_bias_grad_static_max() (2^20 fp32 elements), else NNT_EINVAL and
+ * nothing is launched.  The array's device address is looked up once per GPU:
+ * by nnt_ctx_create on that GPU, else by the first call (make that first call
+ * outside a capture).  All calls on one GPU share the array: calls that may
+ * overlap (different streams without an ordering between them) race; calls on
+ * one stream, or ordered by events, are safe.  dY, db are device pointers the
+ * caller owns; the call is asynchronous on `stream`. */
+NNT_API int64_t nnt_tile_bias_grad_static_max(void);
+NNT_API int32_t nnt_tile_bias_grad_static(void* stream, int32_t dtype, int64_t m, int64_t n, const void* dY,
+                                  float* db, int32_t accumulate);
+
 /* y = gelu(x); dx = dy * gelu'(x)  (section 3, nonlinear activations). */
 NNT_API int32_t nnt_tile_gelu(void* stream, int32_t dtype, int32_t variant, int64_t n, const void* x, void* y);
 NNT_API int32_t nnt_tile_gelu_bwd(void* stream, int32_t dtype, int32_t variant, int64_t n,

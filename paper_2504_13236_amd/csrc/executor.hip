@@ -326,6 +326,7 @@ int32_t nnt_ctx_create(int32_t device, int32_t n_streams, void* const* caller_st
     if (!out || n_streams < 1 || n_streams > kMaxStreams) return NNT_EINVAL;
     *out = nullptr;
     if (hipSetDevice(device) != hipSuccess) return NNT_EHIP;
+    if (static_scratch_setup() != NNT_OK) return NNT_EHIP;      // this device's address of the static scratch array
     nnt_ctx* ctx = new (std::nothrow) nnt_ctx();
     if (!ctx) return NNT_ENOMEM;
     ctx->device = device;

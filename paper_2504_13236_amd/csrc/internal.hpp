@@ -177,6 +177,7 @@ void profile_mark(nnt_ctx* ctx, hipStream_t st, const char* label, double work, 
 int32_t submit(nnt_ctx* ctx, const std::vector<Access>& acc,
                const std::function<int32_t(hipStream_t)>& launch, int n_launches = 1);
 int32_t ensure_scratch(nnt_ctx* ctx, int64_t elems);
+int32_t static_scratch_setup();      // looks up the current device's address of the static scratch array (norm.hip)
 
 // Adam on several parameter tensors in one launch (elementwise.hip); the group owns small device tables.
 struct AdamGroup;

@@ -13,6 +13,7 @@
 #include "internal.hpp"
 
 #include <algorithm>
+#include <mutex>
 
 namespace nnt {
 namespace {
@@ -572,6 +573,41 @@ using namespace nnt;
 
 static inline bool cols_ok(int64_t m, int64_t n) { return m >= 1 && n >= 0 && m <= INT32_MAX && n <= (int64_t)INT32_MAX * 4; }
 
+// ------------------------------------------------------------------ bias gradient without any allocation
+// Partial column sums of nnt_tile_bias_grad_static live in this array: one copy per GPU, held until
+// the process ends.  In host code the array's name is only a stand-in for the symbol; the device
+// address is looked up once per device and kept.
+constexpr int64_t kStaticScratchElems = (int64_t)1 << 20;      // 4 MiB of fp32
+constexpr int kStaticMaxDevices = 64;
+static __device__ __align__(256) float static_scratch[kStaticScratchElems];
+
+namespace {
+std::mutex g_static_mu;
+float* g_static_ptr[kStaticMaxDevices] = {};
+
+// device address of this GPU's copy of `static_scratch` (current device), or nullptr with *rc set
+float* static_scratch_of_current_device(int32_t* rc) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kStaticMaxDevices) { *rc = NNT_EHIP; return nullptr; }
+    std::lock_guard<std::mutex> lock(g_static_mu);
+    if (!g_static_ptr[dev]) {
+        float* ptr = nullptr;
+        if (hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(static_scratch)) != hipSuccess || !ptr) { *rc = NNT_EHIP; return nullptr; }
+        g_static_ptr[dev] = ptr;
+    }
+    *rc = NNT_OK;
+    return g_static_ptr[dev];
+}
+}  // namespace
+
+namespace nnt {
+int32_t static_scratch_setup() {
+    int32_t rc;
+    (void)static_scratch_of_current_device(&rc);
+    return rc;
+}
+}  // namespace nnt
+
 extern "C" {
 
 int32_t nnt_tile_ln_stats(void* stream, int32_t dtype, int64_t m, int64_t n, const void* x, float* stats,
@@ -646,6 +682,22 @@ int32_t nnt_tile_bias_grad(void* stream, int32_t dtype, int64_t m, int64_t n, co
     if (!cols_ok(m, n)) return NNT_EINVAL;
     if (!dY || !db || !scratch) return NNT_EINVAL;
     return rowsum_single((hipStream_t)stream, dtype, 0, m, n, dY, nullptr, nullptr, db, nullptr, accumulate, scratch);
+}
+
+// ------------------------------------------------------------------ bias gradient without any allocation
+int64_t nnt_tile_bias_grad_static_max(void) { return kStaticScratchElems; }
+
+int32_t nnt_tile_bias_grad_static(void* stream, int32_t dtype, int64_t m, int64_t n, const void* dY, float* db,
+                                  int32_t accumulate) {
+    if (!DT_OK(dtype)) return NNT_EDTYPE;
+    if (!cols_ok(m, n)) return NNT_EINVAL;
+    if (!dY || !db) return NNT_EINVAL;
+    if (scratch_elems(m, n, 0) > kStaticScratchElems) return NNT_EINVAL;      // partial sums would not fit the static array
+    int32_t rc;
+    float* part = static_scratch_of_current_device(&rc);
+    if (!part) return rc;
+    // every partial row that stage 2 reads is written by stage 1 of this call: nothing to clear
+    return rowsum_single((hipStream_t)stream, dtype, 0, m, n, dY, nullptr, nullptr, db, nullptr, accumulate, part);
 }
 
 // ------------------------------------------------------------------ tensor form
