@@ -320,7 +320,9 @@ def measure(args, cfg, inp, attention, capi, tiled, torch, workload):
                 if len(parts) == 3 and parts[0] == dom.replace(" batched", ""):
                     roofline["traffic"] = float(parts[1]) + float(parts[2])      # HBM bytes per launch, read + written
                     roofline["traffic_detail"] = {"read_bytes_per_launch": float(parts[1]), "written_bytes_per_launch": float(parts[2]),
-                                                  "source": "profiles/" + os.path.basename(tpath)}
+                                                  "source": "profiles/" + os.path.basename(tpath),
+                                                  "note": "stored figure of the named rocprofv3 --pmc runs of this command "
+                                                          "(hardware counters cannot be read from inside the run); not measured now"}
         wg = [v for k, v in gemms.items()]
         tot_ms = sum(v["ms_per_step"] for v in wg)
         tot_fl = sum(v["TFLOP/s"] * v["ms_per_step"] for v in wg)
@@ -445,6 +447,8 @@ def main():
                          "tensor (the paper's flow, the default); fused: one kernel per direction that never stores it")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-next-rows", action="store_true", help="skip the extra pass with the fused attention kernels")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="default run only: skip the bf16 configurations C3 and C5 that are timed beside the headline")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="instead of the benchmark, copy MIB MiB of fp32 a few times with the library's cast kernel "
                          "(a plain copy kernel of known size, for scaling HBM counters)")
@@ -504,6 +508,22 @@ def main():
         f = measure(args, cfg, inp, "fused", capi, tiled, torch, workload)
         out["next_rows"] = {"fused_attention": {k: f[k] for k in ("value", "unit", "ms_per_step", "config", "summary")}}
         out["next_rows"]["fused_attention"]["kernels"] = {k: v for k, v in f["kernels"].items() if k.startswith("attention")}
+    if args.config == 2 and args.blocks == 1 and args.granularity == "op" and not args.graph and not args.no_other_configs:
+        # the bf16 configurations beside the headline (same run, same launch configuration, fewer steps for the
+        # large one): the metric's second figure, tile-GEMM share of the MFMA peak, for bf16
+        out["other_configs"] = {}
+        for number in (3, 5):
+            ocfg = workload.CONFIGS[number]
+            oargs = argparse.Namespace(**vars(args))
+            oargs.config = number
+            oargs.steps = args.steps if number == 3 else max(3, args.steps // 4)
+            oargs.warmup = min(args.warmup, 2)
+            oinp = workload.generate(ocfg)
+            o = measure(oargs, ocfg, oinp, "tiles", capi, tiled, torch, workload)
+            del oinp
+            out["other_configs"][ocfg.name] = {k: o[k] for k in ("value", "unit", "steps", "ms_per_step", "dtype", "config",
+                                                                 "tile_gemm_pct_mfma_peak", "elementwise_GBps", "roofline", "summary")}
+            torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
         # the whole workload takes the oracle a few seconds up to C4; C5 is sampled on one batch member
         sb = args.cpu_sample_batch or (cfg.N_b if args.config <= 4 else 1)

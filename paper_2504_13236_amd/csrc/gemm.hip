@@ -110,6 +110,7 @@ struct GemmPlan {
     std::vector<int64_t> task_wg0;             // first workgroup of each task (+ total at the end)
     std::vector<int64_t> task_nfast;           // leading workgroups of each task that qualify for the direct-load kernel
     int64_t op_nfast = 0;                      // the same for the whole-operation order
+    bool dl_ragged = false;                    // they need the direct-load kernel's variant for ragged macro-tiles and short k-steps
     std::vector<int64_t> task_ctile;           // C tile index per task
     std::vector<std::vector<int64_t>> task_atiles, task_btiles;   // operand tiles per task (dependencies)
     std::vector<int64_t> task_bias_tile;
@@ -157,7 +158,7 @@ void drop_plans_of(nnt_ctx* ctx, uint64_t id) {
 
 // The first `nfast` workgroups of the table qualify for the direct-load kernel of the type.
 static int32_t launch_any(hipStream_t st, int dtype_in, int dtype_out, int akf, int bkf, int cfg,
-                          const GemmArgs& g, int64_t nwg, int64_t nfast = 0) {
+                          const GemmArgs& g, int64_t nwg, int64_t nfast = 0, bool ragged = false) {
     const bool f32 = dtype_in == NNT_F32;
     auto general = [&](const GemmArgs& ga, int64_t n) {
         return f32 ? launch_gemm_f32(st, akf, bkf, cfg, ga, n) : launch_gemm_bf16(st, dtype_out == NNT_F32, akf, bkf, cfg, ga, n);
@@ -165,7 +166,7 @@ static int32_t launch_any(hipStream_t st, int dtype_in, int dtype_out, int akf, 
     // debugging aid: NNT_GEMM_NO_DL=1 sends every workgroup to the general kernels
     static const bool no_dl = getenv("NNT_GEMM_NO_DL") != nullptr;
     if (nfast <= 0 || no_dl) return general(g, nwg);
-    int32_t rc = f32 ? launch_gemm_f32_dl(st, akf, bkf, cfg, g, nfast) : launch_gemm_bf16_dl(st, dtype_out == NNT_F32, akf, bkf, cfg, g, nfast);
+    int32_t rc = f32 ? launch_gemm_f32_dl(st, akf, bkf, cfg, g, nfast) : launch_gemm_bf16_dl(st, dtype_out == NNT_F32, akf, bkf, cfg, ragged, g, nfast);
     if (rc != NNT_OK || nfast == nwg) return rc;
     GemmArgs rest = g;
     if (rest.wgs) rest.wgs += nfast;
@@ -246,14 +247,17 @@ static void xcd_interleave(std::vector<GemmWg>& wgs, int bm, int bn) {
 // the model only has to rank the candidates.
 constexpr int kSplitStep = 64;
 struct ShapeChoice { int cfg; int64_t n_split; int s; };
+// `ragged`: tile extents or chunk lengths that only the 256 x 128 bf16 direct-load kernel takes (the 256 x 256
+// shape would run on the general kernel, at about a third of the rate).
 static ShapeChoice choose_shape(bool bf16, bool out_f32, int akf, int bkf, const std::vector<int64_t>& tm,
-                                const std::vector<int64_t>& tn, const std::vector<int64_t>& ktot, bool may_split) {
+                                const std::vector<int64_t>& tn, const std::vector<int64_t>& ktot, bool may_split, bool ragged = false) {
     // rate of a compute unit with its full set of workgroups; start-up time of a workgroup; factor by
     // which a workgroup that is alone on its unit is slower than its share of that rate
     struct Cand { int cfg; double flops_per_s_cu; double t0; double solo; };
     static const Cand f32c[] = {{kCfgSquare, 0.56e12, 2.5e-6, 1.7}, {kCfgMid, 0.45e12, 2.0e-6, 1.3}};
     static const Cand bf16c[] = {{kCfgSquare, 4.4e12, 8.0e-6, 1.0}, {kCfgTall, 4.2e12, 3.0e-6, 1.6}, {kCfgMid, 1.6e12, 3.0e-6, 1.5}};
-    const Cand* cands = bf16 ? bf16c : f32c;
+    static const Cand bf16r[] = {{kCfgSquare, 1.5e12, 8.0e-6, 1.0}, {kCfgTall, 4.0e12, 3.0e-6, 1.6}, {kCfgMid, 1.6e12, 3.0e-6, 1.5}};
+    const Cand* cands = bf16 ? (ragged ? bf16r : bf16c) : f32c;
     const int ncand = bf16 ? 3 : 2;
     ShapeChoice best = {kCfgSquare, 0, 1};
     double best_t = 1e30;
@@ -348,15 +352,23 @@ extern "C" int32_t nnt_tile_gemm(void* stream, int32_t dtype_in, int32_t dtype_o
     g.beta = beta;
     int bm, bn;
     int cfg = pick_cfg(bf, m, n, ((m + 255) / 256) * ((n + 255) / 256) * batch, k);
-    if (batch == 1 && (cfg == kCfgSquare || cfg == kCfgMid || cfg == kCfgTall)) cfg = choose_shape(bf, dtype_out == NNT_F32, opA == NNT_OP_T, opB == NNT_OP_N, {m}, {n}, {k}, false).cfg;
+    const bool odd_shape = bf && (m % 256 != 0 || n % 256 != 0 || k % 64 != 0);
+    if (batch == 1 && (cfg == kCfgSquare || cfg == kCfgMid || cfg == kCfgTall))
+        cfg = choose_shape(bf, dtype_out == NNT_F32, opA == NNT_OP_T, opB == NNT_OP_N, {m}, {n}, {k}, false, odd_shape).cfg;
     gemm_cfg_tile(bf, cfg, &bm, &bn);
     g.grid_m = (int32_t)((m + bm - 1) / bm);
     g.grid_n = (int32_t)((n + bn - 1) / bn);
     const int64_t nwg = (int64_t)g.grid_m * g.grid_n * batch;
     if (nwg > INT32_MAX) return NNT_EINVAL;
-    const bool fast = (bf ? (cfg == kCfgSquare || cfg == kCfgTall) : (cfg == kCfgSquare || cfg == kCfgSkinny64n128 || cfg == kCfgMid)) && m % bm == 0 && n % bn == 0 && k > 0 &&
-                      k % ((bf && cfg == kCfgSquare) ? 64 : 32) == 0 && g.one_chunk.vec_ok == 3;
-    return launch_any((hipStream_t)stream, dtype_in, dtype_out, opA == NNT_OP_T, opB == NNT_OP_N, cfg, g, nwg, fast ? nwg : 0);
+    bool fast = (bf ? (cfg == kCfgSquare || cfg == kCfgTall) : (cfg == kCfgSquare || cfg == kCfgSkinny64n128 || cfg == kCfgMid)) && m % bm == 0 && n % bn == 0 && k > 0 &&
+                k % ((bf && cfg == kCfgSquare) ? 64 : 32) == 0 && g.one_chunk.vec_ok == 3;
+    bool ragged = false;
+    if (!fast && bf && cfg == kCfgTall && k > 0 && k % 8 == 0 && g.one_chunk.vec_ok == 3) {
+        // the variant for macro-tiles that end inside the tile and for a short last k-step
+        const bool akf = opA == NNT_OP_T, bkf = opB == NNT_OP_N;
+        fast = ragged = (akf || (m % bm) % 8 == 0) && (bkf || (n % bn) % 8 == 0);
+    }
+    return launch_any((hipStream_t)stream, dtype_in, dtype_out, opA == NNT_OP_T, opB == NNT_OP_N, cfg, g, nwg, fast ? nwg : 0, ragged);
 }
 
 // ---------------------------------------------------------------- tensor-level product
@@ -548,7 +560,10 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
         // products of whole matrices: macro-tile shape and k-slices by the cost model
         std::vector<int64_t> tm, tn;
         for (const TaskGeom& gq : geom) { tm.push_back(gq.m); tn.push_back(gq.n); }
-        const ShapeChoice sc = choose_shape(bf, C->dtype == NNT_F32, P->akf, P->bkf, tm, tn, ktot, true);
+        bool ragged = false;
+        for (const TaskGeom& gq : geom) ragged = ragged || gq.m % 256 != 0 || gq.n % 256 != 0;
+        for (const GemmChunk& c : P->chunks) ragged = ragged || c.k % 64 != 0;
+        const ShapeChoice sc = choose_shape(bf, C->dtype == NNT_F32, P->akf, P->bkf, tm, tn, ktot, true, bf && ragged);
         P->cfg = sc.cfg;
         S = sc.s;
         n_split = sc.n_split;
@@ -707,14 +722,29 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
     P->task_nfast.assign(P->task_ctile.size(), 0);
     if (bf ? (P->cfg == kCfgSquare || P->cfg == kCfgTall) : (P->cfg == kCfgSquare || P->cfg == kCfgSkinny64n128 || P->cfg == kCfgMid)) {
         const int kmul = (bf && P->cfg == kCfgSquare) ? 64 : 32;   // loads are started two k-steps at a time
-        std::vector<char> task_ok(P->tasks.size(), 1);
+        // the 256 x 128 bf16 kernel has a variant for chunk lengths that are multiples of 8 and macro-tiles that end
+        // inside their C tile (at a multiple of 8 rows of an operand whose row index is the contiguous one)
+        const bool rag_ok = bf && P->cfg == kCfgTall;
+        std::vector<char> task_ok(P->tasks.size(), 1), task_rag(P->tasks.size(), 0);
         for (size_t ti = 0; ti < P->tasks.size(); ti++)
-            for (int32_t q = P->tasks[ti].chunk0; q < P->tasks[ti].chunk0 + P->tasks[ti].nchunk; q++)
-                if (P->chunks[q].vec_ok != 3 || P->chunks[q].k <= 0 || P->chunks[q].k % kmul != 0) task_ok[ti] = 0;
-        auto qualifies = [&](const GemmWg& w) {
+            for (int32_t q = P->tasks[ti].chunk0; q < P->tasks[ti].chunk0 + P->tasks[ti].nchunk; q++) {
+                const GemmChunk& c = P->chunks[q];
+                if (c.vec_ok != 3 || c.k <= 0 || c.k % (rag_ok ? 8 : kmul) != 0) task_ok[ti] = 0;
+                else if (c.k % kmul != 0) task_rag[ti] = 1;
+            }
+        auto edge_ok = [&](const GemmWg& w) {
             const GemmTask& t = P->tasks[w.task];
-            return task_ok[w.task] && w.m0 + bm <= t.m && w.n0 + bn <= t.n;
+            const int mv = std::min(bm, t.m - w.m0), nv = std::min(bn, t.n - w.n0);
+            return rag_ok && (P->akf || mv % 8 == 0) && (P->bkf || nv % 8 == 0);
         };
+        auto whole = [&](const GemmWg& w) {
+            const GemmTask& t = P->tasks[w.task];
+            return w.m0 + bm <= t.m && w.n0 + bn <= t.n;
+        };
+        auto qualifies = [&](const GemmWg& w) { return task_ok[w.task] && (whole(w) || edge_ok(w)); };
+        for (const std::vector<GemmWg>* list : {&P->wgs, &P->wgs_op, &P->wgs_ts})
+            for (const GemmWg& w : *list)
+                if (qualifies(w) && (task_rag[w.task] || !whole(w))) P->dl_ragged = true;
         P->op_nfast = std::stable_partition(P->wgs_op.begin(), P->wgs_op.end(), qualifies) - P->wgs_op.begin();
         for (size_t ti = 0; ti + 1 < P->task_wg0.size(); ti++)
             P->task_nfast[ti] = std::stable_partition(P->wgs.begin() + P->task_wg0[ti], P->wgs.begin() + P->task_wg0[ti + 1], qualifies) -
@@ -730,7 +760,7 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
             std::ostringstream l;
             if (bf)
                 l << (P->cfg == kCfgTall ? "gemm_bf16_dl_tall_kernel<" : "gemm_bf16_dl_kernel<") << (C->dtype == NNT_F32 ? "float" : "unsigned short")
-                  << ", " << tf[P->akf] << ", " << tf[P->bkf] << ">";
+                  << ", " << tf[P->akf] << ", " << tf[P->bkf] << (P->cfg == kCfgTall ? (P->dl_ragged ? ", true>" : ", false>") : ">");
             else
                 l << "gemm_f32_dl_kernel<" << tf[P->akf] << ", " << tf[P->bkf] << (P->cfg == kCfgSquare ? ", 2, 2>" : ", 1, 2>");
             P->label = l.str() + P->label.substr(old_name.size());
@@ -790,7 +820,7 @@ extern "C" int32_t nnt_gemm(nnt_ctx* ctx, float alpha, int32_t opA, nnt_tensor* 
             acc.push_back(Access{&P->ws_dep, 1, kReadWrite});
             const double red_bytes = (double)P->n_split * P->slice_elems * 4.0 * (P->splits + 1);
             return submit(ctx, acc, [=](hipStream_t st) {
-                int32_t rc = launch_any(st, P->dtype_in, P->dtype_out, P->akf, P->bkf, P->cfg, g, nwg, P->op_nfast);
+                int32_t rc = launch_any(st, P->dtype_in, P->dtype_out, P->akf, P->bkf, P->cfg, g, nwg, P->op_nfast, P->dl_ragged);
                 if (rc != NNT_OK) return rc;
                 profile_mark(ctx, st, "splitk_reduce", red_bytes, true);
                 const dim3 grid((unsigned)P->red_blocks, (unsigned)P->n_split), block(256);
@@ -800,7 +830,7 @@ extern "C" int32_t nnt_gemm(nnt_ctx* ctx, float alpha, int32_t opA, nnt_tensor* 
             }, 2);
         }
         return submit(ctx, acc, [=](hipStream_t st) {
-            return launch_any(st, P->dtype_in, P->dtype_out, P->akf, P->bkf, P->cfg, g, nwg, P->op_nfast);
+            return launch_any(st, P->dtype_in, P->dtype_out, P->akf, P->bkf, P->cfg, g, nwg, P->op_nfast, P->dl_ragged);
         });
     }
     const size_t n_tile_tasks = P->task_ctile.size();
@@ -818,7 +848,7 @@ extern "C" int32_t nnt_gemm(nnt_ctx* ctx, float alpha, int32_t opA, nnt_tensor* 
             gt.wgs = P->d_wgs_ts + ts.wg0;
             const double red_bytes = (double)ts.nred * P->slice_elems_ts * 4.0 * (ts.nwg / ts.nred + 1);
             rc = submit(ctx, acc, [=](hipStream_t st) {
-                int32_t r = launch_any(st, P->dtype_in, P->dtype_out, P->akf, P->bkf, P->cfg, gt, ts.nwg, ts.nfast);
+                int32_t r = launch_any(st, P->dtype_in, P->dtype_out, P->akf, P->bkf, P->cfg, gt, ts.nwg, ts.nfast, P->dl_ragged);
                 if (r != NNT_OK) return r;
                 profile_mark(ctx, st, "splitk_reduce", red_bytes, true);
                 const dim3 grid((unsigned)P->red_blocks, (unsigned)ts.nred), block(256);
@@ -831,7 +861,7 @@ extern "C" int32_t nnt_gemm(nnt_ctx* ctx, float alpha, int32_t opA, nnt_tensor* 
             const int64_t nwg = P->task_wg0[ti + 1] - P->task_wg0[ti];
             const int64_t nfast = P->task_nfast[ti];
             rc = submit(ctx, acc, [=](hipStream_t st) {
-                return launch_any(st, P->dtype_in, P->dtype_out, P->akf, P->bkf, P->cfg, gt, nwg, nfast);
+                return launch_any(st, P->dtype_in, P->dtype_out, P->akf, P->bkf, P->cfg, gt, nwg, nfast, P->dl_ragged);
             });
         }
         if (rc != NNT_OK) return rc;

@@ -59,6 +59,31 @@ __device__ __forceinline__ uint32_t load_offset(int ld, int wave, int lane, int 
     return (uint32_t)(((8 * wave + kk) * ld + c * 8) * 2);
 }
 
+// The same for a block of which only `rows` rows (a multiple of 8 when the row index is the
+// contiguous one) and `kv` of the 32 k (a multiple of 8) exist: a lane whose 16 bytes lie outside
+// fetches an existing vector of the block instead (row clamped to the last one, k or row group set
+// back to the first), so that no address leaves the operand.  What lands in LDS for the missing
+// rows only reaches results that are never stored; what lands for the missing k is multiplied by
+// fragments that the kernel sets to zero.
+template <bool KF, int ROWS>
+__device__ __forceinline__ uint32_t load_offset_clamped(int ld, int wave, int lane, int j, int rows, int kv) {
+    constexpr int NI = ROWS / 64;
+    if (KF) {
+        const int r = lane >> 2;
+        int c = (lane & 3) ^ ((r >> 2) & 3);
+        if (c * 8 >= kv) c = 0;
+        const int row = min(16 * (NI * wave + j) + r, rows - 1);
+        return (uint32_t)((row * ld + c * 8) * 2);
+    }
+    constexpr int LPL = ROWS / 8, LPI = 64 / LPL;
+    const int kk = LPI * j + lane / LPL;
+    int c = (lane % LPL) ^ ((kk & 3) << 2);
+    if (c * 8 >= rows) c = 0;
+    int line = 8 * wave + kk;
+    if (line >= kv) line = 0;
+    return (uint32_t)((line * ld + c * 8) * 2);
+}
+
 // Per-lane part of the fragment address of an operand region of ROWS rows.
 template <bool KF, int ROWS>
 __device__ __forceinline__ uint32_t frag_lane_offset(int lane) {
@@ -78,11 +103,26 @@ struct Frag {
     bf16x8 v;
     __device__ __forceinline__ void tie() { asm volatile("" : "+v"(v)); }
     __device__ __forceinline__ bf16x8 value() const { return v; }
+    // keeps the fragment (mask = ~0) or sets it to zero (mask = 0); only after its read has been waited for
+    __device__ __forceinline__ void mask(uint32_t m) {
+        typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+        u32x4 x = __builtin_bit_cast(u32x4, v);
+        x &= m;
+        v = __builtin_bit_cast(bf16x8, x);
+    }
 };
 template <>
 struct Frag<false> {
     s16x4 lo, hi;
     __device__ __forceinline__ void tie() { asm volatile("" : "+v"(lo), "+v"(hi)); }
+    __device__ __forceinline__ void mask(uint32_t m) {
+        typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+        u32x2 a = __builtin_bit_cast(u32x2, lo), b = __builtin_bit_cast(u32x2, hi);
+        a &= m;
+        b &= m;
+        lo = __builtin_bit_cast(s16x4, a);
+        hi = __builtin_bit_cast(s16x4, b);
+    }
     __device__ __forceinline__ bf16x8 value() const {
         typedef short s16x8 __attribute__((ext_vector_type(8)));
         const s16x8 x = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
@@ -134,7 +174,11 @@ struct DlShape {
     static constexpr int kLdsBytes = kStages * kStageBytes;
 };
 
-template <typename TO, bool AKF, bool BKF, int WNB>
+// RAG: the macro-tile may end inside its C tile (rows of the operands beyond the tile's edge are
+// not loaded, see load_offset_clamped; the epilogue stores nothing for them) and chunk lengths are
+// multiples of 8 instead of 32 (the last k-step of such a chunk is short: the fragments of the A
+// operand that stand for k beyond it are set to zero before the matrix instructions).
+template <typename TO, bool AKF, bool BKF, int WNB, bool RAG = false>
 __device__ __forceinline__ void dl_body(const GemmArgs& g, char* lds) {
     constexpr int WMB = 4, BM = 256, BN = 64 * WNB;
     constexpr int kStages = DlShape<WNB>::kStages;
@@ -145,6 +189,7 @@ __device__ __forceinline__ void dl_body(const GemmArgs& g, char* lds) {
     // must be multiples of 64 long.
     constexpr bool kPaired = WNB == 4;
     static_assert(!kPaired || kStages == 5, "the paired schedule needs five stages");
+    static_assert(!(kPaired && RAG), "short k-steps need the schedule that starts its loads one step at a time");
     static_assert(4 * 32 * (32 * WMB + 4) * 4 <= kStages * kStageBytes, "result staging must fit the pipeline's LDS");
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -182,9 +227,9 @@ __device__ __forceinline__ void dl_body(const GemmArgs& g, char* lds) {
     if (table) {
         chunk_i = __builtin_amdgcn_readfirstlane(task.chunk0);
         const int nch = __builtin_amdgcn_readfirstlane(task.nchunk);
-        for (int c = 0; c < nch; c++) T += sload_chunk(g.chunks + chunk_i + c).k / kBK;
+        for (int c = 0; c < nch; c++) T += (sload_chunk(g.chunks + chunk_i + c).k + (RAG ? kBK - 1 : 0)) / kBK;
     } else if (task.nchunk > 0) {
-        T = g.one_chunk.k / kBK;
+        T = (g.one_chunk.k + (RAG ? kBK - 1 : 0)) / kBK;
     }
     T = __builtin_amdgcn_readfirstlane(T);
 
@@ -201,6 +246,8 @@ __device__ __forceinline__ void dl_body(const GemmArgs& g, char* lds) {
         const char* baseB = nullptr;
         int64_t advA = 0, advB = 0;
         uint32_t voffA[NIA], voffB[NIB];
+        uint32_t toffA[RAG ? NIA : 1], toffB[RAG ? NIB : 1];      // offsets for the short last step of the chunk
+        const int rowsA = RAG ? min(BM, task.m - m0) : BM, rowsB = RAG ? min(BN, task.n - n0) : BN;
         auto set_chunk = [&](const ChunkS& ch) {
             chk = ch.k;
             const int lda = (int)ch.lda, ldb = (int)ch.ldb;
@@ -210,10 +257,24 @@ __device__ __forceinline__ void dl_body(const GemmArgs& g, char* lds) {
             baseB = reinterpret_cast<const char*>(BKF ? Bb + (int64_t)n0 * ldb : Bb + n0);
             advA = AKF ? kBK * 2 : (int64_t)kBK * lda * 2;
             advB = BKF ? kBK * 2 : (int64_t)kBK * ldb * 2;
+            if constexpr (RAG) {
+                const int kt = chk % kBK ? chk % kBK : kBK;
 #pragma unroll
-            for (int j = 0; j < NIA; j++) voffA[j] = load_offset<AKF, BM>(lda, wave, lane, j);
+                for (int j = 0; j < NIA; j++) {
+                    voffA[j] = load_offset_clamped<AKF, BM>(lda, wave, lane, j, rowsA, kBK);
+                    toffA[j] = load_offset_clamped<AKF, BM>(lda, wave, lane, j, rowsA, kt);
+                }
 #pragma unroll
-            for (int j = 0; j < NIB; j++) voffB[j] = load_offset<BKF, BN>(ldb, wave, lane, j);
+                for (int j = 0; j < NIB; j++) {
+                    voffB[j] = load_offset_clamped<BKF, BN>(ldb, wave, lane, j, rowsB, kBK);
+                    toffB[j] = load_offset_clamped<BKF, BN>(ldb, wave, lane, j, rowsB, kt);
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < NIA; j++) voffA[j] = load_offset<AKF, BM>(lda, wave, lane, j);
+#pragma unroll
+                for (int j = 0; j < NIB; j++) voffB[j] = load_offset<BKF, BN>(ldb, wave, lane, j);
+            }
         };
         if (table) {
             set_chunk(sload_chunk(g.chunks + chunk_i));
@@ -228,11 +289,14 @@ __device__ __forceinline__ void dl_body(const GemmArgs& g, char* lds) {
         // load instruction i (first those of A, then those of B) of the k-step at the current position
         auto load_one = [&](int stage, int i) {
             char* sa = lds + stage * kStageBytes;
+            const bool short_step = RAG && chk - k0 < kBK;       // uniform: the step at the current position is the chunk's short last one
             if (i < NIA) {
-                __builtin_amdgcn_global_load_lds((glb_void_ptr)(baseA + voffA[i]), (lds_void_ptr)(sa + (wave * NIA + i) * 1024), 16, 0, 0);
+                const uint32_t off = short_step ? toffA[RAG ? i : 0] : voffA[i];
+                __builtin_amdgcn_global_load_lds((glb_void_ptr)(baseA + off), (lds_void_ptr)(sa + (wave * NIA + i) * 1024), 16, 0, 0);
             } else {
                 const int j = i - NIA;
-                __builtin_amdgcn_global_load_lds((glb_void_ptr)(baseB + voffB[j]), (lds_void_ptr)(sa + kOpABytes + (wave * NIB + j) * 1024), 16, 0, 0);
+                const uint32_t off = short_step ? toffB[RAG ? j : 0] : voffB[j];
+                __builtin_amdgcn_global_load_lds((glb_void_ptr)(baseB + off), (lds_void_ptr)(sa + kOpABytes + (wave * NIB + j) * 1024), 16, 0, 0);
             }
         };
         auto advance = [&]() {
@@ -328,9 +392,30 @@ __device__ __forceinline__ void dl_body(const GemmArgs& g, char* lds) {
         // substep F_KS of the stage at `f_addr` are fetched into the other set and NL load
         // instructions are started through `load(i)`.  The pieces are dealt out evenly over the
         // matrix instructions and fenced so that they stay there.
-        auto substep = [&](auto NL, auto F_KS, int buf, uint32_t f_addr, auto&& load) {
+        // RAG: k that the step under the matrix instructions really has (32 except in the short last
+        // step of a chunk), and a cursor over the chunk lengths on the computing side
+        int kv_now = kBK, c_rem = 0, c_chunk = chunk_i;
+        if constexpr (RAG) {
+            c_rem = table ? sload_chunk(g.chunks + c_chunk).k : g.one_chunk.k;
+            kv_now = min(kBK, c_rem);
+        }
+        auto next_step_k = [&]() {
+            c_rem -= kv_now;
+            if (c_rem <= 0 && ++c_chunk < chunk_end) c_rem = sload_chunk(g.chunks + c_chunk).k;
+            kv_now = c_rem > 0 ? min(kBK, c_rem) : kBK;       // (past the last step: nothing is multiplied any more)
+        };
+        const int lane_k8 = (lane >> 5) * 8;                  // first k, within a substep of 16, of the lane's fragments
+        auto substep = [&](auto NL, auto F_KS, int buf, uint32_t f_addr, auto&& load, int ks_now = 0) {
             constexpr int kItems = kFrags + decltype(NL)::value;
             wait_frags(buf);
+            if constexpr (RAG) {
+                if (kv_now < kBK) {
+                    // short step: the A fragments that stand for k >= kv_now become zero
+                    const uint32_t keep = 16 * ks_now + lane_k8 < kv_now ? 0xffffffffu : 0u;
+#pragma unroll
+                    for (int i = 0; i < WMB; i++) qf[buf][i].mask(keep);
+                }
+            }
             __builtin_amdgcn_sched_barrier(0);
             static_for<kMfma>([&](auto Q) {
                 constexpr int q = decltype(Q)::value;
@@ -384,14 +469,15 @@ __device__ __forceinline__ void dl_body(const GemmArgs& g, char* lds) {
             int stage = 0, next_stage = kStages - 1;
             for (int t = 0; t < T; t++) {
                 const int stage1 = next_of(stage);
-                substep(None{}, KS1{}, 0, stage_addr(stage), no_load);
+                substep(None{}, KS1{}, 0, stage_addr(stage), no_load, 0);
                 // step t + 1 complete for everybody (loads of steps t + 2 .. t + kStages - 2 may
                 // remain), and everybody done with the stage of step t - 1, which the next loads overwrite
                 __builtin_amdgcn_s_waitcnt(wait_vm((kStages - 3) * kLoads));
                 asm volatile("s_barrier" ::: "memory");
                 // (after the last step the fragment reads hit a stage that holds no new data: in
                 // bounds and unused)
-                substep(std::integral_constant<int, kLoads>{}, KS0{}, 1, stage_addr(stage1), [&](int i) { load_one(next_stage, i); });
+                substep(std::integral_constant<int, kLoads>{}, KS0{}, 1, stage_addr(stage1), [&](int i) { load_one(next_stage, i); }, 1);
+                if constexpr (RAG) next_step_k();
                 advance();
                 next_stage = next_of(next_stage);
                 stage = stage1;
@@ -420,39 +506,43 @@ __global__ void __launch_bounds__(256) gemm_bf16_dl_kernel(const GemmArgs g) {
 }
 
 // two workgroups per compute unit: at most 256 registers per lane
-template <typename TO, bool AKF, bool BKF>
+template <typename TO, bool AKF, bool BKF, bool RAG>
 __global__ void __launch_bounds__(256, 2) gemm_bf16_dl_tall_kernel(const GemmArgs g) {
     __shared__ __attribute__((aligned(16))) char lds[DlShape<2>::kLdsBytes];
-    dl_body<TO, AKF, BKF, 2>(g, lds);
+    dl_body<TO, AKF, BKF, 2, RAG>(g, lds);
 }
 
 using KernelFn = void (*)(const GemmArgs);
 
+template <typename TO, bool RAG>
+KernelFn tall_kernel_of(int akf, int bkf) {
+    if (akf) return bkf ? gemm_bf16_dl_tall_kernel<TO, true, true, RAG> : gemm_bf16_dl_tall_kernel<TO, true, false, RAG>;
+    return bkf ? gemm_bf16_dl_tall_kernel<TO, false, true, RAG> : gemm_bf16_dl_tall_kernel<TO, false, false, RAG>;
+}
+
 template <typename TO>
-KernelFn kernel_of(int akf, int bkf, bool tall) {
-    if (tall) {
-        if (akf) return bkf ? gemm_bf16_dl_tall_kernel<TO, true, true> : gemm_bf16_dl_tall_kernel<TO, true, false>;
-        return bkf ? gemm_bf16_dl_tall_kernel<TO, false, true> : gemm_bf16_dl_tall_kernel<TO, false, false>;
-    }
+KernelFn kernel_of(int akf, int bkf, bool tall, bool ragged) {
+    if (tall) return ragged ? tall_kernel_of<TO, true>(akf, bkf) : tall_kernel_of<TO, false>(akf, bkf);
     if (akf) return bkf ? gemm_bf16_dl_kernel<TO, true, true> : gemm_bf16_dl_kernel<TO, true, false>;
     return bkf ? gemm_bf16_dl_kernel<TO, false, true> : gemm_bf16_dl_kernel<TO, false, false>;
 }
 
-KernelFn kernel_of(int out_is_f32, int akf, int bkf, int cfg) {
-    return out_is_f32 ? kernel_of<float>(akf, bkf, cfg == kCfgTall) : kernel_of<uint16_t>(akf, bkf, cfg == kCfgTall);
+KernelFn kernel_of(int out_is_f32, int akf, int bkf, int cfg, bool ragged) {
+    return out_is_f32 ? kernel_of<float>(akf, bkf, cfg == kCfgTall, ragged) : kernel_of<uint16_t>(akf, bkf, cfg == kCfgTall, ragged);
 }
 
 }  // namespace
 
-int32_t launch_gemm_bf16_dl(hipStream_t st, int out_is_f32, int akf, int bkf, int cfg, const GemmArgs& g, int64_t nwg) {
+int32_t launch_gemm_bf16_dl(hipStream_t st, int out_is_f32, int akf, int bkf, int cfg, bool ragged, const GemmArgs& g, int64_t nwg) {
     if (nwg <= 0) return NNT_OK;
-    hipLaunchKernelGGL(kernel_of(out_is_f32, akf, bkf, cfg), dim3((unsigned)nwg), dim3(256), 0, st, g);
+    if (ragged && cfg != kCfgTall) return NNT_EINVAL;
+    hipLaunchKernelGGL(kernel_of(out_is_f32, akf, bkf, cfg, ragged), dim3((unsigned)nwg), dim3(256), 0, st, g);
     return hipGetLastError() == hipSuccess ? NNT_OK : NNT_EHIP;
 }
 
 int gemm_bf16_dl_occupancy(int out_is_f32, int akf, int bkf, int cfg) {
     int n = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel_of(out_is_f32, akf, bkf, cfg), 256, 0) != hipSuccess || n < 1) n = 1;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel_of(out_is_f32, akf, bkf, cfg, false), 256, 0) != hipSuccess || n < 1) n = 1;
     return n;
 }
 

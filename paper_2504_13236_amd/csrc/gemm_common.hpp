@@ -70,8 +70,9 @@ inline void gemm_cfg_tile(int dtype_is_bf16, int cfg, int* bm, int* bn) {
 int32_t launch_gemm_f32(hipStream_t st, int akf, int bkf, int cfg, const GemmArgs& g, int64_t nwg);
 int32_t launch_gemm_bf16(hipStream_t st, int out_is_f32, int akf, int bkf, int cfg, const GemmArgs& g, int64_t nwg);
 // 256 x 256 (kCfgSquare) or 256 x 128 (kCfgTall) macro-tiles that lie wholly inside their C tile, with 16-byte aligned operands and
-// chunk lengths that are multiples of 64 (kCfgSquare) or 32 (kCfgTall); loads go straight to LDS
-int32_t launch_gemm_bf16_dl(hipStream_t st, int out_is_f32, int akf, int bkf, int cfg, const GemmArgs& g, int64_t nwg);
+// chunk lengths that are multiples of 64 (kCfgSquare) or 32 (kCfgTall); loads go straight to LDS.  `ragged` (kCfgTall only):
+// macro-tiles may end inside their C tile (row-contiguous operands: at a multiple of 8 rows) and chunk lengths are multiples of 8
+int32_t launch_gemm_bf16_dl(hipStream_t st, int out_is_f32, int akf, int bkf, int cfg, bool ragged, const GemmArgs& g, int64_t nwg);
 int gemm_bf16_dl_occupancy(int out_is_f32, int akf, int bkf, int cfg);
 // fp32: 128 x 128 (kCfgSquare) or 64 x 128 (kCfgMid, kCfgSkinny64n128) macro-tiles that lie wholly inside their
 // C tile, 16-byte aligned operands, chunk lengths that are multiples of 32

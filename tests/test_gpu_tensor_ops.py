@@ -117,6 +117,42 @@ def test_attention_products_with_causal_structure(mods, gran, dtype, tiles):
         check(tdK.download(), D.contract(sc, "N", Q, "T", dA, 0.0, None, 1, 2), dtype, "dK = Q dA^T / sqrt(h)")
 
 
+@pytest.mark.parametrize("gran", GRANS)
+def test_gemm_bf16_tiles_of_400_run_on_the_direct_load_kernel(mods, gran):
+    """Linear-layer products on tiles of 400 (GPT-2-XL's tiling: 400 = 256 + 144 rows per macro-tile column,
+    12 k-steps of 32 and a short one of 16, sequence tiles 400 + 224): forward with bias, input gradient,
+    weight gradient over two contracted axes, against the oracle; in whole-operation launches the profile
+    must name the direct-load kernel's ragged variant."""
+    capi, tiled = mods
+    r = rng(40)
+    N_d, N_e, N_s, N_b = 1200, 800, 624, 4
+    W = quant(r.standard_normal((N_d, N_e)) * 0.05, "bf16")
+    X = quant(r.standard_normal((N_e, N_s, N_b)), "bf16")
+    b = r.standard_normal(N_d).astype(np.float32)
+    dY = quant(r.standard_normal((N_d, N_s, N_b)), "bf16")
+    with tiled.Context(n_streams=2, granularity=gran) as ctx:
+        tW, tX = T(tiled, ctx, W, (400, 400), "bf16"), T(tiled, ctx, X, (400, 400, N_b), "bf16")
+        tb = T(tiled, ctx, b, (400,), "f32")
+        tY = tiled.TiledTensor(ctx, "bf16", (N_d, N_s, N_b), (400, 400, N_b))
+        tdY = T(tiled, ctx, dY, (400, 400, N_b), "bf16")
+        tdX = tiled.TiledTensor(ctx, "bf16", X.shape, (400, 400, N_b))
+        tdW = tiled.TiledTensor(ctx, "f32", W.shape, (400, 400))
+        ctx.profile(True)
+        capi.nnt_gemm(ctx.h, 1.0, 0, tW.h, 0, tX.h, 0.0, tY.h, 1, 0, tb.h)
+        capi.nnt_gemm(ctx.h, 1.0, 1, tW.h, 0, tdY.h, 0.0, tdX.h, 1, 0, None)
+        capi.nnt_gemm(ctx.h, 1.0, 0, tdY.h, 1, tX.h, 0.0, tdW.h, 2, 0, None)
+        ctx.wait()
+        labels = sorted(ctx.profile_read())
+        ctx.profile(False)
+        check(tY.download(), D.linear_fwd(W, X, b), "bf16", "linear fwd")
+        dXr, dWr, _ = D.linear_bwd(W, X, dY)
+        check(tdX.download(), dXr, "bf16", "linear dX")
+        check(tdW.download(), dWr, "f32", "linear dW")
+        if gran == 0:
+            products = [l for l in labels if l.startswith("gemm_")]
+            assert products and all(l.startswith("gemm_bf16_dl_tall_kernel<") and l.split(">")[0].endswith("true") for l in products), labels
+
+
 def test_gemm_direct_load_randomized_sweep_over_tile_tables(mods):
     """Seeded random draws of tensor-level products whose tiles are whole macro-tiles and whose contracted
     tiles are multiples of 32 long (several chunks per C tile, including chunks of 32 and 64): the

@@ -150,6 +150,26 @@ def test_gemm_direct_load_randomized_sweep(capi):
                                 (draw, din, dout, opA, opB, m, n, k, batch, alpha, beta, pad), e)
 
 
+def test_gemm_bf16_ragged_shapes_randomized_sweep(capi):
+    """bf16 products whose extents are multiples of 8 but of nothing larger (macro-tiles that end inside the
+    matrix, a short last k-step, k shorter than one step): the shapes of the direct-load kernel's ragged
+    variant and its neighbours, every orientation, against the oracle.  Stops at the first failure."""
+    r = np.random.default_rng(4004)
+    for draw in range(72):
+        dout = ("bf16", "f32")[draw % 2]
+        m = 8 * int(r.integers(20, 90))
+        n = 8 * int(r.integers(16, 120))
+        k = 8 * int(r.choice([1, 2, 3, 4, 5, 7, 13, 28, 50, 51, 64, 70]))
+        opA, opB = "NT"[int(r.integers(2))], "NT"[int(r.integers(2))]
+        batch = 1 if draw % 3 else 2
+        alpha, beta = ((1.0, 0.0), (0.7, -1.3))[int(r.integers(2))]
+        pad = 8 * int(r.integers(0, 3))
+        got, ref = run_gemm(capi, "bf16", dout, opA, opB, m, n, k, batch, alpha, beta, pad, seed=5000 + draw)
+        e = relerr(got, ref)
+        assert e <= TOL[dout], ("draw %d: bf16->%s %s%s %dx%dx%d batch %d alpha %g beta %g pad %d" %
+                                (draw, dout, opA, opB, m, n, k, batch, alpha, beta, pad), e)
+
+
 def test_gemm_degenerate(capi):
     # k = 0: C <- beta * C; beta = 0 must not propagate NaNs already in C
     C0 = rng(1).standard_normal((9, 5)).astype(np.float32)
