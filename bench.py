@@ -206,6 +206,54 @@ def tile_kernels(cfg, capi, torch):
     return out
 
 
+def gemm_ceiling(capi, torch):
+    """What bounds the product kernels on the box at hand: the matrix-core issue rate on register
+    operands (constants / values that change from instruction to instruction), and one large product
+    per type through nnt_tile_gemm on operands of different content (the clock drops with the power the
+    operands' bit toggling draws, so the same kernel runs at different rates on zeros and on noise)."""
+    import ctypes as C
+    st = torch.cuda.current_stream().cuda_stream
+    sink = torch.zeros(1, device="cuda")
+
+    def timed(call, iters=5):
+        call()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            call()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters
+
+    out = {"mfma_only": [], "products_8192_cubed": []}
+    for dt, name in ((capi.NNT_F32, "f32"), (capi.NNT_BF16, "bf16")):
+        for rnd in (0, 1):
+            for occ in (1, 2):
+                fl = C.c_double()
+                wgs, iters = 256 * occ, 1 << 15
+                ms = timed(lambda: capi.nnt_probe_mfma_rate(st, dt, rnd, iters, wgs, sink.data_ptr(), C.byref(fl)))
+                out["mfma_only"].append({"dtype": name, "operands": "random" if rnd else "constant", "waves_per_simd": occ,
+                                         "TFLOP/s": fl.value / ms / 1e9, "frac_mfma_peak": fl.value / ms / 1e9 / PEAK_TFLOPS[name]})
+    m = n = k = 8192
+    content = {"zeros": lambda t: t.zero_(), "ones": lambda t: t.fill_(1.0), "normal(0,1)": lambda t: t.normal_(),
+               "normal(0,0.02)": lambda t: t.normal_(0.0, 0.02)}
+    for dt, name, tdt in ((capi.NNT_F32, "f32", torch.float32), (capi.NNT_BF16, "bf16", torch.bfloat16)):
+        A = torch.empty(m * k, device="cuda", dtype=tdt)
+        B = torch.empty(k * n, device="cuda", dtype=tdt)
+        Cm = torch.empty(m * n, device="cuda", dtype=tdt)
+        for cname, fill in content.items():
+            fill(A)
+            fill(B)
+            for opA, opB, on in ((1, 0, "TN"), (0, 0, "NN")):
+                ms = timed(lambda: capi.nnt_tile_gemm(st, dt, dt, opA, opB, m, n, k, 1, 1.0, A.data_ptr(), k if opA else m, m * k,
+                                                      B.data_ptr(), k, k * n, 0.0, Cm.data_ptr(), m, m * n))
+                tf = 2.0 * m * n * k / ms / 1e9
+                out["products_8192_cubed"].append({"dtype": name, "op": on, "operands": cname, "TFLOP/s": tf,
+                                                   "frac_mfma_peak": tf / PEAK_TFLOPS[name]})
+    return out
+
+
 def measure(args, cfg, inp, attention, capi, tiled, torch, workload):
     """Times K steps of the block (forward + backward [+ Adam]) with the given attention flow and
     returns the bench record."""
@@ -457,6 +505,9 @@ def main():
                     help="instead of the block benchmark, time single calls of the tile kernels at the config's shapes: "
                          "products against the MFMA peak, memory-bound kernels against HBM, warm (one buffer set) and "
                          "cold (rotating over > 512 MB of buffer sets, more than the 256 MB Infinity Cache)")
+    ap.add_argument("--gemm-ceiling", action="store_true",
+                    help="instead of the block benchmark, measure the matrix-core issue rate on register operands (constant / "
+                         "random) and one 8192^3 product per type on operands of different content")
     ap.add_argument("--model", action="store_true",
                     help="instead of the block benchmark, time whole training iterations of a language model made of "
                          "--blocks blocks (default 12) of the config: embeddings, blocks, final layer norm, tied head, loss, "
@@ -491,6 +542,9 @@ def main():
         print(json.dumps({"copy_calibration": {"bytes_read": 4 * n, "bytes_written": 4 * n, "launches": 8, "ms": ms,
                                                "GB/s": 8.0 * n / ms / 1e6,
                                                "kernel": "ew_kernel<CastF<float, float>>"}}))
+        return
+    if args.gemm_ceiling:
+        print(json.dumps({"gemm_ceiling": gemm_ceiling(capi, torch)}))
         return
     if args.tile_kernels:
         res = tile_kernels(workload.CONFIGS[args.config], capi, torch)

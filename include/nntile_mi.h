@@ -517,6 +517,17 @@ NNT_API int32_t nnt_gpt2_stack_adam(nnt_gpt2_stack* st, int32_t step, const nnt_
 
 NNT_API const char* nnt_version(void);
 
+/* Measurement aid (no part of the method): launches `workgroups` workgroups of four
+ * wavefronts that each issue `iters` x 8 matrix instructions back to back on operands held in
+ * registers -- fp32 (32x32x2) or bf16 (32x32x16, fp32 accumulate) -- with no memory traffic.
+ * random_operands != 0: operand registers hold pseudo-random values that differ from
+ * instruction to instruction (as in a real product); 0: constants.  Timed by the caller (events
+ * on `stream`), it gives the matrix-core rate that bounds the product kernels on the chip at
+ * hand.  sink: device float the kernel practically never writes; flops_out (host, nullable):
+ * flops issued by the launch. */
+NNT_API int32_t nnt_probe_mfma_rate(void* stream, int32_t dtype, int32_t random_operands, int32_t iters,
+                            int32_t workgroups, float* sink, double* flops_out);
+
 #ifdef __cplusplus
 }
 #endif

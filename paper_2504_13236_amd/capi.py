@@ -114,6 +114,7 @@ PROTOTYPES = {
     "nnt_tile_bias_add": (_i32, [_p, _i32, _i64, _i64, _p, _p]),
     "nnt_tile_bias_grad_scratch": (_i64, [_i64, _i64]),
     "nnt_tile_bias_grad": (_i32, [_p, _i32, _i64, _i64, _p, _p, _i32, _p]),
+    "nnt_probe_mfma_rate": (_i32, [_p, _i32, _i32, _i32, _i32, _p, _p]),
     "nnt_tile_bias_grad_static_max": (_i64, []),
     "nnt_tile_bias_grad_static": (_i32, [_p, _i32, _i64, _i64, _p, _p, _i32]),
     "nnt_tile_gelu": (_i32, [_p, _i32, _i32, _i64, _p, _p]),

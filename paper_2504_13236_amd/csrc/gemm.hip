@@ -355,6 +355,9 @@ extern "C" int32_t nnt_tile_gemm(void* stream, int32_t dtype_in, int32_t dtype_o
     const bool odd_shape = bf && (m % 256 != 0 || n % 256 != 0 || k % 64 != 0);
     if (batch == 1 && (cfg == kCfgSquare || cfg == kCfgMid || cfg == kCfgTall))
         cfg = choose_shape(bf, dtype_out == NNT_F32, opA == NNT_OP_T, opB == NNT_OP_N, {m}, {n}, {k}, false, odd_shape).cfg;
+    // debugging aid: NNT_TILE_GEMM_CFG=<number of a macro-tile configuration> overrides the choice for this entry point
+    static const char* const force = getenv("NNT_TILE_GEMM_CFG");
+    if (force && atoi(force) >= kCfgSquare && atoi(force) <= kCfgTall) cfg = atoi(force);
     gemm_cfg_tile(bf, cfg, &bm, &bn);
     g.grid_m = (int32_t)((m + bm - 1) / bm);
     g.grid_n = (int32_t)((n + bn - 1) / bn);

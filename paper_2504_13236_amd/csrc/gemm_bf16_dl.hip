@@ -185,6 +185,10 @@ __device__ __forceinline__ void dl_body(const GemmArgs& g, char* lds) {
     constexpr int kOpABytes = BM * kBK * 2, kStageBytes = DlShape<WNB>::kStageBytes;
     constexpr int NIA = BM / 64, NIB = BN / 64, kLoads = NIA + NIB;     // load instructions per wave and step
     constexpr int kFrags = WNB + WMB, kMfma = WNB * WMB;
+#ifndef NNT_FRAG_SPAN_NUM
+#define NNT_FRAG_SPAN_NUM 2
+#endif
+    constexpr int kFragSpan = kMfma * NNT_FRAG_SPAN_NUM / 4;
     // The 256 x 256 shape starts its loads two k-steps at a time (see the loop below); its chunks
     // must be multiples of 64 long.
     constexpr bool kPaired = WNB == 4;
@@ -378,7 +382,9 @@ __device__ __forceinline__ void dl_body(const GemmArgs& g, char* lds) {
         };
         // all fragment reads issued so far have landed; the matrix instructions on set `buf` stay behind this
         auto wait_frags = [&](int buf) {
+#ifndef NNT_PROBE_NO_LGKM
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#endif
 #pragma unroll
             for (int i = 0; i < WNB; i++) pf[buf][i].tie();
 #pragma unroll
@@ -422,7 +428,10 @@ __device__ __forceinline__ void dl_body(const GemmArgs& g, char* lds) {
                 mfma_one(buf, q);
                 static_for<kItems>([&](auto I) {
                     constexpr int i = decltype(I)::value;
-                    if constexpr (i * kMfma / kItems == q) {
+                    // fragment reads go under the first kFragSpan matrix instructions (their latency
+                    // has the rest of the substep to pass), load instructions are spread over all of them
+                    constexpr int slot = i < kFrags ? i * kFragSpan / kFrags : (i - kFrags) * kMfma / (kItems > kFrags ? kItems - kFrags : 1);
+                    if constexpr (slot == q) {
                         if constexpr (i < kFrags) frag_one(I, F_KS, buf ^ 1, f_addr);
                         else load(i - kFrags);
                     }
@@ -447,14 +456,22 @@ __device__ __forceinline__ void dl_body(const GemmArgs& g, char* lds) {
                 const int s1 = next_of(st), s2 = next_of(s1), s3 = next_of(s2), s4 = next_of(s3);
                 substep(None{}, KS1{}, 0, stage_addr(st), no_load);
                 // pair u complete for everybody (pair u + 1 may remain in flight)
+#ifndef NNT_PROBE_NO_VM
                 __builtin_amdgcn_s_waitcnt(wait_vm(2 * kLoads));
+#endif
+#ifndef NNT_PROBE_NO_BAR
                 asm volatile("s_barrier" ::: "memory");
+#endif
                 substep(None{}, KS0{}, 1, stage_addr(s1), no_load);
                 substep(None{}, KS1{}, 0, stage_addr(s1), no_load);
                 // pair u + 1 complete for everybody, and everybody done with the stages of steps
                 // 2u - 1 and 2u, which the next pair of loads overwrites
+#ifndef NNT_PROBE_NO_VM
                 __builtin_amdgcn_s_waitcnt(wait_vm(0));
+#endif
+#ifndef NNT_PROBE_NO_BAR
                 asm volatile("s_barrier" ::: "memory");
+#endif
                 // (after the last pair the fragment reads hit a stage that holds no new data: in
                 // bounds and unused)
                 substep(std::integral_constant<int, 2 * kLoads>{}, KS0{}, 1, stage_addr(s2), [&](int i) { load_pair_item(s4, st, i); });
