@@ -17,9 +17,16 @@
  *  - Pointers named `stream` are hipStream_t values passed as void* (NULL is the
  *    legacy default stream).  Pointers to tile data are DEVICE pointers; every
  *    other pointer (shapes, descriptors, out-parameters) is a HOST pointer.
- *  - The caller owns all tile memory.  The library allocates only its own small
- *    descriptor tables and reduction scratch on the device, and releases them in
- *    the matching destroy call.
+ *  - The caller owns all tile memory.  On the device the library allocates only
+ *    (a) descriptor tables: the tile-pointer table of every tensor, the tables of
+ *    cached product plans and of grouped optimiser steps; (b) the fp32 scratch of
+ *    the two-stage column sums (grows on demand, at least 4 MiB once used); (c)
+ *    for products whose contraction is cut into k-slices, an fp32 workspace of
+ *    slices x macro-tile partial sums per cached plan (at most 2 GiB each; a plan
+ *    whose workspace would be larger is built without slices).  nnt_ctx_stats
+ *    reports the bytes held for (a) and for (b) + (c).  Tables and workspaces of a
+ *    plan are released when one of its tensors or the context is destroyed, the
+ *    rest in the matching destroy call.
  *  - Element types: NNT_F32 (IEEE binary32) and NNT_BF16 (bfloat16, converted
  *    with round-to-nearest-even).  All arithmetic, reductions and accumulation
  *    are in fp32 whatever the storage type.
@@ -107,6 +114,9 @@ typedef struct nnt_exec_stats {
     int64_t launches;       /* kernel launches issued                               */
     int64_t event_waits;    /* cross-stream dependencies turned into event waits    */
     int64_t plans;          /* product plans (descriptor tables) built and cached   */
+    int64_t device_table_bytes;      /* device memory held for descriptor tables             */
+    int64_t device_workspace_bytes;  /* device memory held for reduction scratch and the
+                                        k-slice workspaces of the cached product plans       */
 } nnt_exec_stats;
 NNT_API int32_t nnt_ctx_stats(nnt_ctx* ctx, nnt_exec_stats* out);
 
@@ -514,6 +524,47 @@ NNT_API int32_t nnt_gpt2_stack_destroy(nnt_gpt2_stack* st);
 NNT_API int32_t nnt_gpt2_stack_forward(nnt_gpt2_stack* st);
 NNT_API int32_t nnt_gpt2_stack_backward(nnt_gpt2_stack* st);
 NNT_API int32_t nnt_gpt2_stack_adam(nnt_gpt2_stack* st, int32_t step, const nnt_adam_cfg* cfg);
+
+/* A GPT-2-shaped language model as one flow of tasks (section 3: embedding
+ * layer, the blocks, layer normalization, linear head, Cross-Entropy loss,
+ * optimizer): token and position embedding lookup and their sum, a chain of
+ * blocks, the final layer norm, the head tied to the token embedding
+ * (logits = W_te^T X_f), the loss summed over positions, the whole backward pass
+ * and one Adam step on every parameter.  The caller creates the blocks and the
+ * stack's activations as above, asks nnt_gpt2_model_slot for type, shape and
+ * tiling of each of the model's own tensors, allocates them and hands them over;
+ * the model keeps pointers, not ownership.
+ *   parameters (fp32 masters): W_te [N_e, N_v] (one column per vocabulary item,
+ *   tiled tile_e x tile_v), W_pe [N_e, N_s] (one column per position), gain and
+ *   bias of the final layer norm [N_e]; + NNT_MDL_GRAD their gradients, +
+ *   NNT_MDL_ADAM_M / _V their Adam moments; NNT_MDL_LOWP + {0, 1}: bf16 copies of
+ *   W_te, W_pe (bf16 models only).
+ *   activations: X_pos (position embeddings of the batch), X_f (final layer norm),
+ *   dX_f, its statistics, the logits [N_v, N_s, N_b] (overwritten with their own
+ *   gradient by the loss) and the loss's column statistics.
+ * forward: tokens, positions, labels are device pointers to N_s * N_b int32
+ * (position s + N_s * b of the batch); col_loss (N_s * N_b floats) and loss (1
+ * float) are device buffers of the caller, valid after nnt_wait.  backward uses
+ * the tokens / positions of the last forward call.  The gradient of W_te collects
+ * the head's and the lookup's share; sums over positions that share a token use
+ * hardware fp32 atomics (order not fixed). */
+typedef struct nnt_gpt2_model nnt_gpt2_model;
+enum {
+    NNT_MDL_WTE = 0, NNT_MDL_WPE = 1, NNT_MDL_GAMMA_F = 2, NNT_MDL_BETA_F = 3,
+    NNT_MDL_GRAD = 4, NNT_MDL_ADAM_M = 8, NNT_MDL_ADAM_V = 12, NNT_MDL_LOWP = 16,
+    NNT_MDL_XPOS = 18, NNT_MDL_XF = 19, NNT_MDL_DXF = 20, NNT_MDL_STATS_F = 21, NNT_MDL_LOGITS = 22, NNT_MDL_LOSS_STATS = 23,
+    NNT_MDL_NSLOTS = 24
+};
+NNT_API int32_t nnt_gpt2_model_slot(const nnt_gpt2_block_cfg* cfg, int64_t N_v, int64_t tile_v, int32_t slot, nnt_slot_info* out);
+NNT_API int32_t nnt_gpt2_model_create(nnt_ctx* ctx, const nnt_gpt2_block_cfg* cfg, int64_t N_v, int64_t tile_v,
+                              nnt_gpt2_stack* stack, nnt_tensor* const* slots, nnt_gpt2_model** out);
+NNT_API int32_t nnt_gpt2_model_destroy(nnt_gpt2_model* m);
+/* bf16 models: refreshes the bf16 copies of W_te, W_pe from the fp32 masters (after the caller wrote them) */
+NNT_API int32_t nnt_gpt2_model_sync_lowp(nnt_gpt2_model* m);
+NNT_API int32_t nnt_gpt2_model_forward(nnt_gpt2_model* m, const int32_t* tokens, const int32_t* positions,
+                               const int32_t* labels, float* col_loss, float* loss);
+NNT_API int32_t nnt_gpt2_model_backward(nnt_gpt2_model* m);
+NNT_API int32_t nnt_gpt2_model_adam(nnt_gpt2_model* m, int32_t step, const nnt_adam_cfg* cfg);
 
 NNT_API const char* nnt_version(void);
 

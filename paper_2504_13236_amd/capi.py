@@ -32,6 +32,10 @@ NNT_BLK_GRAD, NNT_BLK_ADAM_M, NNT_BLK_ADAM_V, NNT_BLK_LOWP = 12, 24, 36, 48
  NNT_BLK_BH, NNT_BLK_BM, NNT_BLK_X2, NNT_BLK_STATS2, NNT_BLK_X3, NNT_BLK_H1, NNT_BLK_G,
  NNT_BLK_DG, NNT_BLK_DX3, NNT_BLK_DX2, NNT_BLK_DBM, NNT_BLK_DBH, NNT_BLK_DP,
  NNT_BLK_DQ, NNT_BLK_DK, NNT_BLK_DV, NNT_BLK_DQKV, NNT_BLK_DX1, NNT_BLK_NSLOTS) = range(52, 79)
+# slots of a language model's own tensors
+NNT_MDL_WTE, NNT_MDL_WPE, NNT_MDL_GAMMA_F, NNT_MDL_BETA_F = 0, 1, 2, 3
+NNT_MDL_GRAD, NNT_MDL_ADAM_M, NNT_MDL_ADAM_V, NNT_MDL_LOWP = 4, 8, 12, 16
+(NNT_MDL_XPOS, NNT_MDL_XF, NNT_MDL_DXF, NNT_MDL_STATS_F, NNT_MDL_LOGITS, NNT_MDL_LOSS_STATS, NNT_MDL_NSLOTS) = range(18, 25)
 
 
 class NntError(RuntimeError):
@@ -41,7 +45,8 @@ class NntError(RuntimeError):
 
 
 class nnt_exec_stats(C.Structure):
-    _fields_ = [("tasks", C.c_int64), ("launches", C.c_int64), ("event_waits", C.c_int64), ("plans", C.c_int64)]
+    _fields_ = [("tasks", C.c_int64), ("launches", C.c_int64), ("event_waits", C.c_int64), ("plans", C.c_int64),
+                ("device_table_bytes", C.c_int64), ("device_workspace_bytes", C.c_int64)]
 
 
 class nnt_profile_entry(C.Structure):
@@ -114,6 +119,13 @@ PROTOTYPES = {
     "nnt_tile_bias_add": (_i32, [_p, _i32, _i64, _i64, _p, _p]),
     "nnt_tile_bias_grad_scratch": (_i64, [_i64, _i64]),
     "nnt_tile_bias_grad": (_i32, [_p, _i32, _i64, _i64, _p, _p, _i32, _p]),
+    "nnt_gpt2_model_slot": (_i32, [C.POINTER(nnt_gpt2_block_cfg), _i64, _i64, _i32, C.POINTER(nnt_slot_info)]),
+    "nnt_gpt2_model_create": (_i32, [_p, C.POINTER(nnt_gpt2_block_cfg), _i64, _i64, _p, _p, _pp]),
+    "nnt_gpt2_model_destroy": (_i32, [_p]),
+    "nnt_gpt2_model_sync_lowp": (_i32, [_p]),
+    "nnt_gpt2_model_forward": (_i32, [_p, _p, _p, _p, _p, _p]),
+    "nnt_gpt2_model_backward": (_i32, [_p]),
+    "nnt_gpt2_model_adam": (_i32, [_p, _i32, C.POINTER(nnt_adam_cfg)]),
     "nnt_probe_mfma_rate": (_i32, [_p, _i32, _i32, _i32, _i32, _p, _p]),
     "nnt_tile_bias_grad_static_max": (_i64, []),
     "nnt_tile_bias_grad_static": (_i32, [_p, _i32, _i64, _i64, _p, _p, _i32]),
@@ -175,7 +187,9 @@ _CTX_FIRST = {n for n, (r, a) in PROTOTYPES.items()
               and n not in ("nnt_ctx_create", "nnt_version", "nnt_gpt2_block_slot", "nnt_last_error", "nnt_sched_simulate")
               and not n.startswith("nnt_tensor_") and not n.startswith("nnt_graph_")
               and not n.startswith("nnt_gpt2_block_")
-              and (not n.startswith("nnt_gpt2_stack_") or n == "nnt_gpt2_stack_create")}
+              and (not n.startswith("nnt_gpt2_stack_") or n == "nnt_gpt2_stack_create")
+              and (not n.startswith("nnt_gpt2_model_") or n == "nnt_gpt2_model_create")
+              and not n.startswith("nnt_probe_")}
 
 
 def _wrap(name, restype, argtypes):

@@ -31,6 +31,18 @@ struct nnt_gpt2_stack {
     std::vector<nnt_tensor*> acts, dacts;
 };
 
+// A language model around a chain of blocks: the model's own tensors by slot, and what the last
+// forward call was given.
+struct nnt_gpt2_model {
+    nnt_ctx* ctx;
+    nnt_gpt2_block_cfg cfg;
+    int64_t N_v;
+    nnt_gpt2_stack* stack;
+    nnt_tensor* s[NNT_MDL_NSLOTS];
+    const int32_t* tokens;
+    const int32_t* positions;
+};
+
 using namespace nnt;
 
 namespace {
@@ -364,6 +376,145 @@ int32_t nnt_gpt2_block_sync_lowp(nnt_gpt2_block* b) {
     NNT_CHECK_CTX(ctx);
     if (b->cfg.dtype != NNT_BF16) return NNT_OK;
     for (int p = 0; p < 4; p++) TRY(nnt_cast(ctx, b->s[p], b->s[NNT_BLK_LOWP + p]));
+    return NNT_OK;
+}
+
+// ---------------------------------------------------------------- language model
+int32_t nnt_gpt2_model_slot(const nnt_gpt2_block_cfg* c, int64_t N_v, int64_t tile_v, int32_t slot, nnt_slot_info* o) {
+    if (!cfg_ok(c) || !o || slot < 0 || slot >= NNT_MDL_NSLOTS || N_v < 1 || tile_v < 1) return NNT_EINVAL;
+    *o = nnt_slot_info{};
+    const int64_t e = c->N_e, sq = c->N_s, b = c->N_b, te = c->tile_e, ts = c->tile_s, tb = c->tile_b;
+    const int64_t wte[2] = {e, N_v}, wteb[2] = {te, tile_v}, wpe[2] = {e, sq}, wpeb[2] = {te, ts}, vec[1] = {e}, vecb[1] = {te};
+    const int64_t act3[3] = {e, sq, b}, act3b[3] = {te, ts, tb}, st3[3] = {2, sq, b}, st3b[3] = {2, ts, tb};
+    const int64_t lg3[3] = {N_v, sq, b}, lg3b[3] = {tile_v, ts, tb};
+    if (slot < NNT_MDL_LOWP + 2) {
+        const int p = slot < NNT_MDL_LOWP ? slot % 4 : slot - NNT_MDL_LOWP;
+        const int dt = slot < NNT_MDL_LOWP ? NNT_F32 : NNT_BF16;
+        if (slot >= NNT_MDL_LOWP && c->dtype != NNT_BF16) return NNT_OK;      // unused in fp32 models
+        if (p == NNT_MDL_WTE) set(o, dt, 2, wte, wteb);
+        else if (p == NNT_MDL_WPE) set(o, dt, 2, wpe, wpeb);
+        else set(o, dt, 1, vec, vecb);
+        return NNT_OK;
+    }
+    switch (slot) {
+        case NNT_MDL_XPOS: case NNT_MDL_XF: case NNT_MDL_DXF: set(o, c->dtype, 3, act3, act3b); break;
+        case NNT_MDL_STATS_F: case NNT_MDL_LOSS_STATS: set(o, NNT_F32, 3, st3, st3b); break;
+        case NNT_MDL_LOGITS: set(o, c->dtype, 3, lg3, lg3b); break;
+        default: return NNT_EINVAL;
+    }
+    return NNT_OK;
+}
+
+int32_t nnt_gpt2_model_create(nnt_ctx* ctx, const nnt_gpt2_block_cfg* cfg, int64_t N_v, int64_t tile_v, nnt_gpt2_stack* stack,
+                              nnt_tensor* const* slots, nnt_gpt2_model** out) {
+    NNT_CHECK_CTX(ctx);
+    if (!out) return NNT_EINVAL;
+    *out = nullptr;
+    if (!cfg_ok(cfg) || !slots || !stack || stack->ctx != ctx || N_v < 1 || tile_v < 1)
+        return fail(ctx, NNT_EINVAL, "nnt_gpt2_model_create: bad argument");
+    if (!same_tiling(stack->acts[0], stack->blocks[0]->s[NNT_BLK_X1]) || stack->blocks[0]->cfg.N_e != cfg->N_e ||
+        stack->blocks[0]->cfg.N_s != cfg->N_s || stack->blocks[0]->cfg.N_b != cfg->N_b || stack->blocks[0]->cfg.dtype != cfg->dtype)
+        return fail(ctx, NNT_EINVAL, "nnt_gpt2_model_create: the stack's blocks do not match the configuration");
+    nnt_gpt2_model* m = new (std::nothrow) nnt_gpt2_model();
+    if (!m) return fail(ctx, NNT_ENOMEM, "host allocation failed");
+    m->ctx = ctx;
+    m->cfg = *cfg;
+    m->N_v = N_v;
+    m->stack = stack;
+    m->tokens = m->positions = nullptr;
+    for (int i = 0; i < NNT_MDL_NSLOTS; i++) {
+        nnt_slot_info info;
+        nnt_gpt2_model_slot(cfg, N_v, tile_v, i, &info);
+        nnt_tensor* t = slots[i];
+        m->s[i] = t;
+        if (!info.used) continue;
+        const bool optional = i >= NNT_MDL_ADAM_M && i < NNT_MDL_LOWP;
+        if (!t) {
+            if (optional) continue;
+            delete m;
+            return fail(ctx, NNT_EINVAL, "nnt_gpt2_model_create: missing tensor for slot " + std::to_string(i));
+        }
+        bool ok = t->ctx == ctx && t->dtype == info.dtype && t->ndim == info.ndim;
+        for (int a = 0; ok && a < info.ndim; a++) ok = t->shape[a] == info.shape[a] && t->base[a] == info.basetile[a];
+        if (!ok) {
+            delete m;
+            return fail(ctx, NNT_EINVAL, "nnt_gpt2_model_create: tensor of slot " + std::to_string(i) + " has the wrong type, shape or tiling");
+        }
+    }
+    *out = m;
+    return NNT_OK;
+}
+
+int32_t nnt_gpt2_model_destroy(nnt_gpt2_model* m) {
+    if (!m) return NNT_EINVAL;
+    delete m;
+    return NNT_OK;
+}
+
+static nnt_tensor* table_of(nnt_gpt2_model* m, int p) { return m->cfg.dtype == NNT_BF16 ? m->s[NNT_MDL_LOWP + p] : m->s[p]; }
+
+int32_t nnt_gpt2_model_sync_lowp(nnt_gpt2_model* m) {
+    if (!m) return NNT_EINVAL;
+    NNT_CHECK_CTX(m->ctx);
+    if (m->cfg.dtype != NNT_BF16) return NNT_OK;
+    for (int p = 0; p < 2; p++) TRY(nnt_cast(m->ctx, m->s[p], m->s[NNT_MDL_LOWP + p]));
+    return NNT_OK;
+}
+
+int32_t nnt_gpt2_model_forward(nnt_gpt2_model* m, const int32_t* tokens, const int32_t* positions, const int32_t* labels,
+                               float* col_loss, float* loss) {
+    if (!m) return NNT_EINVAL;
+    nnt_ctx* ctx = m->ctx;
+    NNT_CHECK_CTX(ctx);
+    if (!tokens || !positions || !labels || !col_loss || !loss) return fail(ctx, NNT_EINVAL, "nnt_gpt2_model_forward: null argument");
+    nnt_gpt2_stack* st = m->stack;
+    nnt_tensor** s = m->s;
+    m->tokens = tokens;
+    m->positions = positions;
+    // X_0 = W_te[:, token] + W_pe[:, position]
+    TRY(nnt_embedding_fwd(ctx, tokens, table_of(m, NNT_MDL_WTE), st->acts[0]));
+    TRY(nnt_embedding_fwd(ctx, positions, table_of(m, NNT_MDL_WPE), s[NNT_MDL_XPOS]));
+    TRY(nnt_add(ctx, 1.f, s[NNT_MDL_XPOS], 1.f, st->acts[0]));
+    TRY(nnt_gpt2_stack_forward(st));
+    TRY(nnt_layernorm_fwd(ctx, st->acts.back(), s[NNT_MDL_GAMMA_F], s[NNT_MDL_BETA_F], m->cfg.eps, s[NNT_MDL_XF], s[NNT_MDL_STATS_F]));
+    // logits = W_te^T X_f (the head shares the token embedding), then the loss, which leaves dL/dlogits in place
+    TRY(nnt_gemm(ctx, 1.f, NNT_OP_T, table_of(m, NNT_MDL_WTE), NNT_OP_N, s[NNT_MDL_XF], 0.f, s[NNT_MDL_LOGITS], 1, 0, nullptr));
+    return nnt_cross_entropy(ctx, s[NNT_MDL_LOGITS], labels, s[NNT_MDL_LOSS_STATS], col_loss, loss);
+}
+
+int32_t nnt_gpt2_model_backward(nnt_gpt2_model* m) {
+    if (!m) return NNT_EINVAL;
+    nnt_ctx* ctx = m->ctx;
+    NNT_CHECK_CTX(ctx);
+    if (!m->tokens) return fail(ctx, NNT_ESTATE, "nnt_gpt2_model_backward: no forward pass to differentiate");
+    nnt_gpt2_stack* st = m->stack;
+    nnt_tensor** s = m->s;
+    nnt_tensor** g = s + NNT_MDL_GRAD;
+    // dX_f = W_te dlogits;  dW_te = X_f dlogits^T (the head's share, summed over positions and batch)
+    TRY(nnt_gemm(ctx, 1.f, NNT_OP_N, table_of(m, NNT_MDL_WTE), NNT_OP_N, s[NNT_MDL_LOGITS], 0.f, s[NNT_MDL_DXF], 1, 0, nullptr));
+    TRY(nnt_gemm(ctx, 1.f, NNT_OP_N, s[NNT_MDL_XF], NNT_OP_T, s[NNT_MDL_LOGITS], 0.f, g[NNT_MDL_WTE], 2, 0, nullptr));
+    TRY(nnt_layernorm_bwd(ctx, st->acts.back(), s[NNT_MDL_STATS_F], s[NNT_MDL_GAMMA_F], s[NNT_MDL_DXF], nullptr, st->dacts.back(),
+                          g[NNT_MDL_GAMMA_F], g[NNT_MDL_BETA_F]));
+    TRY(nnt_gpt2_stack_backward(st));
+    // the lookups' share: columns of dX_0 added to the columns of their tokens / positions
+    TRY(nnt_embedding_bwd(ctx, m->tokens, st->dacts[0], g[NNT_MDL_WTE]));
+    TRY(nnt_fill(ctx, 0.f, g[NNT_MDL_WPE]));
+    return nnt_embedding_bwd(ctx, m->positions, st->dacts[0], g[NNT_MDL_WPE]);
+}
+
+int32_t nnt_gpt2_model_adam(nnt_gpt2_model* m, int32_t step, const nnt_adam_cfg* cfg) {
+    if (!m) return NNT_EINVAL;
+    nnt_ctx* ctx = m->ctx;
+    NNT_CHECK_CTX(ctx);
+    if (!cfg || step < 1) return fail(ctx, NNT_EINVAL, "nnt_gpt2_model_adam: bad argument");
+    for (int p = 0; p < 4; p++)
+        if (!m->s[NNT_MDL_ADAM_M + p] || !m->s[NNT_MDL_ADAM_V + p])
+            return fail(ctx, NNT_ESTATE, "nnt_gpt2_model_adam: the model was created without Adam moments");
+    TRY(nnt_gpt2_stack_adam(m->stack, step, cfg));
+    for (int p = 0; p < 4; p++) {
+        nnt_tensor* lowp = (m->cfg.dtype == NNT_BF16 && p < 2) ? m->s[NNT_MDL_LOWP + p] : nullptr;
+        TRY(nnt_adam_step(ctx, cfg, step, m->s[NNT_MDL_GRAD + p], m->s[p], m->s[NNT_MDL_ADAM_M + p], m->s[NNT_MDL_ADAM_V + p], lowp));
+    }
     return NNT_OK;
 }
 

@@ -423,10 +423,13 @@ struct AdamGroup {
     int64_t entries = 0, max_numel = 0;
     bool vec = true;
     double bytes = 0.0;
+    nnt_ctx* ctx = nullptr;
+    int64_t table_bytes = 0;
 };
 
 void adam_group_destroy(AdamGroup* a) {
     if (!a) return;
+    if (a->ctx) a->ctx->table_bytes -= a->table_bytes;
     if (a->tabs) (void)hipFree(a->tabs);
     if (a->numel) (void)hipFree(a->numel);
     delete a;
@@ -466,6 +469,9 @@ int32_t adam_group_create(nnt_ctx* ctx, int n, nnt_tensor* const* G, nnt_tensor*
     NNT_HIP(ctx, hipMalloc(&a->numel, E * sizeof(int64_t)));
     NNT_HIP(ctx, hipMemcpy(a->tabs, all.data(), 5 * E * sizeof(void*), hipMemcpyHostToDevice));
     NNT_HIP(ctx, hipMemcpy(a->numel, ne.data(), E * sizeof(int64_t), hipMemcpyHostToDevice));
+    a->ctx = ctx;
+    a->table_bytes = (int64_t)(5 * E * sizeof(void*) + E * sizeof(int64_t));
+    ctx->table_bytes += a->table_bytes;
     *out = a.release();
     return NNT_OK;
 }

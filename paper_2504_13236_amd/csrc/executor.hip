@@ -417,6 +417,9 @@ int32_t nnt_ctx_stats(nnt_ctx* ctx, nnt_exec_stats* out) {
     if (!ctx || !out) return NNT_EINVAL;
     *out = ctx->stats;
     out->plans = (int64_t)ctx->gemm_plans.size();
+    out->device_table_bytes = ctx->table_bytes;
+    out->device_workspace_bytes = ctx->red_scratch_elems * (int64_t)sizeof(float);
+    plan_device_bytes(ctx, &out->device_table_bytes, &out->device_workspace_bytes);
     return NNT_OK;
 }
 

@@ -110,6 +110,7 @@ struct GemmPlan {
     std::vector<int64_t> task_wg0;             // first workgroup of each task (+ total at the end)
     std::vector<int64_t> task_nfast;           // leading workgroups of each task that qualify for the direct-load kernel
     int64_t op_nfast = 0;                      // the same for the whole-operation order
+    int64_t table_bytes = 0, ws_bytes = 0;     // device memory of the descriptor tables / the k-slice workspaces
     bool dl_ragged = false;                    // they need the direct-load kernel's variant for ragged macro-tiles and short k-steps
     std::vector<int64_t> task_ctile;           // C tile index per task
     std::vector<std::vector<int64_t>> task_atiles, task_btiles;   // operand tiles per task (dependencies)
@@ -147,6 +148,13 @@ struct GemmPlan {
             if (p) (void)hipFree(p);
     }
 };
+
+void plan_device_bytes(nnt_ctx* ctx, int64_t* tables, int64_t* workspaces) {
+    for (const auto& kv : ctx->gemm_plans) {
+        *tables += kv.second->table_bytes;
+        *workspaces += kv.second->ws_bytes;
+    }
+}
 
 void drop_plans_of(nnt_ctx* ctx, uint64_t id) {
     for (auto it = ctx->gemm_plans.begin(); it != ctx->gemm_plans.end();) {
@@ -618,6 +626,11 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
     xcd_interleave(P->wgs_op, bm, bn);
 
     // ---- k-slices for the last n_split macro-tiles of the whole-operation order
+    // (a workspace above 2 GiB is not worth its memory: such a product runs without slices)
+    if (S > 1 && (int64_t)std::min<int64_t>(n_split, (int64_t)P->wgs_op.size()) * S * bm * bn * (int64_t)sizeof(float) > ((int64_t)2 << 30)) {
+        S = 1;
+        n_split = 0;
+    }
     P->splits = S;
     P->n_split = n_split = std::min<int64_t>(n_split, (int64_t)P->wgs_op.size());
     if (S > 1 && n_split > 0) {
@@ -626,6 +639,7 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
         P->wgs_op.resize(keep);
         const int64_t slice = (int64_t)bm * bn;
         NNT_HIP(ctx, hipMalloc((void**)&P->d_ws, (size_t)n_split * S * slice * sizeof(float)));
+        P->ws_bytes += (int64_t)n_split * S * slice * (int64_t)sizeof(float);
         // chunk ranges of the slices, built once per C tile
         std::vector<std::vector<std::pair<int32_t, int32_t>>> ranges(P->tasks.size());
         std::vector<SplitReduce> red;
@@ -662,6 +676,7 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
         P->red_blocks = (int)((slice / 4 + 255) / 256);
         P->slice_elems = slice;
         NNT_HIP(ctx, hipMalloc((void**)&P->d_red, red.size() * sizeof(SplitReduce)));
+        P->table_bytes += (int64_t)(red.size() * sizeof(SplitReduce));
         NNT_HIP(ctx, hipMemcpy(P->d_red, red.data(), red.size() * sizeof(SplitReduce), hipMemcpyHostToDevice));
     } else {
         P->splits = 1;
@@ -696,6 +711,7 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
         }
         if (ws_blocks > 0) {
             NNT_HIP(ctx, hipMalloc((void**)&P->d_ws_ts, (size_t)ws_blocks * slice * sizeof(float)));
+            P->ws_bytes += (int64_t)ws_blocks * slice * (int64_t)sizeof(float);
             float* next_block = P->d_ws_ts;
             for (size_t ti = 0; ti < n_tile_tasks; ti++) {
                 const int St = st[ti];
@@ -717,6 +733,7 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
             P->red_blocks = (int)((slice / 4 + 255) / 256);    // (the same value the whole-operation slices set)
             P->slice_elems_ts = slice;
             NNT_HIP(ctx, hipMalloc((void**)&P->d_red_ts, red_ts.size() * sizeof(SplitReduce)));
+            P->table_bytes += (int64_t)(red_ts.size() * sizeof(SplitReduce));
             NNT_HIP(ctx, hipMemcpy(P->d_red_ts, red_ts.data(), red_ts.size() * sizeof(SplitReduce), hipMemcpyHostToDevice));
         }
     }
@@ -774,6 +791,7 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
         if (bytes == 0) return hipSuccess;
         hipError_t e = hipMalloc(d, bytes);
         if (e != hipSuccess) return e;
+        P->table_bytes += (int64_t)bytes;
         return hipMemcpy(*d, h, bytes, hipMemcpyHostToDevice);
     };
     NNT_HIP(ctx, up((void**)&P->d_tasks, P->tasks.data(), P->tasks.size() * sizeof(GemmTask)));

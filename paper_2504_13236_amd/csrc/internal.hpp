@@ -120,7 +120,8 @@ struct nnt_ctx {
     std::vector<hipEvent_t> capture_events;               // fork / join events of the open capture
     int rr = 0;                      // round-robin cursor
     bool capturing = false;
-    nnt_exec_stats stats = {0, 0, 0, 0};
+    nnt_exec_stats stats = {0, 0, 0, 0, 0, 0};
+    int64_t table_bytes = 0;         // device bytes of tensor tile tables and optimiser group tables (plans count their own)
     uint64_t next_tensor_id = 1;
     std::map<std::string, std::shared_ptr<nnt::GemmPlan>> gemm_plans;
     int64_t live_tensors = 0;
@@ -186,6 +187,7 @@ int32_t adam_group_create(nnt_ctx* ctx, int n, nnt_tensor* const* G, nnt_tensor*
 int32_t adam_group_step(nnt_ctx* ctx, AdamGroup* a, const nnt_adam_cfg* cfg, int32_t step);
 void adam_group_destroy(AdamGroup* a);
 void drop_plans_of(nnt_ctx* ctx, uint64_t tensor_id);
+void plan_device_bytes(nnt_ctx* ctx, int64_t* tables, int64_t* workspaces);      // adds what the cached product plans hold
 
 inline bool same_tiling(const nnt_tensor* a, const nnt_tensor* b) {
     if (a->ndim != b->ndim) return false;

@@ -67,6 +67,7 @@ int32_t nnt_tensor_create(nnt_ctx* ctx, int32_t dtype, int32_t ndim, const int64
         return fail(ctx, NNT_EHIP, std::string("tile table upload: ") + hipGetErrorString(e));
     }
     ctx->live_tensors++;
+    ctx->table_bytes += t->ntiles * (int64_t)sizeof(void*);
     *out = t;
     return NNT_OK;
 }
@@ -78,6 +79,7 @@ int32_t nnt_tensor_destroy(nnt_tensor* t) {
     for (int s = 0; s < ctx->n_streams; s++) (void)hipStreamSynchronize(ctx->streams[s]);
     drop_plans_of(ctx, t->id);
     (void)hipFree(t->d_tiles);
+    ctx->table_bytes -= t->ntiles * (int64_t)sizeof(void*);
     ctx->live_tensors--;
     delete t;
     return NNT_OK;

@@ -50,7 +50,8 @@ class Context:
     def stats(self):
         s = capi.nnt_exec_stats()
         capi.nnt_ctx_stats(self.h, C.byref(s))
-        return dict(tasks=s.tasks, launches=s.launches, event_waits=s.event_waits, plans=s.plans)
+        return dict(tasks=s.tasks, launches=s.launches, event_waits=s.event_waits, plans=s.plans,
+                    device_table_bytes=s.device_table_bytes, device_workspace_bytes=s.device_workspace_bytes)
 
     def profile(self, on=True):
         capi.nnt_profile_enable(self.h, 1 if on else 0)
@@ -307,9 +308,10 @@ class Gpt2Stack:
 
 
 class Gpt2Model:
-    """A GPT-2-shaped language model as one flow of tasks: token + position embedding lookup, a chain
-    of blocks, the final layer norm, the head tied to the token embedding, the cross-entropy loss, the
-    whole backward pass and one Adam step.  Allocation and call order only: every step is a library call.
+    """A GPT-2-shaped language model (token + position embedding lookup, a chain of blocks, the final
+    layer norm, the head tied to the token embedding, the cross-entropy loss, the whole backward pass and
+    one Adam step) through the library's nnt_gpt2_model_* entry points.  This class only allocates the
+    tensors the library describes slot by slot and marshals the calls.
 
     Tensors (paper's axis order): `wte` [N_e, N_v] and `wpe` [N_e, N_s] fp32 masters (one column per
     vocabulary item / position), their gradients and Adam moments, bf16 copies for bf16 models."""
@@ -319,35 +321,35 @@ class Gpt2Model:
         b0 = self.blocks[0]
         self.N_e, self.N_s, self.N_b = b0.act_shape
         self.N_v = int(N_v)
-        te, ts, tb = b0.act_base
         self.dtype = b0.dtype
-        self.lowp = self.dtype == capi.NNT_BF16
         self.stack = Gpt2Stack(ctx, self.blocks)
+        self.slots = [None] * capi.NNT_MDL_NSLOTS
+        for s in range(capi.NNT_MDL_NSLOTS):
+            info = capi.nnt_slot_info()
+            capi.nnt_gpt2_model_slot(C.byref(b0.cfg), self.N_v, int(tile_v), s, C.byref(info))
+            if info.used:
+                zero = s < capi.NNT_MDL_LOWP            # parameters, gradients and moments start at zero
+                self.slots[s] = TiledTensor(ctx, info.dtype, tuple(info.shape[:info.ndim]), tuple(info.basetile[:info.ndim]),
+                                            fill=0 if zero else None)
+        h = C.c_void_p()
+        capi.nnt_gpt2_model_create(ctx.h, C.byref(b0.cfg), self.N_v, int(tile_v), self.stack.h,
+                                   capi.ptr_array([t.h.value if t is not None else None for t in self.slots]), C.byref(h))
+        self.h = h
 
-        def table(ncol, tcol):
-            t = dict(p=TiledTensor.zeros(ctx, (self.N_e, ncol), (te, tcol)), g=TiledTensor.zeros(ctx, (self.N_e, ncol), (te, tcol)),
-                     m=TiledTensor.zeros(ctx, (self.N_e, ncol), (te, tcol)), v=TiledTensor.zeros(ctx, (self.N_e, ncol), (te, tcol)))
-            t["lowp"] = TiledTensor(ctx, "bf16", (self.N_e, ncol), (te, tcol)) if self.lowp else None
-            return t
-
-        def vector():
-            return dict(p=TiledTensor.zeros(ctx, (self.N_e,), (te,)), g=TiledTensor.zeros(ctx, (self.N_e,), (te,)),
-                        m=TiledTensor.zeros(ctx, (self.N_e,), (te,)), v=TiledTensor.zeros(ctx, (self.N_e,), (te,)), lowp=None)
-        self.wte, self.wpe = table(self.N_v, tile_v), table(self.N_s, ts)
-        self.gamma, self.beta = vector(), vector()
-        self.Xpos = b0.activation()                       # position embeddings of the batch
-        self.Xf = b0.activation()                         # final layer norm's output
-        self.dXf = b0.activation()
-        self.stats = TiledTensor(ctx, "f32", (2, self.N_s, self.N_b), (2, ts, tb))
-        self.logits = TiledTensor(ctx, self.dtype, (self.N_v, self.N_s, self.N_b), (tile_v, ts, tb))
-        self.lstats = TiledTensor(ctx, "f32", (2, self.N_s, self.N_b), (2, ts, tb))
-        self.col_loss = torch.empty(self.N_s * self.N_b, dtype=torch.float32, device="cuda:%d" % ctx.device)
-        self.loss = torch.zeros(1, dtype=torch.float32, device="cuda:%d" % ctx.device)
+        def group(p):
+            lowp = self.slots[capi.NNT_MDL_LOWP + p] if p < 2 else None
+            return dict(p=self.slots[p], g=self.slots[capi.NNT_MDL_GRAD + p], m=self.slots[capi.NNT_MDL_ADAM_M + p],
+                        v=self.slots[capi.NNT_MDL_ADAM_V + p], lowp=lowp)
+        self.wte, self.wpe = group(capi.NNT_MDL_WTE), group(capi.NNT_MDL_WPE)
+        self.gamma, self.beta = group(capi.NNT_MDL_GAMMA_F), group(capi.NNT_MDL_BETA_F)
+        self.logits = self.slots[capi.NNT_MDL_LOGITS]
+        dev = "cuda:%d" % ctx.device
+        self.col_loss = torch.empty(self.N_s * self.N_b, dtype=torch.float32, device=dev)
+        self.loss = torch.zeros(1, dtype=torch.float32, device=dev)
         pos = np.repeat(np.arange(self.N_s, dtype=np.int32)[:, None], self.N_b, axis=1)
-        self.pos = torch.from_numpy(np.ascontiguousarray(pos.reshape(-1, order="F"))).to("cuda:%d" % ctx.device)
-        self.tokens = torch.zeros(self.N_s * self.N_b, dtype=torch.int32, device="cuda:%d" % ctx.device)
-        self.labels = torch.zeros(self.N_s * self.N_b, dtype=torch.int32, device="cuda:%d" % ctx.device)
-        self.eps = float(b0.cfg.eps)
+        self.pos = torch.from_numpy(np.ascontiguousarray(pos.reshape(-1, order="F"))).to(dev)
+        self.tokens = torch.zeros(self.N_s * self.N_b, dtype=torch.int32, device=dev)
+        self.labels = torch.zeros(self.N_s * self.N_b, dtype=torch.int32, device=dev)
         torch.cuda.synchronize()
 
     def set_params(self, wte, wpe, gamma, beta):
@@ -355,10 +357,8 @@ class Gpt2Model:
         self.wpe["p"].upload(wpe)
         self.gamma["p"].upload(gamma)
         self.beta["p"].upload(beta)
-        if self.lowp:
-            capi.nnt_cast(self.ctx.h, self.wte["p"].h, self.wte["lowp"].h)
-            capi.nnt_cast(self.ctx.h, self.wpe["p"].h, self.wpe["lowp"].h)
-            self.ctx.wait()
+        capi.nnt_gpt2_model_sync_lowp(self.h)
+        self.ctx.wait()
 
     def set_batch(self, tokens, labels):
         """tokens, labels: integer arrays [N_s, N_b]."""
@@ -366,38 +366,20 @@ class Gpt2Model:
             dst.copy_(torch.from_numpy(np.ascontiguousarray(np.asarray(a, np.int32).reshape(-1, order="F"))))
         torch.cuda.synchronize()
 
-    def _w(self, t):
-        return (t["lowp"] if self.lowp else t["p"]).h
-
     def forward(self):
-        c, st = self.ctx.h, self.stack
-        capi.nnt_embedding_fwd(c, self.tokens.data_ptr(), self._w(self.wte), st.acts[0].h)
-        capi.nnt_embedding_fwd(c, self.pos.data_ptr(), self._w(self.wpe), self.Xpos.h)
-        capi.nnt_add(c, 1.0, self.Xpos.h, 1.0, st.acts[0].h)
-        st.forward()
-        capi.nnt_layernorm_fwd(c, st.acts[-1].h, self.gamma["p"].h, self.beta["p"].h, self.eps, self.Xf.h, self.stats.h)
-        capi.nnt_gemm(c, 1.0, 1, self._w(self.wte), 0, self.Xf.h, 0.0, self.logits.h, 1, 0, None)      # logits = wte^T Xf
-        capi.nnt_cross_entropy(c, self.logits.h, self.labels.data_ptr(), self.lstats.h, self.col_loss.data_ptr(), self.loss.data_ptr())
+        capi.nnt_gpt2_model_forward(self.h, self.tokens.data_ptr(), self.pos.data_ptr(), self.labels.data_ptr(),
+                                    self.col_loss.data_ptr(), self.loss.data_ptr())
 
     def backward(self):
-        """After forward(): `logits` holds the loss gradient with respect to the logits."""
-        c, st = self.ctx.h, self.stack
-        capi.nnt_gemm(c, 1.0, 0, self._w(self.wte), 0, self.logits.h, 0.0, self.dXf.h, 1, 0, None)    # dXf = wte dlogits
-        capi.nnt_gemm(c, 1.0, 0, self.Xf.h, 1, self.logits.h, 0.0, self.wte["g"].h, 2, 0, None)       # dwte = Xf dlogits^T
-        capi.nnt_layernorm_bwd(c, st.acts[-1].h, self.stats.h, self.gamma["p"].h, self.dXf.h, None, st.dacts[-1].h,
-                               self.gamma["g"].h, self.beta["g"].h)
-        st.backward()
-        capi.nnt_embedding_bwd(c, self.tokens.data_ptr(), st.dacts[0].h, self.wte["g"].h)              # + the lookup's share
-        capi.nnt_fill(c, 0.0, self.wpe["g"].h)
-        capi.nnt_embedding_bwd(c, self.pos.data_ptr(), st.dacts[0].h, self.wpe["g"].h)
+        capi.nnt_gpt2_model_backward(self.h)
 
     def adam(self, step, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0):
-        self.stack.adam(step, lr, beta1, beta2, eps, weight_decay)
         cfg = capi.nnt_adam_cfg(lr, beta1, beta2, eps, weight_decay)
-        for t in (self.wte, self.wpe, self.gamma, self.beta):
-            capi.nnt_adam_step(self.ctx.h, C.byref(cfg), step, t["g"].h, t["p"].h, t["m"].h, t["v"].h,
-                               t["lowp"].h if t["lowp"] is not None else None)
+        capi.nnt_gpt2_model_adam(self.h, step, C.byref(cfg))
 
     def close(self):
         self.ctx.wait()
+        if self.h:
+            capi.nnt_gpt2_model_destroy(self.h)
+            self.h = None
         self.stack.close()
