@@ -121,7 +121,9 @@ struct TaskPlan {
 // A task must run after the last writer of every tile it touches (read-after-write, write-after-write)
 // and, if it writes, after every reader since that write (write-after-read).  One sequence number
 // per stream is enough because a stream runs its tasks in order.
-static TaskPlan plan_task(const std::vector<Access>& acc, int ns, bool serial, const uint64_t* tail_seq,
+// `ns` streams may take the task; dependencies are looked for on all `ns_all` streams of the context (while a
+// capture is open fewer streams take tasks than exist).
+static TaskPlan plan_task(const std::vector<Access>& acc, int ns, int ns_all, bool serial, const uint64_t* tail_seq,
                           const uint64_t* synced_seq, uint64_t (*waited)[kMaxStreams], int* rr) {
     uint64_t need[kMaxStreams] = {0, 0, 0, 0, 0, 0, 0, 0};
     for (const Access& a : acc) {
@@ -129,10 +131,10 @@ static TaskPlan plan_task(const std::vector<Access>& acc, int ns, bool serial, c
             const TileDep& d = a.first[i];
             if (d.w_stream >= 0) need[d.w_stream] = std::max(need[d.w_stream], d.w_seq);
             if (a.mode & kWrite)
-                for (int s = 0; s < ns; s++) need[s] = std::max(need[s], d.r_seq[s]);
+                for (int s = 0; s < ns_all; s++) need[s] = std::max(need[s], d.r_seq[s]);
         }
     }
-    for (int s = 0; s < ns; s++)
+    for (int s = 0; s < ns_all; s++)
         if (need[s] <= synced_seq[s]) need[s] = 0;
 
     // Stream choice: stay behind a producer whose task is the tail of its stream
@@ -152,7 +154,7 @@ static TaskPlan plan_task(const std::vector<Access>& acc, int ns, bool serial, c
         }
     }
     plan.chosen = chosen;
-    for (int s = 0; s < ns; s++) {
+    for (int s = 0; s < ns_all; s++) {
         if (s == chosen || !need[s]) continue;
         if (waited[chosen][s] >= need[s]) continue;      // an earlier task of this stream already waited that far
         plan.wait_seq[s] = need[s];
@@ -183,10 +185,10 @@ int32_t submit(nnt_ctx* ctx, const std::vector<Access>& acc,
     // While a capture is open only streams 0 and 1 take tasks: ending a capture in which two forked
     // streams wait on each other's events has crashed inside the HIP runtime on this ROCm release.
     const int ns = ctx->capturing ? std::min(ctx->n_streams, 2) : ctx->n_streams;
-    const TaskPlan plan = plan_task(acc, ns, ctx->serial, ctx->tail_seq, ctx->synced_seq, ctx->waited, &ctx->rr);
+    const TaskPlan plan = plan_task(acc, ns, ctx->n_streams, ctx->serial, ctx->tail_seq, ctx->synced_seq, ctx->waited, &ctx->rr);
     const int chosen = plan.chosen;
     hipStream_t st = ctx->streams[chosen];
-    for (int s = 0; s < ns; s++) {
+    for (int s = 0; s < ctx->n_streams; s++) {
         if (!plan.wait_seq[s]) continue;
         // the task waited for is consumed across streams: from now on its like gets an event of its own
         const uint64_t rel = plan.wait_seq[s] - ctx->synced_seq[s] - 1;
@@ -297,7 +299,7 @@ int32_t nnt_sched_simulate(int32_t n_streams, int32_t serial, int32_t n_tiles, i
             if (acc_tile[i] < 0 || acc_tile[i] >= n_tiles || acc_mode[i] < kRead || acc_mode[i] > kReadWrite) return NNT_EINVAL;
             acc.push_back(Access{&tiles[(size_t)acc_tile[i]], 1, acc_mode[i]});
         }
-        const TaskPlan plan = plan_task(acc, n_streams, serial != 0, tail, synced, waited, &rr);
+        const TaskPlan plan = plan_task(acc, n_streams, n_streams, serial != 0, tail, synced, waited, &rr);
         // the waits as the executor would issue them: on the first recorded event that covers the
         // task asked for, else on a new one at the tail of that stream
         for (int s = 0; s < kMaxStreams; s++) {

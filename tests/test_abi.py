@@ -116,6 +116,36 @@ def test_block_slot_table_host_only(capi):
     assert used == capi.NNT_BLK_NSLOTS - 4
 
 
+def test_model_slot_table_host_only(capi):
+    """Type, shape and tiling of a language model's own tensors, as the library describes them."""
+    import workload
+    cfg = workload.CONFIGS[3]
+    bt = workload.base_tiles(cfg)
+    c = capi.nnt_gpt2_block_cfg(cfg.N_e, cfg.N_h, cfg.N_m, cfg.N_s, cfg.N_b, bt["e"], bt["m"], bt["s"], bt["b"], bt["j"], bt["i"],
+                                capi.NNT_BF16, capi.NNT_GELU_TANH, 1e-5, 1)
+    info = capi.nnt_slot_info()
+    N_v, tv = 50304, 8192
+    capi.nnt_gpt2_model_slot(C.byref(c), N_v, tv, capi.NNT_MDL_WTE, C.byref(info))
+    assert info.used and info.dtype == capi.NNT_F32 and list(info.shape)[:2] == [1024, N_v] and list(info.basetile)[:2] == [512, tv]
+    capi.nnt_gpt2_model_slot(C.byref(c), N_v, tv, capi.NNT_MDL_LOWP + capi.NNT_MDL_WPE, C.byref(info))
+    assert info.used and info.dtype == capi.NNT_BF16 and list(info.shape)[:2] == [1024, 1024] and list(info.basetile)[:2] == [512, 512]
+    capi.nnt_gpt2_model_slot(C.byref(c), N_v, tv, capi.NNT_MDL_GRAD + capi.NNT_MDL_GAMMA_F, C.byref(info))
+    assert info.dtype == capi.NNT_F32 and info.ndim == 1 and info.shape[0] == 1024
+    capi.nnt_gpt2_model_slot(C.byref(c), N_v, tv, capi.NNT_MDL_LOGITS, C.byref(info))
+    assert info.dtype == capi.NNT_BF16 and list(info.shape)[:3] == [N_v, 1024, 16] and list(info.basetile)[:3] == [tv, 512, 16]
+    capi.nnt_gpt2_model_slot(C.byref(c), N_v, tv, capi.NNT_MDL_LOSS_STATS, C.byref(info))
+    assert info.dtype == capi.NNT_F32 and list(info.shape)[:3] == [2, 1024, 16]
+    c.dtype = capi.NNT_F32
+    capi.nnt_gpt2_model_slot(C.byref(c), N_v, tv, capi.NNT_MDL_LOWP, C.byref(info))
+    assert not info.used                                                  # fp32 models keep no bf16 copies
+    assert capi.nnt_gpt2_model_slot.raw(C.byref(c), 0, tv, 0, C.byref(info)) == capi.NNT_EINVAL
+    assert capi.nnt_gpt2_model_slot.raw(C.byref(c), N_v, tv, capi.NNT_MDL_NSLOTS, C.byref(info)) == capi.NNT_EINVAL
+    assert capi.nnt_gpt2_model_forward.raw(None, None, None, None, None, None) == capi.NNT_EINVAL
+    assert capi.nnt_probe_mfma_rate.raw(None, 5, 0, 1, 1, None, None) == capi.NNT_EDTYPE
+    assert capi.nnt_probe_mfma_rate.raw(None, 0, 0, 0, 1, None, None) == capi.NNT_EINVAL
+    assert capi.nnt_tile_bias_grad_static.raw(None, 0, 1 << 20, 1 << 20, None, None, 0) == capi.NNT_EINVAL
+
+
 def test_build_guard_finds_scratch_only_inside_loops():
     """The build refuses direct-load kernels that touch scratch memory inside a loop: their
     fragment registers are filled by LDS reads that are waited for later by hand."""

@@ -226,6 +226,33 @@ def test_gemm_long_contraction_few_tiles(mods, dtype, dout, form):
         assert e <= TOL[dout], (form, e)
 
 
+def test_device_memory_of_the_library_is_reported(mods):
+    """nnt_ctx_stats: tile-pointer tables and plan tables count as table bytes, the fp32 workspace of a
+    product cut into k-slices as workspace bytes; both shrink again when the tensors go."""
+    capi, tiled = mods
+    with tiled.Context(n_streams=1) as ctx:
+        base = ctx.stats()
+        assert base["device_table_bytes"] == 0 and base["device_workspace_bytes"] == 0
+        A = tiled.TiledTensor(ctx, "f32", (256, 8192), (256, 2048))          # dW-like: few output tiles, long contraction
+        B = tiled.TiledTensor(ctx, "f32", (256, 8192), (256, 2048))
+        Cc = tiled.TiledTensor(ctx, "f32", (256, 256), (256, 256))
+        for t in (A, B):
+            for k in range(len(t.tile_index)):
+                t.tile_view(k).normal_()
+        one = ctx.stats()
+        assert one["device_table_bytes"] == (4 + 4 + 1) * 8                   # one pointer per tile
+        capi.nnt_gemm(ctx.h, 1.0, 0, A.h, 1, B.h, 0.0, Cc.h, 1, 0, None)
+        ctx.wait()
+        two = ctx.stats()
+        assert two["plans"] == 1 and two["device_table_bytes"] > one["device_table_bytes"]
+        assert two["device_workspace_bytes"] >= 2 * 128 * 128 * 4             # at least two slices of one macro-tile
+        assert two["device_workspace_bytes"] <= 2 << 30
+        assert relerr(Cc.download(), D.matmul2d(1.0, "N", A.download(), "T", B.download(), 0.0, None)) <= 1e-5
+        Cc.close()                                                            # drops the plan and its workspace
+        three = ctx.stats()
+        assert three["plans"] == 0 and three["device_workspace_bytes"] == 0 and three["device_table_bytes"] == 8 * 8
+
+
 def test_gemm_rejects_mismatched_tilings(mods):
     capi, tiled = mods
     with tiled.Context(n_streams=1) as ctx:
