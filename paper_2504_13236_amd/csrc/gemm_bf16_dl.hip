@@ -501,7 +501,11 @@ __device__ __forceinline__ void dl_body(const GemmArgs& g, char* lds) {
             }
         }
         // nothing may still be on its way into LDS or into fragment registers when the results are staged
-        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+        // (the fragment registers are named once more behind the wait, so that none of them is handed to
+        // another value while the last, unused reads are still filling them)
+        wait_frags(0);
+        wait_frags(1);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         asm volatile("s_barrier" ::: "memory");
     }
 
