@@ -330,6 +330,14 @@ NNT_API int32_t nnt_tile_sgd(void* stream, int64_t n, double lr, double momentum
 NNT_API int32_t nnt_gemm(nnt_ctx* ctx, float alpha, int32_t opA, nnt_tensor* A, int32_t opB, nnt_tensor* B,
                  float beta, nnt_tensor* C, int32_t n_contract_axes, int32_t n_batch_axes,
                  nnt_tensor* bias);
+/* The same product with the beta term taken from a second tensor: C = alpha * op(A) * op(B) +.
+ * bias + beta * R (section 3: a linear layer whose result is added to the layer's input, as
+ * the residual connections of a transformer block do), in one pass over C.  R has C's type,
+ * shape and tiling and a tile wherever C has one; it is only read.  R = NULL or R = C is
+ * nnt_gemm. */
+NNT_API int32_t nnt_gemm_res(nnt_ctx* ctx, float alpha, int32_t opA, nnt_tensor* A, int32_t opB, nnt_tensor* B,
+                     float beta, nnt_tensor* C, int32_t n_contract_axes, int32_t n_batch_axes, nnt_tensor* bias,
+                     nnt_tensor* R);
 
 NNT_API int32_t nnt_fill(nnt_ctx* ctx, float value, nnt_tensor* X);
 NNT_API int32_t nnt_add(nnt_ctx* ctx, float alpha, nnt_tensor* X, float beta, nnt_tensor* Y);

@@ -179,13 +179,16 @@ int32_t nnt_gpt2_block_destroy(nnt_gpt2_block* blk) {
 
 static nnt_tensor* weight(nnt_gpt2_block* b, int p) { return b->cfg.dtype == NNT_BF16 ? b->s[NNT_BLK_LOWP + p] : b->s[p]; }
 
-// Y = W X +. bias: the bias rides in the product's epilogue when one launch covers
-// the whole operation, and is its own tile task otherwise.
-static int32_t linear(nnt_gpt2_block* b, nnt_tensor* W, nnt_tensor* X, nnt_tensor* bias, nnt_tensor* Y) {
+// Y = W X +. bias (+ R, the input of a residual connection): bias and residual ride in the
+// product's epilogue when one launch covers the whole operation, and are tile tasks of their
+// own otherwise.
+static int32_t linear(nnt_gpt2_block* b, nnt_tensor* W, nnt_tensor* X, nnt_tensor* bias, nnt_tensor* Y, nnt_tensor* R = nullptr) {
     nnt_ctx* ctx = b->ctx;
-    if (ctx->granularity == NNT_GRAN_OP) return nnt_gemm(ctx, 1.f, NNT_OP_N, W, NNT_OP_N, X, 0.f, Y, 1, 0, bias);
+    if (ctx->granularity == NNT_GRAN_OP)
+        return nnt_gemm_res(ctx, 1.f, NNT_OP_N, W, NNT_OP_N, X, R ? 1.f : 0.f, Y, 1, 0, bias, R);
     TRY(nnt_gemm(ctx, 1.f, NNT_OP_N, W, NNT_OP_N, X, 0.f, Y, 1, 0, nullptr));
-    return nnt_bias_add(ctx, bias, Y);
+    TRY(nnt_bias_add(ctx, bias, Y));
+    return R ? nnt_add(ctx, 1.f, R, 1.f, Y) : NNT_OK;
 }
 
 // dX = W^T dY,  dW = sum_{s,b} dY X^T,  db = sum_{s,b} dY
@@ -221,13 +224,11 @@ int32_t nnt_gpt2_block_forward(nnt_gpt2_block* b, nnt_tensor* X, nnt_tensor* Out
     }
     nnt_tensor* bh[1] = {s[NNT_BLK_BH]};
     TRY(nnt_head_merge(ctx, 1, bh, s[NNT_BLK_BM]));
-    TRY(linear(b, weight(b, NNT_BLK_W_O), s[NNT_BLK_BM], s[NNT_BLK_B_O], s[NNT_BLK_X2]));
-    TRY(nnt_add(ctx, 1.f, X, 1.f, s[NNT_BLK_X2]));
+    TRY(linear(b, weight(b, NNT_BLK_W_O), s[NNT_BLK_BM], s[NNT_BLK_B_O], s[NNT_BLK_X2], X));      // X2 = X + W_o Bm +. b_o
     TRY(nnt_layernorm_fwd(ctx, s[NNT_BLK_X2], s[NNT_BLK_GAMMA2], s[NNT_BLK_BETA2], c.eps, s[NNT_BLK_X3], s[NNT_BLK_STATS2]));
     TRY(linear(b, weight(b, NNT_BLK_W_1), s[NNT_BLK_X3], s[NNT_BLK_B_1], s[NNT_BLK_H1]));
     TRY(nnt_gelu(ctx, c.gelu_variant, s[NNT_BLK_H1], s[NNT_BLK_G]));
-    TRY(linear(b, weight(b, NNT_BLK_W_2), s[NNT_BLK_G], s[NNT_BLK_B_2], Out));
-    return nnt_add(ctx, 1.f, s[NNT_BLK_X2], 1.f, Out);
+    return linear(b, weight(b, NNT_BLK_W_2), s[NNT_BLK_G], s[NNT_BLK_B_2], Out, s[NNT_BLK_X2]);   // Out = X2 + W_2 G +. b_2
 }
 
 int32_t nnt_gpt2_block_backward(nnt_gpt2_block* b, nnt_tensor* dOut, nnt_tensor* dX) {

@@ -18,6 +18,7 @@ struct SplitReduce {
     const float* ws;        // slice s of element (i, j) of the macro-tile at ws[s * slice + j * ldw + i]
     int64_t ldc, slice;
     int32_t m0, n0, rows, cols, ldw, nsplit;
+    int64_t cin_off;        // the beta term is read at C + cin_off elements (0: C itself; else a residual input's tile)
 };
 
 template <typename TO>
@@ -48,7 +49,7 @@ __global__ void __launch_bounds__(256) splitk_reduce(const SplitReduce* tab, flo
     TO* c = static_cast<TO*>(t.C) + (t.m0 + i) + (int64_t)(t.n0 + j) * t.ldc;
     if constexpr (sizeof(TO) == 4) {
         // four whole rows at a 16-byte aligned address: one vector access instead of four
-        if (n == 4 && (reinterpret_cast<uintptr_t>(c) & 15) == 0) {
+        if (n == 4 && (reinterpret_cast<uintptr_t>(c) & 15) == 0 && (t.cin_off & 3) == 0) {
             float4 o = make_float4(alpha * acc[0], alpha * acc[1], alpha * acc[2], alpha * acc[3]);
             if (t.bias) {
                 const float* bp = t.bias + t.m0 + i;
@@ -56,18 +57,18 @@ __global__ void __launch_bounds__(256) splitk_reduce(const SplitReduce* tab, flo
             }
             float4* c4 = reinterpret_cast<float4*>(c);
             if (beta != 0.f) {
-                const float4 old = *c4;
+                const float4 old = *reinterpret_cast<const float4*>(c + t.cin_off);
                 o.x += beta * old.x; o.y += beta * old.y; o.z += beta * old.z; o.w += beta * old.w;
             }
             *c4 = o;
             return;
         }
     } else {
-        if (n == 4 && (reinterpret_cast<uintptr_t>(c) & 7) == 0) {
+        if (n == 4 && (reinterpret_cast<uintptr_t>(c) & 7) == 0 && (t.cin_off & 3) == 0) {
             float o[4];
             uint2* c2 = reinterpret_cast<uint2*>(c);
             uint2 old = make_uint2(0u, 0u);
-            if (beta != 0.f) old = *c2;
+            if (beta != 0.f) old = *reinterpret_cast<const uint2*>(c + t.cin_off);
             const uint32_t ow[2] = {old.x, old.y};
 #pragma unroll
             for (int jj = 0; jj < 4; jj++) {
@@ -89,8 +90,8 @@ __global__ void __launch_bounds__(256) splitk_reduce(const SplitReduce* tab, flo
         float v = alpha * acc[jj];
         if (t.bias) v += t.bias[t.m0 + i + jj];
         if (beta != 0.f) {
-            if constexpr (sizeof(TO) == 4) v += beta * (float)c[jj];
-            else v += beta * __uint_as_float((uint32_t)c[jj] << 16);
+            if constexpr (sizeof(TO) == 4) v += beta * (float)c[t.cin_off + jj];
+            else v += beta * __uint_as_float((uint32_t)c[t.cin_off + jj] << 16);
         }
         if constexpr (sizeof(TO) == 4) c[jj] = v;
         else { const __bf16 h = (__bf16)v; c[jj] = __builtin_bit_cast(uint16_t, h); }
@@ -99,7 +100,7 @@ __global__ void __launch_bounds__(256) splitk_reduce(const SplitReduce* tab, flo
 
 struct GemmPlan {
     nnt_ctx* ctx = nullptr;
-    uint64_t ids[4] = {0, 0, 0, 0};            // tensors the tables point into (A, B, C, bias)
+    uint64_t ids[5] = {0, 0, 0, 0, 0};         // tensors the tables point into (A, B, C, bias, residual input)
     int dtype_in = NNT_F32, dtype_out = NNT_F32;
     int akf = 0, bkf = 0, cfg = kCfgSquare;
     double flops = 0.0;                        // 2 m n k summed over tasks, chunks and batch members
@@ -159,7 +160,7 @@ void plan_device_bytes(nnt_ctx* ctx, int64_t* tables, int64_t* workspaces) {
 void drop_plans_of(nnt_ctx* ctx, uint64_t id) {
     for (auto it = ctx->gemm_plans.begin(); it != ctx->gemm_plans.end();) {
         const uint64_t* ids = it->second->ids;
-        if (ids[0] == id || ids[1] == id || ids[2] == id || ids[3] == id) it = ctx->gemm_plans.erase(it);
+        if (ids[0] == id || ids[1] == id || ids[2] == id || ids[3] == id || ids[4] == id) it = ctx->gemm_plans.erase(it);
         else ++it;
     }
 }
@@ -431,7 +432,7 @@ SplitReduce add_slice_tasks(GemmPlan* P, const GemmTask& t0, const GemmWg& mw, c
     const int S = (int)ranges.size();
     const int64_t slice = (int64_t)bm * bn;
     SplitReduce r;
-    r.C = t0.C; r.bias = t0.bias; r.ws = block; r.ldc = t0.ldc; r.slice = slice;
+    r.C = t0.C; r.bias = t0.bias; r.ws = block; r.ldc = t0.ldc; r.slice = slice; r.cin_off = t0.cin_off;
     r.m0 = mw.m0; r.n0 = mw.n0;
     r.rows = std::min<int32_t>(bm, t0.m - mw.m0);
     r.cols = std::min<int32_t>(bn, t0.n - mw.n0);
@@ -443,6 +444,7 @@ SplitReduce add_slice_tasks(GemmPlan* P, const GemmTask& t0, const GemmWg& mw, c
         t.ldc = bm;
         t.strideC = 0;
         t.bias = nullptr;
+        t.cin_off = 0;
         t.partial = 1;
         t.chunk0 = ranges[sidx].first;
         t.nchunk = ranges[sidx].second;
@@ -453,7 +455,7 @@ SplitReduce add_slice_tasks(GemmPlan* P, const GemmTask& t0, const GemmWg& mw, c
 }
 
 int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B, nnt_tensor* C, int ncon, int nbat,
-                   nnt_tensor* bias, GemmPlan* P) {
+                   nnt_tensor* bias, nnt_tensor* R, GemmPlan* P) {
     const int na = A->ndim - nbat, nb = B->ndim - nbat;
     if (ncon < 1 || nbat < 0 || na < ncon || nb < ncon)
         return fail(ctx, NNT_EINVAL, "nnt_gemm: axis counts do not fit the operands");
@@ -488,7 +490,7 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
     }
 
     P->ctx = ctx;
-    P->ids[0] = A->id; P->ids[1] = B->id; P->ids[2] = C->id; P->ids[3] = bias ? bias->id : 0;
+    P->ids[0] = A->id; P->ids[1] = B->id; P->ids[2] = C->id; P->ids[3] = bias ? bias->id : 0; P->ids[4] = R ? R->id : 0;
     P->dtype_in = A->dtype;
     P->dtype_out = C->dtype;
     P->akf = opA == NNT_OP_T;
@@ -516,6 +518,12 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
         t.C = C->tiles[ci];
         t.bias = bias ? static_cast<const float*>(bias->tiles[cc[0]]) : nullptr;
         if (bias && !t.bias) return fail(ctx, NNT_EINVAL, "nnt_gemm: bias tile missing");
+        if (R) {
+            // the beta term of this tile comes from the residual input's tile: same geometry, so one offset does
+            const ptrdiff_t delta = static_cast<const char*>(R->tiles[ci]) - static_cast<const char*>(C->tiles[ci]);
+            if (delta % (ptrdiff_t)C->elem_size() != 0) return fail(ctx, NNT_EINVAL, "nnt_gemm_res: residual tile not aligned to the element size");
+            t.cin_off = delta / (ptrdiff_t)C->elem_size();
+        }
         t.ldc = m;
         t.strideC = m * n;
         t.m = (int32_t)m;
@@ -806,18 +814,31 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
 
 extern "C" int32_t nnt_gemm(nnt_ctx* ctx, float alpha, int32_t opA, nnt_tensor* A, int32_t opB, nnt_tensor* B,
                             float beta, nnt_tensor* C, int32_t ncon, int32_t nbat, nnt_tensor* bias) {
+    return nnt_gemm_res(ctx, alpha, opA, A, opB, B, beta, C, ncon, nbat, bias, nullptr);
+}
+
+extern "C" int32_t nnt_gemm_res(nnt_ctx* ctx, float alpha, int32_t opA, nnt_tensor* A, int32_t opB, nnt_tensor* B,
+                                float beta, nnt_tensor* C, int32_t ncon, int32_t nbat, nnt_tensor* bias, nnt_tensor* R) {
     NNT_CHECK_CTX(ctx);
     if (!A || !B || !C) return fail(ctx, NNT_EINVAL, "nnt_gemm: null tensor");
     if ((opA != NNT_OP_N && opA != NNT_OP_T) || (opB != NNT_OP_N && opB != NNT_OP_T))
         return fail(ctx, NNT_EINVAL, "nnt_gemm: bad op");
+    if (R == C) R = nullptr;
+    if (R) {
+        if (R->dtype != C->dtype || !same_tiling(R, C)) return fail(ctx, NNT_EINVAL, "nnt_gemm_res: the residual input must have C's type, shape and tiling");
+        for (int64_t t = 0; t < C->ntiles; t++)
+            if (C->tiles[t] && !R->tiles[t]) return fail(ctx, NNT_EINVAL, "nnt_gemm_res: the residual input lacks a tile that C has");
+        if (R == A || R == B) return fail(ctx, NNT_EINVAL, "nnt_gemm_res: the residual input must not be an operand");
+    }
     std::ostringstream key;
-    key << opA << opB << ':' << A->id << ':' << B->id << ':' << C->id << ':' << (bias ? bias->id : 0) << ':' << ncon << ':' << nbat;
+    key << opA << opB << ':' << A->id << ':' << B->id << ':' << C->id << ':' << (bias ? bias->id : 0) << ':' << ncon << ':' << nbat
+        << ':' << (R ? R->id : 0);
     GemmPlan* P;
     auto it = ctx->gemm_plans.find(key.str());
     if (it == ctx->gemm_plans.end()) {
         if (ctx->capturing) return fail(ctx, NNT_ESTATE, "nnt_gemm: plan must exist before capture (run the call once first)");
         std::shared_ptr<GemmPlan> np(new GemmPlan());
-        int32_t rc = build_plan(ctx, opA, A, opB, B, C, ncon, nbat, bias, np.get());
+        int32_t rc = build_plan(ctx, opA, A, opB, B, C, ncon, nbat, bias, R, np.get());
         if (rc != NNT_OK) return rc;
         P = np.get();
         ctx->gemm_plans[key.str()] = np;
@@ -832,8 +853,9 @@ extern "C" int32_t nnt_gemm(nnt_ctx* ctx, float alpha, int32_t opA, nnt_tensor* 
     g.beta = beta;
     const int cmode = beta != 0.f ? kReadWrite : kWrite;
     if (ctx->granularity == NNT_GRAN_OP) {
-        std::vector<Access> acc = {A->all(kRead), B->all(kRead), C->all(cmode)};
+        std::vector<Access> acc = {A->all(kRead), B->all(kRead), C->all(R ? kWrite : cmode)};
         if (bias) acc.push_back(bias->all(kRead));
+        if (R && beta != 0.f) acc.push_back(R->all(kRead));
         g.wgs = P->d_wgs_op;
         const int64_t nwg = P->op_nwg;
         if (nwg == 0) return NNT_OK;
@@ -857,7 +879,8 @@ extern "C" int32_t nnt_gemm(nnt_ctx* ctx, float alpha, int32_t opA, nnt_tensor* 
     const size_t n_tile_tasks = P->task_ctile.size();
     for (size_t ti = 0; ti < n_tile_tasks; ti++) {
         std::vector<Access> acc;
-        acc.push_back(C->one(P->task_ctile[ti], cmode));
+        acc.push_back(C->one(P->task_ctile[ti], R ? kWrite : cmode));
+        if (R && beta != 0.f) acc.push_back(R->one(P->task_ctile[ti], kRead));
         for (int64_t a : P->task_atiles[ti]) acc.push_back(A->one(a, kRead));
         for (int64_t b : P->task_btiles[ti]) acc.push_back(B->one(b, kRead));
         if (bias) acc.push_back(bias->one(P->task_bias_tile[ti], kRead));

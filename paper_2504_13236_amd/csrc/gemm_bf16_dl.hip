@@ -516,7 +516,7 @@ __device__ __forceinline__ void dl_body(const GemmArgs& g, char* lds) {
                                     1.f, 0.f, m_base, n_base, task.m, task.n, lane);
     } else {
         write_tile<TO, WMB, WNB>(stage, acc, static_cast<TO*>(task.C) + (int64_t)bat * task.strideC, task.ldc, task.bias,
-                                 g.alpha, g.beta, m_base, n_base, task.m, task.n, lane);
+                                 g.alpha, g.beta, m_base, n_base, task.m, task.n, lane, task.cin_off);
     }
 }
 

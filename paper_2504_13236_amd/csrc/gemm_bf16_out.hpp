@@ -28,20 +28,21 @@ __device__ __forceinline__ float load_out(const uint16_t* p) { return __uint_as_
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-// Writes one wave's (32 WMB) x (32 WNB) block of C = alpha * acc + bias + beta * C.  `stage` is
+// Writes one wave's (32 WMB) x (32 WNB) block of C = alpha * acc + bias + beta * C[+ cin_off].  `stage` is
 // 32 rows of 32 WMB + 4 floats of LDS owned by the wave; every wave of the workgroup must call
 // this (it synchronises the workgroup between the passes).  Vector stores need a 16-byte
 // aligned tile and leading dimension; anything else, and the ragged edge, goes element by element.
 template <typename TO, int WMB, int WNB>
 __device__ __forceinline__ void write_tile(float* stage, const f32x16 (&acc)[WNB][WMB], TO* C, int64_t ldc,
                                            const float* bias, float alpha, float beta, int m_base, int n_base,
-                                           int m_lim, int n_lim, int lane) {
+                                           int m_lim, int n_lim, int lane, int64_t cin_off = 0) {
     constexpr int MW = 32 * WMB, ROW = MW + 4;
     constexpr int V = 16 / (int)sizeof(TO);          // elements per 16-byte store
     constexpr int CH = MW / V, RPI = 64 / CH;        // vectors per row, rows per pass of the wave
     static_assert(CH <= 64 && 32 % RPI == 0, "row shape");
     const int r32 = lane & 31, half = lane >> 5;
-    const bool vec_ok = (reinterpret_cast<uintptr_t>(C) % 16 == 0) && (ldc % V == 0);
+    // (the beta term comes from C + cin_off: the tile itself, or the tile of a residual input with the same geometry)
+    const bool vec_ok = (reinterpret_cast<uintptr_t>(C) % 16 == 0) && (ldc % V == 0) && (cin_off % V == 0);
 #pragma unroll
     for (int bn = 0; bn < WNB; bn++) {
 #pragma unroll
@@ -78,14 +79,14 @@ __device__ __forceinline__ void write_tile(float* stage, const f32x16 (&acc)[WNB
                     }
                     if constexpr (sizeof(TO) == 4) {
                         if (beta != 0.f) {
-                            const f32x4 c = *reinterpret_cast<const f32x4*>(p);
+                            const f32x4 c = *reinterpret_cast<const f32x4*>(p + cin_off);
                             v[0] += beta * c[0]; v[1] += beta * c[1]; v[2] += beta * c[2]; v[3] += beta * c[3];
                         }
                         f32x4 o = {v[0], v[1], v[2], v[3]};
                         *reinterpret_cast<f32x4*>(p) = o;
                     } else {
                         if (beta != 0.f) {
-                            const uint4 c = *reinterpret_cast<const uint4*>(p);
+                            const uint4 c = *reinterpret_cast<const uint4*>(p + cin_off);
                             const uint32_t w[4] = {c.x, c.y, c.z, c.w};
 #pragma unroll
                             for (int j = 0; j < 4; j++) {
@@ -106,7 +107,7 @@ __device__ __forceinline__ void write_tile(float* stage, const f32x16 (&acc)[WNB
                     for (int j = 0; j < V; j++) {
                         if (gm + j < m_lim) {
                             float x = v[j] + (bias ? bias[gm + j] : 0.f);
-                            if (beta != 0.f) x += beta * load_out(p + j);
+                            if (beta != 0.f) x += beta * load_out(p + cin_off + j);
                             store_out(p + j, x);
                         }
                     }

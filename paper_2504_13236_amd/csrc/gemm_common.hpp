@@ -20,6 +20,8 @@ struct GemmTask {
     int32_t chunk0, nchunk;
     int32_t partial;        // 1: one k-slice of a split product; C is an fp32 scratch tile that receives the raw sum
     int32_t pad;
+    int64_t cin_off;        // the beta term is read at C + cin_off (elements of C's type): 0 = from C itself, else from
+                            // the tile of a second tensor with C's geometry (a residual input)
 };
 
 struct GemmChunk {

@@ -225,7 +225,7 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(const GemmArgs g) {
                 if (gn < task.n) {
                     float* p = C + gm + (int64_t)gn * task.ldc;
                     float v = alpha * acc[bn][bm][i] + bias;
-                    if (beta != 0.f) v += beta * *p;
+                    if (beta != 0.f) v += beta * p[task.cin_off];
                     *p = v;
                 }
             }

@@ -334,7 +334,7 @@ __global__ void __launch_bounds__(256, 2) gemm_f32_dl_kernel(const GemmArgs g) {
                 const int gn = n0 + (wn * WNB + bn) * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
                 float* p = C + gm + (int64_t)gn * task.ldc;
                 float v = alpha * acc[bn][bm][i] + bias;
-                if (beta != 0.f) v += beta * *p;
+                if (beta != 0.f) v += beta * p[task.cin_off];
                 *p = v;
             }
         }

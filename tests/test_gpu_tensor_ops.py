@@ -226,6 +226,41 @@ def test_gemm_long_contraction_few_tiles(mods, dtype, dout, form):
         assert e <= TOL[dout], (form, e)
 
 
+@pytest.mark.parametrize("gran", GRANS)
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", ["ragged", "direct-load", "k-slices"])
+def test_gemm_with_a_residual_input(mods, gran, dtype, shape):
+    """Y = alpha W X +. b + beta R with R a second tensor of Y's geometry (the residual connection of a
+    block folded into the product): general kernels on ragged tiles, the direct-load kernels on whole
+    macro-tiles, and a product whose contraction is cut into k-slices (the sum kernel adds R)."""
+    capi, tiled = mods
+    r = rng(77)
+    if shape == "ragged":
+        m, n, k, tw, tx, ty = 200, 150, 136, (64, 48), (48, 40), (64, 40)
+    elif shape == "direct-load":
+        m, n, k, tw, tx, ty = 512, 512, 192, (256, 64), (64, 256), (256, 256)
+    else:
+        m, n, k, tw, tx, ty = 256, 256, 4096, (256, 1024), (1024, 256), (256, 256)
+    W = quant(r.standard_normal((m, k)) * 0.1, dtype)
+    X = quant(r.standard_normal((k, n)), dtype)
+    b = r.standard_normal(m).astype(np.float32)
+    R = quant(r.standard_normal((m, n)), dtype)
+    Y0 = quant(r.standard_normal((m, n)), dtype)                      # must not enter the result
+    want = D.contract(0.5, "N", W, "N", X, -1.5, R, 1, 0) + b.reshape(-1, 1)
+    with tiled.Context(n_streams=2, granularity=gran) as ctx:
+        tW, tX, tR, tY = T(tiled, ctx, W, tw, dtype), T(tiled, ctx, X, tx, dtype), T(tiled, ctx, R, ty, dtype), T(tiled, ctx, Y0, ty, dtype)
+        tb = T(tiled, ctx, b, ty[:1], "f32")
+        capi.nnt_gemm_res(ctx.h, 0.5, 0, tW.h, 0, tX.h, -1.5, tY.h, 1, 0, tb.h, tR.h)
+        check(tY.download(), want, dtype, "W X + b + beta R")
+        np.testing.assert_array_equal(tR.download(), np.asarray(R, np.float32))     # the residual input is only read
+        # R = NULL and R = C are the plain product with beta on C
+        capi.nnt_gemm_res(ctx.h, 0.5, 0, tW.h, 0, tX.h, 1.0, tR.h, 1, 0, None, tR.h)
+        check(tR.download(), D.contract(0.5, "N", W, "N", X, 1.0, R, 1, 0), dtype, "R = C")
+        other = tiled.TiledTensor(ctx, dtype, (m, n), (ty[0] // 2, ty[1]))
+        with pytest.raises(capi.NntError):
+            capi.nnt_gemm_res(ctx.h, 1.0, 0, tW.h, 0, tX.h, 1.0, tY.h, 1, 0, None, other.h)   # tiled differently
+
+
 def test_device_memory_of_the_library_is_reported(mods):
     """nnt_ctx_stats: tile-pointer tables and plan tables count as table bytes, the fp32 workspace of a
     product cut into k-slices as workspace bytes; both shrink again when the tensors go."""
