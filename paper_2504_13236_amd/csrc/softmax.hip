@@ -195,6 +195,145 @@ __global__ void __launch_bounds__(256) softmax_bwd_fused(TiledView P, TiledView 
     });
 }
 
+// ------------------------------------------------------------------ several columns per wavefront
+// The same two kernels for CPW consecutive columns (queries) per wavefront, for columns that fit in
+// registers.  The host only picks them when groups of CPW queries never straddle a tile (extent and base
+// tile of the query axis are multiples of CPW), so the columns of a wave share their tile pointers and
+// differ by one column pitch: the look-up of the tiles is paid once per CPW columns, and the loads of
+// all of them are in flight together.  Short columns in a narrow type (1024 bf16 keys are 2 KB) are
+// otherwise bound by that look-up and by the latency of a single round of loads.
+template <typename T, int V, int NV, int CPW>
+__global__ void __launch_bounds__(256) softmax_fwd_multi(TiledView A, TiledView S, float scale, int causal, int64_t ncols) {
+    const int lane = threadIdx.x & 63;
+    const int64_t col = ((int64_t)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6)) * CPW;
+    if (col >= ncols) return;
+    const Column c = column_of(A, col);
+    const int nk = A.shape[0];
+    const int kmax_last = causal ? min(nk, c.c1 + CPW) : nk;      // visible keys of the wave's last column
+    const float sc2 = scale * 1.4426950408889634f;
+    float cache[CPW][NV][V];
+    float mx[CPW], sum[CPW];
+#pragma unroll
+    for (int q = 0; q < CPW; q++) {
+        mx[q] = kNegInf;
+        sum[q] = 0.f;
+#pragma unroll
+        for (int i = 0; i < NV; i++)
+#pragma unroll
+            for (int k = 0; k < V; k++) cache[q][i][k] = 0.f;
+    }
+    walk_keys<V, NV>(A, lane, kmax_last, [&](int slot, int l, int e, int ext) {
+        const T* p = col_ptr<const T>(A, c, l, ext);
+        const int k0 = l * A.base[0] + e;
+#pragma unroll
+        for (int q = 0; q < CPW; q++) {
+            const int kmax = causal ? min(nk, c.c1 + q + 1) : nk;
+            const int lim = p ? kmax - k0 : 0;                     // elements [0, lim) of the vector are visible to column q
+            float x[V];
+            if (lim > 0) {
+                ldv<V>(p + (int64_t)q * ext + e, x);
+            } else {
+#pragma unroll
+                for (int k = 0; k < V; k++) x[k] = kNegInf;
+            }
+#pragma unroll
+            for (int k = 0; k < V; k++) {
+                x[k] = k < lim ? x[k] * sc2 : kNegInf;
+                mx[q] = fmaxf(mx[q], x[k]);
+                cache[q][slot][k] = x[k];
+            }
+        }
+    });
+#pragma unroll
+    for (int q = 0; q < CPW; q++) mx[q] = wave_max(mx[q]);
+    // shifted exponentials: the walk visits exactly the slots that were loaded (masked entries are -inf -> 0;
+    // slots it does not reach keep their 0)
+    walk_keys<V, NV>(A, lane, kmax_last, [&](int slot, int l, int e, int ext) {
+#pragma unroll
+        for (int q = 0; q < CPW; q++)
+#pragma unroll
+            for (int k = 0; k < V; k++) {
+                const float x = __builtin_amdgcn_exp2f(cache[q][slot][k] - mx[q]);
+                sum[q] += x;
+                cache[q][slot][k] = x;
+            }
+    });
+    float inv[CPW];
+#pragma unroll
+    for (int q = 0; q < CPW; q++) {
+        sum[q] = wave_sum(sum[q]);
+        inv[q] = 1.f / sum[q];
+    }
+    // every vector of every present tile is written: masked entries (and slots never loaded) are 0
+    walk_keys<V, NV>(A, lane, nk, [&](int slot, int l, int e, int ext) {
+        T* p = col_ptr<T>(A, c, l, ext);
+        if (!p) return;
+#pragma unroll
+        for (int q = 0; q < CPW; q++) {
+            float x[V];
+#pragma unroll
+            for (int k = 0; k < V; k++) x[k] = cache[q][slot][k] * inv[q];
+            stv<V>(p + (int64_t)q * ext + e, x);
+        }
+    });
+    if (lane < CPW) {
+        float* s = static_cast<float*>(S.tiles[c.stat_tile]) + 2 * (int64_t)(c.colidx + lane);
+        float m = mx[0], d = sum[0];
+#pragma unroll
+        for (int q = 1; q < CPW; q++)
+            if (lane == q) { m = mx[q]; d = sum[q]; }
+        s[0] = m * 0.6931471805599453f;       // back to natural units
+        s[1] = d;
+    }
+}
+
+template <typename T, int V, int NV, int CPW>
+__global__ void __launch_bounds__(256) softmax_bwd_multi(TiledView P, TiledView dP, int64_t ncols) {
+    const int lane = threadIdx.x & 63;
+    const int64_t col = ((int64_t)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6)) * CPW;
+    if (col >= ncols) return;
+    const Column c = column_of(P, col);
+    const int nk = P.shape[0];
+    float cp[CPW][NV][V], cd[CPW][NV][V];
+    float dot[CPW];
+#pragma unroll
+    for (int q = 0; q < CPW; q++) dot[q] = 0.f;
+    walk_keys<V, NV>(P, lane, nk, [&](int slot, int l, int e, int ext) {
+        const T* p = col_ptr<const T>(P, c, l, ext);
+        const T* d = col_ptr<const T>(dP, c, l, ext);
+#pragma unroll
+        for (int q = 0; q < CPW; q++) {
+            float x[V], y[V];
+            if (p) {
+                ldv<V>(p + (int64_t)q * ext + e, x);
+                ldv<V>(d + (int64_t)q * ext + e, y);
+            } else {
+#pragma unroll
+                for (int k = 0; k < V; k++) x[k] = y[k] = 0.f;
+            }
+#pragma unroll
+            for (int k = 0; k < V; k++) {
+                dot[q] += x[k] * y[k];
+                cp[q][slot][k] = x[k];
+                cd[q][slot][k] = y[k];
+            }
+        }
+    });
+#pragma unroll
+    for (int q = 0; q < CPW; q++) dot[q] = wave_sum(dot[q]);
+    walk_keys<V, NV>(P, lane, nk, [&](int slot, int l, int e, int ext) {
+        T* d = col_ptr<T>(dP, c, l, ext);
+        if (!d) return;
+#pragma unroll
+        for (int q = 0; q < CPW; q++) {
+            float y[V];
+#pragma unroll
+            for (int k = 0; k < V; k++) y[k] = cp[q][slot][k] * (cd[q][slot][k] - dot[q]);
+            stv<V>(d + (int64_t)q * ext + e, y);
+        }
+    });
+}
+
 // ------------------------------------------------------------------ tile form: one wave per column of a tk x ncol tile
 template <typename T, int V>
 __global__ void __launch_bounds__(256) softmax_stats_tile(const T* a, float* stats, int tk, int tq, int64_t ncol, int k0, int q0,
@@ -328,6 +467,26 @@ using namespace nnt;
         }                                                                                              \
     } while (0)
 
+// Columns per wavefront of the tensor-level kernels: several when the column fits a small register cache
+// and groups of that many queries never straddle a tile of the query axis; DISPATCH_MULTI launches the
+// instance for what columns_per_wave returned.
+// (The adjoint keeps two register caches per column: it takes two columns per wavefront in bf16 and stays at
+// one in fp32, where more measured slower.)
+static inline int columns_per_wave(const nnt_tensor* A, bool vec, int nv, bool adjoint) {
+    if (!vec || nv > 4 || A->ndim < 2) return 1;
+    int want;
+    if (adjoint) want = A->dtype == NNT_F32 ? 1 : 2;
+    else want = A->dtype == NNT_F32 ? 2 : (nv <= 2 ? 4 : 2);
+    return (A->shape[1] % want == 0 && A->base[1] % want == 0) ? want : 1;
+}
+#define DISPATCH_MULTI(dtype, nv, cpw, KERNEL, ...)                                                        \
+    do {                                                                                                   \
+        if ((dtype) == NNT_F32) hipLaunchKernelGGL((KERNEL<float, 4, 4, 2>), grid, block, 0, st, __VA_ARGS__);            \
+        else if ((nv) <= 2 && (cpw) == 4) hipLaunchKernelGGL((KERNEL<bf16_t, 8, 2, 4>), grid, block, 0, st, __VA_ARGS__); \
+        else if ((nv) <= 2) hipLaunchKernelGGL((KERNEL<bf16_t, 8, 2, 2>), grid, block, 0, st, __VA_ARGS__);               \
+        else hipLaunchKernelGGL((KERNEL<bf16_t, 8, 4, 2>), grid, block, 0, st, __VA_ARGS__);                             \
+    } while (0)
+
 static inline bool sm_ok(int64_t tk, int64_t tq, int64_t batch) {
     return tk >= 1 && tq >= 1 && batch >= 0 && tk <= INT32_MAX && tq <= INT32_MAX && tq * batch <= (int64_t)INT32_MAX * 4;
 }
@@ -432,9 +591,11 @@ int32_t nnt_softmax_fwd(nnt_ctx* ctx, nnt_tensor* A, nnt_tensor* stats, float sc
         const TiledView va = A->view(), vs = stats->view();
         const int64_t ncols = n_columns(A);
         if (ncols > INT32_MAX) return fail(ctx, NNT_EINVAL, "nnt_softmax_fwd: tensor too large");
+        const int cpw = columns_per_wave(A, vec, nv, false);
         return submit(ctx, {A->all(kReadWrite), stats->all(kWrite)}, [=](hipStream_t st) {
-            const dim3 grid((unsigned)((ncols + 3) / 4)), block(256);
-            DISPATCH_TVN(dtype, vec, nv, softmax_fwd_fused, va, vs, scale, (int)causal, ncols);
+            const dim3 grid((unsigned)((ncols / cpw + 3) / 4)), block(256);
+            if (cpw > 1) DISPATCH_MULTI(dtype, nv, cpw, softmax_fwd_multi, va, vs, scale, (int)causal, ncols);
+            else DISPATCH_TVN(dtype, vec, nv, softmax_fwd_fused, va, vs, scale, (int)causal, ncols);
             return hipGetLastError() == hipSuccess ? (int32_t)NNT_OK : (int32_t)NNT_EHIP;
         });
     }
@@ -490,9 +651,11 @@ int32_t nnt_softmax_bwd(nnt_ctx* ctx, nnt_tensor* P, nnt_tensor* dP) {
         const TiledView vp = P->view(), vd = dP->view();
         const int64_t ncols = n_columns(P);
         if (ncols > INT32_MAX) return fail(ctx, NNT_EINVAL, "nnt_softmax_bwd: tensor too large");
+        const int cpw = columns_per_wave(P, vec, nv, true);
         return submit(ctx, {P->all(kRead), dP->all(kReadWrite)}, [=](hipStream_t st) {
-            const dim3 grid((unsigned)((ncols + 3) / 4)), block(256);
-            DISPATCH_TVN(dtype, vec, nv, softmax_bwd_fused, vp, vd, ncols);
+            const dim3 grid((unsigned)((ncols / cpw + 3) / 4)), block(256);
+            if (cpw > 1) DISPATCH_MULTI(dtype, nv, cpw, softmax_bwd_multi, vp, vd, ncols);
+            else DISPATCH_TVN(dtype, vec, nv, softmax_bwd_fused, vp, vd, ncols);
             return hipGetLastError() == hipSuccess ? (int32_t)NNT_OK : (int32_t)NNT_EHIP;
         });
     }

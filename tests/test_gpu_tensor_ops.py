@@ -185,6 +185,41 @@ def test_gemm_direct_load_randomized_sweep_over_tile_tables(mods):
                                 (draw, dtype, dout, opA, opB, m, n, k, tm, tn, tk, alpha, beta, gran), e)
 
 
+@pytest.mark.parametrize("causal", [1, 0])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape,base", [((1024, 64, 2, 2), (512, 32, 2, 1)),      # two key tiles: four bf16 columns per wavefront
+                                        ((1000, 48, 1, 2), (400, 24, 1, 2)),      # tiles of 400 + 400 + 200: two columns per wavefront
+                                        ((256, 40, 3, 1), (256, 20, 2, 1)),       # one key tile
+                                        ((200, 30, 2, 1), (64, 15, 1, 1)),        # odd query tiles: one column per wavefront
+                                        ((96, 7, 1, 1), (40, 7, 1, 1))])
+def test_softmax_tensor_forward_backward(mods, shape, base, dtype, causal):
+    """SoftMax over the key axis of a tiled score tensor, in place, and its adjoint: probabilities, the
+    fp32 column statistics (maximum, sum of shifted exponentials) and dA against the oracle, for tilings
+    that take one, two and four columns per wavefront."""
+    capi, tiled = mods
+    r = rng(sum(shape) + causal)
+    A = quant(3.0 * r.standard_normal(shape), dtype)
+    dPn = quant(r.standard_normal(shape), dtype)
+    scale = 0.37
+    Pref, tmax, den = D.softmax_fwd(scale * A, causal=bool(causal))
+    with tiled.Context(n_streams=2) as ctx:
+        tA = T(tiled, ctx, A, base, dtype)
+        tS = tiled.TiledTensor(ctx, "f32", (2,) + shape[1:], (2,) + base[1:])
+        capi.nnt_softmax_fwd(ctx.h, tA.h, tS.h, scale, causal)
+        P = tA.download().astype(np.float64)
+        check(P, Pref, dtype, "probabilities")
+        if causal:
+            k = np.arange(shape[0])[:, None]
+            q = np.arange(shape[1])[None, :]
+            assert np.all(P[(k > q)] == 0.0), "masked probabilities must be exactly 0"
+        stats = tS.download()
+        check(stats[0], tmax, "f32", "column maximum")
+        check(stats[1], den, "f32", "sum of shifted exponentials")
+        tdP = T(tiled, ctx, dPn, base, dtype)
+        capi.nnt_softmax_bwd(ctx.h, tA.h, tdP.h)
+        check(tdP.download(), D.softmax_bwd(P, dPn), dtype, "softmax adjoint")
+
+
 @pytest.mark.parametrize("dtype,dout", [("f32", "f32"), ("bf16", "f32"), ("bf16", "bf16")])
 @pytest.mark.parametrize("form", ["dW", "dX", "fwd"])
 def test_gemm_long_contraction_few_tiles(mods, dtype, dout, form):
