@@ -22,12 +22,16 @@ namespace {
 // along axis 0, e the first row inside it and ext the tile's extent.  With NV > 0
 // the loop is fully unrolled and `slot` is a compile-time index into a per-lane
 // register cache; with NV == 0 it is a plain loop and slot is 0.
-template <int V, int NV, typename Fn>
-__device__ __forceinline__ void walk(const TiledView& v, int lane, Fn fn) {
+template <int V, int NV, int WPT = 1, typename Fn>
+__device__ __forceinline__ void walk(const TiledView& v, int lane, Fn fn, int w = 0) {
     const int g0 = v.grid[0];
     if constexpr (NV > 0) {
         const int vpt = (v.base[0] + 64 * V - 1) / (64 * V);
         int l = 0, j = 0;                 // slot it is vector j of tile l (counted up: no division per slot)
+        if constexpr (WPT > 1) {          // wave w of the WPT that share the column takes every WPT-th vector
+            l = w / vpt;
+            j = w - l * vpt;
+        }
 #pragma unroll
         for (int it = 0; it < NV; it++) {
             if (l < g0) {
@@ -35,24 +39,51 @@ __device__ __forceinline__ void walk(const TiledView& v, int lane, Fn fn) {
                 const int e = (j * 64 + lane) * V;
                 if (e < ext) fn(it, l, e, ext);
             }
-            if (++j == vpt) {
-                j = 0;
-                l++;
+            if constexpr (WPT == 1) {
+                if (++j == vpt) {
+                    j = 0;
+                    l++;
+                }
+            } else {
+                j += WPT;
+                while (j >= vpt) {
+                    j -= vpt;
+                    l++;
+                }
             }
         }
     } else {
         for (int l = 0; l < g0; l++) {
             const int ext = ext0_of(v, l);
-            for (int e = lane * V; e < ext; e += 64 * V) fn(0, l, e, ext);
+            for (int e = (w * 64 + lane) * V; e < ext; e += 64 * V * WPT) fn(0, l, e, ext);
         }
     }
 }
 
-template <typename T, int V, int NV>
+// Sum over the WPT wavefronts that share a column (all of one workgroup), in wave order.
+template <int WPT>
+__device__ __forceinline__ float column_sum(float x, float* red, int w, int lane) {
+    x = wave_sum(x);
+    if constexpr (WPT == 1) return x;
+    if (lane == 0) red[w] = x;
+    __syncthreads();
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < WPT; i++) s += red[i];
+    __syncthreads();
+    return s;
+}
+
+// WPT = 1: one wavefront per token, four tokens per workgroup.  WPT = 4: the workgroup's four wavefronts share
+// one token (long tokens: a quarter of the registers per wave, four times the waves in flight).
+template <typename T, int V, int NV, int WPT = 1>
 __global__ void __launch_bounds__(256) ln_fwd_fused(TiledView X, TiledView Y, TiledView S, TiledView G, TiledView Bt,
                                                      float eps, int64_t ncols) {
+    __shared__ float red[4];
     const int lane = threadIdx.x & 63;
-    const int64_t col = (int64_t)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);      // wave-uniform: the index arithmetic below runs on the scalar unit
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);      // wave-uniform: the index arithmetic below runs on the scalar unit
+    const int64_t col = WPT == 1 ? (int64_t)blockIdx.x * 4 + wave : (int64_t)blockIdx.x;
+    const int w = WPT == 1 ? 0 : wave;
     if (col >= ncols) return;
     const Column c = column_of(X, col);
     const int N = X.shape[0];
@@ -61,7 +92,7 @@ __global__ void __launch_bounds__(256) ln_fwd_fused(TiledView X, TiledView Y, Ti
     // element of the token lies far from the rest).  The second pass runs over the register cache when
     // the token fits there and re-reads the token otherwise (it is still in the L2 of this wave's XCD).
     float s1 = 0.f;
-    walk<V, NV>(X, lane, [&](int slot, int l, int e, int ext) {
+    walk<V, NV, WPT>(X, lane, [&](int slot, int l, int e, int ext) {
         float x[V];
         ldv<V>(col_ptr<const T>(X, c, l, ext) + e, x);
 #pragma unroll
@@ -69,10 +100,10 @@ __global__ void __launch_bounds__(256) ln_fwd_fused(TiledView X, TiledView Y, Ti
             s1 += x[k];
             if constexpr (NV > 0) cache[slot][k] = x[k];
         }
-    });
-    const float mean = wave_sum(s1) / (float)N;
+    }, w);
+    const float mean = column_sum<WPT>(s1, red, w, lane) / (float)N;
     float s2 = 0.f;
-    walk<V, NV>(X, lane, [&](int slot, int l, int e, int ext) {
+    walk<V, NV, WPT>(X, lane, [&](int slot, int l, int e, int ext) {
         float x[V];
         if constexpr (NV > 0) {
 #pragma unroll
@@ -82,10 +113,10 @@ __global__ void __launch_bounds__(256) ln_fwd_fused(TiledView X, TiledView Y, Ti
         }
 #pragma unroll
         for (int k = 0; k < V; k++) s2 += (x[k] - mean) * (x[k] - mean);
-    });
-    const float var = wave_sum(s2) / (float)N;
+    }, w);
+    const float var = column_sum<WPT>(s2, red, w, lane) / (float)N;
     const float rstd = 1.f / sqrtf(var + eps);
-    walk<V, NV>(X, lane, [&](int slot, int l, int e, int ext) {
+    walk<V, NV, WPT>(X, lane, [&](int slot, int l, int e, int ext) {
         float x[V], g[V], b[V];
         if constexpr (NV > 0) {
 #pragma unroll
@@ -98,19 +129,22 @@ __global__ void __launch_bounds__(256) ln_fwd_fused(TiledView X, TiledView Y, Ti
 #pragma unroll
         for (int k = 0; k < V; k++) x[k] = g[k] * ((x[k] - mean) * rstd) + b[k];
         stv<V>(col_ptr<T>(Y, c, l, ext) + e, x);
-    });
-    if (lane == 0) {
+    }, w);
+    if (lane == 0 && w == 0) {
         float* s = static_cast<float*>(S.tiles[c.stat_tile]) + 2 * (int64_t)c.colidx;
         s[0] = mean;
         s[1] = rstd;
     }
 }
 
-template <typename T, int V, int NV>
+template <typename T, int V, int NV, int WPT = 1>
 __global__ void __launch_bounds__(256) ln_bwd_fused(TiledView X, TiledView S, TiledView G, TiledView dY, TiledView dR,
                                                      TiledView dX, int has_res, int64_t ncols) {
+    __shared__ float red[4];
     const int lane = threadIdx.x & 63;
-    const int64_t col = (int64_t)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);      // wave-uniform: the index arithmetic below runs on the scalar unit
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);      // wave-uniform: the index arithmetic below runs on the scalar unit
+    const int64_t col = WPT == 1 ? (int64_t)blockIdx.x * 4 + wave : (int64_t)blockIdx.x;
+    const int w = WPT == 1 ? 0 : wave;
     if (col >= ncols) return;
     const Column c = column_of(X, col);
     const int N = X.shape[0];
@@ -118,7 +152,7 @@ __global__ void __launch_bounds__(256) ln_bwd_fused(TiledView X, TiledView S, Ti
     const float mean = st[0], rstd = st[1];
     float cg[NV > 0 ? NV : 1][V], ch[NV > 0 ? NV : 1][V];   // g = dy * gamma, xhat
     float a = 0.f, b = 0.f;
-    walk<V, NV>(X, lane, [&](int slot, int l, int e, int ext) {
+    walk<V, NV, WPT>(X, lane, [&](int slot, int l, int e, int ext) {
         float x[V], d[V], g[V];
         ldv<V>(col_ptr<const T>(X, c, l, ext) + e, x);
         ldv<V>(col_ptr<const T>(dY, c, l, ext) + e, d);
@@ -130,10 +164,10 @@ __global__ void __launch_bounds__(256) ln_bwd_fused(TiledView X, TiledView S, Ti
             b += gg * xh;
             if constexpr (NV > 0) { cg[slot][k] = gg; ch[slot][k] = xh; }
         }
-    });
-    a = wave_sum(a) / (float)N;
-    b = wave_sum(b) / (float)N;
-    walk<V, NV>(X, lane, [&](int slot, int l, int e, int ext) {
+    }, w);
+    a = column_sum<WPT>(a, red, w, lane) / (float)N;
+    b = column_sum<WPT>(b, red, w, lane) / (float)N;
+    walk<V, NV, WPT>(X, lane, [&](int slot, int l, int e, int ext) {
         float gg[V], xh[V], r[V];
         if constexpr (NV > 0) {
 #pragma unroll
@@ -155,7 +189,7 @@ __global__ void __launch_bounds__(256) ln_bwd_fused(TiledView X, TiledView S, Ti
             for (int k = 0; k < V; k++) r[k] += q[k];
         }
         stv<V>(col_ptr<T>(dX, c, l, ext) + e, r);
-    });
+    }, w);
 }
 
 // ------------------------------------------------------------------ tile-form kernels (one wave per token of an m x n tile)
@@ -514,15 +548,24 @@ bool tensors_vec_ok(std::initializer_list<const nnt_tensor*> ts, int V) {
     return true;
 }
 
+// Tokens of more vectors per lane than this are shared by the four wavefronts of a workgroup (measured: shorter
+// tokens lose to the two workgroup barriers, longer ones gain from four times the loads in flight).
+constexpr int kLnShareAbove = 4;
+
 template <typename T>
 int32_t launch_ln_fwd(hipStream_t st, bool vec, int nv_needed, const TiledView& X, const TiledView& Y, const TiledView& S,
                       const TiledView& G, const TiledView& B, float eps, int64_t ncols) {
     constexpr int V = VecOf<T>::V;
-    const dim3 grid((unsigned)((ncols + 3) / 4)), block(256);
+    // tokens of more than `kLnShareAbove` vectors per lane are shared by the four wavefronts of a workgroup
+    const bool shared = vec && nv_needed > kLnShareAbove;
+    const dim3 grid((unsigned)(shared ? ncols : (ncols + 3) / 4)), block(256);
     if (!vec) hipLaunchKernelGGL((ln_fwd_fused<T, 1, 0>), grid, block, 0, st, X, Y, S, G, B, eps, ncols);
-    else if (nv_needed <= 4) hipLaunchKernelGGL((ln_fwd_fused<T, V, 4>), grid, block, 0, st, X, Y, S, G, B, eps, ncols);
-    else if (nv_needed <= 16) hipLaunchKernelGGL((ln_fwd_fused<T, V, 16>), grid, block, 0, st, X, Y, S, G, B, eps, ncols);
-    else hipLaunchKernelGGL((ln_fwd_fused<T, V, 0>), grid, block, 0, st, X, Y, S, G, B, eps, ncols);
+    else if (!shared && nv_needed <= 4) hipLaunchKernelGGL((ln_fwd_fused<T, V, 4>), grid, block, 0, st, X, Y, S, G, B, eps, ncols);
+    else if (!shared && nv_needed <= 16) hipLaunchKernelGGL((ln_fwd_fused<T, V, 16>), grid, block, 0, st, X, Y, S, G, B, eps, ncols);
+    else if (!shared) hipLaunchKernelGGL((ln_fwd_fused<T, V, 0>), grid, block, 0, st, X, Y, S, G, B, eps, ncols);
+    else if (nv_needed <= 16) hipLaunchKernelGGL((ln_fwd_fused<T, V, 4, 4>), grid, block, 0, st, X, Y, S, G, B, eps, ncols);
+    else if (nv_needed <= 64) hipLaunchKernelGGL((ln_fwd_fused<T, V, 16, 4>), grid, block, 0, st, X, Y, S, G, B, eps, ncols);
+    else hipLaunchKernelGGL((ln_fwd_fused<T, V, 0, 4>), grid, block, 0, st, X, Y, S, G, B, eps, ncols);
     return hipGetLastError() == hipSuccess ? NNT_OK : NNT_EHIP;
 }
 
@@ -530,11 +573,15 @@ template <typename T>
 int32_t launch_ln_bwd(hipStream_t st, bool vec, int nv_needed, const TiledView& X, const TiledView& S, const TiledView& G,
                       const TiledView& dY, const TiledView& dR, const TiledView& dX, int has_res, int64_t ncols) {
     constexpr int V = VecOf<T>::V;
-    const dim3 grid((unsigned)((ncols + 3) / 4)), block(256);
+    const bool shared = vec && nv_needed > kLnShareAbove;
+    const dim3 grid((unsigned)(shared ? ncols : (ncols + 3) / 4)), block(256);
     if (!vec) hipLaunchKernelGGL((ln_bwd_fused<T, 1, 0>), grid, block, 0, st, X, S, G, dY, dR, dX, has_res, ncols);
-    else if (nv_needed <= 4) hipLaunchKernelGGL((ln_bwd_fused<T, V, 4>), grid, block, 0, st, X, S, G, dY, dR, dX, has_res, ncols);
-    else if (nv_needed <= 8) hipLaunchKernelGGL((ln_bwd_fused<T, V, 8>), grid, block, 0, st, X, S, G, dY, dR, dX, has_res, ncols);
-    else hipLaunchKernelGGL((ln_bwd_fused<T, V, 0>), grid, block, 0, st, X, S, G, dY, dR, dX, has_res, ncols);
+    else if (!shared && nv_needed <= 4) hipLaunchKernelGGL((ln_bwd_fused<T, V, 4>), grid, block, 0, st, X, S, G, dY, dR, dX, has_res, ncols);
+    else if (!shared && nv_needed <= 8) hipLaunchKernelGGL((ln_bwd_fused<T, V, 8>), grid, block, 0, st, X, S, G, dY, dR, dX, has_res, ncols);
+    else if (!shared) hipLaunchKernelGGL((ln_bwd_fused<T, V, 0>), grid, block, 0, st, X, S, G, dY, dR, dX, has_res, ncols);
+    else if (nv_needed <= 16) hipLaunchKernelGGL((ln_bwd_fused<T, V, 4, 4>), grid, block, 0, st, X, S, G, dY, dR, dX, has_res, ncols);
+    else if (nv_needed <= 32) hipLaunchKernelGGL((ln_bwd_fused<T, V, 8, 4>), grid, block, 0, st, X, S, G, dY, dR, dX, has_res, ncols);
+    else hipLaunchKernelGGL((ln_bwd_fused<T, V, 0, 4>), grid, block, 0, st, X, S, G, dY, dR, dX, has_res, ncols);
     return hipGetLastError() == hipSuccess ? NNT_OK : NNT_EHIP;
 }
 

@@ -343,7 +343,9 @@ def test_gemm_rejects_mismatched_tilings(mods):
 # ------------------------------------------------------------------ memory-bound operations
 @pytest.mark.parametrize("gran", GRANS)
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("shape,base", [((768, 40, 3), (256, 16, 3)), ((100, 37, 2), (48, 10, 1)), ((1600, 12, 2), (400, 12, 2))])
+@pytest.mark.parametrize("shape,base", [((768, 40, 3), (256, 16, 3)), ((100, 37, 2), (48, 10, 1)), ((1600, 12, 2), (400, 12, 2)),
+                                        # long tokens, shared by the wavefronts of a workgroup: register-cached and looping forms
+                                        ((8192, 5, 2), (1024, 5, 1)), ((2560, 7, 1), (512, 7, 1)), ((20000, 3, 1), (5000, 3, 1))])
 def test_layernorm_tensor(mods, gran, dtype, shape, base):
     capi, tiled = mods
     r = rng(3)
