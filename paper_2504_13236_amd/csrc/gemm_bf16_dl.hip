@@ -238,6 +238,7 @@ __device__ __forceinline__ void dl_body(const GemmArgs& g, char* lds) {
     T = __builtin_amdgcn_readfirstlane(T);
 
     if (T > 0) {
+        const int chunk_first = chunk_i;
         const int chunk_end = chunk_i + __builtin_amdgcn_readfirstlane(task.nchunk);
         // Position of the next k-step to load.  A lane's loads of a step are `base + offset` with a
         // uniform base that moves on by a fixed amount per step and per-lane byte offsets that only
@@ -400,7 +401,9 @@ __device__ __forceinline__ void dl_body(const GemmArgs& g, char* lds) {
         // matrix instructions and fenced so that they stay there.
         // RAG: k that the step under the matrix instructions really has (32 except in the short last
         // step of a chunk), and a cursor over the chunk lengths on the computing side
-        int kv_now = kBK, c_rem = 0, c_chunk = chunk_i;
+        // (it starts at the task's first chunk: the loading side has already moved on, past that chunk
+        // when it is no longer than the steps the prologue starts)
+        int kv_now = kBK, c_rem = 0, c_chunk = chunk_first;
         if constexpr (RAG) {
             c_rem = table ? sload_chunk(g.chunks + c_chunk).k : g.one_chunk.k;
             kv_now = min(kBK, c_rem);

@@ -185,6 +185,60 @@ def test_gemm_direct_load_randomized_sweep_over_tile_tables(mods):
                                 (draw, dtype, dout, opA, opB, m, n, k, tm, tn, tk, alpha, beta, gran), e)
 
 
+def test_gemm_bf16_short_contracted_tiles_randomized_sweep(mods):
+    """bf16 tensor-level products whose contracted tiles are multiples of 8 but not of 32 long and often shorter
+    than the k-steps a workgroup starts before its loop (8 .. 72, several per C tile, a shorter last one), with
+    C tiles that are and are not whole macro-tiles: the table-driven launches of the direct-load kernel's
+    ragged variant, whose loading side runs ahead of the multiplying side by whole chunks here.  Every operand
+    orientation, both granularities, against the oracle's contraction; stops at the first failure."""
+    capi, tiled = mods
+    r = np.random.default_rng(250413)
+    for draw in range(40):
+        dout = ("bf16", "f32")[draw % 2]
+        tm, tn = (256, 512, 400, 328)[int(r.integers(4))], (256, 128, 400, 136)[int(r.integers(4))]
+        m, n = tm * int(r.integers(1, 3)) + 8 * int(r.integers(0, 20)), tn * int(r.integers(1, 4)) + 8 * int(r.integers(0, 12))
+        tk = 8 * int(r.choice([1, 2, 3, 5, 7, 9]))
+        k = tk * int(r.integers(2, 6)) + 8 * int(r.integers(0, tk // 8))
+        opA, opB = int(r.integers(2)), int(r.integers(2))
+        alpha, beta = ((1.0, 0.0), (0.6, -1.5))[int(r.integers(2))]
+        gran = int(r.integers(2))
+        A = quant(r.standard_normal((m, k) if opA == 0 else (k, m)), "bf16")
+        B = quant(r.standard_normal((k, n) if opB == 0 else (n, k)), "bf16")
+        C0 = quant(r.standard_normal((m, n)), dout)
+        ref = D.contract(alpha, "NT"[opA], A, "NT"[opB], B, beta, C0, 1, 0)
+        with tiled.Context(n_streams=2, granularity=gran) as ctx:
+            tA = T(tiled, ctx, A, (tm, tk) if opA == 0 else (tk, tm), "bf16")
+            tB = T(tiled, ctx, B, (tk, tn) if opB == 0 else (tn, tk), "bf16")
+            tC = T(tiled, ctx, C0, (tm, tn), dout)
+            capi.nnt_gemm(ctx.h, alpha, opA, tA.h, opB, tB.h, beta, tC.h, 1, 0, None)
+            e = relerr(tC.download(), ref)
+        assert e <= TOL[dout], ("draw %d: bf16->%s op %d%d %dx%dx%d tiles %dx%dx%d alpha %g beta %g gran %d" %
+                                (draw, dout, opA, opB, m, n, k, tm, tn, tk, alpha, beta, gran), e)
+
+
+def test_gemm_bf16_batched_products_with_ragged_sequence_tiles(mods):
+    """Score-shaped and head-row products of an attention layer whose sequence length is not a multiple of its
+    tile (1000 = 3 x 256 + 232) and whose head size is not a multiple of a k-step (72): batched launches in which
+    macro-tiles end inside their tiles and every chunk ends in a short k-step."""
+    capi, tiled = mods
+    r = rng(77)
+    h, N_s, N_b, N_h, ts = 72, 1000, 2, 8, 256        # 16 x 16 blocks of 256 x 256: enough for the 256 x 128 direct-load shape
+    Q, K, V = [quant(r.standard_normal((h, N_s, N_b, N_h)), "bf16") for _ in range(3)]
+    with tiled.Context(n_streams=2) as ctx:
+        hb, sb = (h, ts, N_b, N_h), (ts, ts, N_b, N_h)
+        tQ, tK, tV = [T(tiled, ctx, a, hb, "bf16") for a in (Q, K, V)]
+        tA = tiled.TiledTensor(ctx, "bf16", (N_s, N_s, N_b, N_h), sb)
+        capi.nnt_gemm(ctx.h, 0.25, 1, tK.h, 0, tQ.h, 0.0, tA.h, 1, 2, None)
+        Adev = tA.download().astype(np.float64)
+        check(Adev, D.contract(0.25, "T", K, "N", Q, 0.0, None, 1, 2), "bf16", "K^T Q")
+        tB = tiled.TiledTensor(ctx, "bf16", Q.shape, hb)
+        capi.nnt_gemm(ctx.h, 1.0, 0, tV.h, 0, tA.h, 0.0, tB.h, 1, 2, None)
+        check(tB.download(), D.contract(1.0, "N", V, "N", Adev, 0.0, None, 1, 2), "bf16", "V A")
+        tD = tiled.TiledTensor(ctx, "bf16", Q.shape, hb)
+        capi.nnt_gemm(ctx.h, 1.0, 0, tV.h, 1, tA.h, 0.0, tD.h, 1, 2, None)
+        check(tD.download(), D.contract(1.0, "N", V, "T", Adev, 0.0, None, 1, 2), "bf16", "V A^T")
+
+
 @pytest.mark.parametrize("causal", [1, 0])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("shape,base", [((1024, 64, 2, 2), (512, 32, 2, 1)),      # two key tiles: four bf16 columns per wavefront
