@@ -309,12 +309,16 @@ static ShapeChoice choose_shape(bool bf16, bool out_f32, int akf, int bkf, const
 }
 
 static int pick_cfg(int bf16, int64_t m_max, int64_t n_max, int64_t n_tiles_big, int64_t k_max) {
-    if (m_max <= 64) return bf16 ? kCfgSkinny64 : kCfgSkinny64n128;   // fp32: the shape its direct-load kernel has
+    // bf16 products with few rows (m = head size) read a score-shaped operand and are bound by that traffic: the
+    // 128-row direct-load shape streams it four k-steps ahead
+    if (bf16 && m_max <= 128) return kCfgWide;
+    if (m_max <= 64) return kCfgSkinny64n128;                         // (fp32 from here to the next line) the shape its direct-load kernel has
     if (m_max <= 128 && n_max > 128) return kCfgSkinny128;
     if (bf16 && (m_max <= 128 || n_max <= 128 || n_tiles_big < 256)) return kCfgMid;
     // short contractions are bound by the result stores: several small workgroups per compute
     // unit overlap one's stores with another's loads, one large workgroup cannot
-    if (bf16 && k_max <= 128) return (m_max % 256 == 0 && n_max % 128 == 0) ? kCfgTall : kCfgMid;
+    // (tiles that are not whole macro-tiles go to the ragged variant of that kernel: C4's tiles of 400 are 256 + 144 by 3 x 128 + 16)
+    if (bf16 && k_max <= 128) return (m_max >= 256 && n_max >= 128) ? kCfgTall : kCfgMid;
     return kCfgSquare;
 }
 
@@ -366,16 +370,16 @@ extern "C" int32_t nnt_tile_gemm(void* stream, int32_t dtype_in, int32_t dtype_o
         cfg = choose_shape(bf, dtype_out == NNT_F32, opA == NNT_OP_T, opB == NNT_OP_N, {m}, {n}, {k}, false, odd_shape).cfg;
     // debugging aid: NNT_TILE_GEMM_CFG=<number of a macro-tile configuration> overrides the choice for this entry point
     static const char* const force = getenv("NNT_TILE_GEMM_CFG");
-    if (force && atoi(force) >= kCfgSquare && atoi(force) <= kCfgTall) cfg = atoi(force);
+    if (force && atoi(force) >= kCfgSquare && atoi(force) <= kCfgWide) cfg = atoi(force);
     gemm_cfg_tile(bf, cfg, &bm, &bn);
     g.grid_m = (int32_t)((m + bm - 1) / bm);
     g.grid_n = (int32_t)((n + bn - 1) / bn);
     const int64_t nwg = (int64_t)g.grid_m * g.grid_n * batch;
     if (nwg > INT32_MAX) return NNT_EINVAL;
-    bool fast = (bf ? (cfg == kCfgSquare || cfg == kCfgTall) : (cfg == kCfgSquare || cfg == kCfgSkinny64n128 || cfg == kCfgMid)) && m % bm == 0 && n % bn == 0 && k > 0 &&
+    bool fast = (bf ? (cfg == kCfgSquare || cfg == kCfgTall || cfg == kCfgWide) : (cfg == kCfgSquare || cfg == kCfgSkinny64n128 || cfg == kCfgMid)) && m % bm == 0 && n % bn == 0 && k > 0 &&
                 k % ((bf && cfg == kCfgSquare) ? 64 : 32) == 0 && g.one_chunk.vec_ok == 3;
     bool ragged = false;
-    if (!fast && bf && cfg == kCfgTall && k > 0 && k % 8 == 0 && g.one_chunk.vec_ok == 3) {
+    if (!fast && bf && (cfg == kCfgTall || cfg == kCfgWide) && k > 0 && k % 8 == 0 && g.one_chunk.vec_ok == 3) {
         // the variant for macro-tiles that end inside the tile and for a short last k-step
         const bool akf = opA == NNT_OP_T, bkf = opB == NNT_OP_N;
         fast = ragged = (akf || (m % bm) % 8 == 0) && (bkf || (n % bn) % 8 == 0);
@@ -591,7 +595,7 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
     gemm_cfg_tile(bf, P->cfg, &bm, &bn);
     {
         // spelled like the demangled kernel name, so that profiler output can be matched against it
-        static const char* const shape[7] = {"2, 2, 4, 4", "2, 2, 2, 2", "1, 4, 2, 2", "1, 4, 4, 2", "1, 4, 2, 1", "2, 2, 1, 1", "2, 2, 4, 2"};
+        static const char* const shape[8] = {"2, 2, 4, 4", "2, 2, 2, 2", "1, 4, 2, 2", "1, 4, 4, 2", "1, 4, 2, 1", "2, 2, 1, 1", "2, 2, 4, 2", "2, 2, 2, 2"};
         std::ostringstream l;
         const char* tf[2] = {"false", "true"};
         if (A->dtype == NNT_F32) l << "gemm_f32_kernel<" << tf[P->akf] << ", " << tf[P->bkf] << ", " << (P->cfg == kCfgSquare ? "2, 2, 2, 2" : P->cfg == kCfgMid ? "2, 2, 1, 2" : shape[P->cfg]) << ">";
@@ -748,11 +752,11 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
 
     // workgroups that qualify for the direct-load kernel go first in every launch range
     P->task_nfast.assign(P->task_ctile.size(), 0);
-    if (bf ? (P->cfg == kCfgSquare || P->cfg == kCfgTall) : (P->cfg == kCfgSquare || P->cfg == kCfgSkinny64n128 || P->cfg == kCfgMid)) {
+    if (bf ? (P->cfg == kCfgSquare || P->cfg == kCfgTall || P->cfg == kCfgWide) : (P->cfg == kCfgSquare || P->cfg == kCfgSkinny64n128 || P->cfg == kCfgMid)) {
         const int kmul = (bf && P->cfg == kCfgSquare) ? 64 : 32;   // loads are started two k-steps at a time
         // the 256 x 128 bf16 kernel has a variant for chunk lengths that are multiples of 8 and macro-tiles that end
         // inside their C tile (at a multiple of 8 rows of an operand whose row index is the contiguous one)
-        const bool rag_ok = bf && P->cfg == kCfgTall;
+        const bool rag_ok = bf && (P->cfg == kCfgTall || P->cfg == kCfgWide);
         std::vector<char> task_ok(P->tasks.size(), 1), task_rag(P->tasks.size(), 0);
         for (size_t ti = 0; ti < P->tasks.size(); ti++)
             for (int32_t q = P->tasks[ti].chunk0; q < P->tasks[ti].chunk0 + P->tasks[ti].nchunk; q++) {
@@ -787,7 +791,8 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
             const char* tf[2] = {"false", "true"};
             std::ostringstream l;
             if (bf)
-                l << (P->cfg == kCfgTall ? "gemm_bf16_dl_tall_kernel<" : "gemm_bf16_dl_kernel<") << (C->dtype == NNT_F32 ? "float" : "unsigned short")
+                l << (P->cfg == kCfgTall ? "gemm_bf16_dl_tall_kernel<" : P->cfg == kCfgWide ? "gemm_bf16_dl_wide_kernel<" : "gemm_bf16_dl_kernel<")
+                  << (C->dtype == NNT_F32 ? "float" : "unsigned short")
                   << ", " << tf[P->akf] << ", " << tf[P->bkf] << (P->cfg == kCfgTall ? (P->dl_ragged ? ", true>" : ", false>") : ">");
             else
                 l << "gemm_f32_dl_kernel<" << tf[P->akf] << ", " << tf[P->bkf] << (P->cfg == kCfgSquare ? ", 2, 2>" : ", 1, 2>");

@@ -327,6 +327,7 @@ KernelFn kernel_of(int cfg) {
         case kCfgSkinny64n128: return gemm_bf16_kernel<TO, AKF, BKF, 1, 4, 2, 1, 32>;
         case kCfgSkinny64n64: return gemm_bf16_kernel<TO, AKF, BKF, 2, 2, 1, 1, 32>;
         case kCfgTall: return gemm_bf16_kernel<TO, AKF, BKF, 2, 2, 4, 2, 32>;
+        case kCfgWide: return gemm_bf16_kernel<TO, AKF, BKF, 2, 2, 2, 2, 32>;      // (what the direct-load kernel of the shape does not take)
         default: return gemm_bf16_kernel<TO, AKF, BKF, 1, 4, 4, 2, 32>;
     }
 }

@@ -167,10 +167,12 @@ struct FragAddr {
     __device__ __forceinline__ uint32_t at(uint32_t stage_addr) const { return stage_addr + v[KF ? KS : B]; }
 };
 
-template <int WNB>
+// WM waves along m (2: the four waves as 2 x 2, 256 rows; 1: side by side, 128 rows), each 128 rows x 32 WNB columns.
+template <int WNB, int WM = 2>
 struct DlShape {
-    static constexpr int kStages = WNB == 4 ? 5 : 3;
-    static constexpr int kStageBytes = (256 + 64 * WNB) * kBK * 2;
+    static constexpr int BM = 128 * WM, BN = 32 * WNB * (4 / WM);
+    static constexpr int kStages = (WNB == 4 || WM == 1) ? 5 : 3;
+    static constexpr int kStageBytes = (BM + BN) * kBK * 2;
     static constexpr int kLdsBytes = kStages * kStageBytes;
 };
 
@@ -178,11 +180,11 @@ struct DlShape {
 // not loaded, see load_offset_clamped; the epilogue stores nothing for them) and chunk lengths are
 // multiples of 8 instead of 32 (the last k-step of such a chunk is short: the fragments of the A
 // operand that stand for k beyond it are set to zero before the matrix instructions).
-template <typename TO, bool AKF, bool BKF, int WNB, bool RAG = false>
+template <typename TO, bool AKF, bool BKF, int WNB, bool RAG = false, int WM = 2>
 __device__ __forceinline__ void dl_body(const GemmArgs& g, char* lds) {
-    constexpr int WMB = 4, BM = 256, BN = 64 * WNB;
-    constexpr int kStages = DlShape<WNB>::kStages;
-    constexpr int kOpABytes = BM * kBK * 2, kStageBytes = DlShape<WNB>::kStageBytes;
+    constexpr int WMB = 4, BM = DlShape<WNB, WM>::BM, BN = DlShape<WNB, WM>::BN;
+    constexpr int kStages = DlShape<WNB, WM>::kStages;
+    constexpr int kOpABytes = BM * kBK * 2, kStageBytes = DlShape<WNB, WM>::kStageBytes;
     constexpr int NIA = BM / 64, NIB = BN / 64, kLoads = NIA + NIB;     // load instructions per wave and step
     constexpr int kFrags = WNB + WMB, kMfma = WNB * WMB;
 #ifndef NNT_FRAG_SPAN_NUM
@@ -191,14 +193,14 @@ __device__ __forceinline__ void dl_body(const GemmArgs& g, char* lds) {
     constexpr int kFragSpan = kMfma * NNT_FRAG_SPAN_NUM / 4;
     // The 256 x 256 shape starts its loads two k-steps at a time (see the loop below); its chunks
     // must be multiples of 64 long.
-    constexpr bool kPaired = WNB == 4;
+    constexpr bool kPaired = WNB == 4 && WM == 2;
     static_assert(!kPaired || kStages == 5, "the paired schedule needs five stages");
     static_assert(!(kPaired && RAG), "short k-steps need the schedule that starts its loads one step at a time");
     static_assert(4 * 32 * (32 * WMB + 4) * 4 <= kStages * kStageBytes, "result staging must fit the pipeline's LDS");
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave & 1, wn = wave >> 1;
+    const int wm = WM == 2 ? wave & 1 : 0, wn = WM == 2 ? wave >> 1 : wave;
 
     GemmTask task;
     int m0, n0, bat;
@@ -536,7 +538,23 @@ __global__ void __launch_bounds__(256, 2) gemm_bf16_dl_tall_kernel(const GemmArg
     dl_body<TO, AKF, BKF, 2, RAG>(g, lds);
 }
 
+// 128 x 128 macro-tiles for products with few rows (m = head size: the other operand is the score-shaped one and
+// the kernel streams it): the four waves side by side, 128 rows x 32 columns each, five stages of 16 KB so that
+// the loads of four k-steps are in flight, two workgroups per compute unit.  Always the ragged variant (m = 64
+// is half a macro-tile; sequence tiles need not be multiples of 128).
+template <typename TO, bool AKF, bool BKF>
+__global__ void __launch_bounds__(256, 2) gemm_bf16_dl_wide_kernel(const GemmArgs g) {
+    __shared__ __attribute__((aligned(16))) char lds[DlShape<1, 1>::kLdsBytes];
+    dl_body<TO, AKF, BKF, 1, true, 1>(g, lds);
+}
+
 using KernelFn = void (*)(const GemmArgs);
+
+template <typename TO>
+KernelFn wide_kernel_of(int akf, int bkf) {
+    if (akf) return bkf ? gemm_bf16_dl_wide_kernel<TO, true, true> : gemm_bf16_dl_wide_kernel<TO, true, false>;
+    return bkf ? gemm_bf16_dl_wide_kernel<TO, false, true> : gemm_bf16_dl_wide_kernel<TO, false, false>;
+}
 
 template <typename TO, bool RAG>
 KernelFn tall_kernel_of(int akf, int bkf) {
@@ -552,6 +570,7 @@ KernelFn kernel_of(int akf, int bkf, bool tall, bool ragged) {
 }
 
 KernelFn kernel_of(int out_is_f32, int akf, int bkf, int cfg, bool ragged) {
+    if (cfg == kCfgWide) return out_is_f32 ? wide_kernel_of<float>(akf, bkf) : wide_kernel_of<uint16_t>(akf, bkf);
     return out_is_f32 ? kernel_of<float>(akf, bkf, cfg == kCfgTall, ragged) : kernel_of<uint16_t>(akf, bkf, cfg == kCfgTall, ragged);
 }
 
@@ -559,7 +578,7 @@ KernelFn kernel_of(int out_is_f32, int akf, int bkf, int cfg, bool ragged) {
 
 int32_t launch_gemm_bf16_dl(hipStream_t st, int out_is_f32, int akf, int bkf, int cfg, bool ragged, const GemmArgs& g, int64_t nwg) {
     if (nwg <= 0) return NNT_OK;
-    if (ragged && cfg != kCfgTall) return NNT_EINVAL;
+    if (ragged && cfg != kCfgTall && cfg != kCfgWide) return NNT_EINVAL;
     hipLaunchKernelGGL(kernel_of(out_is_f32, akf, bkf, cfg, ragged), dim3((unsigned)nwg), dim3(256), 0, st, g);
     return hipGetLastError() == hipSuccess ? NNT_OK : NNT_EHIP;
 }

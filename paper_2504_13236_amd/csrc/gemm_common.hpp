@@ -54,7 +54,8 @@ enum GemmCfg {
     kCfgSkinny128 = 3, // 128 x 256  (head size 128)
     kCfgSkinny64n128 = 4, // 64 x 128
     kCfgSkinny64n64 = 5,  // 64 x 64   (the two narrower shapes give memory-bound products more workgroups)
-    kCfgTall = 6          // bf16 256 x 128 (two workgroups per compute unit); f32 128 x 128
+    kCfgTall = 6,         // bf16 256 x 128 (two workgroups per compute unit); f32 128 x 128
+    kCfgWide = 7          // bf16 128 x 128, four waves side by side (products with at most 128 rows: m = head size); f32 128 x 256
 };
 
 inline void gemm_cfg_tile(int dtype_is_bf16, int cfg, int* bm, int* bn) {
@@ -65,6 +66,7 @@ inline void gemm_cfg_tile(int dtype_is_bf16, int cfg, int* bm, int* bn) {
         case kCfgSkinny64n128: *bm = 64; *bn = 128; break;
         case kCfgSkinny64n64: *bm = 64; *bn = 64; break;
         case kCfgTall: *bm = dtype_is_bf16 ? 256 : 128; *bn = 128; break;
+        case kCfgWide: *bm = 128; *bn = dtype_is_bf16 ? 128 : 256; break;
         default: *bm = 128; *bn = 256; break;
     }
 }
@@ -73,7 +75,8 @@ int32_t launch_gemm_f32(hipStream_t st, int akf, int bkf, int cfg, const GemmArg
 int32_t launch_gemm_bf16(hipStream_t st, int out_is_f32, int akf, int bkf, int cfg, const GemmArgs& g, int64_t nwg);
 // 256 x 256 (kCfgSquare) or 256 x 128 (kCfgTall) macro-tiles that lie wholly inside their C tile, with 16-byte aligned operands and
 // chunk lengths that are multiples of 64 (kCfgSquare) or 32 (kCfgTall); loads go straight to LDS.  `ragged` (kCfgTall only):
-// macro-tiles may end inside their C tile (row-contiguous operands: at a multiple of 8 rows) and chunk lengths are multiples of 8
+// macro-tiles may end inside their C tile (row-contiguous operands: at a multiple of 8 rows) and chunk lengths are multiples of 8.
+// kCfgWide: 128 x 128 macro-tiles, always under the rules of `ragged`.
 int32_t launch_gemm_bf16_dl(hipStream_t st, int out_is_f32, int akf, int bkf, int cfg, bool ragged, const GemmArgs& g, int64_t nwg);
 int gemm_bf16_dl_occupancy(int out_is_f32, int akf, int bkf, int cfg);
 // fp32: 128 x 128 (kCfgSquare) or 64 x 128 (kCfgMid, kCfgSkinny64n128) macro-tiles that lie wholly inside their

@@ -170,6 +170,28 @@ def test_gemm_bf16_ragged_shapes_randomized_sweep(capi):
                                 (draw, dout, opA, opB, m, n, k, batch, alpha, beta, pad), e)
 
 
+def test_gemm_bf16_few_rows_randomized_sweep(capi):
+    """bf16 products with at most 128 rows (m = head size in the attention layer: 64, 128, and whatever else a
+    caller may bring) against long and short second operands: the 128 x 128 direct-load shape with its clamped
+    loads (macro-tiles mostly empty, columns that end anywhere, a short last k-step, k shorter than a step) and
+    the general kernel for what it does not take (extents that are not multiples of 8).  Every orientation,
+    batches, against the oracle; stops at the first failure."""
+    r = np.random.default_rng(128128)
+    for draw in range(96):
+        dout = ("bf16", "f32")[draw % 2]
+        m = int(r.choice([8, 16, 24, 40, 64, 64, 72, 96, 120, 128, 128, 20, 100]))
+        n = int(r.choice([8 * int(r.integers(1, 100)), 128 * int(r.integers(1, 6)), int(r.integers(1, 300))]))
+        k = int(r.choice([8 * int(r.integers(1, 40)), 32 * int(r.integers(1, 12)), int(r.integers(1, 200))]))
+        opA, opB = "NT"[int(r.integers(2))], "NT"[int(r.integers(2))]
+        batch = int(r.choice([1, 1, 2, 5]))
+        alpha, beta = ((1.0, 0.0), (0.7, -1.3))[int(r.integers(2))]
+        pad = 8 * int(r.integers(0, 3))
+        got, ref = run_gemm(capi, "bf16", dout, opA, opB, m, n, k, batch, alpha, beta, pad, seed=7000 + draw)
+        e = relerr(got, ref)
+        assert e <= TOL[dout], ("draw %d: bf16->%s %s%s %dx%dx%d batch %d alpha %g beta %g pad %d" %
+                                (draw, dout, opA, opB, m, n, k, batch, alpha, beta, pad), e)
+
+
 def test_gemm_degenerate(capi):
     # k = 0: C <- beta * C; beta = 0 must not propagate NaNs already in C
     C0 = rng(1).standard_normal((9, 5)).astype(np.float32)
