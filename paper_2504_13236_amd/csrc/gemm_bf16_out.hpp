@@ -57,8 +57,22 @@ __device__ __forceinline__ void write_tile(float* stage, const f32x16 (&acc)[WNB
                 *reinterpret_cast<f32x4*>(&stage[r32 * ROW + bm * 32 + 8 * q + 4 * half]) = v;
             }
         __syncthreads();
+        // the beta term (C itself, or a residual input's tile behind cin_off) of every row of this pass is
+        // asked for before the pass's first store: a load placed after a store to what may be the same
+        // tile waits for that store
+        constexpr int NIT = 32 / RPI;
+        uint4 cin[NIT];
+        if (beta != 0.f && vec_ok) {
 #pragma unroll
-        for (int it = 0; it < 32 / RPI; it++) {
+            for (int it = 0; it < NIT; it++) {
+                const int row = it * RPI + lane / CH, mc = (lane % CH) * V;
+                const int gn = n_base + bn * 32 + row, gm = m_base + mc;
+                cin[it] = make_uint4(0u, 0u, 0u, 0u);
+                if (gn < n_lim && gm + V <= m_lim) cin[it] = *reinterpret_cast<const uint4*>(C + gm + (int64_t)gn * ldc + cin_off);
+            }
+        }
+#pragma unroll
+        for (int it = 0; it < NIT; it++) {
             const int row = it * RPI + lane / CH, mc = (lane % CH) * V;
             float v[V];
 #pragma unroll
@@ -79,14 +93,15 @@ __device__ __forceinline__ void write_tile(float* stage, const f32x16 (&acc)[WNB
                     }
                     if constexpr (sizeof(TO) == 4) {
                         if (beta != 0.f) {
-                            const f32x4 c = *reinterpret_cast<const f32x4*>(p + cin_off);
-                            v[0] += beta * c[0]; v[1] += beta * c[1]; v[2] += beta * c[2]; v[3] += beta * c[3];
+                            const uint4 c = cin[it];
+                            v[0] += beta * __uint_as_float(c.x); v[1] += beta * __uint_as_float(c.y);
+                            v[2] += beta * __uint_as_float(c.z); v[3] += beta * __uint_as_float(c.w);
                         }
                         f32x4 o = {v[0], v[1], v[2], v[3]};
                         *reinterpret_cast<f32x4*>(p) = o;
                     } else {
                         if (beta != 0.f) {
-                            const uint4 c = *reinterpret_cast<const uint4*>(p + cin_off);
+                            const uint4 c = cin[it];
                             const uint32_t w[4] = {c.x, c.y, c.z, c.w};
 #pragma unroll
                             for (int j = 0; j < 4; j++) {

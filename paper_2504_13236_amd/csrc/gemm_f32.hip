@@ -217,16 +217,27 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(const GemmArgs g) {
         const int gm = m0 + (wm * WMB + bm) * 32 + r32;
         if (gm >= task.m) continue;
         const float bias = task.bias ? task.bias[gm] : 0.f;
+        // (the beta term of the whole row block is read before its first store: a load behind a store to
+        // what may be the same tile would wait for it)
+        float cin[WNB][16];
+        if (beta != 0.f) {
+#pragma unroll
+            for (int bn = 0; bn < WNB; bn++)
+#pragma unroll
+                for (int i = 0; i < 16; i++) {
+                    const int gn = n0 + (wn * WNB + bn) * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
+                    cin[bn][i] = gn < task.n ? C[gm + (int64_t)gn * task.ldc + task.cin_off] : 0.f;
+                }
+        }
 #pragma unroll
         for (int bn = 0; bn < WNB; bn++) {
 #pragma unroll
             for (int i = 0; i < 16; i++) {
                 const int gn = n0 + (wn * WNB + bn) * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
                 if (gn < task.n) {
-                    float* p = C + gm + (int64_t)gn * task.ldc;
                     float v = alpha * acc[bn][bm][i] + bias;
-                    if (beta != 0.f) v += beta * p[task.cin_off];
-                    *p = v;
+                    if (beta != 0.f) v += beta * cin[bn][i];
+                    C[gm + (int64_t)gn * task.ldc] = v;
                 }
             }
         }

@@ -323,19 +323,32 @@ __global__ void __launch_bounds__(256, 2) gemm_f32_dl_kernel(const GemmArgs g) {
     // epilogue: lane holds row m = r32, columns n = 8 * (i / 4) + 4 * half + i % 4 of each 32 x 32 block
     float* C = static_cast<float*>(task.C) + (int64_t)bat * task.strideC;
     const float alpha = task.partial ? 1.f : g.alpha, beta = task.partial ? 0.f : g.beta;
+    // The beta term (C itself, or the tile of a residual input behind cin_off) is read for a whole row block
+    // before the first store of that block: a load placed after a store to what may be the same tile has
+    // to wait for it, and 32 such round trips per block cost a product with one round of workgroups a
+    // quarter of its time.
 #pragma unroll
     for (int bm = 0; bm < WMB; bm++) {
         const int gm = m0 + (wm * WMB + bm) * 32 + r32;
         const float bias = (task.bias && !task.partial) ? task.bias[gm] : 0.f;
+        float cin[WNB][16];
+        if (beta != 0.f) {
+#pragma unroll
+            for (int bn = 0; bn < WNB; bn++)
+#pragma unroll
+                for (int i = 0; i < 16; i++) {
+                    const int gn = n0 + (wn * WNB + bn) * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
+                    cin[bn][i] = C[gm + (int64_t)gn * task.ldc + task.cin_off];
+                }
+        }
 #pragma unroll
         for (int bn = 0; bn < WNB; bn++) {
 #pragma unroll
             for (int i = 0; i < 16; i++) {
                 const int gn = n0 + (wn * WNB + bn) * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
-                float* p = C + gm + (int64_t)gn * task.ldc;
                 float v = alpha * acc[bn][bm][i] + bias;
-                if (beta != 0.f) v += beta * p[task.cin_off];
-                *p = v;
+                if (beta != 0.f) v += beta * cin[bn][i];
+                C[gm + (int64_t)gn * task.ldc] = v;
             }
         }
     }
