@@ -63,6 +63,28 @@ template <int V> __device__ __forceinline__ void stv(bf16_t* p, const float (&f)
     }
 }
 
+// Streaming forms for data that is touched once per launch and far larger than the caches (optimiser state):
+// non-temporal loads and stores.
+typedef float nt_f32x4 __attribute__((ext_vector_type(4)));
+template <int V> __device__ __forceinline__ void ldv_stream(const float* p, float (&f)[V]) {
+    if constexpr (V == 4) {
+        const nt_f32x4 x = __builtin_nontemporal_load(reinterpret_cast<const nt_f32x4*>(p));
+        f[0] = x[0]; f[1] = x[1]; f[2] = x[2]; f[3] = x[3];
+    } else {
+#pragma unroll
+        for (int i = 0; i < V; i++) f[i] = __builtin_nontemporal_load(p + i);
+    }
+}
+template <int V> __device__ __forceinline__ void stv_stream(float* p, const float (&f)[V]) {
+    if constexpr (V == 4) {
+        const nt_f32x4 x = {f[0], f[1], f[2], f[3]};
+        __builtin_nontemporal_store(x, reinterpret_cast<nt_f32x4*>(p));
+    } else {
+#pragma unroll
+        for (int i = 0; i < V; i++) __builtin_nontemporal_store(f[i], p + i);
+    }
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);

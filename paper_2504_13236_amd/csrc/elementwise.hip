@@ -248,8 +248,12 @@ int32_t nnt_tile_gelu_bwd(void* stream, int32_t dtype, int32_t variant, int64_t 
     return launch_ew((hipStream_t)stream, GeluBwdF<bf16_t>{ptr(x), ptr(dy), ptr(dx), variant}, single_geom(n), n, 1, vec);
 }
 
-static AdamF make_adam(int32_t step, double lr, double b1, double b2, double eps, double wd) {
+// State larger than this is streamed past the caches (four times the 256 MB last-level cache).
+constexpr double kAdamStreamBytes = 1024.0 * 1024.0 * 1024.0;
+
+static AdamF make_adam(int32_t step, double lr, double b1, double b2, double eps, double wd, double bytes) {
     AdamF f = {};
+    f.stream = bytes > kAdamStreamBytes ? 1 : 0;
     f.lr = (float)lr; f.beta1 = (float)b1; f.beta2 = (float)b2; f.eps = (float)eps; f.wd = (float)wd;
     f.omb1 = (float)(1.0 - b1); f.omb2 = (float)(1.0 - b2);
     f.inv_bc1 = (float)(1.0 / (1.0 - std::pow((double)b1, (double)step)));
@@ -260,7 +264,7 @@ static AdamF make_adam(int32_t step, double lr, double b1, double b2, double eps
 int32_t nnt_tile_adam(void* stream, int64_t n, int32_t step, double lr, double beta1, double beta2, double eps,
                       double weight_decay, const float* g, float* p, float* m, float* v, void* p_lowp) {
     if (n < 0 || step < 1 || (n > 0 && (!g || !p || !m || !v))) return NNT_EINVAL;
-    AdamF f = make_adam(step, lr, beta1, beta2, eps, weight_decay);
+    AdamF f = make_adam(step, lr, beta1, beta2, eps, weight_decay, 30.0 * (double)n);
     f.g = ptr(g); f.p = ptr(p); f.m = ptr(m); f.v = ptr(v); f.lp = ptr(p_lowp);
     const bool vec = aligned16(g) && aligned16(p) && aligned16(m) && aligned16(v) && (!p_lowp || ((uintptr_t)p_lowp & 7) == 0);
     return launch_ew((hipStream_t)stream, f, single_geom(n), n, 1, vec);
@@ -396,7 +400,7 @@ int32_t nnt_adam_step(nnt_ctx* ctx, const nnt_adam_cfg* cfg, int32_t step, nnt_t
         return fail(ctx, NNT_EDTYPE, "nnt_adam_step: g, p, m, v must be fp32 and the low-precision copy bf16");
     const bool vec = all_aligned(G) && all_aligned(P) && all_aligned(M) && all_aligned(V) && (!LP || all_aligned(LP));
     OpTag tag(ctx, "adam", present_numel(P) * (28 + (LP ? 2 : 0)), true);
-    AdamF base = make_adam(step, cfg->lr, cfg->beta1, cfg->beta2, cfg->eps, cfg->weight_decay);
+    AdamF base = make_adam(step, cfg->lr, cfg->beta1, cfg->beta2, cfg->eps, cfg->weight_decay, present_numel(P) * 30.0);
     std::vector<std::pair<nnt_tensor*, int>> ops = {{G, kRead}, {P, kReadWrite}, {M, kReadWrite}, {V, kReadWrite}};
     if (LP) ops.push_back({LP, kWrite});
     return run_tensor_ew(ctx, P, ops, vec, [=](int64_t t) {
@@ -479,7 +483,7 @@ int32_t adam_group_create(nnt_ctx* ctx, int n, nnt_tensor* const* G, nnt_tensor*
 // One Adam step on every tensor of the group: one task, one launch (whole-operation granularity).
 int32_t adam_group_step(nnt_ctx* ctx, AdamGroup* a, const nnt_adam_cfg* cfg, int32_t step) {
     OpTag tag(ctx, "adam", a->bytes, true);
-    AdamF f = make_adam(step, cfg->lr, cfg->beta1, cfg->beta2, cfg->eps, cfg->weight_decay);
+    AdamF f = make_adam(step, cfg->lr, cfg->beta1, cfg->beta2, cfg->eps, cfg->weight_decay, (double)a->bytes);
     const size_t E = (size_t)a->entries;
     f.g = Operand{a->tabs, nullptr}; f.p = Operand{a->tabs + E, nullptr}; f.m = Operand{a->tabs + 2 * E, nullptr};
     f.v = Operand{a->tabs + 3 * E, nullptr}; f.lp = Operand{a->tabs + 4 * E, nullptr};

@@ -271,6 +271,8 @@ struct AdamF {
     static constexpr int V = 4, NIN = 4;
     Operand g, p, m, v, lp;
     float lr, beta1, beta2, omb1, omb2, eps, wd, inv_bc1, inv_bc2;   // omb = 1 - beta, formed in double on the host
+    int stream;       // non-temporal accesses: the state is far larger than the last-level cache (measured: 4 % faster
+                      // at 24 GB per step, 6 % slower at 0.4 GB, where the gradients still sit in that cache)
     struct Ctx { const float* g; float* p; float* m; float* v; bf16_t* lp; };
     __device__ bool setup(Ctx& c, const EwGeom&, int tile) const {
         c.g = pick<const float>(g, tile);
@@ -281,10 +283,17 @@ struct AdamF {
         return c.p != nullptr;
     }
     template <int W> __device__ void load(const Ctx& c, int64_t i, float (&in)[4][W]) const {
-        ldv<W>(c.g + i, in[0]);
-        ldv<W>(c.p + i, in[1]);
-        ldv<W>(c.m + i, in[2]);
-        ldv<W>(c.v + i, in[3]);
+        if (stream) {
+            ldv_stream<W>(c.g + i, in[0]);
+            ldv_stream<W>(c.p + i, in[1]);
+            ldv_stream<W>(c.m + i, in[2]);
+            ldv_stream<W>(c.v + i, in[3]);
+        } else {
+            ldv<W>(c.g + i, in[0]);
+            ldv<W>(c.p + i, in[1]);
+            ldv<W>(c.m + i, in[2]);
+            ldv<W>(c.v + i, in[3]);
+        }
     }
     template <int W> __device__ void store(const Ctx& c, int64_t i, float (&in)[4][W]) const {
         float pp[W], mm[W], vv[W];
@@ -297,9 +306,15 @@ struct AdamF {
             const float vhat = vv[j] * inv_bc2;
             pp[j] = in[1][j] - lr * wd * in[1][j] - lr * mhat / (sqrtf(vhat) + eps);
         }
-        stv<W>(c.p + i, pp);
-        stv<W>(c.m + i, mm);
-        stv<W>(c.v + i, vv);
+        if (stream) {
+            stv_stream<W>(c.p + i, pp);
+            stv_stream<W>(c.m + i, mm);
+            stv_stream<W>(c.v + i, vv);
+        } else {
+            stv<W>(c.p + i, pp);
+            stv<W>(c.m + i, mm);
+            stv<W>(c.v + i, vv);
+        }
         if (c.lp) {
             if constexpr (W == 4) {
                 uint2 x;

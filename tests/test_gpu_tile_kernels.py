@@ -439,6 +439,28 @@ def test_adam_tile(capi, n, wd):
     np.testing.assert_array_equal(got_lp.view(np.uint32), D.round_to_bf16(dp.cpu().numpy()).view(np.uint32))
 
 
+def test_adam_tile_with_state_beyond_the_caches(capi):
+    """One tile whose optimiser state (30 bytes per parameter) exceeds 1 GiB: the kernel streams it with
+    non-temporal accesses.  Two steps against the oracle, every element; a ragged tail of three."""
+    n = 36 * 1024 * 1024 + 3
+    r = rng(36)
+    p = r.standard_normal(n).astype(np.float32)
+    g = r.standard_normal(n).astype(np.float32)
+    dp, dm, dv, dg = to_dev(p), to_dev(np.zeros(n, np.float32)), to_dev(np.zeros(n, np.float32)), to_dev(g)
+    lp = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+    pr, mr, vr = p.astype(np.float64), np.zeros(n), np.zeros(n)
+    for step in (1, 2):
+        capi.nnt_tile_adam(stream_ptr(), n, step, 1e-3, 0.9, 0.999, 1e-8, 0.01, dg.data_ptr(), dp.data_ptr(), dm.data_ptr(),
+                           dv.data_ptr(), lp.data_ptr())
+        pr, mr, vr = D.adam_step(pr, g, mr, vr, step, weight_decay=0.01)
+    torch.cuda.synchronize()
+    check(from_dev(dp, (n,)), pr, "f32", "adam p")
+    check(from_dev(dm, (n,)), mr, "f32", "adam m")
+    check(from_dev(dv, (n,)), vr, "f32", "adam v")
+    got_lp = lp.to(torch.float32).cpu().numpy()
+    np.testing.assert_array_equal(got_lp.view(np.uint32), D.round_to_bf16(dp.cpu().numpy()).view(np.uint32))
+
+
 def test_adam_first_step_closed_form(capi):
     n = 64
     g = rng(5).standard_normal(n).astype(np.float32)
