@@ -22,11 +22,29 @@ constexpr float kNegInf = -__builtin_huge_valf();
 // and made the forward kernel arithmetic-bound).  -inf gives 0.
 __device__ __forceinline__ float fexp(float x) { return __builtin_amdgcn_exp2f(x * 1.4426950408889634f); }
 
-// fn(slot, l, e, ext) over the vectors of a column whose first key index is below `kmax`
-template <int V, int NV, typename Fn>
+// fn(slot, l, e, ext) over the vectors of a column whose first key index is below `kmax`.
+// FLAT: the vectors of all key tiles are numbered through and dealt to the lanes 64 at a time, so a lane's
+// tile differs from its neighbour's (its pointer comes out of the table per lane).  For key tiles whose
+// vector count is no multiple of 64 (tiles of 400 are 50 vectors of 8 bf16: three slots of 50 lanes
+// otherwise, two full ones this way).
+template <int V, int NV, bool FLAT = false, typename Fn>
 __device__ __forceinline__ void walk_keys(const TiledView& v, int lane, int kmax, Fn fn) {
     const int g0 = v.grid[0];
-    if constexpr (NV > 0) {
+    if constexpr (FLAT) {
+        static_assert(NV > 0, "the flat numbering is for columns that fit in registers");
+        const int vt = v.base[0] / V;                      // vectors of a whole tile
+        const float inv_vt = 1.f / (float)vt;
+#pragma unroll
+        for (int it = 0; it < NV; it++) {
+            const int f = it * 64 + lane;
+            const int l = (int)(((float)f + 0.5f) * inv_vt);   // f / vt: the half keeps the product away from an integer
+            if (l < g0) {
+                const int ext = ext0_of(v, l);
+                const int e = (f - l * vt) * V;
+                if (e < ext && l * v.base[0] + e < kmax) fn(it, l, e, ext);
+            }
+        }
+    } else if constexpr (NV > 0) {
         const int vpt = (v.base[0] + 64 * V - 1) / (64 * V);
         int l = 0, j = 0;                 // slot it is vector j of tile l (counted up: no division per slot)
 #pragma unroll
@@ -202,7 +220,7 @@ __global__ void __launch_bounds__(256) softmax_bwd_fused(TiledView P, TiledView 
 // differ by one column pitch: the look-up of the tiles is paid once per CPW columns, and the loads of
 // all of them are in flight together.  Short columns in a narrow type (1024 bf16 keys are 2 KB) are
 // otherwise bound by that look-up and by the latency of a single round of loads.
-template <typename T, int V, int NV, int CPW>
+template <typename T, int V, int NV, int CPW, bool FLAT = false>
 __global__ void __launch_bounds__(256) softmax_fwd_multi(TiledView A, TiledView S, float scale, int causal, int64_t ncols) {
     const int lane = threadIdx.x & 63;
     const int64_t col = ((int64_t)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6)) * CPW;
@@ -222,7 +240,7 @@ __global__ void __launch_bounds__(256) softmax_fwd_multi(TiledView A, TiledView 
 #pragma unroll
             for (int k = 0; k < V; k++) cache[q][i][k] = 0.f;
     }
-    walk_keys<V, NV>(A, lane, kmax_last, [&](int slot, int l, int e, int ext) {
+    walk_keys<V, NV, FLAT>(A, lane, kmax_last, [&](int slot, int l, int e, int ext) {
         const T* p = col_ptr<const T>(A, c, l, ext);
         const int k0 = l * A.base[0] + e;
 #pragma unroll
@@ -248,7 +266,7 @@ __global__ void __launch_bounds__(256) softmax_fwd_multi(TiledView A, TiledView 
     for (int q = 0; q < CPW; q++) mx[q] = wave_max(mx[q]);
     // shifted exponentials: the walk visits exactly the slots that were loaded (masked entries are -inf -> 0;
     // slots it does not reach keep their 0)
-    walk_keys<V, NV>(A, lane, kmax_last, [&](int slot, int l, int e, int ext) {
+    walk_keys<V, NV, FLAT>(A, lane, kmax_last, [&](int slot, int l, int e, int ext) {
 #pragma unroll
         for (int q = 0; q < CPW; q++)
 #pragma unroll
@@ -265,7 +283,7 @@ __global__ void __launch_bounds__(256) softmax_fwd_multi(TiledView A, TiledView 
         inv[q] = 1.f / sum[q];
     }
     // every vector of every present tile is written: masked entries (and slots never loaded) are 0
-    walk_keys<V, NV>(A, lane, nk, [&](int slot, int l, int e, int ext) {
+    walk_keys<V, NV, FLAT>(A, lane, nk, [&](int slot, int l, int e, int ext) {
         T* p = col_ptr<T>(A, c, l, ext);
         if (!p) return;
 #pragma unroll
@@ -287,7 +305,7 @@ __global__ void __launch_bounds__(256) softmax_fwd_multi(TiledView A, TiledView 
     }
 }
 
-template <typename T, int V, int NV, int CPW>
+template <typename T, int V, int NV, int CPW, bool FLAT = false>
 __global__ void __launch_bounds__(256) softmax_bwd_multi(TiledView P, TiledView dP, int64_t ncols) {
     const int lane = threadIdx.x & 63;
     const int64_t col = ((int64_t)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6)) * CPW;
@@ -298,7 +316,7 @@ __global__ void __launch_bounds__(256) softmax_bwd_multi(TiledView P, TiledView 
     float dot[CPW];
 #pragma unroll
     for (int q = 0; q < CPW; q++) dot[q] = 0.f;
-    walk_keys<V, NV>(P, lane, nk, [&](int slot, int l, int e, int ext) {
+    walk_keys<V, NV, FLAT>(P, lane, nk, [&](int slot, int l, int e, int ext) {
         const T* p = col_ptr<const T>(P, c, l, ext);
         const T* d = col_ptr<const T>(dP, c, l, ext);
 #pragma unroll
@@ -321,7 +339,7 @@ __global__ void __launch_bounds__(256) softmax_bwd_multi(TiledView P, TiledView 
     });
 #pragma unroll
     for (int q = 0; q < CPW; q++) dot[q] = wave_sum(dot[q]);
-    walk_keys<V, NV>(P, lane, nk, [&](int slot, int l, int e, int ext) {
+    walk_keys<V, NV, FLAT>(P, lane, nk, [&](int slot, int l, int e, int ext) {
         T* d = col_ptr<T>(dP, c, l, ext);
         if (!d) return;
 #pragma unroll
@@ -479,12 +497,30 @@ static inline int columns_per_wave(const nnt_tensor* A, bool vec, int nv, bool a
     else want = A->dtype == NNT_F32 ? 2 : (nv <= 2 ? 4 : 2);
     return (A->shape[1] % want == 0 && A->base[1] % want == 0) ? want : 1;
 }
+// Slots of the flat numbering (all vectors of a column, 64 per slot), or 0 when it saves nothing over the
+// numbering by tile or the column does not fit four slots.
+static inline int flat_slots(const nnt_tensor* A, bool vec, int nv_by_tile) {
+    const int V = A->dtype == NNT_F32 ? 4 : 8;
+    if (!vec || A->grid[0] < 2 || (A->base[0] / V) % 64 == 0) return 0;
+    const int nv = (int)((A->shape[0] / V + 63) / 64);
+    return (nv <= 4 && nv < nv_by_tile) ? nv : 0;
+}
 #define DISPATCH_MULTI(dtype, nv, cpw, KERNEL, ...)                                                        \
     do {                                                                                                   \
         if ((dtype) == NNT_F32) hipLaunchKernelGGL((KERNEL<float, 4, 4, 2>), grid, block, 0, st, __VA_ARGS__);            \
         else if ((nv) <= 2 && (cpw) == 4) hipLaunchKernelGGL((KERNEL<bf16_t, 8, 2, 4>), grid, block, 0, st, __VA_ARGS__); \
         else if ((nv) <= 2) hipLaunchKernelGGL((KERNEL<bf16_t, 8, 2, 2>), grid, block, 0, st, __VA_ARGS__);               \
         else hipLaunchKernelGGL((KERNEL<bf16_t, 8, 4, 2>), grid, block, 0, st, __VA_ARGS__);                             \
+    } while (0)
+// the same with the flat numbering (also for one column per wavefront: the fp32 adjoint)
+#define DISPATCH_FLAT(dtype, nv, cpw, KERNEL, ...)                                                                        \
+    do {                                                                                                                  \
+        if ((dtype) == NNT_F32 && (cpw) == 2) hipLaunchKernelGGL((KERNEL<float, 4, 4, 2, true>), grid, block, 0, st, __VA_ARGS__);      \
+        else if ((dtype) == NNT_F32) hipLaunchKernelGGL((KERNEL<float, 4, 4, 1, true>), grid, block, 0, st, __VA_ARGS__);                \
+        else if ((nv) <= 2 && (cpw) == 4) hipLaunchKernelGGL((KERNEL<bf16_t, 8, 2, 4, true>), grid, block, 0, st, __VA_ARGS__);          \
+        else if ((nv) <= 2 && (cpw) == 2) hipLaunchKernelGGL((KERNEL<bf16_t, 8, 2, 2, true>), grid, block, 0, st, __VA_ARGS__);          \
+        else if ((cpw) == 2) hipLaunchKernelGGL((KERNEL<bf16_t, 8, 4, 2, true>), grid, block, 0, st, __VA_ARGS__);                       \
+        else hipLaunchKernelGGL((KERNEL<bf16_t, 8, 4, 1, true>), grid, block, 0, st, __VA_ARGS__);                                       \
     } while (0)
 
 static inline bool sm_ok(int64_t tk, int64_t tq, int64_t batch) {
@@ -591,10 +627,12 @@ int32_t nnt_softmax_fwd(nnt_ctx* ctx, nnt_tensor* A, nnt_tensor* stats, float sc
         const TiledView va = A->view(), vs = stats->view();
         const int64_t ncols = n_columns(A);
         if (ncols > INT32_MAX) return fail(ctx, NNT_EINVAL, "nnt_softmax_fwd: tensor too large");
-        const int cpw = columns_per_wave(A, vec, nv, false);
+        const int nvf = flat_slots(A, vec, nv);
+        const int cpw = columns_per_wave(A, vec, nvf ? nvf : nv, false);
         return submit(ctx, {A->all(kReadWrite), stats->all(kWrite)}, [=](hipStream_t st) {
             const dim3 grid((unsigned)((ncols / cpw + 3) / 4)), block(256);
-            if (cpw > 1) DISPATCH_MULTI(dtype, nv, cpw, softmax_fwd_multi, va, vs, scale, (int)causal, ncols);
+            if (nvf) DISPATCH_FLAT(dtype, nvf, cpw, softmax_fwd_multi, va, vs, scale, (int)causal, ncols);
+            else if (cpw > 1) DISPATCH_MULTI(dtype, nv, cpw, softmax_fwd_multi, va, vs, scale, (int)causal, ncols);
             else DISPATCH_TVN(dtype, vec, nv, softmax_fwd_fused, va, vs, scale, (int)causal, ncols);
             return hipGetLastError() == hipSuccess ? (int32_t)NNT_OK : (int32_t)NNT_EHIP;
         });
@@ -651,10 +689,12 @@ int32_t nnt_softmax_bwd(nnt_ctx* ctx, nnt_tensor* P, nnt_tensor* dP) {
         const TiledView vp = P->view(), vd = dP->view();
         const int64_t ncols = n_columns(P);
         if (ncols > INT32_MAX) return fail(ctx, NNT_EINVAL, "nnt_softmax_bwd: tensor too large");
-        const int cpw = columns_per_wave(P, vec, nv, true);
+        const int nvf = flat_slots(P, vec, nv);
+        const int cpw = columns_per_wave(P, vec, nvf ? nvf : nv, true);
         return submit(ctx, {P->all(kRead), dP->all(kReadWrite)}, [=](hipStream_t st) {
             const dim3 grid((unsigned)((ncols / cpw + 3) / 4)), block(256);
-            if (cpw > 1) DISPATCH_MULTI(dtype, nv, cpw, softmax_bwd_multi, vp, vd, ncols);
+            if (nvf) DISPATCH_FLAT(dtype, nvf, cpw, softmax_bwd_multi, vp, vd, ncols);
+            else if (cpw > 1) DISPATCH_MULTI(dtype, nv, cpw, softmax_bwd_multi, vp, vd, ncols);
             else DISPATCH_TVN(dtype, vec, nv, softmax_bwd_fused, vp, vd, ncols);
             return hipGetLastError() == hipSuccess ? (int32_t)NNT_OK : (int32_t)NNT_EHIP;
         });
