@@ -185,6 +185,12 @@ __global__ void __launch_bounds__(256) gemm_bf16_kernel(const GemmArgs g) {
         n0 = ((b / g.grid_m) % g.grid_n) * BN;
         bat = b / (g.grid_m * g.grid_n);
     }
+    // (batch members that are pairs: see GemmTask::nb1)
+    int bat_lo = bat, bat_hi = 0;
+    if (task.nb1 > 0) {
+        bat_hi = bat / task.nb1;
+        bat_lo = bat - bat_hi * task.nb1;
+    }
 
     f32x16 acc[WNB][WMB];
 #pragma unroll
@@ -213,8 +219,8 @@ __global__ void __launch_bounds__(256) gemm_bf16_kernel(const GemmArgs g) {
             chvec = __builtin_amdgcn_readfirstlane(ch.vec_ok);
             lda = __builtin_amdgcn_readfirstlane((int)ch.lda);
             ldb = __builtin_amdgcn_readfirstlane((int)ch.ldb);
-            Ab = uniform_ptr(static_cast<const uint16_t*>(ch.A) + (int64_t)bat * ch.strideA);
-            Bb = uniform_ptr(static_cast<const uint16_t*>(ch.B) + (int64_t)bat * ch.strideB);
+            Ab = uniform_ptr(static_cast<const uint16_t*>(ch.A) + (int64_t)bat_lo * ch.strideA + (int64_t)bat_hi * ch.strideA2);
+            Bb = uniform_ptr(static_cast<const uint16_t*>(ch.B) + (int64_t)bat_lo * ch.strideB + (int64_t)bat_hi * ch.strideB2);
         };
         set_chunk(table ? g.chunks[task.chunk0] : g.one_chunk);
         typename LoaderSel<AKF, BM, BKT>::type la;
@@ -308,10 +314,10 @@ __global__ void __launch_bounds__(256) gemm_bf16_kernel(const GemmArgs g) {
     const int m_base = m0 + wm * WMB * 32, n_base = n0 + wn * WNB * 32;
     if (task.partial) {
         // one k-slice of a split product: raw fp32 sums into the scratch tile
-        write_tile<float, WMB, WNB>(stage, acc, static_cast<float*>(task.C) + (int64_t)bat * task.strideC, task.ldc, nullptr,
+        write_tile<float, WMB, WNB>(stage, acc, static_cast<float*>(task.C) + (int64_t)bat_lo * task.strideC + (int64_t)bat_hi * task.strideC2, task.ldc, nullptr,
                                     1.f, 0.f, m_base, n_base, task.m, task.n, lane);
     } else {
-        write_tile<TO, WMB, WNB>(stage, acc, static_cast<TO*>(task.C) + (int64_t)bat * task.strideC, task.ldc, task.bias,
+        write_tile<TO, WMB, WNB>(stage, acc, static_cast<TO*>(task.C) + (int64_t)bat_lo * task.strideC + (int64_t)bat_hi * task.strideC2, task.ldc, task.bias,
                                  g.alpha, g.beta, m_base, n_base, task.m, task.n, lane, task.cin_off);
     }
 }

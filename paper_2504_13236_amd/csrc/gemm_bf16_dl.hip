@@ -219,6 +219,12 @@ __device__ __forceinline__ void dl_body(const GemmArgs& g, char* lds) {
     m0 = __builtin_amdgcn_readfirstlane(m0);
     n0 = __builtin_amdgcn_readfirstlane(n0);
     bat = __builtin_amdgcn_readfirstlane(bat);
+    // (batch members that are pairs: see GemmTask::nb1)
+    int bat_lo = bat, bat_hi = 0;
+    if (task.nb1 > 0) {
+        bat_hi = bat / task.nb1;
+        bat_lo = bat - bat_hi * task.nb1;
+    }
 
     f32x16 acc[WNB][WMB];
 #pragma unroll
@@ -258,8 +264,8 @@ __device__ __forceinline__ void dl_body(const GemmArgs& g, char* lds) {
         auto set_chunk = [&](const ChunkS& ch) {
             chk = ch.k;
             const int lda = (int)ch.lda, ldb = (int)ch.ldb;
-            const uint16_t* Ab = reinterpret_cast<const uint16_t*>(ch.A) + (int64_t)bat * ch.strideA;
-            const uint16_t* Bb = reinterpret_cast<const uint16_t*>(ch.B) + (int64_t)bat * ch.strideB;
+            const uint16_t* Ab = reinterpret_cast<const uint16_t*>(ch.A) + (int64_t)bat_lo * ch.strideA + (int64_t)bat_hi * ch.strideA2;
+            const uint16_t* Bb = reinterpret_cast<const uint16_t*>(ch.B) + (int64_t)bat_lo * ch.strideB + (int64_t)bat_hi * ch.strideB2;
             baseA = reinterpret_cast<const char*>(AKF ? Ab + (int64_t)m0 * lda : Ab + m0);
             baseB = reinterpret_cast<const char*>(BKF ? Bb + (int64_t)n0 * ldb : Bb + n0);
             advA = AKF ? kBK * 2 : (int64_t)kBK * lda * 2;
@@ -290,6 +296,7 @@ __device__ __forceinline__ void dl_body(const GemmArgs& g, char* lds) {
             one.A = reinterpret_cast<uint64_t>(g.one_chunk.A); one.B = reinterpret_cast<uint64_t>(g.one_chunk.B);
             one.lda = g.one_chunk.lda; one.ldb = g.one_chunk.ldb;
             one.strideA = g.one_chunk.strideA; one.strideB = g.one_chunk.strideB;
+            one.strideA2 = g.one_chunk.strideA2; one.strideB2 = g.one_chunk.strideB2;
             one.k = g.one_chunk.k; one.vec_ok = g.one_chunk.vec_ok;
             set_chunk(one);
         }
@@ -517,10 +524,10 @@ __device__ __forceinline__ void dl_body(const GemmArgs& g, char* lds) {
     float* stage = reinterpret_cast<float*>(lds) + wave * (32 * (32 * WMB + 4));
     const int m_base = m0 + wm * WMB * 32, n_base = n0 + wn * WNB * 32;
     if (task.partial) {
-        write_tile<float, WMB, WNB>(stage, acc, static_cast<float*>(task.C) + (int64_t)bat * task.strideC, task.ldc, nullptr,
+        write_tile<float, WMB, WNB>(stage, acc, static_cast<float*>(task.C) + (int64_t)bat_lo * task.strideC + (int64_t)bat_hi * task.strideC2, task.ldc, nullptr,
                                     1.f, 0.f, m_base, n_base, task.m, task.n, lane);
     } else {
-        write_tile<TO, WMB, WNB>(stage, acc, static_cast<TO*>(task.C) + (int64_t)bat * task.strideC, task.ldc, task.bias,
+        write_tile<TO, WMB, WNB>(stage, acc, static_cast<TO*>(task.C) + (int64_t)bat_lo * task.strideC + (int64_t)bat_hi * task.strideC2, task.ldc, task.bias,
                                  g.alpha, g.beta, m_base, n_base, task.m, task.n, lane, task.cin_off);
     }
 }

@@ -19,9 +19,12 @@ struct GemmTask {
     int32_t m, n;
     int32_t chunk0, nchunk;
     int32_t partial;        // 1: one k-slice of a split product; C is an fp32 scratch tile that receives the raw sum
-    int32_t pad;
+    int32_t nb1;            // > 0: batch member `bat` is the pair (bat % nb1, bat / nb1) and the second index moves the
+                            // operands and C by their second strides (attention products on tensors that keep the heads
+                            // side by side along their first axis: the pair is (batch member, head)); 0: one stride
     int64_t cin_off;        // the beta term is read at C + cin_off (elements of C's type): 0 = from C itself, else from
                             // the tile of a second tensor with C's geometry (a residual input)
+    int64_t strideC2;       // elements
 };
 
 struct GemmChunk {
@@ -30,6 +33,7 @@ struct GemmChunk {
     int64_t lda, ldb, strideA, strideB;   // elements
     int32_t k;
     int32_t vec_ok;         // bit 0: A may be read with 16-byte vectors, bit 1: B
+    int64_t strideA2, strideB2;           // second batch strides (see GemmTask::nb1), elements
 };
 
 struct GemmWg {

@@ -23,18 +23,19 @@ struct ChunkS {
     uint64_t A, B;
     int64_t lda, ldb, strideA, strideB;
     int32_t k, vec_ok;
+    int64_t strideA2, strideB2;
 };
-static_assert(sizeof(ChunkS) == sizeof(GemmChunk) && sizeof(GemmChunk) == 56, "descriptor layout");
+static_assert(sizeof(ChunkS) == sizeof(GemmChunk) && sizeof(GemmChunk) == 72, "descriptor layout");
 
 __device__ __forceinline__ ChunkS sload_chunk(const GemmChunk* p) {
     typedef uint32_t u32x8 __attribute__((ext_vector_type(8)));
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
     typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
     u32x8 a;
-    u32x4 b;
+    u32x4 b, d;
     u32x2 c;
-    asm volatile("s_load_dwordx8 %0, %3, 0x0\n\ts_load_dwordx4 %1, %3, 0x20\n\ts_load_dwordx2 %2, %3, 0x30\n\ts_waitcnt lgkmcnt(0)"
-                 : "=&s"(a), "=&s"(b), "=&s"(c)
+    asm volatile("s_load_dwordx8 %0, %4, 0x0\n\ts_load_dwordx4 %1, %4, 0x20\n\ts_load_dwordx2 %2, %4, 0x30\n\ts_load_dwordx4 %3, %4, 0x38\n\ts_waitcnt lgkmcnt(0)"
+                 : "=&s"(a), "=&s"(b), "=&s"(c), "=&s"(d)
                  : "s"(p)
                  : "memory");
     ChunkS r;
@@ -46,6 +47,8 @@ __device__ __forceinline__ ChunkS sload_chunk(const GemmChunk* p) {
     r.strideB = (int64_t)(b[2] | ((uint64_t)b[3] << 32));
     r.k = (int32_t)c[0];
     r.vec_ok = (int32_t)c[1];
+    r.strideA2 = (int64_t)(d[0] | ((uint64_t)d[1] << 32));
+    r.strideB2 = (int64_t)(d[2] | ((uint64_t)d[3] << 32));
     return r;
 }
 

@@ -132,6 +132,12 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(const GemmArgs g) {
         n0 = ((b / g.grid_m) % g.grid_n) * BN;
         bat = b / (g.grid_m * g.grid_n);
     }
+    // (batch members that are pairs: see GemmTask::nb1)
+    int bat_lo = bat, bat_hi = 0;
+    if (task.nb1 > 0) {
+        bat_hi = bat / task.nb1;
+        bat_lo = bat - bat_hi * task.nb1;
+    }
 
     f32x16 acc[WNB][WMB];
 #pragma unroll
@@ -153,8 +159,8 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(const GemmArgs g) {
             chvec = __builtin_amdgcn_readfirstlane(ch.vec_ok);
             lda = __builtin_amdgcn_readfirstlane((int)ch.lda);
             ldb = __builtin_amdgcn_readfirstlane((int)ch.ldb);
-            Ab = uniform_ptr(static_cast<const float*>(ch.A) + (int64_t)bat * ch.strideA);
-            Bb = uniform_ptr(static_cast<const float*>(ch.B) + (int64_t)bat * ch.strideB);
+            Ab = uniform_ptr(static_cast<const float*>(ch.A) + (int64_t)bat_lo * ch.strideA + (int64_t)bat_hi * ch.strideA2);
+            Bb = uniform_ptr(static_cast<const float*>(ch.B) + (int64_t)bat_lo * ch.strideB + (int64_t)bat_hi * ch.strideB2);
         };
         set_chunk(table ? g.chunks[task.chunk0] : g.one_chunk);
         f32x4 va[BM / 64], vb[BN / 64];
@@ -210,7 +216,7 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(const GemmArgs g) {
     }
 
     // epilogue: lane holds row m = r32, columns n = 8 * (i / 4) + 4 * half + i % 4 of each 32 x 32 block
-    float* C = static_cast<float*>(task.C) + (int64_t)bat * task.strideC;
+    float* C = static_cast<float*>(task.C) + (int64_t)bat_lo * task.strideC + (int64_t)bat_hi * task.strideC2;
     const float alpha = task.partial ? 1.f : g.alpha, beta = task.partial ? 0.f : g.beta;
 #pragma unroll
     for (int bm = 0; bm < WMB; bm++) {

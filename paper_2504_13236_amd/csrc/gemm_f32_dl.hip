@@ -143,6 +143,12 @@ __global__ void __launch_bounds__(256, 2) gemm_f32_dl_kernel(const GemmArgs g) {
     m0 = __builtin_amdgcn_readfirstlane(m0);
     n0 = __builtin_amdgcn_readfirstlane(n0);
     bat = __builtin_amdgcn_readfirstlane(bat);
+    // (batch members that are pairs: see GemmTask::nb1)
+    int bat_lo = bat, bat_hi = 0;
+    if (task.nb1 > 0) {
+        bat_hi = bat / task.nb1;
+        bat_lo = bat - bat_hi * task.nb1;
+    }
 
     f32x16 acc[WNB][WMB];
 #pragma unroll
@@ -179,8 +185,8 @@ __global__ void __launch_bounds__(256, 2) gemm_f32_dl_kernel(const GemmArgs g) {
         auto set_chunk = [&](const ChunkS& ch) {
             chk = ch.k;
             const int lda = (int)ch.lda, ldb = (int)ch.ldb;
-            const float* Ab = reinterpret_cast<const float*>(ch.A) + (int64_t)bat * ch.strideA;
-            const float* Bb = reinterpret_cast<const float*>(ch.B) + (int64_t)bat * ch.strideB;
+            const float* Ab = reinterpret_cast<const float*>(ch.A) + (int64_t)bat_lo * ch.strideA + (int64_t)bat_hi * ch.strideA2;
+            const float* Bb = reinterpret_cast<const float*>(ch.B) + (int64_t)bat_lo * ch.strideB + (int64_t)bat_hi * ch.strideB2;
             baseA = reinterpret_cast<const char*>(AKF ? Ab + (int64_t)m0 * lda : Ab + m0);
             baseB = reinterpret_cast<const char*>(BKF ? Bb + (int64_t)n0 * ldb : Bb + n0);
             advA = AKF ? kBK * 4 : (int64_t)kBK * lda * 4;
@@ -197,6 +203,7 @@ __global__ void __launch_bounds__(256, 2) gemm_f32_dl_kernel(const GemmArgs g) {
             one.A = reinterpret_cast<uint64_t>(g.one_chunk.A); one.B = reinterpret_cast<uint64_t>(g.one_chunk.B);
             one.lda = g.one_chunk.lda; one.ldb = g.one_chunk.ldb;
             one.strideA = g.one_chunk.strideA; one.strideB = g.one_chunk.strideB;
+            one.strideA2 = g.one_chunk.strideA2; one.strideB2 = g.one_chunk.strideB2;
             one.k = g.one_chunk.k; one.vec_ok = g.one_chunk.vec_ok;
             set_chunk(one);
         }
@@ -321,7 +328,7 @@ __global__ void __launch_bounds__(256, 2) gemm_f32_dl_kernel(const GemmArgs g) {
     }
 
     // epilogue: lane holds row m = r32, columns n = 8 * (i / 4) + 4 * half + i % 4 of each 32 x 32 block
-    float* C = static_cast<float*>(task.C) + (int64_t)bat * task.strideC;
+    float* C = static_cast<float*>(task.C) + (int64_t)bat_lo * task.strideC + (int64_t)bat_hi * task.strideC2;
     const float alpha = task.partial ? 1.f : g.alpha, beta = task.partial ? 0.f : g.beta;
     // The beta term (C itself, or the tile of a residual input behind cin_off) is read for a whole row block
     // before the first store of that block: a load placed after a store to what may be the same tile has
