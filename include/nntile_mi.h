@@ -339,6 +339,23 @@ NNT_API int32_t nnt_gemm_res(nnt_ctx* ctx, float alpha, int32_t opA, nnt_tensor*
                      float beta, nnt_tensor* C, int32_t n_contract_axes, int32_t n_batch_axes, nnt_tensor* bias,
                      nnt_tensor* R);
 
+/* The per-head products of the attention layer (section 3, attention layer: K^T Q, V P and their four
+ * adjoint products, one per batch member and head) on tensors that keep the heads side by side along their
+ * first axis, as the linear layers around the attention produce and consume them, so that no copy into a
+ * per-head layout is needed.  C = alpha * op(A) . op(B), one contracted axis, batch axes (N_b, N_h).
+ * Each of A, B, C is given with a part number:
+ *   part >= 0: a tensor [n_parts * N_h * h, N_s, N_b]; its rows [part * N_h * h, (part + 1) * N_h * h) are
+ *              taken as [h, N_s, N_b, N_h] (row head * h + d is component d of that head).  Its row tiles
+ *              must hold whole heads (base % h == 0) and a part whole row tiles (N_h * h % base == 0), and all
+ *              its tiles must be present.  As C, only the rows of the part are written.
+ *   part < 0:  a tensor [., ., N_b, N_h] as nnt_gemm(n_contract_axes = 1, n_batch_axes = 2) takes it (the
+ *              scores and their adjoint); its head axis must be tiled in multiples of base / h heads.
+ * At least one part must be >= 0, and the tensors with parts share one row tiling.  Host pointers to
+ * descriptors; data stays where the tensors' tiles are.  The product is one launch whatever the context's
+ * granularity; its tasks are ordered by whole tensors.  Errors: NNT_EINVAL for geometry that does not fit. */
+NNT_API int32_t nnt_gemm_heads(nnt_ctx* ctx, float alpha, int32_t opA, nnt_tensor* A, int32_t partA, int32_t opB, nnt_tensor* B,
+                       int32_t partB, nnt_tensor* C, int32_t partC, int32_t h, int32_t N_h);
+
 NNT_API int32_t nnt_fill(nnt_ctx* ctx, float value, nnt_tensor* X);
 NNT_API int32_t nnt_add(nnt_ctx* ctx, float alpha, nnt_tensor* X, float beta, nnt_tensor* Y);
 NNT_API int32_t nnt_cast(nnt_ctx* ctx, nnt_tensor* X, nnt_tensor* Y);

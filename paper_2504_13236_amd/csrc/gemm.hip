@@ -458,8 +458,13 @@ SplitReduce add_slice_tasks(GemmPlan* P, const GemmTask& t0, const GemmWg& mw, c
     return r;
 }
 
+// `view_ld` (or nullptr): per operand (A, B, C) the leading dimension of a tensor that is a window on a tensor
+// with the heads side by side along its first axis (see nnt_gemm_heads), or 0 for an ordinary tensor.  With it
+// the two batch axes stay apart (batch member, head): GemmTask::nb1 and the second strides.
 int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B, nnt_tensor* C, int ncon, int nbat,
-                   nnt_tensor* bias, nnt_tensor* R, GemmPlan* P) {
+                   nnt_tensor* bias, nnt_tensor* R, GemmPlan* P, const int64_t* view_ld = nullptr) {
+    const bool pairs = view_ld != nullptr;
+    if (pairs && (nbat != 2 || ncon != 1 || bias || R)) return fail(ctx, NNT_EINVAL, "nnt_gemm_heads: unsupported form");
     const int na = A->ndim - nbat, nb = B->ndim - nbat;
     if (ncon < 1 || nbat < 0 || na < ncon || nb < ncon)
         return fail(ctx, NNT_EINVAL, "nnt_gemm: axis counts do not fit the operands");
@@ -528,8 +533,14 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
             if (delta % (ptrdiff_t)C->elem_size() != 0) return fail(ctx, NNT_EINVAL, "nnt_gemm_res: residual tile not aligned to the element size");
             t.cin_off = delta / (ptrdiff_t)C->elem_size();
         }
-        t.ldc = m;
-        t.strideC = m * n;
+        t.ldc = (pairs && view_ld[2]) ? view_ld[2] : m;
+        t.strideC = t.ldc * n;
+        int64_t nb1 = 0;
+        if (pairs) {
+            nb1 = C->tile_extent(nfa + nfb, cc[nfa + nfb]);         // batch members of the tile; the heads follow
+            t.nb1 = (int32_t)nb1;
+            t.strideC2 = view_ld[2] ? m : t.strideC * nb1;           // a window keeps head hl at rows hl * h .. of its tile
+        }
         t.m = (int32_t)m;
         t.n = (int32_t)n;
         t.chunk0 = (int32_t)P->chunks.size();
@@ -545,15 +556,21 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
             const int64_t ai = A->tile_index(ac), bi = B->tile_index(bc);
             if (!A->tiles[ai] || !B->tiles[bi]) continue;      // structural zeros: no contribution
             const int64_t k = prod_extent(A, ac, ax.a_con);
-            GemmChunk ch;
+            GemmChunk ch = {};
             ch.A = A->tiles[ai];
             ch.B = B->tiles[bi];
-            ch.lda = P->akf ? k : m;
-            ch.ldb = P->bkf ? k : n;
-            ch.strideA = m * k;
-            ch.strideB = k * n;
+            ch.lda = (pairs && view_ld[0]) ? view_ld[0] : (P->akf ? k : m);
+            ch.ldb = (pairs && view_ld[1]) ? view_ld[1] : (P->bkf ? k : n);
+            ch.strideA = ch.lda * (P->akf ? m : k);
+            ch.strideB = ch.ldb * (P->bkf ? n : k);
             ch.k = (int32_t)k;
-            ch.vec_ok = vec_flag(ch.A, ch.lda, ch.strideA, elem) | (vec_flag(ch.B, ch.ldb, ch.strideB, elem) << 1);
+            if (pairs) {
+                // the first axis of a window is the head size: m of A (k when A is read transposed), k of B (n when transposed)
+                ch.strideA2 = view_ld[0] ? (P->akf ? k : m) : ch.strideA * nb1;
+                ch.strideB2 = view_ld[1] ? (P->bkf ? k : n) : ch.strideB * nb1;
+            }
+            ch.vec_ok = (vec_flag(ch.A, ch.lda, ch.strideA, elem) && ch.strideA2 % (16 / elem) == 0 ? 1 : 0) |
+                        (vec_flag(ch.B, ch.ldb, ch.strideB, elem) && ch.strideB2 % (16 / elem) == 0 ? 2 : 0);
             P->chunks.push_back(ch);
             atl.push_back(ai);
             btl.push_back(bi);
@@ -822,34 +839,32 @@ extern "C" int32_t nnt_gemm(nnt_ctx* ctx, float alpha, int32_t opA, nnt_tensor* 
     return nnt_gemm_res(ctx, alpha, opA, A, opB, B, beta, C, ncon, nbat, bias, nullptr);
 }
 
-extern "C" int32_t nnt_gemm_res(nnt_ctx* ctx, float alpha, int32_t opA, nnt_tensor* A, int32_t opB, nnt_tensor* B,
-                                float beta, nnt_tensor* C, int32_t ncon, int32_t nbat, nnt_tensor* bias, nnt_tensor* R) {
-    NNT_CHECK_CTX(ctx);
-    if (!A || !B || !C) return fail(ctx, NNT_EINVAL, "nnt_gemm: null tensor");
-    if ((opA != NNT_OP_N && opA != NNT_OP_T) || (opB != NNT_OP_N && opB != NNT_OP_T))
-        return fail(ctx, NNT_EINVAL, "nnt_gemm: bad op");
-    if (R == C) R = nullptr;
-    if (R) {
-        if (R->dtype != C->dtype || !same_tiling(R, C)) return fail(ctx, NNT_EINVAL, "nnt_gemm_res: the residual input must have C's type, shape and tiling");
-        for (int64_t t = 0; t < C->ntiles; t++)
-            if (C->tiles[t] && !R->tiles[t]) return fail(ctx, NNT_EINVAL, "nnt_gemm_res: the residual input lacks a tile that C has");
-        if (R == A || R == B) return fail(ctx, NNT_EINVAL, "nnt_gemm_res: the residual input must not be an operand");
-    }
+namespace {
+
+// The product proper.  A, B, C give the geometry (ordinary tensors, or the windows of nnt_gemm_heads: then `view_ld`
+// and `key_extra` are set); `dep` are the tensors whose tiles order the tasks (the operands themselves, or what
+// the windows look at).
+int32_t gemm_core(nnt_ctx* ctx, float alpha, int32_t opA, nnt_tensor* A, int32_t opB, nnt_tensor* B, float beta, nnt_tensor* C,
+                  int32_t ncon, int32_t nbat, nnt_tensor* bias, nnt_tensor* R, nnt_tensor* const* dep, const int64_t* view_ld,
+                  const std::string& key_extra) {
     std::ostringstream key;
     key << opA << opB << ':' << A->id << ':' << B->id << ':' << C->id << ':' << (bias ? bias->id : 0) << ':' << ncon << ':' << nbat
-        << ':' << (R ? R->id : 0);
+        << ':' << (R ? R->id : 0) << key_extra;
     GemmPlan* P;
     auto it = ctx->gemm_plans.find(key.str());
     if (it == ctx->gemm_plans.end()) {
         if (ctx->capturing) return fail(ctx, NNT_ESTATE, "nnt_gemm: plan must exist before capture (run the call once first)");
         std::shared_ptr<GemmPlan> np(new GemmPlan());
-        int32_t rc = build_plan(ctx, opA, A, opB, B, C, ncon, nbat, bias, R, np.get());
+        int32_t rc = build_plan(ctx, opA, A, opB, B, C, ncon, nbat, bias, R, np.get(), view_ld);
         if (rc != NNT_OK) return rc;
         P = np.get();
         ctx->gemm_plans[key.str()] = np;
     } else {
         P = it->second.get();
     }
+    nnt_tensor* const dA = dep[0];
+    nnt_tensor* const dB = dep[1];
+    nnt_tensor* const dC = dep[2];
     OpTag tag(ctx, P->label.c_str(), P->flops, false);
     GemmArgs g = {};
     g.tasks = P->d_tasks;
@@ -857,8 +872,9 @@ extern "C" int32_t nnt_gemm_res(nnt_ctx* ctx, float alpha, int32_t opA, nnt_tens
     g.alpha = alpha;
     g.beta = beta;
     const int cmode = beta != 0.f ? kReadWrite : kWrite;
-    if (ctx->granularity == NNT_GRAN_OP) {
-        std::vector<Access> acc = {A->all(kRead), B->all(kRead), C->all(R ? kWrite : cmode)};
+    if (ctx->granularity == NNT_GRAN_OP || view_ld) {
+        // (a window writes some rows of every tile it touches and leaves the others: the tiles count as read too)
+        std::vector<Access> acc = {dA->all(kRead), dB->all(kRead), dC->all((view_ld && view_ld[2]) ? kReadWrite : (R ? kWrite : cmode))};
         if (bias) acc.push_back(bias->all(kRead));
         if (R && beta != 0.f) acc.push_back(R->all(kRead));
         g.wgs = P->d_wgs_op;
@@ -913,7 +929,128 @@ extern "C" int32_t nnt_gemm_res(nnt_ctx* ctx, float alpha, int32_t opA, nnt_tens
                 return launch_any(st, P->dtype_in, P->dtype_out, P->akf, P->bkf, P->cfg, gt, nwg, nfast, P->dl_ragged);
             });
         }
+
         if (rc != NNT_OK) return rc;
     }
     return NNT_OK;
+}
+
+// A window on `T` ([n_parts * N_h * h, N_s, N_b], the heads side by side along the first axis): rows
+// [part * N_h * h, (part + 1) * N_h * h) seen as [h, N_s, N_b, N_h].  Its tiles are T's own (one per group of
+// base[0] / h heads), addressed with T's leading dimension; nothing is copied.  Parts and groups of heads must
+// coincide with T's row tiles.
+int32_t make_window(nnt_ctx* ctx, nnt_tensor* T, int32_t part, int64_t h, int64_t N_h, nnt_tensor* W, int64_t* ld) {
+    const int64_t N_e = h * N_h, t0 = T->base[0];
+    if (T->ndim != 3 || part < 0 || T->shape[0] % N_e != 0 || (int64_t)(part + 1) * N_e > T->shape[0])
+        return fail(ctx, NNT_EINVAL, "nnt_gemm_heads: a window needs a 3-axis tensor of whole parts of N_h * h rows and a part inside it");
+    if (t0 % h != 0 || N_e % t0 != 0)
+        return fail(ctx, NNT_EINVAL, "nnt_gemm_heads: row tiles must hold whole heads and a part whole row tiles");
+    const int64_t hp = t0 / h;
+    W->ctx = ctx;
+    W->dtype = T->dtype;
+    W->ndim = 4;
+    const int64_t shape[4] = {h, T->shape[1], T->shape[2], N_h}, base[4] = {h, T->base[1], T->base[2], hp};
+    W->ntiles = 1;
+    for (int a = 0; a < 4; a++) {
+        W->shape[a] = shape[a];
+        W->base[a] = base[a];
+        W->grid[a] = (shape[a] + base[a] - 1) / base[a];
+        W->ntiles *= W->grid[a];
+    }
+    W->tiles.assign((size_t)W->ntiles, nullptr);
+    W->d_tiles = nullptr;
+    W->id = T->id;
+    for (int64_t i = 0; i < W->ntiles; i++) {
+        int64_t wc[kMaxDim], tc[kMaxDim] = {0, 0, 0, 0};
+        W->tile_coords(i, wc);
+        tc[0] = (int64_t)part * (N_e / t0) + wc[3];
+        tc[1] = wc[1];
+        tc[2] = wc[2];
+        W->tiles[(size_t)i] = T->tiles[(size_t)T->tile_index(tc)];
+        if (!W->tiles[(size_t)i]) return fail(ctx, NNT_EINVAL, "nnt_gemm_heads: a tensor with the heads side by side must hold all its tiles");
+    }
+    *ld = t0;
+    return NNT_OK;
+}
+
+// An ordinary tensor [., ., N_b, N_h] seen with `hp` heads per tile along its last axis (what the windows on the
+// other operands have): a tile of the coarser tiling is cut along its slowest axis, so the pieces are contiguous
+// and keep its strides.  Absent tiles stay absent.
+int32_t make_retiled(nnt_ctx* ctx, nnt_tensor* T, int64_t hp, nnt_tensor* W) {
+    if (T->ndim != 4 || T->base[3] % hp != 0)
+        return fail(ctx, NNT_EINVAL, "nnt_gemm_heads: the head axis of an ordinary operand must be tiled in multiples of the heads per row tile");
+    *W = *T;                           // geometry, type, id
+    W->deps.clear();
+    W->d_tiles = nullptr;
+    W->base[3] = hp;
+    W->grid[3] = (T->shape[3] + hp - 1) / hp;
+    W->ntiles = W->grid[0] * W->grid[1] * W->grid[2] * W->grid[3];
+    W->tiles.assign((size_t)W->ntiles, nullptr);
+    for (int64_t i = 0; i < W->ntiles; i++) {
+        int64_t wc[kMaxDim], tc[kMaxDim];
+        W->tile_coords(i, wc);
+        for (int a = 0; a < 3; a++) tc[a] = wc[a];
+        tc[3] = wc[3] * hp / T->base[3];
+        char* basep = static_cast<char*>(T->tiles[(size_t)T->tile_index(tc)]);
+        if (!basep) continue;
+        const int64_t first = wc[3] * hp - tc[3] * T->base[3];           // heads of the coarse tile before this piece
+        const int64_t per_head = T->tile_extent(0, tc[0]) * T->tile_extent(1, tc[1]) * T->tile_extent(2, tc[2]);
+        W->tiles[(size_t)i] = basep + first * per_head * T->elem_size();
+    }
+    return NNT_OK;
+}
+
+}  // namespace
+
+extern "C" int32_t nnt_gemm_res(nnt_ctx* ctx, float alpha, int32_t opA, nnt_tensor* A, int32_t opB, nnt_tensor* B,
+                                float beta, nnt_tensor* C, int32_t ncon, int32_t nbat, nnt_tensor* bias, nnt_tensor* R) {
+    NNT_CHECK_CTX(ctx);
+    if (!A || !B || !C) return fail(ctx, NNT_EINVAL, "nnt_gemm: null tensor");
+    if ((opA != NNT_OP_N && opA != NNT_OP_T) || (opB != NNT_OP_N && opB != NNT_OP_T))
+        return fail(ctx, NNT_EINVAL, "nnt_gemm: bad op");
+    if (R == C) R = nullptr;
+    if (R) {
+        if (R->dtype != C->dtype || !same_tiling(R, C)) return fail(ctx, NNT_EINVAL, "nnt_gemm_res: the residual input must have C's type, shape and tiling");
+        for (int64_t t = 0; t < C->ntiles; t++)
+            if (C->tiles[t] && !R->tiles[t]) return fail(ctx, NNT_EINVAL, "nnt_gemm_res: the residual input lacks a tile that C has");
+        if (R == A || R == B) return fail(ctx, NNT_EINVAL, "nnt_gemm_res: the residual input must not be an operand");
+    }
+    nnt_tensor* const dep[3] = {A, B, C};
+    return gemm_core(ctx, alpha, opA, A, opB, B, beta, C, ncon, nbat, bias, R, dep, nullptr, std::string());
+}
+
+extern "C" int32_t nnt_gemm_heads(nnt_ctx* ctx, float alpha, int32_t opA, nnt_tensor* A, int32_t partA, int32_t opB, nnt_tensor* B,
+                                  int32_t partB, nnt_tensor* C, int32_t partC, int32_t h, int32_t N_h) {
+    NNT_CHECK_CTX(ctx);
+    if (!A || !B || !C) return fail(ctx, NNT_EINVAL, "nnt_gemm_heads: null tensor");
+    if ((opA != NNT_OP_N && opA != NNT_OP_T) || (opB != NNT_OP_N && opB != NNT_OP_T) || h < 1 || N_h < 1)
+        return fail(ctx, NNT_EINVAL, "nnt_gemm_heads: bad argument");
+    nnt_tensor win[3];
+    nnt_tensor* geo[3] = {A, B, C};
+    nnt_tensor* const dep[3] = {A, B, C};
+    const int32_t part[3] = {partA, partB, partC};
+    int64_t view_ld[3] = {0, 0, 0};
+    std::ostringstream extra;
+    extra << ":heads" << h << 'x' << N_h;
+    int64_t hp = 0;
+    for (int i = 0; i < 3; i++) {
+        extra << ':' << part[i];
+        if (part[i] < 0) continue;
+        int32_t rc = make_window(ctx, dep[i], part[i], h, N_h, &win[i], &view_ld[i]);
+        if (rc != NNT_OK) return rc;
+        geo[i] = &win[i];
+        if (hp && hp != win[i].base[3]) return fail(ctx, NNT_EINVAL, "nnt_gemm_heads: the tensors with parts must have one row tiling");
+        hp = win[i].base[3];
+    }
+    if (!hp) return fail(ctx, NNT_EINVAL, "nnt_gemm_heads: no operand has a part (use nnt_gemm)");
+    for (int i = 0; i < 3; i++) {
+        if (part[i] >= 0) continue;
+        if (dep[i]->ndim != 4 || dep[i]->shape[3] != N_h)
+            return fail(ctx, NNT_EINVAL, "nnt_gemm_heads: tensors without a part must have the axes [., ., N_b, N_h]");
+        if (dep[i]->base[3] == hp) continue;
+        int32_t rc = make_retiled(ctx, dep[i], hp, &win[i]);
+        if (rc != NNT_OK) return rc;
+        geo[i] = &win[i];
+    }
+    return gemm_core(ctx, alpha, opA, geo[0], opB, geo[1], 0.f, geo[2], 1, 2, nullptr, nullptr, dep, view_ld, extra.str());
 }

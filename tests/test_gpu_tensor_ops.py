@@ -504,6 +504,68 @@ def test_head_split_merge(mods, gran, dtype, zb, pb):
 
 
 @pytest.mark.parametrize("gran", GRANS)
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("geom", [(64, 6, 128, 100, 40, 3, 2, 6),      # h, N_h, row tile, N_s, seq tile, N_b, batch tile, head tile of the scores
+                                  (64, 4, 256, 96, 96, 2, 2, 4),
+                                  (128, 4, 256, 72, 24, 1, 1, 2),
+                                  (16, 8, 32, 50, 50, 2, 1, 8)])
+def test_attention_products_on_tensors_with_the_heads_side_by_side(mods, gran, dtype, geom):
+    """The six per-head products of the attention layer read Q, K, V and dB straight out of, and write B, dQ, dK,
+    dV straight into, tensors [parts * N_h * h, N_s, N_b] (what the linear layers produce and consume): against
+    the oracle's head split, batched contraction and head merge.  Scores with causal structure (absent tiles) and
+    a head axis tiled coarser than the windows; rows of a result tensor outside the written part keep their values."""
+    capi, tiled = mods
+    h, N_h, t0, N_s, ts, N_b, tb, tjP = geom
+    N_e = h * N_h
+    r = rng(sum(geom))
+    QKV = quant(r.standard_normal((3 * N_e, N_s, N_b)), dtype)
+    dBm = quant(r.standard_normal((N_e, N_s, N_b)), dtype)
+    Q, K, V = D.split_heads(QKV, N_h, 3)
+    dB = D.split_heads(dBm, N_h, 1)[0]
+    sc = 1.0 / math.sqrt(h)
+    with tiled.Context(n_streams=4, granularity=gran) as ctx:
+        tQKV = T(tiled, ctx, QKV, (t0, ts, tb), dtype)
+        tdBm = T(tiled, ctx, dBm, (t0, ts, tb), dtype)
+        sb = (ts, ts, tb, tjP)
+        absent = tiled.causal_absent(ts, ts, N_s)
+        tP = tiled.TiledTensor(ctx, dtype, (N_s, N_s, N_b, N_h), sb, absent)
+        tS = tiled.TiledTensor(ctx, "f32", (2, N_s, N_b, N_h), (2, ts, tb, tjP))
+        capi.nnt_gemm_heads(ctx.h, sc, 1, tQKV.h, 1, 0, tQKV.h, 0, tP.h, -1, h, N_h)           # K^T Q
+        capi.nnt_softmax_fwd(ctx.h, tP.h, tS.h, 1.0, 1)
+        A = D.attention_scores(K, Q)
+        if dtype == "bf16":
+            A = quant(A, dtype)
+        Pref, _, _ = D.softmax_fwd(A, causal=True)
+        P = tP.download().astype(np.float64)
+        check(P, Pref, dtype, "softmax(K^T Q)")
+        marker = quant(r.standard_normal((2 * N_e, N_s, N_b)), dtype)
+        tBm = T(tiled, ctx, marker, (t0, ts, tb), dtype)                                       # B goes into part 1 of two
+        capi.nnt_gemm_heads(ctx.h, 1.0, 0, tQKV.h, 2, 0, tP.h, -1, tBm.h, 1, h, N_h)           # V P
+        got = tBm.download()
+        check(got[N_e:], D.merge_heads([D.attention_values(V, P)]), dtype, "V P")
+        np.testing.assert_array_equal(got[:N_e], marker[:N_e].astype(np.float32))
+        tdP = tiled.TiledTensor(ctx, dtype, (N_s, N_s, N_b, N_h), sb, absent)
+        tdQKV = tiled.TiledTensor(ctx, dtype, QKV.shape, (t0, ts, tb))
+        capi.nnt_gemm_heads(ctx.h, 1.0, 0, tdBm.h, 0, 1, tP.h, -1, tdQKV.h, 2, h, N_h)         # dV = dB P^T
+        capi.nnt_gemm_heads(ctx.h, 1.0, 1, tQKV.h, 2, 0, tdBm.h, 0, tdP.h, -1, h, N_h)         # dP = V^T dB
+        dPdev = tdP.download().astype(np.float64)
+        capi.nnt_softmax_bwd(ctx.h, tP.h, tdP.h)
+        dA = tdP.download().astype(np.float64)
+        check(dA, D.softmax_bwd(P, dPdev), dtype, "softmax bwd")
+        capi.nnt_gemm_heads(ctx.h, sc, 0, tQKV.h, 1, 0, tdP.h, -1, tdQKV.h, 0, h, N_h)         # dQ = K dA
+        capi.nnt_gemm_heads(ctx.h, sc, 0, tQKV.h, 0, 1, tdP.h, -1, tdQKV.h, 1, h, N_h)         # dK = Q dA^T
+        ref = D.merge_heads([D.contract(sc, "N", K, "N", dA, 0.0, None, 1, 2), D.contract(sc, "N", Q, "T", dA, 0.0, None, 1, 2),
+                             D.contract(1.0, "N", dB, "T", P, 0.0, None, 1, 2)])
+        got = tdQKV.download()
+        for part, name in enumerate(("dQ = K dA / sqrt(h)", "dK = Q dA^T / sqrt(h)", "dV = dB P^T")):
+            check(got[part * N_e:(part + 1) * N_e], ref[part * N_e:(part + 1) * N_e], dtype, name)
+        # geometry that does not fit is refused and leaves the context usable
+        assert capi.nnt_gemm_heads.raw(ctx.h, 1.0, 0, tQKV.h, 3, 0, tP.h, -1, tBm.h, 1, h, N_h) == capi.NNT_EINVAL
+        assert capi.nnt_gemm_heads.raw(ctx.h, 1.0, 0, tP.h, -1, 0, tP.h, -1, tP.h, -1, h, N_h) == capi.NNT_EINVAL
+        ctx.wait()
+
+
+@pytest.mark.parametrize("gran", GRANS)
 @pytest.mark.parametrize("lowp", [False, True])
 def test_adam_tensor(mods, gran, lowp):
     capi, tiled = mods
