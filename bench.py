@@ -486,7 +486,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=2, help="workload number 1..5 (default: the fp32 GPT-2-small-shaped block)")
-    ap.add_argument("--streams", type=int, default=4)
+    ap.add_argument("--streams", type=int, default=2)
     ap.add_argument("--granularity", choices=["op", "tile"], default="op")
     ap.add_argument("--graph", action="store_true", help="replay the step from a captured HIP graph")
     ap.add_argument("--blocks", type=int, default=1, help="chain this many identical blocks into one flow of tasks")

@@ -143,7 +143,9 @@ NNT_API int32_t nnt_profile_read(nnt_ctx* ctx, nnt_profile_entry* out, int32_t c
  * submitted in sequence and run asynchronously, ordered only by their data): for
  * n_tasks tasks over n_tiles tiles -- task t accesses the tiles
  * acc_tile[task_first[t] .. task_first[t+1]-1] with the modes acc_mode[...]
- * (1 read, 2 write, 3 read-write) -- reports the stream each task would run on, its
+ * (1 read, 2 write, 3 read-write, 6 + 256 * p write of part p of the tile: writers of
+ * different parts of a tile are not ordered among themselves, as the attention products
+ * that write the rows of Q, K and V inside one tensor) -- reports the stream each task would run on, its
  * sequence number on that stream, and per task NNT_MAX_STREAMS entries: the sequence
  * number on every other stream that it would wait for (0 = none).  Uses the same
  * code as the executor, touches no device: it lets a test check on the CPU that

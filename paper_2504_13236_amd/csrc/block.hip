@@ -200,6 +200,18 @@ static int32_t linear_bwd(nnt_gpt2_block* b, nnt_tensor* W, nnt_tensor* X, nnt_t
     return nnt_gemm(ctx, 1.f, NNT_OP_T, W, NNT_OP_N, dY, 0.f, dX, 1, 0, nullptr);
 }
 
+// Whether the attention products read and write the tensors of the linear layers directly (nnt_gemm_heads)
+// instead of per-head copies: whole-operation launches, the products as separate operations, and row tiles that
+// hold whole heads and divide the embedding size.  (NNT_BLOCK_HEAD_COPIES=1 keeps the copies: a measuring aid.)
+static bool head_windows(const nnt_gpt2_block* b) {
+    static const bool copies = getenv("NNT_BLOCK_HEAD_COPIES") != nullptr;
+    const nnt_gpt2_block_cfg& c = b->cfg;
+    if (copies || c.fused_attention || b->ctx->granularity != NNT_GRAN_OP) return false;
+    const int64_t h = c.N_e / c.N_h, t0 = b->s[NNT_BLK_QKV]->base[0];
+    return t0 % h == 0 && c.N_e % t0 == 0 && b->s[NNT_BLK_BM]->base[0] == t0 && b->s[NNT_BLK_DBM]->base[0] == t0 &&
+           b->s[NNT_BLK_DQKV]->base[0] == t0;
+}
+
 int32_t nnt_gpt2_block_forward(nnt_gpt2_block* b, nnt_tensor* X, nnt_tensor* Out) {
     if (!b) return NNT_EINVAL;
     nnt_ctx* ctx = b->ctx;
@@ -213,17 +225,25 @@ int32_t nnt_gpt2_block_forward(nnt_gpt2_block* b, nnt_tensor* X, nnt_tensor* Out
     b->X = X;
     TRY(nnt_layernorm_fwd(ctx, X, s[NNT_BLK_GAMMA1], s[NNT_BLK_BETA1], c.eps, s[NNT_BLK_X1], s[NNT_BLK_STATS1]));
     TRY(linear(b, weight(b, NNT_BLK_W_QKV), s[NNT_BLK_X1], s[NNT_BLK_B_QKV], s[NNT_BLK_QKV]));
-    nnt_tensor* qkv[3] = {s[NNT_BLK_Q], s[NNT_BLK_K], s[NNT_BLK_V]};
-    TRY(nnt_head_split(ctx, s[NNT_BLK_QKV], 3, qkv));
-    if (c.fused_attention) {
-        TRY(nnt_attention_fwd(ctx, s[NNT_BLK_Q], s[NNT_BLK_K], s[NNT_BLK_V], sc, c.causal, s[NNT_BLK_BH], s[NNT_BLK_SM_STATS]));
-    } else {
-        TRY(nnt_gemm(ctx, sc, NNT_OP_T, s[NNT_BLK_K], NNT_OP_N, s[NNT_BLK_Q], 0.f, s[NNT_BLK_P], 1, 2, nullptr));
+    if (head_windows(b)) {
+        // parts 0, 1, 2 of the QKV rows are Q, K, V; the heads' results go straight into Bm
+        const int32_t h = (int32_t)(c.N_e / c.N_h), N_h = (int32_t)c.N_h;
+        TRY(nnt_gemm_heads(ctx, sc, NNT_OP_T, s[NNT_BLK_QKV], 1, NNT_OP_N, s[NNT_BLK_QKV], 0, s[NNT_BLK_P], -1, h, N_h));
         TRY(nnt_softmax_fwd(ctx, s[NNT_BLK_P], s[NNT_BLK_SM_STATS], 1.f, c.causal));
-        TRY(nnt_gemm(ctx, 1.f, NNT_OP_N, s[NNT_BLK_V], NNT_OP_N, s[NNT_BLK_P], 0.f, s[NNT_BLK_BH], 1, 2, nullptr));
+        TRY(nnt_gemm_heads(ctx, 1.f, NNT_OP_N, s[NNT_BLK_QKV], 2, NNT_OP_N, s[NNT_BLK_P], -1, s[NNT_BLK_BM], 0, h, N_h));
+    } else {
+        nnt_tensor* qkv[3] = {s[NNT_BLK_Q], s[NNT_BLK_K], s[NNT_BLK_V]};
+        TRY(nnt_head_split(ctx, s[NNT_BLK_QKV], 3, qkv));
+        if (c.fused_attention) {
+            TRY(nnt_attention_fwd(ctx, s[NNT_BLK_Q], s[NNT_BLK_K], s[NNT_BLK_V], sc, c.causal, s[NNT_BLK_BH], s[NNT_BLK_SM_STATS]));
+        } else {
+            TRY(nnt_gemm(ctx, sc, NNT_OP_T, s[NNT_BLK_K], NNT_OP_N, s[NNT_BLK_Q], 0.f, s[NNT_BLK_P], 1, 2, nullptr));
+            TRY(nnt_softmax_fwd(ctx, s[NNT_BLK_P], s[NNT_BLK_SM_STATS], 1.f, c.causal));
+            TRY(nnt_gemm(ctx, 1.f, NNT_OP_N, s[NNT_BLK_V], NNT_OP_N, s[NNT_BLK_P], 0.f, s[NNT_BLK_BH], 1, 2, nullptr));
+        }
+        nnt_tensor* bh[1] = {s[NNT_BLK_BH]};
+        TRY(nnt_head_merge(ctx, 1, bh, s[NNT_BLK_BM]));
     }
-    nnt_tensor* bh[1] = {s[NNT_BLK_BH]};
-    TRY(nnt_head_merge(ctx, 1, bh, s[NNT_BLK_BM]));
     TRY(linear(b, weight(b, NNT_BLK_W_O), s[NNT_BLK_BM], s[NNT_BLK_B_O], s[NNT_BLK_X2], X));      // X2 = X + W_o Bm +. b_o
     TRY(nnt_layernorm_fwd(ctx, s[NNT_BLK_X2], s[NNT_BLK_GAMMA2], s[NNT_BLK_BETA2], c.eps, s[NNT_BLK_X3], s[NNT_BLK_STATS2]));
     TRY(linear(b, weight(b, NNT_BLK_W_1), s[NNT_BLK_X3], s[NNT_BLK_B_1], s[NNT_BLK_H1]));
@@ -252,21 +272,32 @@ int32_t nnt_gpt2_block_backward(nnt_gpt2_block* b, nnt_tensor* dOut, nnt_tensor*
                           g[NNT_BLK_GAMMA2], g[NNT_BLK_BETA2]));
     // attention output projection
     TRY(linear_bwd(b, weight(b, NNT_BLK_W_O), s[NNT_BLK_BM], s[NNT_BLK_DX2], s[NNT_BLK_DBM], g[NNT_BLK_W_O], g[NNT_BLK_B_O]));
-    nnt_tensor* dbh[1] = {s[NNT_BLK_DBH]};
-    TRY(nnt_head_split(ctx, s[NNT_BLK_DBM], 1, dbh));
-    if (c.fused_attention) {
-        TRY(nnt_attention_bwd(ctx, s[NNT_BLK_Q], s[NNT_BLK_K], s[NNT_BLK_V], s[NNT_BLK_BH], s[NNT_BLK_SM_STATS], s[NNT_BLK_DBH],
-                              sc, c.causal, s[NNT_BLK_DQ], s[NNT_BLK_DK], s[NNT_BLK_DV]));
-    } else {
-        // dV = dB P^T, dP = V^T dB, softmax adjoint, dQ = K dA / sqrt(h), dK = Q dA^T / sqrt(h)
-        TRY(nnt_gemm(ctx, 1.f, NNT_OP_N, s[NNT_BLK_DBH], NNT_OP_T, s[NNT_BLK_P], 0.f, s[NNT_BLK_DV], 1, 2, nullptr));
-        TRY(nnt_gemm(ctx, 1.f, NNT_OP_T, s[NNT_BLK_V], NNT_OP_N, s[NNT_BLK_DBH], 0.f, s[NNT_BLK_DP], 1, 2, nullptr));
+    if (head_windows(b)) {
+        // dV = dB P^T, dP = V^T dB, softmax adjoint, dQ = K dA / sqrt(h), dK = Q dA^T / sqrt(h): dB is read out of dBm,
+        // the three results are the parts of dQKV
+        const int32_t h = (int32_t)(c.N_e / c.N_h), N_h = (int32_t)c.N_h;
+        TRY(nnt_gemm_heads(ctx, 1.f, NNT_OP_N, s[NNT_BLK_DBM], 0, NNT_OP_T, s[NNT_BLK_P], -1, s[NNT_BLK_DQKV], 2, h, N_h));
+        TRY(nnt_gemm_heads(ctx, 1.f, NNT_OP_T, s[NNT_BLK_QKV], 2, NNT_OP_N, s[NNT_BLK_DBM], 0, s[NNT_BLK_DP], -1, h, N_h));
         TRY(nnt_softmax_bwd(ctx, s[NNT_BLK_P], s[NNT_BLK_DP]));
-        TRY(nnt_gemm(ctx, sc, NNT_OP_N, s[NNT_BLK_K], NNT_OP_N, s[NNT_BLK_DP], 0.f, s[NNT_BLK_DQ], 1, 2, nullptr));
-        TRY(nnt_gemm(ctx, sc, NNT_OP_N, s[NNT_BLK_Q], NNT_OP_T, s[NNT_BLK_DP], 0.f, s[NNT_BLK_DK], 1, 2, nullptr));
+        TRY(nnt_gemm_heads(ctx, sc, NNT_OP_N, s[NNT_BLK_QKV], 1, NNT_OP_N, s[NNT_BLK_DP], -1, s[NNT_BLK_DQKV], 0, h, N_h));
+        TRY(nnt_gemm_heads(ctx, sc, NNT_OP_N, s[NNT_BLK_QKV], 0, NNT_OP_T, s[NNT_BLK_DP], -1, s[NNT_BLK_DQKV], 1, h, N_h));
+    } else {
+        nnt_tensor* dbh[1] = {s[NNT_BLK_DBH]};
+        TRY(nnt_head_split(ctx, s[NNT_BLK_DBM], 1, dbh));
+        if (c.fused_attention) {
+            TRY(nnt_attention_bwd(ctx, s[NNT_BLK_Q], s[NNT_BLK_K], s[NNT_BLK_V], s[NNT_BLK_BH], s[NNT_BLK_SM_STATS], s[NNT_BLK_DBH],
+                                  sc, c.causal, s[NNT_BLK_DQ], s[NNT_BLK_DK], s[NNT_BLK_DV]));
+        } else {
+            // dV = dB P^T, dP = V^T dB, softmax adjoint, dQ = K dA / sqrt(h), dK = Q dA^T / sqrt(h)
+            TRY(nnt_gemm(ctx, 1.f, NNT_OP_N, s[NNT_BLK_DBH], NNT_OP_T, s[NNT_BLK_P], 0.f, s[NNT_BLK_DV], 1, 2, nullptr));
+            TRY(nnt_gemm(ctx, 1.f, NNT_OP_T, s[NNT_BLK_V], NNT_OP_N, s[NNT_BLK_DBH], 0.f, s[NNT_BLK_DP], 1, 2, nullptr));
+            TRY(nnt_softmax_bwd(ctx, s[NNT_BLK_P], s[NNT_BLK_DP]));
+            TRY(nnt_gemm(ctx, sc, NNT_OP_N, s[NNT_BLK_K], NNT_OP_N, s[NNT_BLK_DP], 0.f, s[NNT_BLK_DQ], 1, 2, nullptr));
+            TRY(nnt_gemm(ctx, sc, NNT_OP_N, s[NNT_BLK_Q], NNT_OP_T, s[NNT_BLK_DP], 0.f, s[NNT_BLK_DK], 1, 2, nullptr));
+        }
+        nnt_tensor* dqkv[3] = {s[NNT_BLK_DQ], s[NNT_BLK_DK], s[NNT_BLK_DV]};
+        TRY(nnt_head_merge(ctx, 3, dqkv, s[NNT_BLK_DQKV]));
     }
-    nnt_tensor* dqkv[3] = {s[NNT_BLK_DQ], s[NNT_BLK_DK], s[NNT_BLK_DV]};
-    TRY(nnt_head_merge(ctx, 3, dqkv, s[NNT_BLK_DQKV]));
     TRY(linear_bwd(b, weight(b, NNT_BLK_W_QKV), s[NNT_BLK_X1], s[NNT_BLK_DQKV], s[NNT_BLK_DX1], g[NNT_BLK_W_QKV], g[NNT_BLK_B_QKV]));
     // first layer norm; the residual branch adds dX2
     return nnt_layernorm_bwd(ctx, b->X, s[NNT_BLK_STATS1], s[NNT_BLK_GAMMA1], s[NNT_BLK_DX1], s[NNT_BLK_DX2], dX,

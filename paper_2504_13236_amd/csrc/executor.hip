@@ -130,6 +130,9 @@ static TaskPlan plan_task(const std::vector<Access>& acc, int ns, int ns_all, bo
         for (int64_t i = 0; i < a.count; i++) {
             const TileDep& d = a.first[i];
             if (d.w_stream >= 0) need[d.w_stream] = std::max(need[d.w_stream], d.w_seq);
+            // writers of parts: everybody comes after them, except a writer of another part
+            for (int s = 0; s < ns_all; s++)
+                if (d.p_seq[s] && !(a.mode == kWritePart && d.p_part[s] != a.part && !d.p_mixed[s])) need[s] = std::max(need[s], d.p_seq[s]);
             if (a.mode & kWrite)
                 for (int s = 0; s < ns_all; s++) need[s] = std::max(need[s], d.r_seq[s]);
         }
@@ -168,10 +171,18 @@ static void commit_task(const std::vector<Access>& acc, int chosen, uint64_t seq
     for (const Access& a : acc) {
         for (int64_t i = 0; i < a.count; i++) {
             TileDep& d = a.first[i];
-            if (a.mode & kWrite) {
+            if (a.mode == kWritePart) {
+                // (the readers it has waited for stay on record: a later writer waits for them once more)
+                if (d.p_seq[chosen] && d.p_part[chosen] != a.part) d.p_mixed[chosen] = 1;
+                d.p_seq[chosen] = seq;
+                d.p_part[chosen] = a.part;
+            } else if (a.mode & kWrite) {
                 d.w_stream = chosen;
                 d.w_seq = seq;
                 std::memset(d.r_seq, 0, sizeof(d.r_seq));
+                std::memset(d.p_seq, 0, sizeof(d.p_seq));
+                std::memset(d.p_part, 0, sizeof(d.p_part));
+                std::memset(d.p_mixed, 0, sizeof(d.p_mixed));
             } else {
                 d.r_seq[chosen] = seq;
             }
@@ -296,8 +307,11 @@ int32_t nnt_sched_simulate(int32_t n_streams, int32_t serial, int32_t n_tiles, i
     for (int t = 0; t < n_tasks; t++) {
         std::vector<Access> acc;
         for (int i = task_first[t]; i < task_first[t + 1]; i++) {
-            if (acc_tile[i] < 0 || acc_tile[i] >= n_tiles || acc_mode[i] < kRead || acc_mode[i] > kReadWrite) return NNT_EINVAL;
-            acc.push_back(Access{&tiles[(size_t)acc_tile[i]], 1, acc_mode[i]});
+            const int mode = acc_mode[i] & 0xff, part = acc_mode[i] >> 8;
+            if (acc_tile[i] < 0 || acc_tile[i] >= n_tiles || acc_mode[i] < 0 || !((mode >= kRead && mode <= kReadWrite) || mode == kWritePart) ||
+                (mode != kWritePart && part != 0))
+                return NNT_EINVAL;
+            acc.push_back(Access{&tiles[(size_t)acc_tile[i]], 1, mode, part});
         }
         const TaskPlan plan = plan_task(acc, n_streams, n_streams, serial != 0, tail, synced, waited, &rr);
         // the waits as the executor would issue them: on the first recorded event that covers the

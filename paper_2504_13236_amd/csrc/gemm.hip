@@ -846,7 +846,7 @@ namespace {
 // the windows look at).
 int32_t gemm_core(nnt_ctx* ctx, float alpha, int32_t opA, nnt_tensor* A, int32_t opB, nnt_tensor* B, float beta, nnt_tensor* C,
                   int32_t ncon, int32_t nbat, nnt_tensor* bias, nnt_tensor* R, nnt_tensor* const* dep, const int64_t* view_ld,
-                  const std::string& key_extra) {
+                  const std::string& key_extra, int32_t part_c = 0) {
     std::ostringstream key;
     key << opA << opB << ':' << A->id << ':' << B->id << ':' << C->id << ':' << (bias ? bias->id : 0) << ':' << ncon << ':' << nbat
         << ':' << (R ? R->id : 0) << key_extra;
@@ -873,8 +873,9 @@ int32_t gemm_core(nnt_ctx* ctx, float alpha, int32_t opA, nnt_tensor* A, int32_t
     g.beta = beta;
     const int cmode = beta != 0.f ? kReadWrite : kWrite;
     if (ctx->granularity == NNT_GRAN_OP || view_ld) {
-        // (a window writes some rows of every tile it touches and leaves the others: the tiles count as read too)
-        std::vector<Access> acc = {dA->all(kRead), dB->all(kRead), dC->all((view_ld && view_ld[2]) ? kReadWrite : (R ? kWrite : cmode))};
+        // (a window writes the rows of its part in every tile it touches and leaves the others)
+        std::vector<Access> acc = {dA->all(kRead), dB->all(kRead), dC->all((view_ld && view_ld[2]) ? kWritePart : (R ? kWrite : cmode))};
+        acc[2].part = part_c;
         if (bias) acc.push_back(bias->all(kRead));
         if (R && beta != 0.f) acc.push_back(R->all(kRead));
         g.wgs = P->d_wgs_op;
@@ -1052,5 +1053,5 @@ extern "C" int32_t nnt_gemm_heads(nnt_ctx* ctx, float alpha, int32_t opA, nnt_te
         if (rc != NNT_OK) return rc;
         geo[i] = &win[i];
     }
-    return gemm_core(ctx, alpha, opA, geo[0], opB, geo[1], 0.f, geo[2], 1, 2, nullptr, nullptr, dep, view_ld, extra.str());
+    return gemm_core(ctx, alpha, opA, geo[0], opB, geo[1], 0.f, geo[2], 1, 2, nullptr, nullptr, dep, view_ld, extra.str(), partC > 0 ? partC : 0);
 }

@@ -34,14 +34,23 @@ struct TileDep {
     int32_t w_stream = -1;
     uint64_t w_seq = 0;
     uint64_t r_seq[kMaxStreams] = {0, 0, 0, 0, 0, 0, 0, 0};
+    // writers of parts of the tile (kWritePart) since the last writer of all of it: per stream the last one's
+    // sequence number and part, and whether that stream has had writers of different parts
+    uint64_t p_seq[kMaxStreams] = {0, 0, 0, 0, 0, 0, 0, 0};
+    int32_t p_part[kMaxStreams] = {0, 0, 0, 0, 0, 0, 0, 0};
+    uint8_t p_mixed[kMaxStreams] = {0, 0, 0, 0, 0, 0, 0, 0};
 };
 
-enum AccessMode { kRead = 1, kWrite = 2, kReadWrite = 3 };
+// kWritePart: the task writes the part `Access::part` of every tile it names and leaves the rest of the tile as
+// it is (the attention products that write the rows of Q, K or V inside one tensor).  Writers of different parts
+// are not ordered among themselves; towards everything else each of them is a writer.
+enum AccessMode { kRead = 1, kWrite = 2, kReadWrite = 3, kWritePart = 6 };
 
 struct Access {
     TileDep* first;
     int64_t count;
     int mode;
+    int32_t part = 0;
 };
 
 struct GemmPlan;

@@ -208,7 +208,8 @@ def test_executor_orders_every_conflicting_pair(capi, n_streams):
         for _ in range(n_tasks):
             k = int(r.integers(1, min(4, n_tiles) + 1))
             chosen = r.choice(n_tiles, size=k, replace=False)
-            tasks.append([(int(t), int(r.choice([1, 1, 2, 3]))) for t in chosen])
+            # modes: read, write, read-write, and writes of part 0, 1 or 2 of the tile (6 + 256 * part)
+            tasks.append([(int(t), int(r.choice([1, 1, 2, 3, 6, 6 + 256, 6 + 512]))) for t in chosen])
         stream, seq, waits = _simulate(capi, n_streams, 0, n_tiles, tasks)
         assert stream.min() >= 0 and stream.max() < n_streams
         at = {(int(stream[t]), int(seq[t])): t for t in range(n_tasks)}
@@ -236,11 +237,38 @@ def test_executor_orders_every_conflicting_pair(capi, n_streams):
             for i in range(j):
                 for ti, mi in tasks[i]:
                     for tj, mj in tasks[j]:
-                        if ti == tj and ((mi | mj) & 2):
+                        # writers of different parts of a tile do not conflict; everything else with a writer does
+                        parts_apart = (mi & 0xff) == 6 and (mj & 0xff) == 6 and mi != mj
+                        if ti == tj and ((mi | mj) & 2) and not parts_apart:
                             assert i in before[j], (trial, i, j, tasks[i], tasks[j])
     # serial mode keeps everything on one stream
     stream, seq, waits = _simulate(capi, n_streams, 1, 3, [[(0, 2)], [(1, 2)], [(0, 1), (1, 1)], [(2, 3)]])
     assert not stream.any() and not waits.any()
+
+
+def test_executor_lets_writers_of_different_parts_overlap(capi):
+    """Three tasks write parts 0, 1, 2 of the same tiles (the attention products that fill the rows of Q, K and V of
+    one tensor): they land on different streams and wait for nothing but the tensor's previous writer; a reader
+    after them waits for all three; a second writer of part 1 waits for that reader, not for the other parts."""
+    W, P0, P1, P2, R = 2, 6, 6 + 256, 6 + 512, 1
+    tasks = [[(0, W), (1, W)], [(0, P0), (1, P0)], [(0, P1), (1, P1)], [(0, P2), (1, P2)], [(0, R), (1, R)], [(0, P1), (1, P1)]]
+    stream, seq, waits = _simulate(capi, 4, 0, 2, tasks)
+    assert len({int(stream[t]) for t in (1, 2, 3)}) == 3                       # the three part writers run side by side
+    for t in (1, 2, 3):
+        # (a wait names the first recorded event that covers the task asked for, so only its stream is checked)
+        others = [o for o in range(8) if waits[t, o]]
+        assert all(o == stream[0] for o in others) and (others or stream[t] == stream[0])
+    covered = {int(stream[4])} | {o for o in range(8) if waits[4, o]}
+    assert {int(stream[t]) for t in (1, 2, 3)} <= covered                      # the reader comes after every part writer
+    assert stream[5] == stream[4] or waits[5, int(stream[4])] >= seq[4]         # the next writer of part 1 comes after the reader
+    # a part number on a mode other than 6 is refused
+    import numpy as np
+    import ctypes as C
+    bad = np.array([1 + 256], np.int32)
+    tf, at = np.array([0, 1], np.int32), np.array([0], np.int32)
+    so, sq, wo = np.zeros(1, np.int32), np.zeros(1, np.int64), np.zeros(8, np.int64)
+    p = lambda a: a.ctypes.data_as(C.c_void_p)
+    assert capi.nnt_sched_simulate.raw(2, 0, 1, 1, p(tf), p(at), p(bad), p(so), p(sq), p(wo)) == capi.NNT_EINVAL
 
 
 def test_executor_spreads_independent_tasks_and_chains_dependent_ones(capi):
