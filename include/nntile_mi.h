@@ -518,7 +518,11 @@ NNT_API int32_t nnt_gpt2_block_create(nnt_ctx* ctx, const nnt_gpt2_block_cfg* cf
                               nnt_gpt2_block** out);
 NNT_API int32_t nnt_gpt2_block_destroy(nnt_gpt2_block* blk);
 /* X, Out, dOut, dX: [N_e, N_s, N_b] tensors of the block's dtype, tiled (tile_e,
- * tile_s, tile_b).  forward keeps X (by reference) for backward. */
+ * tile_s, tile_b).  forward keeps X (by reference) for backward.  Where the row tiles
+ * hold whole heads and divide N_e (whole-operation launches, attention as separate
+ * products) the attention products work on NNT_BLK_QKV, NNT_BLK_BM, NNT_BLK_DBM and
+ * NNT_BLK_DQKV directly (nnt_gemm_heads) and the per-head slots Q, K, V, BH, DBH, DQ, DK,
+ * DV stay untouched; otherwise those are filled by head split / merge passes. */
 NNT_API int32_t nnt_gpt2_block_forward(nnt_gpt2_block* blk, nnt_tensor* X, nnt_tensor* Out);
 NNT_API int32_t nnt_gpt2_block_backward(nnt_gpt2_block* blk, nnt_tensor* dOut, nnt_tensor* dX);
 /* Adam step on all 12 parameters; bf16 blocks also refresh the bf16 weight copies.
