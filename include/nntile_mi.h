@@ -413,6 +413,17 @@ NNT_API int32_t nnt_attention_fwd(nnt_ctx* ctx, nnt_tensor* Q, nnt_tensor* K, nn
 NNT_API int32_t nnt_attention_bwd(nnt_ctx* ctx, nnt_tensor* Q, nnt_tensor* K, nnt_tensor* V, nnt_tensor* B,
                           nnt_tensor* stats, nnt_tensor* dB, float scale, int32_t causal,
                           nnt_tensor* dQ, nnt_tensor* dK, nnt_tensor* dV);
+/* The same two operations on tensors that keep the heads side by side along their first axis
+ * (section 3, attention layer: what the linear layers before and after it produce and consume), so
+ * that no per-head copies are needed: QKV and dQKV are [3 * N_h * h, N_s, N_b] with Q, K, V (their
+ * adjoints) in rows [0, N_h h), [N_h h, 2 N_h h), [2 N_h h, 3 N_h h); Bm and dBm are [N_h * h, N_s, N_b];
+ * row head * h + d is component d of that head.  All share one tiling whose row tiles hold whole heads
+ * and divide N_h * h; h is 64 or 128; stats is fp32 (2, N_s, N_b, N_h) tiled like them along N_s and N_b.
+ * One launch (two for the adjoint) whatever the context's granularity.  Errors as above. */
+NNT_API int32_t nnt_attention_fwd_heads(nnt_ctx* ctx, nnt_tensor* QKV, float scale, int32_t causal, nnt_tensor* Bm,
+                                nnt_tensor* stats, int32_t N_h);
+NNT_API int32_t nnt_attention_bwd_heads(nnt_ctx* ctx, nnt_tensor* QKV, nnt_tensor* Bm, nnt_tensor* stats, nnt_tensor* dBm,
+                                float scale, int32_t causal, nnt_tensor* dQKV, int32_t N_h);
 
 typedef struct nnt_adam_cfg {
     double lr, beta1, beta2, eps, weight_decay;   /* doubles: 1 - beta is formed before rounding to fp32 */
@@ -519,10 +530,10 @@ NNT_API int32_t nnt_gpt2_block_create(nnt_ctx* ctx, const nnt_gpt2_block_cfg* cf
 NNT_API int32_t nnt_gpt2_block_destroy(nnt_gpt2_block* blk);
 /* X, Out, dOut, dX: [N_e, N_s, N_b] tensors of the block's dtype, tiled (tile_e,
  * tile_s, tile_b).  forward keeps X (by reference) for backward.  Where the row tiles
- * hold whole heads and divide N_e (whole-operation launches, attention as separate
- * products) the attention products work on NNT_BLK_QKV, NNT_BLK_BM, NNT_BLK_DBM and
- * NNT_BLK_DQKV directly (nnt_gemm_heads) and the per-head slots Q, K, V, BH, DBH, DQ, DK,
- * DV stay untouched; otherwise those are filled by head split / merge passes. */
+ * hold whole heads and divide N_e (whole-operation launches) the attention works on
+ * NNT_BLK_QKV, NNT_BLK_BM, NNT_BLK_DBM and NNT_BLK_DQKV directly (nnt_gemm_heads, or
+ * nnt_attention_fwd_heads / _bwd_heads with fused attention) and the per-head slots Q, K, V,
+ * BH, DBH, DQ, DK, DV stay untouched; otherwise those are filled by head split / merge passes. */
 NNT_API int32_t nnt_gpt2_block_forward(nnt_gpt2_block* blk, nnt_tensor* X, nnt_tensor* Out);
 NNT_API int32_t nnt_gpt2_block_backward(nnt_gpt2_block* blk, nnt_tensor* dOut, nnt_tensor* dX);
 /* Adam step on all 12 parameters; bf16 blocks also refresh the bf16 weight copies.

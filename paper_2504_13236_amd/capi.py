@@ -161,6 +161,8 @@ PROTOTYPES = {
     "nnt_head_merge": (_i32, [_p, _i32, _pp, _p]),
     "nnt_attention_fwd": (_i32, [_p, _p, _p, _p, _f, _i32, _p, _p]),
     "nnt_attention_bwd": (_i32, [_p, _p, _p, _p, _p, _p, _p, _f, _i32, _p, _p, _p]),
+    "nnt_attention_fwd_heads": (_i32, [_p, _p, _f, _i32, _p, _p, _i32]),
+    "nnt_attention_bwd_heads": (_i32, [_p, _p, _p, _p, _p, _f, _i32, _p, _i32]),
     "nnt_adam_step": (_i32, [_p, C.POINTER(nnt_adam_cfg), _i32, _p, _p, _p, _p, _p]),
     "nnt_embedding_fwd": (_i32, [_p, _p, _p, _p]),
     "nnt_embedding_bwd": (_i32, [_p, _p, _p, _p]),

@@ -47,7 +47,14 @@ struct AttnGeom {
     int tile0;           // first sequence tile this launch covers
     int causal;
     float scale;
+    // Operands that are windows on tensors [parts * N_h * H, N_s, N_b] with the heads side by side along the first
+    // axis (win = 1; the statistics stay an ordinary tensor, to which bh and gh then belong): `pitch` elements
+    // between the rows of consecutive positions (H otherwise), `hp` heads per row tile.
+    int win, pitch, hp;
 };
+
+// Where a windowed operand starts in its tensor: first row tile of its part, row tiles of the tensor.
+struct Win { int im0, g0; };
 
 struct Slab {
     int64_t off;   // where (0, 0, b, j) sits in its tile, counted in rows (a row = the first-axis elements of one position)
@@ -80,6 +87,14 @@ __device__ __forceinline__ Slab slab_of(const AttnGeom& g, const Pair& p, int l)
 template <typename T>
 __device__ __forceinline__ T* rows_of(void* const* tiles, const Slab& s, int width) {
     return static_cast<T*>(tiles[s.tile]) + s.off * width;
+}
+// Row 0 of (batch b, head j) in sequence tile `s` of a data operand; its rows are g.pitch elements apart.
+template <typename T>
+__device__ __forceinline__ T* rows_win(void* const* tiles, const AttnGeom& g, const Win& w, const Pair& pr, const Slab& s, int b, int j) {
+    if (!g.win) return static_cast<T*>(tiles[s.tile]) + s.off * g.H;
+    const int tb = b / g.bb, l = s.tile - pr.tile, hl = j / g.hp;
+    const int tile = (w.im0 + hl) + w.g0 * (l + g.gs * tb);
+    return static_cast<T*>(tiles[tile]) + (j - hl * g.hp) * g.H + (int64_t)g.pitch * ((int64_t)s.ext * (b - tb * g.bb));
 }
 
 // ---------------------------------------------------------------- element-type traits
@@ -130,8 +145,8 @@ template <int H_> struct F32Traits {
             d[0] = x.x; d[1] = x.y; d[2] = x.z; d[3] = x.w;
         }
     }
-    static __device__ __forceinline__ void load_own(const T* slab, int row, int hh, bool valid, Own& o) {
-        const float4* p = reinterpret_cast<const float4*>(slab + (int64_t)row * H + (H / 2) * hh);
+    static __device__ __forceinline__ void load_own(const T* slab, int pitch, int row, int hh, bool valid, Own& o) {
+        const float4* p = reinterpret_cast<const float4*>(slab + (int64_t)row * pitch + (H / 2) * hh);
 #pragma unroll
         for (int s4 = 0; s4 < H / 8; s4++) {
             const float4 x = valid ? p[s4] : make_float4(0.f, 0.f, 0.f, 0.f);
@@ -201,8 +216,8 @@ template <int H_> struct Bf16Traits {
     static __device__ __forceinline__ void put(T* lds, int row, int c, const Vec& x) {
         *reinterpret_cast<Vec*>(lds + row * LDX + c * kPer) = x;
     }
-    static __device__ __forceinline__ void load_own(const T* slab, int row, int hh, bool valid, Own& o) {
-        const uint4* p = reinterpret_cast<const uint4*>(slab + (int64_t)row * H + 8 * hh);
+    static __device__ __forceinline__ void load_own(const T* slab, int pitch, int row, int hh, bool valid, Own& o) {
+        const uint4* p = reinterpret_cast<const uint4*>(slab + (int64_t)row * pitch + 8 * hh);
 #pragma unroll
         for (int s = 0; s < H / 16; s++) {
             const uint4 x = valid ? p[2 * s] : make_uint4(0u, 0u, 0u, 0u);
@@ -261,15 +276,15 @@ template <int H_> struct Bf16Traits {
     }
 };
 
-// rows r0 .. r0+63 of a slab (rows of H contiguous elements) into registers, zeros beyond `ext`
+// rows r0 .. r0+63 of a slab (rows of H contiguous elements, `pitch` apart) into registers, zeros beyond `ext`
 template <class X>
-__device__ __forceinline__ void load_block(const typename X::T* slab, int r0, int ext, int tid, typename X::Vec (&reg)[X::kVec]) {
+__device__ __forceinline__ void load_block(const typename X::T* slab, int pitch, int r0, int ext, int tid, typename X::Vec (&reg)[X::kVec]) {
     constexpr int kRowVecs = X::H / X::kPer;
 #pragma unroll
     for (int c = 0; c < X::kVec; c++) {
         const int idx = tid + 256 * c;
         const int row = idx / kRowVecs, cv = idx % kRowVecs;
-        reg[c] = (r0 + row < ext) ? *reinterpret_cast<const typename X::Vec*>(slab + (int64_t)(r0 + row) * X::H + cv * X::kPer)
+        reg[c] = (r0 + row < ext) ? *reinterpret_cast<const typename X::Vec*>(slab + (int64_t)(r0 + row) * pitch + cv * X::kPer)
                                   : X::zero_vec();
     }
 }
@@ -285,9 +300,9 @@ __device__ __forceinline__ void store_block(typename X::T* lds, int tid, const t
 
 // accumulators (lane = this lane's row of the slab, register r = first-axis element 32 rb + acc_row(r)) to memory
 template <class X>
-__device__ __forceinline__ void store_own_row(typename X::T* slab, int row, int hh, bool valid, float mul, const f32x16 (&acc)[X::H / 32]) {
+__device__ __forceinline__ void store_own_row(typename X::T* slab, int pitch, int row, int hh, bool valid, float mul, const f32x16 (&acc)[X::H / 32]) {
     if (!valid) return;
-    typename X::T* p = slab + (int64_t)row * X::H;
+    typename X::T* p = slab + (int64_t)row * pitch;
 #pragma unroll
     for (int rb = 0; rb < X::H / 32; rb++)
 #pragma unroll
@@ -299,6 +314,7 @@ __device__ __forceinline__ void store_own_row(typename X::T* slab, int row, int 
 struct FwdArgs {
     AttnGeom g;
     void* const* Q; void* const* K; void* const* V; void* const* O; void* const* stats;
+    Win wQ, wK, wV, wO;
 };
 
 // ---------------------------------------------------------------- forward
@@ -326,7 +342,7 @@ __global__ void __launch_bounds__(256, 2) attn_fwd(const FwdArgs a) {
     const float sc2 = g.scale * kLog2e;        // scores are kept in units of log 2
 
     typename X::Own qf;
-    X::load_own(rows_of<const T>(a.Q, sq, H), eq, hh, qvalid, qf);
+    X::load_own(rows_win<const T>(a.Q, g, a.wQ, pr, sq, b, j), g.pitch, eq, hh, qvalid, qf);
 
     int nit;
     if (g.causal) nit = (wg_qlast / g.bs) * g.nstep + (wg_qlast % g.bs) / kBlk + 1;
@@ -341,8 +357,8 @@ __global__ void __launch_bounds__(256, 2) attn_fwd(const FwdArgs a) {
     auto fetch = [&](int it) {
         const int lk = it / g.nstep, k0 = (it % g.nstep) * kBlk;
         const Slab sk = slab_of(g, pr, lk);
-        load_block<X>(rows_of<const T>(a.K, sk, H), k0, sk.ext, tid, kr);
-        load_block<X>(rows_of<const T>(a.V, sk, H), k0, sk.ext, tid, vr);
+        load_block<X>(rows_win<const T>(a.K, g, a.wK, pr, sk, b, j), g.pitch, k0, sk.ext, tid, kr);
+        load_block<X>(rows_win<const T>(a.V, g, a.wV, pr, sk, b, j), g.pitch, k0, sk.ext, tid, vr);
     };
     auto stash = [&](int buf) {
         store_block<X, LDK>(lds[buf], tid, kr);
@@ -418,7 +434,7 @@ __global__ void __launch_bounds__(256, 2) attn_fwd(const FwdArgs a) {
         __syncthreads();
     }
     lsum += __shfl_xor(lsum, 32, 64);
-    store_own_row<X>(rows_of<T>(a.O, sq, H), eq, hh, qvalid, 1.f / lsum, O);
+    store_own_row<X>(rows_win<T>(a.O, g, a.wO, pr, sq, b, j), g.pitch, eq, hh, qvalid, 1.f / lsum, O);
     if (qvalid && hh == 0) {
         float* st = rows_of<float>(a.stats, sq, 2) + 2 * (int64_t)eq;
         st[0] = m * g.scale;
@@ -431,6 +447,7 @@ struct BwdArgs {
     void* const* Q; void* const* K; void* const* V; void* const* O; void* const* stats; void* const* dO;
     void* const* dQ; void* const* dK; void* const* dV;
     float* aux;     // per (query, batch, head): log2 of (softmax denominator times 2^maximum), and D
+    Win wQ, wK, wV, wO, wdO, wdQ, wdK, wdV;
 };
 
 // ---------------------------------------------------------------- dQ (also writes aux)
@@ -456,12 +473,12 @@ __global__ void __launch_bounds__(256, 2) attn_dq(const BwdArgs a) {
     const float sc2 = g.scale * kLog2e;
 
     typename X::Own qf, dof;
-    X::load_own(rows_of<const T>(a.Q, sq, H), eq, hh, qvalid, qf);
-    X::load_own(rows_of<const T>(a.dO, sq, H), eq, hh, qvalid, dof);
+    X::load_own(rows_win<const T>(a.Q, g, a.wQ, pr, sq, b, j), g.pitch, eq, hh, qvalid, qf);
+    X::load_own(rows_win<const T>(a.dO, g, a.wdO, pr, sq, b, j), g.pitch, eq, hh, qvalid, dof);
     float lse = 0.f, D = 0.f;
     {
         typename X::Own of;
-        X::load_own(rows_of<const T>(a.O, sq, H), eq, hh, qvalid, of);
+        X::load_own(rows_win<const T>(a.O, g, a.wO, pr, sq, b, j), g.pitch, eq, hh, qvalid, of);
         D = X::dot_own(of, dof);
         D += __shfl_xor(D, 32, 64);
         if (qvalid) {
@@ -487,8 +504,8 @@ __global__ void __launch_bounds__(256, 2) attn_dq(const BwdArgs a) {
     auto fetch = [&](int it) {
         const int lk = it / g.nstep, k0 = (it % g.nstep) * kBlk;
         const Slab sk = slab_of(g, pr, lk);
-        load_block<X>(rows_of<const T>(a.K, sk, H), k0, sk.ext, tid, kr);
-        load_block<X>(rows_of<const T>(a.V, sk, H), k0, sk.ext, tid, vr);
+        load_block<X>(rows_win<const T>(a.K, g, a.wK, pr, sk, b, j), g.pitch, k0, sk.ext, tid, kr);
+        load_block<X>(rows_win<const T>(a.V, g, a.wV, pr, sk, b, j), g.pitch, k0, sk.ext, tid, vr);
     };
     auto stash = [&](int buf) {
         store_block<X, LD>(lds[buf], tid, kr);
@@ -533,7 +550,7 @@ __global__ void __launch_bounds__(256, 2) attn_dq(const BwdArgs a) {
         if (it + 1 < nit) stash((it + 1) & 1);
         __syncthreads();
     }
-    store_own_row<X>(rows_of<T>(a.dQ, sq, H), eq, hh, qvalid, g.scale, dQ);
+    store_own_row<X>(rows_win<T>(a.dQ, g, a.wdQ, pr, sq, b, j), g.pitch, eq, hh, qvalid, g.scale, dQ);
 }
 
 // ---------------------------------------------------------------- dK and dV (reads aux)
@@ -561,8 +578,8 @@ __global__ void __launch_bounds__(256, X::kDkvBlocks) attn_dkv(const BwdArgs a) 
     const float sc2 = g.scale * kLog2e;
 
     typename X::Own kf, vf;
-    X::load_own(rows_of<const T>(a.K, sk, H), ek, hh, kvalid, kf);
-    X::load_own(rows_of<const T>(a.V, sk, H), ek, hh, kvalid, vf);
+    X::load_own(rows_win<const T>(a.K, g, a.wK, pr, sk, b, j), g.pitch, ek, hh, kvalid, kf);
+    X::load_own(rows_win<const T>(a.V, g, a.wV, pr, sk, b, j), g.pitch, ek, hh, kvalid, vf);
 
     const int nit = (g.gs - 1) * g.nstep + (g.Ns - (g.gs - 1) * g.bs + kBlk - 1) / kBlk;
     // with the causal mask the first query block that sees any of these keys is the one that holds key e0
@@ -578,8 +595,8 @@ __global__ void __launch_bounds__(256, X::kDkvBlocks) attn_dkv(const BwdArgs a) 
     auto fetch = [&](int it) {
         const int lq = it / g.nstep, q0 = (it % g.nstep) * kBlk;
         const Slab sq = slab_of(g, pr, lq);
-        load_block<X>(rows_of<const T>(a.Q, sq, H), q0, sq.ext, tid, qr);
-        load_block<X>(rows_of<const T>(a.dO, sq, H), q0, sq.ext, tid, dr);
+        load_block<X>(rows_win<const T>(a.Q, g, a.wQ, pr, sq, b, j), g.pitch, q0, sq.ext, tid, qr);
+        load_block<X>(rows_win<const T>(a.dO, g, a.wdO, pr, sq, b, j), g.pitch, q0, sq.ext, tid, dr);
         if (tid < kBlk) {
             const bool ok = q0 + tid < sq.ext;
             ar = ok ? *reinterpret_cast<const float2*>(aux_pair + 2 * (lq * g.bs + q0 + tid)) : make_float2(0.f, 0.f);
@@ -648,8 +665,8 @@ __global__ void __launch_bounds__(256, X::kDkvBlocks) attn_dkv(const BwdArgs a) 
         if (it + 1 < nit) stash((it + 1) & 1);
         __syncthreads();
     }
-    store_own_row<X>(rows_of<T>(a.dK, sk, H), ek, hh, kvalid, g.scale, dK);
-    store_own_row<X>(rows_of<T>(a.dV, sk, H), ek, hh, kvalid, 1.f, dV);
+    store_own_row<X>(rows_win<T>(a.dK, g, a.wdK, pr, sk, b, j), g.pitch, ek, hh, kvalid, g.scale, dK);
+    store_own_row<X>(rows_win<T>(a.dV, g, a.wdV, pr, sk, b, j), g.pitch, ek, hh, kvalid, 1.f, dV);
 }
 
 using FwdKernel = void (*)(const FwdArgs);
@@ -714,8 +731,57 @@ AttnGeom geom_of(const nnt_tensor* q, float scale, int causal) {
     g.tile0 = 0;
     g.causal = causal;
     g.scale = scale;
+    g.win = 0;
+    g.pitch = g.H;
+    g.hp = 1;
     return g;
 }
+
+// Geometry for operands that are windows on tensors [parts * N_h * H, N_s, N_b] (`ts`: the tensors with their
+// part counts); the statistics are an ordinary tensor (2, N_s, N_b, N_h).
+int32_t geom_of_windows(nnt_ctx* ctx, const char* who, std::initializer_list<std::pair<const nnt_tensor*, int>> ts, const nnt_tensor* stats,
+                        int32_t N_h, float scale, int causal, AttnGeom* out) {
+    const nnt_tensor* first = ts.begin()->first;
+    if (!first || !stats || N_h < 1) return fail(ctx, NNT_EINVAL, std::string(who) + ": null tensor or bad head count");
+    const int64_t N_e = first->ndim == 3 ? first->shape[0] / ts.begin()->second : 0;
+    if (N_e < 1 || N_e % N_h != 0) return fail(ctx, NNT_EINVAL, std::string(who) + ": rows are not whole parts of N_h heads");
+    const int64_t H = N_e / N_h, t0 = first->base[0];
+    if (H != 64 && H != 128) return fail(ctx, NNT_EINVAL, std::string(who) + ": head size must be 64 or 128");
+    if (t0 % H != 0 || N_e % t0 != 0) return fail(ctx, NNT_EINVAL, std::string(who) + ": row tiles must hold whole heads and a part whole row tiles");
+    for (const auto& tp : ts) {
+        const nnt_tensor* t = tp.first;
+        if (!t) return fail(ctx, NNT_EINVAL, std::string(who) + ": null tensor");
+        if (t->ndim != 3 || t->dtype != first->dtype || t->shape[0] != tp.second * N_e || t->base[0] != t0 || t->shape[1] != first->shape[1] ||
+            t->shape[2] != first->shape[2] || t->base[1] != first->base[1] || t->base[2] != first->base[2])
+            return fail(ctx, NNT_EINVAL, std::string(who) + ": operands differ in type, extents or tiling");
+        for (void* p : t->tiles)
+            if (!p || !aligned16(p)) return fail(ctx, NNT_EINVAL, std::string(who) + ": missing or unaligned tile");
+    }
+    if (first->dtype != NNT_F32 && first->dtype != NNT_BF16) return fail(ctx, NNT_EDTYPE, std::string(who) + ": fp32 or bf16 operands");
+    if (!(scale > 0.f)) return fail(ctx, NNT_EINVAL, std::string(who) + ": scale must be positive");
+    if (stats->dtype != NNT_F32 || stats->ndim != 4 || stats->shape[0] != 2 || stats->base[0] != 2 || stats->shape[3] != N_h ||
+        stats->shape[1] != first->shape[1] || stats->shape[2] != first->shape[2] || stats->base[1] != first->base[1] || stats->base[2] != first->base[2])
+        return fail(ctx, NNT_EINVAL, std::string(who) + ": stats must be fp32 (2, N_s, N_b, N_h), tiled like the operands along N_s and N_b");
+    for (void* p : stats->tiles)
+        if (!p) return fail(ctx, NNT_EINVAL, std::string(who) + ": stats tile missing");
+    if (first->grid[1] * ((first->base[1] + kWgRows - 1) / kWgRows) > 65535 || first->shape[2] * (int64_t)N_h > INT32_MAX)
+        return fail(ctx, NNT_EINVAL, std::string(who) + ": sequence too long for one launch");
+    AttnGeom g;
+    g.H = (int)H; g.Ns = (int)first->shape[1]; g.Nb = (int)first->shape[2]; g.Nh = N_h;
+    g.bs = (int)first->base[1]; g.bb = (int)first->base[2]; g.bh = (int)stats->base[3];
+    g.gs = (int)first->grid[1]; g.gb = (int)first->grid[2]; g.gh = (int)stats->grid[3];
+    g.nblk = (g.bs + kWgRows - 1) / kWgRows;
+    g.nstep = (g.bs + kBlk - 1) / kBlk;
+    g.tile0 = 0;
+    g.causal = causal;
+    g.scale = scale;
+    g.win = 1;
+    g.pitch = (int)t0;
+    g.hp = (int)(t0 / H);
+    *out = g;
+    return NNT_OK;
+}
+Win window_at(const nnt_tensor* t, int part, int64_t N_e) { return Win{(int)(part * (N_e / t->base[0])), (int)t->grid[0]}; }
 
 // visible (key, query) pairs of one (batch, head) pair for queries q0 .. q1-1
 double visible_pairs(int64_t Ns, int64_t q0, int64_t q1, int causal) {
@@ -787,6 +853,53 @@ int32_t nnt_attention_bwd(nnt_ctx* ctx, nnt_tensor* Q, nnt_tensor* K, nnt_tensor
     OpTag tag(ctx, "attention_bwd_dq", 3.0 * pair_flops * pairs, false);
     return submit(ctx, {Q->all(kRead), K->all(kRead), V->all(kRead), B->all(kRead), stats->all(kRead), dB->all(kRead),
                         dQ->all(kWrite), dK->all(kWrite), dV->all(kWrite), scr},
+                  [=](hipStream_t st) {
+                      const dim3 grid((unsigned)(a.g.Nb * a.g.Nh), (unsigned)(a.g.gs * a.g.nblk)), block(256);
+                      hipLaunchKernelGGL(k_dq, grid, block, 0, st, a);
+                      if (hipGetLastError() != hipSuccess) return (int32_t)NNT_EHIP;
+                      profile_mark(ctx, st, "attention_bwd_dkv", 4.0 * pair_flops * pairs, false);
+                      hipLaunchKernelGGL(k_dkv, grid, block, 0, st, a);
+                      return hipGetLastError() == hipSuccess ? (int32_t)NNT_OK : (int32_t)NNT_EHIP;
+                  }, 2);
+}
+
+int32_t nnt_attention_fwd_heads(nnt_ctx* ctx, nnt_tensor* QKV, float scale, int32_t causal, nnt_tensor* Bm, nnt_tensor* stats, int32_t N_h) {
+    NNT_CHECK_CTX(ctx);
+    AttnGeom g;
+    int32_t rc = geom_of_windows(ctx, "nnt_attention_fwd_heads", {{QKV, 3}, {Bm, 1}}, stats, N_h, scale, causal, &g);
+    if (rc != NNT_OK) return rc;
+    const int64_t N_e = (int64_t)g.H * g.Nh;
+    FwdArgs a{g, QKV->d_tiles, QKV->d_tiles, QKV->d_tiles, Bm->d_tiles, stats->d_tiles,
+              window_at(QKV, 0, N_e), window_at(QKV, 1, N_e), window_at(QKV, 2, N_e), window_at(Bm, 0, N_e)};
+    const double pair_flops = 4.0 * g.H * g.Nb * g.Nh;
+    const FwdKernel kernel = fwd_kernel(QKV->dtype, g.H);
+    OpTag tag(ctx, "attention_fwd", pair_flops * visible_pairs(g.Ns, 0, g.Ns, causal), false);
+    return submit(ctx, {QKV->all(kRead), Bm->all(kWrite), stats->all(kWrite)}, [=](hipStream_t st) {
+        const dim3 grid((unsigned)(a.g.Nb * a.g.Nh), (unsigned)(a.g.gs * a.g.nblk)), block(256);
+        hipLaunchKernelGGL(kernel, grid, block, 0, st, a);
+        return hipGetLastError() == hipSuccess ? (int32_t)NNT_OK : (int32_t)NNT_EHIP;
+    });
+}
+
+int32_t nnt_attention_bwd_heads(nnt_ctx* ctx, nnt_tensor* QKV, nnt_tensor* Bm, nnt_tensor* stats, nnt_tensor* dBm, float scale,
+                                int32_t causal, nnt_tensor* dQKV, int32_t N_h) {
+    NNT_CHECK_CTX(ctx);
+    AttnGeom g;
+    int32_t rc = geom_of_windows(ctx, "nnt_attention_bwd_heads", {{QKV, 3}, {Bm, 1}, {dBm, 1}, {dQKV, 3}}, stats, N_h, scale, causal, &g);
+    if (rc != NNT_OK) return rc;
+    rc = ensure_scratch(ctx, 2 * (int64_t)g.Ns * g.Nb * g.Nh);
+    if (rc != NNT_OK) return rc;
+    const int64_t N_e = (int64_t)g.H * g.Nh;
+    BwdArgs a{g, QKV->d_tiles, QKV->d_tiles, QKV->d_tiles, Bm->d_tiles, stats->d_tiles, dBm->d_tiles,
+              dQKV->d_tiles, dQKV->d_tiles, dQKV->d_tiles, ctx->red_scratch,
+              window_at(QKV, 0, N_e), window_at(QKV, 1, N_e), window_at(QKV, 2, N_e), window_at(Bm, 0, N_e), window_at(dBm, 0, N_e),
+              window_at(dQKV, 0, N_e), window_at(dQKV, 1, N_e), window_at(dQKV, 2, N_e)};
+    const double pair_flops = 2.0 * g.H * g.Nb * g.Nh;
+    const double pairs = visible_pairs(g.Ns, 0, g.Ns, causal);
+    const Access scr{&ctx->red_dep, 1, kReadWrite};
+    const BwdKernel k_dq = dq_kernel(QKV->dtype, g.H), k_dkv = dkv_kernel(QKV->dtype, g.H);
+    OpTag tag(ctx, "attention_bwd_dq", 3.0 * pair_flops * pairs, false);
+    return submit(ctx, {QKV->all(kRead), Bm->all(kRead), stats->all(kRead), dBm->all(kRead), dQKV->all(kWrite), scr},
                   [=](hipStream_t st) {
                       const dim3 grid((unsigned)(a.g.Nb * a.g.Nh), (unsigned)(a.g.gs * a.g.nblk)), block(256);
                       hipLaunchKernelGGL(k_dq, grid, block, 0, st, a);

@@ -201,13 +201,14 @@ static int32_t linear_bwd(nnt_gpt2_block* b, nnt_tensor* W, nnt_tensor* X, nnt_t
 }
 
 // Whether the attention products read and write the tensors of the linear layers directly (nnt_gemm_heads)
-// instead of per-head copies: whole-operation launches, the products as separate operations, and row tiles that
-// hold whole heads and divide the embedding size.  (NNT_BLOCK_HEAD_COPIES=1 keeps the copies: a measuring aid.)
+// instead of per-head copies: whole-operation launches and row tiles that hold whole heads and divide the
+// embedding size.  (NNT_BLOCK_HEAD_COPIES=1 keeps the copies: a measuring aid.)
 static bool head_windows(const nnt_gpt2_block* b) {
     static const bool copies = getenv("NNT_BLOCK_HEAD_COPIES") != nullptr;
     const nnt_gpt2_block_cfg& c = b->cfg;
-    if (copies || c.fused_attention || b->ctx->granularity != NNT_GRAN_OP) return false;
+    if (copies || b->ctx->granularity != NNT_GRAN_OP) return false;
     const int64_t h = c.N_e / c.N_h, t0 = b->s[NNT_BLK_QKV]->base[0];
+    if (c.fused_attention && h != 64 && h != 128) return false;
     return t0 % h == 0 && c.N_e % t0 == 0 && b->s[NNT_BLK_BM]->base[0] == t0 && b->s[NNT_BLK_DBM]->base[0] == t0 &&
            b->s[NNT_BLK_DQKV]->base[0] == t0;
 }
@@ -228,9 +229,13 @@ int32_t nnt_gpt2_block_forward(nnt_gpt2_block* b, nnt_tensor* X, nnt_tensor* Out
     if (head_windows(b)) {
         // parts 0, 1, 2 of the QKV rows are Q, K, V; the heads' results go straight into Bm
         const int32_t h = (int32_t)(c.N_e / c.N_h), N_h = (int32_t)c.N_h;
-        TRY(nnt_gemm_heads(ctx, sc, NNT_OP_T, s[NNT_BLK_QKV], 1, NNT_OP_N, s[NNT_BLK_QKV], 0, s[NNT_BLK_P], -1, h, N_h));
-        TRY(nnt_softmax_fwd(ctx, s[NNT_BLK_P], s[NNT_BLK_SM_STATS], 1.f, c.causal));
-        TRY(nnt_gemm_heads(ctx, 1.f, NNT_OP_N, s[NNT_BLK_QKV], 2, NNT_OP_N, s[NNT_BLK_P], -1, s[NNT_BLK_BM], 0, h, N_h));
+        if (c.fused_attention) {
+            TRY(nnt_attention_fwd_heads(ctx, s[NNT_BLK_QKV], sc, c.causal, s[NNT_BLK_BM], s[NNT_BLK_SM_STATS], N_h));
+        } else {
+            TRY(nnt_gemm_heads(ctx, sc, NNT_OP_T, s[NNT_BLK_QKV], 1, NNT_OP_N, s[NNT_BLK_QKV], 0, s[NNT_BLK_P], -1, h, N_h));
+            TRY(nnt_softmax_fwd(ctx, s[NNT_BLK_P], s[NNT_BLK_SM_STATS], 1.f, c.causal));
+            TRY(nnt_gemm_heads(ctx, 1.f, NNT_OP_N, s[NNT_BLK_QKV], 2, NNT_OP_N, s[NNT_BLK_P], -1, s[NNT_BLK_BM], 0, h, N_h));
+        }
     } else {
         nnt_tensor* qkv[3] = {s[NNT_BLK_Q], s[NNT_BLK_K], s[NNT_BLK_V]};
         TRY(nnt_head_split(ctx, s[NNT_BLK_QKV], 3, qkv));
@@ -276,11 +281,16 @@ int32_t nnt_gpt2_block_backward(nnt_gpt2_block* b, nnt_tensor* dOut, nnt_tensor*
         // dV = dB P^T, dP = V^T dB, softmax adjoint, dQ = K dA / sqrt(h), dK = Q dA^T / sqrt(h): dB is read out of dBm,
         // the three results are the parts of dQKV
         const int32_t h = (int32_t)(c.N_e / c.N_h), N_h = (int32_t)c.N_h;
-        TRY(nnt_gemm_heads(ctx, 1.f, NNT_OP_N, s[NNT_BLK_DBM], 0, NNT_OP_T, s[NNT_BLK_P], -1, s[NNT_BLK_DQKV], 2, h, N_h));
-        TRY(nnt_gemm_heads(ctx, 1.f, NNT_OP_T, s[NNT_BLK_QKV], 2, NNT_OP_N, s[NNT_BLK_DBM], 0, s[NNT_BLK_DP], -1, h, N_h));
-        TRY(nnt_softmax_bwd(ctx, s[NNT_BLK_P], s[NNT_BLK_DP]));
-        TRY(nnt_gemm_heads(ctx, sc, NNT_OP_N, s[NNT_BLK_QKV], 1, NNT_OP_N, s[NNT_BLK_DP], -1, s[NNT_BLK_DQKV], 0, h, N_h));
-        TRY(nnt_gemm_heads(ctx, sc, NNT_OP_N, s[NNT_BLK_QKV], 0, NNT_OP_T, s[NNT_BLK_DP], -1, s[NNT_BLK_DQKV], 1, h, N_h));
+        if (c.fused_attention) {
+            TRY(nnt_attention_bwd_heads(ctx, s[NNT_BLK_QKV], s[NNT_BLK_BM], s[NNT_BLK_SM_STATS], s[NNT_BLK_DBM], sc, c.causal,
+                                        s[NNT_BLK_DQKV], N_h));
+        } else {
+            TRY(nnt_gemm_heads(ctx, 1.f, NNT_OP_N, s[NNT_BLK_DBM], 0, NNT_OP_T, s[NNT_BLK_P], -1, s[NNT_BLK_DQKV], 2, h, N_h));
+            TRY(nnt_gemm_heads(ctx, 1.f, NNT_OP_T, s[NNT_BLK_QKV], 2, NNT_OP_N, s[NNT_BLK_DBM], 0, s[NNT_BLK_DP], -1, h, N_h));
+            TRY(nnt_softmax_bwd(ctx, s[NNT_BLK_P], s[NNT_BLK_DP]));
+            TRY(nnt_gemm_heads(ctx, sc, NNT_OP_N, s[NNT_BLK_QKV], 1, NNT_OP_N, s[NNT_BLK_DP], -1, s[NNT_BLK_DQKV], 0, h, N_h));
+            TRY(nnt_gemm_heads(ctx, sc, NNT_OP_N, s[NNT_BLK_QKV], 0, NNT_OP_T, s[NNT_BLK_DP], -1, s[NNT_BLK_DQKV], 1, h, N_h));
+        }
     } else {
         nnt_tensor* dbh[1] = {s[NNT_BLK_DBH]};
         TRY(nnt_head_split(ctx, s[NNT_BLK_DBM], 1, dbh));

@@ -77,6 +77,54 @@ def test_fused_attention(mods, case, dtype, causal, gran):
         check(tdK.download(), dK, dtype, "attention dK, second call")
 
 
+# h, N_h, row tile, N_s, sequence tile, N_b, batch tile, head tile of the statistics
+HEADS_CASES = [
+    (64, 6, 128, 200, 96, 3, 2, 6),          # two heads per row tile, ragged sequence and batch tiles
+    (64, 4, 256, 330, 400, 1, 1, 2),         # all heads of a part in one row tile, one ragged sequence tile
+    (128, 4, 256, 160, 72, 2, 1, 1),         # head size 128, statistics tiled one head at a time
+    (64, 3, 64, 72, 40, 2, 2, 3),            # one head per row tile
+]
+
+
+@pytest.mark.parametrize("gran", [0, 1])
+@pytest.mark.parametrize("causal", [1, 0])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", HEADS_CASES, ids=lambda c: "h%d-Nh%d-t%d-Ns%d-ts%d" % c[:5])
+def test_fused_attention_on_tensors_with_the_heads_side_by_side(mods, case, dtype, causal, gran):
+    """The fused kernels read Q, K, V and dB out of, and write B, dQ, dK, dV into, the tensors of the linear layers
+    ([3 N_h h, N_s, N_b] and [N_h h, N_s, N_b]): against the oracle's head split, attention and head merge."""
+    capi, tiled = mods
+    h, N_h, t0, N_s, ts, N_b, tb, th = case
+    N_e = h * N_h
+    r = np.random.default_rng(hash((case, causal)) % (2 ** 31))
+    QKV = quant(r.standard_normal((3 * N_e, N_s, N_b)), dtype)
+    dBm = quant(r.standard_normal((N_e, N_s, N_b)), dtype)
+    Q, K, V = D.split_heads(QKV, N_h, 3)
+    dB = D.split_heads(dBm, N_h, 1)[0]
+    scale = 1.0 / math.sqrt(h)
+    B, tmax, den, dQ, dK, dV = reference(Q, K, V, dB, bool(causal))
+    with tiled.Context(n_streams=2, granularity=gran) as ctx:
+        tQKV, tdBm = T(tiled, ctx, QKV, (t0, ts, tb), dtype), T(tiled, ctx, dBm, (t0, ts, tb), dtype)
+        tBm = tiled.TiledTensor(ctx, dtype, (N_e, N_s, N_b), (t0, ts, tb))
+        tS = tiled.TiledTensor(ctx, "f32", (2, N_s, N_b, N_h), (2, ts, tb, th))
+        capi.nnt_attention_fwd_heads(ctx.h, tQKV.h, scale, causal, tBm.h, tS.h, N_h)
+        check(tBm.download(), D.merge_heads([B]), dtype, "attention fwd")
+        stats = tS.download()
+        check(stats[0], tmax, "f32", "running maximum")
+        check(stats[1], den, "f32", "sum of shifted exponentials")
+        tdQKV = tiled.TiledTensor(ctx, dtype, QKV.shape, (t0, ts, tb))
+        capi.nnt_attention_bwd_heads(ctx.h, tQKV.h, tBm.h, tS.h, tdBm.h, scale, causal, tdQKV.h, N_h)
+        got, ref = tdQKV.download(), D.merge_heads([dQ, dK, dV])
+        for part, name in enumerate(("attention dQ", "attention dK", "attention dV")):
+            check(got[part * N_e:(part + 1) * N_e], ref[part * N_e:(part + 1) * N_e], dtype, name)
+        # geometry that does not fit is refused
+        bad = tiled.TiledTensor(ctx, dtype, (2 * N_e, N_s, N_b), (t0, ts, tb))
+        with pytest.raises(capi.NntError):
+            capi.nnt_attention_fwd_heads(ctx.h, bad.h, scale, causal, tBm.h, tS.h, N_h)
+        with pytest.raises(capi.NntError):
+            capi.nnt_attention_fwd_heads(ctx.h, tQKV.h, scale, causal, tBm.h, tS.h, N_h + 1)
+
+
 def test_fused_attention_survives_large_scores(mods):
     """Scores of several hundred: the running maximum keeps every exponent at or below zero."""
     capi, tiled = mods
