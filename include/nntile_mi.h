@@ -340,6 +340,20 @@ NNT_API int32_t nnt_gemm(nnt_ctx* ctx, float alpha, int32_t opA, nnt_tensor* A, 
 NNT_API int32_t nnt_gemm_res(nnt_ctx* ctx, float alpha, int32_t opA, nnt_tensor* A, int32_t opB, nnt_tensor* B,
                      float beta, nnt_tensor* C, int32_t n_contract_axes, int32_t n_batch_axes, nnt_tensor* bias,
                      nnt_tensor* R);
+/* A linear layer with the activation that follows it (section 3: the MLP is linear, GELU, linear):
+ * C = alpha * op(A) . op(B) +. bias and G = gelu(C) leave one launch, so the activation is not a pass
+ * of its own over C.  No batch axes; G has C's type, shape and tiling, a tile wherever C has one, and
+ * is neither A, B nor C; it is written, C too (both are kept: the backward pass needs C).  One launch
+ * for fp32 tensors whose tiles are whole macro-tiles of the direct-load kernels with op(B) = B; any
+ * other form runs nnt_gemm and nnt_gelu one after the other (same result).  variant: NNT_GELU_*. */
+NNT_API int32_t nnt_gemm_gelu(nnt_ctx* ctx, float alpha, int32_t opA, nnt_tensor* A, int32_t opB, nnt_tensor* B,
+                      nnt_tensor* C, int32_t n_contract_axes, nnt_tensor* bias, int32_t variant, nnt_tensor* G);
+/* The adjoint of that pair, seen from the next layer: C = (alpha * op(A) . op(B)) * gelu'(X) element by
+ * element (section 3: the gradient that the second linear layer sends back, times the activation's
+ * derivative at the first layer's result X).  X is only read; same conditions on it as on G above
+ * (one launch: fp32, whole macro-tiles, op(A) = A^T, op(B) = B; else nnt_gemm, then nnt_gelu_bwd). */
+NNT_API int32_t nnt_gemm_gelu_bwd(nnt_ctx* ctx, float alpha, int32_t opA, nnt_tensor* A, int32_t opB, nnt_tensor* B,
+                          nnt_tensor* C, int32_t n_contract_axes, int32_t variant, nnt_tensor* X);
 
 /* The per-head products of the attention layer (section 3, attention layer: K^T Q, V P and their four
  * adjoint products, one per batch member and head) on tensors that keep the heads side by side along their

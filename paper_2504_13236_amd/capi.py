@@ -145,6 +145,8 @@ PROTOTYPES = {
     "nnt_tile_sgd": (_i32, [_p, _i64, _d, _d, _d, _i32, _p, _p, _p, _p]),
     "nnt_gemm": (_i32, [_p, _f, _i32, _p, _i32, _p, _f, _p, _i32, _i32, _p]),
     "nnt_gemm_res": (_i32, [_p, _f, _i32, _p, _i32, _p, _f, _p, _i32, _i32, _p, _p]),
+    "nnt_gemm_gelu": (_i32, [_p, _f, _i32, _p, _i32, _p, _p, _i32, _p, _i32, _p]),
+    "nnt_gemm_gelu_bwd": (_i32, [_p, _f, _i32, _p, _i32, _p, _p, _i32, _i32, _p]),
     "nnt_gemm_heads": (_i32, [_p, _f, _i32, _p, _i32, _i32, _p, _i32, _p, _i32, _i32, _i32]),
     "nnt_fill": (_i32, [_p, _f, _p]),
     "nnt_add": (_i32, [_p, _f, _p, _f, _p]),

@@ -200,6 +200,14 @@ static int32_t linear_bwd(nnt_gpt2_block* b, nnt_tensor* W, nnt_tensor* X, nnt_t
     return nnt_gemm(ctx, 1.f, NNT_OP_T, W, NNT_OP_N, dY, 0.f, dX, 1, 0, nullptr);
 }
 
+// Whether the activation and its derivative ride on the result paths of the products next to them (nnt_gemm_gelu,
+// nnt_gemm_gelu_bwd) instead of being passes of their own: whole-operation launches in fp32 (the bf16 product kernels
+// have no such form).  (NNT_BLOCK_GELU_PASSES=1 keeps the passes: a measuring aid.)
+static bool gelu_in_products(const nnt_gpt2_block* b) {
+    static const bool passes = getenv("NNT_BLOCK_GELU_PASSES") != nullptr;
+    return !passes && b->ctx->granularity == NNT_GRAN_OP && b->cfg.dtype == NNT_F32;
+}
+
 // Whether the attention products read and write the tensors of the linear layers directly (nnt_gemm_heads)
 // instead of per-head copies: whole-operation launches and row tiles that hold whole heads and divide the
 // embedding size.  (NNT_BLOCK_HEAD_COPIES=1 keeps the copies: a measuring aid.)
@@ -251,8 +259,13 @@ int32_t nnt_gpt2_block_forward(nnt_gpt2_block* b, nnt_tensor* X, nnt_tensor* Out
     }
     TRY(linear(b, weight(b, NNT_BLK_W_O), s[NNT_BLK_BM], s[NNT_BLK_B_O], s[NNT_BLK_X2], X));      // X2 = X + W_o Bm +. b_o
     TRY(nnt_layernorm_fwd(ctx, s[NNT_BLK_X2], s[NNT_BLK_GAMMA2], s[NNT_BLK_BETA2], c.eps, s[NNT_BLK_X3], s[NNT_BLK_STATS2]));
-    TRY(linear(b, weight(b, NNT_BLK_W_1), s[NNT_BLK_X3], s[NNT_BLK_B_1], s[NNT_BLK_H1]));
-    TRY(nnt_gelu(ctx, c.gelu_variant, s[NNT_BLK_H1], s[NNT_BLK_G]));
+    if (gelu_in_products(b)) {                                                                   // H1 and G = gelu(H1) from one launch
+        TRY(nnt_gemm_gelu(ctx, 1.f, NNT_OP_N, weight(b, NNT_BLK_W_1), NNT_OP_N, s[NNT_BLK_X3], s[NNT_BLK_H1], 1, s[NNT_BLK_B_1],
+                          c.gelu_variant, s[NNT_BLK_G]));
+    } else {
+        TRY(linear(b, weight(b, NNT_BLK_W_1), s[NNT_BLK_X3], s[NNT_BLK_B_1], s[NNT_BLK_H1]));
+        TRY(nnt_gelu(ctx, c.gelu_variant, s[NNT_BLK_H1], s[NNT_BLK_G]));
+    }
     return linear(b, weight(b, NNT_BLK_W_2), s[NNT_BLK_G], s[NNT_BLK_B_2], Out, s[NNT_BLK_X2]);   // Out = X2 + W_2 G +. b_2
 }
 
@@ -269,8 +282,14 @@ int32_t nnt_gpt2_block_backward(nnt_gpt2_block* b, nnt_tensor* dOut, nnt_tensor*
         return fail(ctx, NNT_EINVAL, "nnt_gpt2_block_backward: dOut / dX do not match the block's activations");
     nnt_tensor** g = s + NNT_BLK_GRAD;
     // MLP
-    TRY(linear_bwd(b, weight(b, NNT_BLK_W_2), s[NNT_BLK_G], dOut, s[NNT_BLK_DG], g[NNT_BLK_W_2], g[NNT_BLK_B_2]));
-    TRY(nnt_gelu_bwd(ctx, c.gelu_variant, s[NNT_BLK_H1], s[NNT_BLK_DG], s[NNT_BLK_DG]));
+    if (gelu_in_products(b)) {                                                                   // dH1 = (W_2^T dOut) * gelu'(H1) from one launch
+        TRY(nnt_gemm(ctx, 1.f, NNT_OP_N, dOut, NNT_OP_T, s[NNT_BLK_G], 0.f, g[NNT_BLK_W_2], 2, 0, nullptr));
+        TRY(nnt_bias_grad(ctx, dOut, g[NNT_BLK_B_2]));
+        TRY(nnt_gemm_gelu_bwd(ctx, 1.f, NNT_OP_T, weight(b, NNT_BLK_W_2), NNT_OP_N, dOut, s[NNT_BLK_DG], 1, c.gelu_variant, s[NNT_BLK_H1]));
+    } else {
+        TRY(linear_bwd(b, weight(b, NNT_BLK_W_2), s[NNT_BLK_G], dOut, s[NNT_BLK_DG], g[NNT_BLK_W_2], g[NNT_BLK_B_2]));
+        TRY(nnt_gelu_bwd(ctx, c.gelu_variant, s[NNT_BLK_H1], s[NNT_BLK_DG], s[NNT_BLK_DG]));
+    }
     TRY(linear_bwd(b, weight(b, NNT_BLK_W_1), s[NNT_BLK_X3], s[NNT_BLK_DG], s[NNT_BLK_DX3], g[NNT_BLK_W_1], g[NNT_BLK_B_1]));
     // second layer norm; the residual branch adds dOut
     TRY(nnt_layernorm_bwd(ctx, s[NNT_BLK_X2], s[NNT_BLK_STATS2], s[NNT_BLK_GAMMA2], s[NNT_BLK_DX3], dOut, s[NNT_BLK_DX2],

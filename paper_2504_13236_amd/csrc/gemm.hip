@@ -112,6 +112,8 @@ struct GemmPlan {
     std::vector<int64_t> task_nfast;           // leading workgroups of each task that qualify for the direct-load kernel
     int64_t op_nfast = 0;                      // the same for the whole-operation order
     int64_t table_bytes = 0, ws_bytes = 0;     // device memory of the descriptor tables / the k-slice workspaces
+    int epi_mode = 0;                          // GemmEpi mode of a product with an activation on its result path
+    bool epi_ok = false;                       // every workgroup runs in a direct-load kernel that has that form
     bool dl_ragged = false;                    // they need the direct-load kernel's variant for ragged macro-tiles and short k-steps
     std::vector<int64_t> task_ctile;           // C tile index per task
     std::vector<std::vector<int64_t>> task_atiles, task_btiles;   // operand tiles per task (dependencies)
@@ -167,8 +169,12 @@ void drop_plans_of(nnt_ctx* ctx, uint64_t id) {
 
 // The first `nfast` workgroups of the table qualify for the direct-load kernel of the type.
 static int32_t launch_any(hipStream_t st, int dtype_in, int dtype_out, int akf, int bkf, int cfg,
-                          const GemmArgs& g, int64_t nwg, int64_t nfast = 0, bool ragged = false) {
+                          const GemmArgs& g, int64_t nwg, int64_t nfast = 0, bool ragged = false, int epi_mode = 0) {
     const bool f32 = dtype_in == NNT_F32;
+    if (epi_mode) {     // (plans with an activation form are only run when all their workgroups qualify: GemmPlan::epi_ok)
+        if (nfast != nwg) return NNT_EINVAL;
+        return f32 ? launch_gemm_f32_dl(st, akf, bkf, cfg, g, nwg, epi_mode) : NNT_EINVAL;
+    }
     auto general = [&](const GemmArgs& ga, int64_t n) {
         return f32 ? launch_gemm_f32(st, akf, bkf, cfg, ga, n) : launch_gemm_bf16(st, dtype_out == NNT_F32, akf, bkf, cfg, ga, n);
     };
@@ -449,6 +455,7 @@ SplitReduce add_slice_tasks(GemmPlan* P, const GemmTask& t0, const GemmWg& mw, c
         t.strideC = 0;
         t.bias = nullptr;
         t.cin_off = 0;
+        t.epi = 0;
         t.partial = 1;
         t.chunk0 = ranges[sidx].first;
         t.nchunk = ranges[sidx].second;
@@ -462,8 +469,9 @@ SplitReduce add_slice_tasks(GemmPlan* P, const GemmTask& t0, const GemmWg& mw, c
 // with the heads side by side along its first axis (see nnt_gemm_heads), or 0 for an ordinary tensor.  With it
 // the two batch axes stay apart (batch member, head): GemmTask::nb1 and the second strides.
 int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B, nnt_tensor* C, int ncon, int nbat,
-                   nnt_tensor* bias, nnt_tensor* R, GemmPlan* P, const int64_t* view_ld = nullptr) {
+                   nnt_tensor* bias, nnt_tensor* R, GemmPlan* P, const int64_t* view_ld = nullptr, int epi = 0) {
     const bool pairs = view_ld != nullptr;
+    if (epi && (nbat != 0 || !R || pairs)) return fail(ctx, NNT_EINVAL, "nnt_gemm_gelu: unsupported form");
     if (pairs && (nbat != 2 || ncon != 1 || bias || R)) return fail(ctx, NNT_EINVAL, "nnt_gemm_heads: unsupported form");
     const int na = A->ndim - nbat, nb = B->ndim - nbat;
     if (ncon < 1 || nbat < 0 || na < ncon || nb < ncon)
@@ -532,6 +540,7 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
             const ptrdiff_t delta = static_cast<const char*>(R->tiles[ci]) - static_cast<const char*>(C->tiles[ci]);
             if (delta % (ptrdiff_t)C->elem_size() != 0) return fail(ctx, NNT_EINVAL, "nnt_gemm_res: residual tile not aligned to the element size");
             t.cin_off = delta / (ptrdiff_t)C->elem_size();
+            t.epi = epi;
         }
         t.ldc = (pairs && view_ld[2]) ? view_ld[2] : m;
         t.strideC = t.ldc * n;
@@ -603,7 +612,8 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
         bool ragged = false;
         for (const TaskGeom& gq : geom) ragged = ragged || gq.m % 256 != 0 || gq.n % 256 != 0;
         for (const GemmChunk& c : P->chunks) ragged = ragged || c.k % 64 != 0;
-        const ShapeChoice sc = choose_shape(bf, C->dtype == NNT_F32, P->akf, P->bkf, tm, tn, ktot, true, bf && ragged);
+        // (the activation forms keep the whole contraction in one workgroup: the slice sum does not know them)
+        const ShapeChoice sc = choose_shape(bf, C->dtype == NNT_F32, P->akf, P->bkf, tm, tn, ktot, epi == 0, bf && ragged);
         P->cfg = sc.cfg;
         S = sc.s;
         n_split = sc.n_split;
@@ -717,7 +727,7 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
     const size_t n_tile_tasks = P->task_ctile.size();
     P->tile_split.assign(n_tile_tasks, GemmPlan::TileSplit{});
     std::vector<SplitReduce> red_ts;
-    if (nbat == 0 && ctx->granularity == NNT_GRAN_TILE) {      // (a plan first built for whole-operation launches has none)
+    if (nbat == 0 && epi == 0 && ctx->granularity == NNT_GRAN_TILE) {      // (a plan first built for whole-operation launches has none)
         constexpr int64_t kTargetWgs = 64, kMinSlice = 512;
         constexpr int64_t kScratchCap = (int64_t)2 << 30;      // bytes of slice scratch per plan
         const int64_t slice = (int64_t)bm * bn;
@@ -817,6 +827,20 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
         }
     }
 
+    if (epi) {
+        P->epi_mode = epi & 15;
+        bool all_fast = P->op_nwg > 0 && P->op_nfast == P->op_nwg && getenv("NNT_GEMM_NO_DL") == nullptr;
+        for (size_t ti = 0; ti + 1 < P->task_wg0.size(); ti++) all_fast = all_fast && P->task_nfast[ti] == P->task_wg0[ti + 1] - P->task_wg0[ti];
+        P->epi_ok = all_fast && !bf && gemm_f32_dl_has_act(P->akf, P->bkf, P->epi_mode);
+        if (P->epi_ok) {
+            const std::string old_name = P->label.substr(0, P->label.find('>') + 1);
+            const char* tf[2] = {"false", "true"};
+            std::ostringstream l;
+            l << "gemm_f32_dl_act_kernel<" << tf[P->akf] << (P->cfg == kCfgSquare ? ", 2, 2, " : ", 1, 2, ") << P->epi_mode << ">";
+            P->label = l.str() + P->label.substr(old_name.size());
+        }
+    }
+
     auto up = [&](void** d, const void* h, size_t bytes) -> hipError_t {
         if (bytes == 0) return hipSuccess;
         hipError_t e = hipMalloc(d, bytes);
@@ -841,12 +865,16 @@ extern "C" int32_t nnt_gemm(nnt_ctx* ctx, float alpha, int32_t opA, nnt_tensor* 
 
 namespace {
 
+// what gemm_core answers when the plan of a product with an activation form has workgroups that no kernel with that
+// form takes (never leaves the library: the callers then run the product and the activation as two passes)
+constexpr int32_t kNoActKernel = 1 << 20;
+
 // The product proper.  A, B, C give the geometry (ordinary tensors, or the windows of nnt_gemm_heads: then `view_ld`
 // and `key_extra` are set); `dep` are the tensors whose tiles order the tasks (the operands themselves, or what
 // the windows look at).
 int32_t gemm_core(nnt_ctx* ctx, float alpha, int32_t opA, nnt_tensor* A, int32_t opB, nnt_tensor* B, float beta, nnt_tensor* C,
                   int32_t ncon, int32_t nbat, nnt_tensor* bias, nnt_tensor* R, nnt_tensor* const* dep, const int64_t* view_ld,
-                  const std::string& key_extra, int32_t part_c = 0) {
+                  const std::string& key_extra, int32_t part_c = 0, int epi = 0) {
     std::ostringstream key;
     key << opA << opB << ':' << A->id << ':' << B->id << ':' << C->id << ':' << (bias ? bias->id : 0) << ':' << ncon << ':' << nbat
         << ':' << (R ? R->id : 0) << key_extra;
@@ -855,13 +883,15 @@ int32_t gemm_core(nnt_ctx* ctx, float alpha, int32_t opA, nnt_tensor* A, int32_t
     if (it == ctx->gemm_plans.end()) {
         if (ctx->capturing) return fail(ctx, NNT_ESTATE, "nnt_gemm: plan must exist before capture (run the call once first)");
         std::shared_ptr<GemmPlan> np(new GemmPlan());
-        int32_t rc = build_plan(ctx, opA, A, opB, B, C, ncon, nbat, bias, R, np.get(), view_ld);
+        int32_t rc = build_plan(ctx, opA, A, opB, B, C, ncon, nbat, bias, R, np.get(), view_ld, epi);
         if (rc != NNT_OK) return rc;
         P = np.get();
         ctx->gemm_plans[key.str()] = np;
     } else {
         P = it->second.get();
     }
+    if (epi && !P->epi_ok) return kNoActKernel;
+    const int epi_mode = P->epi_mode;
     nnt_tensor* const dA = dep[0];
     nnt_tensor* const dB = dep[1];
     nnt_tensor* const dC = dep[2];
@@ -877,7 +907,7 @@ int32_t gemm_core(nnt_ctx* ctx, float alpha, int32_t opA, nnt_tensor* A, int32_t
         std::vector<Access> acc = {dA->all(kRead), dB->all(kRead), dC->all((view_ld && view_ld[2]) ? kWritePart : (R ? kWrite : cmode))};
         acc[2].part = part_c;
         if (bias) acc.push_back(bias->all(kRead));
-        if (R && beta != 0.f) acc.push_back(R->all(kRead));
+        if (R && (beta != 0.f || epi)) acc.push_back(R->all((epi & 15) == kEpiGeluOut ? kWrite : kRead));
         g.wgs = P->d_wgs_op;
         const int64_t nwg = P->op_nwg;
         if (nwg == 0) return NNT_OK;
@@ -895,14 +925,14 @@ int32_t gemm_core(nnt_ctx* ctx, float alpha, int32_t opA, nnt_tensor* A, int32_t
             }, 2);
         }
         return submit(ctx, acc, [=](hipStream_t st) {
-            return launch_any(st, P->dtype_in, P->dtype_out, P->akf, P->bkf, P->cfg, g, nwg, P->op_nfast, P->dl_ragged);
+            return launch_any(st, P->dtype_in, P->dtype_out, P->akf, P->bkf, P->cfg, g, nwg, P->op_nfast, P->dl_ragged, epi_mode);
         });
     }
     const size_t n_tile_tasks = P->task_ctile.size();
     for (size_t ti = 0; ti < n_tile_tasks; ti++) {
         std::vector<Access> acc;
         acc.push_back(C->one(P->task_ctile[ti], R ? kWrite : cmode));
-        if (R && beta != 0.f) acc.push_back(R->one(P->task_ctile[ti], kRead));
+        if (R && (beta != 0.f || epi)) acc.push_back(R->one(P->task_ctile[ti], (epi & 15) == kEpiGeluOut ? kWrite : kRead));
         for (int64_t a : P->task_atiles[ti]) acc.push_back(A->one(a, kRead));
         for (int64_t b : P->task_btiles[ti]) acc.push_back(B->one(b, kRead));
         if (bias) acc.push_back(bias->one(P->task_bias_tile[ti], kRead));
@@ -927,7 +957,7 @@ int32_t gemm_core(nnt_ctx* ctx, float alpha, int32_t opA, nnt_tensor* A, int32_t
             const int64_t nwg = P->task_wg0[ti + 1] - P->task_wg0[ti];
             const int64_t nfast = P->task_nfast[ti];
             rc = submit(ctx, acc, [=](hipStream_t st) {
-                return launch_any(st, P->dtype_in, P->dtype_out, P->akf, P->bkf, P->cfg, gt, nwg, nfast, P->dl_ragged);
+                return launch_any(st, P->dtype_in, P->dtype_out, P->akf, P->bkf, P->cfg, gt, nwg, nfast, P->dl_ragged, epi_mode);
             });
         }
 
@@ -1018,6 +1048,41 @@ extern "C" int32_t nnt_gemm_res(nnt_ctx* ctx, float alpha, int32_t opA, nnt_tens
     }
     nnt_tensor* const dep[3] = {A, B, C};
     return gemm_core(ctx, alpha, opA, A, opB, B, beta, C, ncon, nbat, bias, R, dep, nullptr, std::string());
+}
+
+namespace {
+
+int32_t gemm_gelu(nnt_ctx* ctx, const char* who, int mode, float alpha, int32_t opA, nnt_tensor* A, int32_t opB, nnt_tensor* B, nnt_tensor* C,
+                  int32_t ncon, nnt_tensor* bias, int32_t variant, nnt_tensor* X) {
+    NNT_CHECK_CTX(ctx);
+    if (!A || !B || !C || !X) return fail(ctx, NNT_EINVAL, std::string(who) + ": null tensor");
+    if ((opA != NNT_OP_N && opA != NNT_OP_T) || (opB != NNT_OP_N && opB != NNT_OP_T) || (variant != NNT_GELU_TANH && variant != NNT_GELU_ERF))
+        return fail(ctx, NNT_EINVAL, std::string(who) + ": bad op or GELU variant");
+    if (X == C || X == A || X == B || X->dtype != C->dtype || !same_tiling(X, C))
+        return fail(ctx, NNT_EINVAL, std::string(who) + ": the second tensor must be distinct from A, B and C and have C's type, shape and tiling");
+    for (int64_t t = 0; t < C->ntiles; t++)
+        if (C->tiles[t] && !X->tiles[t]) return fail(ctx, NNT_EINVAL, std::string(who) + ": the second tensor lacks a tile that C has");
+    nnt_tensor* const dep[3] = {A, B, C};
+    std::ostringstream extra;
+    extra << ":gelu" << mode << variant;
+    const int32_t rc = gemm_core(ctx, alpha, opA, A, opB, B, 0.f, C, ncon, 0, bias, X, dep, nullptr, extra.str(), 0, mode | (variant << 4));
+    if (rc != kNoActKernel) return rc;
+    // bf16, or ragged macro-tiles, operand forms or alignments that only the general kernels take: product, then activation
+    int32_t r2 = gemm_core(ctx, alpha, opA, A, opB, B, 0.f, C, ncon, 0, bias, nullptr, dep, nullptr, std::string());
+    if (r2 != NNT_OK) return r2;
+    return mode == kEpiGeluOut ? nnt_gelu(ctx, variant, C, X) : nnt_gelu_bwd(ctx, variant, X, C, C);
+}
+
+}  // namespace
+
+extern "C" int32_t nnt_gemm_gelu(nnt_ctx* ctx, float alpha, int32_t opA, nnt_tensor* A, int32_t opB, nnt_tensor* B, nnt_tensor* C,
+                                 int32_t ncon, nnt_tensor* bias, int32_t variant, nnt_tensor* G) {
+    return gemm_gelu(ctx, "nnt_gemm_gelu", kEpiGeluOut, alpha, opA, A, opB, B, C, ncon, bias, variant, G);
+}
+
+extern "C" int32_t nnt_gemm_gelu_bwd(nnt_ctx* ctx, float alpha, int32_t opA, nnt_tensor* A, int32_t opB, nnt_tensor* B, nnt_tensor* C,
+                                     int32_t ncon, int32_t variant, nnt_tensor* X) {
+    return gemm_gelu(ctx, "nnt_gemm_gelu_bwd", kEpiGeluGradMul, alpha, opA, A, opB, B, C, ncon, nullptr, variant, X);
 }
 
 extern "C" int32_t nnt_gemm_heads(nnt_ctx* ctx, float alpha, int32_t opA, nnt_tensor* A, int32_t partA, int32_t opB, nnt_tensor* B,

@@ -25,6 +25,19 @@ struct GemmTask {
     int64_t cin_off;        // the beta term is read at C + cin_off (elements of C's type): 0 = from C itself, else from
                             // the tile of a second tensor with C's geometry (a residual input)
     int64_t strideC2;       // elements
+    int32_t epi;            // 0, or an activation applied on the way out (GemmEpi mode | GELU variant << 4) by the kernels
+                            // built for it; beta is not used then
+};
+
+// Activations of the result path (section 3: the activation follows the first linear layer of the MLP and its
+// derivative multiplies what the second one's adjoint yields).  Both use the tile of a second tensor with C's
+// geometry at C + cin_off.  Only the fp32 direct-load kernels have these forms: their result path has matrix
+// work of other workgroups to hide behind, while the bf16 kernels, eight times faster per flop, showed the
+// activation's arithmetic in full (slower than a pass of its own over the stored result).
+enum GemmEpi {
+    kEpiNone = 0,
+    kEpiGeluOut = 1,      // C = alpha A B + bias, and gelu(C) is stored at C + cin_off
+    kEpiGeluGradMul = 2   // C = (alpha A B + bias) * gelu'(x), x read at C + cin_off
 };
 
 struct GemmChunk {
@@ -85,7 +98,10 @@ int32_t launch_gemm_bf16_dl(hipStream_t st, int out_is_f32, int akf, int bkf, in
 int gemm_bf16_dl_occupancy(int out_is_f32, int akf, int bkf, int cfg);
 // fp32: 128 x 128 (kCfgSquare) or 64 x 128 (kCfgMid, kCfgSkinny64n128) macro-tiles that lie wholly inside their
 // C tile, 16-byte aligned operands, chunk lengths that are multiples of 32
-int32_t launch_gemm_f32_dl(hipStream_t st, int akf, int bkf, int cfg, const GemmArgs& g, int64_t nwg);
+// `epi_mode` (a GemmEpi mode, 0 for the plain product) picks the kernels with an activation on the result path; they exist
+// for the forms gemm_f32_dl_has_act names.
+int32_t launch_gemm_f32_dl(hipStream_t st, int akf, int bkf, int cfg, const GemmArgs& g, int64_t nwg, int epi_mode = 0);
+bool gemm_f32_dl_has_act(int akf, int bkf, int epi_mode);
 int gemm_f32_dl_occupancy(int akf, int bkf, int cfg);
 // workgroups of the kernel instance that a compute unit holds at a time (registers, LDS)
 int gemm_f32_occupancy(int akf, int bkf, int cfg);

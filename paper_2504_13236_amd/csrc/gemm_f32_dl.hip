@@ -24,6 +24,7 @@
 //     banks.  A fragment of a substep is four 32-bit reads.
 // A k-step is two substeps of 8 k: in substep s lane (row, h) holds k = 8 s + 4 h + i,
 // i = 0..3, and matrix instruction i multiplies the two k that the half-waves hold.
+#include "gelu_math.hpp"
 #include "gemm_common.hpp"
 #include "gemm_dl_common.hpp"
 #include "nntile_mi.h"
@@ -113,13 +114,13 @@ __device__ __forceinline__ void read_frag(typename FragSel<KF>::type& f, const F
 }
 
 // Macro-tile (64 WMB) x (64 WNB): four waves as 2 x 2, each (32 WMB) x (32 WNB).
-template <bool AKF, bool BKF, int WMB, int WNB>
-__global__ void __launch_bounds__(256, 2) gemm_f32_dl_kernel(const GemmArgs g) {
+// EPI: the activation form of the result path (GemmEpi), 0 for the plain one.
+template <bool AKF, bool BKF, int WMB, int WNB, int EPI>
+__device__ __forceinline__ void f32_dl_body(const GemmArgs& g, char* lds) {
     constexpr int BM = 64 * WMB, BN = 64 * WNB;
     constexpr int kOpABytes = BM * kBK * 4, kOpBBytes = BN * kBK * 4, kStageBytes = kOpABytes + kOpBBytes;
     constexpr int NIA = BM / 64, NIB = BN / 64, kLoads = NIA + NIB;     // load instructions per wave and step
     constexpr int kFrags = WNB + WMB, kMfma = 4 * WNB * WMB;            // per substep
-    __shared__ __attribute__((aligned(16))) char lds[kStages * kStageBytes];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -330,6 +331,8 @@ __global__ void __launch_bounds__(256, 2) gemm_f32_dl_kernel(const GemmArgs g) {
     // epilogue: lane holds row m = r32, columns n = 8 * (i / 4) + 4 * half + i % 4 of each 32 x 32 block
     float* C = static_cast<float*>(task.C) + (int64_t)bat_lo * task.strideC + (int64_t)bat_hi * task.strideC2;
     const float alpha = task.partial ? 1.f : g.alpha, beta = task.partial ? 0.f : g.beta;
+    constexpr int emode = EPI;          // (the activation forms are never k-slices)
+    const int evar = task.epi >> 4;
     // The beta term (C itself, or the tile of a residual input behind cin_off) is read for a whole row block
     // before the first store of that block: a load placed after a store to what may be the same tile has
     // to wait for it, and 32 such round trips per block cost a product with one round of workgroups a
@@ -339,7 +342,7 @@ __global__ void __launch_bounds__(256, 2) gemm_f32_dl_kernel(const GemmArgs g) {
         const int gm = m0 + (wm * WMB + bm) * 32 + r32;
         const float bias = (task.bias && !task.partial) ? task.bias[gm] : 0.f;
         float cin[WNB][16];
-        if (beta != 0.f) {
+        if (beta != 0.f || emode == kEpiGeluGradMul) {
 #pragma unroll
             for (int bn = 0; bn < WNB; bn++)
 #pragma unroll
@@ -354,14 +357,36 @@ __global__ void __launch_bounds__(256, 2) gemm_f32_dl_kernel(const GemmArgs g) {
             for (int i = 0; i < 16; i++) {
                 const int gn = n0 + (wn * WNB + bn) * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
                 float v = alpha * acc[bn][bm][i] + bias;
-                if (beta != 0.f) v += beta * cin[bn][i];
+                if (emode == kEpiGeluGradMul) v *= gelu_grad_f(cin[bn][i], evar);
+                else if (beta != 0.f) v += beta * cin[bn][i];
                 C[gm + (int64_t)gn * task.ldc] = v;
+                if (emode == kEpiGeluOut) C[gm + (int64_t)gn * task.ldc + task.cin_off] = gelu_f(v, evar);
             }
         }
     }
 }
 
+template <bool AKF, bool BKF, int WMB, int WNB>
+__global__ void __launch_bounds__(256, 2) gemm_f32_dl_kernel(const GemmArgs g) {
+    __shared__ __attribute__((aligned(16))) char lds[kStages * (64 * WMB + 64 * WNB) * kBK * 4];
+    f32_dl_body<AKF, BKF, WMB, WNB, 0>(g, lds);
+}
+
+// The same product with an activation on its result path (nnt_gemm_gelu: EPI = kEpiGeluOut, B as [k, n];
+// nnt_gemm_gelu_bwd: kEpiGeluGradMul, A read transposed): kernels of their own, so that the plain ones carry
+// none of that code.
+template <bool AKF, int WMB, int WNB, int EPI>
+__global__ void __launch_bounds__(256, 2) gemm_f32_dl_act_kernel(const GemmArgs g) {
+    __shared__ __attribute__((aligned(16))) char lds[kStages * (64 * WMB + 64 * WNB) * kBK * 4];
+    f32_dl_body<AKF, true, WMB, WNB, EPI>(g, lds);
+}
+
 using KernelFn = void (*)(const GemmArgs);
+
+template <int WMB, int WNB>
+KernelFn act_kernel_of(int epi_mode) {
+    return epi_mode == kEpiGeluOut ? gemm_f32_dl_act_kernel<false, WMB, WNB, kEpiGeluOut> : gemm_f32_dl_act_kernel<true, WMB, WNB, kEpiGeluGradMul>;
+}
 
 template <int WMB, int WNB>
 KernelFn kernel_of(int akf, int bkf) {
@@ -375,8 +400,19 @@ KernelFn kernel_of(int akf, int bkf, int cfg) {
 
 }  // namespace
 
-int32_t launch_gemm_f32_dl(hipStream_t st, int akf, int bkf, int cfg, const GemmArgs& g, int64_t nwg) {
+bool gemm_f32_dl_has_act(int akf, int bkf, int epi_mode) {
+    return bkf && ((epi_mode == kEpiGeluOut && !akf) || (epi_mode == kEpiGeluGradMul && akf));
+}
+
+int32_t launch_gemm_f32_dl(hipStream_t st, int akf, int bkf, int cfg, const GemmArgs& g, int64_t nwg, int epi_mode) {
     if (nwg <= 0) return NNT_OK;
+    if (epi_mode) {
+        if (!gemm_f32_dl_has_act(akf, bkf, epi_mode)) return NNT_EINVAL;
+        const bool mid = cfg == kCfgSkinny64n128 || cfg == kCfgMid;
+        const KernelFn fn = mid ? act_kernel_of<1, 2>(epi_mode) : act_kernel_of<2, 2>(epi_mode);
+        hipLaunchKernelGGL(fn, dim3((unsigned)nwg), dim3(256), 0, st, g);
+        return hipGetLastError() == hipSuccess ? NNT_OK : NNT_EHIP;
+    }
     hipLaunchKernelGGL(kernel_of(akf, bkf, cfg), dim3((unsigned)nwg), dim3(256), 0, st, g);
     return hipGetLastError() == hipSuccess ? NNT_OK : NNT_EHIP;
 }

@@ -350,6 +350,55 @@ def test_gemm_with_a_residual_input(mods, gran, dtype, shape):
             capi.nnt_gemm_res(ctx.h, 1.0, 0, tW.h, 0, tX.h, 1.0, tY.h, 1, 0, None, other.h)   # tiled differently
 
 
+@pytest.mark.parametrize("gran", GRANS)
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("variant", [0, 1])
+@pytest.mark.parametrize("shape", ["ragged", "direct-load", "long-k"])
+def test_gemm_with_the_activation_on_its_way_out(mods, gran, dtype, variant, shape):
+    """H = W X +. b and G = gelu(H) from one launch, and dH = (W^T dY) * gelu'(H) from one launch (the MLP of
+    section 3 without activation passes of their own): general kernels on ragged tiles, the direct-load
+    kernels on whole macro-tiles, and a long contraction that a plain product would cut into k-slices."""
+    capi, tiled = mods
+    r = rng(91 + variant)
+    if shape == "ragged":
+        m, n, k, tw, tx, ty = 200, 150, 136, (64, 48), (48, 40), (64, 40)
+    elif shape == "direct-load":
+        m, n, k, tw, tx, ty = 512, 768, 192, (256, 64), (64, 256), (256, 256)
+    else:
+        m, n, k, tw, tx, ty = 256, 256, 4096, (256, 1024), (1024, 256), (256, 256)
+    name = ("tanh", "erf")[variant]
+    W = quant(r.standard_normal((m, k)) / np.sqrt(k), dtype)
+    X = quant(r.standard_normal((k, n)) * 1.5, dtype)
+    b = r.standard_normal(m).astype(np.float32) * 0.5
+    H = D.contract(1.0, "N", W, "N", X, 0.0, None, 1, 0) + b.reshape(-1, 1)
+    junk = quant(r.standard_normal((m, n)), dtype)
+    with tiled.Context(n_streams=2, granularity=gran) as ctx:
+        tW, tX = T(tiled, ctx, W, tw, dtype), T(tiled, ctx, X, tx, dtype)
+        tH, tG = T(tiled, ctx, junk, ty, dtype), T(tiled, ctx, junk, ty, dtype)
+        tb = T(tiled, ctx, b, ty[:1], "f32")
+        capi.nnt_gemm_gelu(ctx.h, 1.0, 0, tW.h, 0, tX.h, tH.h, 1, tb.h, variant, tG.h)
+        Hd = tH.download()
+        check(Hd, H, dtype, "H = W X + b")
+        check(tG.download(), D.gelu(H, name), dtype, "G = gelu(H)")
+        # the same G as the activation pass over the stored H gives
+        tG2 = T(tiled, ctx, junk, ty, dtype)
+        capi.nnt_gelu(ctx.h, variant, tH.h, tG2.h)
+        np.testing.assert_array_equal(tG.download(), tG2.download())
+        # adjoint: dX3-shaped product W^T dY (k x n here: contraction over m) times gelu' of a tensor of its shape
+        dY = quant(r.standard_normal((m, n)), dtype)
+        Z = quant(r.standard_normal((k, n)) * 1.5, dtype)
+        tk = (tw[1], tx[1])
+        tdY, tZ, tdZ = T(tiled, ctx, dY, ty, dtype), T(tiled, ctx, Z, tk, dtype), T(tiled, ctx, quant(r.standard_normal((k, n)), dtype), tk, dtype)
+        capi.nnt_gemm_gelu_bwd(ctx.h, 0.5, 1, tW.h, 0, tdY.h, tdZ.h, 1, variant, tZ.h)
+        want = D.contract(0.5, "T", W, "N", dY, 0.0, None, 1, 0) * D.gelu_grad(np.asarray(Z, np.float64), name)
+        check(tdZ.download(), want, dtype, "dZ = (W^T dY) gelu'(Z)")
+        np.testing.assert_array_equal(tZ.download(), np.asarray(Z, np.float32))      # only read
+        with pytest.raises(capi.NntError):
+            capi.nnt_gemm_gelu(ctx.h, 1.0, 0, tW.h, 0, tX.h, tH.h, 1, tb.h, variant, tH.h)      # G must not be C
+        with pytest.raises(capi.NntError):
+            capi.nnt_gemm_gelu_bwd(ctx.h, 1.0, 1, tW.h, 0, tdY.h, tdZ.h, 1, 7, tZ.h)            # unknown variant
+
+
 def test_device_memory_of_the_library_is_reported(mods):
     """nnt_ctx_stats: tile-pointer tables and plan tables count as table bytes, the fp32 workspace of a
     product cut into k-slices as workspace bytes; both shrink again when the tensors go."""
