@@ -1065,8 +1065,10 @@ int32_t gemm_gelu(nnt_ctx* ctx, const char* who, int mode, float alpha, int32_t 
     nnt_tensor* const dep[3] = {A, B, C};
     std::ostringstream extra;
     extra << ":gelu" << mode << variant;
-    const int32_t rc = gemm_core(ctx, alpha, opA, A, opB, B, 0.f, C, ncon, 0, bias, X, dep, nullptr, extra.str(), 0, mode | (variant << 4));
-    if (rc != kNoActKernel) return rc;
+    if (A->dtype == NNT_F32 && gemm_f32_dl_has_act(opA == NNT_OP_T, opB == NNT_OP_N, mode)) {
+        const int32_t rc = gemm_core(ctx, alpha, opA, A, opB, B, 0.f, C, ncon, 0, bias, X, dep, nullptr, extra.str(), 0, mode | (variant << 4));
+        if (rc != kNoActKernel) return rc;
+    }
     // bf16, or ragged macro-tiles, operand forms or alignments that only the general kernels take: product, then activation
     int32_t r2 = gemm_core(ctx, alpha, opA, A, opB, B, 0.f, C, ncon, 0, bias, nullptr, dep, nullptr, std::string());
     if (r2 != NNT_OK) return r2;
