@@ -260,7 +260,10 @@ def measure(args, cfg, inp, attention, capi, tiled, torch, workload):
     gran = capi.NNT_GRAN_OP if args.granularity == "op" else capi.NNT_GRAN_TILE
     ctx = tiled.Context(n_streams=args.streams, granularity=gran)
     nblk = max(1, args.blocks)
-    blks = [tiled.Gpt2Block(ctx, cfg.N_e, cfg.N_h, cfg.N_m, cfg.N_s, cfg.N_b, workload.base_tiles(cfg), dtype=cfg.dtype,
+    tiles = workload.base_tiles(cfg)
+    if args.batch_tile:
+        tiles = dict(tiles, b=min(args.batch_tile, cfg.N_b))
+    blks = [tiled.Gpt2Block(ctx, cfg.N_e, cfg.N_h, cfg.N_m, cfg.N_s, cfg.N_b, tiles, dtype=cfg.dtype,
                             eps=cfg.eps, gelu=cfg.gelu, adam=cfg.adam, fused_attention=attention == "fused") for _ in range(nblk)]
     for b in blks:
         b.set_params({k: inp[k] for k in workload.PARAM_NAMES})
@@ -399,7 +402,7 @@ def measure(args, cfg, inp, attention, capi, tiled, torch, workload):
            "config": {"workload": "%s: one GPT-2 block %s N_e=%d N_h=%d N_m=%d N_s=%d N_b=%d tile=%d, forward+backward%s, causal"
                                   % (cfg.name, cfg.dtype, cfg.N_e, cfg.N_h, cfg.N_m, cfg.N_s, cfg.N_b, cfg.tile,
                                      "+Adam" if cfg.adam else ""),
-                      "streams": args.streams, "granularity": args.granularity, "graph_replay": bool(args.graph),
+                      "streams": args.streams, "granularity": args.granularity, "batch_tile": tiles["b"], "graph_replay": bool(args.graph),
                       "attention": attention, "blocks": nblk,
                       "flops_per_step": flops,
                       "attention_flops": "visible (key, query) pairs only, no recomputation" if attention == "fused"
@@ -488,6 +491,9 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="workload number 1..5 (default: the fp32 GPT-2-small-shaped block)")
     ap.add_argument("--streams", type=int, default=2)
     ap.add_argument("--granularity", choices=["op", "tile"], default="op")
+    ap.add_argument("--batch-tile", type=int, default=0, metavar="N",
+                    help="cut the batch axis every N members (default: whole; 1 with --granularity tile is the stress "
+                         "case of the executor: every tile of every batch member a task of its own)")
     ap.add_argument("--graph", action="store_true", help="replay the step from a captured HIP graph")
     ap.add_argument("--blocks", type=int, default=1, help="chain this many identical blocks into one flow of tasks")
     ap.add_argument("--attention", choices=["tiles", "fused"], default="tiles",
@@ -562,7 +568,7 @@ def main():
         f = measure(args, cfg, inp, "fused", capi, tiled, torch, workload)
         out["next_rows"] = {"fused_attention": {k: f[k] for k in ("value", "unit", "ms_per_step", "config", "summary")}}
         out["next_rows"]["fused_attention"]["kernels"] = {k: v for k, v in f["kernels"].items() if k.startswith("attention")}
-    if args.config == 2 and args.blocks == 1 and args.granularity == "op" and not args.graph and not args.no_other_configs:
+    if args.config == 2 and args.blocks == 1 and args.granularity == "op" and not args.graph and not args.batch_tile and not args.no_other_configs:
         # the bf16 configurations beside the headline (same run, same launch configuration, fewer steps for the
         # largest one): the metric's second figure, tile-GEMM share of the MFMA peak, for bf16
         out["other_configs"] = {}
