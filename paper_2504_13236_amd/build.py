@@ -34,6 +34,9 @@ FLAGS = [
 # inline assembly and waited for later by hand): a register the compiler spills or reloads
 # between a read and its wait would hold stale data, so inside their loops these kernels
 # must not touch scratch memory.  (Spills in the prologue or after the last wait are harmless.)
+# Their assembly is also scanned for any instruction that names a register between the LDS read that
+# targets it and the next full wait (registers_touched_in_flight): a copy or move the compiler
+# places there would read stale data just the same.
 IN_FLIGHT_SOURCES = ("gemm_bf16_dl.hip", "gemm_f32_dl.hip")
 
 
@@ -51,6 +54,61 @@ def scratch_in_loops(asm_text: str) -> list:
             in_loop = "Loop" in t
         elif in_loop and t.startswith("scratch_"):
             hits.append((kernel, no))
+    return hits
+
+
+_VREG = re.compile(r"\bv(\d+)\b|\bv\[(\d+):(\d+)\]")
+
+
+def _vregs(text: str) -> set:
+    out = set()
+    for m in _VREG.finditer(text):
+        if m.group(1) is not None:
+            out.add(int(m.group(1)))
+        else:
+            out.update(range(int(m.group(2)), int(m.group(3)) + 1))
+    return out
+
+
+def registers_touched_in_flight(asm_text: str) -> list:
+    """[(kernel, line number, register, line of the read)]: instructions of a device assembly listing that name a
+    vector register while an LDS read into it is still in flight, i.e. between the ds_read that targets it and
+    the next `s_waitcnt lgkmcnt(0)`.
+
+    The compiler believes such a register holds its value from the read's asm statement on, so a copy, a move to
+    an accumulation register or any other use it schedules before the hand-placed wait would see stale data.
+    The scan is linear per kernel (listing order); only a full wait clears the reads in flight."""
+    hits = []
+    kernel, pending = None, {}
+    for no, line in enumerate(asm_text.splitlines(), 1):
+        t = line.split(";")[0].strip()
+        if not t:
+            continue
+        if t.startswith("_Z") and t.endswith(":"):
+            kernel, pending = t[:-1], {}
+            continue
+        if t.endswith(":") or t.startswith("."):
+            continue
+        op, _, rest = t.partition(" ")
+        if op == "s_waitcnt":
+            if "lgkmcnt(0)" in rest:
+                pending = {}
+            continue
+        if op == "s_endpgm":
+            pending = {}
+            continue
+        if op.startswith("ds_read"):
+            ops = [o.strip() for o in rest.split(",")]
+            for o in ops[1:]:                       # the address is read now
+                for r in _vregs(o):
+                    if r in pending:
+                        hits.append((kernel, no, "v%d" % r, pending[r]))
+            for r in _vregs(ops[0]):
+                pending[r] = no
+            continue
+        for r in _vregs(rest):
+            if r in pending:
+                hits.append((kernel, no, "v%d" % r, pending[r]))
     return hits
 
 
@@ -99,6 +157,11 @@ def _compile(src: str, only_if_stale: bool = False) -> str:
             raise RuntimeError("%s: scratch access inside a loop of %s (assembly line %d, %d in all): "
                                "in-flight fragment registers do not survive a spill"
                                % (os.path.basename(src), hits[0][0], hits[0][1], len(hits)))
+        with open(os.path.join(OBJ, stem + "-hip-amdgcn-amd-amdhsa-gfx950.s")) as f:
+            early = registers_touched_in_flight(f.read())
+        if early:
+            raise RuntimeError("%s: %s, assembly line %d, uses %s before the wait for the LDS read of line %d (%d such uses in all)"
+                               % (os.path.basename(src), early[0][0], early[0][1], early[0][2], early[0][3], len(early)))
     with open(obj + ".usage.json", "w") as f:
         json.dump(usage, f, indent=1, sort_keys=True)
     return obj

@@ -175,6 +175,34 @@ def test_build_guard_finds_scratch_only_inside_loops():
     assert resource_usage(remarks) == {"_Z6kernelv": {"VGPRs": 72, "ScratchSize": 8, "LDS Size": 61440}}
 
 
+def test_build_guard_finds_registers_used_while_their_lds_read_is_in_flight():
+    """The build also refuses direct-load kernels in whose assembly any instruction names a register
+    between the LDS read that targets it and the next full wait (a copy the compiler schedules there
+    would read stale data)."""
+    from paper_2504_13236_amd.build import registers_touched_in_flight
+    listing = "\n".join([
+        "_Z6kernelv:                             ; @_Z6kernelv",
+        "\tds_read_b128 v[4:7], v1 offset:16",
+        "\tv_mfma_f32_32x32x2_f32 v[16:31], v2, v3, v[16:31]",       # other registers: fine
+        "\tv_mov_b32_e32 v9, v5",                                     # copies a register of the read in flight
+        "\ts_waitcnt vmcnt(0)",                                       # not a wait for LDS
+        "\tds_read_b32 v10, v6",                                      # address taken from a register in flight
+        "\ts_waitcnt lgkmcnt(0)",
+        "\tv_mfma_f32_32x32x2_f32 v[16:31], v4, v10, v[16:31]",      # after the wait: fine
+        ".LBB0_1:                                ; =>This Inner Loop Header: Depth=1",
+        "\tds_read_b64_tr_b16 v[12:13], v1 offset:64",
+        "\ts_waitcnt lgkmcnt(1)",                                     # a partial wait clears nothing
+        "\tv_accvgpr_write_b32 a0, v13",
+        "\ts_waitcnt vmcnt(0) lgkmcnt(0)",
+        "\tv_accvgpr_write_b32 a0, v13",
+        "\ts_endpgm",
+        "_Z5otherv:",
+        "\tv_mov_b32_e32 v9, v12",                                    # another kernel starts clean
+    ])
+    assert registers_touched_in_flight(listing) == [("_Z6kernelv", 4, "v5", 2), ("_Z6kernelv", 6, "v6", 2),
+                                                    ("_Z6kernelv", 12, "v13", 10)]
+
+
 def _simulate(capi, n_streams, serial, n_tiles, tasks):
     import numpy as np
     first = np.zeros(len(tasks) + 1, np.int32)
