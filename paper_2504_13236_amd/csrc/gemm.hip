@@ -314,7 +314,11 @@ static ShapeChoice choose_shape(bool bf16, bool out_f32, int akf, int bkf, const
     return best;
 }
 
-static int pick_cfg(int bf16, int64_t m_max, int64_t n_max, int64_t n_tiles_big, int64_t k_max) {
+// `kk`: both operands are k-contiguous (A read transposed, B as [k, n]).
+static int pick_cfg(int bf16, int64_t m_max, int64_t n_max, int64_t n_tiles_big, int64_t k_max, bool kk = false) {
+    // fp32 products whose whole contraction is a head size and whose result is score-shaped: bound by their result
+    // stores, which a workgroup waits out before it ends, so the shape of which a compute unit holds three
+    if (!bf16 && kk && k_max <= 64 && m_max >= 64 && n_max >= 128) return kCfgResident;
     // bf16 products with few rows (m = head size) read a score-shaped operand and are bound by that traffic: the
     // 128-row direct-load shape streams it four k-steps ahead
     if (bf16 && m_max <= 128) return kCfgWide;
@@ -370,20 +374,20 @@ extern "C" int32_t nnt_tile_gemm(void* stream, int32_t dtype_in, int32_t dtype_o
     g.alpha = alpha;
     g.beta = beta;
     int bm, bn;
-    int cfg = pick_cfg(bf, m, n, ((m + 255) / 256) * ((n + 255) / 256) * batch, k);
+    int cfg = pick_cfg(bf, m, n, ((m + 255) / 256) * ((n + 255) / 256) * batch, k, opA == NNT_OP_T && opB == NNT_OP_N);
     const bool odd_shape = bf && (m % 256 != 0 || n % 256 != 0 || k % 64 != 0);
     if (batch == 1 && (cfg == kCfgSquare || cfg == kCfgMid || cfg == kCfgTall))
         cfg = choose_shape(bf, dtype_out == NNT_F32, opA == NNT_OP_T, opB == NNT_OP_N, {m}, {n}, {k}, false, odd_shape).cfg;
     // debugging aid: NNT_TILE_GEMM_CFG=<number of a macro-tile configuration> overrides the choice for this entry point
     static const char* const force = getenv("NNT_TILE_GEMM_CFG");
-    if (force && atoi(force) >= kCfgSquare && atoi(force) <= kCfgWide) cfg = atoi(force);
+    if (force && atoi(force) >= kCfgSquare && atoi(force) <= kCfgWide) cfg = atoi(force);      // (not kCfgResident: it exists for one operand form)
     gemm_cfg_tile(bf, cfg, &bm, &bn);
     g.grid_m = (int32_t)((m + bm - 1) / bm);
     g.grid_n = (int32_t)((n + bn - 1) / bn);
     const int64_t nwg = (int64_t)g.grid_m * g.grid_n * batch;
     if (nwg > INT32_MAX) return NNT_EINVAL;
-    bool fast = (bf ? (cfg == kCfgSquare || cfg == kCfgTall || cfg == kCfgWide) : (cfg == kCfgSquare || cfg == kCfgSkinny64n128 || cfg == kCfgMid)) && m % bm == 0 && n % bn == 0 && k > 0 &&
-                k % ((bf && cfg == kCfgSquare) ? 64 : 32) == 0 && g.one_chunk.vec_ok == 3;
+    bool fast = (bf ? (cfg == kCfgSquare || cfg == kCfgTall || cfg == kCfgWide) : (cfg == kCfgSquare || cfg == kCfgSkinny64n128 || cfg == kCfgMid || cfg == kCfgResident)) &&
+                m % bm == 0 && n % bn == 0 && k > 0 && k % ((bf && cfg == kCfgSquare) ? 64 : 32) == 0 && g.one_chunk.vec_ok == 3;
     bool ragged = false;
     if (!fast && bf && (cfg == kCfgTall || cfg == kCfgWide) && k > 0 && k % 8 == 0 && g.one_chunk.vec_ok == 3) {
         // the variant for macro-tiles that end inside the tile and for a short last k-step
@@ -602,7 +606,7 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
         for (int32_t q = P->tasks[ti].chunk0; q < P->tasks[ti].chunk0 + P->tasks[ti].nchunk; q++) ktot[ti] += P->chunks[q].k;
     int64_t k_max = 0;
     for (int64_t kq : ktot) k_max = std::max(k_max, kq);
-    P->cfg = pick_cfg(bf, m_max, n_max, big, k_max);
+    P->cfg = pick_cfg(bf, m_max, n_max, big, k_max, P->akf && P->bkf);
     int S = 1;
     int64_t n_split = 0;
     if (nbat == 0 && !P->tasks.empty() && (P->cfg == kCfgSquare || P->cfg == kCfgMid || P->cfg == kCfgTall)) {
@@ -622,7 +626,7 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
     gemm_cfg_tile(bf, P->cfg, &bm, &bn);
     {
         // spelled like the demangled kernel name, so that profiler output can be matched against it
-        static const char* const shape[8] = {"2, 2, 4, 4", "2, 2, 2, 2", "1, 4, 2, 2", "1, 4, 4, 2", "1, 4, 2, 1", "2, 2, 1, 1", "2, 2, 4, 2", "2, 2, 2, 2"};
+        static const char* const shape[9] = {"2, 2, 4, 4", "2, 2, 2, 2", "1, 4, 2, 2", "1, 4, 4, 2", "1, 4, 2, 1", "2, 2, 1, 1", "2, 2, 4, 2", "2, 2, 2, 2", "2, 2, 1, 2"};
         std::ostringstream l;
         const char* tf[2] = {"false", "true"};
         if (A->dtype == NNT_F32) l << "gemm_f32_kernel<" << tf[P->akf] << ", " << tf[P->bkf] << ", " << (P->cfg == kCfgSquare ? "2, 2, 2, 2" : P->cfg == kCfgMid ? "2, 2, 1, 2" : shape[P->cfg]) << ">";
@@ -779,12 +783,15 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
 
     // workgroups that qualify for the direct-load kernel go first in every launch range
     P->task_nfast.assign(P->task_ctile.size(), 0);
-    if (bf ? (P->cfg == kCfgSquare || P->cfg == kCfgTall || P->cfg == kCfgWide) : (P->cfg == kCfgSquare || P->cfg == kCfgSkinny64n128 || P->cfg == kCfgMid)) {
+    if (bf ? (P->cfg == kCfgSquare || P->cfg == kCfgTall || P->cfg == kCfgWide) : (P->cfg == kCfgSquare || P->cfg == kCfgSkinny64n128 || P->cfg == kCfgMid || P->cfg == kCfgResident)) {
         const int kmul = (bf && P->cfg == kCfgSquare) ? 64 : 32;   // loads are started two k-steps at a time
         // the 256 x 128 bf16 kernel has a variant for chunk lengths that are multiples of 8 and macro-tiles that end
         // inside their C tile (at a multiple of 8 rows of an operand whose row index is the contiguous one)
         const bool rag_ok = bf && (P->cfg == kCfgTall || P->cfg == kCfgWide);
         std::vector<char> task_ok(P->tasks.size(), 1), task_rag(P->tasks.size(), 0);
+        if (P->cfg == kCfgResident)      // the whole contraction, one chunk of at most 64, sits in LDS at once
+            for (size_t ti = 0; ti < P->tasks.size(); ti++)
+                if (P->tasks[ti].nchunk != 1 || P->chunks[P->tasks[ti].chunk0].k > 64) task_ok[ti] = 0;
         for (size_t ti = 0; ti < P->tasks.size(); ti++)
             for (int32_t q = P->tasks[ti].chunk0; q < P->tasks[ti].chunk0 + P->tasks[ti].nchunk; q++) {
                 const GemmChunk& c = P->chunks[q];
@@ -821,6 +828,8 @@ int32_t build_plan(nnt_ctx* ctx, int opA, nnt_tensor* A, int opB, nnt_tensor* B,
                 l << (P->cfg == kCfgTall ? "gemm_bf16_dl_tall_kernel<" : P->cfg == kCfgWide ? "gemm_bf16_dl_wide_kernel<" : "gemm_bf16_dl_kernel<")
                   << (C->dtype == NNT_F32 ? "float" : "unsigned short")
                   << ", " << tf[P->akf] << ", " << tf[P->bkf] << (P->cfg == kCfgTall ? (P->dl_ragged ? ", true>" : ", false>") : ">");
+            else if (P->cfg == kCfgResident)
+                l << "gemm_f32_dl_rk_kernel";
             else
                 l << "gemm_f32_dl_kernel<" << tf[P->akf] << ", " << tf[P->bkf] << (P->cfg == kCfgSquare ? ", 2, 2>" : ", 1, 2>");
             P->label = l.str() + P->label.substr(old_name.size());

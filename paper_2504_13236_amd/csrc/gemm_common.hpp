@@ -72,7 +72,9 @@ enum GemmCfg {
     kCfgSkinny64n128 = 4, // 64 x 128
     kCfgSkinny64n64 = 5,  // 64 x 64   (the two narrower shapes give memory-bound products more workgroups)
     kCfgTall = 6,         // bf16 256 x 128 (two workgroups per compute unit); f32 128 x 128
-    kCfgWide = 7          // bf16 128 x 128, four waves side by side (products with at most 128 rows: m = head size); f32 128 x 256
+    kCfgWide = 7,         // bf16 128 x 128, four waves side by side (products with at most 128 rows: m = head size); f32 128 x 256
+    kCfgResident = 8      // f32 64 x 128 for contractions of at most 64 (k = head size: the score-shaped products) with both
+                          // operands k-contiguous: the whole contraction sits in LDS at once, three workgroups per compute unit
 };
 
 inline void gemm_cfg_tile(int dtype_is_bf16, int cfg, int* bm, int* bn) {
@@ -84,6 +86,7 @@ inline void gemm_cfg_tile(int dtype_is_bf16, int cfg, int* bm, int* bn) {
         case kCfgSkinny64n64: *bm = 64; *bn = 64; break;
         case kCfgTall: *bm = dtype_is_bf16 ? 256 : 128; *bn = 128; break;
         case kCfgWide: *bm = 128; *bn = dtype_is_bf16 ? 128 : 256; break;
+        case kCfgResident: *bm = dtype_is_bf16 ? 128 : 64; *bn = 128; break;
         default: *bm = 128; *bn = 256; break;
     }
 }
@@ -96,8 +99,9 @@ int32_t launch_gemm_bf16(hipStream_t st, int out_is_f32, int akf, int bkf, int c
 // kCfgWide: 128 x 128 macro-tiles, always under the rules of `ragged`.
 int32_t launch_gemm_bf16_dl(hipStream_t st, int out_is_f32, int akf, int bkf, int cfg, bool ragged, const GemmArgs& g, int64_t nwg);
 int gemm_bf16_dl_occupancy(int out_is_f32, int akf, int bkf, int cfg);
-// fp32: 128 x 128 (kCfgSquare) or 64 x 128 (kCfgMid, kCfgSkinny64n128) macro-tiles that lie wholly inside their
-// C tile, 16-byte aligned operands, chunk lengths that are multiples of 32
+// fp32: 128 x 128 (kCfgSquare) or 64 x 128 (kCfgMid, kCfgSkinny64n128, kCfgResident) macro-tiles that lie wholly inside their
+// C tile, 16-byte aligned operands, chunk lengths that are multiples of 32.  kCfgResident: one chunk of 32 or 64 per task,
+// A read transposed and B as [k, n] (both k-contiguous)
 // `epi_mode` (a GemmEpi mode, 0 for the plain product) picks the kernels with an activation on the result path; they exist
 // for the forms gemm_f32_dl_has_act names.
 int32_t launch_gemm_f32_dl(hipStream_t st, int akf, int bkf, int cfg, const GemmArgs& g, int64_t nwg, int epi_mode = 0);

@@ -257,7 +257,8 @@ KernelFn kernel_of(int cfg) {
     switch (cfg) {
         case kCfgSquare:
         case kCfgTall: return gemm_f32_kernel<AKF, BKF, 2, 2, 2, 2>;
-        case kCfgMid: return gemm_f32_kernel<AKF, BKF, 2, 2, 1, 2>;
+        case kCfgMid:
+        case kCfgResident: return gemm_f32_kernel<AKF, BKF, 2, 2, 1, 2>;
         case kCfgSkinny64: return gemm_f32_kernel<AKF, BKF, 1, 4, 2, 2>;
         case kCfgSkinny64n128: return gemm_f32_kernel<AKF, BKF, 1, 4, 2, 1>;
         case kCfgSkinny64n64: return gemm_f32_kernel<AKF, BKF, 2, 2, 1, 1>;

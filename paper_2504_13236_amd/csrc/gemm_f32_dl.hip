@@ -115,8 +115,12 @@ __device__ __forceinline__ void read_frag(typename FragSel<KF>::type& f, const F
 
 // Macro-tile (64 WMB) x (64 WNB): four waves as 2 x 2, each (32 WMB) x (32 WNB).
 // EPI: the activation form of the result path (GemmEpi), 0 for the plain one.
-template <bool AKF, bool BKF, int WMB, int WNB, int EPI>
+// RES: the whole contraction (two or four k-steps) is loaded by the prologue into four stages and the loop starts no
+// loads (products whose contraction is a head size: their workgroups live a few microseconds, most of them waiting for
+// their result stores to be acknowledged, so what counts is how many of them a compute unit holds).
+template <bool AKF, bool BKF, int WMB, int WNB, int EPI, bool RES = false>
 __device__ __forceinline__ void f32_dl_body(const GemmArgs& g, char* lds) {
+    constexpr int kStages = RES ? 4 : nnt::kStages;
     constexpr int BM = 64 * WMB, BN = 64 * WNB;
     constexpr int kOpABytes = BM * kBK * 4, kOpBBytes = BN * kBK * 4, kStageBytes = kOpABytes + kOpBBytes;
     constexpr int NIA = BM / 64, NIB = BN / 64, kLoads = NIA + NIB;     // load instructions per wave and step
@@ -320,8 +324,12 @@ __device__ __forceinline__ void f32_dl_body(const GemmArgs& g, char* lds) {
             asm volatile("s_barrier" ::: "memory");
             // (after the last pair the fragment reads hit a stage that holds no new data: in bounds
             // and unused)
-            substep(std::integral_constant<int, 2 * kLoads>{}, KS0{}, 1, stage_addr(s2), [&](int i) { load_pair_item(s4, st, i); });
-            advance2();
+            if constexpr (RES) {
+                substep(None{}, KS0{}, 1, stage_addr(s2), no_load);
+            } else {
+                substep(std::integral_constant<int, 2 * kLoads>{}, KS0{}, 1, stage_addr(s2), [&](int i) { load_pair_item(s4, st, i); });
+                advance2();
+            }
             st = s2;
         }
         // nothing may still be on its way into LDS or into fragment registers at the end
@@ -381,6 +389,13 @@ __global__ void __launch_bounds__(256, 2) gemm_f32_dl_act_kernel(const GemmArgs 
     f32_dl_body<AKF, true, WMB, WNB, EPI>(g, lds);
 }
 
+// 64 x 128 macro-tiles of products with a contraction of 32 or 64, both operands k-contiguous (the scores K^T Q and
+// their like): 48 KB of LDS and at most 168 registers, so that a compute unit holds three workgroups.
+__global__ void __launch_bounds__(256, 3) gemm_f32_dl_rk_kernel(const GemmArgs g) {
+    __shared__ __attribute__((aligned(16))) char lds[4 * (64 + 128) * kBK * 4];
+    f32_dl_body<true, true, 1, 2, 0, true>(g, lds);
+}
+
 using KernelFn = void (*)(const GemmArgs);
 
 template <int WMB, int WNB>
@@ -395,6 +410,7 @@ KernelFn kernel_of(int akf, int bkf) {
 }
 
 KernelFn kernel_of(int akf, int bkf, int cfg) {
+    if (cfg == kCfgResident) return (akf && bkf) ? gemm_f32_dl_rk_kernel : nullptr;
     return (cfg == kCfgSkinny64n128 || cfg == kCfgMid) ? kernel_of<1, 2>(akf, bkf) : kernel_of<2, 2>(akf, bkf);
 }
 
@@ -413,12 +429,14 @@ int32_t launch_gemm_f32_dl(hipStream_t st, int akf, int bkf, int cfg, const Gemm
         hipLaunchKernelGGL(fn, dim3((unsigned)nwg), dim3(256), 0, st, g);
         return hipGetLastError() == hipSuccess ? NNT_OK : NNT_EHIP;
     }
+    if (!kernel_of(akf, bkf, cfg)) return NNT_EINVAL;
     hipLaunchKernelGGL(kernel_of(akf, bkf, cfg), dim3((unsigned)nwg), dim3(256), 0, st, g);
     return hipGetLastError() == hipSuccess ? NNT_OK : NNT_EHIP;
 }
 
 int gemm_f32_dl_occupancy(int akf, int bkf, int cfg) {
     int n = 0;
+    if (!kernel_of(akf, bkf, cfg)) return 1;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel_of(akf, bkf, cfg), 256, 0) != hipSuccess || n < 1) n = 1;
     return n;
 }

@@ -125,6 +125,17 @@ def test_gemm_f32_whole_macro_tiles_aligned(capi, opA, opB, m, n, k):
         check(got, ref, "f32", "gemm f32 %s%s %dx%dx%d b%d" % (opA, opB, m, n, k, batch))
 
 
+@pytest.mark.parametrize("m,n", [(64, 128), (256, 256), (192, 384), (128, 200), (100, 256)])
+@pytest.mark.parametrize("k", [32, 64])
+def test_gemm_f32_whole_contraction_resident(capi, m, n, k):
+    """fp32 products A^T B with a contraction of 32 or 64 (a head size) and both operands k-contiguous, the form of
+    the scores K^T Q: whole 64 x 128 macro-tiles run in the kernel that holds the whole contraction in LDS, the last
+    two shapes have ragged edges and leave it; batch, alpha / beta and padded leading dimensions."""
+    for batch, alpha, beta, pad in ((1, 1.0, 0.0, 0), (5, 0.125, 0.0, 0), (3, 0.7, -1.3, 4)):
+        got, ref = run_gemm(capi, "f32", "f32", "T", "N", m, n, k, batch, alpha, beta, pad, seed=7 * m + n + k)
+        check(got, ref, "f32", "gemm f32 TN %dx%dx%d b%d" % (m, n, k, batch))
+
+
 def test_gemm_direct_load_randomized_sweep(capi):
     """Seeded random draws over the shapes that qualify for the kernels which load straight into LDS and
     keep fragment reads in flight between the matrix instructions: m, n multiples of the macro-tile, k
